@@ -1,0 +1,247 @@
+"""ctypes front end of the CPU oracle (``sparseloco_oracle.c``).
+
+TEST INFRASTRUCTURE ONLY: imported by ``tests/``, by the smoke check and by the
+benchmark's ``cpu_baseline`` leg.  The product package never imports it, and
+this module imports nothing from the product package.  It only marshals numpy
+arrays into the C functions; all arithmetic of the method is in the C file.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libsparseloco_oracle.so")
+
+LAYOUT_FLAT = 0
+LAYOUT_TILE = 1
+
+
+class SloTensor(C.Structure):
+    _fields_ = [
+        ("rows", C.c_int64),
+        ("cols", C.c_int64),
+        ("offset", C.c_int64),
+        ("layout", C.c_int32),
+        ("reserved", C.c_int32),
+    ]
+
+
+def build() -> str:
+    """Compile the oracle's C source (always recompiles)."""
+    subprocess.check_call(["sh", os.path.join(_HERE, "build.sh")])
+    return _LIB_PATH
+
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            build()
+        L = C.CDLL(_LIB_PATH)
+        i64, i32, vp = C.c_int64, C.c_int, C.c_void_p
+        tp = C.POINTER(SloTensor)
+        L.slo_tensor_chunks.restype = i64
+        L.slo_tensor_chunks.argtypes = [tp, i32]
+        L.slo_num_chunks.restype = i64
+        L.slo_num_chunks.argtypes = [tp, i32, i32]
+        L.slo_element_of.restype = i64
+        L.slo_element_of.argtypes = [tp, i32, i64, i32]
+        L.slo_record_bytes.restype = i64
+        L.slo_record_bytes.argtypes = [i32]
+        L.slo_payload_bytes.restype = i64
+        L.slo_payload_bytes.argtypes = [tp, i32, i32, i32]
+        L.slo_tensor_block_bytes.restype = i64
+        L.slo_tensor_block_bytes.argtypes = [tp, i32, i32]
+        L.slo_pack_record.restype = None
+        L.slo_pack_record.argtypes = [vp, vp, i32, vp]
+        L.slo_unpack_record.restype = None
+        L.slo_unpack_record.argtypes = [vp, i32, vp, vp]
+        L.slo_pack_indices.restype = i32
+        L.slo_pack_indices.argtypes = [vp, vp, i64, i32, vp]
+        L.slo_tree_sum.restype = C.c_double
+        L.slo_tree_sum.argtypes = [vp, i64]
+        L.slo_accumulate.restype = None
+        L.slo_accumulate.argtypes = [vp, vp, C.c_float, i64]
+        L.slo_topk_chunk.restype = i32
+        L.slo_topk_chunk.argtypes = [tp, i32, i64, vp, i32, vp, vp]
+        L.slo_quantize_tensor.restype = i32
+        L.slo_quantize_tensor.argtypes = [vp, i64, i32, vp, vp, vp]
+        L.slo_compress.restype = i32
+        L.slo_compress.argtypes = [tp, i32, i32, i32, vp, vp, C.c_float, i32, vp, vp, vp, vp, vp]
+        L.slo_decompress_avg_apply.restype = i32
+        L.slo_decompress_avg_apply.argtypes = [tp, i32, i32, i32, vp, vp, i32, C.c_float]
+        L.slo_decompress_dense.restype = i32
+        L.slo_decompress_dense.argtypes = [tp, i32, i32, i32, vp, vp]
+        L.slo_max_threads.restype = i32
+        L.slo_max_threads.argtypes = []
+        _lib = L
+    return _lib
+
+
+def _ptr(a):
+    return None if a is None else a.ctypes.data_as(C.c_void_p)
+
+
+def _check(a, dtype):
+    assert isinstance(a, np.ndarray) and a.dtype == dtype and a.flags["C_CONTIGUOUS"], (
+        f"need C-contiguous {dtype} array"
+    )
+    return a
+
+
+def make_tensors(descs):
+    """descs: iterable of (rows, cols, offset, layout) -> ctypes array."""
+    descs = list(descs)
+    arr = (SloTensor * max(1, len(descs)))()
+    for i, (r, c, off, lay) in enumerate(descs):
+        arr[i] = SloTensor(int(r), int(c), int(off), int(lay), 0)
+    return arr, len(descs)
+
+
+def num_chunks(descs, tile=64):
+    arr, n = make_tensors(descs)
+    return int(lib().slo_num_chunks(arr, n, tile))
+
+
+def tensor_chunks(desc, tile=64):
+    arr, _ = make_tensors([desc])
+    return int(lib().slo_tensor_chunks(arr, tile))
+
+
+def element_of(desc, c, j, tile=64):
+    arr, _ = make_tensors([desc])
+    return int(lib().slo_element_of(arr, tile, int(c), int(j)))
+
+
+def record_bytes(k):
+    return int(lib().slo_record_bytes(k))
+
+
+def payload_bytes(descs, k, tile=64):
+    arr, n = make_tensors(descs)
+    return int(lib().slo_payload_bytes(arr, n, tile, k))
+
+
+def tensor_block_bytes(desc, k, tile=64):
+    arr, _ = make_tensors([desc])
+    return int(lib().slo_tensor_block_bytes(arr, tile, k))
+
+
+def pack_record(idx, code):
+    idx = _check(np.ascontiguousarray(idx, dtype=np.uint16), np.uint16)
+    code = _check(np.ascontiguousarray(code, dtype=np.uint8), np.uint8)
+    k = idx.size
+    out = np.zeros(record_bytes(k), dtype=np.uint8)
+    lib().slo_pack_record(_ptr(idx), _ptr(code), k, _ptr(out))
+    return out
+
+
+def unpack_record(rec, k):
+    rec = _check(np.ascontiguousarray(rec, dtype=np.uint8), np.uint8)
+    idx = np.zeros(k, dtype=np.uint16)
+    code = np.zeros(k, dtype=np.uint8)
+    lib().slo_unpack_record(_ptr(rec), k, _ptr(idx), _ptr(code))
+    return idx, code
+
+
+def pack_indices(idx, code, n_chunks, k):
+    idx = _check(np.ascontiguousarray(idx, dtype=np.uint16), np.uint16)
+    code = _check(np.ascontiguousarray(code, dtype=np.uint8), np.uint8)
+    out = np.zeros(n_chunks * record_bytes(k), dtype=np.uint8)
+    st = lib().slo_pack_indices(_ptr(idx), _ptr(code), n_chunks, k, _ptr(out))
+    if st:
+        raise ValueError(f"slo_pack_indices: status {st}")
+    return out
+
+
+def tree_sum(values):
+    v = np.ascontiguousarray(values, dtype=np.float64)
+    return float(lib().slo_tree_sum(_ptr(v), v.size))
+
+
+def accumulate(e, delta, beta):
+    """In place: e <- fma(beta, e, delta)."""
+    _check(e, np.float32), _check(delta, np.float32)
+    assert e.size == delta.size
+    lib().slo_accumulate(_ptr(e), _ptr(delta), float(beta), e.size)
+
+
+def topk_chunk(desc, c, a, k, tile=64):
+    arr, _ = make_tensors([desc])
+    _check(a, np.float32)
+    idx = np.zeros(k, dtype=np.uint16)
+    val = np.zeros(k, dtype=np.float32)
+    n = lib().slo_topk_chunk(arr, tile, int(c), _ptr(a), k, _ptr(idx), _ptr(val))
+    if n < 0:
+        raise ValueError("chunk has fewer than k valid elements")
+    return idx, val
+
+
+def quantize_tensor(x, n_chunks, k):
+    """x: the tensor's selected values in canonical order. -> codes, lut, stats"""
+    x = _check(np.ascontiguousarray(x, dtype=np.float32), np.float32)
+    assert x.size == n_chunks * k
+    code = np.zeros(x.size, dtype=np.uint8)
+    lut = np.zeros(4, dtype=np.float32)
+    stats = np.zeros(8, dtype=np.float64)
+    st = lib().slo_quantize_tensor(_ptr(x), n_chunks, k, _ptr(code), _ptr(lut), _ptr(stats))
+    if st:
+        raise RuntimeError(f"slo_quantize_tensor: status {st}")
+    return code, lut, stats
+
+
+def compress(descs, k, e, delta, beta, tile=64, ef_frozen=False, want_detail=False):
+    """Updates e in place; returns payload bytes (and the selection when asked)."""
+    arr, n = make_tensors(descs)
+    _check(e, np.float32), _check(delta, np.float32)
+    nbytes = int(lib().slo_payload_bytes(arr, n, tile, k))
+    payload = np.zeros(nbytes, dtype=np.uint8)
+    det = None
+    args = [None, None, None, None]
+    if want_detail:
+        nc = int(lib().slo_num_chunks(arr, n, tile))
+        det = dict(
+            idx=np.zeros(nc * k, dtype=np.uint16),
+            val=np.zeros(nc * k, dtype=np.float32),
+            code=np.zeros(nc * k, dtype=np.uint8),
+            lut=np.zeros(4 * n, dtype=np.float32),
+        )
+        args = [_ptr(det["idx"]), _ptr(det["val"]), _ptr(det["code"]), _ptr(det["lut"])]
+    st = lib().slo_compress(arr, n, tile, k, _ptr(e), _ptr(delta), float(beta),
+                            int(bool(ef_frozen)), _ptr(payload), *args)
+    if st:
+        raise ValueError(f"slo_compress: status {st}")
+    return (payload, det) if want_detail else payload
+
+
+def decompress_avg_apply(descs, k, theta, payloads, lr, tile=64):
+    """In place: theta <- theta - lr * mean_r(dequantised payload_r)."""
+    arr, n = make_tensors(descs)
+    _check(theta, np.float32)
+    R = len(payloads)
+    for p in payloads:
+        _check(p, np.uint8)
+    ptrs = (C.c_void_p * max(1, R))(*[p.ctypes.data for p in payloads])
+    st = lib().slo_decompress_avg_apply(arr, n, tile, k, _ptr(theta), ptrs, R, float(lr))
+    if st:
+        raise ValueError(f"slo_decompress_avg_apply: status {st}")
+
+
+def decompress_dense(descs, k, payload, n_elems, tile=64):
+    arr, n = make_tensors(descs)
+    out = np.zeros(n_elems, dtype=np.float32)
+    st = lib().slo_decompress_dense(arr, n, tile, k, _ptr(payload), _ptr(out))
+    if st:
+        raise ValueError(f"slo_decompress_dense: status {st}")
+    return out
+
+
+def max_threads():
+    return int(lib().slo_max_threads())

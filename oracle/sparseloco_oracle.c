@@ -1,0 +1,510 @@
+/*
+ * SparseLoCo compress + aggregate path: plain CPU oracle.
+ *
+ * TEST INFRASTRUCTURE ONLY.  This file is the slow, obviously-correct statement
+ * of what the hot path computes.  It is used by the tests, by the smoke check
+ * and by the benchmark's reported CPU baseline; the product (the HIP library)
+ * never calls it and shares no code, header, table or helper with it.
+ *
+ * Every function cites the passage of the SparseLoCo paper (arXiv 2508.15706)
+ * it follows.  Where the paper is silent the reading taken is stated next to
+ * the code.  Floating point: the path itself is fp32 (the error buffer, the
+ * pseudo-gradient and the parameters are fp32 tensors); all quantizer
+ * statistics are fp64 with a fixed summation tree so that the bytes of a
+ * payload are a function of the inputs alone.
+ *
+ * Parity pins (tests marked "not gpu"): brute-force Top-k on tiny chunks,
+ * exactly-rounded rational arithmetic for the accumulate, hand-computed tree
+ * sums, the closed form of the quantizer on +-c inputs, exact rational
+ * quantizer statistics on dyadic inputs, a big-integer bit-stream model of the
+ * wire format, a dense numpy model of the aggregation, and the invariants of
+ * Eq. (2).  No function here is "parity unpinned"; what is pinned for the
+ * quantizer is the reading of Section 4's description stated below, since the
+ * paper prints no worked example of it.
+ *
+ * Build: gcc -O2 -std=c11 -ffp-contract=off -fopenmp -shared -fPIC
+ *        (no -ffast-math, no -march: fmaf must stay a single correctly
+ *        rounded operation and nothing else may be contracted).
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+#define SLO_OK 0
+#define SLO_ERR_ARG (-1)
+#define SLO_ERR_PAYLOAD (-2)
+#define SLO_ERR_NOMEM (-3)
+
+#define SLO_LAYOUT_FLAT 0 /* contiguous runs of tile*tile elements (1-D rule)   */
+#define SLO_LAYOUT_TILE 1 /* tile x tile blocks of a row-major matrix (2-D rule) */
+
+/* One tensor of the list.  All tensors live in flat fp32 arenas (e, delta,
+ * theta) at element offset `offset`, row-major rows x cols.  A 1-D tensor is
+ * rows = 1. */
+typedef struct {
+    int64_t rows, cols, offset;
+    int32_t layout;
+    int32_t reserved;
+} slo_tensor;
+
+/* ------------------------------------------------------------------------- */
+/* Chunk geometry (Section 3.3, last paragraph; Section 4 "chunk size 4096,   */
+/* non-overlapping square 64x64 grids for 2D parameters").                    */
+/*                                                                           */
+/* 2-D rule: the matrix is cut into tile x tile blocks, blocks numbered       */
+/* row-major over the block grid; inside a block the local index is           */
+/* j = tile*lr + lc.  1-D rule: runs of C = tile*tile consecutive elements,   */
+/* j = position in the run.  Reading for shapes that are not multiples of     */
+/* the tile: edge chunks are partial, only in-range positions are candidates, */
+/* j keeps the full-tile stride, k is not scaled down.                        */
+/* ------------------------------------------------------------------------- */
+
+static int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+
+int64_t slo_tensor_chunks(const slo_tensor *t, int tile)
+{
+    int64_t C = (int64_t)tile * tile;
+    if (t->layout == SLO_LAYOUT_TILE)
+        return ceil_div(t->rows, tile) * ceil_div(t->cols, tile);
+    return ceil_div(t->rows * t->cols, C);
+}
+
+int64_t slo_num_chunks(const slo_tensor *t, int nt, int tile)
+{
+    int64_t n = 0;
+    for (int i = 0; i < nt; ++i) n += slo_tensor_chunks(&t[i], tile);
+    return n;
+}
+
+/* Arena element index of local position j of chunk c of tensor t, or -1 when
+ * that position lies outside the tensor. */
+int64_t slo_element_of(const slo_tensor *t, int tile, int64_t c, int j)
+{
+    if (t->layout == SLO_LAYOUT_TILE) {
+        int64_t tiles_c = ceil_div(t->cols, tile);
+        int64_t tr = c / tiles_c, tc = c % tiles_c;
+        int64_t row = tr * tile + j / tile;
+        int64_t col = tc * tile + j % tile;
+        if (row >= t->rows || col >= t->cols) return -1;
+        return t->offset + row * t->cols + col;
+    } else {
+        int64_t C = (int64_t)tile * tile;
+        int64_t pos = c * C + j;
+        if (pos >= t->rows * t->cols) return -1;
+        return t->offset + pos;
+    }
+}
+
+/* ------------------------------------------------------------------------- */
+/* Wire format.  Appendix "Compression of indices in Top-k" fixes only the    */
+/* bit counts: an index inside a chunk of 4096 needs 12 bits, a quantized     */
+/* value 2 bits.  Reading for the byte layout:                                */
+/*   per tensor, at a 16-byte aligned offset: float LUT[4] (little endian),   */
+/*   then one record per chunk in chunk order; a record is the k indices in   */
+/*   ascending order as a little-endian stream of 12-bit fields, followed by  */
+/*   the k codes, four per byte, entry m in bits 2*(m mod 4).                 */
+/* Record size 7k/4 bytes (k a multiple of 4), tensor block padded to 16.     */
+/* ------------------------------------------------------------------------- */
+
+int64_t slo_record_bytes(int k) { return (int64_t)7 * k / 4; }
+
+int64_t slo_tensor_block_bytes(const slo_tensor *t, int tile, int k)
+{
+    int64_t b = 16 + slo_tensor_chunks(t, tile) * slo_record_bytes(k);
+    return (b + 15) / 16 * 16;
+}
+
+int64_t slo_payload_bytes(const slo_tensor *t, int nt, int tile, int k)
+{
+    int64_t n = 0;
+    for (int i = 0; i < nt; ++i) n += slo_tensor_block_bytes(&t[i], tile, k);
+    return n;
+}
+
+/* Encode one record: idx[0..k) ascending 12-bit values, code[0..k) in 0..3. */
+void slo_pack_record(const uint16_t *idx, const uint8_t *code, int k, uint8_t *out)
+{
+    int nidx = 3 * k / 2;
+    memset(out, 0, (size_t)slo_record_bytes(k));
+    for (int m = 0; m < k; ++m) {
+        int bit = 12 * m; /* first bit of field m in the stream */
+        unsigned v = idx[m] & 0xFFFu;
+        for (int b = 0; b < 12; ++b)
+            if (v >> b & 1u) out[(bit + b) / 8] |= (uint8_t)(1u << ((bit + b) % 8));
+    }
+    for (int m = 0; m < k; ++m)
+        out[nidx + m / 4] |= (uint8_t)((code[m] & 3u) << (2 * (m % 4)));
+}
+
+void slo_unpack_record(const uint8_t *in, int k, uint16_t *idx, uint8_t *code)
+{
+    int nidx = 3 * k / 2;
+    for (int m = 0; m < k; ++m) {
+        int bit = 12 * m;
+        unsigned v = 0;
+        for (int b = 0; b < 12; ++b)
+            v |= (unsigned)(in[(bit + b) / 8] >> ((bit + b) % 8) & 1u) << b;
+        idx[m] = (uint16_t)v;
+    }
+    for (int m = 0; m < k; ++m) code[m] = (uint8_t)(in[nidx + m / 4] >> (2 * (m % 4)) & 3u);
+}
+
+/* The record encoder alone over n_chunks records (what sl_pack_indices does). */
+int slo_pack_indices(const uint16_t *idx, const uint8_t *code, int64_t n_chunks, int k,
+                     uint8_t *out)
+{
+    if (k < 4 || k % 4 || k > 4096 || n_chunks < 0) return SLO_ERR_ARG;
+    for (int64_t c = 0; c < n_chunks; ++c)
+        slo_pack_record(idx + c * k, code + c * k, k, out + c * slo_record_bytes(k));
+    return SLO_OK;
+}
+
+/* ------------------------------------------------------------------------- */
+/* Fixed-shape fp64 summation.  The paper does not say in which order the     */
+/* quantizer's sums are taken; since a payload has to be reproducible bit for */
+/* bit, the reading is: pad the sequence on the right with +0.0 to the next   */
+/* power of two, then replace it by the sums of adjacent pairs until one      */
+/* value is left.                                                             */
+/* ------------------------------------------------------------------------- */
+
+double slo_tree_sum(const double *s, int64_t n)
+{
+    int64_t P = 1;
+    while (P < n) P *= 2;
+    double *w = (double *)malloc((size_t)P * sizeof(double));
+    if (!w) return NAN;
+    for (int64_t i = 0; i < P; ++i) w[i] = i < n ? s[i] : 0.0;
+    for (int64_t m = P; m > 1; m /= 2)
+        for (int64_t i = 0; i < m / 2; ++i) w[i] = w[2 * i] + w[2 * i + 1];
+    double r = w[0];
+    free(w);
+    return r;
+}
+
+/* Sum over a tensor's selected entries of a per-entry quantity y, laid out
+ * y[c*k + m]: first the tree sum of each chunk's k entries, then the tree sum
+ * of those per-chunk leaves in chunk order. */
+static double two_level_sum(const double *y, int64_t n_chunks, int k)
+{
+    double *leaf = (double *)malloc((size_t)(n_chunks > 0 ? n_chunks : 1) * sizeof(double));
+    for (int64_t c = 0; c < n_chunks; ++c) leaf[c] = slo_tree_sum(y + c * k, k);
+    double r = slo_tree_sum(leaf, n_chunks);
+    free(leaf);
+    return r;
+}
+
+/* ------------------------------------------------------------------------- */
+/* Step 1: error-feedback accumulate, first line of Eq. (2) / the argument of */
+/* Top-k in Algorithm 1:  a = beta * e + delta.  Reading for the rounding:    */
+/* one fused multiply-add in fp32 (a single rounding).                        */
+/* ------------------------------------------------------------------------- */
+
+void slo_accumulate(float *e, const float *delta, float beta, int64_t n)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < n; ++i) e[i] = fmaf(beta, e[i], delta[i]);
+}
+
+/* ------------------------------------------------------------------------- */
+/* Step 2: chunk-wise Top-k by magnitude (Section 3.3 last paragraph;         */
+/* "Top-k largest magnitude entries", Section 4.2).  Plain definition: sort   */
+/* the chunk's valid positions by |a| descending and keep the first k.        */
+/* |a| is compared through its bit pattern with the sign cleared, which is    */
+/* the same order as the real magnitude for finite values.  Ties (paper       */
+/* silent): the lower local index wins.  Output is in ascending local index.  */
+/* ------------------------------------------------------------------------- */
+
+typedef struct {
+    uint32_t key;
+    int32_t j;
+} slo_cand;
+
+static int cmp_mag_desc_then_index(const void *pa, const void *pb)
+{
+    const slo_cand *a = (const slo_cand *)pa, *b = (const slo_cand *)pb;
+    if (a->key != b->key) return a->key > b->key ? -1 : 1;
+    return a->j < b->j ? -1 : (a->j > b->j ? 1 : 0);
+}
+
+static int cmp_index_asc(const void *pa, const void *pb)
+{
+    const slo_cand *a = (const slo_cand *)pa, *b = (const slo_cand *)pb;
+    return a->j < b->j ? -1 : (a->j > b->j ? 1 : 0);
+}
+
+static uint32_t f32_bits(float x)
+{
+    uint32_t u;
+    memcpy(&u, &x, 4);
+    return u;
+}
+
+/* Select within one chunk of tensor t.  a = arena holding the accumulated
+ * values.  Returns the number of valid positions in the chunk, or -1 when it
+ * has fewer than k. */
+int slo_topk_chunk(const slo_tensor *t, int tile, int64_t c, const float *a, int k,
+                   uint16_t *sel_idx, float *sel_val)
+{
+    int C = tile * tile, n = 0;
+    slo_cand *cand = (slo_cand *)malloc((size_t)C * sizeof(slo_cand));
+    for (int j = 0; j < C; ++j) {
+        int64_t i = slo_element_of(t, tile, c, j);
+        if (i < 0) continue;
+        cand[n].key = f32_bits(a[i]) & 0x7FFFFFFFu;
+        cand[n].j = j;
+        ++n;
+    }
+    if (n < k) {
+        free(cand);
+        return -1;
+    }
+    qsort(cand, (size_t)n, sizeof(slo_cand), cmp_mag_desc_then_index);
+    qsort(cand, (size_t)k, sizeof(slo_cand), cmp_index_asc);
+    for (int m = 0; m < k; ++m) {
+        sel_idx[m] = (uint16_t)cand[m].j;
+        sel_val[m] = a[slo_element_of(t, tile, c, cand[m].j)];
+    }
+    free(cand);
+    return n;
+}
+
+/* ------------------------------------------------------------------------- */
+/* Step 3: 2-bit statistical quantizer (Section 4, experimental set-up: all   */
+/* selected values of one tensor are quantized together; they are centred by  */
+/* their mean, [-6 sigma, 6 sigma] is cut into uniform bins - four for 2 bits */
+/* - and each bin keeps the centroid of the values assigned to it as a        */
+/* look-up table).  Readings where the paper gives no formula:                */
+/*   - statistics in fp64 over x in canonical order (chunk, then index) with  */
+/*     the two-level tree above; S1 = sum x, S2 = sum x*x;                    */
+/*   - mu = S1/M; var = S2/M - mu*mu (population), clamped at 0;              */
+/*   - bin width 3 sigma, edges -3 sigma, 0, +3 sigma on d = x - mu, bins     */
+/*     half-open [lo, hi), values beyond +-6 sigma fall in the end bins;      */
+/*     decided on squares so that no square root is involved:                 */
+/*        T = 9*var, dd = d*d,                                                */
+/*        code = d < 0 ? (dd > T ? 0 : 1) : (dd >= T ? 3 : 2);                */
+/*   - LUT[b] = centroid of the raw values with code b, fp64 sum / count,     */
+/*     rounded to fp32; an empty bin, or a centroid equal to zero, is +0.0f.  */
+/* Dequantisation is then the single look-up LUT[code].                       */
+/* stats (optional, 8 doubles out): S1, S2, mu, var, n0..n3.                  */
+/* ------------------------------------------------------------------------- */
+
+int slo_quantize_tensor(const float *x, int64_t n_chunks, int k, uint8_t *code, float lut[4],
+                        double *stats)
+{
+    int64_t M = n_chunks * k;
+    for (int b = 0; b < 4; ++b) lut[b] = 0.0f;
+    if (M == 0) return SLO_OK;
+    double *y = (double *)calloc((size_t)M, sizeof(double));
+    if (!y) return SLO_ERR_NOMEM;
+
+    for (int64_t i = 0; i < M; ++i) y[i] = (double)x[i];
+    double S1 = two_level_sum(y, n_chunks, k);
+    for (int64_t i = 0; i < M; ++i) y[i] = (double)x[i] * (double)x[i];
+    double S2 = two_level_sum(y, n_chunks, k);
+
+    double mu = S1 / (double)M;
+    double q = S2 / (double)M;
+    double p = mu * mu;
+    double var = q - p;
+    if (var < 0.0) var = 0.0;
+    double T = 9.0 * var;
+
+    int64_t cnt[4] = {0, 0, 0, 0};
+    for (int64_t i = 0; i < M; ++i) {
+        double d = (double)x[i] - mu;
+        double dd = d * d;
+        int cde = d < 0.0 ? (dd > T ? 0 : 1) : (dd >= T ? 3 : 2);
+        code[i] = (uint8_t)cde;
+        cnt[cde]++;
+    }
+    for (int b = 0; b < 4; ++b) {
+        for (int64_t i = 0; i < M; ++i) y[i] = code[i] == b ? (double)x[i] : 0.0;
+        double Sb = two_level_sum(y, n_chunks, k);
+        float cen = cnt[b] ? (float)(Sb / (double)cnt[b]) : 0.0f;
+        if (cen == 0.0f) cen = 0.0f; /* -0.0f -> +0.0f */
+        lut[b] = cen;
+    }
+    if (stats) {
+        stats[0] = S1, stats[1] = S2, stats[2] = mu, stats[3] = var;
+        for (int b = 0; b < 4; ++b) stats[4 + b] = (double)cnt[b];
+    }
+    free(y);
+    return SLO_OK;
+}
+
+/* ------------------------------------------------------------------------- */
+/* The compression half of Algorithm 1 ("Compression + Error Feedback"; first */
+/* two lines of Eq. (2)) over a tensor list:                                  */
+/*     a      = beta*e + delta                                                */
+/*     payload= Q(Top-k(a))                                                   */
+/*     e      = a - dequantised payload   (a itself where nothing was sent)   */
+/* e is updated in place.  Optional outputs (may be NULL), all laid out in    */
+/* list chunk order: sel_idx/sel_val/sel_code [n_chunks*k], lut [nt*4].       */
+/* ef_frozen != 0 is the error-feedback freeze of Appendix "Freezing Error    */
+/* Feedback": the buffer is neither used nor accumulated, i.e. a = delta and  */
+/* e is left untouched.                                                       */
+/* ------------------------------------------------------------------------- */
+
+int slo_compress(const slo_tensor *t, int nt, int tile, int k, float *e, const float *delta,
+                 float beta, int ef_frozen, uint8_t *payload, uint16_t *sel_idx, float *sel_val,
+                 uint8_t *sel_code, float *lut_out)
+{
+    if (nt < 0 || tile < 1 || tile > 64 || k < 4 || k % 4 || k > tile * tile) return SLO_ERR_ARG;
+    int64_t rec = slo_record_bytes(k);
+    int64_t chunk0 = 0, pay_off = 0;
+    int status = SLO_OK;
+
+    for (int ti = 0; ti < nt; ++ti) {
+        const slo_tensor *T = &t[ti];
+        int64_t n = T->rows * T->cols;
+        int64_t nc = slo_tensor_chunks(T, tile);
+        int64_t M = nc * k;
+
+        /* a = beta*e + delta; while frozen a = delta and e is not touched.
+         * `a` points at the tensor's first element; L is the same tensor
+         * addressed from there. */
+        slo_tensor L = *T;
+        L.offset = 0;
+        const float *a;
+        if (ef_frozen) {
+            a = delta + T->offset;
+        } else {
+            slo_accumulate(e + T->offset, delta + T->offset, beta, n);
+            a = e + T->offset;
+        }
+
+        uint16_t *idx = (uint16_t *)malloc((size_t)(M > 0 ? M : 1) * sizeof(uint16_t));
+        float *val = (float *)malloc((size_t)(M > 0 ? M : 1) * sizeof(float));
+        uint8_t *code = (uint8_t *)malloc((size_t)(M > 0 ? M : 1));
+        int bad = 0;
+#pragma omp parallel for schedule(dynamic, 16) reduction(| : bad)
+        for (int64_t c = 0; c < nc; ++c)
+            if (slo_topk_chunk(&L, tile, c, a, k, idx + c * k, val + c * k) < 0) bad |= 1;
+        if (bad) status = SLO_ERR_ARG;
+
+        float lut[4];
+        if (!bad) {
+            slo_quantize_tensor(val, nc, k, code, lut, NULL);
+
+            /* residual: last part of Eq. (2) line 2 / Algorithm 1 error update */
+            if (!ef_frozen)
+                for (int64_t c = 0; c < nc; ++c)
+                    for (int m = 0; m < k; ++m) {
+                        int64_t i = slo_element_of(&L, tile, c, idx[c * k + m]);
+                        e[T->offset + i] = a[i] - lut[code[c * k + m]];
+                    }
+
+            if (payload) {
+                uint8_t *blk = payload + pay_off;
+                memset(blk, 0, (size_t)slo_tensor_block_bytes(T, tile, k));
+                memcpy(blk, lut, 16);
+                for (int64_t c = 0; c < nc; ++c)
+                    slo_pack_record(idx + c * k, code + c * k, k, blk + 16 + c * rec);
+            }
+            if (sel_idx) memcpy(sel_idx + chunk0 * k, idx, (size_t)M * sizeof(uint16_t));
+            if (sel_val) memcpy(sel_val + chunk0 * k, val, (size_t)M * sizeof(float));
+            if (sel_code) memcpy(sel_code + chunk0 * k, code, (size_t)M);
+            if (lut_out) memcpy(lut_out + 4 * ti, lut, 16);
+        }
+        free(idx), free(val), free(code);
+        if (bad) return status;
+        chunk0 += nc;
+        pay_off += slo_tensor_block_bytes(T, tile, k);
+    }
+    return status;
+}
+
+/* ------------------------------------------------------------------------- */
+/* The aggregation half of Algorithm 1 ("Aggregate + Outer Update"; last two  */
+/* lines of Eq. (2)): dequantise every worker's payload, average over the R   */
+/* workers (a coordinate a worker did not send counts as zero), and take the  */
+/* outer SGD step theta <- theta - lr * average.  Order (paper silent): per   */
+/* chunk a zero fp32 accumulator, workers added in order r = 0..R-1, then     */
+/* theta = fma(-lr, acc * (1/R), theta) with 1/R rounded once to fp32.        */
+/* ------------------------------------------------------------------------- */
+
+int slo_decompress_avg_apply(const slo_tensor *t, int nt, int tile, int k, float *theta,
+                             const uint8_t *const *payloads, int R, float lr)
+{
+    if (nt < 0 || tile < 1 || tile > 64 || k < 4 || k % 4 || k > tile * tile || R < 1)
+        return SLO_ERR_ARG;
+    int C = tile * tile;
+    int64_t rec = slo_record_bytes(k);
+    float invR = 1.0f / (float)R;
+    int64_t pay_off = 0;
+    int bad = 0;
+
+    for (int ti = 0; ti < nt; ++ti) {
+        const slo_tensor *T = &t[ti];
+        int64_t nc = slo_tensor_chunks(T, tile);
+#pragma omp parallel for schedule(dynamic, 16) reduction(| : bad)
+        for (int64_t c = 0; c < nc; ++c) {
+            float *acc = (float *)calloc((size_t)C, sizeof(float));
+            uint16_t *idx = (uint16_t *)malloc((size_t)k * sizeof(uint16_t));
+            uint8_t *code = (uint8_t *)malloc((size_t)k);
+            for (int r = 0; r < R; ++r) {
+                const uint8_t *blk = payloads[r] + pay_off;
+                float lut[4];
+                memcpy(lut, blk, 16);
+                slo_unpack_record(blk + 16 + c * rec, k, idx, code);
+                for (int m = 0; m < k; ++m) {
+                    if (idx[m] >= C) {
+                        bad |= 1;
+                        continue;
+                    }
+                    acc[idx[m]] = acc[idx[m]] + lut[code[m]];
+                }
+            }
+            for (int j = 0; j < C; ++j) {
+                int64_t i = slo_element_of(T, tile, c, j);
+                if (i < 0) continue;
+                theta[i] = fmaf(-lr, acc[j] * invR, theta[i]);
+            }
+            free(acc), free(idx), free(code);
+        }
+        pay_off += slo_tensor_block_bytes(T, tile, k);
+    }
+    return bad ? SLO_ERR_PAYLOAD : SLO_OK;
+}
+
+/* Dense view of one worker's payload: out[i] = dequantised value at every
+ * transmitted coordinate, untouched elsewhere (callers pass zeros).  A helper
+ * for tests of the identities of Eq. (2); not a step of the path. */
+int slo_decompress_dense(const slo_tensor *t, int nt, int tile, int k, const uint8_t *payload,
+                         float *out)
+{
+    int64_t rec = slo_record_bytes(k), pay_off = 0;
+    uint16_t *idx = (uint16_t *)malloc((size_t)k * sizeof(uint16_t));
+    uint8_t *code = (uint8_t *)malloc((size_t)k);
+    for (int ti = 0; ti < nt; ++ti) {
+        const slo_tensor *T = &t[ti];
+        int64_t nc = slo_tensor_chunks(T, tile);
+        float lut[4];
+        memcpy(lut, payload + pay_off, 16);
+        for (int64_t c = 0; c < nc; ++c) {
+            slo_unpack_record(payload + pay_off + 16 + c * rec, k, idx, code);
+            for (int m = 0; m < k; ++m) {
+                int64_t i = slo_element_of(T, tile, c, idx[m]);
+                if (i < 0) {
+                    free(idx), free(code);
+                    return SLO_ERR_PAYLOAD;
+                }
+                out[i] = lut[code[m]];
+            }
+        }
+        pay_off += slo_tensor_block_bytes(T, tile, k);
+    }
+    free(idx), free(code);
+    return SLO_OK;
+}
+
+int slo_max_threads(void)
+{
+#ifdef _OPENMP
+    extern int omp_get_max_threads(void);
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
