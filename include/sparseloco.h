@@ -1,0 +1,141 @@
+/*
+ * sparseloco.h - C ABI of the MI355X (gfx950) SparseLoCo compress + aggregate library.
+ *
+ * The library implements, for a list of fp32 tensors that live in flat device
+ * arenas, the two communication-side blocks of SparseLoCo's outer step
+ * (arXiv 2508.15706, Algorithm 1 and Eq. (2)):
+ *
+ *   compress   (Algorithm 1, "Compression + Error Feedback"; Eq. (2) lines 1-2)
+ *       a = beta * e + delta ;  payload = Q(Top-k(a)) ;  e = a - dequantised payload
+ *   aggregate  (Algorithm 1, "Aggregate + Outer Update"; Eq. (2) lines 3-4)
+ *       theta = theta - lr * (1/R) * sum_r dequantised payload_r
+ *
+ * Top-k is chunk-wise (Section 3.3, last paragraph): 64x64 blocks of a 2-D
+ * tensor, runs of 4096 elements of a 1-D tensor, k largest |a| per chunk.  Q is
+ * the 2-bit statistical quantizer of Section 4 (per tensor: centre by the mean,
+ * four uniform bins over [-6 sigma, 6 sigma], per-bin centroid look-up table).
+ * Indices travel as 12-bit fields (appendix "Compression of indices in Top-k").
+ *
+ * Conventions for every function
+ *   - returns SL_OK (0) or a negative sl_status; never throws, never aborts;
+ *   - arguments are validated on the host before anything is enqueued; on an
+ *     argument error nothing is launched and no buffer is touched;
+ *   - "device" pointers are HIP device memory of the device that was current
+ *     when the plan was created; "host" pointers are ordinary host memory;
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream);
+ *     kernels are enqueued on it and the call returns without synchronising;
+ *   - the caller owns every buffer it passes; the library owns only sl_plan.
+ *   - results are deterministic: the same inputs give the same bytes.
+ */
+#ifndef SPARSELOCO_H
+#define SPARSELOCO_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    SL_OK = 0,
+    SL_ERR_INVALID_ARG = -1, /* null / misaligned pointer, bad k, R or shape        */
+    SL_ERR_BAD_PAYLOAD = -2, /* reserved for payload validation                     */
+    SL_ERR_HIP = -3,         /* a HIP runtime call failed; see sl_last_hip_error()  */
+    SL_ERR_NOMEM = -4,       /* host or device allocation failed (plan creation)    */
+    SL_ERR_DEVICE = -5       /* current device differs from the plan's device       */
+} sl_status;
+
+enum { SL_LAYOUT_FLAT = 0,    /* chunks are runs of 4096 consecutive elements      */
+       SL_LAYOUT_TILE64 = 1 };/* chunks are 64x64 blocks of the row-major matrix   */
+
+/* flags of sl_compress */
+enum { SL_COMPRESS_DEFAULT = 0,
+       SL_COMPRESS_EF_FROZEN = 1 /* appendix "Freezing Error Feedback": the buffer
+                                    is neither used nor accumulated, i.e. a = delta
+                                    and e is left untouched                        */ };
+
+enum { SL_CHUNK = 4096, SL_MAX_WORKERS = 64 };
+
+/* One tensor of the list: row-major rows x cols fp32 at element `offset` of the
+ * arenas (a 1-D tensor is rows = 1).  offset must be a multiple of 4 elements
+ * (16 bytes).  Chunks are numbered tensor by tensor; inside a TILE64 tensor
+ * row-major over the block grid with local index j = 64*row_in_block +
+ * col_in_block; inside a FLAT tensor j is the position in the run.  Edge chunks
+ * are partial: positions outside the tensor are never candidates; every chunk
+ * must still hold at least k elements. */
+typedef struct {
+    int64_t rows, cols, offset;
+    int32_t layout;
+    int32_t reserved; /* must be 0 */
+} sl_tensor;
+
+typedef struct sl_plan sl_plan; /* opaque: chunk work list and per-tensor tables */
+
+/* Builds the work list for a tensor list and a per-chunk k (Section 3.3:
+ * chunk-wise Top-k with a fixed k per chunk, density k/4096).  `tensors` is a
+ * host array, copied.  k must be a multiple of 4 with 4 <= k <= 4096.  Allocates
+ * small device tables on the current device (freed by sl_plan_destroy).
+ * Errors: INVALID_ARG (shape, alignment, overlap, a chunk with fewer than k
+ * elements), NOMEM, HIP. */
+int sl_plan_create(const sl_tensor *tensors, int n_tensors, int k, sl_plan **out);
+int sl_plan_destroy(sl_plan *plan);
+
+int64_t sl_plan_num_chunks(const sl_plan *plan);   /* chunks in the whole list        */
+int64_t sl_plan_num_elements(const sl_plan *plan); /* sum of rows*cols                */
+/* Size of one worker's payload:  sum over tensors of align16(16 + chunks*7k/4).
+ * Wire format: per tensor, at a 16-byte aligned offset, float LUT[4] (little
+ * endian) and then one record per chunk: the k selected local indices in
+ * ascending order as a little-endian stream of 12-bit fields, then the k 2-bit
+ * codes, four per byte, entry m in bits 2*(m mod 4).  Padding bytes are zero. */
+size_t sl_payload_bytes(const sl_plan *plan);
+/* Byte offset of tensor `t`'s block inside a payload, or (size_t)-1. */
+size_t sl_payload_tensor_offset(const sl_plan *plan, int t);
+/* Size of the scratch buffer sl_compress needs (selected values and partial
+ * sums of the quantizer statistics).  Contents are undefined between calls. */
+size_t sl_workspace_bytes(const sl_plan *plan);
+
+/* Compression + error feedback (Algorithm 1, compression block; Eq. (2)):
+ *   a = fma(beta, e, delta) in fp32; per chunk the k largest |a| (ties: lowest
+ *   local index); per tensor the 2-bit quantizer over its selected values
+ *   (fp64 statistics, fixed summation tree); payload written in the wire
+ *   format; e <- a - LUT[code] at the selected positions, e <- a elsewhere.
+ * e        inout, device, fp32 arena, 16-byte aligned
+ * delta    in,    device, fp32 arena, 16-byte aligned, must not alias e
+ * payload  out,   device, sl_payload_bytes() bytes, 16-byte aligned
+ * workspace       device, sl_workspace_bytes() bytes, 256-byte aligned
+ * flags    SL_COMPRESS_DEFAULT or SL_COMPRESS_EF_FROZEN
+ * Elements of the arenas that belong to no tensor are neither read nor written. */
+int sl_compress(sl_plan *plan, float *e, const float *delta, float beta, int flags,
+                void *payload, void *workspace, void *stream);
+
+/* Aggregate + outer update (Algorithm 1, aggregation block; Eq. (2) lines 3-4):
+ *   per chunk a zero fp32 accumulator, workers added in the order r = 0..R-1
+ *   (acc[j] += LUT_r[code]), then theta = fma(-lr, acc * (1/R), theta) for every
+ *   element of the chunk; a coordinate a worker did not send counts as zero.
+ * theta    inout, device, fp32 arena, 16-byte aligned
+ * payloads in, HOST array of R DEVICE pointers, each a payload of this plan,
+ *          16-byte aligned; read only during the call's kernels
+ * R        1..SL_MAX_WORKERS
+ * Indices in a payload are trusted to be < 4096 (they are 12-bit by format) and
+ * to lie inside the tensor; payloads produced by sl_compress always do. */
+int sl_decompress_avg_apply(sl_plan *plan, float *theta, const void *const *payloads, int R,
+                            float lr, void *stream);
+
+/* The record encoder of the wire format on its own (appendix "Compression of
+ * indices in Top-k": 12-bit indices + 2-bit values): for each of n_chunks
+ * chunks, k ascending indices (< 4096) and k codes (0..3) -> one 7k/4-byte
+ * record; records are written back to back, without LUT headers.
+ * idx    in, device, uint16[n_chunks*k]
+ * codes  in, device, uint8[n_chunks*k]
+ * out    out, device, n_chunks*7k/4 bytes */
+int sl_pack_indices(const uint16_t *idx, const uint8_t *codes, int64_t n_chunks, int k, void *out,
+                    void *stream);
+
+const char *sl_strerror(int status);   /* static string                            */
+const char *sl_last_hip_error(void);   /* text of the last HIP failure, or ""      */
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SPARSELOCO_H */

@@ -1,0 +1,187 @@
+"""Thin ctypes binding of libsparseloco.so - argument marshalling only.
+
+Every step of the path runs in the HIP kernels behind the C ABI declared in
+include/sparseloco.h; the functions here carry the same names and only turn
+torch tensors (device memory owned by the caller) into pointers.  There is no
+CPU fallback: if the library has not been built, importing symbols raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional, Sequence
+
+import torch
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libsparseloco.so")
+
+SL_LAYOUT_FLAT = 0
+SL_LAYOUT_TILE64 = 1
+SL_COMPRESS_DEFAULT = 0
+SL_COMPRESS_EF_FROZEN = 1
+SL_MAX_WORKERS = 64
+
+EXPORTS = [
+    "sl_plan_create", "sl_plan_destroy", "sl_plan_num_chunks", "sl_plan_num_elements",
+    "sl_payload_bytes", "sl_payload_tensor_offset", "sl_workspace_bytes", "sl_compress",
+    "sl_decompress_avg_apply", "sl_pack_indices", "sl_strerror", "sl_last_hip_error",
+]
+
+
+class SlTensor(C.Structure):
+    _fields_ = [("rows", C.c_int64), ("cols", C.c_int64), ("offset", C.c_int64),
+                ("layout", C.c_int32), ("reserved", C.c_int32)]
+
+
+class SparseLoCoError(RuntimeError):
+    def __init__(self, fn: str, status: int):
+        msg = lib().sl_strerror(status).decode()
+        hip = lib().sl_last_hip_error().decode()
+        super().__init__(f"{fn}: {msg} ({status})" + (f": {hip}" if status == -3 and hip else ""))
+        self.status = status
+
+
+_lib = None
+
+
+def lib():
+    """Loads the built library; raises if it is missing (there is no fallback)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(
+                f"{LIB_PATH} is not built - run `python -m paper_2508_15706_amd.build` "
+                "(or __graft_entry__.build()) first; this package has no CPU fallback")
+        L = C.CDLL(LIB_PATH)
+        vp, i64, i32, sz = C.c_void_p, C.c_int64, C.c_int, C.c_size_t
+        L.sl_plan_create.restype = i32
+        L.sl_plan_create.argtypes = [C.POINTER(SlTensor), i32, i32, C.POINTER(vp)]
+        L.sl_plan_destroy.restype = i32
+        L.sl_plan_destroy.argtypes = [vp]
+        L.sl_plan_num_chunks.restype = i64
+        L.sl_plan_num_chunks.argtypes = [vp]
+        L.sl_plan_num_elements.restype = i64
+        L.sl_plan_num_elements.argtypes = [vp]
+        L.sl_payload_bytes.restype = sz
+        L.sl_payload_bytes.argtypes = [vp]
+        L.sl_payload_tensor_offset.restype = sz
+        L.sl_payload_tensor_offset.argtypes = [vp, i32]
+        L.sl_workspace_bytes.restype = sz
+        L.sl_workspace_bytes.argtypes = [vp]
+        L.sl_compress.restype = i32
+        L.sl_compress.argtypes = [vp, vp, vp, C.c_float, i32, vp, vp, vp]
+        L.sl_decompress_avg_apply.restype = i32
+        L.sl_decompress_avg_apply.argtypes = [vp, vp, C.POINTER(vp), i32, C.c_float, vp]
+        L.sl_pack_indices.restype = i32
+        L.sl_pack_indices.argtypes = [vp, vp, i64, i32, vp, vp]
+        L.sl_strerror.restype = C.c_char_p
+        L.sl_strerror.argtypes = [i32]
+        L.sl_last_hip_error.restype = C.c_char_p
+        L.sl_last_hip_error.argtypes = []
+        _lib = L
+    return _lib
+
+
+def _stream_ptr(stream) -> Optional[int]:
+    if stream is None:
+        return torch.cuda.current_stream().cuda_stream or None
+    if isinstance(stream, torch.cuda.Stream):
+        return stream.cuda_stream or None
+    return int(stream) or None
+
+
+def _dev_ptr(t: Optional[torch.Tensor], dtype=None) -> Optional[int]:
+    if t is None:
+        return None
+    if not t.is_cuda or not t.is_contiguous():
+        raise ValueError("expected a contiguous device tensor")
+    if dtype is not None and t.dtype != dtype:
+        raise ValueError(f"expected dtype {dtype}, got {t.dtype}")
+    return t.data_ptr()
+
+
+class Plan:
+    """Owner of an sl_plan handle."""
+
+    def __init__(self, handle: int, k: int, n_tensors: int):
+        self.handle, self.k, self.n_tensors = handle, k, n_tensors
+
+    @property
+    def num_chunks(self) -> int:
+        return int(lib().sl_plan_num_chunks(self.handle))
+
+    @property
+    def num_elements(self) -> int:
+        return int(lib().sl_plan_num_elements(self.handle))
+
+    @property
+    def payload_bytes(self) -> int:
+        return int(lib().sl_payload_bytes(self.handle))
+
+    @property
+    def workspace_bytes(self) -> int:
+        return int(lib().sl_workspace_bytes(self.handle))
+
+    def tensor_offset(self, t: int) -> int:
+        return int(lib().sl_payload_tensor_offset(self.handle, t))
+
+    def close(self):
+        if self.handle:
+            lib().sl_plan_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def sl_plan_create(descs: Sequence[Sequence[int]], k: int) -> Plan:
+    """descs: (rows, cols, offset, layout) per tensor."""
+    descs = list(descs)
+    arr = (SlTensor * max(1, len(descs)))()
+    for i, (r, c, off, lay) in enumerate(descs):
+        arr[i] = SlTensor(int(r), int(c), int(off), int(lay), 0)
+    h = C.c_void_p()
+    st = lib().sl_plan_create(arr, len(descs), int(k), C.byref(h))
+    if st:
+        raise SparseLoCoError("sl_plan_create", st)
+    return Plan(h.value, int(k), len(descs))
+
+
+def sl_compress(plan: Plan, e: Optional[torch.Tensor], delta: torch.Tensor, beta: float,
+                payload: torch.Tensor, workspace: torch.Tensor, flags: int = SL_COMPRESS_DEFAULT,
+                stream=None) -> None:
+    st = lib().sl_compress(plan.handle, _dev_ptr(e, torch.float32), _dev_ptr(delta, torch.float32),
+                           float(beta), int(flags), _dev_ptr(payload, torch.uint8),
+                           _dev_ptr(workspace, torch.uint8), _stream_ptr(stream))
+    if st:
+        raise SparseLoCoError("sl_compress", st)
+
+
+def sl_decompress_avg_apply(plan: Plan, theta: torch.Tensor, payloads: Sequence[torch.Tensor],
+                            lr: float, stream=None) -> None:
+    R = len(payloads)
+    ptrs = (C.c_void_p * max(1, R))(*[_dev_ptr(p, torch.uint8) for p in payloads])
+    st = lib().sl_decompress_avg_apply(plan.handle, _dev_ptr(theta, torch.float32), ptrs, R,
+                                       float(lr), _stream_ptr(stream))
+    if st:
+        raise SparseLoCoError("sl_decompress_avg_apply", st)
+
+
+def sl_pack_indices(idx: torch.Tensor, codes: torch.Tensor, n_chunks: int, k: int,
+                    out: torch.Tensor, stream=None) -> None:
+    st = lib().sl_pack_indices(_dev_ptr(idx, torch.uint16), _dev_ptr(codes, torch.uint8),
+                               int(n_chunks), int(k), _dev_ptr(out, torch.uint8), _stream_ptr(stream))
+    if st:
+        raise SparseLoCoError("sl_pack_indices", st)
+
+
+def alloc_payload(plan: Plan, device="cuda") -> torch.Tensor:
+    return torch.zeros(max(16, plan.payload_bytes), dtype=torch.uint8, device=device)
+
+
+def alloc_workspace(plan: Plan, device="cuda") -> torch.Tensor:
+    return torch.empty(plan.workspace_bytes, dtype=torch.uint8, device=device)

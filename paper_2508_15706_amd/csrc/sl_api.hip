@@ -1,0 +1,248 @@
+// Host side of the C ABI: plan construction (chunk work list), argument
+// validation and kernel sequencing.  See include/sparseloco.h for the contract.
+#include <algorithm>
+#include <cstdlib>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "sl_internal.h"
+
+static thread_local char g_hip_error[256] = "";
+
+void sl_note_hip_error(hipError_t e)
+{
+    std::strncpy(g_hip_error, hipGetErrorString(e), sizeof(g_hip_error) - 1);
+    g_hip_error[sizeof(g_hip_error) - 1] = 0;
+}
+
+static int hip_fail(hipError_t e)
+{
+    sl_note_hip_error(e);
+    return SL_ERR_HIP;
+}
+
+static size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+extern "C" {
+
+const char *sl_strerror(int status)
+{
+    switch (status) {
+        case SL_OK: return "ok";
+        case SL_ERR_INVALID_ARG: return "invalid argument";
+        case SL_ERR_BAD_PAYLOAD: return "malformed payload";
+        case SL_ERR_HIP: return "HIP runtime error";
+        case SL_ERR_NOMEM: return "out of memory";
+        case SL_ERR_DEVICE: return "plan belongs to another device";
+        default: return "unknown status";
+    }
+}
+
+const char *sl_last_hip_error(void) { return g_hip_error; }
+
+int sl_plan_create(const sl_tensor *tensors, int n_tensors, int k, sl_plan **out)
+{
+    if (!out) return SL_ERR_INVALID_ARG;
+    *out = nullptr;
+    if (n_tensors < 0 || (n_tensors > 0 && !tensors)) return SL_ERR_INVALID_ARG;
+    if (k < 4 || k > SL_CHUNK || (k & 3)) return SL_ERR_INVALID_ARG;
+
+    const int64_t rec = (int64_t)7 * k / 4;
+    std::vector<SlChunkDesc> desc;
+    std::vector<int> chunk_tensor;
+    std::vector<SlTensorDev> tdev((size_t)n_tensors);
+    int64_t n_elements = 0, n_partial = 0;
+    size_t pay = 0;
+
+    // tensors must not overlap: results would depend on processing order
+    {
+        std::vector<std::pair<int64_t, int64_t>> span;
+        for (int t = 0; t < n_tensors; ++t) {
+            const sl_tensor &T = tensors[t];
+            if (T.rows < 1 || T.cols < 1 || T.offset < 0 || (T.offset & 3) || T.reserved != 0)
+                return SL_ERR_INVALID_ARG;
+            if (T.layout != SL_LAYOUT_FLAT && T.layout != SL_LAYOUT_TILE64) return SL_ERR_INVALID_ARG;
+            if (T.rows > (int64_t)1 << 40 || T.cols > (int64_t)1 << 40 ||
+                T.rows * T.cols > (int64_t)1 << 46)
+                return SL_ERR_INVALID_ARG;
+            if (T.layout == SL_LAYOUT_TILE64 && T.cols > (int64_t)1 << 24) return SL_ERR_INVALID_ARG;
+            span.emplace_back(T.offset, T.offset + T.rows * T.cols);
+        }
+        std::sort(span.begin(), span.end());
+        for (size_t i = 1; i < span.size(); ++i)
+            if (span[i].first < span[i - 1].second) return SL_ERR_INVALID_ARG;
+    }
+
+    try {
+        for (int t = 0; t < n_tensors; ++t) {
+            const sl_tensor &T = tensors[t];
+            SlTensorDev &D = tdev[(size_t)t];
+            D.chunk0 = (long long)desc.size();
+            if (T.layout == SL_LAYOUT_TILE64) {
+                const int64_t tr = (T.rows + 63) / 64, tc = (T.cols + 63) / 64;
+                for (int64_t a = 0; a < tr; ++a)
+                    for (int64_t b = 0; b < tc; ++b) {
+                        SlChunkDesc d;
+                        d.base = T.offset + a * 64 * T.cols + b * 64;
+                        d.stride = (int)T.cols;
+                        const int64_t rv = std::min<int64_t>(64, T.rows - a * 64);
+                        const int64_t cv = std::min<int64_t>(64, T.cols - b * 64);
+                        if (rv * cv < k) return SL_ERR_INVALID_ARG;
+                        d.rows = (unsigned char)rv;
+                        d.cols = d.last_cols = (unsigned char)cv;
+                        d.flags = (rv == 64 && cv == 64 && (T.cols & 3) == 0) ? SLC_FULL : 0;
+                        desc.push_back(d);
+                        chunk_tensor.push_back(t);
+                    }
+            } else {
+                const int64_t n = T.rows * T.cols;
+                for (int64_t a = 0; a * SL_CHUNK < n; ++a) {
+                    SlChunkDesc d;
+                    d.base = T.offset + a * SL_CHUNK;
+                    d.stride = 64;
+                    const int64_t nv = std::min<int64_t>(SL_CHUNK, n - a * SL_CHUNK);
+                    if (nv < k) return SL_ERR_INVALID_ARG;
+                    d.rows = (unsigned char)((nv + 63) / 64);
+                    d.cols = 64;
+                    d.last_cols = (unsigned char)(nv - (int64_t)(d.rows - 1) * 64);
+                    d.flags = nv == SL_CHUNK ? SLC_FULL : 0;
+                    desc.push_back(d);
+                    chunk_tensor.push_back(t);
+                }
+            }
+            D.n_chunks = (long long)desc.size() - D.chunk0;
+            D.pay_off = (long long)pay;
+            D.block_bytes = (long long)align_up((size_t)(16 + D.n_chunks * rec), 16);
+            pay += (size_t)D.block_bytes;
+            n_elements += T.rows * T.cols;
+        }
+    } catch (const std::bad_alloc &) {
+        return SL_ERR_NOMEM;
+    }
+    if (desc.size() > 0x7FFFFFFFu) return SL_ERR_INVALID_ARG;
+    for (const SlChunkDesc &d : desc) n_partial += !(d.flags & SLC_FULL);
+
+    sl_plan *p = new (std::nothrow) sl_plan();
+    if (!p) return SL_ERR_NOMEM;
+    std::memset(p, 0, sizeof(*p));
+    p->k = k;
+    p->n_tensors = n_tensors;
+    p->n_chunks = (int64_t)desc.size();
+    p->n_elements = n_elements;
+    p->n_partial = n_partial;
+    p->payload_bytes = pay;
+
+    size_t off = 0;
+    p->ws_vals = off;   off = align_up(off + (size_t)p->n_chunks * k * sizeof(float), 256);
+    p->ws_leafA = off;  off = align_up(off + (size_t)p->n_chunks * 2 * sizeof(double), 256);
+    p->ws_leafC = off;  off = align_up(off + (size_t)p->n_chunks * 4 * sizeof(double), 256);
+    p->ws_cnt = off;    off = align_up(off + (size_t)p->n_chunks * 4 * sizeof(unsigned), 256);
+    p->ws_tstat = off;  off = align_up(off + (size_t)n_tensors * sizeof(SlTensorStat), 256);
+    p->ws_bytes = off ? off : 256;
+
+    hipError_t err = hipGetDevice(&p->device);
+    if (err != hipSuccess) {
+        delete p;
+        return hip_fail(err);
+    }
+    p->h_tensors = (SlTensorDev *)std::malloc(sizeof(SlTensorDev) * (size_t)std::max(1, n_tensors));
+    if (!p->h_tensors) {
+        delete p;
+        return SL_ERR_NOMEM;
+    }
+    if (n_tensors) std::memcpy(p->h_tensors, tdev.data(), sizeof(SlTensorDev) * (size_t)n_tensors);
+
+    if (p->n_chunks > 0) {
+        const size_t b_desc = desc.size() * sizeof(SlChunkDesc), b_ct = desc.size() * sizeof(int),
+                     b_t = (size_t)n_tensors * sizeof(SlTensorDev);
+        if ((err = hipMalloc((void **)&p->d_desc, b_desc)) != hipSuccess ||
+            (err = hipMalloc((void **)&p->d_chunk_tensor, b_ct)) != hipSuccess ||
+            (err = hipMalloc((void **)&p->d_tensors, b_t)) != hipSuccess ||
+            (err = hipMemcpy(p->d_desc, desc.data(), b_desc, hipMemcpyHostToDevice)) != hipSuccess ||
+            (err = hipMemcpy(p->d_chunk_tensor, chunk_tensor.data(), b_ct, hipMemcpyHostToDevice)) !=
+                hipSuccess ||
+            (err = hipMemcpy(p->d_tensors, tdev.data(), b_t, hipMemcpyHostToDevice)) != hipSuccess) {
+            const int rc = err == hipErrorOutOfMemory ? SL_ERR_NOMEM : hip_fail(err);
+            sl_plan_destroy(p);
+            return rc;
+        }
+    }
+    *out = p;
+    return SL_OK;
+}
+
+int sl_plan_destroy(sl_plan *p)
+{
+    if (!p) return SL_OK;
+    if (p->d_desc) (void)hipFree(p->d_desc);
+    if (p->d_chunk_tensor) (void)hipFree(p->d_chunk_tensor);
+    if (p->d_tensors) (void)hipFree(p->d_tensors);
+    std::free(p->h_tensors);
+    delete p;
+    return SL_OK;
+}
+
+int64_t sl_plan_num_chunks(const sl_plan *p) { return p ? p->n_chunks : -1; }
+int64_t sl_plan_num_elements(const sl_plan *p) { return p ? p->n_elements : -1; }
+size_t sl_payload_bytes(const sl_plan *p) { return p ? p->payload_bytes : 0; }
+size_t sl_workspace_bytes(const sl_plan *p) { return p ? p->ws_bytes : 0; }
+
+size_t sl_payload_tensor_offset(const sl_plan *p, int t)
+{
+    if (!p || t < 0 || t >= p->n_tensors) return (size_t)-1;
+    return (size_t)p->h_tensors[t].pay_off;
+}
+
+static int check_device(const sl_plan *p)
+{
+    int dev = -1;
+    hipError_t err = hipGetDevice(&dev);
+    if (err != hipSuccess) return hip_fail(err);
+    return dev == p->device ? SL_OK : SL_ERR_DEVICE;
+}
+
+static bool misaligned(const void *ptr, size_t a) { return ((uintptr_t)ptr & (a - 1)) != 0; }
+
+int sl_compress(sl_plan *p, float *e, const float *delta, float beta, int flags, void *payload,
+                void *workspace, void *stream)
+{
+    if (!p || !delta || !payload || !workspace) return SL_ERR_INVALID_ARG;
+    if (flags & ~SL_COMPRESS_EF_FROZEN) return SL_ERR_INVALID_ARG;
+    const int frozen = (flags & SL_COMPRESS_EF_FROZEN) ? 1 : 0;
+    if (!frozen && !e) return SL_ERR_INVALID_ARG;
+    if (e == delta) return SL_ERR_INVALID_ARG;
+    if (misaligned(e, 16) || misaligned(delta, 16) || misaligned(payload, 16) ||
+        misaligned(workspace, 256))
+        return SL_ERR_INVALID_ARG;
+    int rc = check_device(p);
+    if (rc) return rc;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    unsigned char *pay = static_cast<unsigned char *>(payload);
+    unsigned char *ws = static_cast<unsigned char *>(workspace);
+    if ((rc = slk_select(p, e, delta, beta, frozen, pay, ws, st))) return rc;
+    return slk_quantize(p, e, frozen, pay, ws, st);
+}
+
+int sl_decompress_avg_apply(sl_plan *p, float *theta, const void *const *payloads, int R, float lr,
+                            void *stream)
+{
+    if (!p || !theta || !payloads || R < 1 || R > SL_MAX_WORKERS) return SL_ERR_INVALID_ARG;
+    if (misaligned(theta, 16)) return SL_ERR_INVALID_ARG;
+    for (int r = 0; r < R; ++r)
+        if (!payloads[r] || misaligned(payloads[r], 16)) return SL_ERR_INVALID_ARG;
+    int rc = check_device(p);
+    if (rc) return rc;
+    return slk_apply(p, theta, payloads, R, lr, static_cast<hipStream_t>(stream));
+}
+
+int sl_pack_indices(const uint16_t *idx, const uint8_t *codes, int64_t n_chunks, int k, void *out,
+                    void *stream)
+{
+    if (n_chunks < 0 || k < 4 || k > SL_CHUNK || (k & 3)) return SL_ERR_INVALID_ARG;
+    if (n_chunks > 0 && (!idx || !codes || !out)) return SL_ERR_INVALID_ARG;
+    return slk_pack(idx, codes, n_chunks, k, static_cast<unsigned char *>(out),
+                    static_cast<hipStream_t>(stream));
+}
+
+}  // extern "C"

@@ -1,0 +1,199 @@
+// sl_decompress_avg_apply: dequantise R workers' sparse payloads, average and
+// take the outer SGD step in one pass over theta (Algorithm 1, "Aggregate +
+// Outer Update"; Eq. (2) lines 3-4), and the stand-alone record encoder
+// sl_pack_indices (12-bit index fields + 2-bit codes).
+//
+// One wavefront owns one chunk.  The dense average never exists in HBM: the
+// chunk's 4096 fp32 accumulators live in LDS (16 KB), the R records (7k/4 bytes
+// each) are staged into LDS with coalesced loads, entries of one worker are
+// distinct positions so they are added without conflicts, workers are added in
+// the order r = 0..R-1, and theta streams through registers once
+// (8 bytes per element of HBM traffic plus R*7k/4 bytes per chunk).
+#include "sl_device.h"
+#include "sl_internal.h"
+
+namespace {
+
+struct ApplyArgs {
+    const SlChunkDesc *desc;
+    const int *chunk_tensor;
+    const SlTensorDev *tensors;
+    float *theta;
+    float neg_lr, inv_R;
+    int R, k;
+    int batch;               // records staged per round
+    const unsigned char *payload[SL_MAX_WORKERS];
+};
+
+__global__ void __launch_bounds__(64) k_apply(ApplyArgs A)
+{
+    extern __shared__ __align__(16) unsigned char smem[];
+    float *acc = reinterpret_cast<float *>(smem);                    // 4096 floats
+    unsigned char *stage = smem + SL_CHUNK * sizeof(float);
+    const int lane = threadIdx.x, k = A.k;
+    const long long c = blockIdx.x;
+    const SlChunkDesc d = A.desc[c];
+    const int t = A.chunk_tensor[c];
+    const SlTensorDev td = A.tensors[t];
+    const int rec_bytes = 7 * k / 4;
+    const int rec_pad = ((rec_bytes + 3) & ~3) + 16;                 // staging pitch: LUT + record
+    const long long rec_off = td.pay_off + 16 + (c - td.chunk0) * (long long)rec_bytes;
+
+    float *tc = A.theta + d.base;
+    const int lr = lane >> 4, lc = (lane & 15) * 4;
+    const unsigned stride = (unsigned)d.stride;
+    const bool full = d.flags & SLC_FULL;
+
+    // theta loads are issued first so that their latency overlaps the decode
+    float4 th[16];
+    if (full) {
+        const unsigned o0 = lr * stride + lc;
+#pragma unroll
+        for (int i = 0; i < 16; ++i)
+            th[i] = *reinterpret_cast<const float4 *>(tc + (o0 + 4u * i * stride));
+    }
+
+#pragma unroll
+    for (int i = 0; i < 16; ++i)
+        reinterpret_cast<float4 *>(acc)[i * 64 + lane] = make_float4(0.f, 0.f, 0.f, 0.f);
+
+    for (int r0 = 0; r0 < A.R; r0 += A.batch) {
+        const int nb = min(A.batch, A.R - r0);
+        __syncthreads();
+        for (int w = lane; w < nb * 4; w += 64) {                    // the tensor's LUT of each worker
+            const int r = w >> 2, q = w & 3;
+            reinterpret_cast<unsigned *>(stage)[r * (rec_pad >> 2) + q] =
+                reinterpret_cast<const unsigned *>(A.payload[r0 + r] + td.pay_off)[q];
+        }
+        if ((rec_bytes & 3) == 0) {
+            const int words = rec_bytes >> 2;
+            for (int w = lane; w < nb * words; w += 64) {
+                const int r = w / words, q = w - r * words;
+                reinterpret_cast<unsigned *>(stage)[r * (rec_pad >> 2) + 4 + q] =
+                    reinterpret_cast<const unsigned *>(A.payload[r0 + r] + rec_off)[q];
+            }
+        } else {
+            for (int b = lane; b < nb * rec_bytes; b += 64) {
+                const int r = b / rec_bytes, q = b - r * rec_bytes;
+                stage[r * rec_pad + 16 + q] = A.payload[r0 + r][rec_off + q];
+            }
+        }
+        __syncthreads();
+        for (int r = 0; r < nb; ++r) {
+            const float4 lut = *reinterpret_cast<const float4 *>(stage + r * rec_pad);
+            const unsigned char *rec = stage + r * rec_pad + 16;
+            const unsigned char *codes = rec + 3 * k / 2;
+            for (int m = lane; m < k; m += 64) {
+                const int b = (3 * m) >> 1;
+                const unsigned w = (unsigned)rec[b] | ((unsigned)rec[b + 1] << 8);
+                const unsigned j = (m & 1) ? (w >> 4) : (w & 0xFFFu);
+                const unsigned code = (codes[m >> 2] >> (2 * (m & 3))) & 3u;
+                const float q = code == 0 ? lut.x : code == 1 ? lut.y : code == 2 ? lut.z : lut.w;
+                acc[j] = acc[j] + q;
+            }
+            __syncthreads();          // worker r is complete before worker r+1 is added
+        }
+    }
+
+    if (full) {
+        const unsigned o0 = lr * stride + lc;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            const float4 a = reinterpret_cast<const float4 *>(acc)[i * 64 + lane];
+            float4 v = th[i];
+            v.x = fmaf(A.neg_lr, a.x * A.inv_R, v.x);
+            v.y = fmaf(A.neg_lr, a.y * A.inv_R, v.y);
+            v.z = fmaf(A.neg_lr, a.z * A.inv_R, v.z);
+            v.w = fmaf(A.neg_lr, a.w * A.inv_R, v.w);
+            *reinterpret_cast<float4 *>(tc + (o0 + 4u * i * stride)) = v;
+        }
+    } else {
+        const int rows = d.rows, cols = d.cols, last_cols = d.last_cols;
+        for (int i = 0; i < 16; ++i) {
+            const int row = 4 * i + lr;
+            const int lim = row < rows - 1 ? cols : (row == rows - 1 ? last_cols : 0);
+            for (int cc = 0; cc < 4; ++cc) {
+                const int col = lc + cc;
+                if (col < lim) {
+                    const unsigned o = row * stride + col;
+                    tc[o] = fmaf(A.neg_lr, acc[256 * i + 4 * lane + cc] * A.inv_R, tc[o]);
+                }
+            }
+        }
+    }
+}
+
+// One thread per output byte of the record stream.
+__global__ void __launch_bounds__(256)
+k_pack(const uint16_t *idx, const uint8_t *codes, long long n_chunks, int k, unsigned char *out)
+{
+    const long long rec_bytes = (long long)7 * k / 4;
+    const long long total = n_chunks * rec_bytes;
+    const int nidx = 3 * k / 2;
+    for (long long o = (long long)blockIdx.x * blockDim.x + threadIdx.x; o < total;
+         o += (long long)gridDim.x * blockDim.x) {
+        const long long c = o / rec_bytes;
+        const int b = (int)(o - c * rec_bytes);
+        unsigned v;
+        if (b < nidx) {
+            const int bit0 = 8 * b, m = bit0 / 12, sh = bit0 - 12 * m;   // sh = 0, 4 or 8
+            v = ((unsigned)idx[c * k + m] & 0xFFFu) >> sh;
+            if (sh == 8 && m + 1 < k) v |= ((unsigned)idx[c * k + m + 1] & 0xFFFu) << 4;
+        } else {
+            const int m0 = 4 * (b - nidx);
+            v = 0;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) v |= ((unsigned)codes[c * k + m0 + q] & 3u) << (2 * q);
+        }
+        out[o] = (unsigned char)v;
+    }
+}
+
+}  // namespace
+
+int slk_apply(const sl_plan *p, float *theta, const void *const *payloads, int R, float lr,
+              hipStream_t st)
+{
+    if (p->n_chunks == 0) return SL_OK;
+    ApplyArgs A;
+    A.desc = p->d_desc;
+    A.chunk_tensor = p->d_chunk_tensor;
+    A.tensors = p->d_tensors;
+    A.theta = theta;
+    A.neg_lr = -lr;
+    A.inv_R = 1.0f / (float)R;
+    A.R = R;
+    A.k = p->k;
+    const int rec_pad = ((7 * p->k / 4 + 3) & ~3) + 16;
+    int batch = 16384 / rec_pad;          // at most 16 KB of staged records
+    if (batch < 1) batch = 1;
+    if (batch > R) batch = R;
+    A.batch = batch;
+    for (int r = 0; r < SL_MAX_WORKERS; ++r)
+        A.payload[r] = r < R ? static_cast<const unsigned char *>(payloads[r]) : nullptr;
+    const size_t lds = SL_CHUNK * sizeof(float) + (size_t)batch * rec_pad;
+    hipLaunchKernelGGL(k_apply, dim3((unsigned)p->n_chunks), dim3(64), lds, st, A);
+    hipError_t err = hipGetLastError();
+    if (err != hipSuccess) {
+        sl_note_hip_error(err);
+        return SL_ERR_HIP;
+    }
+    return SL_OK;
+}
+
+int slk_pack(const uint16_t *idx, const uint8_t *codes, int64_t n_chunks, int k, unsigned char *out,
+             hipStream_t st)
+{
+    const long long total = n_chunks * ((long long)7 * k / 4);
+    if (total == 0) return SL_OK;
+    long long blocks = (total + 255) / 256;
+    if (blocks > 65536) blocks = 65536;
+    hipLaunchKernelGGL(k_pack, dim3((unsigned)blocks), dim3(256), 0, st, idx, codes,
+                       (long long)n_chunks, k, out);
+    hipError_t err = hipGetLastError();
+    if (err != hipSuccess) {
+        sl_note_hip_error(err);
+        return SL_ERR_HIP;
+    }
+    return SL_OK;
+}

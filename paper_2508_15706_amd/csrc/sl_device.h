@@ -1,0 +1,87 @@
+// Wave64 helpers for the gfx950 kernels: ballots, cross-lane butterflies and
+// the fixed-shape fp64 summation tree.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#define SL_DEV __device__ __forceinline__
+
+SL_DEV unsigned long long sl_ballot(bool p) { return __builtin_amdgcn_ballot_w64(p); }
+
+// Number of set bits of `m` below this lane.
+SL_DEV int sl_mbcnt(unsigned long long m)
+{
+    return __builtin_amdgcn_mbcnt_hi((unsigned)(m >> 32), __builtin_amdgcn_mbcnt_lo((unsigned)m, 0u));
+}
+
+SL_DEV int sl_popc(unsigned long long m) { return __builtin_popcountll(m); }
+
+SL_DEV int sl_uniform(int v) { return __builtin_amdgcn_readfirstlane(v); }
+
+SL_DEV int sl_wave_max(int v)
+{
+#pragma unroll
+    for (int s = 32; s >= 1; s >>= 1) v = max(v, __shfl_xor(v, s));
+    return sl_uniform(v);
+}
+
+SL_DEV int sl_wave_min(int v)
+{
+#pragma unroll
+    for (int s = 32; s >= 1; s >>= 1) v = min(v, __shfl_xor(v, s));
+    return sl_uniform(v);
+}
+
+SL_DEV int sl_pow2ceil(int n)
+{
+    int p = 1;
+    while (p < n) p <<= 1;
+    return p;
+}
+
+// Adjacent-pair tree over the 64 lanes' values, `levels` levels (1 <= 2^levels
+// <= 64): afterwards every lane whose index is a multiple of 2^levels holds the
+// sum of its aligned group in the fixed pairing (v[2i] + v[2i+1] at each level).
+SL_DEV double sl_wave_tree(double v, int levels)
+{
+    for (int l = 0; l < levels; ++l) v = v + __shfl_xor(v, 1 << l);
+    return v;
+}
+
+SL_DEV double sl_lane0(double v)
+{
+    int lo = __builtin_amdgcn_readfirstlane(__double2loint(v));
+    int hi = __builtin_amdgcn_readfirstlane(__double2hiint(v));
+    return __hiloint2double(hi, lo);
+}
+
+// Fixed summation tree of one chunk's k per-entry values (the leaf of the
+// two-level sum).  Entry p lives in lane p % 64, slot p / 64; y(slot) returns
+// this lane's value for that slot (+0.0 beyond k).  The sequence is padded with
+// +0.0 to P = pow2ceil(k) and reduced by adjacent pairs.  `scratch` is a
+// 64-double LDS array private to the wave.  The result is uniform.
+template <class F>
+SL_DEV double sl_chunk_tree(int k, int lane, double *scratch, F y)
+{
+    const int P = sl_pow2ceil(k);
+    if (P <= 64) {
+        int levels = 0;
+        while ((1 << levels) < P) ++levels;
+        return sl_lane0(sl_wave_tree(y(0), levels));
+    }
+    const int slots = P / 64;           // power of two, <= 64
+    const int used = (k + 63) / 64;
+    __syncthreads();
+    if (lane >= used && lane < slots) scratch[lane] = 0.0;
+    for (int s = 0; s < used; ++s) {
+        double t = sl_wave_tree(y(s), 6);
+        if (lane == 0) scratch[s] = t;
+    }
+    __syncthreads();
+    double v = lane < slots ? scratch[lane] : 0.0;
+    int levels = 0;
+    while ((1 << levels) < slots) ++levels;
+    double r = sl_lane0(sl_wave_tree(v, levels));
+    __syncthreads();
+    return r;
+}

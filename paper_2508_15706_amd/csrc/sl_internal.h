@@ -1,0 +1,63 @@
+// Internal structures shared by the host API and the gfx950 kernels.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "sparseloco.h"
+
+// One 4096-element chunk seen as a 64-row view: element (row, col) of the view
+// is arena[base + row*stride + col].  A FLAT chunk is the view with stride 64.
+// `rows` valid rows; every valid row has `cols` valid columns except the last
+// valid row, which has `last_cols`.
+struct SlChunkDesc {
+    long long base;
+    int stride;
+    unsigned char rows, cols, last_cols, flags;
+};
+static_assert(sizeof(SlChunkDesc) == 16, "descriptor is one 16-byte load");
+enum { SLC_FULL = 1 };   // all 4096 positions valid and every row 16-byte aligned
+
+struct SlTensorDev {
+    long long chunk0;       // first chunk of the tensor in list order
+    long long n_chunks;
+    long long pay_off;      // byte offset of the tensor's block in a payload
+    long long block_bytes;  // align16(16 + n_chunks * record_bytes)
+};
+
+// Per-tensor quantizer state produced during sl_compress.
+struct SlTensorStat {
+    double mu;      // mean of the selected values
+    double T;       // 9 * variance: squared distance of the outer bin edges from the mean
+    float lut[4];   // centroids
+};
+static_assert(sizeof(SlTensorStat) == 32, "");
+
+struct sl_plan {
+    int k;
+    int n_tensors;
+    int device;
+    int64_t n_chunks;
+    int64_t n_elements;
+    int64_t n_partial;          // chunks without SLC_FULL
+    size_t payload_bytes;
+    size_t ws_bytes;
+    // workspace sections (byte offsets)
+    size_t ws_vals, ws_leafA, ws_leafC, ws_cnt, ws_tstat;
+    // device tables
+    SlChunkDesc *d_desc;
+    int *d_chunk_tensor;
+    SlTensorDev *d_tensors;
+    // host copies
+    SlTensorDev *h_tensors;
+};
+
+// launchers (defined next to their kernels)
+int slk_select(const sl_plan *p, float *e, const float *delta, float beta, int frozen,
+               unsigned char *payload, unsigned char *ws, hipStream_t st);
+int slk_quantize(const sl_plan *p, float *e, int frozen, unsigned char *payload, unsigned char *ws,
+                 hipStream_t st);
+int slk_apply(const sl_plan *p, float *theta, const void *const *payloads, int R, float lr,
+              hipStream_t st);
+int slk_pack(const uint16_t *idx, const uint8_t *codes, int64_t n_chunks, int k, unsigned char *out,
+             hipStream_t st);
+void sl_note_hip_error(hipError_t e);

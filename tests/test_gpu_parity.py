@@ -1,0 +1,264 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle.
+
+Bar: selected indices and payload bytes bit-exact; fp32 values (e, theta, LUT)
+within 1e-6 relative - the tests first check bit-identity, which the pinned
+operation order makes attainable, and report the relative error otherwise.
+"""
+import numpy as np
+import pytest
+import torch
+
+pytestmark = pytest.mark.gpu
+
+FLAT, TILE = 0, 1
+REL_TOL = 1e-6
+
+
+@pytest.fixture(scope="module")
+def sl():
+    from paper_2508_15706_amd import binding
+    binding.lib()
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    return binding
+
+
+def layout_list(shapes):
+    descs, off = [], 0
+    for r, c, lay in shapes:
+        descs.append((r, c, off, lay))
+        off += (r * c + 63) // 64 * 64
+    return descs, off
+
+
+def assert_f32_close(got, want, what):
+    got, want = np.asarray(got), np.asarray(want)
+    if np.array_equal(got.view(np.uint32), want.view(np.uint32)):
+        return
+    denom = np.maximum(np.abs(want), 1e-30)
+    rel = np.abs(got.astype(np.float64) - want.astype(np.float64)) / denom
+    bad = int((got.view(np.uint32) != want.view(np.uint32)).sum())
+    assert rel.max() <= REL_TOL, f"{what}: {bad} values differ, max rel err {rel.max():.3e}"
+
+
+def gpu_compress(sl, plan, e_host, d_host, beta, flags=0):
+    e = torch.from_numpy(e_host).cuda()
+    d = torch.from_numpy(d_host).cuda()
+    pay = sl.alloc_payload(plan)
+    pay.fill_(0xAB)                      # every byte must be written by the library
+    ws = sl.alloc_workspace(plan)
+    sl.sl_compress(plan, e, d, beta, pay, ws, flags=flags)
+    torch.cuda.synchronize()
+    return e.cpu().numpy(), pay[:plan.payload_bytes].cpu().numpy(), pay
+
+
+def check_compress(sl, oracle, descs, n, k, e0, delta, beta, flags=0, what=""):
+    plan = sl.sl_plan_create(descs, k)
+    assert plan.num_chunks == oracle.num_chunks(descs)
+    assert plan.payload_bytes == oracle.payload_bytes(descs, k)
+    e_gpu, pay_gpu, _ = gpu_compress(sl, plan, e0, delta, beta, flags)
+    e_ref = e0.copy()
+    pay_ref = oracle.compress(descs, k, e_ref, delta, beta, ef_frozen=bool(flags & 1))
+    if not np.array_equal(pay_gpu, pay_ref):
+        diff = np.nonzero(pay_gpu != pay_ref)[0]
+        raise AssertionError(f"{what} k={k}: payload differs at {diff.size} bytes, first at {diff[:8]}")
+    assert_f32_close(e_gpu, e_ref, f"{what} k={k} e")
+    plan.close()
+    return pay_ref, e_ref
+
+
+# --------------------------------------------------------------------------- compress
+@pytest.mark.parametrize("k", [4, 8, 20, 32, 64, 128, 256, 512, 1000])
+def test_compress_small_list_all_k_paths(sl, oracle, k):
+    """Several tiles, ragged edges in both directions, 16-column matrix, 1-D tails;
+    k covers every pruning width, the byte-wise record writer and the unpruned path."""
+    if k <= 256:      # smallest chunk: 22 x 18 = 396 elements
+        shapes = [(150, 210, TILE), (1, 9000, FLAT), (1024, 16, TILE), (64, 64, TILE),
+                  (1, 4096 + 1030, FLAT), (128, 192, TILE)]
+        if k <= 32:   # smallest chunk: 6 x 6 = 36 elements
+            shapes += [(140, 200, TILE), (70, 70, TILE)]
+    else:             # smallest chunk: 1000 elements
+        shapes = [(160, 224, TILE), (1024, 16, TILE), (1, 8192 + 1000, FLAT), (100, 133, FLAT)]
+    descs, n = layout_list(shapes)
+    rng = np.random.default_rng(100 + k)
+    e0 = rng.normal(0, 1e-3, n).astype(np.float32)
+    delta = rng.normal(0, 1e-3, n).astype(np.float32)
+    check_compress(sl, oracle, descs, n, k, e0, delta, 0.95, what="small list")
+
+
+def test_compress_dense_case_k_4096(sl, oracle):
+    descs, n = layout_list([(64, 128, TILE), (1, 8192, FLAT)])
+    rng = np.random.default_rng(7)
+    e0 = rng.normal(0, 1e-3, n).astype(np.float32)
+    delta = rng.normal(0, 1e-3, n).astype(np.float32)
+    check_compress(sl, oracle, descs, n, 4096, e0, delta, 0.95, what="dense")
+
+
+@pytest.mark.parametrize("k", [32, 64, 128])
+def test_compress_ties_zeros_and_heavy_tails(sl, oracle, k):
+    """Degenerate inputs: all-zero tensors (all ties), few distinct magnitudes, signed
+    zeros, denormals, a heavy-tailed tensor, a tensor with one hot column."""
+    shapes = [(128, 128, TILE), (128, 128, TILE), (128, 128, TILE), (1, 8192, FLAT), (128, 128, TILE),
+              (128, 128, TILE), (1, 4096 + 700, FLAT)]
+    descs, n = layout_list(shapes)
+    rng = np.random.default_rng(200 + k)
+    delta = np.zeros(n, dtype=np.float32)
+    e0 = np.zeros(n, dtype=np.float32)
+    o = [d[2] for d in descs]
+    sz = [d[0] * d[1] for d in descs]
+    # tensor 0: all zero.  tensor 1: few distinct magnitudes with both signs
+    delta[o[1]:o[1] + sz[1]] = rng.choice([-3e-3, -1e-3, -0.0, 0.0, 1e-3, 3e-3], sz[1]).astype(np.float32)
+    # tensor 2: fewer than k non-zeros per chunk
+    t2 = np.zeros(sz[2], dtype=np.float32)
+    t2[rng.choice(sz[2], 40, replace=False)] = rng.normal(0, 1e-3, 40)
+    delta[o[2]:o[2] + sz[2]] = t2
+    # tensor 3: denormals and tiny values
+    delta[o[3]:o[3] + sz[3]] = (rng.integers(-200, 200, sz[3]) * 2.0**-149).astype(np.float32)
+    # tensor 4: heavy tails
+    delta[o[4]:o[4] + sz[4]] = (1e-3 * rng.standard_t(3, sz[4])).astype(np.float32)
+    # tensor 5: one hot column on top of noise
+    t5 = rng.normal(0, 1e-4, (128, 128)).astype(np.float32)
+    t5[:, 37] += 1.0
+    delta[o[5]:o[5] + sz[5]] = t5.ravel()
+    # tensor 6: constant (every value ties)
+    delta[o[6]:o[6] + sz[6]] = np.float32(2.5e-4)
+    e0[o[4]:o[4] + sz[4]] = rng.normal(0, 1e-3, sz[4]).astype(np.float32)
+    check_compress(sl, oracle, descs, n, k, e0, delta, 0.95, what="degenerate")
+
+
+def test_compress_ef_frozen(sl, oracle):
+    descs, n = layout_list([(140, 200, TILE), (1, 9000, FLAT)])
+    rng = np.random.default_rng(9)
+    e0 = rng.normal(0, 1e-3, n).astype(np.float32)
+    delta = rng.normal(0, 1e-3, n).astype(np.float32)
+    _, e_ref = check_compress(sl, oracle, descs, n, 32, e0, delta, 0.95, flags=sl.SL_COMPRESS_EF_FROZEN,
+                              what="frozen")
+    assert np.array_equal(e_ref, e0)
+
+
+def test_compress_is_deterministic_and_leaves_padding(sl, oracle):
+    descs, n = layout_list([(200, 140, TILE), (1, 5000, FLAT), (64, 64, TILE)])
+    n += 64
+    rng = np.random.default_rng(10)
+    e0 = rng.normal(0, 1e-3, n).astype(np.float32)
+    delta = rng.normal(0, 1e-3, n).astype(np.float32)
+    plan = sl.sl_plan_create(descs, 64)
+    e1, p1, _ = gpu_compress(sl, plan, e0, delta, 0.95)
+    e2, p2, _ = gpu_compress(sl, plan, e0, delta, 0.95)
+    assert np.array_equal(p1, p2) and np.array_equal(e1.view(np.uint32), e2.view(np.uint32))
+    inside = np.zeros(n, bool)
+    for r, c, off, _ in descs:
+        inside[off:off + r * c] = True
+    assert np.array_equal(e1[~inside].view(np.uint32), e0[~inside].view(np.uint32))
+
+
+# --------------------------------------------------------------------------- aggregate
+@pytest.mark.parametrize("R,k,lr", [(1, 32, 1.0), (3, 64, 0.7), (4, 64, 0.7), (8, 64, 1.0), (16, 32, 0.8),
+                                     (5, 20, 0.6), (33, 128, 0.5)])
+def test_apply_matches_oracle(sl, oracle, R, k, lr):
+    shapes = [(150, 210, TILE), (1, 9000, FLAT), (128, 128, TILE), (1024, 16, TILE)]
+    descs, n = layout_list(shapes)
+    rng = np.random.default_rng(300 + R)
+    plan = sl.sl_plan_create(descs, k)
+    payloads_dev, payloads_host = [], []
+    for r in range(R):
+        e0 = np.zeros(n, dtype=np.float32)
+        delta = rng.normal(0, 1e-3, n).astype(np.float32)
+        _, pay_host, pay_dev = gpu_compress(sl, plan, e0, delta, 0.95)
+        ref = oracle.compress(descs, k, e0.copy(), delta, 0.95)
+        assert np.array_equal(pay_host, ref)
+        payloads_dev.append(pay_dev)
+        payloads_host.append(ref)
+    theta0 = rng.normal(0, 0.02, n).astype(np.float32)
+    theta = torch.from_numpy(theta0).cuda()
+    sl.sl_decompress_avg_apply(plan, theta, payloads_dev, lr)
+    torch.cuda.synchronize()
+    want = theta0.copy()
+    oracle.decompress_avg_apply(descs, k, want, payloads_host, lr)
+    assert_f32_close(theta.cpu().numpy(), want, f"theta R={R}")
+
+
+def test_apply_order_of_workers_is_r_ascending(sl, oracle):
+    """Hand-made payloads: the fp32 sum at one coordinate depends on the order."""
+    descs = [(1, 4096, 0, FLAT)]
+    k = 4
+    plan = sl.sl_plan_create(descs, k)
+    vals = [1.0, 2.0**-24, 2.0**-24]
+    host = []
+    for v in vals:
+        blk = np.zeros(oracle.payload_bytes(descs, k), dtype=np.uint8)
+        blk[:16] = np.array([0, 0, v, 0], dtype=np.float32).view(np.uint8)
+        blk[16:23] = oracle.pack_record([5, 6, 7, 8], [2, 1, 1, 1])
+        host.append(blk)
+    for order in (host, host[::-1]):
+        dev = [torch.from_numpy(p).cuda() for p in order]
+        theta = torch.zeros(4096, dtype=torch.float32, device="cuda")
+        sl.sl_decompress_avg_apply(plan, theta, dev, 1.0)
+        want = np.zeros(4096, dtype=np.float32)
+        oracle.decompress_avg_apply(descs, k, want, order, 1.0)
+        assert np.array_equal(theta.cpu().numpy().view(np.uint32), want.view(np.uint32))
+
+
+# --------------------------------------------------------------------------- configuration 1, all rounds
+def test_config1_three_rounds_four_workers(sl, oracle):
+    from paper_2508_15706_amd import synth
+    w = synth.workload(1)
+    descs = [s.desc() for s in w.specs]
+    n = w.arena
+    plan = sl.sl_plan_create(descs, w.k)
+    ws = sl.alloc_workspace(plan)
+    e_dev = [torch.zeros(n, dtype=torch.float32, device="cuda") for _ in range(w.R)]
+    e_ref = [np.zeros(n, dtype=np.float32) for _ in range(w.R)]
+    theta = torch.empty(n, dtype=torch.float32, device="cuda")
+    synth.fill_theta(w, theta)
+    theta_ref = theta.cpu().numpy().copy()
+    delta = torch.empty(n, dtype=torch.float32, device="cuda")
+    pays = [sl.alloc_payload(plan) for _ in range(w.R)]
+    for rnd in range(1, w.rounds + 1):
+        ref_pays = []
+        for r in range(w.R):
+            synth.fill_delta(w, delta, rnd, r)
+            sl.sl_compress(plan, e_dev[r], delta, w.beta, pays[r], ws)
+            torch.cuda.synchronize()
+            ref = oracle.compress(descs, w.k, e_ref[r], delta.cpu().numpy(), w.beta)
+            assert np.array_equal(pays[r][:plan.payload_bytes].cpu().numpy(), ref), (rnd, r)
+            assert_f32_close(e_dev[r].cpu().numpy(), e_ref[r], f"e round {rnd} worker {r}")
+            ref_pays.append(ref)
+        sl.sl_decompress_avg_apply(plan, theta, pays, w.lr)
+        torch.cuda.synchronize()
+        oracle.decompress_avg_apply(descs, w.k, theta_ref, ref_pays, w.lr)
+        assert_f32_close(theta.cpu().numpy(), theta_ref, f"theta round {rnd}")
+
+
+# --------------------------------------------------------------------------- record encoder
+@pytest.mark.parametrize("k", [4, 32, 64, 100, 4096])
+def test_pack_indices(sl, oracle, k):
+    rng = np.random.default_rng(400 + k)
+    nc = 37
+    idx = np.stack([np.sort(rng.choice(4096, k, replace=False)) for _ in range(nc)]).astype(np.uint16)
+    code = rng.integers(0, 4, (nc, k)).astype(np.uint8)
+    out = torch.full((nc * 7 * k // 4,), 0xCD, dtype=torch.uint8, device="cuda")
+    idx_dev = torch.from_numpy(idx.view(np.int16)).cuda().view(torch.uint16)
+    sl.sl_pack_indices(idx_dev, torch.from_numpy(code).cuda(), nc, k, out)
+    torch.cuda.synchronize()
+    assert np.array_equal(out.cpu().numpy(), oracle.pack_indices(idx.ravel(), code.ravel(), nc, k))
+
+
+# --------------------------------------------------------------------------- argument errors
+def test_argument_errors_are_reported_not_launched(sl):
+    with pytest.raises(sl.SparseLoCoError):
+        sl.sl_plan_create([(64, 64, 0, TILE)], 6)                 # k not a multiple of 4
+    with pytest.raises(sl.SparseLoCoError):
+        sl.sl_plan_create([(1, 100, 0, FLAT)], 128)               # chunk smaller than k
+    with pytest.raises(sl.SparseLoCoError):
+        sl.sl_plan_create([(64, 64, 2, TILE)], 32)                # offset not 16-byte aligned
+    with pytest.raises(sl.SparseLoCoError):
+        sl.sl_plan_create([(64, 64, 0, TILE), (64, 64, 4000, TILE)], 32)   # overlap
+    plan = sl.sl_plan_create([(64, 64, 0, TILE)], 32)
+    theta = torch.zeros(4096, dtype=torch.float32, device="cuda")
+    pay = sl.alloc_payload(plan)
+    with pytest.raises(sl.SparseLoCoError):
+        sl.sl_decompress_avg_apply(plan, theta, [], 1.0)          # R = 0
+    with pytest.raises(sl.SparseLoCoError):
+        sl.sl_decompress_avg_apply(plan, theta, [pay] * 65, 1.0)  # R too large
+    with pytest.raises(sl.SparseLoCoError):
+        sl.sl_compress(plan, theta, theta, 0.95, pay, sl.alloc_workspace(plan))   # e aliases delta
