@@ -1,0 +1,181 @@
+#!/usr/bin/env python3
+"""Benchmark of the SparseLoCo compress + aggregate path on one MI355X.
+
+One "step" is one worker-round: sl_compress of one worker's pseudo-gradient
+(error-feedback accumulate, chunk Top-k, 2-bit quantizer, residual, payload) and
+sl_decompress_avg_apply of R workers' payloads fused with the outer SGD step,
+over the whole tensor list.  Inputs are synthetic and resident in HBM before
+the timed region.  Prints ONE JSON line.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 4] [--no-cpu-baseline]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E peak
+
+
+def cpu_baseline(w, sample_layers):
+    """The CPU oracle, as it stands, on a bounded sample of the same workload: the
+    tensors of the first `sample_layers` transformer layers, R workers compressed
+    (each timed) and one aggregation (timed)."""
+    import numpy as np
+    import torch
+    from oracle import oracle
+    from paper_2508_15706_amd import synth
+
+    names = tuple(f"l{l}." for l in range(sample_layers))
+    specs = [s for s in w.specs if s.name.startswith(names)] or list(w.specs)
+    base = min(s.offset for s in specs)
+    descs = [(s.rows, s.cols, s.offset - base, s.layout) for s in specs]
+    n = max(d[2] + d[0] * d[1] for d in descs)
+    n_el = sum(d[0] * d[1] for d in descs)
+    g = torch.Generator().manual_seed(synth.seed_for(w.config_id, 50, 0))
+    t_comp, pays = [], []
+    for r in range(w.R):
+        e = (torch.randn(n, generator=g) * w.scale).numpy()
+        d = (torch.randn(n, generator=g) * w.scale).numpy()
+        t0 = time.perf_counter()
+        pays.append(oracle.compress(descs, w.k, e, d, w.beta))
+        t_comp.append(time.perf_counter() - t0)
+    theta = (torch.randn(n, generator=g) * 0.02).numpy()
+    t0 = time.perf_counter()
+    oracle.decompress_avg_apply(descs, w.k, theta, pays, w.lr)
+    t_apply = time.perf_counter() - t0
+    t_round = sum(t_comp) / len(t_comp) + t_apply
+    return {
+        "value": n_el / t_round / 1e9, "unit": "Gelem/s", "cores": oracle.max_threads(),
+        "kind": "oracle",
+        "sample": f"tensors of the first {sample_layers} layers of the list ({len(specs)} tensors, "
+                  f"{n_el} elements): mean of R={w.R} compress calls + one aggregation; "
+                  f"cpu work {sum(t_comp) + t_apply:.1f} s",
+        "ms_compress": 1e3 * sum(t_comp) / len(t_comp), "ms_apply": 1e3 * t_apply,
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", type=int, default=4)
+    ap.add_argument("--k", type=int, default=None)
+    ap.add_argument("--flat", action="store_true", help="cut every tensor into runs of 4096")
+    ap.add_argument("--delta-buffers", type=int, default=3)
+    ap.add_argument("--cpu-layers", type=int, default=4)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on exactly one GPU (the R workers are R payload buffers on "
+              "it, no collectives); --gpus must be 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2508_15706_amd import binding as sl
+    from paper_2508_15706_amd import synth
+
+    sl.lib()                                   # fails loudly if the HIP library is not built
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    dev = torch.device("cuda:0")
+
+    w = synth.workload(args.config, k=args.k, flat=args.flat)
+    descs = [s.desc() for s in w.specs]
+    plan = sl.sl_plan_create(descs, w.k)
+    N, n_chunks, arena = plan.num_elements, plan.num_chunks, w.arena
+    ws = sl.alloc_workspace(plan)
+
+    # state: theta, worker 0's error buffer (persistent), R payload buffers
+    theta = torch.empty(arena, dtype=torch.float32, device=dev)
+    synth.fill_theta(w, theta)
+    e0 = torch.zeros(arena, dtype=torch.float32, device=dev)
+    pays = [sl.alloc_payload(plan) for _ in range(w.R)]
+    deltas = [torch.empty(arena, dtype=torch.float32, device=dev) for _ in range(args.delta_buffers)]
+
+    # set-up (untimed): the other workers' payloads of this round, each from its own delta
+    scratch_e = torch.zeros(arena, dtype=torch.float32, device=dev)
+    for r in range(1, w.R):
+        synth.fill_delta(w, deltas[0], 1, r)
+        scratch_e.zero_()
+        sl.sl_compress(plan, scratch_e, deltas[0], w.beta, pays[r], ws)
+    del scratch_e
+    for i, d in enumerate(deltas):             # worker 0's pseudo-gradients of successive rounds
+        synth.fill_delta(w, d, 1 + i, 0)
+    torch.cuda.synchronize()
+
+    def step(i):
+        sl.sl_compress(plan, e0, deltas[i % len(deltas)], w.beta, pays[0], ws)
+        sl.sl_decompress_avg_apply(plan, theta, pays, w.lr)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    sl.sl_profile_begin(plan, args.steps)
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(args.warmup + i)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    prof = sl.sl_profile_end(plan)
+
+    ms_step = 1e3 * dt / args.steps
+    rec = 7 * w.k // 4
+    bytes_round = 20 * N + (w.R + 1) * rec * n_chunks + 16 * len(descs) * (w.R + 1)
+    # dominant kernel: accumulate + select.  Algorithmic bytes per launch: read e and
+    # delta, write e (12 B/element) + the packed indices it writes (3k/2 B per chunk)
+    sel_ms = prof["select"][0]
+    sel_bytes = 12 * N + (3 * w.k // 2) * n_chunks
+    sel_gbs = sel_bytes / (sel_ms * 1e-3) / 1e9 if sel_ms > 0 else 0.0
+    apply_ms = prof["apply"][0]
+    apply_bytes = 8 * N + w.R * (rec * n_chunks + 16 * len(descs))
+    compress_ms = sum(prof[p][0] for p in ("select", "stats", "codes", "lut", "residual"))
+
+    # a plain device copy of the same footprint as a practical ceiling (context only)
+    src, dst = deltas[0], deltas[1 % len(deltas)]
+    torch.cuda.synchronize()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    dst.copy_(src)
+    ev0.record()
+    for _ in range(5):
+        dst.copy_(src)
+    ev1.record()
+    torch.cuda.synchronize()
+    copy_gbs = 5 * 8 * arena / (ev0.elapsed_time(ev1) * 1e-3) / 1e9
+
+    out = {
+        "metric": "pseudo-gradient elements compressed+aggregated/sec",
+        "value": N / (ms_step * 1e-3) / 1e9,
+        "unit": "Gelem/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"config {w.config_id}: {w.name}, {len(descs)} fp32 tensors, "
+                               f"N={N}, chunk 4096 ({'flat runs' if args.flat else '64x64 tiles / 1-D runs'}), "
+                               f"k={w.k}, R={w.R}, beta={w.beta}, lr={w.lr}",
+                   "n_elements": N, "n_chunks": n_chunks, "k": w.k, "R": w.R},
+        "roofline": {"bound": "hbm", "kernel": "k_select (EF accumulate + chunk Top-k)",
+                     "achieved": sel_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": sel_gbs / HBM_PEAK_GBS, "traffic": None,
+                     "ms": sel_ms, "algorithmic_bytes": sel_bytes},
+        "path_hbm": {"algorithmic_bytes_per_step": bytes_round,
+                     "achieved_GBps": bytes_round / (ms_step * 1e-3) / 1e9,
+                     "frac_of_peak": bytes_round / (ms_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                     "device_copy_GBps": copy_gbs},
+        "kernels_ms": {p: prof[p][0] for p in prof},
+        "compress_ms": compress_ms, "apply_ms": apply_ms,
+        "apply_GBps": apply_bytes / (apply_ms * 1e-3) / 1e9 if apply_ms > 0 else 0.0,
+    }
+    if not args.no_cpu_baseline:
+        del deltas, theta, e0
+        out["cpu_baseline"] = cpu_baseline(w, args.cpu_layers)
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -132,6 +132,25 @@ int sl_decompress_avg_apply(sl_plan *plan, float *theta, const void *const *payl
 int sl_pack_indices(const uint16_t *idx, const uint8_t *codes, int64_t n_chunks, int k, void *out,
                     void *stream);
 
+/* Per-kernel timing for benchmarks.  Between sl_profile_begin and
+ * sl_profile_end every sl_compress / sl_decompress_avg_apply call on the plan
+ * records HIP events on its stream around each of its kernels (no
+ * synchronisation; at most `max_calls` calls of each kind are recorded, later
+ * ones run unrecorded).  sl_profile_end waits for the recorded events and
+ * writes, per phase, the mean milliseconds per call into ms[SL_PROF_PHASES] and
+ * the number of calls averaged into calls[SL_PROF_PHASES]; either may be NULL.
+ * A phase's time runs from the end of the previous kernel on the stream to the
+ * end of its own, so it includes the launch gap before it. */
+enum { SL_PROF_SELECT = 0,  /* accumulate + chunk Top-k          (sl_compress)   */
+       SL_PROF_STATS = 1,   /* per-tensor mean / variance                        */
+       SL_PROF_CODES = 2,   /* 2-bit codes + record codes                        */
+       SL_PROF_LUT = 3,     /* per-tensor centroids                              */
+       SL_PROF_RESIDUAL = 4,/* e <- a - LUT[code] at the selected positions      */
+       SL_PROF_APPLY = 5,   /* sl_decompress_avg_apply                           */
+       SL_PROF_PHASES = 6 };
+int sl_profile_begin(sl_plan *plan, int max_calls);
+int sl_profile_end(sl_plan *plan, double *ms, int *calls);
+
 const char *sl_strerror(int status);   /* static string                            */
 const char *sl_last_hip_error(void);   /* text of the last HIP failure, or ""      */
 

@@ -26,7 +26,9 @@ EXPORTS = [
     "sl_plan_create", "sl_plan_destroy", "sl_plan_num_chunks", "sl_plan_num_elements",
     "sl_payload_bytes", "sl_payload_tensor_offset", "sl_workspace_bytes", "sl_compress",
     "sl_decompress_avg_apply", "sl_pack_indices", "sl_strerror", "sl_last_hip_error",
+    "sl_profile_begin", "sl_profile_end",
 ]
+PROF_PHASES = ["select", "stats", "codes", "lut", "residual", "apply"]
 
 
 class SlTensor(C.Structure):
@@ -75,6 +77,10 @@ def lib():
         L.sl_decompress_avg_apply.argtypes = [vp, vp, C.POINTER(vp), i32, C.c_float, vp]
         L.sl_pack_indices.restype = i32
         L.sl_pack_indices.argtypes = [vp, vp, i64, i32, vp, vp]
+        L.sl_profile_begin.restype = i32
+        L.sl_profile_begin.argtypes = [vp, i32]
+        L.sl_profile_end.restype = i32
+        L.sl_profile_end.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(i32)]
         L.sl_strerror.restype = C.c_char_p
         L.sl_strerror.argtypes = [i32]
         L.sl_last_hip_error.restype = C.c_char_p
@@ -185,3 +191,19 @@ def alloc_payload(plan: Plan, device="cuda") -> torch.Tensor:
 
 def alloc_workspace(plan: Plan, device="cuda") -> torch.Tensor:
     return torch.empty(plan.workspace_bytes, dtype=torch.uint8, device=device)
+
+
+def sl_profile_begin(plan: Plan, max_calls: int) -> None:
+    st = lib().sl_profile_begin(plan.handle, int(max_calls))
+    if st:
+        raise SparseLoCoError("sl_profile_begin", st)
+
+
+def sl_profile_end(plan: Plan) -> dict:
+    """-> {phase: (mean ms per call, calls)}"""
+    ms = (C.c_double * len(PROF_PHASES))()
+    calls = (C.c_int * len(PROF_PHASES))()
+    st = lib().sl_profile_end(plan.handle, ms, calls)
+    if st:
+        raise SparseLoCoError("sl_profile_end", st)
+    return {name: (ms[i], calls[i]) for i, name in enumerate(PROF_PHASES)}

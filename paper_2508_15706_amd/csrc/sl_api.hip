@@ -24,6 +24,8 @@ static int hip_fail(hipError_t e)
 
 static size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
+extern "C" int sl_profile_end(sl_plan *p, double *ms, int *calls);
+
 extern "C" {
 
 const char *sl_strerror(int status)
@@ -179,6 +181,10 @@ int sl_plan_destroy(sl_plan *p)
     if (p->d_chunk_tensor) (void)hipFree(p->d_chunk_tensor);
     if (p->d_tensors) (void)hipFree(p->d_tensors);
     std::free(p->h_tensors);
+    if (p->prof) {
+        double ms[SL_PROF_PHASES];
+        (void)sl_profile_end(p, ms, nullptr);
+    }
     delete p;
     return SL_OK;
 }
@@ -220,7 +226,9 @@ int sl_compress(sl_plan *p, float *e, const float *delta, float beta, int flags,
     hipStream_t st = static_cast<hipStream_t>(stream);
     unsigned char *pay = static_cast<unsigned char *>(payload);
     unsigned char *ws = static_cast<unsigned char *>(workspace);
+    sl_prof_mark(p, -1, st);
     if ((rc = slk_select(p, e, delta, beta, frozen, pay, ws, st))) return rc;
+    sl_prof_mark(p, SL_PROF_SELECT, st);
     return slk_quantize(p, e, frozen, pay, ws, st);
 }
 
@@ -233,7 +241,10 @@ int sl_decompress_avg_apply(sl_plan *p, float *theta, const void *const *payload
         if (!payloads[r] || misaligned(payloads[r], 16)) return SL_ERR_INVALID_ARG;
     int rc = check_device(p);
     if (rc) return rc;
-    return slk_apply(p, theta, payloads, R, lr, static_cast<hipStream_t>(stream));
+    sl_prof_mark(p, -2, static_cast<hipStream_t>(stream));
+    rc = slk_apply(p, theta, payloads, R, lr, static_cast<hipStream_t>(stream));
+    sl_prof_mark(p, SL_PROF_APPLY, static_cast<hipStream_t>(stream));
+    return rc;
 }
 
 int sl_pack_indices(const uint16_t *idx, const uint8_t *codes, int64_t n_chunks, int k, void *out,
@@ -246,3 +257,135 @@ int sl_pack_indices(const uint16_t *idx, const uint8_t *codes, int64_t n_chunks,
 }
 
 }  // extern "C"
+
+// ---------------------------------------------------------------------------
+// Optional per-kernel timing.  A compress call records 6 events (start + one
+// after each of its 5 kernels), an apply call 2.
+struct SlProfile {
+    int max_calls;
+    int n_compress, n_apply;
+    bool in_compress;
+    std::vector<hipEvent_t> ev_compress;   // [max_calls][6]
+    std::vector<hipEvent_t> ev_apply;      // [max_calls][2]
+    std::vector<unsigned char> have;       // [max_calls][6] which compress events were recorded
+    int cur;                               // slot of the call being recorded, or -1
+};
+
+void sl_prof_mark(const sl_plan *p, int phase, hipStream_t st)
+{
+    SlProfile *P = p->prof;
+    if (!P) return;
+    if (phase < 0) {               // start of a call: phase -1 = compress, -2 = apply
+        P->in_compress = phase == -1;
+        int &n = P->in_compress ? P->n_compress : P->n_apply;
+        if (n >= P->max_calls) {
+            P->cur = -1;
+            return;
+        }
+        P->cur = n++;
+        if (P->in_compress) {
+            for (int i = 0; i < 6; ++i) P->have[(size_t)P->cur * 6 + i] = 0;
+            P->have[(size_t)P->cur * 6] = 1;
+            (void)hipEventRecord(P->ev_compress[(size_t)P->cur * 6], st);
+        } else {
+            (void)hipEventRecord(P->ev_apply[(size_t)P->cur * 2], st);
+        }
+        return;
+    }
+    if (P->cur < 0) return;
+    if (phase == SL_PROF_APPLY) {
+        (void)hipEventRecord(P->ev_apply[(size_t)P->cur * 2 + 1], st);
+    } else {
+        P->have[(size_t)P->cur * 6 + 1 + phase] = 1;
+        (void)hipEventRecord(P->ev_compress[(size_t)P->cur * 6 + 1 + phase], st);
+    }
+}
+
+static void prof_free(SlProfile *P)
+{
+    if (!P) return;
+    for (hipEvent_t e : P->ev_compress) (void)hipEventDestroy(e);
+    for (hipEvent_t e : P->ev_apply) (void)hipEventDestroy(e);
+    delete P;
+}
+
+extern "C" int sl_profile_begin(sl_plan *p, int max_calls)
+{
+    if (!p || max_calls < 1 || max_calls > 4096) return SL_ERR_INVALID_ARG;
+    if (p->prof) {
+        prof_free(p->prof);
+        p->prof = nullptr;
+    }
+    SlProfile *P = new (std::nothrow) SlProfile();
+    if (!P) return SL_ERR_NOMEM;
+    P->max_calls = max_calls;
+    P->n_compress = P->n_apply = 0;
+    P->cur = -1;
+    P->in_compress = false;
+    P->have.assign((size_t)max_calls * 6, 0);
+    for (int i = 0; i < max_calls * 6; ++i) {
+        hipEvent_t e;
+        hipError_t err = hipEventCreate(&e);
+        if (err != hipSuccess) {
+            prof_free(P);
+            return hip_fail(err);
+        }
+        P->ev_compress.push_back(e);
+    }
+    for (int i = 0; i < max_calls * 2; ++i) {
+        hipEvent_t e;
+        hipError_t err = hipEventCreate(&e);
+        if (err != hipSuccess) {
+            prof_free(P);
+            return hip_fail(err);
+        }
+        P->ev_apply.push_back(e);
+    }
+    p->prof = P;
+    return SL_OK;
+}
+
+extern "C" int sl_profile_end(sl_plan *p, double *ms, int *calls)
+{
+    if (!p || !p->prof) return SL_ERR_INVALID_ARG;
+    SlProfile *P = p->prof;
+    double sum[SL_PROF_PHASES] = {0, 0, 0, 0, 0, 0};
+    int cnt[SL_PROF_PHASES] = {0, 0, 0, 0, 0, 0};
+    int rc = SL_OK;
+    for (int c = 0; c < P->n_compress && rc == SL_OK; ++c) {
+        int prev = 0;
+        for (int ph = 0; ph < 5; ++ph) {
+            if (!P->have[(size_t)c * 6 + 1 + ph]) continue;
+            hipEvent_t a = P->ev_compress[(size_t)c * 6 + prev], b = P->ev_compress[(size_t)c * 6 + 1 + ph];
+            hipError_t err = hipEventSynchronize(b);
+            float t = 0.f;
+            if (err == hipSuccess) err = hipEventElapsedTime(&t, a, b);
+            if (err != hipSuccess) {
+                rc = hip_fail(err);
+                break;
+            }
+            sum[ph] += t;
+            cnt[ph]++;
+            prev = 1 + ph;
+        }
+    }
+    for (int c = 0; c < P->n_apply && rc == SL_OK; ++c) {
+        hipError_t err = hipEventSynchronize(P->ev_apply[(size_t)c * 2 + 1]);
+        float t = 0.f;
+        if (err == hipSuccess)
+            err = hipEventElapsedTime(&t, P->ev_apply[(size_t)c * 2], P->ev_apply[(size_t)c * 2 + 1]);
+        if (err != hipSuccess) {
+            rc = hip_fail(err);
+            break;
+        }
+        sum[SL_PROF_APPLY] += t;
+        cnt[SL_PROF_APPLY]++;
+    }
+    for (int ph = 0; ph < SL_PROF_PHASES; ++ph) {
+        if (ms) ms[ph] = cnt[ph] ? sum[ph] / cnt[ph] : 0.0;
+        if (calls) calls[ph] = cnt[ph];
+    }
+    prof_free(P);
+    p->prof = nullptr;
+    return rc;
+}

@@ -49,7 +49,12 @@ struct sl_plan {
     SlTensorDev *d_tensors;
     // host copies
     SlTensorDev *h_tensors;
+    // optional per-kernel timing (sl_profile_begin / sl_profile_end)
+    struct SlProfile *prof;
 };
+
+// Records an event after the kernel of `phase` (phase < 0: start of a call).
+void sl_prof_mark(const sl_plan *p, int phase, hipStream_t st);
 
 // launchers (defined next to their kernels)
 int slk_select(const sl_plan *p, float *e, const float *delta, float beta, int frozen,

@@ -281,6 +281,7 @@ int slk_quantize(const sl_plan *p, float *e, int frozen, unsigned char *payload,
     hipLaunchKernelGGL(k_tensor_stats, dim3(p->n_tensors), dim3(RED_THREADS), 0, st, p->d_tensors,
                        leafA, (long long)p->n_chunks, k, tstat);
     if ((rc = check_launch())) return rc;
+    sl_prof_mark(p, SL_PROF_STATS, st);
 
     CodeArgs C;
     C.chunk_tensor = p->d_chunk_tensor;
@@ -295,10 +296,12 @@ int slk_quantize(const sl_plan *p, float *e, int frozen, unsigned char *payload,
     const size_t lds = (size_t)((k + 7) & ~7) + 64 * sizeof(double);
     hipLaunchKernelGGL(k_codes, dim3((unsigned)p->n_chunks), dim3(64), lds, st, C);
     if ((rc = check_launch())) return rc;
+    sl_prof_mark(p, SL_PROF_CODES, st);
 
     hipLaunchKernelGGL(k_tensor_lut, dim3(p->n_tensors), dim3(RED_THREADS), 0, st, p->d_tensors,
                        leafC, cnt, (long long)p->n_chunks, k, tstat, payload);
     if ((rc = check_launch())) return rc;
+    sl_prof_mark(p, SL_PROF_LUT, st);
 
     if (!frozen) {
         ResidualArgs R;
@@ -312,6 +315,7 @@ int slk_quantize(const sl_plan *p, float *e, int frozen, unsigned char *payload,
         R.k = k;
         hipLaunchKernelGGL(k_residual, dim3((unsigned)p->n_chunks), dim3(64), 0, st, R);
         if ((rc = check_launch())) return rc;
+        sl_prof_mark(p, SL_PROF_RESIDUAL, st);
     }
     return SL_OK;
 }
