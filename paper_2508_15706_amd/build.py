@@ -31,7 +31,14 @@ def build_library(verbose: bool = False, extra=()) -> str:
            *[os.path.join(CSRC, s) for s in SOURCES], "-o", LIB]
     if verbose:
         print(" ".join(cmd), flush=True)
-    subprocess.check_call(cmd)
+    r = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    # hipcc's host pass does not know the (device-only) packed-fp32 feature switch: harmless
+    noise = "'-packed-fp32-ops' is not a recognized feature for this target"
+    out = "\n".join(l for l in r.stdout.splitlines() if noise not in l)
+    if out.strip():
+        print(out, flush=True)
+    if r.returncode != 0:
+        raise RuntimeError(f"hipcc failed with exit code {r.returncode}")
     return LIB
 
 

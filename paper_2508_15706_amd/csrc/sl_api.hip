@@ -148,6 +148,13 @@ int sl_plan_create(const sl_tensor *tensors, int n_tensors, int k, sl_plan **out
         delete p;
         return hip_fail(err);
     }
+    p->max_lds = 65536;
+    {
+        int v = 0;
+        if (hipDeviceGetAttribute(&v, hipDeviceAttributeMaxSharedMemoryPerBlock, p->device) == hipSuccess &&
+            v >= 32768)
+            p->max_lds = v;
+    }
     p->h_tensors = (SlTensorDev *)std::malloc(sizeof(SlTensorDev) * (size_t)std::max(1, n_tensors));
     if (!p->h_tensors) {
         delete p;

@@ -22,16 +22,22 @@ struct ApplyArgs {
     float neg_lr, inv_R;
     int R, k;
     int batch;               // records staged per round
+    int lds_per_wave;
+    long long n_chunks;
     const unsigned char *payload[SL_MAX_WORKERS];
 };
 
-__global__ void __launch_bounds__(64) k_apply(ApplyArgs A)
+// One wave per chunk, several independent waves (adjacent chunks) per workgroup.
+__global__ void __launch_bounds__(256) k_apply(ApplyArgs A)
 {
-    extern __shared__ __align__(16) unsigned char smem[];
+    extern __shared__ __align__(16) unsigned char smem_all[];
+    const int lane = threadIdx.x & 63, k = A.k;
+    const int wave = sl_uniform((int)(threadIdx.x >> 6));
+    const long long c = (long long)blockIdx.x * (blockDim.x >> 6) + wave;
+    if (c >= A.n_chunks) return;
+    unsigned char *smem = smem_all + (size_t)wave * A.lds_per_wave;
     float *acc = reinterpret_cast<float *>(smem);                    // 4096 floats
     unsigned char *stage = smem + SL_CHUNK * sizeof(float);
-    const int lane = threadIdx.x, k = A.k;
-    const long long c = blockIdx.x;
     const SlChunkDesc d = A.desc[c];
     const int t = A.chunk_tensor[c];
     const SlTensorDev td = A.tensors[t];
@@ -45,12 +51,11 @@ __global__ void __launch_bounds__(64) k_apply(ApplyArgs A)
     const bool full = d.flags & SLC_FULL;
 
     // theta loads are issued first so that their latency overlaps the decode
-    float4 th[16];
+    sl_f4 th[16];
     if (full) {
         const unsigned o0 = lr * stride + lc;
 #pragma unroll
-        for (int i = 0; i < 16; ++i)
-            th[i] = *reinterpret_cast<const float4 *>(tc + (o0 + 4u * i * stride));
+        for (int i = 0; i < 16; ++i) th[i] = sl_load_stream(tc + (o0 + 4u * i * stride));
     }
 
 #pragma unroll
@@ -59,7 +64,7 @@ __global__ void __launch_bounds__(64) k_apply(ApplyArgs A)
 
     for (int r0 = 0; r0 < A.R; r0 += A.batch) {
         const int nb = min(A.batch, A.R - r0);
-        __syncthreads();
+        sl_wave_sync();
         for (int w = lane; w < nb * 4; w += 64) {                    // the tensor's LUT of each worker
             const int r = w >> 2, q = w & 3;
             reinterpret_cast<unsigned *>(stage)[r * (rec_pad >> 2) + q] =
@@ -78,7 +83,7 @@ __global__ void __launch_bounds__(64) k_apply(ApplyArgs A)
                 stage[r * rec_pad + 16 + q] = A.payload[r0 + r][rec_off + q];
             }
         }
-        __syncthreads();
+        sl_wave_sync();
         for (int r = 0; r < nb; ++r) {
             const float4 lut = *reinterpret_cast<const float4 *>(stage + r * rec_pad);
             const unsigned char *rec = stage + r * rec_pad + 16;
@@ -91,7 +96,7 @@ __global__ void __launch_bounds__(64) k_apply(ApplyArgs A)
                 const float q = code == 0 ? lut.x : code == 1 ? lut.y : code == 2 ? lut.z : lut.w;
                 acc[j] = acc[j] + q;
             }
-            __syncthreads();          // worker r is complete before worker r+1 is added
+            sl_wave_sync();           // worker r is complete before worker r+1 is added
         }
     }
 
@@ -100,12 +105,12 @@ __global__ void __launch_bounds__(64) k_apply(ApplyArgs A)
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
             const float4 a = reinterpret_cast<const float4 *>(acc)[i * 64 + lane];
-            float4 v = th[i];
+            sl_f4 v = th[i];
             v.x = fmaf(A.neg_lr, a.x * A.inv_R, v.x);
             v.y = fmaf(A.neg_lr, a.y * A.inv_R, v.y);
             v.z = fmaf(A.neg_lr, a.z * A.inv_R, v.z);
             v.w = fmaf(A.neg_lr, a.w * A.inv_R, v.w);
-            *reinterpret_cast<float4 *>(tc + (o0 + 4u * i * stride)) = v;
+            sl_store_stream(tc + (o0 + 4u * i * stride), v);
         }
     } else {
         const int rows = d.rows, cols = d.cols, last_cols = d.last_cols;
@@ -171,8 +176,20 @@ int slk_apply(const sl_plan *p, float *theta, const void *const *payloads, int R
     A.batch = batch;
     for (int r = 0; r < SL_MAX_WORKERS; ++r)
         A.payload[r] = r < R ? static_cast<const unsigned char *>(payloads[r]) : nullptr;
-    const size_t lds = SL_CHUNK * sizeof(float) + (size_t)batch * rec_pad;
-    hipLaunchKernelGGL(k_apply, dim3((unsigned)p->n_chunks), dim3(64), lds, st, A);
+    A.n_chunks = p->n_chunks;
+    A.lds_per_wave = (int)((SL_CHUNK * sizeof(float) + (size_t)batch * rec_pad + 15) & ~(size_t)15);
+    int wpb = 4;
+    while (wpb > 1 && (size_t)A.lds_per_wave * wpb > (size_t)p->max_lds) wpb >>= 1;
+    const size_t lds = (size_t)A.lds_per_wave * wpb;
+    if (lds > 65536) {
+        hipError_t aerr = hipFuncSetAttribute(reinterpret_cast<const void *>(k_apply),
+                                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (aerr != hipSuccess) {
+            sl_note_hip_error(aerr);
+            return SL_ERR_HIP;
+        }
+    }
+    hipLaunchKernelGGL(k_apply, dim3((unsigned)((p->n_chunks + wpb - 1) / wpb)), dim3(64 * wpb), lds, st, A);
     hipError_t err = hipGetLastError();
     if (err != hipSuccess) {
         sl_note_hip_error(err);

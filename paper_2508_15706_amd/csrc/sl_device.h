@@ -14,6 +14,29 @@ SL_DEV int sl_mbcnt(unsigned long long m)
     return __builtin_amdgcn_mbcnt_hi((unsigned)(m >> 32), __builtin_amdgcn_mbcnt_lo((unsigned)m, 0u));
 }
 
+// Orders this wavefront's LDS accesses: the hardware executes one wave's LDS
+// instructions in order, so only the compiler has to be kept from moving
+// memory operations across this point.  (Waves of a block never share LDS
+// data in these kernels, so no s_barrier is needed.)
+SL_DEV void sl_wave_sync()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+typedef float sl_f4 __attribute__((ext_vector_type(4)));
+
+// Streaming (non-temporal) 16-byte accesses for data that is touched once.
+SL_DEV sl_f4 sl_load_stream(const float *p)
+{
+    return __builtin_nontemporal_load(reinterpret_cast<const sl_f4 *>(p));
+}
+SL_DEV void sl_store_stream(float *p, sl_f4 v)
+{
+    __builtin_nontemporal_store(v, reinterpret_cast<sl_f4 *>(p));
+}
+
 SL_DEV int sl_popc(unsigned long long m) { return __builtin_popcountll(m); }
 
 SL_DEV int sl_uniform(int v) { return __builtin_amdgcn_readfirstlane(v); }
@@ -71,17 +94,17 @@ SL_DEV double sl_chunk_tree(int k, int lane, double *scratch, F y)
     }
     const int slots = P / 64;           // power of two, <= 64
     const int used = (k + 63) / 64;
-    __syncthreads();
+    sl_wave_sync();
     if (lane >= used && lane < slots) scratch[lane] = 0.0;
     for (int s = 0; s < used; ++s) {
         double t = sl_wave_tree(y(s), 6);
         if (lane == 0) scratch[s] = t;
     }
-    __syncthreads();
+    sl_wave_sync();
     double v = lane < slots ? scratch[lane] : 0.0;
     int levels = 0;
     while ((1 << levels) < slots) ++levels;
     double r = sl_lane0(sl_wave_tree(v, levels));
-    __syncthreads();
+    sl_wave_sync();
     return r;
 }

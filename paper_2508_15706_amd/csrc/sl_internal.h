@@ -36,6 +36,7 @@ struct sl_plan {
     int k;
     int n_tensors;
     int device;
+    int max_lds;                // largest LDS allocation of one workgroup, bytes
     int64_t n_chunks;
     int64_t n_elements;
     int64_t n_partial;          // chunks without SLC_FULL

@@ -120,13 +120,18 @@ struct CodeArgs {
     unsigned char *payload;
     long long n_chunks;
     int k;
+    int lds_per_wave;
 };
 
-__global__ void __launch_bounds__(64) k_codes(CodeArgs A)
+// One wave per chunk, several independent waves per workgroup.
+__global__ void __launch_bounds__(256) k_codes(CodeArgs A)
 {
-    extern __shared__ __align__(16) unsigned char smem[];
-    const int lane = threadIdx.x, k = A.k;
-    const long long c = blockIdx.x;
+    extern __shared__ __align__(16) unsigned char smem_all[];
+    const int lane = threadIdx.x & 63, k = A.k;
+    const int wave = sl_uniform((int)(threadIdx.x >> 6));
+    const long long c = (long long)blockIdx.x * (blockDim.x >> 6) + wave;
+    if (c >= A.n_chunks) return;
+    unsigned char *smem = smem_all + (size_t)wave * A.lds_per_wave;
     const int t = A.chunk_tensor[c];
     const SlTensorDev td = A.tensors[t];
     const double mu = A.tstat[t].mu, T = A.tstat[t].T;
@@ -147,7 +152,7 @@ __global__ void __launch_bounds__(64) k_codes(CodeArgs A)
 #pragma unroll
         for (int b = 0; b < 4; ++b) n_b[b] += sl_popc(sl_ballot(code == b));
     }
-    __syncthreads();
+    sl_wave_sync();
 
     // codes, four per byte, entry m in bits 2*(m mod 4)
     const long long rec_bytes = (long long)7 * k / 4;
@@ -228,13 +233,16 @@ struct ResidualArgs {
     const float *vals;
     const unsigned char *payload;
     float *e;
+    long long n_chunks;
     int k;
 };
 
-__global__ void __launch_bounds__(64) k_residual(ResidualArgs A)
+__global__ void __launch_bounds__(256) k_residual(ResidualArgs A)
 {
-    const int lane = threadIdx.x, k = A.k;
-    const long long c = blockIdx.x;
+    const int lane = threadIdx.x & 63, k = A.k;
+    const int wave = sl_uniform((int)(threadIdx.x >> 6));
+    const long long c = (long long)blockIdx.x * (blockDim.x >> 6) + wave;
+    if (c >= A.n_chunks) return;
     const SlChunkDesc d = A.desc[c];
     const int t = A.chunk_tensor[c];
     const SlTensorDev td = A.tensors[t];
@@ -293,8 +301,10 @@ int slk_quantize(const sl_plan *p, float *e, int frozen, unsigned char *payload,
     C.payload = payload;
     C.n_chunks = p->n_chunks;
     C.k = k;
-    const size_t lds = (size_t)((k + 7) & ~7) + 64 * sizeof(double);
-    hipLaunchKernelGGL(k_codes, dim3((unsigned)p->n_chunks), dim3(64), lds, st, C);
+    C.lds_per_wave = ((k + 15) & ~15) + 64 * (int)sizeof(double);
+    const int wpb = 4;
+    const unsigned nblk = (unsigned)((p->n_chunks + wpb - 1) / wpb);
+    hipLaunchKernelGGL(k_codes, dim3(nblk), dim3(64 * wpb), (size_t)C.lds_per_wave * wpb, st, C);
     if ((rc = check_launch())) return rc;
     sl_prof_mark(p, SL_PROF_CODES, st);
 
@@ -313,7 +323,8 @@ int slk_quantize(const sl_plan *p, float *e, int frozen, unsigned char *payload,
         R.payload = payload;
         R.e = e;
         R.k = k;
-        hipLaunchKernelGGL(k_residual, dim3((unsigned)p->n_chunks), dim3(64), 0, st, R);
+        R.n_chunks = p->n_chunks;
+        hipLaunchKernelGGL(k_residual, dim3(nblk), dim3(64 * wpb), 0, st, R);
         if ((rc = check_launch())) return rc;
         sl_prof_mark(p, SL_PROF_RESIDUAL, st);
     }

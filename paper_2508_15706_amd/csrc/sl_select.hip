@@ -3,31 +3,37 @@
 // paragraph for the chunking).
 //
 // One 64-lane wavefront owns one 4096-element chunk, 64 elements per lane in
-// registers.  HBM traffic per chunk: 16 KB of e and 16 KB of delta read once,
-// 16 KB of e written once, plus 3k/2 bytes of packed indices, 4k bytes of
-// selected values and 16 bytes of partial sums.
+// registers; a workgroup is several independent waves on adjacent chunks (so
+// that a workgroup streams 1 KB of every matrix row it touches).  HBM traffic
+// per chunk: 16 KB of e and 16 KB of delta read once, 16 KB of e written once
+// (all as streaming 16-byte accesses), plus 3k/2 bytes of packed indices,
+// 4k bytes of selected values and 16 bytes of partial sums.
 //
 // Register r = 4*i + cc of lane l holds local index j = 256*i + 4*l + cc, i.e.
 // the lane's i-th 16-byte load.  With rows of 64 elements this is row
 // 4*i + l/16, columns 4*(l%16) .. +3 for both chunk layouts.
 //
-// Selection = exact k-th largest magnitude key T by bitwise bisection with
-// wave ballots as the counting primitive, made cheap by pruning first:
-//   1. every lane keeps the maxima of GPL groups of its registers; the k-th
-//      largest of those 64*GPL maxima is a lower bound L of T (there are k
-//      distinct elements >= L);
-//   2. keys >= L (typically ~1.4k of them) are compacted into LDS and T is
-//      bisected over that short list only;
-//   3. one ordered compaction over the registers emits the selected entries in
-//      ascending local index; ties at T go to the lowest indices.
-// If the candidate list overflows (massive ties) or k is large, T is bisected
-// over the registers directly - slower, same result.
+// Selection = exact k-th largest magnitude key T (key = bit pattern of |a|)
+// by bitwise bisection with wave ballots as the counting primitive, made cheap
+// by pruning first:
+//   1. every lane keeps the maxima of GPL interleaved groups of its registers;
+//      the k-th largest of those 64*GPL maxima is a lower bound L of T (there
+//      are k distinct elements >= L);
+//   2. one ordered compaction over the registers moves the entries with key
+//      >= L (about 1.4k of them when 64*GPL = 2k) into LDS in ascending local
+//      index;
+//   3. T is bisected over that short list, and a second compaction over the
+//      list emits the selected entries, still in ascending local index; ties
+//      at T go to the lowest indices.
+// Partial chunks, a candidate list that overflows (massive ties) and k > 256
+// take the general route: T bisected over the registers directly and one
+// ordered compaction over the registers - slower, same result.
 #include "sl_device.h"
 #include "sl_internal.h"
 
 namespace {
 
-constexpr int CAND_CAP = 512;       // LDS candidate list, entries
+constexpr int CAND_CAP = 512;             // LDS candidate list, entries of 8 bytes
 constexpr int CAND_SLOTS = CAND_CAP / 64;
 
 struct SelectArgs {
@@ -39,6 +45,7 @@ struct SelectArgs {
     float beta;
     int frozen;
     int k;
+    int lds_per_wave;
     float *vals;            // [n_chunks * k] selected values, canonical order
     double *leafA;          // [2][n_chunks] per-chunk tree sums of x and x*x
     unsigned char *payload;
@@ -62,173 +69,27 @@ SL_DEV int bisect_kth(int lo, int hi, int k, CountGE count_ge)
     return T;
 }
 
-template <int GPL>
-SL_DEV void select_chunk(const SelectArgs &A, unsigned char *smem)
+// General route.  key[r] is the magnitude key of register r, or -1 for a
+// position outside the tensor; sg0/sg1 hold the sign of register r at bit
+// 31 - (r & 31) of sg[r / 32].  Writes the k selected (value, index) pairs in
+// ascending local index to sel_val / sel_idx.
+SL_DEV void select_general(int (&key)[64], unsigned sg0, unsigned sg1, int k, int lane,
+                           float *sel_val, unsigned short *sel_idx)
 {
-    const int lane = threadIdx.x;
-    const long long c = blockIdx.x;
-    const SlChunkDesc d = A.desc[c];
-    const int k = A.k;
-
-    int key[64];
-    unsigned sg0 = 0, sg1 = 0;   // sign of register r at bit 31 - (r & 31) of sg[r / 32]
-
-    // ---------------------------------------------------------------- a = beta*e + delta
-    {
-        float *ec = A.e + d.base;
-        const float *dc = A.delta + d.base;
-        const int lr = lane >> 4, lc = (lane & 15) * 4;
-        const unsigned stride = (unsigned)d.stride;
-        if (d.flags & SLC_FULL) {
-            float4 ev[16], dv[16];
-            const unsigned o0 = lr * stride + lc;
-            if (!A.frozen) {
-#pragma unroll
-                for (int i = 0; i < 16; ++i)
-                    ev[i] = *reinterpret_cast<const float4 *>(ec + (o0 + 4u * i * stride));
-            }
-#pragma unroll
-            for (int i = 0; i < 16; ++i)
-                dv[i] = *reinterpret_cast<const float4 *>(dc + (o0 + 4u * i * stride));
-#pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                float4 a;
-                if (!A.frozen) {
-                    a.x = fmaf(A.beta, ev[i].x, dv[i].x);
-                    a.y = fmaf(A.beta, ev[i].y, dv[i].y);
-                    a.z = fmaf(A.beta, ev[i].z, dv[i].z);
-                    a.w = fmaf(A.beta, ev[i].w, dv[i].w);
-                    *reinterpret_cast<float4 *>(ec + (o0 + 4u * i * stride)) = a;
-                } else {
-                    a = dv[i];
-                }
-                const float av[4] = {a.x, a.y, a.z, a.w};
-#pragma unroll
-                for (int cc = 0; cc < 4; ++cc) {
-                    const int r = 4 * i + cc;
-                    const unsigned u = __float_as_uint(av[cc]);
-                    key[r] = (int)(u & 0x7FFFFFFFu);
-                    if (r < 32) sg0 = (sg0 << 1) | (u >> 31);
-                    else sg1 = (sg1 << 1) | (u >> 31);
-                }
-            }
-        } else {
-            const int rows = d.rows, cols = d.cols, last_cols = d.last_cols;
-#pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                const int row = 4 * i + lr;
-                const int lim = row < rows - 1 ? cols : (row == rows - 1 ? last_cols : 0);
-#pragma unroll
-                for (int cc = 0; cc < 4; ++cc) {
-                    const int r = 4 * i + cc;
-                    const int col = lc + cc;
-                    unsigned u = 0;
-                    int kk = -1;
-                    if (col < lim) {
-                        const unsigned o = row * stride + col;
-                        float a;
-                        if (!A.frozen) {
-                            a = fmaf(A.beta, ec[o], dc[o]);
-                            ec[o] = a;
-                        } else {
-                            a = dc[o];
-                        }
-                        u = __float_as_uint(a);
-                        kk = (int)(u & 0x7FFFFFFFu);
-                    }
-                    key[r] = kk;
-                    if (r < 32) sg0 = (sg0 << 1) | (u >> 31);
-                    else sg1 = (sg1 << 1) | (u >> 31);
-                }
-            }
-        }
-    }
-
     auto count_regs = [&](int x) {
         int n = 0;
 #pragma unroll
         for (int r = 0; r < 64; ++r) n += sl_popc(sl_ballot(key[r] >= x));
         return n;
     };
-
-    // ---------------------------------------------------------------- threshold T
-    int T, n_ge;
-    int *cand = reinterpret_cast<int *>(smem);
-    if constexpr (GPL > 0) {
-        constexpr int G = GPL;
-        // group g of a lane = its registers r with r % G == g (interleaved, so
-        // that partial chunks spread their valid positions over all groups)
-        int gm[G];
+    int lmax = key[0];
 #pragma unroll
-        for (int g = 0; g < G; ++g) {
-            int m = key[g];
-#pragma unroll
-            for (int r = g + G; r < 64; r += G) m = max(m, key[r]);
-            gm[g] = m;
-        }
-        int lmin = gm[0], lmax = gm[0];
-#pragma unroll
-        for (int g = 1; g < G; ++g) lmin = min(lmin, gm[g]), lmax = max(lmax, gm[g]);
-        const int hi = sl_wave_max(lmax);               // largest key of the chunk (>= 0)
-        const int lo = max(sl_wave_min(lmin), 0);
-        // L = k-th largest group maximum: a lower bound of T, because k distinct
-        // elements are >= L.  With fewer than k non-empty groups there is no
-        // such bound and L = 0 keeps every valid key.
-        auto count_gm = [&](int x) {
-            int n = 0;
-#pragma unroll
-            for (int g = 0; g < G; ++g) n += sl_popc(sl_ballot(gm[g] >= x));
-            return n;
-        };
-        const int L = count_gm(lo) >= k ? bisect_kth(lo, hi, k, count_gm) : 0;
-        // compact the keys >= L into LDS (order irrelevant here)
-        int ncand = 0;
-#pragma unroll
-        for (int r = 0; r < 64; ++r) {
-            const bool f = key[r] >= L;
-            const unsigned long long m = sl_ballot(f);
-            const int pos = ncand + sl_mbcnt(m);
-            if (f && pos < CAND_CAP) cand[pos] = key[r];
-            ncand += sl_popc(m);
-        }
-        __syncthreads();
-        if (ncand <= CAND_CAP) {
-            int cr[CAND_SLOTS];
-            const int nslots = (ncand + 63) >> 6;
-#pragma unroll
-            for (int s = 0; s < CAND_SLOTS; ++s) {
-                const int p = s * 64 + lane;
-                cr[s] = (s < nslots && p < ncand) ? cand[p] : -1;
-            }
-            auto count_cand = [&](int x) {
-                int n = 0;
-#pragma unroll
-                for (int s = 0; s < CAND_SLOTS; ++s)
-                    if (s < nslots) n += sl_popc(sl_ballot(cr[s] >= x));
-                return n;
-            };
-            T = bisect_kth(L, hi, k, count_cand);
-            n_ge = count_cand(T);
-        } else {
-            T = bisect_kth(L, hi, k, count_regs);
-            n_ge = count_regs(T);
-        }
-        __syncthreads();
-    } else {
-        int lmax = key[0];
-#pragma unroll
-        for (int r = 1; r < 64; ++r) lmax = max(lmax, key[r]);
-        const int hi = sl_wave_max(lmax);
-        T = bisect_kth(0, hi, k, count_regs);
-        n_ge = count_regs(T);
-    }
-
-    // ---------------------------------------------------------------- ordered compaction
-    float *sel_val = reinterpret_cast<float *>(smem);
-    unsigned short *sel_idx = reinterpret_cast<unsigned short *>(smem + 4 * (size_t)k);
+    for (int r = 1; r < 64; ++r) lmax = max(lmax, key[r]);
+    const int hi = sl_wave_max(lmax);
+    const int T = bisect_kth(0, hi, k, count_regs);
+    const int n_ge = count_regs(T);
     const bool ties = n_ge != k;            // more keys equal to T than slots left
-    // need = k - #(key > T): number of tie entries to take, lowest indices first
-    int need = 0;
+    int need = 0;                           // tie entries to take, lowest indices first
     if (ties) {
         int n_gt = 0;
 #pragma unroll
@@ -284,7 +145,215 @@ SL_DEV void select_chunk(const SelectArgs &A, unsigned char *smem)
         }
         base += cnt;
     }
-    __syncthreads();
+}
+
+// 3 waves per SIMD (<= 168 VGPRs): measured faster than 2 (no spills) or 4 (heavy spills).
+#ifndef SL_SELECT_WAVES_PER_EU
+#define SL_SELECT_WAVES_PER_EU 3
+#endif
+#define SL_SELECT_BOUNDS __launch_bounds__(256, SL_SELECT_WAVES_PER_EU)
+
+template <int GPL>
+__global__ void SL_SELECT_BOUNDS k_select(SelectArgs A)
+{
+    extern __shared__ __align__(16) unsigned char smem_all[];
+    const int lane = threadIdx.x & 63;
+    const int wave = sl_uniform((int)(threadIdx.x >> 6));
+    const long long c = (long long)blockIdx.x * (blockDim.x >> 6) + wave;
+    if (c >= A.n_chunks) return;
+    unsigned char *smem = smem_all + (size_t)wave * A.lds_per_wave;
+    const SlChunkDesc d = A.desc[c];
+    const int k = A.k;
+
+    // LDS of this wave: [candidates 8*CAND_CAP][sel_val 4k][sel_idx 2k][tree scratch 512]
+    uint2 *cand = reinterpret_cast<uint2 *>(smem);
+    const size_t cand_bytes = GPL > 0 ? sizeof(uint2) * CAND_CAP : 0;
+    float *sel_val = reinterpret_cast<float *>(smem + cand_bytes);
+    unsigned short *sel_idx = reinterpret_cast<unsigned short *>(smem + cand_bytes + 4 * (size_t)k);
+    double *scratch = reinterpret_cast<double *>(smem + cand_bytes + ((6 * (size_t)k + 7) & ~(size_t)7));
+
+    float *ec = A.e + d.base;
+    const float *dc = A.delta + d.base;
+    const int lr = lane >> 4, lc = (lane & 15) * 4;
+    const unsigned stride = (unsigned)d.stride;
+    const bool full = d.flags & SLC_FULL;
+
+    float a[64];
+    unsigned long long inside = ~0ull;      // bit r: register r is a position of the tensor
+    bool done = false;
+
+    if (full) {
+        // ------------------------------------------------------------ a = beta*e + delta
+        const unsigned o0 = lr * stride + lc;
+        sl_f4 ev[16], dv[16];
+        if (!A.frozen) {
+#pragma unroll
+            for (int i = 0; i < 16; ++i) ev[i] = sl_load_stream(ec + (o0 + 4u * i * stride));
+        }
+#pragma unroll
+        for (int i = 0; i < 16; ++i) dv[i] = sl_load_stream(dc + (o0 + 4u * i * stride));
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            sl_f4 v;
+            if (!A.frozen) {
+                v.x = fmaf(A.beta, ev[i].x, dv[i].x);
+                v.y = fmaf(A.beta, ev[i].y, dv[i].y);
+                v.z = fmaf(A.beta, ev[i].z, dv[i].z);
+                v.w = fmaf(A.beta, ev[i].w, dv[i].w);
+                sl_store_stream(ec + (o0 + 4u * i * stride), v);
+            } else {
+                v = dv[i];
+            }
+            a[4 * i + 0] = v.x, a[4 * i + 1] = v.y, a[4 * i + 2] = v.z, a[4 * i + 3] = v.w;
+        }
+
+        if constexpr (GPL > 0) {
+            constexpr int G = GPL;
+            // group g of a lane = its registers r with r % G == g
+            int gm[G];
+#pragma unroll
+            for (int g = 0; g < G; ++g) {
+                int m = key_of(a[g]);
+#pragma unroll
+                for (int r = g + G; r < 64; r += G) m = max(m, key_of(a[r]));
+                gm[g] = m;
+            }
+            int lmin = gm[0], lmax = gm[0];
+#pragma unroll
+            for (int g = 1; g < G; ++g) lmin = min(lmin, gm[g]), lmax = max(lmax, gm[g]);
+            const int hi = sl_wave_max(lmax);               // largest key of the chunk
+            const int lo = sl_wave_min(lmin);
+            // L = k-th largest group maximum: a lower bound of T, because k
+            // distinct elements are >= L (64*G >= k groups, all non-empty here)
+            const int L = bisect_kth(lo, hi, k, [&](int x) {
+                int n = 0;
+#pragma unroll
+                for (int g = 0; g < G; ++g) n += sl_popc(sl_ballot(gm[g] >= x));
+                return n;
+            });
+            // ordered compaction of the entries with key >= L
+            int ncand = 0;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                bool f[4];
+                int pos = ncand, cnt = 0;
+                unsigned long long any = 0;
+#pragma unroll
+                for (int cc = 0; cc < 4; ++cc) {
+                    f[cc] = key_of(a[4 * i + cc]) >= L;
+                    const unsigned long long m = sl_ballot(f[cc]);
+                    pos += sl_mbcnt(m);
+                    cnt += sl_popc(m);
+                    any |= m;
+                }
+                if (any) {
+#pragma unroll
+                    for (int cc = 0; cc < 4; ++cc) {
+                        if (f[cc]) {
+                            if (pos < CAND_CAP)
+                                cand[pos] = make_uint2(__float_as_uint(a[4 * i + cc]),
+                                                       (unsigned)(256 * i + 4 * lane + cc));
+                            ++pos;
+                        }
+                    }
+                }
+                ncand += cnt;
+            }
+            sl_wave_sync();
+            if (ncand <= CAND_CAP) {
+                const int nslots = (ncand + 63) >> 6;
+                int ck[CAND_SLOTS];
+#pragma unroll
+                for (int s = 0; s < CAND_SLOTS; ++s) {
+                    const int p = s * 64 + lane;
+                    ck[s] = (s < nslots && p < ncand) ? (int)(cand[p].x & 0x7FFFFFFFu) : -1;
+                }
+                auto count_cand = [&](int x) {
+                    int n = 0;
+#pragma unroll
+                    for (int s = 0; s < CAND_SLOTS; ++s)
+                        if (s < nslots) n += sl_popc(sl_ballot(ck[s] >= x));
+                    return n;
+                };
+                const int T = bisect_kth(L, hi, k, count_cand);
+                const int n_ge = count_cand(T);
+                const bool ties = n_ge != k;
+                int need = 0;
+                if (ties) {
+                    int n_gt = 0;
+#pragma unroll
+                    for (int s = 0; s < CAND_SLOTS; ++s)
+                        if (s < nslots) n_gt += sl_popc(sl_ballot(ck[s] > T));
+                    need = k - n_gt;
+                }
+                int base = 0, tbase = 0;
+#pragma unroll
+                for (int s = 0; s < CAND_SLOTS; ++s) {
+                    if (s < nslots) {
+                        bool f;
+                        if (!ties) {
+                            f = ck[s] >= T;
+                        } else {
+                            const bool eq = ck[s] == T;
+                            const unsigned long long me = sl_ballot(eq);
+                            f = ck[s] > T || (eq && tbase + sl_mbcnt(me) < need);
+                            tbase += sl_popc(me);
+                        }
+                        const unsigned long long m = sl_ballot(f);
+                        const int pos = base + sl_mbcnt(m);
+                        if (f && pos < k) {
+                            const uint2 v = cand[s * 64 + lane];
+                            sel_val[pos] = __uint_as_float(v.x);
+                            sel_idx[pos] = (unsigned short)v.y;
+                        }
+                        base += sl_popc(m);
+                    }
+                }
+                done = true;
+            }
+        }
+    } else {
+        // ------------------------------------------------------------ partial chunk, scalar accesses
+        const int rows = d.rows, cols = d.cols, last_cols = d.last_cols;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            const int row = 4 * i + lr;
+            const int lim = row < rows - 1 ? cols : (row == rows - 1 ? last_cols : 0);
+#pragma unroll
+            for (int cc = 0; cc < 4; ++cc) {
+                const int col = lc + cc;
+                float v = 0.0f;
+                if (col < lim) {
+                    const unsigned o = row * stride + col;
+                    if (!A.frozen) {
+                        v = fmaf(A.beta, ec[o], dc[o]);
+                        ec[o] = v;
+                    } else {
+                        v = dc[o];
+                    }
+                } else {
+                    inside &= ~(1ull << (4 * i + cc));
+                }
+                a[4 * i + cc] = v;
+            }
+        }
+    }
+
+    if (!done) {
+        int key[64];
+        unsigned sg0 = 0, sg1 = 0;
+#pragma unroll
+        for (int r = 0; r < 64; ++r) {
+            const unsigned u = __float_as_uint(a[r]);
+            const bool outside = !((inside >> r) & 1ull);
+            key[r] = outside ? -1 : (int)(u & 0x7FFFFFFFu);
+            const unsigned sbit = outside ? 0u : (u >> 31);
+            if (r < 32) sg0 = (sg0 << 1) | sbit;
+            else sg1 = (sg1 << 1) | sbit;
+        }
+        select_general(key, sg0, sg1, k, lane, sel_val, sel_idx);
+    }
+    sl_wave_sync();
 
     // ---------------------------------------------------------------- outputs
     const int t = A.chunk_tensor[c];
@@ -325,7 +394,6 @@ SL_DEV void select_chunk(const SelectArgs &A, unsigned char *smem)
     }
 
     // per-chunk leaves of the quantizer's mean / variance sums
-    double *scratch = reinterpret_cast<double *>(smem + 6 * (size_t)k + 8 - ((6 * (size_t)k) & 7));
     const double s1 = sl_chunk_tree(k, lane, scratch, [&](int s) {
         const int p = s * 64 + lane;
         return p < k ? (double)sel_val[p] : 0.0;
@@ -341,28 +409,22 @@ SL_DEV void select_chunk(const SelectArgs &A, unsigned char *smem)
     }
 }
 
-template <int GPL>
-__global__ void __launch_bounds__(64) k_select(SelectArgs A)
-{
-    extern __shared__ __align__(16) unsigned char smem[];
-    select_chunk<GPL>(A, smem);
-}
-
 }  // namespace
 
-static size_t select_lds_bytes(int k)
+static size_t select_lds_per_wave(int k, bool pruned)
 {
-    size_t sel = 6 * (size_t)k;
-    sel = (sel + 15) / 8 * 8;          // room for the 8-byte alignment of the tree scratch
-    size_t need = sel + 64 * sizeof(double);
-    size_t cand = CAND_CAP * sizeof(int);
-    return need > cand ? need : cand;
+    size_t b = pruned ? sizeof(uint2) * CAND_CAP : 0;
+    b += (6 * (size_t)k + 7) & ~(size_t)7;
+    b += 64 * sizeof(double);
+    return (b + 15) & ~(size_t)15;
 }
 
 int slk_select(const sl_plan *p, float *e, const float *delta, float beta, int frozen,
                unsigned char *payload, unsigned char *ws, hipStream_t st)
 {
     if (p->n_chunks == 0) return SL_OK;
+    const int k = p->k;
+    const bool pruned = k <= 256;
     SelectArgs A;
     A.desc = p->d_desc;
     A.chunk_tensor = p->d_chunk_tensor;
@@ -371,14 +433,16 @@ int slk_select(const sl_plan *p, float *e, const float *delta, float beta, int f
     A.delta = delta;
     A.beta = beta;
     A.frozen = frozen;
-    A.k = p->k;
+    A.k = k;
+    A.lds_per_wave = (int)select_lds_per_wave(k, pruned);
     A.vals = reinterpret_cast<float *>(ws + p->ws_vals);
     A.leafA = reinterpret_cast<double *>(ws + p->ws_leafA);
     A.payload = payload;
     A.n_chunks = p->n_chunks;
-    const dim3 grid((unsigned)p->n_chunks), block(64);
-    const size_t lds = select_lds_bytes(p->k);
-    const int k = p->k;
+    // waves (= chunks) per workgroup: 4 adjacent chunks when their LDS fits
+    const int wpb = 4 * (size_t)A.lds_per_wave <= 65536 ? 4 : 1;
+    const dim3 grid((unsigned)((p->n_chunks + wpb - 1) / wpb)), block(64 * wpb);
+    const size_t lds = (size_t)A.lds_per_wave * wpb;
     if (k <= 32) hipLaunchKernelGGL(k_select<1>, grid, block, lds, st, A);
     else if (k <= 64) hipLaunchKernelGGL(k_select<2>, grid, block, lds, st, A);
     else if (k <= 128) hipLaunchKernelGGL(k_select<4>, grid, block, lds, st, A);
