@@ -70,6 +70,10 @@ def main():
     ap.add_argument("--delta-buffers", type=int, default=3)
     ap.add_argument("--cpu-layers", type=int, default=4)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--mode", choices=["deferred", "eager"], default="deferred",
+                    help="deferred: the error update of a round is folded into the next round's "
+                         "read of e (SL_COMPRESS_DEFER_RESIDUAL + pending); eager: scattered update "
+                         "inside every sl_compress")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (the R workers are R payload buffers on "
@@ -109,20 +113,40 @@ def main():
         synth.fill_delta(w, d, 1 + i, 0)
     torch.cuda.synchronize()
 
-    def step(i):
-        sl.sl_compress(plan, e0, deltas[i % len(deltas)], w.beta, pays[0], ws)
-        sl.sl_decompress_avg_apply(plan, theta, pays, w.lr)
+    # worker 0's payload alternates between two buffers so that the previous round's
+    # payload can be handed back as `pending`
+    own = [pays[0], sl.alloc_payload(plan)]
+    state = {"pending": None, "i": 0}
 
-    for i in range(args.warmup):
-        step(i)
-    torch.cuda.synchronize()
-    sl.sl_profile_begin(plan, args.steps)
-    t0 = time.perf_counter()
-    for i in range(args.steps):
-        step(args.warmup + i)
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
-    prof = sl.sl_profile_end(plan)
+    def step(mode):
+        i = state["i"]
+        out = own[i % 2]
+        if mode == "deferred":
+            sl.sl_compress(plan, e0, deltas[i % len(deltas)], w.beta, out, ws,
+                           flags=sl.SL_COMPRESS_DEFER_RESIDUAL, pending=state["pending"])
+            state["pending"] = out
+        else:
+            sl.sl_compress(plan, e0, deltas[i % len(deltas)], w.beta, out, ws, pending=state["pending"])
+            state["pending"] = None
+        sl.sl_decompress_avg_apply(plan, theta, [out] + pays[1:], w.lr)
+        state["i"] = i + 1
+
+    def timed(mode, steps):
+        for _ in range(args.warmup):
+            step(mode)
+        torch.cuda.synchronize()
+        sl.sl_profile_begin(plan, steps)
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            step(mode)
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        return dt, sl.sl_profile_end(plan)
+
+    other = "eager" if args.mode == "deferred" else "deferred"
+    dt_other, prof_other = timed(other, max(2, args.steps // 4))
+    ms_other = 1e3 * dt_other / max(2, args.steps // 4)
+    dt, prof = timed(args.mode, args.steps)
 
     ms_step = 1e3 * dt / args.steps
     rec = 7 * w.k // 4
@@ -157,7 +181,7 @@ def main():
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"config {w.config_id}: {w.name}, {len(descs)} fp32 tensors, "
                                f"N={N}, chunk 4096 ({'flat runs' if args.flat else '64x64 tiles / 1-D runs'}), "
-                               f"k={w.k}, R={w.R}, beta={w.beta}, lr={w.lr}",
+                               f"k={w.k}, R={w.R}, beta={w.beta}, lr={w.lr}, {args.mode} residual",
                    "n_elements": N, "n_chunks": n_chunks, "k": w.k, "R": w.R},
         "roofline": {"bound": "hbm", "kernel": "k_select (EF accumulate + chunk Top-k)",
                      "achieved": sel_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
@@ -167,6 +191,9 @@ def main():
                      "achieved_GBps": bytes_round / (ms_step * 1e-3) / 1e9,
                      "frac_of_peak": bytes_round / (ms_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
                      "device_copy_GBps": copy_gbs},
+        "mode": args.mode,
+        "other_mode": {"mode": other, "ms_per_step": ms_other, "value": N / (ms_other * 1e-3) / 1e9,
+                       "kernels_ms": {p: prof_other[p][0] for p in prof_other}},
         "kernels_ms": {p: prof[p][0] for p in prof},
         "compress_ms": compress_ms, "apply_ms": apply_ms,
         "apply_GBps": apply_bytes / (apply_ms * 1e-3) / 1e9 if apply_ms > 0 else 0.0,

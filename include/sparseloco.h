@@ -51,9 +51,12 @@ enum { SL_LAYOUT_FLAT = 0,    /* chunks are runs of 4096 consecutive elements   
 
 /* flags of sl_compress */
 enum { SL_COMPRESS_DEFAULT = 0,
-       SL_COMPRESS_EF_FROZEN = 1 /* appendix "Freezing Error Feedback": the buffer
-                                    is neither used nor accumulated, i.e. a = delta
-                                    and e is left untouched                        */ };
+       SL_COMPRESS_EF_FROZEN = 1, /* appendix "Freezing Error Feedback": the buffer
+                                     is neither used nor accumulated, i.e. a = delta
+                                     and e is left untouched                       */
+       SL_COMPRESS_DEFER_RESIDUAL = 2 /* leave e = a: the subtraction of the sent
+                                     values (Eq. (2) line 2) stays pending and is
+                                     folded into the next call, see sl_compress   */ };
 
 enum { SL_CHUNK = 4096, SL_MAX_WORKERS = 64 };
 
@@ -102,12 +105,29 @@ size_t sl_workspace_bytes(const sl_plan *plan);
  *   format; e <- a - LUT[code] at the selected positions, e <- a elsewhere.
  * e        inout, device, fp32 arena, 16-byte aligned
  * delta    in,    device, fp32 arena, 16-byte aligned, must not alias e
+ * flags    SL_COMPRESS_DEFAULT, SL_COMPRESS_EF_FROZEN or SL_COMPRESS_DEFER_RESIDUAL
+ * pending  in, device, or NULL: the payload of the previous call on this e if
+ *          that call was made with SL_COMPRESS_DEFER_RESIDUAL.  Its values are
+ *          subtracted from e while e is read (e_true = e - LUT[code] at its
+ *          positions), so the error update of the previous round costs no
+ *          scattered pass over e.  Must not be `payload`; 16-byte aligned.
  * payload  out,   device, sl_payload_bytes() bytes, 16-byte aligned
  * workspace       device, sl_workspace_bytes() bytes, 256-byte aligned
- * flags    SL_COMPRESS_DEFAULT or SL_COMPRESS_EF_FROZEN
- * Elements of the arenas that belong to no tensor are neither read nor written. */
+ * With SL_COMPRESS_DEFER_RESIDUAL the call leaves e = a everywhere; the true
+ * error buffer of Eq. (2) is then e minus the dequantised `payload`, which the
+ * caller obtains by passing `payload` as `pending` to the next call or by
+ * sl_residual_apply.  Results (payloads, and e once nothing is pending) are
+ * bit-identical between the two modes.  EF_FROZEN excludes both `pending` and
+ * DEFER_RESIDUAL.  Elements of the arenas that belong to no tensor are neither
+ * read nor written. */
 int sl_compress(sl_plan *plan, float *e, const float *delta, float beta, int flags,
-                void *payload, void *workspace, void *stream);
+                const void *pending, void *payload, void *workspace, void *stream);
+
+/* The error update on its own (Eq. (2) line 2, second half; Algorithm 1 error
+ * update): e[i] <- e[i] - LUT[code] at the positions `payload` transmits.  Ends
+ * a chain of SL_COMPRESS_DEFER_RESIDUAL calls (e.g. before a checkpoint).
+ * e inout device arena; payload in device, a payload of this plan. */
+int sl_residual_apply(sl_plan *plan, float *e, const void *payload, void *stream);
 
 /* Aggregate + outer update (Algorithm 1, aggregation block; Eq. (2) lines 3-4):
  *   per chunk a zero fp32 accumulator, workers added in the order r = 0..R-1

@@ -20,13 +20,14 @@ SL_LAYOUT_FLAT = 0
 SL_LAYOUT_TILE64 = 1
 SL_COMPRESS_DEFAULT = 0
 SL_COMPRESS_EF_FROZEN = 1
+SL_COMPRESS_DEFER_RESIDUAL = 2
 SL_MAX_WORKERS = 64
 
 EXPORTS = [
     "sl_plan_create", "sl_plan_destroy", "sl_plan_num_chunks", "sl_plan_num_elements",
     "sl_payload_bytes", "sl_payload_tensor_offset", "sl_workspace_bytes", "sl_compress",
     "sl_decompress_avg_apply", "sl_pack_indices", "sl_strerror", "sl_last_hip_error",
-    "sl_profile_begin", "sl_profile_end",
+    "sl_profile_begin", "sl_profile_end", "sl_residual_apply",
 ]
 PROF_PHASES = ["select", "stats", "codes", "lut", "residual", "apply"]
 
@@ -72,7 +73,9 @@ def lib():
         L.sl_workspace_bytes.restype = sz
         L.sl_workspace_bytes.argtypes = [vp]
         L.sl_compress.restype = i32
-        L.sl_compress.argtypes = [vp, vp, vp, C.c_float, i32, vp, vp, vp]
+        L.sl_compress.argtypes = [vp, vp, vp, C.c_float, i32, vp, vp, vp, vp]
+        L.sl_residual_apply.restype = i32
+        L.sl_residual_apply.argtypes = [vp, vp, vp, vp]
         L.sl_decompress_avg_apply.restype = i32
         L.sl_decompress_avg_apply.argtypes = [vp, vp, C.POINTER(vp), i32, C.c_float, vp]
         L.sl_pack_indices.restype = i32
@@ -159,12 +162,20 @@ def sl_plan_create(descs: Sequence[Sequence[int]], k: int) -> Plan:
 
 def sl_compress(plan: Plan, e: Optional[torch.Tensor], delta: torch.Tensor, beta: float,
                 payload: torch.Tensor, workspace: torch.Tensor, flags: int = SL_COMPRESS_DEFAULT,
-                stream=None) -> None:
+                pending: Optional[torch.Tensor] = None, stream=None) -> None:
     st = lib().sl_compress(plan.handle, _dev_ptr(e, torch.float32), _dev_ptr(delta, torch.float32),
-                           float(beta), int(flags), _dev_ptr(payload, torch.uint8),
-                           _dev_ptr(workspace, torch.uint8), _stream_ptr(stream))
+                           float(beta), int(flags), _dev_ptr(pending, torch.uint8),
+                           _dev_ptr(payload, torch.uint8), _dev_ptr(workspace, torch.uint8),
+                           _stream_ptr(stream))
     if st:
         raise SparseLoCoError("sl_compress", st)
+
+
+def sl_residual_apply(plan: Plan, e: torch.Tensor, payload: torch.Tensor, stream=None) -> None:
+    st = lib().sl_residual_apply(plan.handle, _dev_ptr(e, torch.float32),
+                                 _dev_ptr(payload, torch.uint8), _stream_ptr(stream))
+    if st:
+        raise SparseLoCoError("sl_residual_apply", st)
 
 
 def sl_decompress_avg_apply(plan: Plan, theta: torch.Tensor, payloads: Sequence[torch.Tensor],

@@ -52,7 +52,6 @@ int sl_plan_create(const sl_tensor *tensors, int n_tensors, int k, sl_plan **out
 
     const int64_t rec = (int64_t)7 * k / 4;
     std::vector<SlChunkDesc> desc;
-    std::vector<int> chunk_tensor;
     std::vector<SlTensorDev> tdev((size_t)n_tensors);
     int64_t n_elements = 0, n_partial = 0;
     size_t pay = 0;
@@ -68,7 +67,7 @@ int sl_plan_create(const sl_tensor *tensors, int n_tensors, int k, sl_plan **out
             if (T.rows > (int64_t)1 << 40 || T.cols > (int64_t)1 << 40 ||
                 T.rows * T.cols > (int64_t)1 << 46)
                 return SL_ERR_INVALID_ARG;
-            if (T.layout == SL_LAYOUT_TILE64 && T.cols > (int64_t)1 << 24) return SL_ERR_INVALID_ARG;
+            if (T.layout == SL_LAYOUT_TILE64 && T.cols > (int64_t)1 << 23) return SL_ERR_INVALID_ARG;
             span.emplace_back(T.offset, T.offset + T.rows * T.cols);
         }
         std::sort(span.begin(), span.end());
@@ -94,8 +93,10 @@ int sl_plan_create(const sl_tensor *tensors, int n_tensors, int k, sl_plan **out
                         d.rows = (unsigned char)rv;
                         d.cols = d.last_cols = (unsigned char)cv;
                         d.flags = (rv == 64 && cv == 64 && (T.cols & 3) == 0) ? SLC_FULL : 0;
+                        d.tensor = t;
+                        d.local_chunk = (int)(a * tc + b);
+                        d.rec_off = (long long)pay + 16 + (long long)d.local_chunk * rec;
                         desc.push_back(d);
-                        chunk_tensor.push_back(t);
                     }
             } else {
                 const int64_t n = T.rows * T.cols;
@@ -109,8 +110,10 @@ int sl_plan_create(const sl_tensor *tensors, int n_tensors, int k, sl_plan **out
                     d.cols = 64;
                     d.last_cols = (unsigned char)(nv - (int64_t)(d.rows - 1) * 64);
                     d.flags = nv == SL_CHUNK ? SLC_FULL : 0;
+                    d.tensor = t;
+                    d.local_chunk = (int)a;
+                    d.rec_off = (long long)pay + 16 + (long long)d.local_chunk * rec;
                     desc.push_back(d);
-                    chunk_tensor.push_back(t);
                 }
             }
             D.n_chunks = (long long)desc.size() - D.chunk0;
@@ -163,14 +166,11 @@ int sl_plan_create(const sl_tensor *tensors, int n_tensors, int k, sl_plan **out
     if (n_tensors) std::memcpy(p->h_tensors, tdev.data(), sizeof(SlTensorDev) * (size_t)n_tensors);
 
     if (p->n_chunks > 0) {
-        const size_t b_desc = desc.size() * sizeof(SlChunkDesc), b_ct = desc.size() * sizeof(int),
+        const size_t b_desc = desc.size() * sizeof(SlChunkDesc),
                      b_t = (size_t)n_tensors * sizeof(SlTensorDev);
         if ((err = hipMalloc((void **)&p->d_desc, b_desc)) != hipSuccess ||
-            (err = hipMalloc((void **)&p->d_chunk_tensor, b_ct)) != hipSuccess ||
             (err = hipMalloc((void **)&p->d_tensors, b_t)) != hipSuccess ||
             (err = hipMemcpy(p->d_desc, desc.data(), b_desc, hipMemcpyHostToDevice)) != hipSuccess ||
-            (err = hipMemcpy(p->d_chunk_tensor, chunk_tensor.data(), b_ct, hipMemcpyHostToDevice)) !=
-                hipSuccess ||
             (err = hipMemcpy(p->d_tensors, tdev.data(), b_t, hipMemcpyHostToDevice)) != hipSuccess) {
             const int rc = err == hipErrorOutOfMemory ? SL_ERR_NOMEM : hip_fail(err);
             sl_plan_destroy(p);
@@ -185,7 +185,6 @@ int sl_plan_destroy(sl_plan *p)
 {
     if (!p) return SL_OK;
     if (p->d_desc) (void)hipFree(p->d_desc);
-    if (p->d_chunk_tensor) (void)hipFree(p->d_chunk_tensor);
     if (p->d_tensors) (void)hipFree(p->d_tensors);
     std::free(p->h_tensors);
     if (p->prof) {
@@ -217,16 +216,18 @@ static int check_device(const sl_plan *p)
 
 static bool misaligned(const void *ptr, size_t a) { return ((uintptr_t)ptr & (a - 1)) != 0; }
 
-int sl_compress(sl_plan *p, float *e, const float *delta, float beta, int flags, void *payload,
-                void *workspace, void *stream)
+int sl_compress(sl_plan *p, float *e, const float *delta, float beta, int flags, const void *pending,
+                void *payload, void *workspace, void *stream)
 {
     if (!p || !delta || !payload || !workspace) return SL_ERR_INVALID_ARG;
-    if (flags & ~SL_COMPRESS_EF_FROZEN) return SL_ERR_INVALID_ARG;
+    if (flags & ~(SL_COMPRESS_EF_FROZEN | SL_COMPRESS_DEFER_RESIDUAL)) return SL_ERR_INVALID_ARG;
     const int frozen = (flags & SL_COMPRESS_EF_FROZEN) ? 1 : 0;
+    const int defer = (flags & SL_COMPRESS_DEFER_RESIDUAL) ? 1 : 0;
     if (!frozen && !e) return SL_ERR_INVALID_ARG;
-    if (e == delta) return SL_ERR_INVALID_ARG;
+    if (frozen && (pending || defer)) return SL_ERR_INVALID_ARG;
+    if (e == delta || pending == payload) return SL_ERR_INVALID_ARG;
     if (misaligned(e, 16) || misaligned(delta, 16) || misaligned(payload, 16) ||
-        misaligned(workspace, 256))
+        misaligned(pending, 16) || misaligned(workspace, 256))
         return SL_ERR_INVALID_ARG;
     int rc = check_device(p);
     if (rc) return rc;
@@ -234,9 +235,21 @@ int sl_compress(sl_plan *p, float *e, const float *delta, float beta, int flags,
     unsigned char *pay = static_cast<unsigned char *>(payload);
     unsigned char *ws = static_cast<unsigned char *>(workspace);
     sl_prof_mark(p, -1, st);
-    if ((rc = slk_select(p, e, delta, beta, frozen, pay, ws, st))) return rc;
+    if ((rc = slk_select(p, e, delta, beta, frozen, static_cast<const unsigned char *>(pending), pay,
+                         ws, st)))
+        return rc;
     sl_prof_mark(p, SL_PROF_SELECT, st);
-    return slk_quantize(p, e, frozen, pay, ws, st);
+    return slk_quantize(p, e, frozen || defer, pay, ws, st);
+}
+
+int sl_residual_apply(sl_plan *p, float *e, const void *payload, void *stream)
+{
+    if (!p || !e || !payload) return SL_ERR_INVALID_ARG;
+    if (misaligned(e, 16) || misaligned(payload, 16)) return SL_ERR_INVALID_ARG;
+    int rc = check_device(p);
+    if (rc) return rc;
+    return slk_residual(p, e, static_cast<const unsigned char *>(payload),
+                        static_cast<hipStream_t>(stream));
 }
 
 int sl_decompress_avg_apply(sl_plan *p, float *theta, const void *const *payloads, int R, float lr,

@@ -16,8 +16,6 @@ namespace {
 
 struct ApplyArgs {
     const SlChunkDesc *desc;
-    const int *chunk_tensor;
-    const SlTensorDev *tensors;
     float *theta;
     float neg_lr, inv_R;
     int R, k;
@@ -39,11 +37,9 @@ __global__ void __launch_bounds__(256) k_apply(ApplyArgs A)
     float *acc = reinterpret_cast<float *>(smem);                    // 4096 floats
     unsigned char *stage = smem + SL_CHUNK * sizeof(float);
     const SlChunkDesc d = A.desc[c];
-    const int t = A.chunk_tensor[c];
-    const SlTensorDev td = A.tensors[t];
     const int rec_bytes = 7 * k / 4;
     const int rec_pad = ((rec_bytes + 3) & ~3) + 16;                 // staging pitch: LUT + record
-    const long long rec_off = td.pay_off + 16 + (c - td.chunk0) * (long long)rec_bytes;
+    const long long rec_off = d.rec_off, lut_off = sl_lut_off(d, k);
 
     float *tc = A.theta + d.base;
     const int lr = lane >> 4, lc = (lane & 15) * 4;
@@ -53,9 +49,9 @@ __global__ void __launch_bounds__(256) k_apply(ApplyArgs A)
     // theta loads are issued first so that their latency overlaps the decode
     sl_f4 th[16];
     if (full) {
-        const unsigned o0 = lr * stride + lc;
+        const unsigned o0 = 4u * (lr * stride + lc), step = 16u * stride;
 #pragma unroll
-        for (int i = 0; i < 16; ++i) th[i] = sl_load_stream(tc + (o0 + 4u * i * stride));
+        for (int i = 0; i < 16; ++i) th[i] = sl_load_stream_at(tc, i * step, o0);
     }
 
 #pragma unroll
@@ -68,7 +64,7 @@ __global__ void __launch_bounds__(256) k_apply(ApplyArgs A)
         for (int w = lane; w < nb * 4; w += 64) {                    // the tensor's LUT of each worker
             const int r = w >> 2, q = w & 3;
             reinterpret_cast<unsigned *>(stage)[r * (rec_pad >> 2) + q] =
-                reinterpret_cast<const unsigned *>(A.payload[r0 + r] + td.pay_off)[q];
+                reinterpret_cast<const unsigned *>(A.payload[r0 + r] + lut_off)[q];
         }
         if ((rec_bytes & 3) == 0) {
             const int words = rec_bytes >> 2;
@@ -101,7 +97,7 @@ __global__ void __launch_bounds__(256) k_apply(ApplyArgs A)
     }
 
     if (full) {
-        const unsigned o0 = lr * stride + lc;
+        const unsigned o0 = 4u * (lr * stride + lc), step = 16u * stride;
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
             const float4 a = reinterpret_cast<const float4 *>(acc)[i * 64 + lane];
@@ -110,7 +106,7 @@ __global__ void __launch_bounds__(256) k_apply(ApplyArgs A)
             v.y = fmaf(A.neg_lr, a.y * A.inv_R, v.y);
             v.z = fmaf(A.neg_lr, a.z * A.inv_R, v.z);
             v.w = fmaf(A.neg_lr, a.w * A.inv_R, v.w);
-            sl_store_stream(tc + (o0 + 4u * i * stride), v);
+            sl_store_stream_at(tc, i * step, o0, v);
         }
     } else {
         const int rows = d.rows, cols = d.cols, last_cols = d.last_cols;
@@ -162,8 +158,6 @@ int slk_apply(const sl_plan *p, float *theta, const void *const *payloads, int R
     if (p->n_chunks == 0) return SL_OK;
     ApplyArgs A;
     A.desc = p->d_desc;
-    A.chunk_tensor = p->d_chunk_tensor;
-    A.tensors = p->d_tensors;
     A.theta = theta;
     A.neg_lr = -lr;
     A.inv_R = 1.0f / (float)R;

@@ -28,6 +28,9 @@ SL_DEV void sl_wave_sync()
 typedef float sl_f4 __attribute__((ext_vector_type(4)));
 
 // Streaming (non-temporal) 16-byte accesses for data that is touched once.
+// The *_at forms take a wave-uniform base and a 32-bit byte offset, which the
+// compiler turns into scalar-base + 32-bit vector-offset addressing (one VGPR
+// per address instead of two).
 SL_DEV sl_f4 sl_load_stream(const float *p)
 {
     return __builtin_nontemporal_load(reinterpret_cast<const sl_f4 *>(p));
@@ -35,6 +38,19 @@ SL_DEV sl_f4 sl_load_stream(const float *p)
 SL_DEV void sl_store_stream(float *p, sl_f4 v)
 {
     __builtin_nontemporal_store(v, reinterpret_cast<sl_f4 *>(p));
+}
+
+// (`row_off` is a wave-uniform byte offset and goes into the scalar base, so
+// that all accesses of a chunk share the single vector offset `lane_off`.)
+SL_DEV sl_f4 sl_load_stream_at(const float *base, unsigned row_off, unsigned lane_off)
+{
+    const char *row = reinterpret_cast<const char *>(base) + row_off;
+    return __builtin_nontemporal_load(reinterpret_cast<const sl_f4 *>(row + lane_off));
+}
+SL_DEV void sl_store_stream_at(float *base, unsigned row_off, unsigned lane_off, sl_f4 v)
+{
+    char *row = reinterpret_cast<char *>(base) + row_off;
+    __builtin_nontemporal_store(v, reinterpret_cast<sl_f4 *>(row + lane_off));
 }
 
 SL_DEV int sl_popc(unsigned long long m) { return __builtin_popcountll(m); }

@@ -8,13 +8,17 @@
 // One 4096-element chunk seen as a 64-row view: element (row, col) of the view
 // is arena[base + row*stride + col].  A FLAT chunk is the view with stride 64.
 // `rows` valid rows; every valid row has `cols` valid columns except the last
-// valid row, which has `last_cols`.
+// valid row, which has `last_cols`.  Everything a kernel needs to know about a
+// chunk comes with one 32-byte scalar load.
 struct SlChunkDesc {
     long long base;
     int stride;
     unsigned char rows, cols, last_cols, flags;
+    long long rec_off;      // byte offset of the chunk's record inside a payload
+    int tensor;             // index of the tensor in the list
+    int local_chunk;        // index of the chunk inside its tensor
 };
-static_assert(sizeof(SlChunkDesc) == 16, "descriptor is one 16-byte load");
+static_assert(sizeof(SlChunkDesc) == 32, "descriptor is one 32-byte load");
 enum { SLC_FULL = 1 };   // all 4096 positions valid and every row 16-byte aligned
 
 struct SlTensorDev {
@@ -46,7 +50,6 @@ struct sl_plan {
     size_t ws_vals, ws_leafA, ws_leafC, ws_cnt, ws_tstat;
     // device tables
     SlChunkDesc *d_desc;
-    int *d_chunk_tensor;
     SlTensorDev *d_tensors;
     // host copies
     SlTensorDev *h_tensors;
@@ -54,14 +57,24 @@ struct sl_plan {
     struct SlProfile *prof;
 };
 
+// Byte offset of the LUT header of the chunk's tensor block inside a payload.
+__host__ __device__ inline long long sl_lut_off(const SlChunkDesc &d, int k)
+{
+    return d.rec_off - 16 - (long long)d.local_chunk * ((long long)7 * k / 4);
+}
+
 // Records an event after the kernel of `phase` (phase < 0: start of a call).
 void sl_prof_mark(const sl_plan *p, int phase, hipStream_t st);
 
 // launchers (defined next to their kernels)
 int slk_select(const sl_plan *p, float *e, const float *delta, float beta, int frozen,
-               unsigned char *payload, unsigned char *ws, hipStream_t st);
-int slk_quantize(const sl_plan *p, float *e, int frozen, unsigned char *payload, unsigned char *ws,
-                 hipStream_t st);
+               const unsigned char *pending, unsigned char *payload, unsigned char *ws,
+               hipStream_t st);
+// B, C, D and (unless skip_residual) E
+int slk_quantize(const sl_plan *p, float *e, int skip_residual, unsigned char *payload,
+                 unsigned char *ws, hipStream_t st);
+// E on its own: e[idx] -= LUT[code] for the entries of `payload`
+int slk_residual(const sl_plan *p, float *e, const unsigned char *payload, hipStream_t st);
 int slk_apply(const sl_plan *p, float *theta, const void *const *payloads, int R, float lr,
               hipStream_t st);
 int slk_pack(const uint16_t *idx, const uint8_t *codes, int64_t n_chunks, int k, unsigned char *out,

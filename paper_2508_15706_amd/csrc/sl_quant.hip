@@ -111,8 +111,7 @@ k_tensor_stats(const SlTensorDev *tensors, const double *leafA, long long n_chun
 
 // ------------------------------------------------------------------ kernel C
 struct CodeArgs {
-    const int *chunk_tensor;
-    const SlTensorDev *tensors;
+    const SlChunkDesc *desc;
     const SlTensorStat *tstat;
     const float *vals;
     double *leafC;          // [4][n_chunks] per-chunk tree sums of the values of each bin
@@ -132,9 +131,8 @@ __global__ void __launch_bounds__(256) k_codes(CodeArgs A)
     const long long c = (long long)blockIdx.x * (blockDim.x >> 6) + wave;
     if (c >= A.n_chunks) return;
     unsigned char *smem = smem_all + (size_t)wave * A.lds_per_wave;
-    const int t = A.chunk_tensor[c];
-    const SlTensorDev td = A.tensors[t];
-    const double mu = A.tstat[t].mu, T = A.tstat[t].T;
+    const SlChunkDesc d = A.desc[c];
+    const double mu = A.tstat[d.tensor].mu, T = A.tstat[d.tensor].T;
     unsigned char *code_lds = smem;                                   // k bytes
     double *scratch = reinterpret_cast<double *>(smem + ((k + 7) & ~7));
     const float *x = A.vals + c * k;
@@ -155,8 +153,7 @@ __global__ void __launch_bounds__(256) k_codes(CodeArgs A)
     sl_wave_sync();
 
     // codes, four per byte, entry m in bits 2*(m mod 4)
-    const long long rec_bytes = (long long)7 * k / 4;
-    unsigned char *rec = A.payload + td.pay_off + 16 + (c - td.chunk0) * rec_bytes + 3 * k / 2;
+    unsigned char *rec = A.payload + d.rec_off + 3 * k / 2;
     if ((k & 15) == 0) {
         unsigned *rw = reinterpret_cast<unsigned *>(rec);
         for (int w = lane; w < k / 16; w += 64) {
@@ -227,10 +224,7 @@ k_tensor_lut(const SlTensorDev *tensors, const double *leafC, const unsigned *cn
 // ------------------------------------------------------------------ kernel E
 struct ResidualArgs {
     const SlChunkDesc *desc;
-    const int *chunk_tensor;
-    const SlTensorDev *tensors;
-    const SlTensorStat *tstat;
-    const float *vals;
+    const float *vals;              // the selected values a, or null: read them from e
     const unsigned char *payload;
     float *e;
     long long n_chunks;
@@ -244,12 +238,8 @@ __global__ void __launch_bounds__(256) k_residual(ResidualArgs A)
     const long long c = (long long)blockIdx.x * (blockDim.x >> 6) + wave;
     if (c >= A.n_chunks) return;
     const SlChunkDesc d = A.desc[c];
-    const int t = A.chunk_tensor[c];
-    const SlTensorDev td = A.tensors[t];
-    const float l0 = A.tstat[t].lut[0], l1 = A.tstat[t].lut[1], l2 = A.tstat[t].lut[2],
-                l3 = A.tstat[t].lut[3];
-    const long long rec_bytes = (long long)7 * k / 4;
-    const unsigned char *rec = A.payload + td.pay_off + 16 + (c - td.chunk0) * rec_bytes;
+    const float4 lut = *reinterpret_cast<const float4 *>(A.payload + sl_lut_off(d, k));
+    const unsigned char *rec = A.payload + d.rec_off;
     const unsigned char *codes = rec + 3 * k / 2;
     float *ec = A.e + d.base;
     for (int m = lane; m < k; m += 64) {
@@ -257,8 +247,10 @@ __global__ void __launch_bounds__(256) k_residual(ResidualArgs A)
         const unsigned w = (unsigned)rec[b] | ((unsigned)rec[b + 1] << 8);
         const unsigned j = (m & 1) ? (w >> 4) : (w & 0xFFFu);
         const unsigned code = (codes[m >> 2] >> (2 * (m & 3))) & 3u;
-        const float q = code == 0 ? l0 : code == 1 ? l1 : code == 2 ? l2 : l3;
-        ec[(j >> 6) * (unsigned)d.stride + (j & 63u)] = A.vals[c * k + m] - q;
+        const float q = code == 0 ? lut.x : code == 1 ? lut.y : code == 2 ? lut.z : lut.w;
+        float *dst = ec + ((j >> 6) * (unsigned)d.stride + (j & 63u));
+        const float a = A.vals ? A.vals[c * k + m] : *dst;
+        *dst = a - q;
     }
 }
 
@@ -274,8 +266,30 @@ static int check_launch()
     return SL_OK;
 }
 
-int slk_quantize(const sl_plan *p, float *e, int frozen, unsigned char *payload, unsigned char *ws,
-                 hipStream_t st)
+static int launch_residual(const sl_plan *p, float *e, const float *vals, const unsigned char *payload,
+                           hipStream_t st)
+{
+    ResidualArgs R;
+    R.desc = p->d_desc;
+    R.vals = vals;
+    R.payload = payload;
+    R.e = e;
+    R.k = p->k;
+    R.n_chunks = p->n_chunks;
+    const int wpb = 4;
+    const unsigned nblk = (unsigned)((p->n_chunks + wpb - 1) / wpb);
+    hipLaunchKernelGGL(k_residual, dim3(nblk), dim3(64 * wpb), 0, st, R);
+    return check_launch();
+}
+
+int slk_residual(const sl_plan *p, float *e, const unsigned char *payload, hipStream_t st)
+{
+    if (p->n_chunks == 0) return SL_OK;
+    return launch_residual(p, e, nullptr, payload, st);
+}
+
+int slk_quantize(const sl_plan *p, float *e, int skip_residual, unsigned char *payload,
+                 unsigned char *ws, hipStream_t st)
 {
     if (p->n_chunks == 0) return SL_OK;
     const int k = p->k;
@@ -292,8 +306,7 @@ int slk_quantize(const sl_plan *p, float *e, int frozen, unsigned char *payload,
     sl_prof_mark(p, SL_PROF_STATS, st);
 
     CodeArgs C;
-    C.chunk_tensor = p->d_chunk_tensor;
-    C.tensors = p->d_tensors;
+    C.desc = p->d_desc;
     C.tstat = tstat;
     C.vals = vals;
     C.leafC = leafC;
@@ -313,19 +326,8 @@ int slk_quantize(const sl_plan *p, float *e, int frozen, unsigned char *payload,
     if ((rc = check_launch())) return rc;
     sl_prof_mark(p, SL_PROF_LUT, st);
 
-    if (!frozen) {
-        ResidualArgs R;
-        R.desc = p->d_desc;
-        R.chunk_tensor = p->d_chunk_tensor;
-        R.tensors = p->d_tensors;
-        R.tstat = tstat;
-        R.vals = vals;
-        R.payload = payload;
-        R.e = e;
-        R.k = k;
-        R.n_chunks = p->n_chunks;
-        hipLaunchKernelGGL(k_residual, dim3(nblk), dim3(64 * wpb), 0, st, R);
-        if ((rc = check_launch())) return rc;
+    if (!skip_residual) {
+        if ((rc = launch_residual(p, e, vals, payload, st))) return rc;
         sl_prof_mark(p, SL_PROF_RESIDUAL, st);
     }
     return SL_OK;

@@ -36,16 +36,18 @@ namespace {
 constexpr int CAND_CAP = 512;             // LDS candidate list, entries of 8 bytes
 constexpr int CAND_SLOTS = CAND_CAP / 64;
 
+constexpr int BM_WORDS = SL_CHUNK / 32;  // bitmap of the pending positions
+
 struct SelectArgs {
     const SlChunkDesc *desc;
-    const int *chunk_tensor;
-    const SlTensorDev *tensors;
     float *e;
     const float *delta;
+    const unsigned char *pending;   // payload whose values are still to be subtracted from e
     float beta;
     int frozen;
     int k;
     int lds_per_wave;
+    int pend_off;           // offset of the pending-correction tables in a wave's LDS
     float *vals;            // [n_chunks * k] selected values, canonical order
     double *leafA;          // [2][n_chunks] per-chunk tree sums of x and x*x
     unsigned char *payload;
@@ -182,16 +184,88 @@ __global__ void SL_SELECT_BOUNDS k_select(SelectArgs A)
     unsigned long long inside = ~0ull;      // bit r: register r is a position of the tensor
     bool done = false;
 
+    // Pending error update of the previous round (deferred residual): the
+    // positions its record transmits become a 4096-bit map in LDS, with the
+    // number of set bits before each 32-bit word, and the dequantised values in
+    // record order (= ascending position, so rank in the map = record entry).
+    unsigned *bm = nullptr, *pre = nullptr;
+    float *ql = nullptr;
+    const bool pend = A.pending != nullptr;
+    const unsigned char *prec = nullptr, *pcodes = nullptr;
+    float4 plut = make_float4(0.f, 0.f, 0.f, 0.f);
+    unsigned p_w0 = 0, p_c0 = 0;            // this lane's first record entry, fetched early
+    if (pend) {
+        bm = reinterpret_cast<unsigned *>(smem + A.pend_off);
+        pre = bm + BM_WORDS;
+        ql = reinterpret_cast<float *>(pre + BM_WORDS);
+        prec = A.pending + d.rec_off;
+        pcodes = prec + 3 * k / 2;
+        plut = *reinterpret_cast<const float4 *>(A.pending + sl_lut_off(d, k));
+        if (lane < k) {
+            const int b0 = (3 * lane) >> 1;
+            p_w0 = (unsigned)prec[b0] | ((unsigned)prec[b0 + 1] << 8);
+            p_c0 = pcodes[lane >> 2];
+        }
+    }
+    // Builds the tables; called once the chunk's bulk loads are in flight so that
+    // the small record loads above and this LDS work hide behind them.
+    auto pend_build = [&]() {
+        reinterpret_cast<uint2 *>(bm)[lane] = make_uint2(0u, 0u);
+        sl_wave_sync();
+        auto entry = [&](int m, unsigned w, unsigned cbyte) {
+            const unsigned j = (m & 1) ? (w >> 4) : (w & 0xFFFu);
+            const unsigned code = (cbyte >> (2 * (m & 3))) & 3u;
+            ql[m] = code == 0 ? plut.x : code == 1 ? plut.y : code == 2 ? plut.z : plut.w;
+            atomicOr(&bm[j >> 5], 1u << (j & 31u));
+        };
+        if (lane < k) entry(lane, p_w0, p_c0);
+        for (int m = lane + 64; m < k; m += 64) {
+            const int b0 = (3 * m) >> 1;
+            entry(m, (unsigned)prec[b0] | ((unsigned)prec[b0 + 1] << 8), pcodes[m >> 2]);
+        }
+        sl_wave_sync();
+        const uint2 w2 = reinterpret_cast<const uint2 *>(bm)[lane];
+        const int c0 = __popc(w2.x), c1 = __popc(w2.y);
+        int incl = c0 + c1;
+#pragma unroll
+        for (int sft = 1; sft < 64; sft <<= 1) {
+            const int up = __shfl_up(incl, sft);
+            if (lane >= sft) incl += up;
+        }
+        const int excl = incl - (c0 + c1);
+        reinterpret_cast<uint2 *>(pre)[lane] = make_uint2((unsigned)excl, (unsigned)(excl + c0));
+        sl_wave_sync();
+    };
+
     if (full) {
         // ------------------------------------------------------------ a = beta*e + delta
-        const unsigned o0 = lr * stride + lc;
+        const unsigned o0 = 4u * (lr * stride + lc);   // byte offset of this lane's first load
+        const unsigned step = 16u * stride;            // four rows further, in bytes
         sl_f4 ev[16], dv[16];
         if (!A.frozen) {
 #pragma unroll
-            for (int i = 0; i < 16; ++i) ev[i] = sl_load_stream(ec + (o0 + 4u * i * stride));
+            for (int i = 0; i < 16; ++i) ev[i] = sl_load_stream_at(ec, i * step, o0);
         }
 #pragma unroll
-        for (int i = 0; i < 16; ++i) dv[i] = sl_load_stream(dc + (o0 + 4u * i * stride));
+        for (int i = 0; i < 16; ++i) dv[i] = sl_load_stream_at(dc, i * step, o0);
+        if (pend) {
+            pend_build();
+            // e_true = e - (dequantised pending value) at this lane's positions:
+            // local index 256*i + 4*lane + cc is bit 4*(lane%8) + cc of word 8*i + lane/8
+            const unsigned sh = 4u * (lane & 7);
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const unsigned word = bm[8 * i + (lane >> 3)];
+                const unsigned nib = (word >> sh) & 0xFu;
+                if (nib) {
+                    int rk = (int)pre[8 * i + (lane >> 3)] + __popc(word & ((1u << sh) - 1u));
+                    if (nib & 1u) ev[i].x = ev[i].x - ql[rk++];
+                    if (nib & 2u) ev[i].y = ev[i].y - ql[rk++];
+                    if (nib & 4u) ev[i].z = ev[i].z - ql[rk++];
+                    if (nib & 8u) ev[i].w = ev[i].w - ql[rk++];
+                }
+            }
+        }
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
             sl_f4 v;
@@ -200,7 +274,7 @@ __global__ void SL_SELECT_BOUNDS k_select(SelectArgs A)
                 v.y = fmaf(A.beta, ev[i].y, dv[i].y);
                 v.z = fmaf(A.beta, ev[i].z, dv[i].z);
                 v.w = fmaf(A.beta, ev[i].w, dv[i].w);
-                sl_store_stream(ec + (o0 + 4u * i * stride), v);
+                sl_store_stream_at(ec, i * step, o0, v);
             } else {
                 v = dv[i];
             }
@@ -315,6 +389,7 @@ __global__ void SL_SELECT_BOUNDS k_select(SelectArgs A)
     } else {
         // ------------------------------------------------------------ partial chunk, scalar accesses
         const int rows = d.rows, cols = d.cols, last_cols = d.last_cols;
+        if (pend) pend_build();
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
             const int row = 4 * i + lr;
@@ -326,7 +401,14 @@ __global__ void SL_SELECT_BOUNDS k_select(SelectArgs A)
                 if (col < lim) {
                     const unsigned o = row * stride + col;
                     if (!A.frozen) {
-                        v = fmaf(A.beta, ec[o], dc[o]);
+                        float ee = ec[o];
+                        if (pend) {
+                            const unsigned w = 8 * i + (lane >> 3), bit = 4u * (lane & 7) + cc;
+                            const unsigned word = bm[w];
+                            if ((word >> bit) & 1u)
+                                ee = ee - ql[(int)pre[w] + __popc(word & ((1u << bit) - 1u))];
+                        }
+                        v = fmaf(A.beta, ee, dc[o]);
                         ec[o] = v;
                     } else {
                         v = dc[o];
@@ -356,10 +438,7 @@ __global__ void SL_SELECT_BOUNDS k_select(SelectArgs A)
     sl_wave_sync();
 
     // ---------------------------------------------------------------- outputs
-    const int t = A.chunk_tensor[c];
-    const SlTensorDev td = A.tensors[t];
-    const long long rec_bytes = (long long)7 * k / 4;
-    unsigned char *rec = A.payload + td.pay_off + 16 + (c - td.chunk0) * rec_bytes;
+    unsigned char *rec = A.payload + d.rec_off;
 
     for (int p = lane; p < k; p += 64) A.vals[c * k + p] = sel_val[p];
 
@@ -411,30 +490,30 @@ __global__ void SL_SELECT_BOUNDS k_select(SelectArgs A)
 
 }  // namespace
 
-static size_t select_lds_per_wave(int k, bool pruned)
-{
-    size_t b = pruned ? sizeof(uint2) * CAND_CAP : 0;
-    b += (6 * (size_t)k + 7) & ~(size_t)7;
-    b += 64 * sizeof(double);
-    return (b + 15) & ~(size_t)15;
-}
-
 int slk_select(const sl_plan *p, float *e, const float *delta, float beta, int frozen,
-               unsigned char *payload, unsigned char *ws, hipStream_t st)
+               const unsigned char *pending, unsigned char *payload, unsigned char *ws,
+               hipStream_t st)
 {
     if (p->n_chunks == 0) return SL_OK;
     const int k = p->k;
     const bool pruned = k <= 256;
     SelectArgs A;
     A.desc = p->d_desc;
-    A.chunk_tensor = p->d_chunk_tensor;
-    A.tensors = p->d_tensors;
     A.e = e;
     A.delta = delta;
+    A.pending = pending;
     A.beta = beta;
     A.frozen = frozen;
     A.k = k;
-    A.lds_per_wave = (int)select_lds_per_wave(k, pruned);
+    {
+        size_t b = pruned ? sizeof(uint2) * CAND_CAP : 0;
+        b += (6 * (size_t)k + 7) & ~(size_t)7;
+        b += 64 * sizeof(double);
+        b = (b + 15) & ~(size_t)15;
+        A.pend_off = (int)b;
+        if (pending) b += 2 * BM_WORDS * sizeof(unsigned) + 4 * (size_t)k;
+        A.lds_per_wave = (int)((b + 15) & ~(size_t)15);
+    }
     A.vals = reinterpret_cast<float *>(ws + p->ws_vals);
     A.leafA = reinterpret_cast<double *>(ws + p->ws_leafA);
     A.payload = payload;

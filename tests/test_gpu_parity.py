@@ -151,6 +151,59 @@ def test_compress_is_deterministic_and_leaves_padding(sl, oracle):
     assert np.array_equal(e1[~inside].view(np.uint32), e0[~inside].view(np.uint32))
 
 
+# --------------------------------------------------------------------------- deferred residual
+@pytest.mark.parametrize("k", [8, 32, 64, 128, 512])
+def test_deferred_residual_chain_equals_eager(sl, oracle, k):
+    """Rounds chained with SL_COMPRESS_DEFER_RESIDUAL + `pending`: every payload equals the
+    oracle's, e minus the pending payload equals the oracle's e after every round
+    (checked through sl_residual_apply on a copy), and a final sl_residual_apply
+    leaves exactly the oracle's e."""
+    if k <= 256:
+        shapes = [(150, 210, TILE), (1, 9000, FLAT), (1024, 16, TILE), (128, 192, TILE), (1, 4096 + 1030, FLAT)]
+    else:
+        shapes = [(160, 224, TILE), (1024, 16, TILE), (1, 8192 + 1000, FLAT)]
+    descs, n = layout_list(shapes)
+    rng = np.random.default_rng(500 + k)
+    plan = sl.sl_plan_create(descs, k)
+    ws = sl.alloc_workspace(plan)
+    e_ref = rng.normal(0, 1e-3, n).astype(np.float32)
+    e = torch.from_numpy(e_ref.copy()).cuda()
+    pays = [sl.alloc_payload(plan), sl.alloc_payload(plan)]
+    pending = None
+    for rnd in range(4):
+        if rnd == 2:
+            delta_h = np.zeros(n, dtype=np.float32)          # a round with ties everywhere
+            delta_h[::7] = 1e-3
+        else:
+            delta_h = rng.normal(0, 1e-3, n).astype(np.float32)
+        out = pays[rnd % 2]
+        out.fill_(0xAB)
+        sl.sl_compress(plan, e, torch.from_numpy(delta_h).cuda(), 0.95, out, ws,
+                       flags=sl.SL_COMPRESS_DEFER_RESIDUAL, pending=pending)
+        torch.cuda.synchronize()
+        ref = oracle.compress(descs, k, e_ref, delta_h, 0.95)
+        assert np.array_equal(out[:plan.payload_bytes].cpu().numpy(), ref), f"payload round {rnd}"
+        e_chk = e.clone()
+        sl.sl_residual_apply(plan, e_chk, out)
+        torch.cuda.synchronize()
+        assert_f32_close(e_chk.cpu().numpy(), e_ref, f"e round {rnd}")
+        pending = out
+    sl.sl_residual_apply(plan, e, pending)
+    torch.cuda.synchronize()
+    assert_f32_close(e.cpu().numpy(), e_ref, "e after the final flush")
+    # an eager call may follow a deferred one: pending is consumed, nothing stays pending
+    e2 = torch.from_numpy(e_ref.copy()).cuda()
+    d1 = rng.normal(0, 1e-3, n).astype(np.float32)
+    d2 = rng.normal(0, 1e-3, n).astype(np.float32)
+    sl.sl_compress(plan, e2, torch.from_numpy(d1).cuda(), 0.95, pays[0], ws, flags=sl.SL_COMPRESS_DEFER_RESIDUAL)
+    sl.sl_compress(plan, e2, torch.from_numpy(d2).cuda(), 0.95, pays[1], ws, pending=pays[0])
+    torch.cuda.synchronize()
+    oracle.compress(descs, k, e_ref, d1, 0.95)
+    ref2 = oracle.compress(descs, k, e_ref, d2, 0.95)
+    assert np.array_equal(pays[1][:plan.payload_bytes].cpu().numpy(), ref2)
+    assert_f32_close(e2.cpu().numpy(), e_ref, "e after deferred then eager")
+
+
 # --------------------------------------------------------------------------- aggregate
 @pytest.mark.parametrize("R,k,lr", [(1, 32, 1.0), (3, 64, 0.7), (4, 64, 0.7), (8, 64, 1.0), (16, 32, 0.8),
                                      (5, 20, 0.6), (33, 128, 0.5)])
@@ -262,3 +315,9 @@ def test_argument_errors_are_reported_not_launched(sl):
         sl.sl_decompress_avg_apply(plan, theta, [pay] * 65, 1.0)  # R too large
     with pytest.raises(sl.SparseLoCoError):
         sl.sl_compress(plan, theta, theta, 0.95, pay, sl.alloc_workspace(plan))   # e aliases delta
+    d = torch.zeros_like(theta)
+    with pytest.raises(sl.SparseLoCoError):                       # pending is the output buffer
+        sl.sl_compress(plan, theta, d, 0.95, pay, sl.alloc_workspace(plan), pending=pay)
+    with pytest.raises(sl.SparseLoCoError):                       # frozen excludes a deferred residual
+        sl.sl_compress(plan, theta, d, 0.95, pay, sl.alloc_workspace(plan),
+                       flags=sl.SL_COMPRESS_EF_FROZEN | sl.SL_COMPRESS_DEFER_RESIDUAL)
