@@ -19,6 +19,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E peak
+PROFILE_TAGS = {4: "1p8B"}
 
 
 def cpu_baseline(w, sample_layers):
@@ -172,6 +173,17 @@ def main():
     torch.cuda.synchronize()
     copy_gbs = 5 * 8 * arena / (ev0.elapsed_time(ev1) * 1e-3) / 1e9
 
+    # HBM bytes per launch of the dominant kernel as measured with rocprofv3 counters
+    # (FETCH_SIZE + WRITE_SIZE, scaled by a plain copy; written by
+    # paper_2508_15706_amd/rocprof_summary.py from a profiled run of this same command)
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", f"traffic_config{w.config_id}_{PROFILE_TAGS.get(w.config_id, '')}.json")
+    if os.path.exists(tpath) and not args.flat and args.k is None:
+        tk = json.load(open(tpath))["kernels"]
+        name = next((n for n in tk if n.startswith("k_select")), None)
+        if name and tk[name]["fetch_bytes"] is not None and tk[name]["write_bytes"] is not None:
+            traffic = tk[name]["fetch_bytes"] + tk[name]["write_bytes"]
+
     out = {
         "metric": "pseudo-gradient elements compressed+aggregated/sec",
         "value": N / (ms_step * 1e-3) / 1e9,
@@ -185,7 +197,7 @@ def main():
                    "n_elements": N, "n_chunks": n_chunks, "k": w.k, "R": w.R},
         "roofline": {"bound": "hbm", "kernel": "k_select (EF accumulate + chunk Top-k)",
                      "achieved": sel_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": sel_gbs / HBM_PEAK_GBS, "traffic": None,
+                     "frac": sel_gbs / HBM_PEAK_GBS, "traffic": traffic,
                      "ms": sel_ms, "algorithmic_bytes": sel_bytes},
         "path_hbm": {"algorithmic_bytes_per_step": bytes_round,
                      "achieved_GBps": bytes_round / (ms_step * 1e-3) / 1e9,
