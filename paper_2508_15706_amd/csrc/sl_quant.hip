@@ -119,106 +119,147 @@ struct CodeArgs {
     unsigned char *payload;
     long long n_chunks;
     int k;
-    int lds_per_wave;
 };
 
-// One wave per chunk, several independent waves per workgroup.
-__global__ void __launch_bounds__(256) k_codes(CodeArgs A)
+struct BinStacks {       // one binary-counter stack of partial tree sums per bin
+    double a[13], b[13], c[13], d[13];
+};
+
+// Folds entry m (values v0..v3 for the four bins) into the stacks: while bit L
+// of m is set the partial sum of level L is the left sibling and is added; the
+// first clear bit is where the new partial sum is parked.
+template <int L>
+SL_DEV void stack_push(BinStacks &s, int m, double v0, double v1, double v2, double v3)
 {
-    extern __shared__ __align__(16) unsigned char smem_all[];
-    const int lane = threadIdx.x & 63, k = A.k;
-    const int wave = sl_uniform((int)(threadIdx.x >> 6));
-    const long long c = (long long)blockIdx.x * (blockDim.x >> 6) + wave;
-    if (c >= A.n_chunks) return;
-    unsigned char *smem = smem_all + (size_t)wave * A.lds_per_wave;
-    const SlChunkDesc d = A.desc[c];
-    const double mu = A.tstat[d.tensor].mu, T = A.tstat[d.tensor].T;
-    unsigned char *code_lds = smem;                                   // k bytes
-    double *scratch = reinterpret_cast<double *>(smem + ((k + 7) & ~7));
-    const float *x = A.vals + c * k;
-
-    int n_b[4] = {0, 0, 0, 0};
-    for (int s = 0; s * 64 < k; ++s) {
-        const int p = s * 64 + lane;
-        int code = -1;
-        if (p < k) {
-            const double d = (double)x[p] - mu;
-            const double dd = d * d;
-            code = d < 0.0 ? (dd > T ? 0 : 1) : (dd >= T ? 3 : 2);
-            code_lds[p] = (unsigned char)code;
-        }
-#pragma unroll
-        for (int b = 0; b < 4; ++b) n_b[b] += sl_popc(sl_ballot(code == b));
-    }
-    sl_wave_sync();
-
-    // codes, four per byte, entry m in bits 2*(m mod 4)
-    unsigned char *rec = A.payload + d.rec_off + 3 * k / 2;
-    if ((k & 15) == 0) {
-        unsigned *rw = reinterpret_cast<unsigned *>(rec);
-        for (int w = lane; w < k / 16; w += 64) {
-            unsigned word = 0;
-#pragma unroll
-            for (int q = 0; q < 16; ++q) word |= (unsigned)code_lds[16 * w + q] << (2 * q);
-            rw[w] = word;
-        }
-    } else {
-        for (int b = lane; b < k / 4; b += 64) {
-            unsigned v = 0;
-#pragma unroll
-            for (int q = 0; q < 4; ++q) v |= (unsigned)code_lds[4 * b + q] << (2 * q);
-            rec[b] = (unsigned char)v;
-        }
-    }
-
-#pragma unroll
-    for (int b = 0; b < 4; ++b) {
-        const double sb = sl_chunk_tree(k, lane, scratch, [&](int s) {
-            const int p = s * 64 + lane;
-            return (p < k && code_lds[p] == b) ? (double)x[p] : 0.0;
-        });
-        if (lane == 0) {
-            A.leafC[b * A.n_chunks + c] = sb;
-            A.cnt[b * A.n_chunks + c] = (unsigned)n_b[b];
+    if constexpr (L < 13) {
+        if ((m >> L) & 1) {
+            stack_push<L + 1>(s, m, s.a[L] + v0, s.b[L] + v1, s.c[L] + v2, s.d[L] + v3);
+        } else {
+            s.a[L] = v0, s.b[L] = v1, s.c[L] = v2, s.d[L] = v3;
         }
     }
 }
 
+constexpr int CODE_WAVES = 2;        // waves per workgroup
+constexpr int CODE_PITCH = 65;       // LDS row pitch in floats: conflict-free column reads
+
+// One LANE per chunk, 64 consecutive chunks per wave.  The selected values of
+// the 64 chunks are read with coalesced 16-byte loads, 64 entries per chunk at a
+// time, and transposed through LDS so that every lane walks its own chunk's
+// values in ascending index.  A lane then needs no cross-lane traffic at all:
+// the code is two fp64 compares, and the per-bin fixed-tree sums are kept in a
+// binary-counter stack (entry m is folded into the partial sums of the aligned
+// subtrees that end at m, which reproduces the adjacent-pair tree exactly).
+// The entry index is uniform over the wave, so the stack walk is scalar control flow.
+__global__ void __launch_bounds__(64 * CODE_WAVES, 2) k_codes(CodeArgs A)
+{
+    __shared__ float tile_all[CODE_WAVES][64 * CODE_PITCH];
+    const int lane = threadIdx.x & 63, k = A.k;
+    const int wave = sl_uniform((int)(threadIdx.x >> 6));
+    const long long c0 = ((long long)blockIdx.x * CODE_WAVES + wave) * 64;
+    if (c0 >= A.n_chunks) return;
+    float *tile = tile_all[wave];
+    const long long c = c0 + lane;
+    const bool live = c < A.n_chunks;
+
+    double mu = 0.0, T = 0.0;
+    unsigned char *codes_out = nullptr;
+    if (live) {
+        const SlChunkDesc d = A.desc[c];
+        mu = A.tstat[d.tensor].mu;
+        T = A.tstat[d.tensor].T;
+        codes_out = A.payload + d.rec_off + 3 * k / 2;
+    }
+
+    BinStacks st;
+#pragma unroll
+    for (int l = 0; l < 13; ++l) st.a[l] = st.b[l] = st.c[l] = st.d[l] = 0.0;
+    unsigned n_b[4] = {0u, 0u, 0u, 0u};
+    unsigned word = 0;
+
+    const int lr = lane >> 4, lc = (lane & 15) * 4;
+    for (int s0 = 0; s0 < k; s0 += 64) {
+        const int ncol = min(64, k - s0);          // multiple of 4
+        sl_wave_sync();
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            const int row = 4 * i + lr;
+            if (c0 + row < A.n_chunks && lc < ncol) {
+                const float4 v = *reinterpret_cast<const float4 *>(A.vals + (c0 + row) * k + s0 + lc);
+                float *t = tile + row * CODE_PITCH + lc;
+                t[0] = v.x, t[1] = v.y, t[2] = v.z, t[3] = v.w;
+            }
+        }
+        sl_wave_sync();
+        for (int col = 0; col < ncol; ++col) {
+            const int m = s0 + col;
+            const float xf = tile[lane * CODE_PITCH + col];
+            const double x = (double)xf;
+            const double dlt = x - mu;
+            const double dd = dlt * dlt;
+            const int code = dlt < 0.0 ? (dd > T ? 0 : 1) : (dd >= T ? 3 : 2);
+            n_b[0] += code == 0, n_b[1] += code == 1, n_b[2] += code == 2, n_b[3] += code == 3;
+            stack_push<0>(st, m, code == 0 ? x : 0.0, code == 1 ? x : 0.0, code == 2 ? x : 0.0, code == 3 ? x : 0.0);
+            word |= (unsigned)code << (2 * (m & 15));
+            if ((k & 15) == 0) {
+                if ((m & 15) == 15) {
+                    if (live) reinterpret_cast<unsigned *>(codes_out)[m >> 4] = word;
+                    word = 0;
+                }
+            } else if ((m & 3) == 3) {
+                if (live) codes_out[m >> 2] = (unsigned char)(word >> (2 * (m & 12)));
+                if ((m & 15) == 15) word = 0;
+            }
+        }
+    }
+    // pad with +0.0 up to the next power of two; the root is then at level log2(P)
+    int P = 1, top = 0;
+    while (P < k) P <<= 1, ++top;
+    for (int m = k; m < P; ++m) stack_push<0>(st, m, 0.0, 0.0, 0.0, 0.0);
+    if (live) {
+        double r0 = st.a[0], r1 = st.b[0], r2 = st.c[0], r3 = st.d[0];
+#pragma unroll
+        for (int l = 1; l < 13; ++l)
+            if (top == l) r0 = st.a[l], r1 = st.b[l], r2 = st.c[l], r3 = st.d[l];
+        A.leafC[0 * A.n_chunks + c] = r0;
+        A.leafC[1 * A.n_chunks + c] = r1;
+        A.leafC[2 * A.n_chunks + c] = r2;
+        A.leafC[3 * A.n_chunks + c] = r3;
+#pragma unroll
+        for (int b = 0; b < 4; ++b) A.cnt[b * A.n_chunks + c] = n_b[b];
+    }
+}
+
 // ------------------------------------------------------------------ kernel D
+// One workgroup per (tensor, bin): fixed-tree sum of the bin's leaves, integer
+// count, centroid -> LUT[b] in the tensor block's header.
 __global__ void __launch_bounds__(RED_THREADS)
 k_tensor_lut(const SlTensorDev *tensors, const double *leafC, const unsigned *cnt,
-             long long n_chunks_total, int k, SlTensorStat *tstat, unsigned char *payload)
+             long long n_chunks_total, int k, unsigned char *payload)
 {
     __shared__ RedShared sh;
     const SlTensorDev td = tensors[blockIdx.x];
+    const int b = blockIdx.y;
     const int tid = threadIdx.x;
-    if (tid < 4) sh.cnt[tid] = 0ull;
+    if (tid == 0) sh.cnt[0] = 0ull;
     __syncthreads();
-    for (int b = 0; b < 4; ++b) {
-        unsigned long long part = 0;
-        for (long long i = tid; i < td.n_chunks; i += RED_THREADS)
-            part += cnt[b * n_chunks_total + td.chunk0 + i];
+    unsigned long long part = 0;
+    for (long long i = tid; i < td.n_chunks; i += RED_THREADS)
+        part += cnt[b * n_chunks_total + td.chunk0 + i];
 #pragma unroll
-        for (int s = 32; s >= 1; s >>= 1) part += __shfl_xor(part, s);
-        if ((tid & 63) == 0 && part) atomicAdd(&sh.cnt[b], part);   // integer: order-free
-    }
+    for (int s = 32; s >= 1; s >>= 1) part += __shfl_xor(part, s);
+    if ((tid & 63) == 0 && part) atomicAdd(&sh.cnt[0], part);   // integer: order-free
     __syncthreads();
-    float lut[4];
-    for (int b = 0; b < 4; ++b) {
-        const double Sb = block_tree_sum(leafC + b * n_chunks_total + td.chunk0, td.n_chunks, sh);
-        const unsigned long long nb = sh.cnt[b];
+    const double Sb = block_tree_sum(leafC + b * n_chunks_total + td.chunk0, td.n_chunks, sh);
+    if (tid == 0) {
+        const unsigned long long nb = sh.cnt[0];
         float cen = nb ? (float)(Sb / (double)nb) : 0.0f;
         if (cen == 0.0f) cen = 0.0f;        // never -0.0f on the wire
-        lut[b] = cen;
-    }
-    if (tid == 0) {
-#pragma unroll
-        for (int b = 0; b < 4; ++b) tstat[blockIdx.x].lut[b] = lut[b];
-        *reinterpret_cast<float4 *>(payload + td.pay_off) = make_float4(lut[0], lut[1], lut[2], lut[3]);
+        reinterpret_cast<float *>(payload + td.pay_off)[b] = cen;
     }
     // zero the padding that rounds the tensor block up to 16 bytes
     const long long used = 16 + td.n_chunks * ((long long)7 * k / 4);
-    if (tid < td.block_bytes - used) payload[td.pay_off + used + tid] = 0;
+    if (b == 0 && tid < td.block_bytes - used) payload[td.pay_off + used + tid] = 0;
 }
 
 // ------------------------------------------------------------------ kernel E
@@ -314,15 +355,14 @@ int slk_quantize(const sl_plan *p, float *e, int skip_residual, unsigned char *p
     C.payload = payload;
     C.n_chunks = p->n_chunks;
     C.k = k;
-    C.lds_per_wave = ((k + 15) & ~15) + 64 * (int)sizeof(double);
-    const int wpb = 4;
-    const unsigned nblk = (unsigned)((p->n_chunks + wpb - 1) / wpb);
-    hipLaunchKernelGGL(k_codes, dim3(nblk), dim3(64 * wpb), (size_t)C.lds_per_wave * wpb, st, C);
+    const long long per_block = 64ll * CODE_WAVES;
+    const unsigned nblk = (unsigned)((p->n_chunks + per_block - 1) / per_block);
+    hipLaunchKernelGGL(k_codes, dim3(nblk), dim3(64 * CODE_WAVES), 0, st, C);
     if ((rc = check_launch())) return rc;
     sl_prof_mark(p, SL_PROF_CODES, st);
 
-    hipLaunchKernelGGL(k_tensor_lut, dim3(p->n_tensors), dim3(RED_THREADS), 0, st, p->d_tensors,
-                       leafC, cnt, (long long)p->n_chunks, k, tstat, payload);
+    hipLaunchKernelGGL(k_tensor_lut, dim3(p->n_tensors, 4), dim3(RED_THREADS), 0, st, p->d_tensors,
+                       leafC, cnt, (long long)p->n_chunks, k, payload);
     if ((rc = check_launch())) return rc;
     sl_prof_mark(p, SL_PROF_LUT, st);
 
