@@ -1,0 +1,168 @@
+"""GPU parity at the benchmark configurations' full sizes (configurations 2-5), in the
+launch configuration bench.py times.
+
+The GPU always processes the whole tensor list.  The oracle checks
+  - worker 0, round 1: the WHOLE list (every payload byte, every element of e);
+  - every other worker and every later round: a sample of whole tensors (a tensor's
+    LUT depends on all its chunks, so the unit that can be checked on its own is a
+    tensor), carried across rounds with the oracle's own error buffers;
+  - the aggregation on the same sample, fed with the ORACLE's payloads.
+Worker 0 runs the deferred-residual chain (its e is compared after a final
+sl_residual_apply), the other workers the eager mode.
+"""
+import numpy as np
+import pytest
+import torch
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def sl():
+    from paper_2508_15706_amd import binding
+    binding.lib()
+    assert torch.cuda.is_available()
+    return binding
+
+
+def bits(x):
+    return np.asarray(x).view(np.uint32)
+
+
+class SubList:
+    """Some whole tensors of a workload, re-based into a compact host arena."""
+
+    def __init__(self, w, names=None):
+        self.index = [i for i, s in enumerate(w.specs) if names is None or s.name in names]
+        assert self.index, "empty sample"
+        self.specs = [w.specs[i] for i in self.index]
+        self.descs, off = [], 0
+        for s in self.specs:
+            self.descs.append((s.rows, s.cols, off, s.layout))
+            off += (s.numel + 63) // 64 * 64
+        self.n = off
+
+    def gather(self, dev):
+        out = np.zeros(self.n, dtype=np.float32)
+        for s, d in zip(self.specs, self.descs):
+            out[d[2]:d[2] + s.numel] = dev[s.offset:s.offset + s.numel].cpu().numpy()
+        return out
+
+    def compare_payload(self, oracle, plan, pay_dev, ref, k, what):
+        roff = 0
+        for i, d in zip(self.index, self.descs):
+            nb = oracle.tensor_block_bytes(d, k)
+            goff = plan.tensor_offset(i)
+            got = pay_dev[goff:goff + nb].cpu().numpy()
+            if not np.array_equal(got, ref[roff:roff + nb]):
+                diff = np.nonzero(got != ref[roff:roff + nb])[0]
+                raise AssertionError(f"{what}: payload of tensor {i} differs at {diff.size} of {nb} bytes, "
+                                     f"first at {diff[:6]}")
+            roff += nb
+        assert roff == ref.size
+
+    def compare_values(self, dev, ref, what):
+        got = self.gather(dev)
+        if not np.array_equal(bits(got), bits(ref)):
+            denom = np.maximum(np.abs(ref), 1e-30)
+            rel = np.abs(got.astype(np.float64) - ref.astype(np.float64)) / denom
+            bad = int((bits(got) != bits(ref)).sum())
+            assert rel.max() <= 1e-6, f"{what}: {bad} values differ, max rel err {rel.max():.3e}"
+
+
+def run_config(sl, oracle, config_id, k, rounds, sample_names, full_first=True):
+    from paper_2508_15706_amd import synth
+    w = synth.workload(config_id, k=k)
+    dev = torch.device("cuda:0")
+    descs = [s.desc() for s in w.specs]
+    plan = sl.sl_plan_create(descs, w.k)
+    assert plan.num_elements == w.N
+    ws = sl.alloc_workspace(plan)
+    sample = SubList(w, sample_names)
+    delta = torch.empty(w.arena, dtype=torch.float32, device=dev)
+    theta = torch.empty(w.arena, dtype=torch.float32, device=dev)
+    synth.fill_theta(w, theta)
+    theta_ref = sample.gather(theta)
+    e_dev = [torch.zeros(w.arena, dtype=torch.float32, device=dev) for _ in range(w.R)]
+    e_ref = [np.zeros(sample.n, dtype=np.float32) for _ in range(w.R)]
+    pays = [sl.alloc_payload(plan) for _ in range(w.R)]
+    own = [pays[0], sl.alloc_payload(plan)]          # worker 0 alternates (deferred chain)
+    pending = None
+
+    for rnd in range(1, rounds + 1):
+        ref_pays = []
+        cur = []
+        for r in range(w.R):
+            synth.fill_delta(w, delta, rnd, r)
+            if r == 0:
+                out = own[rnd % 2]
+                sl.sl_compress(plan, e_dev[0], delta, w.beta, out, ws,
+                               flags=sl.SL_COMPRESS_DEFER_RESIDUAL, pending=pending)
+                pending = out
+            else:
+                out = pays[r]
+                sl.sl_compress(plan, e_dev[r], delta, w.beta, out, ws)
+            torch.cuda.synchronize()
+            cur.append(out)
+            if r == 0 and rnd == 1 and full_first:
+                # the whole list against the oracle (e starts at zero for everybody)
+                full = SubList(w, None)
+                e_full = np.zeros(full.n, dtype=np.float32)
+                ref_full = oracle.compress(full.descs, w.k, e_full, full.gather(delta), w.beta)
+                full.compare_payload(oracle, plan, out, ref_full, w.k, f"cfg{config_id} full list")
+                chk = e_dev[0].clone()
+                sl.sl_residual_apply(plan, chk, out)
+                torch.cuda.synchronize()
+                full.compare_values(chk, e_full, f"cfg{config_id} full-list e")
+                del chk, e_full, ref_full, full
+            ref = oracle.compress(sample.descs, w.k, e_ref[r], sample.gather(delta), w.beta)
+            sample.compare_payload(oracle, plan, out, ref, w.k, f"cfg{config_id} round {rnd} worker {r}")
+            if r > 0:
+                sample.compare_values(e_dev[r], e_ref[r], f"cfg{config_id} round {rnd} worker {r} e")
+            ref_pays.append(ref)
+        sl.sl_decompress_avg_apply(plan, theta, cur, w.lr)
+        torch.cuda.synchronize()
+        oracle.decompress_avg_apply(sample.descs, w.k, theta_ref, ref_pays, w.lr)
+        sample.compare_values(theta, theta_ref, f"cfg{config_id} round {rnd} theta")
+    sl.sl_residual_apply(plan, e_dev[0], pending)
+    torch.cuda.synchronize()
+    sample.compare_values(e_dev[0], e_ref[0], f"cfg{config_id} worker 0 e after the deferred chain")
+    plan.close()
+
+
+@pytest.mark.timeout(600)
+def test_config2_190M_full_list_all_workers(sl, oracle):
+    """Configuration 2: every tensor, all 8 workers, payloads, e and theta."""
+    run_config(sl, oracle, 2, None, 1, None, full_first=False)
+
+
+@pytest.mark.timeout(600)
+@pytest.mark.parametrize("k", [32, 128])
+def test_config3_510M_k_sweep_full_list(sl, oracle, k):
+    """Configuration 3 (heavy-tailed mixture), k = 32 and 128: whole list for worker 0,
+    sample for the others."""
+    run_config(sl, oracle, 3, k, 1, {"l0.q", "l3.gate", "l7.norm1", "l23.down", "final_norm"})
+
+
+@pytest.mark.timeout(900)
+def test_config3_510M_five_rounds(sl, oracle):
+    """Configuration 3, k = 64: five consecutive rounds carrying the error buffers."""
+    run_config(sl, oracle, 3, 64, 5, {"l0.q", "l3.gate", "l7.norm1", "l23.down", "final_norm"})
+
+
+@pytest.mark.timeout(900)
+def test_config4_1p8B_three_rounds(sl, oracle):
+    """Configuration 4 (the benchmark workload): whole list for worker 0 in round 1,
+    then three rounds on a sample that includes the ragged-edge head."""
+    run_config(sl, oracle, 4, None, 3, {"l0.q", "l0.norm1", "l11.down", "l23.up", "final_norm", "head"})
+
+
+@pytest.mark.timeout(900)
+def test_config5_moe_full_list(sl, oracle):
+    """Configuration 5 (MoE, R = 16, k = 32): whole list for worker 0; the sample holds a
+    router (16-column tiles), experts with zero pseudo-gradient (all ties) and live ones."""
+    from paper_2508_15706_amd import synth
+    w = synth.workload(5)
+    names = {"l0.router", "l0.q", "l5.norm2", "final_norm"}
+    names |= {s.name for s in w.specs if s.kind == "expert" and s.name.startswith(("l0.x", "l7.x1"))}
+    run_config(sl, oracle, 5, None, 1, names)
