@@ -46,7 +46,34 @@ __global__ void __launch_bounds__(256) k_apply(ApplyArgs A)
     const unsigned stride = (unsigned)d.stride;
     const bool full = d.flags & SLC_FULL;
 
-    // theta loads are issued first so that their latency overlaps the decode
+    // Word w of a batch's staging area: worker r = w / wpr_src, word q of (LUT[4], record)
+    const bool word_path = (rec_bytes & 3) == 0;
+    const int wpr_src = 4 + (rec_bytes >> 2);          // words per worker: LUT + record
+    const int wpr_dst = rec_pad >> 2;
+    auto src_word = [&](int r, int q) -> unsigned {
+        const unsigned char *p = A.payload[r];
+        return q < 4 ? reinterpret_cast<const unsigned *>(p + lut_off)[q]
+                     : reinterpret_cast<const unsigned *>(p + rec_off)[q - 4];
+    };
+    // The first 256 words of the first batch (all of it for R*7k/4 <= ~900 bytes) are
+    // fetched into registers BEFORE the theta loads: loads complete in order, so
+    // the decode below then waits for these few words only and runs while the
+    // chunk's 16 KB of theta are still in flight.
+    constexpr int PF = 4;
+    unsigned pf[PF];
+    const int nb0 = min(A.batch, A.R);
+    if (word_path) {
+#pragma unroll
+        for (int u = 0; u < PF; ++u) {
+            const int w = lane + 64 * u;
+            pf[u] = 0;
+            if (w < nb0 * wpr_src) {
+                const int r = w / wpr_src;
+                pf[u] = src_word(r, w - r * wpr_src);
+            }
+        }
+    }
+
     sl_f4 th[16];
     if (full) {
         const unsigned o0 = 4u * (lr * stride + lc), step = 16u * stride;
@@ -61,19 +88,29 @@ __global__ void __launch_bounds__(256) k_apply(ApplyArgs A)
     for (int r0 = 0; r0 < A.R; r0 += A.batch) {
         const int nb = min(A.batch, A.R - r0);
         sl_wave_sync();
-        for (int w = lane; w < nb * 4; w += 64) {                    // the tensor's LUT of each worker
-            const int r = w >> 2, q = w & 3;
-            reinterpret_cast<unsigned *>(stage)[r * (rec_pad >> 2) + q] =
-                reinterpret_cast<const unsigned *>(A.payload[r0 + r] + lut_off)[q];
-        }
-        if ((rec_bytes & 3) == 0) {
-            const int words = rec_bytes >> 2;
-            for (int w = lane; w < nb * words; w += 64) {
-                const int r = w / words, q = w - r * words;
-                reinterpret_cast<unsigned *>(stage)[r * (rec_pad >> 2) + 4 + q] =
-                    reinterpret_cast<const unsigned *>(A.payload[r0 + r] + rec_off)[q];
+        if (word_path) {
+            int w0 = lane;
+            if (r0 == 0) {
+#pragma unroll
+                for (int u = 0; u < PF; ++u) {
+                    const int w = lane + 64 * u;
+                    if (w < nb * wpr_src) {
+                        const int r = w / wpr_src;
+                        reinterpret_cast<unsigned *>(stage)[r * wpr_dst + (w - r * wpr_src)] = pf[u];
+                    }
+                }
+                w0 = lane + 64 * PF;
+            }
+            for (int w = w0; w < nb * wpr_src; w += 64) {
+                const int r = w / wpr_src, q = w - r * wpr_src;
+                reinterpret_cast<unsigned *>(stage)[r * wpr_dst + q] = src_word(r0 + r, q);
             }
         } else {
+            for (int w = lane; w < nb * 4; w += 64) {                // the tensor's LUT of each worker
+                const int r = w >> 2, q = w & 3;
+                reinterpret_cast<unsigned *>(stage)[r * wpr_dst + q] =
+                    reinterpret_cast<const unsigned *>(A.payload[r0 + r] + lut_off)[q];
+            }
             for (int b = lane; b < nb * rec_bytes; b += 64) {
                 const int r = b / rec_bytes, q = b - r * rec_bytes;
                 stage[r * rec_pad + 16 + q] = A.payload[r0 + r][rec_off + q];
