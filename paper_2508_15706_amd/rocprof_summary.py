@@ -65,10 +65,30 @@ def read_stats(d):
     return out
 
 
+def read_last_calls(d, last_n):
+    """Mean duration (us) of the last `last_n` dispatches of each kernel: the timed
+    steps of bench.py come last, after set-up and the other residual mode."""
+    path = _find(os.path.join(d, "trace"), "*kernel_trace.csv")
+    durs = collections.defaultdict(list)
+    if not path:
+        return {}
+    for r in csv.DictReader(open(path)):
+        s = short_name(r["Kernel_Name"])
+        if s:
+            durs[s].append((int(r["Start_Timestamp"]), (int(r["End_Timestamp"]) - int(r["Start_Timestamp"])) / 1e3))
+    out = {}
+    for k, v in durs.items():
+        v.sort()
+        tail = [x[1] for x in v[-last_n:]]
+        out[k] = sum(tail) / len(tail)
+    return out
+
+
 def summarize(d, arena_bytes):
     fetch = read_counter(d, "fetch", "FETCH_SIZE")
     write = read_counter(d, "write", "WRITE_SIZE")
     stats = read_stats(d)
+    last = read_last_calls(d, int(os.environ.get("SL_LAST_N", "8")))
     known_kib = arena_bytes / 1024.0
     # the largest copies are the whole-arena ones
     f_copy = max(fetch.get(COPY_KERNEL, [0.0]) or [0.0])
@@ -86,6 +106,7 @@ def summarize(d, arena_bytes):
             "avg_us": stats.get(k, (0, 0, 0, 0))[1] / 1e3,
             "min_us": stats.get(k, (0, 0, 0, 0))[2] / 1e3,
             "max_us": stats.get(k, (0, 0, 0, 0))[3] / 1e3,
+            "timed_us": last.get(k),
             "fetch_bytes": None if f is None else f * 1024.0 * f_scale,
             "write_bytes": None if w is None else w * 1024.0 * w_scale,
         }
@@ -105,12 +126,15 @@ def render(summary, bench_args, title):
              f"{s['copy_known_KiB']:.0f} KiB read and written) reads FETCH_SIZE = {s['copy_fetch_KiB']:.1f} KiB "
              f"(scale {s['fetch_scale']:.4f}) and WRITE_SIZE = {s['copy_write_KiB']:.1f} KiB "
              f"(scale {s['write_scale']:.4f}).", "",
-             "| kernel | calls | avg us | min us | max us | HBM read / launch (GB) | HBM write / launch (GB) |",
-             "|---|---|---|---|---|---|---|"]
+             "`timed us` = mean over the last dispatches of the kernel, i.e. the timed steps of the bench "
+             "(the earlier calls are set-up from e = 0 and the other residual mode).", "",
+             "| kernel | calls | avg us | min us | max us | timed us | HBM read / launch (GB) | HBM write / launch (GB) |",
+             "|---|---|---|---|---|---|---|---|"]
     for k, v in s["kernels"].items():
         fb = "-" if v["fetch_bytes"] is None else f"{v['fetch_bytes'] / 1e9:.4f}"
         wb = "-" if v["write_bytes"] is None else f"{v['write_bytes'] / 1e9:.4f}"
-        lines.append(f"| {k} | {v['calls']} | {v['avg_us']:.1f} | {v['min_us']:.1f} | {v['max_us']:.1f} | {fb} | {wb} |")
+        tu = "-" if v.get("timed_us") is None else f"{v['timed_us']:.1f}"
+        lines.append(f"| {k} | {v['calls']} | {v['avg_us']:.1f} | {v['min_us']:.1f} | {v['max_us']:.1f} | {tu} | {fb} | {wb} |")
     lines.append("")
     return "\n".join(lines)
 
@@ -126,7 +150,8 @@ def main(argv):
     with open(out_md, "w") as f:
         f.write(render(summary, bench_args, title))
     if len(argv) > 4:
-        traffic = {k: {"fetch_bytes": v["fetch_bytes"], "write_bytes": v["write_bytes"], "avg_us": v["avg_us"]}
+        traffic = {k: {"fetch_bytes": v["fetch_bytes"], "write_bytes": v["write_bytes"], "avg_us": v["avg_us"],
+                       "timed_us": v.get("timed_us")}
                    for k, v in summary["kernels"].items()}
         with open(argv[4], "w") as f:
             json.dump({"bench_args": bench_args, "fetch_scale": summary["fetch_scale"],
