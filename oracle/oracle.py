@@ -79,6 +79,14 @@ def lib():
         L.slo_decompress_avg_apply.argtypes = [tp, i32, i32, i32, vp, vp, i32, C.c_float]
         L.slo_decompress_dense.restype = i32
         L.slo_decompress_dense.argtypes = [tp, i32, i32, i32, vp, vp]
+        L.slo_rice_param.restype = i32
+        L.slo_rice_param.argtypes = [i32]
+        L.slo_rice_max_bytes.restype = i64
+        L.slo_rice_max_bytes.argtypes = [tp, i32, i32, i32]
+        L.slo_rice_encode.restype = i64
+        L.slo_rice_encode.argtypes = [tp, i32, i32, i32, vp, vp, i64]
+        L.slo_rice_decode.restype = i32
+        L.slo_rice_decode.argtypes = [tp, i32, i32, i32, vp, vp]
         L.slo_max_threads.restype = i32
         L.slo_max_threads.argtypes = []
         _lib = L
@@ -245,3 +253,34 @@ def decompress_dense(descs, k, payload, n_elems, tile=64):
 
 def max_threads():
     return int(lib().slo_max_threads())
+
+
+def rice_param(k):
+    return int(lib().slo_rice_param(k))
+
+
+def rice_max_bytes(descs, k, tile=64):
+    arr, n = make_tensors(descs)
+    return int(lib().slo_rice_max_bytes(arr, n, tile, k))
+
+
+def rice_encode(descs, k, payload, tile=64):
+    """Plain-format payload -> coded buffer (trimmed to its size)."""
+    arr, n = make_tensors(descs)
+    _check(payload, np.uint8)
+    cap = int(lib().slo_rice_max_bytes(arr, n, tile, k))
+    out = np.zeros(cap, dtype=np.uint8)
+    size = int(lib().slo_rice_encode(arr, n, tile, k, _ptr(payload), _ptr(out), cap))
+    if size < 0:
+        raise ValueError(f"slo_rice_encode: status {size}")
+    return out[:size].copy()
+
+
+def rice_decode(descs, k, coded, tile=64):
+    arr, n = make_tensors(descs)
+    _check(coded, np.uint8)
+    out = np.full(int(lib().slo_payload_bytes(arr, n, tile, k)), 0xEE, dtype=np.uint8)
+    st = lib().slo_rice_decode(arr, n, tile, k, _ptr(coded), _ptr(out))
+    if st:
+        raise ValueError(f"slo_rice_decode: status {st}")
+    return out
