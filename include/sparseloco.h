@@ -152,6 +152,26 @@ int sl_decompress_avg_apply(sl_plan *plan, float *theta, const void *const *payl
 int sl_pack_indices(const uint16_t *idx, const uint8_t *codes, int64_t n_chunks, int k, void *out,
                     void *stream);
 
+/* Index coder (appendix "Compression of indices in Top-k": the indices of a
+ * payload are compressed for transmission with sub-chunking and Rice coding;
+ * the paper gives the rates it reaches - 8.9 / 6.6 / 5.6 bits per index for
+ * k = 32 / 128 / 256 - but not the algorithm, so the coded format is this
+ * library's own and is described in csrc/sl_rice.hip).  Lossless both ways.
+ *
+ * sl_rice_encode: payload (plain wire format, device) -> coded buffer `out`
+ *   (device, 16-byte aligned, capacity >= sl_rice_max_bytes(), else
+ *   INVALID_ARG).  When the stream work has completed, bytes 8..15 of `out`
+ *   hold the coded size as a little-endian uint64; only that many bytes need to
+ *   travel.  `workspace`: device, sl_workspace_bytes() bytes, 256-byte aligned.
+ * sl_rice_decode: coded buffer `in` of `in_bytes` bytes (device, 16-byte
+ *   aligned) -> payload in the plain wire format, every byte written.  Reads
+ *   never leave [in, in + in_bytes); malformed input gives indices clamped to
+ *   4095, never a fault. */
+size_t sl_rice_max_bytes(const sl_plan *plan);
+int sl_rice_encode(sl_plan *plan, const void *payload, void *out, size_t out_capacity,
+                   void *workspace, void *stream);
+int sl_rice_decode(sl_plan *plan, const void *in, size_t in_bytes, void *payload, void *stream);
+
 /* Per-kernel timing for benchmarks.  Between sl_profile_begin and
  * sl_profile_end every sl_compress / sl_decompress_avg_apply call on the plan
  * records HIP events on its stream around each of its kernels (no

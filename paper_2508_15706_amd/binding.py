@@ -28,6 +28,7 @@ EXPORTS = [
     "sl_payload_bytes", "sl_payload_tensor_offset", "sl_workspace_bytes", "sl_compress",
     "sl_decompress_avg_apply", "sl_pack_indices", "sl_strerror", "sl_last_hip_error",
     "sl_profile_begin", "sl_profile_end", "sl_residual_apply",
+    "sl_rice_max_bytes", "sl_rice_encode", "sl_rice_decode",
 ]
 PROF_PHASES = ["select", "stats", "codes", "lut", "residual", "apply"]
 
@@ -80,6 +81,12 @@ def lib():
         L.sl_decompress_avg_apply.argtypes = [vp, vp, C.POINTER(vp), i32, C.c_float, vp]
         L.sl_pack_indices.restype = i32
         L.sl_pack_indices.argtypes = [vp, vp, i64, i32, vp, vp]
+        L.sl_rice_max_bytes.restype = sz
+        L.sl_rice_max_bytes.argtypes = [vp]
+        L.sl_rice_encode.restype = i32
+        L.sl_rice_encode.argtypes = [vp, vp, vp, sz, vp, vp]
+        L.sl_rice_decode.restype = i32
+        L.sl_rice_decode.argtypes = [vp, vp, sz, vp, vp]
         L.sl_profile_begin.restype = i32
         L.sl_profile_begin.argtypes = [vp, i32]
         L.sl_profile_end.restype = i32
@@ -218,3 +225,24 @@ def sl_profile_end(plan: Plan) -> dict:
     if st:
         raise SparseLoCoError("sl_profile_end", st)
     return {name: (ms[i], calls[i]) for i, name in enumerate(PROF_PHASES)}
+
+
+def sl_rice_max_bytes(plan: Plan) -> int:
+    return int(lib().sl_rice_max_bytes(plan.handle))
+
+
+def sl_rice_encode(plan: Plan, payload: torch.Tensor, out: torch.Tensor, workspace: torch.Tensor,
+                   stream=None) -> None:
+    """The coded size is in out[8:16] (little-endian uint64) once the stream work is done."""
+    st = lib().sl_rice_encode(plan.handle, _dev_ptr(payload, torch.uint8), _dev_ptr(out, torch.uint8),
+                              out.numel(), _dev_ptr(workspace, torch.uint8), _stream_ptr(stream))
+    if st:
+        raise SparseLoCoError("sl_rice_encode", st)
+
+
+def sl_rice_decode(plan: Plan, coded: torch.Tensor, in_bytes: int, payload: torch.Tensor,
+                   stream=None) -> None:
+    st = lib().sl_rice_decode(plan.handle, _dev_ptr(coded, torch.uint8), int(in_bytes),
+                              _dev_ptr(payload, torch.uint8), _stream_ptr(stream))
+    if st:
+        raise SparseLoCoError("sl_rice_decode", st)

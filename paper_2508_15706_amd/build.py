@@ -9,7 +9,7 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libsparseloco.so")
-SOURCES = ["sl_api.hip", "sl_select.hip", "sl_quant.hip", "sl_apply.hip"]
+SOURCES = ["sl_api.hip", "sl_select.hip", "sl_quant.hip", "sl_apply.hip", "sl_rice.hip"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",

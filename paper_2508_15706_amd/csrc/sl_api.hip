@@ -53,6 +53,7 @@ int sl_plan_create(const sl_tensor *tensors, int n_tensors, int k, sl_plan **out
     const int64_t rec = (int64_t)7 * k / 4;
     std::vector<SlChunkDesc> desc;
     std::vector<SlTensorDev> tdev((size_t)n_tensors);
+    std::vector<SlGroup> groups;
     int64_t n_elements = 0, n_partial = 0;
     size_t pay = 0;
 
@@ -119,6 +120,8 @@ int sl_plan_create(const sl_tensor *tensors, int n_tensors, int k, sl_plan **out
             D.n_chunks = (long long)desc.size() - D.chunk0;
             D.pay_off = (long long)pay;
             D.block_bytes = (long long)align_up((size_t)(16 + D.n_chunks * rec), 16);
+            D.group0 = (long long)groups.size();
+            for (long long g = 0; g * SL_RICE_GROUP < D.n_chunks; ++g) groups.push_back(SlGroup{t, (int)g});
             pay += (size_t)D.block_bytes;
             n_elements += T.rows * T.cols;
         }
@@ -145,6 +148,20 @@ int sl_plan_create(const sl_tensor *tensors, int n_tensors, int k, sl_plan **out
     p->ws_cnt = off;    off = align_up(off + (size_t)p->n_chunks * 4 * sizeof(unsigned), 256);
     p->ws_tstat = off;  off = align_up(off + (size_t)n_tensors * sizeof(SlTensorStat), 256);
     p->ws_bytes = off ? off : 256;
+    p->n_groups = (int64_t)groups.size();
+    {
+        // upper bound of a coded payload (see sl_rice_encode) and the scratch its encoder needs
+        const int b = sl_rice_param(k);
+        const size_t chunk_bits = (size_t)k * (1 + b) + (4096 >> b) + 2 * (size_t)k;
+        size_t total = 16 + 8 * (size_t)n_tensors + 16;
+        for (int t = 0; t < n_tensors; ++t) {
+            const size_t ng = (size_t)((tdev[(size_t)t].n_chunks + SL_RICE_GROUP - 1) / SL_RICE_GROUP);
+            total += 16 + 4 * ng + ng * ((SL_RICE_GROUP * chunk_bits + 31) / 32 * 4) + 16;
+        }
+        p->rice_max_bytes = total;
+        const size_t rice_ws = align_up(8 * groups.size(), 256) + 8 * (size_t)n_tensors + 256;
+        if (p->ws_bytes < rice_ws) p->ws_bytes = rice_ws;
+    }
 
     hipError_t err = hipGetDevice(&p->device);
     if (err != hipSuccess) {
@@ -170,6 +187,9 @@ int sl_plan_create(const sl_tensor *tensors, int n_tensors, int k, sl_plan **out
                      b_t = (size_t)n_tensors * sizeof(SlTensorDev);
         if ((err = hipMalloc((void **)&p->d_desc, b_desc)) != hipSuccess ||
             (err = hipMalloc((void **)&p->d_tensors, b_t)) != hipSuccess ||
+            (err = hipMalloc((void **)&p->d_groups, groups.size() * sizeof(SlGroup))) != hipSuccess ||
+            (err = hipMemcpy(p->d_groups, groups.data(), groups.size() * sizeof(SlGroup),
+                             hipMemcpyHostToDevice)) != hipSuccess ||
             (err = hipMemcpy(p->d_desc, desc.data(), b_desc, hipMemcpyHostToDevice)) != hipSuccess ||
             (err = hipMemcpy(p->d_tensors, tdev.data(), b_t, hipMemcpyHostToDevice)) != hipSuccess) {
             const int rc = err == hipErrorOutOfMemory ? SL_ERR_NOMEM : hip_fail(err);
@@ -186,6 +206,7 @@ int sl_plan_destroy(sl_plan *p)
     if (!p) return SL_OK;
     if (p->d_desc) (void)hipFree(p->d_desc);
     if (p->d_tensors) (void)hipFree(p->d_tensors);
+    if (p->d_groups) (void)hipFree(p->d_groups);
     std::free(p->h_tensors);
     if (p->prof) {
         double ms[SL_PROF_PHASES];
@@ -240,6 +261,32 @@ int sl_compress(sl_plan *p, float *e, const float *delta, float beta, int flags,
         return rc;
     sl_prof_mark(p, SL_PROF_SELECT, st);
     return slk_quantize(p, e, frozen || defer, pay, ws, st);
+}
+
+size_t sl_rice_max_bytes(const sl_plan *p) { return p ? p->rice_max_bytes : 0; }
+
+int sl_rice_encode(sl_plan *p, const void *payload, void *out, size_t out_capacity, void *workspace,
+                   void *stream)
+{
+    if (!p || !payload || !out || !workspace) return SL_ERR_INVALID_ARG;
+    if (out_capacity < p->rice_max_bytes || payload == out) return SL_ERR_INVALID_ARG;
+    if (misaligned(payload, 16) || misaligned(out, 16) || misaligned(workspace, 256))
+        return SL_ERR_INVALID_ARG;
+    int rc = check_device(p);
+    if (rc) return rc;
+    return slk_rice_encode(p, static_cast<const unsigned char *>(payload), static_cast<unsigned char *>(out),
+                           static_cast<unsigned char *>(workspace), static_cast<hipStream_t>(stream));
+}
+
+int sl_rice_decode(sl_plan *p, const void *in, size_t in_bytes, void *payload, void *stream)
+{
+    if (!p || !in || !payload || in == payload) return SL_ERR_INVALID_ARG;
+    if (in_bytes < 16 + 8 * (size_t)p->n_tensors) return SL_ERR_INVALID_ARG;
+    if (misaligned(in, 16) || misaligned(payload, 16)) return SL_ERR_INVALID_ARG;
+    int rc = check_device(p);
+    if (rc) return rc;
+    return slk_rice_decode(p, static_cast<const unsigned char *>(in), in_bytes,
+                           static_cast<unsigned char *>(payload), static_cast<hipStream_t>(stream));
 }
 
 int sl_residual_apply(sl_plan *p, float *e, const void *payload, void *stream)

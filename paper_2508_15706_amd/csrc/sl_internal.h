@@ -26,6 +26,14 @@ struct SlTensorDev {
     long long n_chunks;
     long long pay_off;      // byte offset of the tensor's block in a payload
     long long block_bytes;  // align16(16 + n_chunks * record_bytes)
+    long long group0;       // first coding group (16 chunks) of the tensor, list order
+};
+
+enum { SL_RICE_GROUP = 16 };   // chunks that are coded back to back (decoded sequentially)
+
+struct SlGroup {            // one coding group of the index coder
+    int tensor;
+    int local_group;
 };
 
 // Per-tensor quantizer state produced during sl_compress.
@@ -51,6 +59,9 @@ struct sl_plan {
     // device tables
     SlChunkDesc *d_desc;
     SlTensorDev *d_tensors;
+    SlGroup *d_groups;
+    int64_t n_groups;
+    size_t rice_max_bytes;
     // host copies
     SlTensorDev *h_tensors;
     // optional per-kernel timing (sl_profile_begin / sl_profile_end)
@@ -79,4 +90,9 @@ int slk_apply(const sl_plan *p, float *theta, const void *const *payloads, int R
               hipStream_t st);
 int slk_pack(const uint16_t *idx, const uint8_t *codes, int64_t n_chunks, int k, unsigned char *out,
              hipStream_t st);
+int slk_rice_encode(const sl_plan *p, const unsigned char *payload, unsigned char *out,
+                    unsigned char *ws, hipStream_t st);
+int slk_rice_decode(const sl_plan *p, const unsigned char *in, size_t in_bytes, unsigned char *payload,
+                    hipStream_t st);
+int sl_rice_param(int k);
 void sl_note_hip_error(hipError_t e);

@@ -1,0 +1,354 @@
+// Index coder: transcodes a payload between the plain wire format (12-bit
+// indices) and a Rice-coded format (appendix "Compression of indices in Top-k":
+// the paper compresses the indices with "sub-chunking and Rice coding" and
+// reports 8.9 / 6.6 / 5.6 bits per index for k = 32 / 128 / 256; the algorithm is
+// not described, the format below is this library's own).
+//
+// Coded format.  An ascending index list is coded as gaps g_0 = idx_0,
+// g_i = idx_i - idx_(i-1) - 1, each as a Rice code with parameter
+// b = floor(log2(2839 / k)) (0 when 2839 / k < 1; 2839 = floor(4096 ln 2)):
+// (g >> b) one-bits, a zero bit, the b low bits of g LSB first; bits fill bytes
+// LSB first.  A chunk is its k gap codes followed by its k 2-bit codes.  The
+// chunks of a GROUP of 16 follow each other without padding, a group starts on
+// a 4-byte boundary.  Tensor block (16-byte aligned): float LUT[4]; uint32
+// goff[n_groups] = byte offset of each group from the block start; the
+// streams; zero padding to 16.  Buffer: "SLRICE01", uint64 total bytes, uint64
+// tensor_off[n_tensors], zero padding to 16, the blocks.
+//
+// One lane codes or decodes one group sequentially (a group is the unit that
+// cannot be split); sizes are found first, then two small scans place the
+// groups and the tensor blocks, then the streams are written.
+#include "sl_device.h"
+#include "sl_internal.h"
+
+int sl_rice_param(int k)
+{
+    const int q = 2839 / k;
+    int b = 0;
+    while ((2 << b) <= q) ++b;
+    return q < 1 ? 0 : b;
+}
+
+namespace {
+
+// Sequential reader of bit fields from a byte- or word-addressed stream.
+template <bool WORDS>
+struct BitReader {
+    const unsigned char *p, *end;
+    unsigned long long acc = 0;
+    int n = 0;
+    SL_DEV BitReader(const unsigned char *start, const unsigned char *limit) : p(start), end(limit) {}
+    SL_DEV void refill()
+    {
+        if (WORDS) {
+            const unsigned w = p + 4 <= end ? *reinterpret_cast<const unsigned *>(p) : 0u;
+            acc |= (unsigned long long)w << n;
+            p += 4, n += 32;
+        } else {
+            const unsigned w = p < end ? *p : 0u;
+            acc |= (unsigned long long)w << n;
+            p += 1, n += 8;
+        }
+    }
+    SL_DEV unsigned get(int bits)            // bits <= 32
+    {
+        while (n < bits) refill();
+        const unsigned v = bits == 32 ? (unsigned)acc : (unsigned)acc & ((1u << bits) - 1u);
+        acc >>= bits, n -= bits;
+        return v;
+    }
+    SL_DEV unsigned unary()                  // number of one-bits before the next zero bit
+    {
+        unsigned q = 0;
+        for (;;) {
+            if (n == 0) refill();
+            const unsigned long long inv = ~acc;
+            const int t = inv ? __ffsll((long long)inv) - 1 : 64;
+            if (t >= n) {                    // every buffered bit is a one
+                q += n;
+                acc = 0, n = 0;
+                if (q > 8192) return q;      // malformed input: stop
+            } else {
+                q += t;
+                acc >>= (t + 1), n -= (t + 1);
+                return q;
+            }
+        }
+    }
+};
+
+// Sequential writer; COUNT = only count the bits.
+template <bool COUNT, bool WORDS>
+struct BitWriter {
+    unsigned char *p;
+    unsigned long long acc = 0;
+    int n = 0;
+    long long total = 0;
+    SL_DEV explicit BitWriter(unsigned char *start) : p(start) {}
+    SL_DEV void put(unsigned v, int bits)    // bits <= 32, v < 2^bits
+    {
+        total += bits;
+        if (COUNT) return;
+        acc |= (unsigned long long)v << n;
+        n += bits;
+        if (WORDS) {
+            if (n >= 32) {
+                *reinterpret_cast<unsigned *>(p) = (unsigned)acc;
+                p += 4, acc >>= 32, n -= 32;
+            }
+        } else {
+            while (n >= 8) {
+                *p++ = (unsigned char)acc;
+                acc >>= 8, n -= 8;
+            }
+        }
+    }
+    SL_DEV void flush_word()                 // pad with zero bits to a 4-byte boundary
+    {
+        const int pad = (int)((32 - (total & 31)) & 31);
+        if (pad) put(0u, pad);
+    }
+};
+
+struct RiceArgs {
+    const SlChunkDesc *desc;
+    const SlTensorDev *tensors;
+    const SlGroup *groups;
+    long long n_groups;
+    int n_tensors;
+    int k, b;
+    unsigned *gsize;               // [n_groups] coded bytes of each group
+    unsigned *goff;                // [n_groups] byte offset of each group in its block
+    unsigned long long *tbytes;    // [n_tensors] bytes of each tensor block
+};
+
+// Codes the chunks of group G from the plain payload.  COUNT: returns the
+// coded bytes only.  Otherwise writes the stream at `dst` (4-byte aligned).
+template <bool COUNT, bool WORDS>
+SL_DEV unsigned code_group(const RiceArgs &A, long long G, const unsigned char *payload,
+                           unsigned char *dst)
+{
+    const SlGroup g = A.groups[G];
+    const SlTensorDev td = A.tensors[g.tensor];
+    const int k = A.k, b = A.b;
+    const long long rec = (long long)7 * k / 4;
+    const long long c0 = (long long)g.local_group * SL_RICE_GROUP;
+    const int nc = (int)min((long long)SL_RICE_GROUP, td.n_chunks - c0);
+    BitWriter<COUNT, true> w(dst);
+    for (int i = 0; i < nc; ++i) {
+        const unsigned char *r = payload + td.pay_off + 16 + (c0 + i) * rec;
+        BitReader<WORDS> rd(r, r + rec);
+        int prev = -1;
+        for (int m = 0; m < k; ++m) {
+            const int idx = (int)rd.get(12);
+            unsigned gap = (unsigned)(idx - prev - 1);
+            prev = idx;
+            unsigned q = gap >> b;
+            while (q >= 32) {
+                w.put(0xFFFFFFFFu, 32);
+                q -= 32;
+            }
+            if (q) w.put((1u << q) - 1u, (int)q);
+            w.put((gap & ((1u << b) - 1u)) << 1, b + 1);      // the zero bit, then the remainder
+        }
+        if (WORDS) {
+            for (int m = 0; m < k; m += 16) w.put(rd.get(32), 32);
+        } else {
+            for (int m = 0; m < k; m += 4) w.put(rd.get(8), 8);
+        }
+    }
+    w.flush_word();
+    return (unsigned)(w.total >> 3);
+}
+
+template <bool WORDS>
+__global__ void __launch_bounds__(64) k_rice_sizes(RiceArgs A, const unsigned char *payload)
+{
+    const long long G = (long long)blockIdx.x * 64 + threadIdx.x;
+    if (G >= A.n_groups) return;
+    A.gsize[G] = code_group<true, WORDS>(A, G, payload, nullptr);
+}
+
+// One workgroup per tensor: exclusive scan of its groups' sizes.
+__global__ void __launch_bounds__(256) k_rice_scan(RiceArgs A)
+{
+    __shared__ unsigned long long wsum[4];
+    __shared__ unsigned long long carry;
+    const SlTensorDev td = A.tensors[blockIdx.x];
+    const long long ng = (td.n_chunks + SL_RICE_GROUP - 1) / SL_RICE_GROUP;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    if (tid == 0) carry = 16ull + 4ull * (unsigned long long)ng;
+    __syncthreads();
+    for (long long base = 0; base < ng; base += 256) {
+        const long long i = base + tid;
+        const unsigned long long v = i < ng ? A.gsize[td.group0 + i] : 0ull;
+        unsigned long long incl = v;
+#pragma unroll
+        for (int s = 1; s < 64; s <<= 1) {
+            const unsigned long long up = __shfl_up(incl, s);
+            if (lane >= s) incl += up;
+        }
+        if (lane == 63) wsum[wave] = incl;
+        __syncthreads();
+        unsigned long long before = carry;
+        for (int q = 0; q < wave; ++q) before += wsum[q];
+        if (i < ng) A.goff[td.group0 + i] = (unsigned)(before + incl - v);
+        __syncthreads();
+        if (tid == 255) carry = before + incl;
+        __syncthreads();
+    }
+    if (tid == 0) A.tbytes[blockIdx.x] = (carry + 15ull) & ~15ull;
+}
+
+// Header: magic, total, tensor offsets (one workgroup; the scan over tensors is short).
+__global__ void __launch_bounds__(64) k_rice_header(RiceArgs A, unsigned char *out)
+{
+    if (threadIdx.x != 0) return;
+    unsigned long long *h = reinterpret_cast<unsigned long long *>(out);
+    unsigned long long pos = (16ull + 8ull * (unsigned long long)A.n_tensors + 15ull) & ~15ull;
+    if ((A.n_tensors & 1)) h[2 + A.n_tensors] = 0ull;          // padding of the header to 16 bytes
+    for (int t = 0; t < A.n_tensors; ++t) {
+        h[2 + t] = pos;
+        pos += A.tbytes[t];
+    }
+    h[0] = 0x3130454349524C53ull;                              // "SLRICE01", little endian
+    h[1] = pos;
+}
+
+template <bool WORDS>
+__global__ void __launch_bounds__(64) k_rice_encode(RiceArgs A, const unsigned char *payload,
+                                                    unsigned char *out)
+{
+    const long long G = (long long)blockIdx.x * 64 + threadIdx.x;
+    if (G >= A.n_groups) return;
+    const SlGroup g = A.groups[G];
+    const SlTensorDev td = A.tensors[g.tensor];
+    unsigned char *blk = out + reinterpret_cast<const unsigned long long *>(out)[2 + g.tensor];
+    const unsigned off = A.goff[G];
+    reinterpret_cast<unsigned *>(blk + 16)[g.local_group] = off;
+    const unsigned bytes = code_group<false, WORDS>(A, G, payload, blk + off);
+    if (g.local_group == 0)
+        *reinterpret_cast<float4 *>(blk) = *reinterpret_cast<const float4 *>(payload + td.pay_off);
+    const long long ng = (td.n_chunks + SL_RICE_GROUP - 1) / SL_RICE_GROUP;
+    if (g.local_group == ng - 1)                               // zero padding of the block
+        for (unsigned long long q = off + bytes; q < A.tbytes[g.tensor]; q += 4)
+            *reinterpret_cast<unsigned *>(blk + q) = 0u;
+}
+
+template <bool WORDS>
+__global__ void __launch_bounds__(64) k_rice_decode(RiceArgs A, const unsigned char *in,
+                                                    unsigned long long in_bytes, unsigned char *payload)
+{
+    const long long G = (long long)blockIdx.x * 64 + threadIdx.x;
+    if (G >= A.n_groups) return;
+    const SlGroup g = A.groups[G];
+    const SlTensorDev td = A.tensors[g.tensor];
+    const int k = A.k, b = A.b;
+    const long long rec = (long long)7 * k / 4;
+    const unsigned char *end = in + in_bytes;
+    unsigned long long toff = reinterpret_cast<const unsigned long long *>(in)[2 + g.tensor];
+    if (toff > in_bytes) toff = in_bytes;
+    const unsigned char *blk = in + toff;
+    unsigned long long off = in_bytes;                         // beyond the end: reads as zeros
+    if (blk + 16 + 4ull * (g.local_group + 1) <= end)
+        off = toff + reinterpret_cast<const unsigned *>(blk + 16)[g.local_group];
+    if (off > in_bytes) off = in_bytes;
+    BitReader<true> rd(in + (off & ~3ull), end);
+    const long long c0 = (long long)g.local_group * SL_RICE_GROUP;
+    const int nc = (int)min((long long)SL_RICE_GROUP, td.n_chunks - c0);
+    for (int i = 0; i < nc; ++i) {
+        unsigned char *r = payload + td.pay_off + 16 + (c0 + i) * rec;
+        BitWriter<false, WORDS> w(r);
+        int prev = -1;
+        for (int m = 0; m < k; ++m) {
+            const unsigned q = rd.unary();
+            const unsigned gap = (q << b) | rd.get(b);
+            int idx = prev + 1 + (int)gap;
+            if (idx > 4095 || idx < 0) idx = 4095;             // malformed input stays in range
+            prev = idx;
+            w.put((unsigned)idx, 12);
+        }
+        if (WORDS) {
+            for (int m = 0; m < k; m += 16) w.put(rd.get(32), 32);
+        } else {
+            for (int m = 0; m < k; m += 4) w.put(rd.get(8), 8);
+        }
+    }
+    if (g.local_group == 0) {
+        float4 lut = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (blk + 16 <= end) lut = *reinterpret_cast<const float4 *>(blk);
+        *reinterpret_cast<float4 *>(payload + td.pay_off) = lut;
+    }
+    const long long ng = (td.n_chunks + SL_RICE_GROUP - 1) / SL_RICE_GROUP;
+    if (g.local_group == ng - 1)                               // padding of the plain tensor block
+        for (long long q = 16 + td.n_chunks * rec; q < td.block_bytes; ++q) payload[td.pay_off + q] = 0;
+}
+
+int launched()
+{
+    hipError_t err = hipGetLastError();
+    if (err != hipSuccess) {
+        sl_note_hip_error(err);
+        return SL_ERR_HIP;
+    }
+    return SL_OK;
+}
+
+RiceArgs make_args(const sl_plan *p, unsigned char *ws)
+{
+    RiceArgs A;
+    A.desc = p->d_desc;
+    A.tensors = p->d_tensors;
+    A.groups = p->d_groups;
+    A.n_groups = p->n_groups;
+    A.n_tensors = p->n_tensors;
+    A.k = p->k;
+    A.b = sl_rice_param(p->k);
+    const size_t sec = ((size_t)p->n_groups * 4 + 255) & ~(size_t)255;
+    A.gsize = ws ? reinterpret_cast<unsigned *>(ws) : nullptr;
+    A.goff = ws ? reinterpret_cast<unsigned *>(ws + sec) : nullptr;
+    A.tbytes = ws ? reinterpret_cast<unsigned long long *>(ws + 2 * sec) : nullptr;
+    return A;
+}
+
+}  // namespace
+
+int slk_rice_encode(const sl_plan *p, const unsigned char *payload, unsigned char *out,
+                    unsigned char *ws, hipStream_t st)
+{
+    const RiceArgs A = make_args(p, ws);
+    const bool words = (p->k & 15) == 0;      // records and their code runs are 4-byte aligned
+    const unsigned nblk = (unsigned)((p->n_groups + 63) / 64);
+    int rc;
+    if (p->n_groups > 0) {
+        if (words) hipLaunchKernelGGL(k_rice_sizes<true>, dim3(nblk), dim3(64), 0, st, A, payload);
+        else hipLaunchKernelGGL(k_rice_sizes<false>, dim3(nblk), dim3(64), 0, st, A, payload);
+        if ((rc = launched())) return rc;
+        hipLaunchKernelGGL(k_rice_scan, dim3(p->n_tensors), dim3(256), 0, st, A);
+        if ((rc = launched())) return rc;
+    }
+    hipLaunchKernelGGL(k_rice_header, dim3(1), dim3(64), 0, st, A, out);
+    if ((rc = launched())) return rc;
+    if (p->n_groups > 0) {
+        if (words) hipLaunchKernelGGL(k_rice_encode<true>, dim3(nblk), dim3(64), 0, st, A, payload, out);
+        else hipLaunchKernelGGL(k_rice_encode<false>, dim3(nblk), dim3(64), 0, st, A, payload, out);
+        if ((rc = launched())) return rc;
+    }
+    return SL_OK;
+}
+
+int slk_rice_decode(const sl_plan *p, const unsigned char *in, size_t in_bytes, unsigned char *payload,
+                    hipStream_t st)
+{
+    if (p->n_groups == 0) return SL_OK;
+    const RiceArgs A = make_args(p, nullptr);
+    const bool words = (p->k & 15) == 0;
+    const unsigned nblk = (unsigned)((p->n_groups + 63) / 64);
+    if (words)
+        hipLaunchKernelGGL(k_rice_decode<true>, dim3(nblk), dim3(64), 0, st, A, in,
+                           (unsigned long long)in_bytes, payload);
+    else
+        hipLaunchKernelGGL(k_rice_decode<false>, dim3(nblk), dim3(64), 0, st, A, in,
+                           (unsigned long long)in_bytes, payload);
+    return launched();
+}

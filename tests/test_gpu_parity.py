@@ -321,3 +321,49 @@ def test_argument_errors_are_reported_not_launched(sl):
     with pytest.raises(sl.SparseLoCoError):                       # frozen excludes a deferred residual
         sl.sl_compress(plan, theta, d, 0.95, pay, sl.alloc_workspace(plan),
                        flags=sl.SL_COMPRESS_EF_FROZEN | sl.SL_COMPRESS_DEFER_RESIDUAL)
+
+
+# --------------------------------------------------------------------------- index coder
+@pytest.mark.parametrize("k", [4, 20, 32, 64, 128, 256, 1000])
+def test_rice_transcode_matches_oracle(sl, oracle, k):
+    """sl_rice_encode produces the oracle's coded bytes, sl_rice_decode restores the payload
+    (from the GPU's and from the oracle's coded buffer); a truncated buffer is decoded without
+    leaving the buffer."""
+    if k <= 256:
+        shapes = [(150, 210, TILE), (1, 4096 * 37 + 1100, FLAT), (1024, 16, TILE), (64, 64, TILE), (256, 320, TILE)]
+    else:
+        shapes = [(160, 224, TILE), (1, 4096 * 20 + 1000, FLAT)]
+    descs, n = layout_list(shapes)
+    rng = np.random.default_rng(700 + k)
+    e0 = rng.normal(0, 1e-3, n).astype(np.float32)
+    delta = (1e-3 * rng.standard_t(3, n)).astype(np.float32)
+    plan = sl.sl_plan_create(descs, k)
+    ws = sl.alloc_workspace(plan)
+    _, pay_host, pay_dev = gpu_compress(sl, plan, e0, delta, 0.95)
+    ref_pay = oracle.compress(descs, k, e0.copy(), delta, 0.95)
+    assert np.array_equal(pay_host, ref_pay)
+    ref_enc = oracle.rice_encode(descs, k, ref_pay)
+
+    cap = sl.sl_rice_max_bytes(plan)
+    assert cap >= ref_enc.size
+    out = torch.full((cap,), 0xCD, dtype=torch.uint8, device="cuda")
+    sl.sl_rice_encode(plan, pay_dev, out, ws)
+    torch.cuda.synchronize()
+    got = out.cpu().numpy()
+    size = int(got[8:16].view(np.uint64)[0])
+    assert size == ref_enc.size
+    assert np.array_equal(got[:size], ref_enc)
+    assert size < plan.payload_bytes or k <= 8            # the coded form is smaller
+
+    for src in (out, torch.from_numpy(np.concatenate([ref_enc, np.zeros(16, np.uint8)])).cuda()):
+        back = torch.full((max(16, plan.payload_bytes),), 0xEE, dtype=torch.uint8, device="cuda")
+        sl.sl_rice_decode(plan, src, size, back)
+        torch.cuda.synchronize()
+        assert np.array_equal(back[:plan.payload_bytes].cpu().numpy(), ref_pay)
+
+    back = torch.zeros(max(16, plan.payload_bytes), dtype=torch.uint8, device="cuda")
+    sl.sl_rice_decode(plan, out, size // 2 // 16 * 16, back)   # truncated input: defined, in bounds
+    torch.cuda.synchronize()
+    with pytest.raises(sl.SparseLoCoError):
+        sl.sl_rice_encode(plan, pay_dev, out[:cap - 16], ws)   # capacity too small
+    plan.close()
