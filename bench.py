@@ -210,6 +210,29 @@ def main():
         "compress_ms": compress_ms, "apply_ms": apply_ms,
         "apply_GBps": apply_bytes / (apply_ms * 1e-3) / 1e9 if apply_ms > 0 else 0.0,
     }
+    # index coder (not part of the timed step): coded size and transcoding time of one payload
+    def time_ms(fn, reps=3):
+        fn()
+        torch.cuda.synchronize()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(reps):
+            fn()
+        b.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) / reps
+
+    coded = torch.empty(sl.sl_rice_max_bytes(plan), dtype=torch.uint8, device=dev)
+    back = sl.alloc_payload(plan)
+    enc_ms = time_ms(lambda: sl.sl_rice_encode(plan, own[0], coded, ws))
+    coded_bytes = int(coded[8:16].cpu().numpy().view("uint64")[0])
+    dec_ms = time_ms(lambda: sl.sl_rice_decode(plan, coded, coded_bytes, back))
+    out["index_coder"] = {
+        "plain_bytes": plan.payload_bytes, "coded_bytes": coded_bytes,
+        "bits_per_index": coded_bytes * 8 / (n_chunks * w.k) - 2.0,
+        "lossless": bool(torch.equal(back[:plan.payload_bytes], own[0][:plan.payload_bytes])),
+        "encode_ms": enc_ms, "decode_ms": dec_ms,
+    }
     if not args.no_cpu_baseline:
         del deltas, theta, e0
         out["cpu_baseline"] = cpu_baseline(w, args.cpu_layers)

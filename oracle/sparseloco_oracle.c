@@ -524,7 +524,7 @@ int slo_max_threads(void)
 /*     2839 / k < 1 (the optimum for uniformly random positions);             */
 /*   - bits fill bytes LSB first (as the 12-bit fields of the plain format);  */
 /*   - a chunk = its k gap codes followed by its k 2-bit codes (entry m at    */
-/*     bits 2m, 2m+1 of that run); chunks of a group of 16 follow each other  */
+/*     bits 2m, 2m+1 of that run); chunks of a group of 8 follow each other  */
 /*     without padding; a group starts on a 4-byte boundary (the sub-chunking:*/
 /*     a group is the unit that must be decoded sequentially);                */
 /*   - tensor block, 16-byte aligned: float LUT[4]; uint32 goff[n_groups] =   */
@@ -535,7 +535,7 @@ int slo_max_threads(void)
 /*     then the blocks.                                                       */
 /* ------------------------------------------------------------------------- */
 
-#define SLO_RICE_GROUP 16
+#define SLO_RICE_GROUP 8
 static const char SLO_RICE_MAGIC[8] = {'S', 'L', 'R', 'I', 'C', 'E', '0', '1'};
 
 int slo_rice_param(int k)

@@ -26,10 +26,10 @@ struct SlTensorDev {
     long long n_chunks;
     long long pay_off;      // byte offset of the tensor's block in a payload
     long long block_bytes;  // align16(16 + n_chunks * record_bytes)
-    long long group0;       // first coding group (16 chunks) of the tensor, list order
+    long long group0;       // first coding group (8 chunks) of the tensor, list order
 };
 
-enum { SL_RICE_GROUP = 16 };   // chunks that are coded back to back (decoded sequentially)
+enum { SL_RICE_GROUP = 8 };   // chunks that are coded back to back (decoded sequentially)
 
 struct SlGroup {            // one coding group of the index coder
     int tensor;

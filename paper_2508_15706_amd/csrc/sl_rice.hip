@@ -9,7 +9,7 @@
 // b = floor(log2(2839 / k)) (0 when 2839 / k < 1; 2839 = floor(4096 ln 2)):
 // (g >> b) one-bits, a zero bit, the b low bits of g LSB first; bits fill bytes
 // LSB first.  A chunk is its k gap codes followed by its k 2-bit codes.  The
-// chunks of a GROUP of 16 follow each other without padding, a group starts on
+// chunks of a GROUP of 8 follow each other without padding, a group starts on
 // a 4-byte boundary.  Tensor block (16-byte aligned): float LUT[4]; uint32
 // goff[n_groups] = byte offset of each group from the block start; the
 // streams; zero padding to 16.  Buffer: "SLRICE01", uint64 total bytes, uint64

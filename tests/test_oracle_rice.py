@@ -92,7 +92,7 @@ def test_rice_round_trip(oracle, k):
     toffs = enc[16:16 + 8 * nt].view(np.uint64)
     assert all(int(t) % 16 == 0 for t in toffs) and list(toffs) == sorted(toffs)
     for t, d in zip(toffs, descs):
-        ng = (oracle.tensor_chunks(d) + 15) // 16
+        ng = (oracle.tensor_chunks(d) + 7) // 8
         goff = enc[int(t) + 16:int(t) + 16 + 4 * ng].view(np.uint32)
         assert goff[0] == 16 + 4 * ng and all(int(g) % 4 == 0 for g in goff) and np.all(np.diff(goff.astype(np.int64)) > 0)
 
