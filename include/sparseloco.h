@@ -123,6 +123,16 @@ size_t sl_workspace_bytes(const sl_plan *plan);
 int sl_compress(sl_plan *plan, float *e, const float *delta, float beta, int flags,
                 const void *pending, void *payload, void *workspace, void *stream);
 
+/* sl_compress with the pseudo-gradient formed on the fly (Section 3.1 and
+ * Algorithm 1, "Pseudo-gradient": delta = theta_outer - theta_local, the
+ * parameters before and after the worker's H inner steps): one fp32 subtraction
+ * per element inside the accumulate pass, so delta never exists in memory.
+ * theta_outer, theta_local: in, device, fp32 arenas, 16-byte aligned, distinct
+ * from each other and from e.  Everything else as sl_compress. */
+int sl_compress_params(sl_plan *plan, float *e, const float *theta_outer, const float *theta_local,
+                       float beta, int flags, const void *pending, void *payload, void *workspace,
+                       void *stream);
+
 /* The error update on its own (Eq. (2) line 2, second half; Algorithm 1 error
  * update): e[i] <- e[i] - LUT[code] at the positions `payload` transmits.  Ends
  * a chain of SL_COMPRESS_DEFER_RESIDUAL calls (e.g. before a checkpoint).

@@ -28,7 +28,7 @@ EXPORTS = [
     "sl_payload_bytes", "sl_payload_tensor_offset", "sl_workspace_bytes", "sl_compress",
     "sl_decompress_avg_apply", "sl_pack_indices", "sl_strerror", "sl_last_hip_error",
     "sl_profile_begin", "sl_profile_end", "sl_residual_apply",
-    "sl_rice_max_bytes", "sl_rice_encode", "sl_rice_decode",
+    "sl_rice_max_bytes", "sl_rice_encode", "sl_rice_decode", "sl_compress_params",
 ]
 PROF_PHASES = ["select", "stats", "codes", "lut", "residual", "apply"]
 
@@ -75,6 +75,8 @@ def lib():
         L.sl_workspace_bytes.argtypes = [vp]
         L.sl_compress.restype = i32
         L.sl_compress.argtypes = [vp, vp, vp, C.c_float, i32, vp, vp, vp, vp]
+        L.sl_compress_params.restype = i32
+        L.sl_compress_params.argtypes = [vp, vp, vp, vp, C.c_float, i32, vp, vp, vp, vp]
         L.sl_residual_apply.restype = i32
         L.sl_residual_apply.argtypes = [vp, vp, vp, vp]
         L.sl_decompress_avg_apply.restype = i32
@@ -246,3 +248,16 @@ def sl_rice_decode(plan: Plan, coded: torch.Tensor, in_bytes: int, payload: torc
                               _dev_ptr(payload, torch.uint8), _stream_ptr(stream))
     if st:
         raise SparseLoCoError("sl_rice_decode", st)
+
+
+def sl_compress_params(plan: Plan, e: Optional[torch.Tensor], theta_outer: torch.Tensor,
+                       theta_local: torch.Tensor, beta: float, payload: torch.Tensor,
+                       workspace: torch.Tensor, flags: int = SL_COMPRESS_DEFAULT,
+                       pending: Optional[torch.Tensor] = None, stream=None) -> None:
+    st = lib().sl_compress_params(plan.handle, _dev_ptr(e, torch.float32),
+                                  _dev_ptr(theta_outer, torch.float32), _dev_ptr(theta_local, torch.float32),
+                                  float(beta), int(flags), _dev_ptr(pending, torch.uint8),
+                                  _dev_ptr(payload, torch.uint8), _dev_ptr(workspace, torch.uint8),
+                                  _stream_ptr(stream))
+    if st:
+        raise SparseLoCoError("sl_compress_params", st)

@@ -237,8 +237,8 @@ static int check_device(const sl_plan *p)
 
 static bool misaligned(const void *ptr, size_t a) { return ((uintptr_t)ptr & (a - 1)) != 0; }
 
-int sl_compress(sl_plan *p, float *e, const float *delta, float beta, int flags, const void *pending,
-                void *payload, void *workspace, void *stream)
+static int compress_impl(sl_plan *p, float *e, const float *delta, const float *theta_local, float beta,
+                         int flags, const void *pending, void *payload, void *workspace, void *stream)
 {
     if (!p || !delta || !payload || !workspace) return SL_ERR_INVALID_ARG;
     if (flags & ~(SL_COMPRESS_EF_FROZEN | SL_COMPRESS_DEFER_RESIDUAL)) return SL_ERR_INVALID_ARG;
@@ -246,9 +246,10 @@ int sl_compress(sl_plan *p, float *e, const float *delta, float beta, int flags,
     const int defer = (flags & SL_COMPRESS_DEFER_RESIDUAL) ? 1 : 0;
     if (!frozen && !e) return SL_ERR_INVALID_ARG;
     if (frozen && (pending || defer)) return SL_ERR_INVALID_ARG;
-    if (e == delta || pending == payload) return SL_ERR_INVALID_ARG;
-    if (misaligned(e, 16) || misaligned(delta, 16) || misaligned(payload, 16) ||
-        misaligned(pending, 16) || misaligned(workspace, 256))
+    if (e == delta || (theta_local && (e == theta_local || delta == theta_local)) || pending == payload)
+        return SL_ERR_INVALID_ARG;
+    if (misaligned(e, 16) || misaligned(delta, 16) || misaligned(theta_local, 16) ||
+        misaligned(payload, 16) || misaligned(pending, 16) || misaligned(workspace, 256))
         return SL_ERR_INVALID_ARG;
     int rc = check_device(p);
     if (rc) return rc;
@@ -256,11 +257,25 @@ int sl_compress(sl_plan *p, float *e, const float *delta, float beta, int flags,
     unsigned char *pay = static_cast<unsigned char *>(payload);
     unsigned char *ws = static_cast<unsigned char *>(workspace);
     sl_prof_mark(p, -1, st);
-    if ((rc = slk_select(p, e, delta, beta, frozen, static_cast<const unsigned char *>(pending), pay,
-                         ws, st)))
+    if ((rc = slk_select(p, e, delta, theta_local, beta, frozen,
+                         static_cast<const unsigned char *>(pending), pay, ws, st)))
         return rc;
     sl_prof_mark(p, SL_PROF_SELECT, st);
     return slk_quantize(p, e, frozen || defer, pay, ws, st);
+}
+
+int sl_compress(sl_plan *p, float *e, const float *delta, float beta, int flags, const void *pending,
+                void *payload, void *workspace, void *stream)
+{
+    return compress_impl(p, e, delta, nullptr, beta, flags, pending, payload, workspace, stream);
+}
+
+int sl_compress_params(sl_plan *p, float *e, const float *theta_outer, const float *theta_local,
+                       float beta, int flags, const void *pending, void *payload, void *workspace,
+                       void *stream)
+{
+    if (!theta_local) return SL_ERR_INVALID_ARG;
+    return compress_impl(p, e, theta_outer, theta_local, beta, flags, pending, payload, workspace, stream);
 }
 
 size_t sl_rice_max_bytes(const sl_plan *p) { return p ? p->rice_max_bytes : 0; }

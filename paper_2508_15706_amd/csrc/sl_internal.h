@@ -78,8 +78,8 @@ __host__ __device__ inline long long sl_lut_off(const SlChunkDesc &d, int k)
 void sl_prof_mark(const sl_plan *p, int phase, hipStream_t st);
 
 // launchers (defined next to their kernels)
-int slk_select(const sl_plan *p, float *e, const float *delta, float beta, int frozen,
-               const unsigned char *pending, unsigned char *payload, unsigned char *ws,
+int slk_select(const sl_plan *p, float *e, const float *delta, const float *theta_local, float beta,
+               int frozen, const unsigned char *pending, unsigned char *payload, unsigned char *ws,
                hipStream_t st);
 // B, C, D and (unless skip_residual) E
 int slk_quantize(const sl_plan *p, float *e, int skip_residual, unsigned char *payload,

@@ -41,7 +41,8 @@ constexpr int BM_WORDS = SL_CHUNK / 32;  // bitmap of the pending positions
 struct SelectArgs {
     const SlChunkDesc *desc;
     float *e;
-    const float *delta;
+    const float *delta;             // the pseudo-gradient, or theta_outer when theta_local is set
+    const float *theta_local;       // non-null: delta = theta_outer - theta_local, formed on the fly
     const unsigned char *pending;   // payload whose values are still to be subtracted from e
     float beta;
     int frozen;
@@ -155,7 +156,9 @@ SL_DEV void select_general(int (&key)[64], unsigned sg0, unsigned sg1, int k, in
 #endif
 #define SL_SELECT_BOUNDS __launch_bounds__(256, SL_SELECT_WAVES_PER_EU)
 
-template <int GPL>
+// PARAMS: the pseudo-gradient is formed on the fly from two parameter arenas
+// (a separate instantiation, so that the plain path keeps its register budget).
+template <int GPL, bool PARAMS>
 __global__ void SL_SELECT_BOUNDS k_select(SelectArgs A)
 {
     extern __shared__ __align__(16) unsigned char smem_all[];
@@ -242,12 +245,29 @@ __global__ void SL_SELECT_BOUNDS k_select(SelectArgs A)
         const unsigned o0 = 4u * (lr * stride + lc);   // byte offset of this lane's first load
         const unsigned step = 16u * stride;            // four rows further, in bytes
         sl_f4 ev[16], dv[16];
-        if (!A.frozen) {
+        if constexpr (PARAMS) {
+            // pseudo-gradient delta = theta_outer - theta_local (one fp32 subtraction),
+            // formed before e is fetched so that at most two streams sit in registers
+            const float *lc_ = A.theta_local + d.base;
+            sl_f4 tl[16];
 #pragma unroll
-            for (int i = 0; i < 16; ++i) ev[i] = sl_load_stream_at(ec, i * step, o0);
+            for (int i = 0; i < 16; ++i) dv[i] = sl_load_stream_at(dc, i * step, o0);
+#pragma unroll
+            for (int i = 0; i < 16; ++i) tl[i] = sl_load_stream_at(lc_, i * step, o0);
+#pragma unroll
+            for (int i = 0; i < 16; ++i) dv[i] = dv[i] - tl[i];
+            if (!A.frozen) {
+#pragma unroll
+                for (int i = 0; i < 16; ++i) ev[i] = sl_load_stream_at(ec, i * step, o0);
+            }
+        } else {
+            if (!A.frozen) {
+#pragma unroll
+                for (int i = 0; i < 16; ++i) ev[i] = sl_load_stream_at(ec, i * step, o0);
+            }
+#pragma unroll
+            for (int i = 0; i < 16; ++i) dv[i] = sl_load_stream_at(dc, i * step, o0);
         }
-#pragma unroll
-        for (int i = 0; i < 16; ++i) dv[i] = sl_load_stream_at(dc, i * step, o0);
         if (pend) {
             pend_build();
             // e_true = e - (dequantised pending value) at this lane's positions:
@@ -408,10 +428,10 @@ __global__ void SL_SELECT_BOUNDS k_select(SelectArgs A)
                             if ((word >> bit) & 1u)
                                 ee = ee - ql[(int)pre[w] + __popc(word & ((1u << bit) - 1u))];
                         }
-                        v = fmaf(A.beta, ee, dc[o]);
+                        v = fmaf(A.beta, ee, PARAMS ? dc[o] - (A.theta_local + d.base)[o] : dc[o]);
                         ec[o] = v;
                     } else {
-                        v = dc[o];
+                        v = PARAMS ? dc[o] - (A.theta_local + d.base)[o] : dc[o];
                     }
                 } else {
                     inside &= ~(1ull << (4 * i + cc));
@@ -490,8 +510,8 @@ __global__ void SL_SELECT_BOUNDS k_select(SelectArgs A)
 
 }  // namespace
 
-int slk_select(const sl_plan *p, float *e, const float *delta, float beta, int frozen,
-               const unsigned char *pending, unsigned char *payload, unsigned char *ws,
+int slk_select(const sl_plan *p, float *e, const float *delta, const float *theta_local, float beta,
+               int frozen, const unsigned char *pending, unsigned char *payload, unsigned char *ws,
                hipStream_t st)
 {
     if (p->n_chunks == 0) return SL_OK;
@@ -501,6 +521,7 @@ int slk_select(const sl_plan *p, float *e, const float *delta, float beta, int f
     A.desc = p->d_desc;
     A.e = e;
     A.delta = delta;
+    A.theta_local = theta_local;
     A.pending = pending;
     A.beta = beta;
     A.frozen = frozen;
@@ -522,11 +543,19 @@ int slk_select(const sl_plan *p, float *e, const float *delta, float beta, int f
     const int wpb = 4 * (size_t)A.lds_per_wave <= 65536 ? 4 : 1;
     const dim3 grid((unsigned)((p->n_chunks + wpb - 1) / wpb)), block(64 * wpb);
     const size_t lds = (size_t)A.lds_per_wave * wpb;
-    if (k <= 32) hipLaunchKernelGGL(k_select<1>, grid, block, lds, st, A);
-    else if (k <= 64) hipLaunchKernelGGL(k_select<2>, grid, block, lds, st, A);
-    else if (k <= 128) hipLaunchKernelGGL(k_select<4>, grid, block, lds, st, A);
-    else if (k <= 256) hipLaunchKernelGGL(k_select<8>, grid, block, lds, st, A);
-    else hipLaunchKernelGGL(k_select<0>, grid, block, lds, st, A);
+    if (theta_local) {
+        if (k <= 32) hipLaunchKernelGGL((k_select<1, true>), grid, block, lds, st, A);
+        else if (k <= 64) hipLaunchKernelGGL((k_select<2, true>), grid, block, lds, st, A);
+        else if (k <= 128) hipLaunchKernelGGL((k_select<4, true>), grid, block, lds, st, A);
+        else if (k <= 256) hipLaunchKernelGGL((k_select<8, true>), grid, block, lds, st, A);
+        else hipLaunchKernelGGL((k_select<0, true>), grid, block, lds, st, A);
+    } else {
+        if (k <= 32) hipLaunchKernelGGL((k_select<1, false>), grid, block, lds, st, A);
+        else if (k <= 64) hipLaunchKernelGGL((k_select<2, false>), grid, block, lds, st, A);
+        else if (k <= 128) hipLaunchKernelGGL((k_select<4, false>), grid, block, lds, st, A);
+        else if (k <= 256) hipLaunchKernelGGL((k_select<8, false>), grid, block, lds, st, A);
+        else hipLaunchKernelGGL((k_select<0, false>), grid, block, lds, st, A);
+    }
     hipError_t err = hipGetLastError();
     if (err != hipSuccess) {
         sl_note_hip_error(err);

@@ -367,3 +367,29 @@ def test_rice_transcode_matches_oracle(sl, oracle, k):
     with pytest.raises(sl.SparseLoCoError):
         sl.sl_rice_encode(plan, pay_dev, out[:cap - 16], ws)   # capacity too small
     plan.close()
+
+
+# --------------------------------------------------------------------------- pseudo-gradient formed on the fly
+@pytest.mark.parametrize("k,flags", [(32, 0), (64, 0), (64, 1), (512, 0)])
+def test_compress_params_equals_compress_of_the_difference(sl, oracle, k, flags):
+    """delta = theta_outer - theta_local (one fp32 subtraction per element) inside the kernel:
+    same payload and e as the oracle fed with the numpy difference."""
+    shapes = [(150, 210, TILE), (1, 9000, FLAT), (128, 192, TILE)] if k <= 256 else [(160, 224, TILE), (1, 8192 + 1000, FLAT)]
+    descs, n = layout_list(shapes)
+    rng = np.random.default_rng(800 + k)
+    theta_o = rng.normal(0, 0.02, n).astype(np.float32)
+    theta_l = (theta_o - rng.normal(0, 1e-3, n)).astype(np.float32)
+    e0 = rng.normal(0, 1e-3, n).astype(np.float32)
+    delta = theta_o - theta_l                     # fp32 subtraction, rounded once
+    assert delta.dtype == np.float32
+    plan = sl.sl_plan_create(descs, k)
+    ws = sl.alloc_workspace(plan)
+    e = torch.from_numpy(e0.copy()).cuda()
+    pay = sl.alloc_payload(plan)
+    sl.sl_compress_params(plan, e, torch.from_numpy(theta_o).cuda(), torch.from_numpy(theta_l).cuda(), 0.95,
+                          pay, ws, flags=flags)
+    torch.cuda.synchronize()
+    e_ref = e0.copy()
+    ref = oracle.compress(descs, k, e_ref, delta, 0.95, ef_frozen=bool(flags & 1))
+    assert np.array_equal(pay[:plan.payload_bytes].cpu().numpy(), ref)
+    assert_f32_close(e.cpu().numpy(), e_ref, "e")
