@@ -40,7 +40,7 @@ extern "C" {
 typedef enum {
     SL_OK = 0,
     SL_ERR_INVALID_ARG = -1, /* null / misaligned pointer, bad k, R or shape        */
-    SL_ERR_BAD_PAYLOAD = -2, /* reserved for payload validation                     */
+    SL_ERR_BAD_PAYLOAD = -2, /* sl_payload_validate found a malformed record        */
     SL_ERR_HIP = -3,         /* a HIP runtime call failed; see sl_last_hip_error()  */
     SL_ERR_NOMEM = -4,       /* host or device allocation failed (plan creation)    */
     SL_ERR_DEVICE = -5       /* current device differs from the plan's device       */
@@ -151,6 +151,13 @@ int sl_residual_apply(sl_plan *plan, float *e, const void *payload, void *stream
  * to lie inside the tensor; payloads produced by sl_compress always do. */
 int sl_decompress_avg_apply(sl_plan *plan, float *theta, const void *const *payloads, int R,
                             float lr, void *stream);
+
+/* Checks a received payload before it is trusted by sl_decompress_avg_apply:
+ * in every record the k indices must be strictly ascending and must address
+ * positions inside the chunk (edge chunks are partial).  This call WAITS for
+ * the stream (it returns a verdict): SL_OK or SL_ERR_BAD_PAYLOAD.
+ * workspace: device, >= 256 bytes, 256-byte aligned (its first word is used). */
+int sl_payload_validate(sl_plan *plan, const void *payload, void *workspace, void *stream);
 
 /* The record encoder of the wire format on its own (appendix "Compression of
  * indices in Top-k": 12-bit indices + 2-bit values): for each of n_chunks

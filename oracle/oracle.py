@@ -79,6 +79,8 @@ def lib():
         L.slo_decompress_avg_apply.argtypes = [tp, i32, i32, i32, vp, vp, i32, C.c_float]
         L.slo_decompress_dense.restype = i32
         L.slo_decompress_dense.argtypes = [tp, i32, i32, i32, vp, vp]
+        L.slo_validate_payload.restype = i32
+        L.slo_validate_payload.argtypes = [tp, i32, i32, i32, vp]
         L.slo_rice_param.restype = i32
         L.slo_rice_param.argtypes = [i32]
         L.slo_rice_max_bytes.restype = i64
@@ -249,6 +251,13 @@ def decompress_dense(descs, k, payload, n_elems, tile=64):
     if st:
         raise ValueError(f"slo_decompress_dense: status {st}")
     return out
+
+
+def validate_payload(descs, k, payload, tile=64):
+    """True when every record is strictly ascending and inside its tensor."""
+    arr, n = make_tensors(descs)
+    _check(payload, np.uint8)
+    return int(lib().slo_validate_payload(arr, n, tile, k, _ptr(payload))) == 0
 
 
 def max_threads():

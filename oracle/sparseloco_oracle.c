@@ -499,6 +499,31 @@ int slo_decompress_dense(const slo_tensor *t, int nt, int tile, int k, const uin
     return SLO_OK;
 }
 
+/* Well-formedness of a received payload (a receiver-side check, not a step of
+ * the method): every record lists k strictly ascending positions, each of them
+ * inside the tensor.  Returns SLO_OK or SLO_ERR_PAYLOAD. */
+int slo_validate_payload(const slo_tensor *t, int nt, int tile, int k, const uint8_t *payload)
+{
+    int64_t rec = slo_record_bytes(k), pay_off = 0;
+    uint16_t *idx = (uint16_t *)malloc((size_t)k * sizeof(uint16_t));
+    uint8_t *code = (uint8_t *)malloc((size_t)k);
+    int status = SLO_OK;
+    for (int ti = 0; ti < nt && status == SLO_OK; ++ti) {
+        const slo_tensor *T = &t[ti];
+        int64_t nc = slo_tensor_chunks(T, tile);
+        for (int64_t c = 0; c < nc && status == SLO_OK; ++c) {
+            slo_unpack_record(payload + pay_off + 16 + c * rec, k, idx, code);
+            for (int m = 0; m < k; ++m) {
+                if (m > 0 && idx[m] <= idx[m - 1]) status = SLO_ERR_PAYLOAD;
+                if (slo_element_of(T, tile, c, idx[m]) < 0) status = SLO_ERR_PAYLOAD;
+            }
+        }
+        pay_off += slo_tensor_block_bytes(T, tile, k);
+    }
+    free(idx), free(code);
+    return status;
+}
+
 int slo_max_threads(void)
 {
 #ifdef _OPENMP

@@ -29,6 +29,7 @@ EXPORTS = [
     "sl_decompress_avg_apply", "sl_pack_indices", "sl_strerror", "sl_last_hip_error",
     "sl_profile_begin", "sl_profile_end", "sl_residual_apply",
     "sl_rice_max_bytes", "sl_rice_encode", "sl_rice_decode", "sl_compress_params",
+    "sl_payload_validate",
 ]
 PROF_PHASES = ["select", "stats", "codes", "lut", "residual", "apply"]
 
@@ -77,6 +78,8 @@ def lib():
         L.sl_compress.argtypes = [vp, vp, vp, C.c_float, i32, vp, vp, vp, vp]
         L.sl_compress_params.restype = i32
         L.sl_compress_params.argtypes = [vp, vp, vp, vp, C.c_float, i32, vp, vp, vp, vp]
+        L.sl_payload_validate.restype = i32
+        L.sl_payload_validate.argtypes = [vp, vp, vp, vp]
         L.sl_residual_apply.restype = i32
         L.sl_residual_apply.argtypes = [vp, vp, vp, vp]
         L.sl_decompress_avg_apply.restype = i32
@@ -261,3 +264,14 @@ def sl_compress_params(plan: Plan, e: Optional[torch.Tensor], theta_outer: torch
                                   _stream_ptr(stream))
     if st:
         raise SparseLoCoError("sl_compress_params", st)
+
+
+def sl_payload_validate(plan: Plan, payload: torch.Tensor, workspace: torch.Tensor, stream=None) -> bool:
+    """True when every record is well formed (waits for the stream)."""
+    st = lib().sl_payload_validate(plan.handle, _dev_ptr(payload, torch.uint8),
+                                   _dev_ptr(workspace, torch.uint8), _stream_ptr(stream))
+    if st == -2:
+        return False
+    if st:
+        raise SparseLoCoError("sl_payload_validate", st)
+    return True

@@ -304,6 +304,16 @@ int sl_rice_decode(sl_plan *p, const void *in, size_t in_bytes, void *payload, v
                            static_cast<unsigned char *>(payload), static_cast<hipStream_t>(stream));
 }
 
+int sl_payload_validate(sl_plan *p, const void *payload, void *workspace, void *stream)
+{
+    if (!p || !payload || !workspace) return SL_ERR_INVALID_ARG;
+    if (misaligned(payload, 16) || misaligned(workspace, 256)) return SL_ERR_INVALID_ARG;
+    int rc = check_device(p);
+    if (rc) return rc;
+    return slk_validate(p, static_cast<const unsigned char *>(payload), static_cast<int *>(workspace),
+                        static_cast<hipStream_t>(stream));
+}
+
 int sl_residual_apply(sl_plan *p, float *e, const void *payload, void *stream)
 {
     if (!p || !e || !payload) return SL_ERR_INVALID_ARG;

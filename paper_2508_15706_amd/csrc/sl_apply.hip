@@ -161,6 +161,35 @@ __global__ void __launch_bounds__(256) k_apply(ApplyArgs A)
     }
 }
 
+// Payload check: every record's indices strictly ascending and inside the
+// chunk's valid region.  One wave per chunk; a violation sets *flag.
+__global__ void __launch_bounds__(256)
+k_validate(const SlChunkDesc *desc, long long n_chunks, int k, const unsigned char *payload, int *flag)
+{
+    const int lane = threadIdx.x & 63;
+    const int wave = sl_uniform((int)(threadIdx.x >> 6));
+    const long long c = (long long)blockIdx.x * (blockDim.x >> 6) + wave;
+    if (c >= n_chunks) return;
+    const SlChunkDesc d = desc[c];
+    const unsigned char *rec = payload + d.rec_off;
+    bool bad = false;
+    for (int m = lane; m < k; m += 64) {
+        const int b = (3 * m) >> 1;
+        const unsigned w = (unsigned)rec[b] | ((unsigned)rec[b + 1] << 8);
+        const int j = (int)((m & 1) ? (w >> 4) : (w & 0xFFFu));
+        int prev = -1;
+        if (m > 0) {
+            const int bp = (3 * (m - 1)) >> 1;
+            const unsigned wp = (unsigned)rec[bp] | ((unsigned)rec[bp + 1] << 8);
+            prev = (int)(((m - 1) & 1) ? (wp >> 4) : (wp & 0xFFFu));
+        }
+        const int row = j >> 6, col = j & 63;
+        const int lim = row < d.rows - 1 ? d.cols : (row == d.rows - 1 ? d.last_cols : 0);
+        bad |= j <= prev || col >= lim;
+    }
+    if (sl_ballot(bad) && lane == 0) atomicOr(flag, 1);
+}
+
 // One thread per output byte of the record stream.
 __global__ void __launch_bounds__(256)
 k_pack(const uint16_t *idx, const uint8_t *codes, long long n_chunks, int k, unsigned char *out)
@@ -227,6 +256,24 @@ int slk_apply(const sl_plan *p, float *theta, const void *const *payloads, int R
         return SL_ERR_HIP;
     }
     return SL_OK;
+}
+
+int slk_validate(const sl_plan *p, const unsigned char *payload, int *flag, hipStream_t st)
+{
+    hipError_t err = hipMemsetAsync(flag, 0, sizeof(int), st);
+    if (err == hipSuccess && p->n_chunks > 0) {
+        hipLaunchKernelGGL(k_validate, dim3((unsigned)((p->n_chunks + 3) / 4)), dim3(256), 0, st, p->d_desc,
+                           (long long)p->n_chunks, p->k, payload, flag);
+        err = hipGetLastError();
+    }
+    int host = 0;
+    if (err == hipSuccess) err = hipMemcpyAsync(&host, flag, sizeof(int), hipMemcpyDeviceToHost, st);
+    if (err == hipSuccess) err = hipStreamSynchronize(st);
+    if (err != hipSuccess) {
+        sl_note_hip_error(err);
+        return SL_ERR_HIP;
+    }
+    return host ? SL_ERR_BAD_PAYLOAD : SL_OK;
 }
 
 int slk_pack(const uint16_t *idx, const uint8_t *codes, int64_t n_chunks, int k, unsigned char *out,

@@ -88,6 +88,7 @@ int slk_quantize(const sl_plan *p, float *e, int skip_residual, unsigned char *p
 int slk_residual(const sl_plan *p, float *e, const unsigned char *payload, hipStream_t st);
 int slk_apply(const sl_plan *p, float *theta, const void *const *payloads, int R, float lr,
               hipStream_t st);
+int slk_validate(const sl_plan *p, const unsigned char *payload, int *flag, hipStream_t st);
 int slk_pack(const uint16_t *idx, const uint8_t *codes, int64_t n_chunks, int k, unsigned char *out,
              hipStream_t st);
 int slk_rice_encode(const sl_plan *p, const unsigned char *payload, unsigned char *out,

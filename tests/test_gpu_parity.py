@@ -393,3 +393,45 @@ def test_compress_params_equals_compress_of_the_difference(sl, oracle, k, flags)
     ref = oracle.compress(descs, k, e_ref, delta, 0.95, ef_frozen=bool(flags & 1))
     assert np.array_equal(pay[:plan.payload_bytes].cpu().numpy(), ref)
     assert_f32_close(e.cpu().numpy(), e_ref, "e")
+
+
+# --------------------------------------------------------------------------- payload check
+def test_payload_validate_agrees_with_oracle(sl, oracle):
+    """A compressed payload passes; one planted violation (descending pair, repeated position,
+    position outside an edge chunk) anywhere in the buffer is reported, as by the oracle."""
+    k = 32
+    shapes = [(150, 210, TILE), (1, 4096 * 5 + 1100, FLAT), (70, 100, TILE)]
+    descs, n = layout_list(shapes)
+    rng = np.random.default_rng(900)
+    plan = sl.sl_plan_create(descs, k)
+    ws = sl.alloc_workspace(plan)
+    _, pay_host, pay_dev = gpu_compress(sl, plan, rng.normal(0, 1e-3, n).astype(np.float32),
+                                        rng.normal(0, 1e-3, n).astype(np.float32), 0.95)
+    assert oracle.validate_payload(descs, k, pay_host)
+    assert sl.sl_payload_validate(plan, pay_dev, ws)
+
+    rec = oracle.record_bytes(k)
+    offs, off = [], 0
+    for d in descs:
+        offs.append(off)
+        off += oracle.tensor_block_bytes(d, k)
+    nc0 = oracle.tensor_chunks(descs[0])
+    cases = [
+        (0, 0, lambda idx: idx[[1, 0] + list(range(2, k))]),                # first chunk, first pair swapped
+        (0, nc0 - 1, lambda idx: np.r_[idx[:-1], idx[-2]]),                 # last chunk of tensor 0, repeat
+        (0, nc0 - 1, lambda idx: np.r_[idx[:-1], 4095]),                    # corner tile 22 x 18: outside
+        (1, 5, lambda idx: np.r_[idx[:-1], 1100]),                          # flat tail holds 1100 positions
+        (2, 1, lambda idx: np.r_[idx[:-1], 63 * 64 + 36]),                  # 64 x 36 edge tile, column 36
+        (2, 3, lambda idx: np.r_[idx[:-1], 6 * 64]),                        # 6 x 36 corner tile, row 6
+    ]
+    for ti, c, mutate in cases:
+        bad = pay_host.copy()
+        at = offs[ti] + 16 + c * rec
+        idx, code = oracle.unpack_record(bad[at:at + rec], k)
+        bad[at:at + rec] = oracle.pack_record(np.asarray(mutate(idx), dtype=np.uint16), code)
+        assert not oracle.validate_payload(descs, k, bad), (ti, c)
+        dev = sl.alloc_payload(plan)
+        dev[:bad.size] = torch.from_numpy(bad).cuda()
+        assert not sl.sl_payload_validate(plan, dev, ws), (ti, c)
+    assert sl.sl_payload_validate(plan, pay_dev, ws)        # the flag is cleared per call
+    plan.close()

@@ -647,3 +647,49 @@ def test_multi_round_state_carry(oracle):
         upd = ((dense[0] + dense[1]) * (np.float32(1) / np.float32(2))).astype(np.float32)
         theta_ref = (theta_ref.astype(np.float64) - float(np.float32(lr)) * upd.astype(np.float64)).astype(np.float32)
         assert np.array_equal(bits(theta), bits(theta_ref))
+
+
+# --------------------------------------------------------------------------- payload well-formedness
+def test_validate_payload_by_hand(oracle):
+    """Hand-built records for a 70 x 100 tile-layout tensor (chunks: 64x64, 64x36, 6x64, 6x36):
+    the checker accepts exactly the records whose positions ascend strictly and lie inside the
+    tensor - each violation planted alone is caught."""
+    descs, k = [(70, 100, 0, TILE)], 4
+    rec = oracle.record_bytes(k)
+
+    def payload(records):
+        buf = np.zeros(oracle.payload_bytes(descs, k), dtype=np.uint8)
+        for c, idx in enumerate(records):
+            buf[16 + c * rec:16 + (c + 1) * rec] = oracle.pack_record(idx, [0, 1, 2, 3])
+        return buf
+
+    good = [[0, 63, 64, 4095], [0, 35, 64, 63 * 64 + 35], [0, 63, 5 * 64, 5 * 64 + 63], [0, 35, 64, 5 * 64 + 35]]
+    assert oracle.validate_payload(descs, k, payload(good))
+    for c, bad_rec in [
+        (0, [0, 64, 63, 4095]),            # descending pair
+        (0, [0, 63, 63, 4095]),            # repeated position
+        (1, [0, 36, 64, 100]),             # column 36 of a 36-column edge tile
+        (2, [0, 63, 64, 6 * 64]),          # row 6 of a 6-row edge tile
+        (3, [0, 35, 64, 5 * 64 + 36]),     # corner tile, one column too far
+        (3, [0, 35, 64, 4095]),            # corner tile, far outside
+    ]:
+        recs = [list(r) for r in good]
+        recs[c] = bad_rec
+        assert not oracle.validate_payload(descs, k, payload(recs)), (c, bad_rec)
+
+    flat = [(1, 4096 + 10, 0, FLAT)]
+    buf = np.zeros(oracle.payload_bytes(flat, k), dtype=np.uint8)
+    buf[16:16 + rec] = oracle.pack_record([0, 1, 2, 4095], [0, 0, 0, 0])
+    buf[16 + rec:16 + 2 * rec] = oracle.pack_record([0, 1, 2, 9], [0, 0, 0, 0])
+    assert oracle.validate_payload(flat, k, buf)
+    buf[16 + rec:16 + 2 * rec] = oracle.pack_record([0, 1, 2, 10], [0, 0, 0, 0])   # only 10 valid positions
+    assert not oracle.validate_payload(flat, k, buf)
+
+
+def test_validate_accepts_every_compressed_payload(oracle):
+    descs, n = small_list()
+    rng = np.random.default_rng(77)
+    for k in (4, 32, 64):
+        e = rng.normal(0, 1e-3, n).astype(np.float32)
+        pay = oracle.compress(descs, k, e, rng.normal(0, 1e-3, n).astype(np.float32), 0.95)
+        assert oracle.validate_payload(descs, k, pay)
