@@ -79,6 +79,26 @@ def lib():
         L.slo_decompress_avg_apply.argtypes = [tp, i32, i32, i32, vp, vp, i32, C.c_float]
         L.slo_decompress_dense.restype = i32
         L.slo_decompress_dense.argtypes = [tp, i32, i32, i32, vp, vp]
+        L.slo_header_bytes_b.restype = i64
+        L.slo_header_bytes_b.argtypes = [i32]
+        L.slo_record_bytes_b.restype = i64
+        L.slo_record_bytes_b.argtypes = [i32, i32]
+        L.slo_tensor_block_bytes_b.restype = i64
+        L.slo_tensor_block_bytes_b.argtypes = [tp, i32, i32, i32]
+        L.slo_payload_bytes_b.restype = i64
+        L.slo_payload_bytes_b.argtypes = [tp, i32, i32, i32, i32]
+        L.slo_pack_record_b.restype = None
+        L.slo_pack_record_b.argtypes = [vp, vp, vp, i32, i32, vp]
+        L.slo_unpack_record_b.restype = None
+        L.slo_unpack_record_b.argtypes = [vp, i32, i32, vp, vp, vp]
+        L.slo_quantize_tensor_b.restype = i32
+        L.slo_quantize_tensor_b.argtypes = [vp, i64, i32, i32, vp, vp, vp]
+        L.slo_compress_b.restype = i32
+        L.slo_compress_b.argtypes = [tp, i32, i32, i32, i32, vp, vp, C.c_float, i32, vp, vp, vp, vp, vp]
+        L.slo_decompress_avg_apply_b.restype = i32
+        L.slo_decompress_avg_apply_b.argtypes = [tp, i32, i32, i32, i32, vp, vp, i32, C.c_float]
+        L.slo_decompress_dense_b.restype = i32
+        L.slo_decompress_dense_b.argtypes = [tp, i32, i32, i32, i32, vp, vp]
         L.slo_validate_payload.restype = i32
         L.slo_validate_payload.argtypes = [tp, i32, i32, i32, vp]
         L.slo_rice_param.restype = i32
@@ -250,6 +270,108 @@ def decompress_dense(descs, k, payload, n_elems, tile=64):
     st = lib().slo_decompress_dense(arr, n, tile, k, _ptr(payload), _ptr(out))
     if st:
         raise ValueError(f"slo_decompress_dense: status {st}")
+    return out
+
+
+# ---- other value widths: bits in {1, 2, 3, 4} or 32 (unquantized fp32 values) ----
+def header_bytes_b(bits):
+    return int(lib().slo_header_bytes_b(bits))
+
+
+def record_bytes_b(k, bits):
+    return int(lib().slo_record_bytes_b(k, bits))
+
+
+def tensor_block_bytes_b(desc, k, bits, tile=64):
+    arr, _ = make_tensors([desc])
+    return int(lib().slo_tensor_block_bytes_b(arr, tile, k, bits))
+
+
+def payload_bytes_b(descs, k, bits, tile=64):
+    arr, n = make_tensors(descs)
+    return int(lib().slo_payload_bytes_b(arr, n, tile, k, bits))
+
+
+def pack_record_b(idx, sent, bits):
+    """sent: the k codes (bits <= 4) or the k fp32 values (bits = 32)."""
+    idx = _check(np.ascontiguousarray(idx, dtype=np.uint16), np.uint16)
+    k = idx.size
+    out = np.zeros(record_bytes_b(k, bits), dtype=np.uint8)
+    if bits == 32:
+        val = _check(np.ascontiguousarray(sent, dtype=np.float32), np.float32)
+        lib().slo_pack_record_b(_ptr(idx), None, _ptr(val), k, bits, _ptr(out))
+    else:
+        code = _check(np.ascontiguousarray(sent, dtype=np.uint8), np.uint8)
+        lib().slo_pack_record_b(_ptr(idx), _ptr(code), None, k, bits, _ptr(out))
+    return out
+
+
+def unpack_record_b(rec, k, bits):
+    rec = _check(np.ascontiguousarray(rec, dtype=np.uint8), np.uint8)
+    idx = np.zeros(k, dtype=np.uint16)
+    code = np.zeros(k, dtype=np.uint8)
+    val = np.zeros(k, dtype=np.float32)
+    lib().slo_unpack_record_b(_ptr(rec), k, bits, _ptr(idx), _ptr(code), _ptr(val))
+    return idx, (val if bits == 32 else code)
+
+
+def quantize_tensor_b(x, n_chunks, k, bits):
+    x = _check(np.ascontiguousarray(x, dtype=np.float32), np.float32)
+    assert x.size == n_chunks * k
+    code = np.zeros(x.size, dtype=np.uint8)
+    lut = np.zeros(1 << bits, dtype=np.float32)
+    stats = np.zeros(4 + (1 << bits), dtype=np.float64)
+    st = lib().slo_quantize_tensor_b(_ptr(x), n_chunks, k, bits, _ptr(code), _ptr(lut), _ptr(stats))
+    if st:
+        raise RuntimeError(f"slo_quantize_tensor_b: status {st}")
+    return code, lut, stats
+
+
+def compress_b(descs, k, bits, e, delta, beta, tile=64, ef_frozen=False, want_detail=False):
+    arr, n = make_tensors(descs)
+    _check(e, np.float32), _check(delta, np.float32)
+    nbytes = int(lib().slo_payload_bytes_b(arr, n, tile, k, bits))
+    payload = np.zeros(nbytes, dtype=np.uint8)
+    det = None
+    args = [None, None, None, None]
+    if want_detail:
+        nc = int(lib().slo_num_chunks(arr, n, tile))
+        nb = 0 if bits == 32 else 1 << bits
+        det = dict(
+            idx=np.zeros(nc * k, dtype=np.uint16),
+            val=np.zeros(nc * k, dtype=np.float32),
+            code=np.zeros(nc * k, dtype=np.uint8),
+            lut=np.zeros(max(1, nb * n), dtype=np.float32),
+        )
+        args = [_ptr(det["idx"]), _ptr(det["val"]), _ptr(det["code"]), _ptr(det["lut"])]
+    st = lib().slo_compress_b(arr, n, tile, k, bits, _ptr(e), _ptr(delta), float(beta),
+                              int(bool(ef_frozen)), _ptr(payload), *args)
+    if st:
+        raise ValueError(f"slo_compress_b: status {st}")
+    return (payload, det) if want_detail else payload
+
+
+def decompress_avg_apply_b(descs, k, bits, theta, payloads, lr, tile=64):
+    arr, n = make_tensors(descs)
+    _check(theta, np.float32)
+    R = len(payloads)
+    for p in payloads:
+        _check(p, np.uint8)
+    ptrs = (C.c_void_p * max(1, R))(*[p.ctypes.data for p in payloads])
+    st = lib().slo_decompress_avg_apply_b(arr, n, tile, k, bits, _ptr(theta), ptrs, R, float(lr))
+    if st:
+        raise ValueError(f"slo_decompress_avg_apply_b: status {st}")
+
+
+def decompress_dense_b(descs, k, bits, payload, n_elems, tile=64, out=None):
+    """Writes the sent values into `out` (zeros by default) at the positions the payload names."""
+    arr, n = make_tensors(descs)
+    if out is None:
+        out = np.zeros(n_elems, dtype=np.float32)
+    _check(out, np.float32)
+    st = lib().slo_decompress_dense_b(arr, n, tile, k, bits, _ptr(payload), _ptr(out))
+    if st:
+        raise ValueError(f"slo_decompress_dense_b: status {st}")
     return out
 
 

@@ -499,6 +499,309 @@ int slo_decompress_dense(const slo_tensor *t, int nt, int tile, int k, const uin
     return SLO_OK;
 }
 
+/* ------------------------------------------------------------------------- */
+/* Other value widths (ablation "Effect of quantization on loss": 1-, 2-, 3-,  */
+/* 4-bit and full-precision values; the quantizer of Section 4 cuts            */
+/* [-6 sigma, 6 sigma] into uniform bins, 2^b of them for b bits).  The *_b     */
+/* functions repeat the path above with the number of value bits as a          */
+/* parameter: bits in {1, 2, 3, 4}, or 32 for unquantized fp32 values.  With    */
+/* bits = 2 they produce the same bytes as the functions above.  Readings:     */
+/*   - bin q of 2^b is [mu + sigma*c_q, mu + sigma*c_(q+1)) with               */
+/*     c_j = 12 j / 2^b - 6, the end bins open-ended; a value's code is the    */
+/*     number of inner edges j = 1 .. 2^b - 1 it has reached, each edge        */
+/*     decided on squares against T_j = (c_j*c_j) * var;                       */
+/*   - wire format: per tensor a header of 2^b floats padded to 16 bytes (none */
+/*     for 32 bits), then per chunk the k 12-bit indices followed by the k     */
+/*     codes as a little-endian stream of b-bit fields, or by the k fp32       */
+/*     values; k must be a multiple of 8 unless bits = 2;                      */
+/*   - 32 bits: nothing is quantized, the residual at a sent position is       */
+/*     a - a.                                                                  */
+/* ------------------------------------------------------------------------- */
+
+static int bits_ok(int k, int bits, int tile)
+{
+    if (!(bits == 1 || bits == 2 || bits == 3 || bits == 4 || bits == 32)) return 0;
+    if (k < 4 || k % 4 || k > tile * tile) return 0;
+    if (bits != 2 && k % 8) return 0;
+    return 1;
+}
+
+int64_t slo_header_bytes_b(int bits)
+{
+    if (bits == 32) return 0;
+    int64_t h = (int64_t)4 << bits;
+    return h < 16 ? 16 : h;
+}
+
+int64_t slo_record_bytes_b(int k, int bits)
+{
+    return (int64_t)3 * k / 2 + (bits == 32 ? (int64_t)4 * k : (int64_t)k * bits / 8);
+}
+
+int64_t slo_tensor_block_bytes_b(const slo_tensor *t, int tile, int k, int bits)
+{
+    int64_t b = slo_header_bytes_b(bits) + slo_tensor_chunks(t, tile) * slo_record_bytes_b(k, bits);
+    return (b + 15) / 16 * 16;
+}
+
+int64_t slo_payload_bytes_b(const slo_tensor *t, int nt, int tile, int k, int bits)
+{
+    int64_t n = 0;
+    for (int i = 0; i < nt; ++i) n += slo_tensor_block_bytes_b(&t[i], tile, k, bits);
+    return n;
+}
+
+/* code is used for bits <= 4, val for bits = 32 (the other may be NULL). */
+void slo_pack_record_b(const uint16_t *idx, const uint8_t *code, const float *val, int k, int bits,
+                       uint8_t *out)
+{
+    int nidx = 3 * k / 2;
+    memset(out, 0, (size_t)slo_record_bytes_b(k, bits));
+    for (int m = 0; m < k; ++m) {
+        int bit = 12 * m;
+        unsigned v = idx[m] & 0xFFFu;
+        for (int b = 0; b < 12; ++b)
+            if (v >> b & 1u) out[(bit + b) / 8] |= (uint8_t)(1u << ((bit + b) % 8));
+    }
+    if (bits == 32) {
+        memcpy(out + nidx, val, (size_t)4 * k);
+        return;
+    }
+    for (int m = 0; m < k; ++m) {
+        int bit = bits * m;
+        for (int b = 0; b < bits; ++b)
+            if (code[m] >> b & 1u) out[nidx + (bit + b) / 8] |= (uint8_t)(1u << ((bit + b) % 8));
+    }
+}
+
+void slo_unpack_record_b(const uint8_t *in, int k, int bits, uint16_t *idx, uint8_t *code, float *val)
+{
+    int nidx = 3 * k / 2;
+    for (int m = 0; m < k; ++m) {
+        int bit = 12 * m;
+        unsigned v = 0;
+        for (int b = 0; b < 12; ++b)
+            v |= (unsigned)(in[(bit + b) / 8] >> ((bit + b) % 8) & 1u) << b;
+        idx[m] = (uint16_t)v;
+    }
+    if (bits == 32) {
+        memcpy(val, in + nidx, (size_t)4 * k);
+        return;
+    }
+    for (int m = 0; m < k; ++m) {
+        int bit = bits * m;
+        unsigned v = 0;
+        for (int b = 0; b < bits; ++b)
+            v |= (unsigned)(in[nidx + (bit + b) / 8] >> ((bit + b) % 8) & 1u) << b;
+        code[m] = (uint8_t)v;
+    }
+}
+
+/* lut has 2^bits entries; stats (optional): S1, S2, mu, var, then 2^bits counts. */
+int slo_quantize_tensor_b(const float *x, int64_t n_chunks, int k, int bits, uint8_t *code,
+                          float *lut, double *stats)
+{
+    if (bits < 1 || bits > 4) return SLO_ERR_ARG;
+    int nb = 1 << bits;
+    int64_t M = n_chunks * k;
+    for (int b = 0; b < nb; ++b) lut[b] = 0.0f;
+    if (M == 0) return SLO_OK;
+    double *y = (double *)calloc((size_t)M, sizeof(double));
+    if (!y) return SLO_ERR_NOMEM;
+
+    for (int64_t i = 0; i < M; ++i) y[i] = (double)x[i];
+    double S1 = two_level_sum(y, n_chunks, k);
+    for (int64_t i = 0; i < M; ++i) y[i] = (double)x[i] * (double)x[i];
+    double S2 = two_level_sum(y, n_chunks, k);
+
+    double mu = S1 / (double)M;
+    double q = S2 / (double)M;
+    double p = mu * mu;
+    double var = q - p;
+    if (var < 0.0) var = 0.0;
+
+    int64_t cnt[16] = {0};
+    for (int64_t i = 0; i < M; ++i) {
+        double d = (double)x[i] - mu;
+        double dd = d * d;
+        int reached = 0;
+        for (int j = 1; j < nb; ++j) {
+            double cj = 12.0 * (double)j / (double)nb - 6.0; /* edge in units of sigma, exact */
+            double Tj = (cj * cj) * var;
+            int at_or_above;
+            if (cj < 0.0)
+                at_or_above = d >= 0.0 || dd <= Tj;
+            else if (cj == 0.0)
+                at_or_above = d >= 0.0;
+            else
+                at_or_above = d >= 0.0 && dd >= Tj;
+            reached += at_or_above;
+        }
+        code[i] = (uint8_t)reached;
+        cnt[reached]++;
+    }
+    for (int b = 0; b < nb; ++b) {
+        for (int64_t i = 0; i < M; ++i) y[i] = code[i] == b ? (double)x[i] : 0.0;
+        double Sb = two_level_sum(y, n_chunks, k);
+        float cen = cnt[b] ? (float)(Sb / (double)cnt[b]) : 0.0f;
+        if (cen == 0.0f) cen = 0.0f;
+        lut[b] = cen;
+    }
+    if (stats) {
+        stats[0] = S1, stats[1] = S2, stats[2] = mu, stats[3] = var;
+        for (int b = 0; b < nb; ++b) stats[4 + b] = (double)cnt[b];
+    }
+    free(y);
+    return SLO_OK;
+}
+
+/* slo_compress with a value width.  Optional outputs as there; lut_out holds
+ * 2^bits floats per tensor (unused for bits = 32, where sel_code is unused too
+ * and the sent values are sel_val). */
+int slo_compress_b(const slo_tensor *t, int nt, int tile, int k, int bits, float *e,
+                   const float *delta, float beta, int ef_frozen, uint8_t *payload,
+                   uint16_t *sel_idx, float *sel_val, uint8_t *sel_code, float *lut_out)
+{
+    if (nt < 0 || tile < 1 || tile > 64 || !bits_ok(k, bits, tile)) return SLO_ERR_ARG;
+    int nb = bits == 32 ? 0 : 1 << bits;
+    int64_t rec = slo_record_bytes_b(k, bits), hdr = slo_header_bytes_b(bits);
+    int64_t chunk0 = 0, pay_off = 0;
+
+    for (int ti = 0; ti < nt; ++ti) {
+        const slo_tensor *T = &t[ti];
+        int64_t n = T->rows * T->cols;
+        int64_t nc = slo_tensor_chunks(T, tile);
+        int64_t M = nc * k;
+        slo_tensor L = *T;
+        L.offset = 0;
+        const float *a;
+        if (ef_frozen) {
+            a = delta + T->offset;
+        } else {
+            slo_accumulate(e + T->offset, delta + T->offset, beta, n);
+            a = e + T->offset;
+        }
+
+        uint16_t *idx = (uint16_t *)malloc((size_t)(M > 0 ? M : 1) * sizeof(uint16_t));
+        float *val = (float *)malloc((size_t)(M > 0 ? M : 1) * sizeof(float));
+        uint8_t *code = (uint8_t *)calloc((size_t)(M > 0 ? M : 1), 1);
+        int bad = 0;
+#pragma omp parallel for schedule(dynamic, 16) reduction(| : bad)
+        for (int64_t c = 0; c < nc; ++c)
+            if (slo_topk_chunk(&L, tile, c, a, k, idx + c * k, val + c * k) < 0) bad |= 1;
+        if (bad) {
+            free(idx), free(val), free(code);
+            return SLO_ERR_ARG;
+        }
+
+        float lut[16] = {0};
+        if (bits != 32) slo_quantize_tensor_b(val, nc, k, bits, code, lut, NULL);
+
+        if (!ef_frozen)
+            for (int64_t c = 0; c < nc; ++c)
+                for (int m = 0; m < k; ++m) {
+                    int64_t i = slo_element_of(&L, tile, c, idx[c * k + m]);
+                    float sent = bits == 32 ? val[c * k + m] : lut[code[c * k + m]];
+                    e[T->offset + i] = a[i] - sent;
+                }
+
+        if (payload) {
+            uint8_t *blk = payload + pay_off;
+            memset(blk, 0, (size_t)slo_tensor_block_bytes_b(T, tile, k, bits));
+            memcpy(blk, lut, (size_t)4 * nb);
+            for (int64_t c = 0; c < nc; ++c)
+                slo_pack_record_b(idx + c * k, code + c * k, val + c * k, k, bits, blk + hdr + c * rec);
+        }
+        if (sel_idx) memcpy(sel_idx + chunk0 * k, idx, (size_t)M * sizeof(uint16_t));
+        if (sel_val) memcpy(sel_val + chunk0 * k, val, (size_t)M * sizeof(float));
+        if (sel_code) memcpy(sel_code + chunk0 * k, code, (size_t)M);
+        if (lut_out && nb) memcpy(lut_out + (size_t)nb * ti, lut, (size_t)4 * nb);
+        free(idx), free(val), free(code);
+        chunk0 += nc;
+        pay_off += slo_tensor_block_bytes_b(T, tile, k, bits);
+    }
+    return SLO_OK;
+}
+
+/* slo_decompress_avg_apply with a value width (same order of operations). */
+int slo_decompress_avg_apply_b(const slo_tensor *t, int nt, int tile, int k, int bits, float *theta,
+                               const uint8_t *const *payloads, int R, float lr)
+{
+    if (nt < 0 || tile < 1 || tile > 64 || !bits_ok(k, bits, tile) || R < 1) return SLO_ERR_ARG;
+    int C = tile * tile;
+    int nb = bits == 32 ? 0 : 1 << bits;
+    int64_t rec = slo_record_bytes_b(k, bits), hdr = slo_header_bytes_b(bits);
+    float invR = 1.0f / (float)R;
+    int64_t pay_off = 0;
+    int bad = 0;
+
+    for (int ti = 0; ti < nt; ++ti) {
+        const slo_tensor *T = &t[ti];
+        int64_t nc = slo_tensor_chunks(T, tile);
+#pragma omp parallel for schedule(dynamic, 16) reduction(| : bad)
+        for (int64_t c = 0; c < nc; ++c) {
+            float *acc = (float *)calloc((size_t)C, sizeof(float));
+            uint16_t *idx = (uint16_t *)malloc((size_t)k * sizeof(uint16_t));
+            uint8_t *code = (uint8_t *)calloc((size_t)k, 1);
+            float *val = (float *)calloc((size_t)k, sizeof(float));
+            for (int r = 0; r < R; ++r) {
+                const uint8_t *blk = payloads[r] + pay_off;
+                float lut[16] = {0};
+                memcpy(lut, blk, (size_t)4 * nb);
+                slo_unpack_record_b(blk + hdr + c * rec, k, bits, idx, code, val);
+                for (int m = 0; m < k; ++m) {
+                    if (idx[m] >= C) {
+                        bad |= 1;
+                        continue;
+                    }
+                    float sent = bits == 32 ? val[m] : lut[code[m]];
+                    acc[idx[m]] = acc[idx[m]] + sent;
+                }
+            }
+            for (int j = 0; j < C; ++j) {
+                int64_t i = slo_element_of(T, tile, c, j);
+                if (i < 0) continue;
+                theta[i] = fmaf(-lr, acc[j] * invR, theta[i]);
+            }
+            free(acc), free(idx), free(code), free(val);
+        }
+        pay_off += slo_tensor_block_bytes_b(T, tile, k, bits);
+    }
+    return bad ? SLO_ERR_PAYLOAD : SLO_OK;
+}
+
+int slo_decompress_dense_b(const slo_tensor *t, int nt, int tile, int k, int bits,
+                           const uint8_t *payload, float *out)
+{
+    if (!bits_ok(k, bits, tile)) return SLO_ERR_ARG;
+    int nb = bits == 32 ? 0 : 1 << bits;
+    int64_t rec = slo_record_bytes_b(k, bits), hdr = slo_header_bytes_b(bits), pay_off = 0;
+    uint16_t *idx = (uint16_t *)malloc((size_t)k * sizeof(uint16_t));
+    uint8_t *code = (uint8_t *)calloc((size_t)k, 1);
+    float *val = (float *)calloc((size_t)k, sizeof(float));
+    int status = SLO_OK;
+    for (int ti = 0; ti < nt && status == SLO_OK; ++ti) {
+        const slo_tensor *T = &t[ti];
+        int64_t nc = slo_tensor_chunks(T, tile);
+        float lut[16] = {0};
+        memcpy(lut, payload + pay_off, (size_t)4 * nb);
+        for (int64_t c = 0; c < nc && status == SLO_OK; ++c) {
+            slo_unpack_record_b(payload + pay_off + hdr + c * rec, k, bits, idx, code, val);
+            for (int m = 0; m < k; ++m) {
+                int64_t i = slo_element_of(T, tile, c, idx[m]);
+                if (i < 0) {
+                    status = SLO_ERR_PAYLOAD;
+                    break;
+                }
+                out[i] = bits == 32 ? val[m] : lut[code[m]];
+            }
+        }
+        pay_off += slo_tensor_block_bytes_b(T, tile, k, bits);
+    }
+    free(idx), free(code), free(val);
+    return status;
+}
+
 /* Well-formedness of a received payload (a receiver-side check, not a step of
  * the method): every record lists k strictly ascending positions, each of them
  * inside the tensor.  Returns SLO_OK or SLO_ERR_PAYLOAD. */
