@@ -84,6 +84,23 @@ typedef struct sl_plan sl_plan; /* opaque: chunk work list and per-tensor tables
 int sl_plan_create(const sl_tensor *tensors, int n_tensors, int k, sl_plan **out);
 int sl_plan_destroy(sl_plan *plan);
 
+/* sl_plan_create for another value width (the ablation "Effect of quantization
+ * on loss": 1-, 2-, 3- and 4-bit values and full precision).  value_bits is
+ * 1, 2, 3 or 4 - the quantizer of Section 4 with 2^bits uniform bins over
+ * [-6 sigma, 6 sigma]: bin q covers [c_q, c_(q+1)) sigma around the mean with
+ * c_j = 12 j / 2^bits - 6, end bins open-ended, per-bin centroid table - or 32:
+ * the selected fp32 values travel unquantized and the error update leaves an
+ * exact zero at every sent position.  Every other call works on such a plan
+ * with the sizes and formats that follow from its width, except the index coder
+ * (sl_rice_*: 2-bit plans only, INVALID_ARG otherwise).  Wire format: per
+ * tensor a header of 2^bits floats padded with zeros to 16 bytes (no header at
+ * 32), then per chunk the k 12-bit indices followed by the k codes as a
+ * little-endian stream of bits-wide fields, or by the k fp32 values; a record
+ * is 3k/2 + k*bits/8 bytes.  k must be a multiple of 8 unless value_bits is 2.
+ * value_bits = 2 is sl_plan_create. */
+int sl_plan_create_bits(const sl_tensor *tensors, int n_tensors, int k, int value_bits, sl_plan **out);
+int sl_plan_value_bits(const sl_plan *plan);       /* 1, 2, 3, 4 or 32; -1 for NULL   */
+
 int64_t sl_plan_num_chunks(const sl_plan *plan);   /* chunks in the whole list        */
 int64_t sl_plan_num_elements(const sl_plan *plan); /* sum of rows*cols                */
 /* Size of one worker's payload:  sum over tensors of align16(16 + chunks*7k/4).
@@ -168,6 +185,12 @@ int sl_payload_validate(sl_plan *plan, const void *payload, void *workspace, voi
  * out    out, device, n_chunks*7k/4 bytes */
 int sl_pack_indices(const uint16_t *idx, const uint8_t *codes, int64_t n_chunks, int k, void *out,
                     void *stream);
+/* The same for the other value widths of sl_plan_create_bits: codes (values
+ * below 2^value_bits) for value_bits 1..4, or `values` (device, float
+ * [n_chunks*k]) for value_bits 32; the unused one may be NULL.  Records are
+ * 3k/2 + k*value_bits/8 bytes, back to back. */
+int sl_pack_indices_bits(const uint16_t *idx, const uint8_t *codes, const float *values,
+                         int64_t n_chunks, int k, int value_bits, void *out, void *stream);
 
 /* Index coder (appendix "Compression of indices in Top-k": the indices of a
  * payload are compressed for transmission with sub-chunking and Rice coding;

@@ -29,7 +29,7 @@ EXPORTS = [
     "sl_decompress_avg_apply", "sl_pack_indices", "sl_strerror", "sl_last_hip_error",
     "sl_profile_begin", "sl_profile_end", "sl_residual_apply",
     "sl_rice_max_bytes", "sl_rice_encode", "sl_rice_decode", "sl_compress_params",
-    "sl_payload_validate",
+    "sl_payload_validate", "sl_plan_create_bits", "sl_plan_value_bits", "sl_pack_indices_bits",
 ]
 PROF_PHASES = ["select", "stats", "codes", "lut", "residual", "apply"]
 
@@ -62,6 +62,12 @@ def lib():
         vp, i64, i32, sz = C.c_void_p, C.c_int64, C.c_int, C.c_size_t
         L.sl_plan_create.restype = i32
         L.sl_plan_create.argtypes = [C.POINTER(SlTensor), i32, i32, C.POINTER(vp)]
+        L.sl_plan_create_bits.restype = i32
+        L.sl_plan_create_bits.argtypes = [C.POINTER(SlTensor), i32, i32, i32, C.POINTER(vp)]
+        L.sl_plan_value_bits.restype = i32
+        L.sl_plan_value_bits.argtypes = [vp]
+        L.sl_pack_indices_bits.restype = i32
+        L.sl_pack_indices_bits.argtypes = [vp, vp, vp, i64, i32, i32, vp, vp]
         L.sl_plan_destroy.restype = i32
         L.sl_plan_destroy.argtypes = [vp]
         L.sl_plan_num_chunks.restype = i64
@@ -129,6 +135,10 @@ class Plan:
         self.handle, self.k, self.n_tensors = handle, k, n_tensors
 
     @property
+    def value_bits(self) -> int:
+        return int(lib().sl_plan_value_bits(self.handle))
+
+    @property
     def num_chunks(self) -> int:
         return int(lib().sl_plan_num_chunks(self.handle))
 
@@ -172,6 +182,23 @@ def sl_plan_create(descs: Sequence[Sequence[int]], k: int) -> Plan:
     return Plan(h.value, int(k), len(descs))
 
 
+def sl_plan_create_bits(descs: Sequence[Sequence[int]], k: int, value_bits: int) -> Plan:
+    """sl_plan_create for payload values of 1, 2, 3, 4 bits or unquantized fp32 (32)."""
+    descs = list(descs)
+    arr = (SlTensor * max(1, len(descs)))()
+    for i, (r, c, off, lay) in enumerate(descs):
+        arr[i] = SlTensor(int(r), int(c), int(off), int(lay), 0)
+    h = C.c_void_p()
+    st = lib().sl_plan_create_bits(arr, len(descs), int(k), int(value_bits), C.byref(h))
+    if st:
+        raise SparseLoCoError("sl_plan_create_bits", st)
+    return Plan(h.value, int(k), len(descs))
+
+
+def sl_plan_value_bits(plan: Plan) -> int:
+    return plan.value_bits
+
+
 def sl_compress(plan: Plan, e: Optional[torch.Tensor], delta: torch.Tensor, beta: float,
                 payload: torch.Tensor, workspace: torch.Tensor, flags: int = SL_COMPRESS_DEFAULT,
                 pending: Optional[torch.Tensor] = None, stream=None) -> None:
@@ -206,6 +233,15 @@ def sl_pack_indices(idx: torch.Tensor, codes: torch.Tensor, n_chunks: int, k: in
                                int(n_chunks), int(k), _dev_ptr(out, torch.uint8), _stream_ptr(stream))
     if st:
         raise SparseLoCoError("sl_pack_indices", st)
+
+
+def sl_pack_indices_bits(idx: torch.Tensor, codes: Optional[torch.Tensor], values: Optional[torch.Tensor],
+                         n_chunks: int, k: int, value_bits: int, out: torch.Tensor, stream=None) -> None:
+    st = lib().sl_pack_indices_bits(_dev_ptr(idx, torch.uint16), _dev_ptr(codes, torch.uint8),
+                                    _dev_ptr(values, torch.float32), int(n_chunks), int(k),
+                                    int(value_bits), _dev_ptr(out, torch.uint8), _stream_ptr(stream))
+    if st:
+        raise SparseLoCoError("sl_pack_indices_bits", st)
 
 
 def alloc_payload(plan: Plan, device="cuda") -> torch.Tensor:

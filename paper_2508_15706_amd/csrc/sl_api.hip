@@ -45,12 +45,23 @@ const char *sl_last_hip_error(void) { return g_hip_error; }
 
 int sl_plan_create(const sl_tensor *tensors, int n_tensors, int k, sl_plan **out)
 {
+    return sl_plan_create_bits(tensors, n_tensors, k, 2, out);
+}
+
+int sl_plan_value_bits(const sl_plan *p) { return p ? p->bits : -1; }
+
+int sl_plan_create_bits(const sl_tensor *tensors, int n_tensors, int k, int value_bits, sl_plan **out)
+{
     if (!out) return SL_ERR_INVALID_ARG;
     *out = nullptr;
     if (n_tensors < 0 || (n_tensors > 0 && !tensors)) return SL_ERR_INVALID_ARG;
     if (k < 4 || k > SL_CHUNK || (k & 3)) return SL_ERR_INVALID_ARG;
+    const int bits = value_bits;
+    if (!(bits == 1 || bits == 2 || bits == 3 || bits == 4 || bits == 32)) return SL_ERR_INVALID_ARG;
+    if (bits != 2 && (k & 7)) return SL_ERR_INVALID_ARG;   // records must end on a byte
 
-    const int64_t rec = (int64_t)7 * k / 4;
+    const int64_t rec = sl_rec_bytes(k, bits), hdr = sl_hdr_bytes(bits);
+    const int nbins = bits == 32 ? 0 : 1 << bits;
     std::vector<SlChunkDesc> desc;
     std::vector<SlTensorDev> tdev((size_t)n_tensors);
     std::vector<SlGroup> groups;
@@ -96,7 +107,7 @@ int sl_plan_create(const sl_tensor *tensors, int n_tensors, int k, sl_plan **out
                         d.flags = (rv == 64 && cv == 64 && (T.cols & 3) == 0) ? SLC_FULL : 0;
                         d.tensor = t;
                         d.local_chunk = (int)(a * tc + b);
-                        d.rec_off = (long long)pay + 16 + (long long)d.local_chunk * rec;
+                        d.rec_off = (long long)pay + hdr + (long long)d.local_chunk * rec;
                         desc.push_back(d);
                     }
             } else {
@@ -113,13 +124,13 @@ int sl_plan_create(const sl_tensor *tensors, int n_tensors, int k, sl_plan **out
                     d.flags = nv == SL_CHUNK ? SLC_FULL : 0;
                     d.tensor = t;
                     d.local_chunk = (int)a;
-                    d.rec_off = (long long)pay + 16 + (long long)d.local_chunk * rec;
+                    d.rec_off = (long long)pay + hdr + (long long)d.local_chunk * rec;
                     desc.push_back(d);
                 }
             }
             D.n_chunks = (long long)desc.size() - D.chunk0;
             D.pay_off = (long long)pay;
-            D.block_bytes = (long long)align_up((size_t)(16 + D.n_chunks * rec), 16);
+            D.block_bytes = (long long)align_up((size_t)(hdr + D.n_chunks * rec), 16);
             D.group0 = (long long)groups.size();
             for (long long g = 0; g * SL_RICE_GROUP < D.n_chunks; ++g) groups.push_back(SlGroup{t, (int)g});
             pay += (size_t)D.block_bytes;
@@ -135,6 +146,9 @@ int sl_plan_create(const sl_tensor *tensors, int n_tensors, int k, sl_plan **out
     if (!p) return SL_ERR_NOMEM;
     std::memset(p, 0, sizeof(*p));
     p->k = k;
+    p->bits = bits;
+    p->rec_bytes = (int)rec;
+    p->hdr_bytes = (int)hdr;
     p->n_tensors = n_tensors;
     p->n_chunks = (int64_t)desc.size();
     p->n_elements = n_elements;
@@ -144,8 +158,8 @@ int sl_plan_create(const sl_tensor *tensors, int n_tensors, int k, sl_plan **out
     size_t off = 0;
     p->ws_vals = off;   off = align_up(off + (size_t)p->n_chunks * k * sizeof(float), 256);
     p->ws_leafA = off;  off = align_up(off + (size_t)p->n_chunks * 2 * sizeof(double), 256);
-    p->ws_leafC = off;  off = align_up(off + (size_t)p->n_chunks * 4 * sizeof(double), 256);
-    p->ws_cnt = off;    off = align_up(off + (size_t)p->n_chunks * 4 * sizeof(unsigned), 256);
+    p->ws_leafC = off;  off = align_up(off + (size_t)p->n_chunks * nbins * sizeof(double), 256);
+    p->ws_cnt = off;    off = align_up(off + (size_t)p->n_chunks * nbins * sizeof(unsigned), 256);
     p->ws_tstat = off;  off = align_up(off + (size_t)n_tensors * sizeof(SlTensorStat), 256);
     p->ws_bytes = off ? off : 256;
     p->n_groups = (int64_t)groups.size();
@@ -278,12 +292,12 @@ int sl_compress_params(sl_plan *p, float *e, const float *theta_outer, const flo
     return compress_impl(p, e, theta_outer, theta_local, beta, flags, pending, payload, workspace, stream);
 }
 
-size_t sl_rice_max_bytes(const sl_plan *p) { return p ? p->rice_max_bytes : 0; }
+size_t sl_rice_max_bytes(const sl_plan *p) { return p && p->bits == 2 ? p->rice_max_bytes : 0; }
 
 int sl_rice_encode(sl_plan *p, const void *payload, void *out, size_t out_capacity, void *workspace,
                    void *stream)
 {
-    if (!p || !payload || !out || !workspace) return SL_ERR_INVALID_ARG;
+    if (!p || !payload || !out || !workspace || p->bits != 2) return SL_ERR_INVALID_ARG;
     if (out_capacity < p->rice_max_bytes || payload == out) return SL_ERR_INVALID_ARG;
     if (misaligned(payload, 16) || misaligned(out, 16) || misaligned(workspace, 256))
         return SL_ERR_INVALID_ARG;
@@ -295,7 +309,7 @@ int sl_rice_encode(sl_plan *p, const void *payload, void *out, size_t out_capaci
 
 int sl_rice_decode(sl_plan *p, const void *in, size_t in_bytes, void *payload, void *stream)
 {
-    if (!p || !in || !payload || in == payload) return SL_ERR_INVALID_ARG;
+    if (!p || !in || !payload || in == payload || p->bits != 2) return SL_ERR_INVALID_ARG;
     if (in_bytes < 16 + 8 * (size_t)p->n_tensors) return SL_ERR_INVALID_ARG;
     if (misaligned(in, 16) || misaligned(payload, 16)) return SL_ERR_INVALID_ARG;
     int rc = check_device(p);
@@ -337,6 +351,17 @@ int sl_decompress_avg_apply(sl_plan *p, float *theta, const void *const *payload
     rc = slk_apply(p, theta, payloads, R, lr, static_cast<hipStream_t>(stream));
     sl_prof_mark(p, SL_PROF_APPLY, static_cast<hipStream_t>(stream));
     return rc;
+}
+
+int sl_pack_indices_bits(const uint16_t *idx, const uint8_t *codes, const float *values, int64_t n_chunks,
+                         int k, int value_bits, void *out, void *stream)
+{
+    const int bits = value_bits;
+    if (!(bits == 1 || bits == 2 || bits == 3 || bits == 4 || bits == 32)) return SL_ERR_INVALID_ARG;
+    if (n_chunks < 0 || k < 4 || k > SL_CHUNK || (k & 3) || (bits != 2 && (k & 7))) return SL_ERR_INVALID_ARG;
+    if (n_chunks > 0 && (!idx || !out || (bits == 32 ? !values : !codes))) return SL_ERR_INVALID_ARG;
+    return slk_pack_bits(idx, codes, values, n_chunks, k, bits, static_cast<unsigned char *>(out),
+                         static_cast<hipStream_t>(stream));
 }
 
 int sl_pack_indices(const uint16_t *idx, const uint8_t *codes, int64_t n_chunks, int k, void *out,

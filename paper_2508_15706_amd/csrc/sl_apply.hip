@@ -19,6 +19,7 @@ struct ApplyArgs {
     float *theta;
     float neg_lr, inv_R;
     int R, k;
+    int bits, hdr_bytes, rec_bytes;   // value width and the sizes that follow from it
     int batch;               // records staged per round
     int lds_per_wave;
     long long n_chunks;
@@ -26,6 +27,9 @@ struct ApplyArgs {
 };
 
 // One wave per chunk, several independent waves (adjacent chunks) per workgroup.
+// TWO_BIT: the 2-bit format with its four-entry table kept in registers;
+// otherwise any width (table of 2^bits entries read from LDS, or fp32 values).
+template <bool TWO_BIT>
 __global__ void __launch_bounds__(256) k_apply(ApplyArgs A)
 {
     extern __shared__ __align__(16) unsigned char smem_all[];
@@ -37,23 +41,25 @@ __global__ void __launch_bounds__(256) k_apply(ApplyArgs A)
     float *acc = reinterpret_cast<float *>(smem);                    // 4096 floats
     unsigned char *stage = smem + SL_CHUNK * sizeof(float);
     const SlChunkDesc d = A.desc[c];
-    const int rec_bytes = 7 * k / 4;
-    const int rec_pad = ((rec_bytes + 3) & ~3) + 16;                 // staging pitch: LUT + record
-    const long long rec_off = d.rec_off, lut_off = sl_lut_off(d, k);
+    const int bits = TWO_BIT ? 2 : A.bits;
+    const int hdr = TWO_BIT ? 16 : A.hdr_bytes, hdr_words = hdr >> 2;
+    const int rec_bytes = TWO_BIT ? 7 * k / 4 : A.rec_bytes;
+    const int rec_pad = ((rec_bytes + 3) & ~3) + hdr;                // staging pitch: LUT + record
+    const long long rec_off = d.rec_off, lut_off = sl_lut_off(d, hdr, rec_bytes);
 
     float *tc = A.theta + d.base;
     const int lr = lane >> 4, lc = (lane & 15) * 4;
     const unsigned stride = (unsigned)d.stride;
     const bool full = d.flags & SLC_FULL;
 
-    // Word w of a batch's staging area: worker r = w / wpr_src, word q of (LUT[4], record)
+    // Word w of a batch's staging area: worker r = w / wpr_src, word q of (LUT, record)
     const bool word_path = (rec_bytes & 3) == 0;
-    const int wpr_src = 4 + (rec_bytes >> 2);          // words per worker: LUT + record
+    const int wpr_src = hdr_words + (rec_bytes >> 2);  // words per worker: LUT + record
     const int wpr_dst = rec_pad >> 2;
     auto src_word = [&](int r, int q) -> unsigned {
         const unsigned char *p = A.payload[r];
-        return q < 4 ? reinterpret_cast<const unsigned *>(p + lut_off)[q]
-                     : reinterpret_cast<const unsigned *>(p + rec_off)[q - 4];
+        return q < hdr_words ? reinterpret_cast<const unsigned *>(p + lut_off)[q]
+                             : reinterpret_cast<const unsigned *>(p + rec_off)[q - hdr_words];
     };
     // The first 256 words of the first batch (all of it for R*7k/4 <= ~900 bytes) are
     // fetched into registers BEFORE the theta loads: loads complete in order, so
@@ -106,27 +112,36 @@ __global__ void __launch_bounds__(256) k_apply(ApplyArgs A)
                 reinterpret_cast<unsigned *>(stage)[r * wpr_dst + q] = src_word(r0 + r, q);
             }
         } else {
-            for (int w = lane; w < nb * 4; w += 64) {                // the tensor's LUT of each worker
-                const int r = w >> 2, q = w & 3;
+            for (int w = lane; w < nb * hdr_words; w += 64) {        // the tensor's LUT of each worker
+                const int r = w / hdr_words, q = w - r * hdr_words;
                 reinterpret_cast<unsigned *>(stage)[r * wpr_dst + q] =
                     reinterpret_cast<const unsigned *>(A.payload[r0 + r] + lut_off)[q];
             }
             for (int b = lane; b < nb * rec_bytes; b += 64) {
                 const int r = b / rec_bytes, q = b - r * rec_bytes;
-                stage[r * rec_pad + 16 + q] = A.payload[r0 + r][rec_off + q];
+                stage[r * rec_pad + hdr + q] = A.payload[r0 + r][rec_off + q];
             }
         }
         sl_wave_sync();
         for (int r = 0; r < nb; ++r) {
-            const float4 lut = *reinterpret_cast<const float4 *>(stage + r * rec_pad);
-            const unsigned char *rec = stage + r * rec_pad + 16;
-            const unsigned char *codes = rec + 3 * k / 2;
+            const float *lutp = reinterpret_cast<const float *>(stage + r * rec_pad);
+            float4 lut = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (TWO_BIT) lut = *reinterpret_cast<const float4 *>(lutp);
+            const unsigned char *rec = stage + r * rec_pad + hdr;
+            const unsigned char *codes = rec + 3 * k / 2;   // or the k fp32 values (4-byte aligned)
             for (int m = lane; m < k; m += 64) {
                 const int b = (3 * m) >> 1;
                 const unsigned w = (unsigned)rec[b] | ((unsigned)rec[b + 1] << 8);
                 const unsigned j = (m & 1) ? (w >> 4) : (w & 0xFFFu);
-                const unsigned code = (codes[m >> 2] >> (2 * (m & 3))) & 3u;
-                const float q = code == 0 ? lut.x : code == 1 ? lut.y : code == 2 ? lut.z : lut.w;
+                float q;
+                if (TWO_BIT) {
+                    const unsigned code = (codes[m >> 2] >> (2 * (m & 3))) & 3u;
+                    q = code == 0 ? lut.x : code == 1 ? lut.y : code == 2 ? lut.z : lut.w;
+                } else if (bits == 32) {
+                    q = reinterpret_cast<const float *>(codes)[m];
+                } else {
+                    q = lutp[sl_code_at(codes, m, bits)];
+                }
                 acc[j] = acc[j] + q;
             }
             sl_wave_sync();           // worker r is complete before worker r+1 is added
@@ -216,7 +231,60 @@ k_pack(const uint16_t *idx, const uint8_t *codes, long long n_chunks, int k, uns
     }
 }
 
+// Record encoder for any value width: one thread per output byte; the tail of
+// a record is a little-endian stream of `bits`-wide codes, or the fp32 values.
+__global__ void __launch_bounds__(256)
+k_pack_bits(const uint16_t *idx, const uint8_t *codes, const float *values, long long n_chunks, int k,
+            int bits, unsigned char *out)
+{
+    const long long rec_bytes = sl_rec_bytes(k, bits);
+    const long long total = n_chunks * rec_bytes;
+    const int nidx = 3 * k / 2;
+    for (long long o = (long long)blockIdx.x * blockDim.x + threadIdx.x; o < total;
+         o += (long long)gridDim.x * blockDim.x) {
+        const long long c = o / rec_bytes;
+        const int b = (int)(o - c * rec_bytes);
+        unsigned v;
+        if (b < nidx) {
+            const int bit0 = 8 * b, m = bit0 / 12, sh = bit0 - 12 * m;
+            v = ((unsigned)idx[c * k + m] & 0xFFFu) >> sh;
+            if (sh == 8 && m + 1 < k) v |= ((unsigned)idx[c * k + m + 1] & 0xFFFu) << 4;
+        } else if (bits == 32) {
+            const int q = b - nidx;
+            v = __float_as_uint(values[c * k + (q >> 2)]) >> (8 * (q & 3));
+        } else {
+            // fields that overlap byte b - nidx of the code stream
+            const int bit0 = 8 * (b - nidx);
+            const unsigned mask = (1u << bits) - 1u;
+            v = 0;
+            for (int m = bit0 / bits; m < k && m * bits < bit0 + 8; ++m) {
+                const int sh = m * bits - bit0;
+                const unsigned cde = (unsigned)codes[c * k + m] & mask;
+                v |= sh >= 0 ? cde << sh : cde >> (-sh);
+            }
+        }
+        out[o] = (unsigned char)v;
+    }
+}
+
 }  // namespace
+
+int slk_pack_bits(const uint16_t *idx, const uint8_t *codes, const float *values, int64_t n_chunks, int k,
+                  int bits, unsigned char *out, hipStream_t st)
+{
+    const long long total = n_chunks * (long long)sl_rec_bytes(k, bits);
+    if (total == 0) return SL_OK;
+    long long blocks = (total + 255) / 256;
+    if (blocks > 65536) blocks = 65536;
+    hipLaunchKernelGGL(k_pack_bits, dim3((unsigned)blocks), dim3(256), 0, st, idx, codes, values,
+                       (long long)n_chunks, k, bits, out);
+    hipError_t err = hipGetLastError();
+    if (err != hipSuccess) {
+        sl_note_hip_error(err);
+        return SL_ERR_HIP;
+    }
+    return SL_OK;
+}
 
 int slk_apply(const sl_plan *p, float *theta, const void *const *payloads, int R, float lr,
               hipStream_t st)
@@ -229,7 +297,10 @@ int slk_apply(const sl_plan *p, float *theta, const void *const *payloads, int R
     A.inv_R = 1.0f / (float)R;
     A.R = R;
     A.k = p->k;
-    const int rec_pad = ((7 * p->k / 4 + 3) & ~3) + 16;
+    A.bits = p->bits;
+    A.hdr_bytes = p->hdr_bytes;
+    A.rec_bytes = p->rec_bytes;
+    const int rec_pad = ((p->rec_bytes + 3) & ~3) + p->hdr_bytes;
     int batch = 16384 / rec_pad;          // at most 16 KB of staged records
     if (batch < 1) batch = 1;
     if (batch > R) batch = R;
@@ -241,15 +312,18 @@ int slk_apply(const sl_plan *p, float *theta, const void *const *payloads, int R
     int wpb = 4;
     while (wpb > 1 && (size_t)A.lds_per_wave * wpb > (size_t)p->max_lds) wpb >>= 1;
     const size_t lds = (size_t)A.lds_per_wave * wpb;
+    const void *fn = p->bits == 2 ? reinterpret_cast<const void *>(k_apply<true>)
+                                  : reinterpret_cast<const void *>(k_apply<false>);
     if (lds > 65536) {
-        hipError_t aerr = hipFuncSetAttribute(reinterpret_cast<const void *>(k_apply),
-                                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        hipError_t aerr = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (aerr != hipSuccess) {
             sl_note_hip_error(aerr);
             return SL_ERR_HIP;
         }
     }
-    hipLaunchKernelGGL(k_apply, dim3((unsigned)((p->n_chunks + wpb - 1) / wpb)), dim3(64 * wpb), lds, st, A);
+    const dim3 grid((unsigned)((p->n_chunks + wpb - 1) / wpb)), block(64 * wpb);
+    if (p->bits == 2) hipLaunchKernelGGL(k_apply<true>, grid, block, lds, st, A);
+    else hipLaunchKernelGGL(k_apply<false>, grid, block, lds, st, A);
     hipError_t err = hipGetLastError();
     if (err != hipSuccess) {
         sl_note_hip_error(err);

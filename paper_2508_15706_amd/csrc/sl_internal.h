@@ -39,13 +39,31 @@ struct SlGroup {            // one coding group of the index coder
 // Per-tensor quantizer state produced during sl_compress.
 struct SlTensorStat {
     double mu;      // mean of the selected values
-    double T;       // 9 * variance: squared distance of the outer bin edges from the mean
-    float lut[4];   // centroids
+    double var;     // their population variance (bin edges sit at multiples of sigma)
 };
-static_assert(sizeof(SlTensorStat) == 32, "");
+static_assert(sizeof(SlTensorStat) == 16, "");
+
+// Sizes of the wire format for `bits` value bits (1..4, or 32 = unquantized
+// fp32 values): look-up table header of a tensor block and one chunk record.
+__host__ __device__ inline int sl_hdr_bytes(int bits)
+{
+    return bits == 32 ? 0 : ((4 << bits) < 16 ? 16 : (4 << bits));
+}
+__host__ __device__ inline int sl_rec_bytes(int k, int bits) { return 3 * k / 2 + k * bits / 8; }
+
+// Code of entry m in a little-endian stream of `bits`-wide fields (bits <= 4).
+__host__ __device__ inline unsigned sl_code_at(const unsigned char *codes, int m, int bits)
+{
+    const int bit = m * bits, sh = bit & 7;
+    unsigned w = codes[bit >> 3];
+    if (sh + bits > 8) w |= (unsigned)codes[(bit >> 3) + 1] << 8;
+    return (w >> sh) & ((1u << bits) - 1u);
+}
 
 struct sl_plan {
     int k;
+    int bits;                   // value bits: 1..4, or 32 for unquantized fp32 values
+    int rec_bytes, hdr_bytes;   // sl_rec_bytes(k, bits), sl_hdr_bytes(bits)
     int n_tensors;
     int device;
     int max_lds;                // largest LDS allocation of one workgroup, bytes
@@ -69,9 +87,9 @@ struct sl_plan {
 };
 
 // Byte offset of the LUT header of the chunk's tensor block inside a payload.
-__host__ __device__ inline long long sl_lut_off(const SlChunkDesc &d, int k)
+__host__ __device__ inline long long sl_lut_off(const SlChunkDesc &d, int hdr_bytes, int rec_bytes)
 {
-    return d.rec_off - 16 - (long long)d.local_chunk * ((long long)7 * k / 4);
+    return d.rec_off - hdr_bytes - (long long)d.local_chunk * rec_bytes;
 }
 
 // Records an event after the kernel of `phase` (phase < 0: start of a call).
@@ -91,6 +109,8 @@ int slk_apply(const sl_plan *p, float *theta, const void *const *payloads, int R
 int slk_validate(const sl_plan *p, const unsigned char *payload, int *flag, hipStream_t st);
 int slk_pack(const uint16_t *idx, const uint8_t *codes, int64_t n_chunks, int k, unsigned char *out,
              hipStream_t st);
+int slk_pack_bits(const uint16_t *idx, const uint8_t *codes, const float *values, int64_t n_chunks, int k,
+                  int bits, unsigned char *out, hipStream_t st);
 int slk_rice_encode(const sl_plan *p, const unsigned char *payload, unsigned char *out,
                     unsigned char *ws, hipStream_t st);
 int slk_rice_decode(const sl_plan *p, const unsigned char *in, size_t in_bytes, unsigned char *payload,

@@ -3,7 +3,7 @@
 // line 2, Algorithm 1 error update).
 //
 //   B  per tensor: fixed-tree fp64 sums of x and x*x over its selected values
-//      -> mean mu and T = 9*var (squared distance of the outer bin edges);
+//      -> mean mu and variance;
 //   C  per chunk: 2-bit codes from (x - mu)^2 vs T, codes packed into the
 //      payload record, per-bin partial sums and counts;
 //   D  per tensor: fixed-tree sums per bin -> centroid LUT, written as the
@@ -105,7 +105,7 @@ k_tensor_stats(const SlTensorDev *tensors, const double *leafA, long long n_chun
         double var = q - p;
         if (var < 0.0) var = 0.0;
         tstat[blockIdx.x].mu = mu;
-        tstat[blockIdx.x].T = 9.0 * var;
+        tstat[blockIdx.x].var = var;
     }
 }
 
@@ -167,7 +167,7 @@ __global__ void __launch_bounds__(64 * CODE_WAVES, 2) k_codes(CodeArgs A)
     if (live) {
         const SlChunkDesc d = A.desc[c];
         mu = A.tstat[d.tensor].mu;
-        T = A.tstat[d.tensor].T;
+        T = 9.0 * A.tstat[d.tensor].var;      // squared distance of the outer edges (3 sigma)
         codes_out = A.payload + d.rec_off + 3 * k / 2;
     }
 
@@ -230,12 +230,122 @@ __global__ void __launch_bounds__(64 * CODE_WAVES, 2) k_codes(CodeArgs A)
     }
 }
 
+// ------------------------------------------------------------------ kernel C, other widths
+// The same quantizer with 2^BITS uniform bins over [-6 sigma, 6 sigma] (the
+// paper's quantization ablation: 1, 3 and 4 bits).  Bin q is
+// [c_q, c_(q+1)) sigma around the mean with c_j = 12 j / 2^BITS - 6, the end
+// bins open-ended; the code is the number of inner edges the value has
+// reached, each edge decided on squares against (c_j * c_j) * var.  The bins
+// are handled four at a time (one pass over the chunk's values per group of
+// four), so that the per-bin tree stacks stay in registers.
+template <int BITS>
+SL_DEV int code_of(double dlt, double var)
+{
+    constexpr int NB = 1 << BITS;
+    const double dd = dlt * dlt;
+    int code = 0;
+#pragma unroll
+    for (int j = 1; j < NB; ++j) {
+        const double cj = 12.0 * (double)j / (double)NB - 6.0;   // exact in fp64
+        const double Tj = (cj * cj) * var;
+        bool reached;
+        if (cj < 0.0) reached = dlt >= 0.0 || dd <= Tj;
+        else if (cj == 0.0) reached = dlt >= 0.0;
+        else reached = dlt >= 0.0 && dd >= Tj;
+        code += reached ? 1 : 0;
+    }
+    return code;
+}
+
+template <int BITS>
+__global__ void __launch_bounds__(64 * CODE_WAVES, 2) k_codes_b(CodeArgs A)
+{
+    constexpr int NB = 1 << BITS;
+    constexpr int PASSES = (NB + 3) / 4;
+    __shared__ float tile_all[CODE_WAVES][64 * CODE_PITCH];
+    const int lane = threadIdx.x & 63, k = A.k;
+    const int wave = sl_uniform((int)(threadIdx.x >> 6));
+    const long long c0 = ((long long)blockIdx.x * CODE_WAVES + wave) * 64;
+    if (c0 >= A.n_chunks) return;
+    float *tile = tile_all[wave];
+    const long long c = c0 + lane;
+    const bool live = c < A.n_chunks;
+
+    double mu = 0.0, var = 0.0;
+    unsigned char *codes_out = nullptr;
+    if (live) {
+        const SlChunkDesc d = A.desc[c];
+        mu = A.tstat[d.tensor].mu;
+        var = A.tstat[d.tensor].var;
+        codes_out = A.payload + d.rec_off + 3 * k / 2;
+    }
+    int P = 1, top = 0;
+    while (P < k) P <<= 1, ++top;
+    const int lr = lane >> 4, lc = (lane & 15) * 4;
+
+    for (int pass = 0; pass < PASSES; ++pass) {
+        const int q0 = 4 * pass;
+        BinStacks st;
+#pragma unroll
+        for (int l = 0; l < 13; ++l) st.a[l] = st.b[l] = st.c[l] = st.d[l] = 0.0;
+        unsigned n_b[4] = {0u, 0u, 0u, 0u};
+        unsigned long long bitbuf = 0;          // codes of 8 entries = BITS bytes
+        for (int s0 = 0; s0 < k; s0 += 64) {
+            const int ncol = min(64, k - s0);
+            sl_wave_sync();
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const int row = 4 * i + lr;
+                if (c0 + row < A.n_chunks && lc < ncol) {
+                    const float4 v = *reinterpret_cast<const float4 *>(A.vals + (c0 + row) * k + s0 + lc);
+                    float *t = tile + row * CODE_PITCH + lc;
+                    t[0] = v.x, t[1] = v.y, t[2] = v.z, t[3] = v.w;
+                }
+            }
+            sl_wave_sync();
+            for (int col = 0; col < ncol; ++col) {
+                const int m = s0 + col;
+                const double x = (double)tile[lane * CODE_PITCH + col];
+                const int code = code_of<BITS>(x - mu, var);
+                const int rel = code - q0;
+                n_b[0] += rel == 0, n_b[1] += rel == 1, n_b[2] += rel == 2, n_b[3] += rel == 3;
+                stack_push<0>(st, m, rel == 0 ? x : 0.0, rel == 1 ? x : 0.0, rel == 2 ? x : 0.0,
+                              rel == 3 ? x : 0.0);
+                if (pass == 0) {
+                    bitbuf |= (unsigned long long)code << (BITS * (m & 7));
+                    if ((m & 7) == 7) {         // k is a multiple of 8
+                        if (live) {
+#pragma unroll
+                            for (int q = 0; q < BITS; ++q)
+                                codes_out[(m >> 3) * BITS + q] = (unsigned char)(bitbuf >> (8 * q));
+                        }
+                        bitbuf = 0;
+                    }
+                }
+            }
+        }
+        for (int m = k; m < P; ++m) stack_push<0>(st, m, 0.0, 0.0, 0.0, 0.0);
+        if (live) {
+            double r[4] = {st.a[0], st.b[0], st.c[0], st.d[0]};
+#pragma unroll
+            for (int l = 1; l < 13; ++l)
+                if (top == l) r[0] = st.a[l], r[1] = st.b[l], r[2] = st.c[l], r[3] = st.d[l];
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+                if (q0 + q < NB) {
+                    A.leafC[(long long)(q0 + q) * A.n_chunks + c] = r[q];
+                    A.cnt[(long long)(q0 + q) * A.n_chunks + c] = n_b[q];
+                }
+        }
+    }
+}
+
 // ------------------------------------------------------------------ kernel D
 // One workgroup per (tensor, bin): fixed-tree sum of the bin's leaves, integer
 // count, centroid -> LUT[b] in the tensor block's header.
 __global__ void __launch_bounds__(RED_THREADS)
 k_tensor_lut(const SlTensorDev *tensors, const double *leafC, const unsigned *cnt,
-             long long n_chunks_total, int k, unsigned char *payload)
+             long long n_chunks_total, int hdr_bytes, int rec_bytes, int nbins, unsigned char *payload)
 {
     __shared__ RedShared sh;
     const SlTensorDev td = tensors[blockIdx.x];
@@ -257,9 +367,19 @@ k_tensor_lut(const SlTensorDev *tensors, const double *leafC, const unsigned *cn
         if (cen == 0.0f) cen = 0.0f;        // never -0.0f on the wire
         reinterpret_cast<float *>(payload + td.pay_off)[b] = cen;
     }
-    // zero the padding that rounds the tensor block up to 16 bytes
-    const long long used = 16 + td.n_chunks * ((long long)7 * k / 4);
+    // zero the padding that rounds the header (two floats at 1 bit) and the tensor block up to 16 bytes
+    if (b == 0 && tid >= nbins && 4 * tid < hdr_bytes) reinterpret_cast<float *>(payload + td.pay_off)[tid] = 0.0f;
+    const long long used = hdr_bytes + td.n_chunks * (long long)rec_bytes;
     if (b == 0 && tid < td.block_bytes - used) payload[td.pay_off + used + tid] = 0;
+}
+
+// Unquantized values: there is no table, only the block padding is left to write.
+__global__ void __launch_bounds__(64)
+k_pad_blocks(const SlTensorDev *tensors, int rec_bytes, unsigned char *payload)
+{
+    const SlTensorDev td = tensors[blockIdx.x];
+    const long long used = td.n_chunks * (long long)rec_bytes;
+    if ((long long)threadIdx.x < td.block_bytes - used) payload[td.pay_off + used + threadIdx.x] = 0;
 }
 
 // ------------------------------------------------------------------ kernel E
@@ -269,7 +389,7 @@ struct ResidualArgs {
     const unsigned char *payload;
     float *e;
     long long n_chunks;
-    int k;
+    int k, bits, hdr_bytes, rec_bytes;
 };
 
 __global__ void __launch_bounds__(256) k_residual(ResidualArgs A)
@@ -279,16 +399,16 @@ __global__ void __launch_bounds__(256) k_residual(ResidualArgs A)
     const long long c = (long long)blockIdx.x * (blockDim.x >> 6) + wave;
     if (c >= A.n_chunks) return;
     const SlChunkDesc d = A.desc[c];
-    const float4 lut = *reinterpret_cast<const float4 *>(A.payload + sl_lut_off(d, k));
+    const float *lut = reinterpret_cast<const float *>(A.payload + sl_lut_off(d, A.hdr_bytes, A.rec_bytes));
     const unsigned char *rec = A.payload + d.rec_off;
-    const unsigned char *codes = rec + 3 * k / 2;
+    const unsigned char *codes = rec + 3 * k / 2;       // or the k fp32 values (4-byte aligned)
     float *ec = A.e + d.base;
     for (int m = lane; m < k; m += 64) {
         const int b = (3 * m) >> 1;
         const unsigned w = (unsigned)rec[b] | ((unsigned)rec[b + 1] << 8);
         const unsigned j = (m & 1) ? (w >> 4) : (w & 0xFFFu);
-        const unsigned code = (codes[m >> 2] >> (2 * (m & 3))) & 3u;
-        const float q = code == 0 ? lut.x : code == 1 ? lut.y : code == 2 ? lut.z : lut.w;
+        const float q = A.bits == 32 ? reinterpret_cast<const float *>(codes)[m]
+                                     : lut[sl_code_at(codes, m, A.bits)];
         float *dst = ec + ((j >> 6) * (unsigned)d.stride + (j & 63u));
         const float a = A.vals ? A.vals[c * k + m] : *dst;
         *dst = a - q;
@@ -316,6 +436,9 @@ static int launch_residual(const sl_plan *p, float *e, const float *vals, const 
     R.payload = payload;
     R.e = e;
     R.k = p->k;
+    R.bits = p->bits;
+    R.hdr_bytes = p->hdr_bytes;
+    R.rec_bytes = p->rec_bytes;
     R.n_chunks = p->n_chunks;
     const int wpb = 4;
     const unsigned nblk = (unsigned)((p->n_chunks + wpb - 1) / wpb);
@@ -341,6 +464,19 @@ int slk_quantize(const sl_plan *p, float *e, int skip_residual, unsigned char *p
     SlTensorStat *tstat = reinterpret_cast<SlTensorStat *>(ws + p->ws_tstat);
     int rc;
 
+    if (p->bits == 32) {
+        // nothing to quantize: kernel A wrote the values into the records
+        hipLaunchKernelGGL(k_pad_blocks, dim3(p->n_tensors), dim3(64), 0, st, p->d_tensors, p->rec_bytes,
+                           payload);
+        if ((rc = check_launch())) return rc;
+        sl_prof_mark(p, SL_PROF_LUT, st);
+        if (!skip_residual) {
+            if ((rc = launch_residual(p, e, vals, payload, st))) return rc;
+            sl_prof_mark(p, SL_PROF_RESIDUAL, st);
+        }
+        return SL_OK;
+    }
+
     hipLaunchKernelGGL(k_tensor_stats, dim3(p->n_tensors), dim3(RED_THREADS), 0, st, p->d_tensors,
                        leafA, (long long)p->n_chunks, k, tstat);
     if ((rc = check_launch())) return rc;
@@ -357,12 +493,18 @@ int slk_quantize(const sl_plan *p, float *e, int skip_residual, unsigned char *p
     C.k = k;
     const long long per_block = 64ll * CODE_WAVES;
     const unsigned nblk = (unsigned)((p->n_chunks + per_block - 1) / per_block);
-    hipLaunchKernelGGL(k_codes, dim3(nblk), dim3(64 * CODE_WAVES), 0, st, C);
+    switch (p->bits) {
+        case 1: hipLaunchKernelGGL(k_codes_b<1>, dim3(nblk), dim3(64 * CODE_WAVES), 0, st, C); break;
+        case 3: hipLaunchKernelGGL(k_codes_b<3>, dim3(nblk), dim3(64 * CODE_WAVES), 0, st, C); break;
+        case 4: hipLaunchKernelGGL(k_codes_b<4>, dim3(nblk), dim3(64 * CODE_WAVES), 0, st, C); break;
+        default: hipLaunchKernelGGL(k_codes, dim3(nblk), dim3(64 * CODE_WAVES), 0, st, C); break;
+    }
     if ((rc = check_launch())) return rc;
     sl_prof_mark(p, SL_PROF_CODES, st);
 
-    hipLaunchKernelGGL(k_tensor_lut, dim3(p->n_tensors, 4), dim3(RED_THREADS), 0, st, p->d_tensors,
-                       leafC, cnt, (long long)p->n_chunks, k, payload);
+    hipLaunchKernelGGL(k_tensor_lut, dim3(p->n_tensors, 1 << p->bits), dim3(RED_THREADS), 0, st,
+                       p->d_tensors, leafC, cnt, (long long)p->n_chunks, p->hdr_bytes, p->rec_bytes,
+                       1 << p->bits, payload);
     if ((rc = check_launch())) return rc;
     sl_prof_mark(p, SL_PROF_LUT, st);
 

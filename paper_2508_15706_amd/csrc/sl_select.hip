@@ -47,6 +47,7 @@ struct SelectArgs {
     float beta;
     int frozen;
     int k;
+    int bits, hdr_bytes, rec_bytes; // value width of the payloads and the sizes that follow from it
     int lds_per_wave;
     int pend_off;           // offset of the pending-correction tables in a wave's LDS
     float *vals;            // [n_chunks * k] selected values, canonical order
@@ -158,7 +159,9 @@ SL_DEV void select_general(int (&key)[64], unsigned sg0, unsigned sg1, int k, in
 
 // PARAMS: the pseudo-gradient is formed on the fly from two parameter arenas
 // (a separate instantiation, so that the plain path keeps its register budget).
-template <int GPL, bool PARAMS>
+// TWO_BIT: payloads carry 2-bit codes (the paper's setting; the width is then a
+// compile-time constant); otherwise the width is A.bits.
+template <int GPL, bool PARAMS, bool TWO_BIT>
 __global__ void SL_SELECT_BOUNDS k_select(SelectArgs A)
 {
     extern __shared__ __align__(16) unsigned char smem_all[];
@@ -192,39 +195,62 @@ __global__ void SL_SELECT_BOUNDS k_select(SelectArgs A)
     // number of set bits before each 32-bit word, and the dequantised values in
     // record order (= ascending position, so rank in the map = record entry).
     unsigned *bm = nullptr, *pre = nullptr;
-    float *ql = nullptr;
+    float *ql = nullptr, *lutl = nullptr;
     const bool pend = A.pending != nullptr;
+    const int bits = TWO_BIT ? 2 : A.bits;
     const unsigned char *prec = nullptr, *pcodes = nullptr;
     float4 plut = make_float4(0.f, 0.f, 0.f, 0.f);
+    float p_lutv = 0.f;                     // other widths: table entry `lane`, parked in LDS later
     unsigned p_w0 = 0, p_c0 = 0;            // this lane's first record entry, fetched early
+    // The bytes of the value field of entry m: the code's byte window, or the fp32 value.
+    auto value_window = [&](int m) -> unsigned {
+        if (bits == 32) return reinterpret_cast<const unsigned *>(pcodes)[m];
+        const int bit = m * bits;
+        unsigned w = pcodes[bit >> 3];
+        if ((bit & 7) + bits > 8) w |= (unsigned)pcodes[(bit >> 3) + 1] << 8;
+        return w;
+    };
     if (pend) {
         bm = reinterpret_cast<unsigned *>(smem + A.pend_off);
         pre = bm + BM_WORDS;
         ql = reinterpret_cast<float *>(pre + BM_WORDS);
+        lutl = ql + k;
         prec = A.pending + d.rec_off;
         pcodes = prec + 3 * k / 2;
-        plut = *reinterpret_cast<const float4 *>(A.pending + sl_lut_off(d, k));
+        const unsigned char *lutg =
+            A.pending + (TWO_BIT ? sl_lut_off(d, 16, 7 * k / 4) : sl_lut_off(d, A.hdr_bytes, A.rec_bytes));
+        if (bits == 2) plut = *reinterpret_cast<const float4 *>(lutg);
+        else if (bits != 32 && lane < (1 << bits)) p_lutv = reinterpret_cast<const float *>(lutg)[lane];
         if (lane < k) {
             const int b0 = (3 * lane) >> 1;
             p_w0 = (unsigned)prec[b0] | ((unsigned)prec[b0 + 1] << 8);
-            p_c0 = pcodes[lane >> 2];
+            p_c0 = value_window(lane);
         }
     }
     // Builds the tables; called once the chunk's bulk loads are in flight so that
     // the small record loads above and this LDS work hide behind them.
     auto pend_build = [&]() {
         reinterpret_cast<uint2 *>(bm)[lane] = make_uint2(0u, 0u);
+        if (bits != 2 && bits != 32 && lane < (1 << bits)) lutl[lane] = p_lutv;
         sl_wave_sync();
-        auto entry = [&](int m, unsigned w, unsigned cbyte) {
+        auto entry = [&](int m, unsigned w, unsigned vw) {
             const unsigned j = (m & 1) ? (w >> 4) : (w & 0xFFFu);
-            const unsigned code = (cbyte >> (2 * (m & 3))) & 3u;
-            ql[m] = code == 0 ? plut.x : code == 1 ? plut.y : code == 2 ? plut.z : plut.w;
+            float q;
+            if (bits == 2) {
+                const unsigned code = (vw >> (2 * (m & 3))) & 3u;
+                q = code == 0 ? plut.x : code == 1 ? plut.y : code == 2 ? plut.z : plut.w;
+            } else if (bits == 32) {
+                q = __uint_as_float(vw);
+            } else {
+                q = lutl[(vw >> ((m * bits) & 7)) & ((1u << bits) - 1u)];
+            }
+            ql[m] = q;
             atomicOr(&bm[j >> 5], 1u << (j & 31u));
         };
         if (lane < k) entry(lane, p_w0, p_c0);
         for (int m = lane + 64; m < k; m += 64) {
             const int b0 = (3 * m) >> 1;
-            entry(m, (unsigned)prec[b0] | ((unsigned)prec[b0 + 1] << 8), pcodes[m >> 2]);
+            entry(m, (unsigned)prec[b0] | ((unsigned)prec[b0 + 1] << 8), value_window(m));
         }
         sl_wave_sync();
         const uint2 w2 = reinterpret_cast<const uint2 *>(bm)[lane];
@@ -461,6 +487,8 @@ __global__ void SL_SELECT_BOUNDS k_select(SelectArgs A)
     unsigned char *rec = A.payload + d.rec_off;
 
     for (int p = lane; p < k; p += 64) A.vals[c * k + p] = sel_val[p];
+    if (bits == 32)   // unquantized: the values themselves follow the indices (4-byte aligned)
+        for (int p = lane; p < k; p += 64) reinterpret_cast<float *>(rec + 3 * k / 2)[p] = sel_val[p];
 
     if ((k & 15) == 0) {
         // 12-bit index stream, one 32-bit word per lane (records are 4-byte aligned)
@@ -526,13 +554,16 @@ int slk_select(const sl_plan *p, float *e, const float *delta, const float *thet
     A.beta = beta;
     A.frozen = frozen;
     A.k = k;
+    A.bits = p->bits;
+    A.hdr_bytes = p->hdr_bytes;
+    A.rec_bytes = p->rec_bytes;
     {
         size_t b = pruned ? sizeof(uint2) * CAND_CAP : 0;
         b += (6 * (size_t)k + 7) & ~(size_t)7;
         b += 64 * sizeof(double);
         b = (b + 15) & ~(size_t)15;
         A.pend_off = (int)b;
-        if (pending) b += 2 * BM_WORDS * sizeof(unsigned) + 4 * (size_t)k;
+        if (pending) b += 2 * BM_WORDS * sizeof(unsigned) + 4 * (size_t)k + 16 * sizeof(float);
         A.lds_per_wave = (int)((b + 15) & ~(size_t)15);
     }
     A.vals = reinterpret_cast<float *>(ws + p->ws_vals);
@@ -543,19 +574,23 @@ int slk_select(const sl_plan *p, float *e, const float *delta, const float *thet
     const int wpb = 4 * (size_t)A.lds_per_wave <= 65536 ? 4 : 1;
     const dim3 grid((unsigned)((p->n_chunks + wpb - 1) / wpb)), block(64 * wpb);
     const size_t lds = (size_t)A.lds_per_wave * wpb;
+#define SL_LAUNCH_SELECT(PARAMS, TWO)                                                                 \
+    do {                                                                                              \
+        if (k <= 32) hipLaunchKernelGGL((k_select<1, PARAMS, TWO>), grid, block, lds, st, A);         \
+        else if (k <= 64) hipLaunchKernelGGL((k_select<2, PARAMS, TWO>), grid, block, lds, st, A);    \
+        else if (k <= 128) hipLaunchKernelGGL((k_select<4, PARAMS, TWO>), grid, block, lds, st, A);   \
+        else if (k <= 256) hipLaunchKernelGGL((k_select<8, PARAMS, TWO>), grid, block, lds, st, A);   \
+        else hipLaunchKernelGGL((k_select<0, PARAMS, TWO>), grid, block, lds, st, A);                 \
+    } while (0)
+    const bool two = p->bits == 2;
     if (theta_local) {
-        if (k <= 32) hipLaunchKernelGGL((k_select<1, true>), grid, block, lds, st, A);
-        else if (k <= 64) hipLaunchKernelGGL((k_select<2, true>), grid, block, lds, st, A);
-        else if (k <= 128) hipLaunchKernelGGL((k_select<4, true>), grid, block, lds, st, A);
-        else if (k <= 256) hipLaunchKernelGGL((k_select<8, true>), grid, block, lds, st, A);
-        else hipLaunchKernelGGL((k_select<0, true>), grid, block, lds, st, A);
+        if (two) SL_LAUNCH_SELECT(true, true);
+        else SL_LAUNCH_SELECT(true, false);
     } else {
-        if (k <= 32) hipLaunchKernelGGL((k_select<1, false>), grid, block, lds, st, A);
-        else if (k <= 64) hipLaunchKernelGGL((k_select<2, false>), grid, block, lds, st, A);
-        else if (k <= 128) hipLaunchKernelGGL((k_select<4, false>), grid, block, lds, st, A);
-        else if (k <= 256) hipLaunchKernelGGL((k_select<8, false>), grid, block, lds, st, A);
-        else hipLaunchKernelGGL((k_select<0, false>), grid, block, lds, st, A);
+        if (two) SL_LAUNCH_SELECT(false, true);
+        else SL_LAUNCH_SELECT(false, false);
     }
+#undef SL_LAUNCH_SELECT
     hipError_t err = hipGetLastError();
     if (err != hipSuccess) {
         sl_note_hip_error(err);
