@@ -68,6 +68,8 @@ def main():
     ap.add_argument("--config", type=int, default=4)
     ap.add_argument("--k", type=int, default=None)
     ap.add_argument("--flat", action="store_true", help="cut every tensor into runs of 4096")
+    ap.add_argument("--bits", type=int, default=2, choices=[1, 2, 3, 4, 32],
+                    help="payload value width (the paper's setting is 2; 32 = unquantized fp32)")
     ap.add_argument("--delta-buffers", type=int, default=3)
     ap.add_argument("--cpu-layers", type=int, default=4)
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -92,7 +94,7 @@ def main():
 
     w = synth.workload(args.config, k=args.k, flat=args.flat)
     descs = [s.desc() for s in w.specs]
-    plan = sl.sl_plan_create(descs, w.k)
+    plan = sl.sl_plan_create(descs, w.k) if args.bits == 2 else sl.sl_plan_create_bits(descs, w.k, args.bits)
     N, n_chunks, arena = plan.num_elements, plan.num_chunks, w.arena
     ws = sl.alloc_workspace(plan)
 
@@ -155,15 +157,16 @@ def main():
     dt, prof = timed(args.mode, args.steps)
 
     ms_step = 1e3 * dt / args.steps
-    rec = 7 * w.k // 4
-    bytes_round = 20 * N + (w.R + 1) * rec * n_chunks + 16 * len(descs) * (w.R + 1)
+    rec = 3 * w.k // 2 + w.k * args.bits // 8
+    hdr = 0 if args.bits == 32 else max(16, 4 << args.bits)
+    bytes_round = 20 * N + (w.R + 1) * rec * n_chunks + hdr * len(descs) * (w.R + 1)
     # dominant kernel: accumulate + select.  Algorithmic bytes per launch: read e and
     # delta, write e (12 B/element) + the packed indices it writes (3k/2 B per chunk)
     sel_ms = prof["select"][0]
-    sel_bytes = 12 * N + (3 * w.k // 2) * n_chunks
+    sel_bytes = 12 * N + (3 * w.k // 2 + (4 * w.k if args.bits == 32 else 0)) * n_chunks
     sel_gbs = sel_bytes / (sel_ms * 1e-3) / 1e9 if sel_ms > 0 else 0.0
     apply_ms = prof["apply"][0]
-    apply_bytes = 8 * N + w.R * (rec * n_chunks + 16 * len(descs))
+    apply_bytes = 8 * N + w.R * (rec * n_chunks + hdr * len(descs))
     compress_ms = sum(prof[p][0] for p in ("select", "stats", "codes", "lut", "residual"))
 
     # a plain device copy of the same footprint as a practical ceiling (context only)
@@ -183,7 +186,7 @@ def main():
     # paper_2508_15706_amd/rocprof_summary.py from a profiled run of this same command)
     traffic = None
     tpath = os.path.join(ROOT, "profiles", f"traffic_config{w.config_id}_{PROFILE_TAGS.get(w.config_id, '')}.json")
-    if os.path.exists(tpath) and not args.flat and args.k is None:
+    if os.path.exists(tpath) and not args.flat and args.k is None and args.bits == 2:
         tk = json.load(open(tpath))["kernels"]
         name = next((n for n in tk if n.startswith("k_select")), None)
         if name and tk[name]["fetch_bytes"] is not None and tk[name]["write_bytes"] is not None:
@@ -198,8 +201,9 @@ def main():
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"config {w.config_id}: {w.name}, {len(descs)} fp32 tensors, "
                                f"N={N}, chunk 4096 ({'flat runs' if args.flat else '64x64 tiles / 1-D runs'}), "
-                               f"k={w.k}, R={w.R}, beta={w.beta}, lr={w.lr}, {args.mode} residual",
-                   "n_elements": N, "n_chunks": n_chunks, "k": w.k, "R": w.R},
+                               f"k={w.k}, R={w.R}, beta={w.beta}, lr={w.lr}, "
+                               f"{'fp32' if args.bits == 32 else str(args.bits) + '-bit'} values, {args.mode} residual",
+                   "n_elements": N, "n_chunks": n_chunks, "k": w.k, "R": w.R, "value_bits": args.bits},
         "roofline": {"bound": "hbm", "kernel": "k_select (EF accumulate + chunk Top-k)",
                      "achieved": sel_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": sel_gbs / HBM_PEAK_GBS, "traffic": traffic,
@@ -227,17 +231,18 @@ def main():
         torch.cuda.synchronize()
         return a.elapsed_time(b) / reps
 
-    coded = torch.empty(sl.sl_rice_max_bytes(plan), dtype=torch.uint8, device=dev)
-    back = sl.alloc_payload(plan)
-    enc_ms = time_ms(lambda: sl.sl_rice_encode(plan, own[0], coded, ws))
-    coded_bytes = int(coded[8:16].cpu().numpy().view("uint64")[0])
-    dec_ms = time_ms(lambda: sl.sl_rice_decode(plan, coded, coded_bytes, back))
-    out["index_coder"] = {
-        "plain_bytes": plan.payload_bytes, "coded_bytes": coded_bytes,
-        "bits_per_index": coded_bytes * 8 / (n_chunks * w.k) - 2.0,
-        "lossless": bool(torch.equal(back[:plan.payload_bytes], own[0][:plan.payload_bytes])),
-        "encode_ms": enc_ms, "decode_ms": dec_ms,
-    }
+    if args.bits == 2:
+        coded = torch.empty(sl.sl_rice_max_bytes(plan), dtype=torch.uint8, device=dev)
+        back = sl.alloc_payload(plan)
+        enc_ms = time_ms(lambda: sl.sl_rice_encode(plan, own[0], coded, ws))
+        coded_bytes = int(coded[8:16].cpu().numpy().view("uint64")[0])
+        dec_ms = time_ms(lambda: sl.sl_rice_decode(plan, coded, coded_bytes, back))
+        out["index_coder"] = {
+            "plain_bytes": plan.payload_bytes, "coded_bytes": coded_bytes,
+            "bits_per_index": coded_bytes * 8 / (n_chunks * w.k) - 2.0,
+            "lossless": bool(torch.equal(back[:plan.payload_bytes], own[0][:plan.payload_bytes])),
+            "encode_ms": enc_ms, "decode_ms": dec_ms,
+        }
     if not args.no_cpu_baseline:
         del deltas, theta, e0
         out["cpu_baseline"] = cpu_baseline(w, args.cpu_layers)
