@@ -99,6 +99,15 @@ def lib():
         L.slo_decompress_avg_apply_b.argtypes = [tp, i32, i32, i32, i32, vp, vp, i32, C.c_float]
         L.slo_decompress_dense_b.restype = i32
         L.slo_decompress_dense_b.argtypes = [tp, i32, i32, i32, i32, vp, vp]
+        L.slo_lom_direction.restype = None
+        L.slo_lom_direction.argtypes = [tp, i32, vp, vp, C.c_float, vp]
+        L.slo_dense_avg_apply.restype = i32
+        L.slo_dense_avg_apply.argtypes = [tp, i32, vp, vp, vp, i32, C.c_float, C.c_float]
+        L.slo_decompress_avg_apply_nesterov_b.restype = i32
+        L.slo_decompress_avg_apply_nesterov_b.argtypes = [tp, i32, i32, i32, i32, vp, vp, vp, i32, C.c_float,
+                                                          C.c_float]
+        L.slo_sub_topk.restype = i32
+        L.slo_sub_topk.argtypes = [tp, i32, i32, i32, vp, vp]
         L.slo_validate_payload.restype = i32
         L.slo_validate_payload.argtypes = [tp, i32, i32, i32, vp]
         L.slo_rice_param.restype = i32
@@ -373,6 +382,57 @@ def decompress_dense_b(descs, k, bits, payload, n_elems, tile=64, out=None):
     if st:
         raise ValueError(f"slo_decompress_dense_b: status {st}")
     return out
+
+
+# ---- outer steps of the DiLoCo family (dense momentum variants) ----
+def lom_direction(descs, m, delta, mu, out=None):
+    """m <- mu*m + delta in place; returns dir = delta + mu*m (tensor elements only)."""
+    arr, n = make_tensors(descs)
+    _check(m, np.float32), _check(delta, np.float32)
+    if out is None:
+        out = np.zeros_like(delta)
+    _check(out, np.float32)
+    lib().slo_lom_direction(arr, n, _ptr(m), _ptr(delta), float(mu), _ptr(out))
+    return out
+
+
+def dense_avg_apply(descs, theta, dirs, lr, m=None, mu=0.0):
+    arr, n = make_tensors(descs)
+    _check(theta, np.float32)
+    R = len(dirs)
+    for d in dirs:
+        _check(d, np.float32)
+    if m is not None:
+        _check(m, np.float32)
+    ptrs = (C.c_void_p * max(1, R))(*[d.ctypes.data for d in dirs])
+    st = lib().slo_dense_avg_apply(arr, n, _ptr(theta), None if m is None else _ptr(m), ptrs, R,
+                                   float(lr), float(mu))
+    if st:
+        raise ValueError(f"slo_dense_avg_apply: status {st}")
+
+
+def decompress_avg_apply_nesterov_b(descs, k, bits, theta, m, payloads, lr, mu, tile=64):
+    arr, n = make_tensors(descs)
+    _check(theta, np.float32), _check(m, np.float32)
+    R = len(payloads)
+    for p in payloads:
+        _check(p, np.uint8)
+    ptrs = (C.c_void_p * max(1, R))(*[p.ctypes.data for p in payloads])
+    st = lib().slo_decompress_avg_apply_nesterov_b(arr, n, tile, k, bits, _ptr(theta), _ptr(m), ptrs, R,
+                                                   float(lr), float(mu))
+    if st:
+        raise ValueError(f"slo_decompress_avg_apply_nesterov_b: status {st}")
+
+
+def sub_topk(descs, k, m, tile=64, want_idx=False):
+    """m <- m - Top-k(m) chunk-wise, in place."""
+    arr, n = make_tensors(descs)
+    _check(m, np.float32)
+    idx = np.zeros(num_chunks(descs, tile) * k, dtype=np.uint16) if want_idx else None
+    st = lib().slo_sub_topk(arr, n, tile, k, _ptr(m), None if idx is None else _ptr(idx))
+    if st:
+        raise ValueError(f"slo_sub_topk: status {st}")
+    return idx
 
 
 def validate_payload(descs, k, payload, tile=64):

@@ -827,6 +827,150 @@ int slo_validate_payload(const slo_tensor *t, int nt, int tile, int k, const uin
     return status;
 }
 
+/* ------------------------------------------------------------------------- */
+/* Outer steps of the DiLoCo family that SparseLoCo is built up from and       */
+/* compared with (Eq. (1): DiLoCo's Nesterov outer momentum; Section 3.2:      */
+/* DiLoCo-LOM and DiLoCo-LOM-Sub-k; appendix "Exact algorithmic description of */
+/* DiLoCo variants": DiLoCo+Top-k[+EF], DiLoCo-LOM+Top-k[+EF]).  They reuse    */
+/* the chunk-wise Top-k and the sparse aggregate above (with unquantized       */
+/* values: these variants have no Q) and add dense elementwise steps.          */
+/* Readings for the rounding, as for Eq. (2): every "x <- c*y + z" is one fp32 */
+/* fused multiply-add; a dense average is an fp32 accumulator that starts at   */
+/* +0.0f, adds the R buffers in the order r = 0..R-1 and is multiplied by 1/R  */
+/* rounded once.  Only elements that belong to a tensor are touched.           */
+/* ------------------------------------------------------------------------- */
+
+/* Local outer momentum and local Nesterov direction of one worker (Section
+ * 3.2; first two lines of the LOM outer step):
+ *     m <- mu*m + delta ;  dir <- delta + mu*m.
+ * dir may be the same buffer as delta. */
+void slo_lom_direction(const slo_tensor *t, int nt, float *m, const float *delta, float mu, float *dir)
+{
+    for (int ti = 0; ti < nt; ++ti) {
+        int64_t o = t[ti].offset, n = t[ti].rows * t[ti].cols;
+        for (int64_t i = o; i < o + n; ++i) {
+            float mn = fmaf(mu, m[i], delta[i]);
+            m[i] = mn;
+            dir[i] = fmaf(mu, mn, delta[i]);
+        }
+    }
+}
+
+/* Dense aggregate and outer step.  avg = (1/R) sum_r dirs[r].
+ *   m == NULL : theta <- theta - lr*avg          (last two lines of the LOM outer
+ *               step; with dirs = the raw pseudo-gradients: plain averaging,
+ *               what Eq. (1) reduces to without its second line)
+ *   m != NULL : Eq. (1), DiLoCo:  m <- mu*m + avg ; d <- avg + mu*m ;
+ *               theta <- theta - lr*d. */
+int slo_dense_avg_apply(const slo_tensor *t, int nt, float *theta, float *m, const float *const *dirs,
+                        int R, float lr, float mu)
+{
+    if (R < 1) return SLO_ERR_ARG;
+    float invR = 1.0f / (float)R;
+    for (int ti = 0; ti < nt; ++ti) {
+        int64_t o = t[ti].offset, n = t[ti].rows * t[ti].cols;
+        for (int64_t i = o; i < o + n; ++i) {
+            float acc = 0.0f;
+            for (int r = 0; r < R; ++r) acc = acc + dirs[r][i];
+            float d = acc * invR;
+            if (m) {
+                float mn = fmaf(mu, m[i], d);
+                m[i] = mn;
+                d = fmaf(mu, mn, d);
+            }
+            theta[i] = fmaf(-lr, d, theta[i]);
+        }
+    }
+    return SLO_OK;
+}
+
+/* Sparse aggregate followed by DiLoCo's global Nesterov momentum (appendix
+ * algorithm "Outer step for DiLoCo+Top-k[+EF]", last four lines): the average
+ * of the R sparse payloads as in slo_decompress_avg_apply_b, then
+ *     m <- mu*m + avg ;  d <- avg + mu*m ;  theta <- theta - lr*d
+ * at EVERY element (m is dense: it keeps moving where nothing was sent). */
+int slo_decompress_avg_apply_nesterov_b(const slo_tensor *t, int nt, int tile, int k, int bits,
+                                        float *theta, float *m, const uint8_t *const *payloads, int R,
+                                        float lr, float mu)
+{
+    if (nt < 0 || tile < 1 || tile > 64 || !bits_ok(k, bits, tile) || R < 1) return SLO_ERR_ARG;
+    int C = tile * tile;
+    int nb = bits == 32 ? 0 : 1 << bits;
+    int64_t rec = slo_record_bytes_b(k, bits), hdr = slo_header_bytes_b(bits);
+    float invR = 1.0f / (float)R;
+    int64_t pay_off = 0;
+    int bad = 0;
+    for (int ti = 0; ti < nt; ++ti) {
+        const slo_tensor *T = &t[ti];
+        int64_t nc = slo_tensor_chunks(T, tile);
+        for (int64_t c = 0; c < nc; ++c) {
+            float *acc = (float *)calloc((size_t)C, sizeof(float));
+            uint16_t *idx = (uint16_t *)malloc((size_t)k * sizeof(uint16_t));
+            uint8_t *code = (uint8_t *)calloc((size_t)k, 1);
+            float *val = (float *)calloc((size_t)k, sizeof(float));
+            for (int r = 0; r < R; ++r) {
+                const uint8_t *blk = payloads[r] + pay_off;
+                float lut[16] = {0};
+                memcpy(lut, blk, (size_t)4 * nb);
+                slo_unpack_record_b(blk + hdr + c * rec, k, bits, idx, code, val);
+                for (int q = 0; q < k; ++q) {
+                    if (idx[q] >= C) {
+                        bad |= 1;
+                        continue;
+                    }
+                    float sent = bits == 32 ? val[q] : lut[code[q]];
+                    acc[idx[q]] = acc[idx[q]] + sent;
+                }
+            }
+            for (int j = 0; j < C; ++j) {
+                int64_t i = slo_element_of(T, tile, c, j);
+                if (i < 0) continue;
+                float d = acc[j] * invR;
+                float mn = fmaf(mu, m[i], d);
+                m[i] = mn;
+                d = fmaf(mu, mn, d);
+                theta[i] = fmaf(-lr, d, theta[i]);
+            }
+            free(acc), free(idx), free(code), free(val);
+        }
+        pay_off += slo_tensor_block_bytes_b(T, tile, k, bits);
+    }
+    return bad ? SLO_ERR_PAYLOAD : SLO_OK;
+}
+
+/* DiLoCo-LOM-Sub-k (Section 3.2; boxed line of the LOM outer step):
+ *     m <- m - Top-k(m)
+ * with the chunk-wise Top-k of SparseLoCo (same magnitude order and tie
+ * rule).  At a selected position the result is m - m = +0.0f; every other
+ * element is untouched.  sel_idx (optional): the selected local indices,
+ * [n_chunks * k] in list chunk order. */
+int slo_sub_topk(const slo_tensor *t, int nt, int tile, int k, float *m, uint16_t *sel_idx)
+{
+    if (nt < 0 || tile < 1 || tile > 64 || k < 1 || k > tile * tile) return SLO_ERR_ARG;
+    int64_t chunk0 = 0;
+    uint16_t *idx = (uint16_t *)malloc((size_t)k * sizeof(uint16_t));
+    float *val = (float *)malloc((size_t)k * sizeof(float));
+    int status = SLO_OK;
+    for (int ti = 0; ti < nt && status == SLO_OK; ++ti) {
+        const slo_tensor *T = &t[ti];
+        int64_t nc = slo_tensor_chunks(T, tile);
+        for (int64_t c = 0; c < nc; ++c) {
+            if (slo_topk_chunk(T, tile, c, m, k, idx, val) < 0) {
+                status = SLO_ERR_ARG;
+                break;
+            }
+            for (int q = 0; q < k; ++q) {
+                int64_t i = slo_element_of(T, tile, c, idx[q]);
+                m[i] = val[q] - val[q];
+            }
+            if (sel_idx) memcpy(sel_idx + (chunk0 + c) * k, idx, (size_t)k * sizeof(uint16_t));
+        }
+        chunk0 += nc;
+    }
+    free(idx), free(val);
+    return status;
+}
+
 int slo_max_threads(void)
 {
 #ifdef _OPENMP
