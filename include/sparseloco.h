@@ -169,6 +169,54 @@ int sl_residual_apply(sl_plan *plan, float *e, const void *payload, void *stream
 int sl_decompress_avg_apply(sl_plan *plan, float *theta, const void *const *payloads, int R,
                             float lr, void *stream);
 
+/* ---- Outer steps of the DiLoCo family (Eq. (1); Section 3.2; appendix "Exact
+ * algorithmic description of DiLoCo variants").  SparseLoCo is built up from
+ * these and compared with them; they reuse the chunk-wise Top-k and the sparse
+ * aggregate above - on a 32-bit plan, since these variants have no quantizer -
+ * and add the dense steps below.  Every "c*y + z" is one fp32 fused
+ * multiply-add; only elements that belong to a tensor of the plan are touched;
+ * all buffers are device fp32 arenas, 16-byte aligned.
+ *   DiLoCo (Eq. (1))        sl_dense_avg_apply(theta, momentum, {delta_r})
+ *   DiLoCo-LOM              sl_lom_direction per worker, then
+ *                           sl_dense_avg_apply(theta, NULL, {dir_r})
+ *   DiLoCo-LOM-Sub-k        the same, then sl_sub_topk(m_r) per worker
+ *   DiLoCo+Top-k[+EF]       sl_compress (EF: beta = the EF decay; no EF:
+ *                           SL_COMPRESS_EF_FROZEN), then
+ *                           sl_decompress_avg_apply_nesterov
+ *   DiLoCo-LOM+Top-k[+EF]   sl_lom_direction, sl_compress of dir, then
+ *                           sl_decompress_avg_apply                          */
+
+/* Local outer momentum and local Nesterov direction of one worker (Section 3.2):
+ *   m <- mu*m + delta ;  dir <- delta + mu*m.
+ * m inout; delta in; dir out, may be the same buffer as delta; m must be
+ * distinct from both. */
+int sl_lom_direction(sl_plan *plan, float *m, const float *delta, float mu, float *dir, void *stream);
+
+/* Dense aggregate and outer step: avg = (1/R) * sum_r dirs[r], an fp32
+ * accumulator that starts at +0.0f and adds the buffers in the order r = 0..R-1,
+ * times 1/R rounded once.
+ *   momentum == NULL: theta <- theta - lr*avg (last lines of the LOM outer step;
+ *                     with the raw pseudo-gradients: plain averaging)
+ *   momentum != NULL: Eq. (1): m <- mu*m + avg ; d <- avg + mu*m ;
+ *                     theta <- theta - lr*d.
+ * dirs: HOST array of R DEVICE pointers (1 <= R <= SL_MAX_WORKERS), distinct
+ * from theta and momentum. */
+int sl_dense_avg_apply(sl_plan *plan, float *theta, float *momentum, const float *const *dirs, int R,
+                       float lr, float mu, void *stream);
+
+/* sl_decompress_avg_apply followed by DiLoCo's global Nesterov momentum
+ * (appendix algorithm "Outer step for DiLoCo+Top-k[+EF]"), in the same pass:
+ *   avg as in sl_decompress_avg_apply ; m <- mu*m + avg ; d <- avg + mu*m ;
+ *   theta <- theta - lr*d at EVERY element (the momentum is dense).
+ * momentum inout, distinct from theta. */
+int sl_decompress_avg_apply_nesterov(sl_plan *plan, float *theta, float *momentum,
+                                     const void *const *payloads, int R, float lr, float mu, void *stream);
+
+/* DiLoCo-LOM-Sub-k (Section 3.2): m <- m - Top-k(m) with the plan's chunk-wise
+ * Top-k (same magnitude order and tie rule as sl_compress): the k selected
+ * entries of every chunk become +0.0f, nothing else is written. */
+int sl_sub_topk(sl_plan *plan, float *m, void *stream);
+
 /* Checks a received payload before it is trusted by sl_decompress_avg_apply:
  * in every record the k indices must be strictly ascending and must address
  * positions inside the chunk (edge chunks are partial).  This call WAITS for

@@ -30,6 +30,7 @@ EXPORTS = [
     "sl_profile_begin", "sl_profile_end", "sl_residual_apply",
     "sl_rice_max_bytes", "sl_rice_encode", "sl_rice_decode", "sl_compress_params",
     "sl_payload_validate", "sl_plan_create_bits", "sl_plan_value_bits", "sl_pack_indices_bits",
+    "sl_lom_direction", "sl_dense_avg_apply", "sl_decompress_avg_apply_nesterov", "sl_sub_topk",
 ]
 PROF_PHASES = ["select", "stats", "codes", "lut", "residual", "apply"]
 
@@ -68,6 +69,14 @@ def lib():
         L.sl_plan_value_bits.argtypes = [vp]
         L.sl_pack_indices_bits.restype = i32
         L.sl_pack_indices_bits.argtypes = [vp, vp, vp, i64, i32, i32, vp, vp]
+        L.sl_lom_direction.restype = i32
+        L.sl_lom_direction.argtypes = [vp, vp, vp, C.c_float, vp, vp]
+        L.sl_dense_avg_apply.restype = i32
+        L.sl_dense_avg_apply.argtypes = [vp, vp, vp, C.POINTER(vp), i32, C.c_float, C.c_float, vp]
+        L.sl_decompress_avg_apply_nesterov.restype = i32
+        L.sl_decompress_avg_apply_nesterov.argtypes = [vp, vp, vp, C.POINTER(vp), i32, C.c_float, C.c_float, vp]
+        L.sl_sub_topk.restype = i32
+        L.sl_sub_topk.argtypes = [vp, vp, vp]
         L.sl_plan_destroy.restype = i32
         L.sl_plan_destroy.argtypes = [vp]
         L.sl_plan_num_chunks.restype = i64
@@ -225,6 +234,42 @@ def sl_decompress_avg_apply(plan: Plan, theta: torch.Tensor, payloads: Sequence[
                                        float(lr), _stream_ptr(stream))
     if st:
         raise SparseLoCoError("sl_decompress_avg_apply", st)
+
+
+def sl_decompress_avg_apply_nesterov(plan: Plan, theta: torch.Tensor, momentum: torch.Tensor,
+                                     payloads: Sequence[torch.Tensor], lr: float, mu: float, stream=None) -> None:
+    R = len(payloads)
+    ptrs = (C.c_void_p * max(1, R))(*[_dev_ptr(p, torch.uint8) for p in payloads])
+    st = lib().sl_decompress_avg_apply_nesterov(plan.handle, _dev_ptr(theta, torch.float32),
+                                                _dev_ptr(momentum, torch.float32), ptrs, R, float(lr),
+                                                float(mu), _stream_ptr(stream))
+    if st:
+        raise SparseLoCoError("sl_decompress_avg_apply_nesterov", st)
+
+
+def sl_lom_direction(plan: Plan, m: torch.Tensor, delta: torch.Tensor, mu: float, out: torch.Tensor,
+                     stream=None) -> None:
+    st = lib().sl_lom_direction(plan.handle, _dev_ptr(m, torch.float32), _dev_ptr(delta, torch.float32),
+                                float(mu), _dev_ptr(out, torch.float32), _stream_ptr(stream))
+    if st:
+        raise SparseLoCoError("sl_lom_direction", st)
+
+
+def sl_dense_avg_apply(plan: Plan, theta: torch.Tensor, momentum: Optional[torch.Tensor],
+                       dirs: Sequence[torch.Tensor], lr: float, mu: float = 0.0, stream=None) -> None:
+    R = len(dirs)
+    ptrs = (C.c_void_p * max(1, R))(*[_dev_ptr(d, torch.float32) for d in dirs])
+    st = lib().sl_dense_avg_apply(plan.handle, _dev_ptr(theta, torch.float32),
+                                  _dev_ptr(momentum, torch.float32), ptrs, R, float(lr), float(mu),
+                                  _stream_ptr(stream))
+    if st:
+        raise SparseLoCoError("sl_dense_avg_apply", st)
+
+
+def sl_sub_topk(plan: Plan, m: torch.Tensor, stream=None) -> None:
+    st = lib().sl_sub_topk(plan.handle, _dev_ptr(m, torch.float32), _stream_ptr(stream))
+    if st:
+        raise SparseLoCoError("sl_sub_topk", st)
 
 
 def sl_pack_indices(idx: torch.Tensor, codes: torch.Tensor, n_chunks: int, k: int,

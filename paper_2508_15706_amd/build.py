@@ -9,10 +9,11 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libsparseloco.so")
-SOURCES = ["sl_api.hip", "sl_select.hip", "sl_quant.hip", "sl_apply.hip", "sl_rice.hip"]
+SOURCES = ["sl_api.hip", "sl_select.hip", "sl_quant.hip", "sl_apply.hip", "sl_rice.hip", "sl_outer.hip"]
+OBJ_DIR = os.path.join(PKG, "_build")
 
 HIPCC_FLAGS = [
-    "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
+    "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
     "-ffp-contract=off",                      # the only fused operations are explicit fmaf
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-Wall", "-Wno-unused-function",
@@ -26,9 +27,7 @@ def hipcc() -> str:
     return exe
 
 
-def build_library(verbose: bool = False, extra=()) -> str:
-    cmd = [hipcc(), *HIPCC_FLAGS, *extra, "-I", os.path.join(ROOT, "include"), "-I", CSRC,
-           *[os.path.join(CSRC, s) for s in SOURCES], "-o", LIB]
+def _run(cmd, verbose):
     if verbose:
         print(" ".join(cmd), flush=True)
     r = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
@@ -38,7 +37,20 @@ def build_library(verbose: bool = False, extra=()) -> str:
     if out.strip():
         print(out, flush=True)
     if r.returncode != 0:
-        raise RuntimeError(f"hipcc failed with exit code {r.returncode}")
+        raise RuntimeError(f"hipcc failed with exit code {r.returncode}: {cmd[-1]}")
+
+
+def build_library(verbose: bool = False, extra=()) -> str:
+    """Compiles every source (always, in parallel) and links libsparseloco.so."""
+    from concurrent.futures import ThreadPoolExecutor
+    os.makedirs(OBJ_DIR, exist_ok=True)
+    inc = ["-I", os.path.join(ROOT, "include"), "-I", CSRC]
+    objs = [os.path.join(OBJ_DIR, s.replace(".hip", ".o")) for s in SOURCES]
+    cmds = [[hipcc(), *HIPCC_FLAGS, *extra, *inc, "-c", os.path.join(CSRC, s), "-o", o]
+            for s, o in zip(SOURCES, objs)]
+    with ThreadPoolExecutor(max_workers=min(8, len(cmds))) as pool:
+        list(pool.map(lambda c: _run(c, verbose), cmds))
+    _run([hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", *objs, "-o", LIB], verbose)
     return LIB
 
 

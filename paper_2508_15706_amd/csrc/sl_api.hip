@@ -348,9 +348,55 @@ int sl_decompress_avg_apply(sl_plan *p, float *theta, const void *const *payload
     int rc = check_device(p);
     if (rc) return rc;
     sl_prof_mark(p, -2, static_cast<hipStream_t>(stream));
-    rc = slk_apply(p, theta, payloads, R, lr, static_cast<hipStream_t>(stream));
+    rc = slk_apply(p, theta, nullptr, 0.0f, payloads, R, lr, static_cast<hipStream_t>(stream));
     sl_prof_mark(p, SL_PROF_APPLY, static_cast<hipStream_t>(stream));
     return rc;
+}
+
+int sl_decompress_avg_apply_nesterov(sl_plan *p, float *theta, float *momentum, const void *const *payloads,
+                                     int R, float lr, float mu, void *stream)
+{
+    if (!p || !theta || !momentum || theta == momentum || !payloads || R < 1 || R > SL_MAX_WORKERS)
+        return SL_ERR_INVALID_ARG;
+    if (misaligned(theta, 16) || misaligned(momentum, 16)) return SL_ERR_INVALID_ARG;
+    for (int r = 0; r < R; ++r)
+        if (!payloads[r] || misaligned(payloads[r], 16)) return SL_ERR_INVALID_ARG;
+    int rc = check_device(p);
+    if (rc) return rc;
+    sl_prof_mark(p, -2, static_cast<hipStream_t>(stream));
+    rc = slk_apply(p, theta, momentum, mu, payloads, R, lr, static_cast<hipStream_t>(stream));
+    sl_prof_mark(p, SL_PROF_APPLY, static_cast<hipStream_t>(stream));
+    return rc;
+}
+
+int sl_lom_direction(sl_plan *p, float *m, const float *delta, float mu, float *dir, void *stream)
+{
+    if (!p || !m || !delta || !dir || m == delta || m == dir) return SL_ERR_INVALID_ARG;
+    if (misaligned(m, 16) || misaligned(delta, 16) || misaligned(dir, 16)) return SL_ERR_INVALID_ARG;
+    int rc = check_device(p);
+    if (rc) return rc;
+    return slk_lom_direction(p, m, delta, mu, dir, static_cast<hipStream_t>(stream));
+}
+
+int sl_dense_avg_apply(sl_plan *p, float *theta, float *momentum, const float *const *dirs, int R, float lr,
+                       float mu, void *stream)
+{
+    if (!p || !theta || theta == momentum || !dirs || R < 1 || R > SL_MAX_WORKERS) return SL_ERR_INVALID_ARG;
+    if (misaligned(theta, 16) || misaligned(momentum, 16)) return SL_ERR_INVALID_ARG;
+    for (int r = 0; r < R; ++r)
+        if (!dirs[r] || dirs[r] == theta || dirs[r] == momentum || misaligned(dirs[r], 16))
+            return SL_ERR_INVALID_ARG;
+    int rc = check_device(p);
+    if (rc) return rc;
+    return slk_dense_avg_apply(p, theta, momentum, dirs, R, lr, mu, static_cast<hipStream_t>(stream));
+}
+
+int sl_sub_topk(sl_plan *p, float *m, void *stream)
+{
+    if (!p || !m || misaligned(m, 16)) return SL_ERR_INVALID_ARG;
+    int rc = check_device(p);
+    if (rc) return rc;
+    return slk_sub_topk(p, m, static_cast<hipStream_t>(stream));
 }
 
 int sl_pack_indices_bits(const uint16_t *idx, const uint8_t *codes, const float *values, int64_t n_chunks,

@@ -17,6 +17,8 @@ namespace {
 struct ApplyArgs {
     const SlChunkDesc *desc;
     float *theta;
+    float *mom;              // global outer momentum buffer (Nesterov variant), else null
+    float mu;
     float neg_lr, inv_R;
     int R, k;
     int bits, hdr_bytes, rec_bytes;   // value width and the sizes that follow from it
@@ -29,7 +31,10 @@ struct ApplyArgs {
 // One wave per chunk, several independent waves (adjacent chunks) per workgroup.
 // TWO_BIT: the 2-bit format with its four-entry table kept in registers;
 // otherwise any width (table of 2^bits entries read from LDS, or fp32 values).
-template <bool TWO_BIT>
+// NESTEROV: DiLoCo's global outer momentum on top of the aggregate (Eq. (1);
+// appendix algorithm "Outer step for DiLoCo+Top-k[+EF]"): m <- mu*m + avg,
+// d <- avg + mu*m, theta <- theta - lr*d at every element of the chunk.
+template <bool TWO_BIT, bool NESTEROV>
 __global__ void __launch_bounds__(256) k_apply(ApplyArgs A)
 {
     extern __shared__ __align__(16) unsigned char smem_all[];
@@ -80,11 +85,16 @@ __global__ void __launch_bounds__(256) k_apply(ApplyArgs A)
         }
     }
 
-    sl_f4 th[16];
+    sl_f4 th[16], mo[NESTEROV ? 16 : 1];
+    float *mc = NESTEROV ? A.mom + d.base : nullptr;
     if (full) {
         const unsigned o0 = 4u * (lr * stride + lc), step = 16u * stride;
 #pragma unroll
         for (int i = 0; i < 16; ++i) th[i] = sl_load_stream_at(tc, i * step, o0);
+        if constexpr (NESTEROV) {
+#pragma unroll
+            for (int i = 0; i < 16; ++i) mo[i] = sl_load_stream_at(mc, i * step, o0);
+        }
     }
 
 #pragma unroll
@@ -153,11 +163,21 @@ __global__ void __launch_bounds__(256) k_apply(ApplyArgs A)
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
             const float4 a = reinterpret_cast<const float4 *>(acc)[i * 64 + lane];
+            sl_f4 g;
+            g.x = a.x * A.inv_R, g.y = a.y * A.inv_R, g.z = a.z * A.inv_R, g.w = a.w * A.inv_R;
+            if constexpr (NESTEROV) {
+                sl_f4 m = mo[i];
+                m.x = fmaf(A.mu, m.x, g.x), m.y = fmaf(A.mu, m.y, g.y);
+                m.z = fmaf(A.mu, m.z, g.z), m.w = fmaf(A.mu, m.w, g.w);
+                sl_store_stream_at(mc, i * step, o0, m);
+                g.x = fmaf(A.mu, m.x, g.x), g.y = fmaf(A.mu, m.y, g.y);
+                g.z = fmaf(A.mu, m.z, g.z), g.w = fmaf(A.mu, m.w, g.w);
+            }
             sl_f4 v = th[i];
-            v.x = fmaf(A.neg_lr, a.x * A.inv_R, v.x);
-            v.y = fmaf(A.neg_lr, a.y * A.inv_R, v.y);
-            v.z = fmaf(A.neg_lr, a.z * A.inv_R, v.z);
-            v.w = fmaf(A.neg_lr, a.w * A.inv_R, v.w);
+            v.x = fmaf(A.neg_lr, g.x, v.x);
+            v.y = fmaf(A.neg_lr, g.y, v.y);
+            v.z = fmaf(A.neg_lr, g.z, v.z);
+            v.w = fmaf(A.neg_lr, g.w, v.w);
             sl_store_stream_at(tc, i * step, o0, v);
         }
     } else {
@@ -169,7 +189,13 @@ __global__ void __launch_bounds__(256) k_apply(ApplyArgs A)
                 const int col = lc + cc;
                 if (col < lim) {
                     const unsigned o = row * stride + col;
-                    tc[o] = fmaf(A.neg_lr, acc[256 * i + 4 * lane + cc] * A.inv_R, tc[o]);
+                    float g = acc[256 * i + 4 * lane + cc] * A.inv_R;
+                    if constexpr (NESTEROV) {
+                        const float m = fmaf(A.mu, mc[o], g);
+                        mc[o] = m;
+                        g = fmaf(A.mu, m, g);
+                    }
+                    tc[o] = fmaf(A.neg_lr, g, tc[o]);
                 }
             }
         }
@@ -286,13 +312,15 @@ int slk_pack_bits(const uint16_t *idx, const uint8_t *codes, const float *values
     return SL_OK;
 }
 
-int slk_apply(const sl_plan *p, float *theta, const void *const *payloads, int R, float lr,
-              hipStream_t st)
+int slk_apply(const sl_plan *p, float *theta, float *mom, float mu, const void *const *payloads, int R,
+              float lr, hipStream_t st)
 {
     if (p->n_chunks == 0) return SL_OK;
     ApplyArgs A;
     A.desc = p->d_desc;
     A.theta = theta;
+    A.mom = mom;
+    A.mu = mu;
     A.neg_lr = -lr;
     A.inv_R = 1.0f / (float)R;
     A.R = R;
@@ -312,8 +340,11 @@ int slk_apply(const sl_plan *p, float *theta, const void *const *payloads, int R
     int wpb = 4;
     while (wpb > 1 && (size_t)A.lds_per_wave * wpb > (size_t)p->max_lds) wpb >>= 1;
     const size_t lds = (size_t)A.lds_per_wave * wpb;
-    const void *fn = p->bits == 2 ? reinterpret_cast<const void *>(k_apply<true>)
-                                  : reinterpret_cast<const void *>(k_apply<false>);
+    const bool two = p->bits == 2;
+    const void *fn = mom ? (two ? reinterpret_cast<const void *>(k_apply<true, true>)
+                                : reinterpret_cast<const void *>(k_apply<false, true>))
+                         : (two ? reinterpret_cast<const void *>(k_apply<true, false>)
+                                : reinterpret_cast<const void *>(k_apply<false, false>));
     if (lds > 65536) {
         hipError_t aerr = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (aerr != hipSuccess) {
@@ -322,8 +353,13 @@ int slk_apply(const sl_plan *p, float *theta, const void *const *payloads, int R
         }
     }
     const dim3 grid((unsigned)((p->n_chunks + wpb - 1) / wpb)), block(64 * wpb);
-    if (p->bits == 2) hipLaunchKernelGGL(k_apply<true>, grid, block, lds, st, A);
-    else hipLaunchKernelGGL(k_apply<false>, grid, block, lds, st, A);
+    if (mom) {
+        if (two) hipLaunchKernelGGL((k_apply<true, true>), grid, block, lds, st, A);
+        else hipLaunchKernelGGL((k_apply<false, true>), grid, block, lds, st, A);
+    } else {
+        if (two) hipLaunchKernelGGL((k_apply<true, false>), grid, block, lds, st, A);
+        else hipLaunchKernelGGL((k_apply<false, false>), grid, block, lds, st, A);
+    }
     hipError_t err = hipGetLastError();
     if (err != hipSuccess) {
         sl_note_hip_error(err);

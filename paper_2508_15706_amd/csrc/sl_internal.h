@@ -104,8 +104,14 @@ int slk_quantize(const sl_plan *p, float *e, int skip_residual, unsigned char *p
                  unsigned char *ws, hipStream_t st);
 // E on its own: e[idx] -= LUT[code] for the entries of `payload`
 int slk_residual(const sl_plan *p, float *e, const unsigned char *payload, hipStream_t st);
-int slk_apply(const sl_plan *p, float *theta, const void *const *payloads, int R, float lr,
-              hipStream_t st);
+// mom != null: DiLoCo's global Nesterov momentum on top of the aggregate
+int slk_apply(const sl_plan *p, float *theta, float *mom, float mu, const void *const *payloads, int R,
+              float lr, hipStream_t st);
+// dense outer steps of the DiLoCo family (sl_outer.hip) and Sub-k (sl_select.hip)
+int slk_lom_direction(const sl_plan *p, float *m, const float *delta, float mu, float *dir, hipStream_t st);
+int slk_dense_avg_apply(const sl_plan *p, float *theta, float *mom, const float *const *dirs, int R, float lr,
+                        float mu, hipStream_t st);
+int slk_sub_topk(const sl_plan *p, float *m, hipStream_t st);
 int slk_validate(const sl_plan *p, const unsigned char *payload, int *flag, hipStream_t st);
 int slk_pack(const uint16_t *idx, const uint8_t *codes, int64_t n_chunks, int k, unsigned char *out,
              hipStream_t st);

@@ -157,13 +157,17 @@ SL_DEV void select_general(int (&key)[64], unsigned sg0, unsigned sg1, int k, in
 #endif
 #define SL_SELECT_BOUNDS __launch_bounds__(256, SL_SELECT_WAVES_PER_EU)
 
-// PARAMS: the pseudo-gradient is formed on the fly from two parameter arenas
-// (a separate instantiation, so that the plain path keeps its register budget).
+// MODE 0: a = beta*e + delta.  MODE 1 (PARAMS): the pseudo-gradient is formed on
+// the fly from two parameter arenas (a separate instantiation, so that the plain
+// path keeps its register budget).  MODE 2 (SUBK): no accumulate at all - the
+// buffer itself is the operand of Top-k and its selected entries are set to
+// zero, m <- m - Top-k(m) (Section 3.2, DiLoCo-LOM-Sub-k); nothing else is written.
 // TWO_BIT: payloads carry 2-bit codes (the paper's setting; the width is then a
 // compile-time constant); otherwise the width is A.bits.
-template <int GPL, bool PARAMS, bool TWO_BIT>
+template <int GPL, int MODE, bool TWO_BIT>
 __global__ void SL_SELECT_BOUNDS k_select(SelectArgs A)
 {
+    constexpr bool PARAMS = MODE == 1, SUBK = MODE == 2;
     extern __shared__ __align__(16) unsigned char smem_all[];
     const int lane = threadIdx.x & 63;
     const int wave = sl_uniform((int)(threadIdx.x >> 6));
@@ -181,7 +185,7 @@ __global__ void SL_SELECT_BOUNDS k_select(SelectArgs A)
     double *scratch = reinterpret_cast<double *>(smem + cand_bytes + ((6 * (size_t)k + 7) & ~(size_t)7));
 
     float *ec = A.e + d.base;
-    const float *dc = A.delta + d.base;
+    const float *dc = SUBK ? nullptr : A.delta + d.base;
     const int lr = lane >> 4, lc = (lane & 15) * 4;
     const unsigned stride = (unsigned)d.stride;
     const bool full = d.flags & SLC_FULL;
@@ -271,7 +275,10 @@ __global__ void SL_SELECT_BOUNDS k_select(SelectArgs A)
         const unsigned o0 = 4u * (lr * stride + lc);   // byte offset of this lane's first load
         const unsigned step = 16u * stride;            // four rows further, in bytes
         sl_f4 ev[16], dv[16];
-        if constexpr (PARAMS) {
+        if constexpr (SUBK) {
+#pragma unroll
+            for (int i = 0; i < 16; ++i) ev[i] = sl_load_stream_at(ec, i * step, o0);
+        } else if constexpr (PARAMS) {
             // pseudo-gradient delta = theta_outer - theta_local (one fp32 subtraction),
             // formed before e is fetched so that at most two streams sit in registers
             const float *lc_ = A.theta_local + d.base;
@@ -294,7 +301,7 @@ __global__ void SL_SELECT_BOUNDS k_select(SelectArgs A)
 #pragma unroll
             for (int i = 0; i < 16; ++i) dv[i] = sl_load_stream_at(dc, i * step, o0);
         }
-        if (pend) {
+        if (!SUBK && pend) {
             pend_build();
             // e_true = e - (dequantised pending value) at this lane's positions:
             // local index 256*i + 4*lane + cc is bit 4*(lane%8) + cc of word 8*i + lane/8
@@ -315,7 +322,9 @@ __global__ void SL_SELECT_BOUNDS k_select(SelectArgs A)
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
             sl_f4 v;
-            if (!A.frozen) {
+            if constexpr (SUBK) {
+                v = ev[i];
+            } else if (!A.frozen) {
                 v.x = fmaf(A.beta, ev[i].x, dv[i].x);
                 v.y = fmaf(A.beta, ev[i].y, dv[i].y);
                 v.z = fmaf(A.beta, ev[i].z, dv[i].z);
@@ -435,7 +444,7 @@ __global__ void SL_SELECT_BOUNDS k_select(SelectArgs A)
     } else {
         // ------------------------------------------------------------ partial chunk, scalar accesses
         const int rows = d.rows, cols = d.cols, last_cols = d.last_cols;
-        if (pend) pend_build();
+        if (!SUBK && pend) pend_build();
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
             const int row = 4 * i + lr;
@@ -446,7 +455,9 @@ __global__ void SL_SELECT_BOUNDS k_select(SelectArgs A)
                 float v = 0.0f;
                 if (col < lim) {
                     const unsigned o = row * stride + col;
-                    if (!A.frozen) {
+                    if constexpr (SUBK) {
+                        v = ec[o];
+                    } else if (!A.frozen) {
                         float ee = ec[o];
                         if (pend) {
                             const unsigned w = 8 * i + (lane >> 3), bit = 4u * (lane & 7) + cc;
@@ -482,6 +493,15 @@ __global__ void SL_SELECT_BOUNDS k_select(SelectArgs A)
         select_general(key, sg0, sg1, k, lane, sel_val, sel_idx);
     }
     sl_wave_sync();
+
+    if constexpr (SUBK) {
+        // m - Top-k(m): x - x = +0.0 at the selected positions, the rest stays as it is
+        for (int p = lane; p < k; p += 64) {
+            const unsigned j = sel_idx[p];
+            ec[(j >> 6) * stride + (j & 63u)] = 0.0f;
+        }
+        return;
+    }
 
     // ---------------------------------------------------------------- outputs
     unsigned char *rec = A.payload + d.rec_off;
@@ -538,9 +558,9 @@ __global__ void SL_SELECT_BOUNDS k_select(SelectArgs A)
 
 }  // namespace
 
-int slk_select(const sl_plan *p, float *e, const float *delta, const float *theta_local, float beta,
-               int frozen, const unsigned char *pending, unsigned char *payload, unsigned char *ws,
-               hipStream_t st)
+static int launch_select(const sl_plan *p, float *e, const float *delta, const float *theta_local, float beta,
+                         int frozen, const unsigned char *pending, unsigned char *payload, unsigned char *ws,
+                         bool sub_only, hipStream_t st)
 {
     if (p->n_chunks == 0) return SL_OK;
     const int k = p->k;
@@ -566,29 +586,31 @@ int slk_select(const sl_plan *p, float *e, const float *delta, const float *thet
         if (pending) b += 2 * BM_WORDS * sizeof(unsigned) + 4 * (size_t)k + 16 * sizeof(float);
         A.lds_per_wave = (int)((b + 15) & ~(size_t)15);
     }
-    A.vals = reinterpret_cast<float *>(ws + p->ws_vals);
-    A.leafA = reinterpret_cast<double *>(ws + p->ws_leafA);
+    A.vals = sub_only ? nullptr : reinterpret_cast<float *>(ws + p->ws_vals);
+    A.leafA = sub_only ? nullptr : reinterpret_cast<double *>(ws + p->ws_leafA);
     A.payload = payload;
     A.n_chunks = p->n_chunks;
     // waves (= chunks) per workgroup: 4 adjacent chunks when their LDS fits
     const int wpb = 4 * (size_t)A.lds_per_wave <= 65536 ? 4 : 1;
     const dim3 grid((unsigned)((p->n_chunks + wpb - 1) / wpb)), block(64 * wpb);
     const size_t lds = (size_t)A.lds_per_wave * wpb;
-#define SL_LAUNCH_SELECT(PARAMS, TWO)                                                                 \
+#define SL_LAUNCH_SELECT(MODE, TWO)                                                                   \
     do {                                                                                              \
-        if (k <= 32) hipLaunchKernelGGL((k_select<1, PARAMS, TWO>), grid, block, lds, st, A);         \
-        else if (k <= 64) hipLaunchKernelGGL((k_select<2, PARAMS, TWO>), grid, block, lds, st, A);    \
-        else if (k <= 128) hipLaunchKernelGGL((k_select<4, PARAMS, TWO>), grid, block, lds, st, A);   \
-        else if (k <= 256) hipLaunchKernelGGL((k_select<8, PARAMS, TWO>), grid, block, lds, st, A);   \
-        else hipLaunchKernelGGL((k_select<0, PARAMS, TWO>), grid, block, lds, st, A);                 \
+        if (k <= 32) hipLaunchKernelGGL((k_select<1, MODE, TWO>), grid, block, lds, st, A);         \
+        else if (k <= 64) hipLaunchKernelGGL((k_select<2, MODE, TWO>), grid, block, lds, st, A);    \
+        else if (k <= 128) hipLaunchKernelGGL((k_select<4, MODE, TWO>), grid, block, lds, st, A);   \
+        else if (k <= 256) hipLaunchKernelGGL((k_select<8, MODE, TWO>), grid, block, lds, st, A);   \
+        else hipLaunchKernelGGL((k_select<0, MODE, TWO>), grid, block, lds, st, A);                 \
     } while (0)
     const bool two = p->bits == 2;
-    if (theta_local) {
-        if (two) SL_LAUNCH_SELECT(true, true);
-        else SL_LAUNCH_SELECT(true, false);
+    if (sub_only) {
+        SL_LAUNCH_SELECT(2, false);
+    } else if (theta_local) {
+        if (two) SL_LAUNCH_SELECT(1, true);
+        else SL_LAUNCH_SELECT(1, false);
     } else {
-        if (two) SL_LAUNCH_SELECT(false, true);
-        else SL_LAUNCH_SELECT(false, false);
+        if (two) SL_LAUNCH_SELECT(0, true);
+        else SL_LAUNCH_SELECT(0, false);
     }
 #undef SL_LAUNCH_SELECT
     hipError_t err = hipGetLastError();
@@ -597,4 +619,16 @@ int slk_select(const sl_plan *p, float *e, const float *delta, const float *thet
         return SL_ERR_HIP;
     }
     return SL_OK;
+}
+
+int slk_select(const sl_plan *p, float *e, const float *delta, const float *theta_local, float beta,
+               int frozen, const unsigned char *pending, unsigned char *payload, unsigned char *ws,
+               hipStream_t st)
+{
+    return launch_select(p, e, delta, theta_local, beta, frozen, pending, payload, ws, false, st);
+}
+
+int slk_sub_topk(const sl_plan *p, float *m, hipStream_t st)
+{
+    return launch_select(p, m, nullptr, nullptr, 1.0f, 0, nullptr, nullptr, nullptr, true, st);
 }
