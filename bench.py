@@ -70,6 +70,8 @@ def main():
     ap.add_argument("--flat", action="store_true", help="cut every tensor into runs of 4096")
     ap.add_argument("--bits", type=int, default=2, choices=[1, 2, 3, 4, 32],
                     help="payload value width (the paper's setting is 2; 32 = unquantized fp32)")
+    ap.add_argument("--outer-steps", action="store_true",
+                    help="also time the dense outer steps of the DiLoCo family (extra arenas: R + 1)")
     ap.add_argument("--delta-buffers", type=int, default=3)
     ap.add_argument("--cpu-layers", type=int, default=4)
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -243,6 +245,30 @@ def main():
             "lossless": bool(torch.equal(back[:plan.payload_bytes], own[0][:plan.payload_bytes])),
             "encode_ms": enc_ms, "decode_ms": dec_ms,
         }
+    if args.outer_steps:
+        # the DiLoCo-family entry points, each timed alone on the same list (context rows, not
+        # part of the step): algorithmic bytes = 4 B per element per stream touched
+        mom = torch.zeros(arena, dtype=torch.float32, device=dev)
+        dirs = [torch.empty(arena, dtype=torch.float32, device=dev) for _ in range(w.R)]
+        for r, dbuf in enumerate(dirs):
+            synth.fill_delta(w, dbuf, 2, r)
+        rows = {
+            "lom_direction": (lambda: sl.sl_lom_direction(plan, mom, deltas[0], 0.9, dirs[0]), 16 * N),
+            "dense_avg_apply": (lambda: sl.sl_dense_avg_apply(plan, theta, None, dirs, w.lr), (w.R + 2) * 4 * N),
+            "dense_avg_apply_nesterov": (lambda: sl.sl_dense_avg_apply(plan, theta, mom, dirs, w.lr, 0.9),
+                                         (w.R + 4) * 4 * N),
+            "decompress_avg_apply_nesterov": (
+                lambda: sl.sl_decompress_avg_apply_nesterov(plan, theta, mom, [own[0]] + pays[1:], w.lr, 0.9),
+                apply_bytes + 8 * N),
+            "sub_topk": (lambda: sl.sl_sub_topk(plan, mom), 4 * N + 4 * w.k * n_chunks),
+        }
+        out["outer_steps"] = {}
+        for name, (fn, nbytes) in rows.items():
+            if name == "sub_topk":
+                synth.fill_delta(w, mom, 3, 0)
+            ms = time_ms(fn)
+            out["outer_steps"][name] = {"ms": ms, "algorithmic_GBps": nbytes / (ms * 1e-3) / 1e9}
+        del mom, dirs
     if not args.no_cpu_baseline:
         del deltas, theta, e0
         out["cpu_baseline"] = cpu_baseline(w, args.cpu_layers)
