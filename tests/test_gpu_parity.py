@@ -125,6 +125,28 @@ def test_compress_ties_zeros_and_heavy_tails(sl, oracle, k):
     check_compress(sl, oracle, descs, n, k, e0, delta, 0.95, what="degenerate")
 
 
+@pytest.mark.parametrize("beta", [0.0, 0.9, 0.999, 1.0])
+def test_compress_other_ef_decays(sl, oracle, beta):
+    """The EF decay values of the paper's ablation (0.9, 0.95, 0.999; 1 = plain error feedback;
+    0 = no memory), two rounds so that the decay acts on a non-zero buffer."""
+    descs, n = layout_list([(150, 210, TILE), (1, 9000, FLAT), (128, 192, TILE)])
+    rng = np.random.default_rng(int(beta * 1000) + 11)
+    e0 = rng.normal(0, 1e-3, n).astype(np.float32)
+    for rnd in range(2):
+        delta = rng.normal(0, 1e-3, n).astype(np.float32)
+        _, e0 = check_compress(sl, oracle, descs, n, 64, e0, delta, beta, what=f"beta={beta} round {rnd}")
+
+
+@pytest.mark.parametrize("k", [1024, 2048, 4088])
+def test_compress_high_densities(sl, oracle, k):
+    """Densities of 25 %, 50 % and almost everything (the paper sweeps densities up to 50 %)."""
+    descs, n = layout_list([(128, 192, TILE), (1, 3 * 4096 + 4090, FLAT), (64, 64, TILE)])
+    rng = np.random.default_rng(k)
+    e0 = rng.normal(0, 1e-3, n).astype(np.float32)
+    delta = (1e-3 * rng.standard_t(3, n)).astype(np.float32)
+    check_compress(sl, oracle, descs, n, k, e0, delta, 0.95, what="high density")
+
+
 def test_compress_ef_frozen(sl, oracle):
     descs, n = layout_list([(140, 200, TILE), (1, 9000, FLAT)])
     rng = np.random.default_rng(9)
