@@ -279,19 +279,51 @@ __global__ void SL_SELECT_BOUNDS k_select(SelectArgs A)
 #pragma unroll
             for (int i = 0; i < 16; ++i) ev[i] = sl_load_stream_at(ec, i * step, o0);
         } else if constexpr (PARAMS) {
-            // pseudo-gradient delta = theta_outer - theta_local (one fp32 subtraction),
-            // formed before e is fetched so that at most two streams sit in registers
+            // pseudo-gradient delta = theta_outer - theta_local (one fp32 subtraction).
+            // Three input streams: the chunk is taken in four quarters (four 16-byte
+            // accesses per lane and stream each), finished one after the other, so that
+            // only a quarter of each stream sits in registers next to the result.
             const float *lc_ = A.theta_local + d.base;
-            sl_f4 tl[16];
+            const unsigned sh = 4u * (lane & 7);
 #pragma unroll
-            for (int i = 0; i < 16; ++i) dv[i] = sl_load_stream_at(dc, i * step, o0);
+            for (int q = 0; q < 4; ++q) {
+                sl_f4 dq[4], tq[4], eq[4];
 #pragma unroll
-            for (int i = 0; i < 16; ++i) tl[i] = sl_load_stream_at(lc_, i * step, o0);
+                for (int u = 0; u < 4; ++u) dq[u] = sl_load_stream_at(dc, (4 * q + u) * step, o0);
 #pragma unroll
-            for (int i = 0; i < 16; ++i) dv[i] = dv[i] - tl[i];
-            if (!A.frozen) {
+                for (int u = 0; u < 4; ++u) tq[u] = sl_load_stream_at(lc_, (4 * q + u) * step, o0);
+                if (!A.frozen) {
 #pragma unroll
-                for (int i = 0; i < 16; ++i) ev[i] = sl_load_stream_at(ec, i * step, o0);
+                    for (int u = 0; u < 4; ++u) eq[u] = sl_load_stream_at(ec, (4 * q + u) * step, o0);
+                }
+                if (q == 0 && pend) pend_build();
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const int i = 4 * q + u;
+                    const sl_f4 g = dq[u] - tq[u];
+                    sl_f4 v = g;
+                    if (!A.frozen) {
+                        sl_f4 ee = eq[u];
+                        if (pend) {
+                            const unsigned word = bm[8 * i + (lane >> 3)];
+                            const unsigned nib = (word >> sh) & 0xFu;
+                            if (nib) {
+                                int rk = (int)pre[8 * i + (lane >> 3)] + __popc(word & ((1u << sh) - 1u));
+                                if (nib & 1u) ee.x = ee.x - ql[rk++];
+                                if (nib & 2u) ee.y = ee.y - ql[rk++];
+                                if (nib & 4u) ee.z = ee.z - ql[rk++];
+                                if (nib & 8u) ee.w = ee.w - ql[rk++];
+                            }
+                        }
+                        v.x = fmaf(A.beta, ee.x, g.x);
+                        v.y = fmaf(A.beta, ee.y, g.y);
+                        v.z = fmaf(A.beta, ee.z, g.z);
+                        v.w = fmaf(A.beta, ee.w, g.w);
+                        sl_store_stream_at(ec, i * step, o0, v);
+                    }
+                    a[4 * i + 0] = v.x, a[4 * i + 1] = v.y, a[4 * i + 2] = v.z, a[4 * i + 3] = v.w;
+                }
+                __builtin_amdgcn_sched_barrier(0);   // keep the quarters apart: no hoisting of the next loads
             }
         } else {
             if (!A.frozen) {
@@ -301,7 +333,7 @@ __global__ void SL_SELECT_BOUNDS k_select(SelectArgs A)
 #pragma unroll
             for (int i = 0; i < 16; ++i) dv[i] = sl_load_stream_at(dc, i * step, o0);
         }
-        if (!SUBK && pend) {
+        if (!SUBK && !PARAMS && pend) {
             pend_build();
             // e_true = e - (dequantised pending value) at this lane's positions:
             // local index 256*i + 4*lane + cc is bit 4*(lane%8) + cc of word 8*i + lane/8
@@ -320,7 +352,7 @@ __global__ void SL_SELECT_BOUNDS k_select(SelectArgs A)
             }
         }
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {
+        for (int i = 0; i < (PARAMS ? 0 : 16); ++i) {
             sl_f4 v;
             if constexpr (SUBK) {
                 v = ev[i];
