@@ -70,6 +70,9 @@ def main():
     ap.add_argument("--flat", action="store_true", help="cut every tensor into runs of 4096")
     ap.add_argument("--bits", type=int, default=2, choices=[1, 2, 3, 4, 32],
                     help="payload value width (the paper's setting is 2; 32 = unquantized fp32)")
+    ap.add_argument("--graph", action="store_true",
+                    help="time the steps as replays of a captured HIP graph (takes the launch overhead "
+                         "out of small configurations; per-kernel times still come from eager steps)")
     ap.add_argument("--outer-steps", action="store_true",
                     help="also time the dense outer steps of the DiLoCo family (extra arenas: R + 1)")
     ap.add_argument("--delta-buffers", type=int, default=3)
@@ -157,8 +160,45 @@ def main():
     dt_other, prof_other = timed(other, max(2, args.steps // 4))
     ms_other = 1e3 * dt_other / max(2, args.steps // 4)
     dt, prof = timed(args.mode, args.steps)
-
     ms_step = 1e3 * dt / args.steps
+
+    graph_info = None
+    if args.graph:
+        # one graph = one full cycle of the step's buffer rotation (two payload buffers, the
+        # delta buffers), so that every replay continues the chain exactly as eager steps would
+        import math
+        cycle = 2 * len(deltas) // math.gcd(2, len(deltas))
+        if state["i"] % cycle:
+            for _ in range(cycle - state["i"] % cycle):
+                step(args.mode)
+        if state["pending"] is None and args.mode == "deferred":
+            for _ in range(cycle):
+                step(args.mode)                  # the captured first step expects a pending payload
+        torch.cuda.synchronize()
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(side):
+            with torch.cuda.graph(graph, stream=side):
+                for _ in range(cycle):
+                    step(args.mode)
+        torch.cuda.synchronize()
+        replays = max(1, -(-args.steps // cycle))
+        for _ in range(max(1, args.warmup // cycle)):
+            graph.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(replays):
+            graph.replay()
+        if state["pending"] is not None:
+            sl.sl_residual_apply(plan, e0, state["pending"])
+            state["pending"] = None
+        torch.cuda.synchronize()
+        ms_eager = ms_step
+        ms_step = 1e3 * (time.perf_counter() - t0) / (replays * cycle)
+        graph_info = {"steps_per_graph": cycle, "replays": replays, "eager_ms_per_step": ms_eager}
+        args.steps = replays * cycle
+
     rec = 3 * w.k // 2 + w.k * args.bits // 8
     hdr = 0 if args.bits == 32 else max(16, 4 << args.bits)
     bytes_round = 20 * N + (w.R + 1) * rec * n_chunks + hdr * len(descs) * (w.R + 1)
@@ -214,7 +254,7 @@ def main():
                      "achieved_GBps": bytes_round / (ms_step * 1e-3) / 1e9,
                      "frac_of_peak": bytes_round / (ms_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
                      "device_copy_GBps": copy_gbs},
-        "mode": args.mode,
+        "mode": args.mode, "hip_graph": graph_info,
         "other_mode": {"mode": other, "ms_per_step": ms_other, "value": N / (ms_other * 1e-3) / 1e9,
                        "kernels_ms": {p: prof_other[p][0] for p in prof_other}},
         "kernels_ms": {p: prof[p][0] for p in prof},

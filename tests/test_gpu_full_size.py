@@ -51,7 +51,7 @@ class SubList:
     def compare_payload(self, oracle, plan, pay_dev, ref, k, what):
         roff = 0
         for i, d in zip(self.index, self.descs):
-            nb = oracle.tensor_block_bytes(d, k)
+            nb = oracle.tensor_block_bytes_b(d, k, plan.value_bits)
             goff = plan.tensor_offset(i)
             got = pay_dev[goff:goff + nb].cpu().numpy()
             if not np.array_equal(got, ref[roff:roff + nb]):
@@ -70,12 +70,22 @@ class SubList:
             assert rel.max() <= 1e-6, f"{what}: {bad} values differ, max rel err {rel.max():.3e}"
 
 
-def run_config(sl, oracle, config_id, k, rounds, sample_names, full_first=True):
+def run_config(sl, oracle, config_id, k, rounds, sample_names, full_first=True, bits=2):
     from paper_2508_15706_amd import synth
     w = synth.workload(config_id, k=k)
     dev = torch.device("cuda:0")
     descs = [s.desc() for s in w.specs]
-    plan = sl.sl_plan_create(descs, w.k)
+    plan = sl.sl_plan_create(descs, w.k) if bits == 2 else sl.sl_plan_create_bits(descs, w.k, bits)
+
+    def o_compress(dd, kk, e, d, beta):
+        return oracle.compress(dd, kk, e, d, beta) if bits == 2 else oracle.compress_b(dd, kk, bits, e, d, beta)
+
+    def o_apply(dd, kk, th, pp, lr):
+        if bits == 2:
+            oracle.decompress_avg_apply(dd, kk, th, pp, lr)
+        else:
+            oracle.decompress_avg_apply_b(dd, kk, bits, th, pp, lr)
+
     assert plan.num_elements == w.N
     ws = sl.alloc_workspace(plan)
     sample = SubList(w, sample_names)
@@ -108,21 +118,21 @@ def run_config(sl, oracle, config_id, k, rounds, sample_names, full_first=True):
                 # the whole list against the oracle (e starts at zero for everybody)
                 full = SubList(w, None)
                 e_full = np.zeros(full.n, dtype=np.float32)
-                ref_full = oracle.compress(full.descs, w.k, e_full, full.gather(delta), w.beta)
+                ref_full = o_compress(full.descs, w.k, e_full, full.gather(delta), w.beta)
                 full.compare_payload(oracle, plan, out, ref_full, w.k, f"cfg{config_id} full list")
                 chk = e_dev[0].clone()
                 sl.sl_residual_apply(plan, chk, out)
                 torch.cuda.synchronize()
                 full.compare_values(chk, e_full, f"cfg{config_id} full-list e")
                 del chk, e_full, ref_full, full
-            ref = oracle.compress(sample.descs, w.k, e_ref[r], sample.gather(delta), w.beta)
+            ref = o_compress(sample.descs, w.k, e_ref[r], sample.gather(delta), w.beta)
             sample.compare_payload(oracle, plan, out, ref, w.k, f"cfg{config_id} round {rnd} worker {r}")
             if r > 0:
                 sample.compare_values(e_dev[r], e_ref[r], f"cfg{config_id} round {rnd} worker {r} e")
             ref_pays.append(ref)
         sl.sl_decompress_avg_apply(plan, theta, cur, w.lr)
         torch.cuda.synchronize()
-        oracle.decompress_avg_apply(sample.descs, w.k, theta_ref, ref_pays, w.lr)
+        o_apply(sample.descs, w.k, theta_ref, ref_pays, w.lr)
         sample.compare_values(theta, theta_ref, f"cfg{config_id} round {rnd} theta")
     sl.sl_residual_apply(plan, e_dev[0], pending)
     torch.cuda.synchronize()
@@ -166,3 +176,12 @@ def test_config5_moe_full_list(sl, oracle):
     names = {"l0.router", "l0.q", "l5.norm2", "final_norm"}
     names |= {s.name for s in w.specs if s.kind == "expert" and s.name.startswith(("l0.x", "l7.x1"))}
     run_config(sl, oracle, 5, None, 1, names)
+
+
+@pytest.mark.timeout(600)
+@pytest.mark.parametrize("bits", [1, 4, 32])
+def test_config2_190M_other_value_widths(sl, oracle, bits):
+    """Configuration 2 with 1-bit, 4-bit and unquantized fp32 values: two rounds on a sample
+    of whole tensors (the embedding with its ragged edge tiles among them), all 8 workers."""
+    run_config(sl, oracle, 2, None, 2, {"embed", "l0.q", "l5.gate", "l11.down", "l3.norm1", "final_norm"},
+               full_first=False, bits=bits)
