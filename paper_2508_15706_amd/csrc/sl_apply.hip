@@ -66,11 +66,11 @@ __global__ void __launch_bounds__(256) k_apply(ApplyArgs A)
         return q < hdr_words ? reinterpret_cast<const unsigned *>(p + lut_off)[q]
                              : reinterpret_cast<const unsigned *>(p + rec_off)[q - hdr_words];
     };
-    // The first 256 words of the first batch (all of it for R*7k/4 <= ~900 bytes) are
-    // fetched into registers BEFORE the theta loads: loads complete in order, so
-    // the decode below then waits for these few words only and runs while the
-    // chunk's 16 KB of theta are still in flight.
-    constexpr int PF = 4;
+    // The first 64*PF words of the first batch (all of it for R*(16 + 7k/4) <= 2 KB:
+    // R = 8 up to k = 128, R = 16 up to k = 64) are fetched into registers BEFORE the
+    // theta loads: loads complete in order, so the decode below then waits for these
+    // few words only and runs while the chunk's 16 KB of theta are still in flight.
+    constexpr int PF = 8;
     unsigned pf[PF];
     const int nb0 = min(A.batch, A.R);
     if (word_path) {
