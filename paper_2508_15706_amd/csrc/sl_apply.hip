@@ -4,8 +4,8 @@
 // sl_pack_indices (12-bit index fields + 2-bit codes).
 //
 // One wavefront owns one chunk.  The dense average never exists in HBM: the
-// chunk's 4096 fp32 accumulators live in LDS (16 KB), the R records (7k/4 bytes
-// each) are staged into LDS with coalesced loads, entries of one worker are
+// chunk's fp32 accumulators live in LDS (one half of the chunk at a time, 8 KB),
+// the R records (7k/4 bytes each) are staged into LDS with coalesced loads, entries of one worker are
 // distinct positions so they are added without conflicts, workers are added in
 // the order r = 0..R-1, and theta streams through registers once
 // (8 bytes per element of HBM traffic plus R*7k/4 bytes per chunk).
@@ -13,6 +13,13 @@
 #include "sl_internal.h"
 
 namespace {
+
+// When there is much to decode per chunk (R*k entries), the chunk is aggregated
+// in NH = 2 halves of 32 rows (local indices below / from 2048): 8 KB of
+// accumulators per wave instead of 16, so that twice as many waves - and twice
+// as many bytes of theta in flight - fit a compute unit while the decode runs.
+// With little to decode one pass (NH = 1) is slightly faster.
+constexpr int APPLY_HALVES_FROM = 768;       // R*k from which two halves pay (measured)
 
 struct ApplyArgs {
     const SlChunkDesc *desc;
@@ -34,17 +41,18 @@ struct ApplyArgs {
 // NESTEROV: DiLoCo's global outer momentum on top of the aggregate (Eq. (1);
 // appendix algorithm "Outer step for DiLoCo+Top-k[+EF]"): m <- mu*m + avg,
 // d <- avg + mu*m, theta <- theta - lr*d at every element of the chunk.
-template <bool TWO_BIT, bool NESTEROV>
+template <bool TWO_BIT, bool NESTEROV, int NH>
 __global__ void __launch_bounds__(256) k_apply(ApplyArgs A)
 {
+    constexpr int ACC_FLOATS = SL_CHUNK / NH, ROWS4 = 16 / NH;   // accumulators, 16-byte accesses per lane
     extern __shared__ __align__(16) unsigned char smem_all[];
     const int lane = threadIdx.x & 63, k = A.k;
     const int wave = sl_uniform((int)(threadIdx.x >> 6));
     const long long c = (long long)blockIdx.x * (blockDim.x >> 6) + wave;
     if (c >= A.n_chunks) return;
     unsigned char *smem = smem_all + (size_t)wave * A.lds_per_wave;
-    float *acc = reinterpret_cast<float *>(smem);                    // 4096 floats
-    unsigned char *stage = smem + SL_CHUNK * sizeof(float);
+    float *acc = reinterpret_cast<float *>(smem);                    // the chunk, or one half of it
+    unsigned char *stage = smem + ACC_FLOATS * sizeof(float);
     const SlChunkDesc d = A.desc[c];
     const int bits = TWO_BIT ? 2 : A.bits;
     const int hdr = TWO_BIT ? 16 : A.hdr_bytes, hdr_words = hdr >> 2;
@@ -97,105 +105,114 @@ __global__ void __launch_bounds__(256) k_apply(ApplyArgs A)
         }
     }
 
+    const bool single = A.R <= A.batch;      // every record fits the staging area at once
 #pragma unroll
-    for (int i = 0; i < 16; ++i)
-        reinterpret_cast<float4 *>(acc)[i * 64 + lane] = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int h = 0; h < NH; ++h) {
+#pragma unroll
+        for (int i = 0; i < ROWS4; ++i)
+            reinterpret_cast<float4 *>(acc)[i * 64 + lane] = make_float4(0.f, 0.f, 0.f, 0.f);
 
-    for (int r0 = 0; r0 < A.R; r0 += A.batch) {
-        const int nb = min(A.batch, A.R - r0);
-        sl_wave_sync();
-        if (word_path) {
-            int w0 = lane;
-            if (r0 == 0) {
+        for (int r0 = 0; r0 < A.R; r0 += A.batch) {
+            const int nb = min(A.batch, A.R - r0);
+            sl_wave_sync();
+            if (h == 0 || !single) {
+                if (word_path) {
+                    int w0 = lane;
+                    if (r0 == 0 && h == 0) {
 #pragma unroll
-                for (int u = 0; u < PF; ++u) {
-                    const int w = lane + 64 * u;
-                    if (w < nb * wpr_src) {
-                        const int r = w / wpr_src;
-                        reinterpret_cast<unsigned *>(stage)[r * wpr_dst + (w - r * wpr_src)] = pf[u];
+                        for (int u = 0; u < PF; ++u) {
+                            const int w = lane + 64 * u;
+                            if (w < nb * wpr_src) {
+                                const int r = w / wpr_src;
+                                reinterpret_cast<unsigned *>(stage)[r * wpr_dst + (w - r * wpr_src)] = pf[u];
+                            }
+                        }
+                        w0 = lane + 64 * PF;
+                    }
+                    for (int w = w0; w < nb * wpr_src; w += 64) {
+                        const int r = w / wpr_src, q = w - r * wpr_src;
+                        reinterpret_cast<unsigned *>(stage)[r * wpr_dst + q] = src_word(r0 + r, q);
+                    }
+                } else {
+                    for (int w = lane; w < nb * hdr_words; w += 64) {    // the tensor's LUT of each worker
+                        const int r = w / hdr_words, q = w - r * hdr_words;
+                        reinterpret_cast<unsigned *>(stage)[r * wpr_dst + q] =
+                            reinterpret_cast<const unsigned *>(A.payload[r0 + r] + lut_off)[q];
+                    }
+                    for (int b = lane; b < nb * rec_bytes; b += 64) {
+                        const int r = b / rec_bytes, q = b - r * rec_bytes;
+                        stage[r * rec_pad + hdr + q] = A.payload[r0 + r][rec_off + q];
                     }
                 }
-                w0 = lane + 64 * PF;
+                sl_wave_sync();
             }
-            for (int w = w0; w < nb * wpr_src; w += 64) {
-                const int r = w / wpr_src, q = w - r * wpr_src;
-                reinterpret_cast<unsigned *>(stage)[r * wpr_dst + q] = src_word(r0 + r, q);
+            for (int r = 0; r < nb; ++r) {
+                const float *lutp = reinterpret_cast<const float *>(stage + r * rec_pad);
+                float4 lut = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (TWO_BIT) lut = *reinterpret_cast<const float4 *>(lutp);
+                const unsigned char *rec = stage + r * rec_pad + hdr;
+                const unsigned char *codes = rec + 3 * k / 2;   // or the k fp32 values (4-byte aligned)
+                for (int m = lane; m < k; m += 64) {
+                    const int b = (3 * m) >> 1;
+                    const unsigned w = (unsigned)rec[b] | ((unsigned)rec[b + 1] << 8);
+                    const unsigned j = (m & 1) ? (w >> 4) : (w & 0xFFFu);
+                    if (NH == 1 || (int)(j >> 11) == h) {       // this half's entries
+                        float q;
+                        if (TWO_BIT) {
+                            const unsigned code = (codes[m >> 2] >> (2 * (m & 3))) & 3u;
+                            q = code == 0 ? lut.x : code == 1 ? lut.y : code == 2 ? lut.z : lut.w;
+                        } else if (bits == 32) {
+                            q = reinterpret_cast<const float *>(codes)[m];
+                        } else {
+                            q = lutp[sl_code_at(codes, m, bits)];
+                        }
+                        acc[j & (ACC_FLOATS - 1)] = acc[j & (ACC_FLOATS - 1)] + q;
+                    }
+                }
+                sl_wave_sync();           // worker r is complete before worker r+1 is added
+            }
+        }
+
+        if (full) {
+            const unsigned o0 = 4u * (lr * stride + lc), step = 16u * stride;
+#pragma unroll
+            for (int i8 = 0; i8 < ROWS4; ++i8) {
+                const int i = ROWS4 * h + i8;
+                const float4 a = reinterpret_cast<const float4 *>(acc)[i8 * 64 + lane];
+                sl_f4 g;
+                g.x = a.x * A.inv_R, g.y = a.y * A.inv_R, g.z = a.z * A.inv_R, g.w = a.w * A.inv_R;
+                if constexpr (NESTEROV) {
+                    sl_f4 m = mo[i];
+                    m.x = fmaf(A.mu, m.x, g.x), m.y = fmaf(A.mu, m.y, g.y);
+                    m.z = fmaf(A.mu, m.z, g.z), m.w = fmaf(A.mu, m.w, g.w);
+                    sl_store_stream_at(mc, i * step, o0, m);
+                    g.x = fmaf(A.mu, m.x, g.x), g.y = fmaf(A.mu, m.y, g.y);
+                    g.z = fmaf(A.mu, m.z, g.z), g.w = fmaf(A.mu, m.w, g.w);
+                }
+                sl_f4 v = th[i];
+                v.x = fmaf(A.neg_lr, g.x, v.x);
+                v.y = fmaf(A.neg_lr, g.y, v.y);
+                v.z = fmaf(A.neg_lr, g.z, v.z);
+                v.w = fmaf(A.neg_lr, g.w, v.w);
+                sl_store_stream_at(tc, i * step, o0, v);
             }
         } else {
-            for (int w = lane; w < nb * hdr_words; w += 64) {        // the tensor's LUT of each worker
-                const int r = w / hdr_words, q = w - r * hdr_words;
-                reinterpret_cast<unsigned *>(stage)[r * wpr_dst + q] =
-                    reinterpret_cast<const unsigned *>(A.payload[r0 + r] + lut_off)[q];
-            }
-            for (int b = lane; b < nb * rec_bytes; b += 64) {
-                const int r = b / rec_bytes, q = b - r * rec_bytes;
-                stage[r * rec_pad + hdr + q] = A.payload[r0 + r][rec_off + q];
-            }
-        }
-        sl_wave_sync();
-        for (int r = 0; r < nb; ++r) {
-            const float *lutp = reinterpret_cast<const float *>(stage + r * rec_pad);
-            float4 lut = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (TWO_BIT) lut = *reinterpret_cast<const float4 *>(lutp);
-            const unsigned char *rec = stage + r * rec_pad + hdr;
-            const unsigned char *codes = rec + 3 * k / 2;   // or the k fp32 values (4-byte aligned)
-            for (int m = lane; m < k; m += 64) {
-                const int b = (3 * m) >> 1;
-                const unsigned w = (unsigned)rec[b] | ((unsigned)rec[b + 1] << 8);
-                const unsigned j = (m & 1) ? (w >> 4) : (w & 0xFFFu);
-                float q;
-                if (TWO_BIT) {
-                    const unsigned code = (codes[m >> 2] >> (2 * (m & 3))) & 3u;
-                    q = code == 0 ? lut.x : code == 1 ? lut.y : code == 2 ? lut.z : lut.w;
-                } else if (bits == 32) {
-                    q = reinterpret_cast<const float *>(codes)[m];
-                } else {
-                    q = lutp[sl_code_at(codes, m, bits)];
-                }
-                acc[j] = acc[j] + q;
-            }
-            sl_wave_sync();           // worker r is complete before worker r+1 is added
-        }
-    }
-
-    if (full) {
-        const unsigned o0 = 4u * (lr * stride + lc), step = 16u * stride;
-#pragma unroll
-        for (int i = 0; i < 16; ++i) {
-            const float4 a = reinterpret_cast<const float4 *>(acc)[i * 64 + lane];
-            sl_f4 g;
-            g.x = a.x * A.inv_R, g.y = a.y * A.inv_R, g.z = a.z * A.inv_R, g.w = a.w * A.inv_R;
-            if constexpr (NESTEROV) {
-                sl_f4 m = mo[i];
-                m.x = fmaf(A.mu, m.x, g.x), m.y = fmaf(A.mu, m.y, g.y);
-                m.z = fmaf(A.mu, m.z, g.z), m.w = fmaf(A.mu, m.w, g.w);
-                sl_store_stream_at(mc, i * step, o0, m);
-                g.x = fmaf(A.mu, m.x, g.x), g.y = fmaf(A.mu, m.y, g.y);
-                g.z = fmaf(A.mu, m.z, g.z), g.w = fmaf(A.mu, m.w, g.w);
-            }
-            sl_f4 v = th[i];
-            v.x = fmaf(A.neg_lr, g.x, v.x);
-            v.y = fmaf(A.neg_lr, g.y, v.y);
-            v.z = fmaf(A.neg_lr, g.z, v.z);
-            v.w = fmaf(A.neg_lr, g.w, v.w);
-            sl_store_stream_at(tc, i * step, o0, v);
-        }
-    } else {
-        const int rows = d.rows, cols = d.cols, last_cols = d.last_cols;
-        for (int i = 0; i < 16; ++i) {
-            const int row = 4 * i + lr;
-            const int lim = row < rows - 1 ? cols : (row == rows - 1 ? last_cols : 0);
-            for (int cc = 0; cc < 4; ++cc) {
-                const int col = lc + cc;
-                if (col < lim) {
-                    const unsigned o = row * stride + col;
-                    float g = acc[256 * i + 4 * lane + cc] * A.inv_R;
-                    if constexpr (NESTEROV) {
-                        const float m = fmaf(A.mu, mc[o], g);
-                        mc[o] = m;
-                        g = fmaf(A.mu, m, g);
+            const int rows = d.rows, cols = d.cols, last_cols = d.last_cols;
+            for (int i8 = 0; i8 < ROWS4; ++i8) {
+                const int row = 4 * (ROWS4 * h + i8) + lr;
+                const int lim = row < rows - 1 ? cols : (row == rows - 1 ? last_cols : 0);
+                for (int cc = 0; cc < 4; ++cc) {
+                    const int col = lc + cc;
+                    if (col < lim) {
+                        const unsigned o = row * stride + col;
+                        float g = acc[256 * i8 + 4 * lane + cc] * A.inv_R;
+                        if constexpr (NESTEROV) {
+                            const float m = fmaf(A.mu, mc[o], g);
+                            mc[o] = m;
+                            g = fmaf(A.mu, m, g);
+                        }
+                        tc[o] = fmaf(A.neg_lr, g, tc[o]);
                     }
-                    tc[o] = fmaf(A.neg_lr, g, tc[o]);
                 }
             }
         }
@@ -336,30 +353,28 @@ int slk_apply(const sl_plan *p, float *theta, float *mom, float mu, const void *
     for (int r = 0; r < SL_MAX_WORKERS; ++r)
         A.payload[r] = r < R ? static_cast<const unsigned char *>(payloads[r]) : nullptr;
     A.n_chunks = p->n_chunks;
-    A.lds_per_wave = (int)((SL_CHUNK * sizeof(float) + (size_t)batch * rec_pad + 15) & ~(size_t)15);
+    const bool halves = (long long)R * p->k >= APPLY_HALVES_FROM;
+    const size_t acc_bytes = SL_CHUNK * sizeof(float) / (halves ? 2 : 1);
+    A.lds_per_wave = (int)((acc_bytes + (size_t)batch * rec_pad + 15) & ~(size_t)15);
     int wpb = 4;
     while (wpb > 1 && (size_t)A.lds_per_wave * wpb > (size_t)p->max_lds) wpb >>= 1;
     const size_t lds = (size_t)A.lds_per_wave * wpb;
     const bool two = p->bits == 2;
-    const void *fn = mom ? (two ? reinterpret_cast<const void *>(k_apply<true, true>)
-                                : reinterpret_cast<const void *>(k_apply<false, true>))
-                         : (two ? reinterpret_cast<const void *>(k_apply<true, false>)
-                                : reinterpret_cast<const void *>(k_apply<false, false>));
+    typedef void (*kernel_t)(ApplyArgs);
+    static const kernel_t table[2][2][2] = {
+        {{k_apply<false, false, 1>, k_apply<false, false, 2>}, {k_apply<false, true, 1>, k_apply<false, true, 2>}},
+        {{k_apply<true, false, 1>, k_apply<true, false, 2>}, {k_apply<true, true, 1>, k_apply<true, true, 2>}}};
+    const kernel_t fn = table[two ? 1 : 0][mom ? 1 : 0][halves ? 1 : 0];
     if (lds > 65536) {
-        hipError_t aerr = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        hipError_t aerr = hipFuncSetAttribute(reinterpret_cast<const void *>(fn),
+                                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (aerr != hipSuccess) {
             sl_note_hip_error(aerr);
             return SL_ERR_HIP;
         }
     }
     const dim3 grid((unsigned)((p->n_chunks + wpb - 1) / wpb)), block(64 * wpb);
-    if (mom) {
-        if (two) hipLaunchKernelGGL((k_apply<true, true>), grid, block, lds, st, A);
-        else hipLaunchKernelGGL((k_apply<false, true>), grid, block, lds, st, A);
-    } else {
-        if (two) hipLaunchKernelGGL((k_apply<true, false>), grid, block, lds, st, A);
-        else hipLaunchKernelGGL((k_apply<false, false>), grid, block, lds, st, A);
-    }
+    hipLaunchKernelGGL(fn, grid, block, lds, st, A);
     hipError_t err = hipGetLastError();
     if (err != hipSuccess) {
         sl_note_hip_error(err);
