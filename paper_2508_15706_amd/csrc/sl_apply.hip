@@ -353,7 +353,8 @@ int slk_apply(const sl_plan *p, float *theta, float *mom, float mu, const void *
     for (int r = 0; r < SL_MAX_WORKERS; ++r)
         A.payload[r] = r < R ? static_cast<const unsigned char *>(payloads[r]) : nullptr;
     A.n_chunks = p->n_chunks;
-    const bool halves = (long long)R * p->k >= APPLY_HALVES_FROM;
+    // (not when the staged records themselves are the larger part of the LDS: nothing would be gained)
+    const bool halves = (long long)R * p->k >= APPLY_HALVES_FROM && (size_t)batch * rec_pad <= 8192;
     const size_t acc_bytes = SL_CHUNK * sizeof(float) / (halves ? 2 : 1);
     A.lds_per_wave = (int)((acc_bytes + (size_t)batch * rec_pad + 15) & ~(size_t)15);
     int wpb = 4;
