@@ -200,6 +200,8 @@ __global__ void SL_SELECT_BOUNDS k_select(SelectArgs A)
     // record order (= ascending position, so rank in the map = record entry).
     unsigned *bm = nullptr, *pre = nullptr;
     float *ql = nullptr, *lutl = nullptr;
+    unsigned *tm = nullptr;                 // the same map once more, lane-major (see pend_build)
+    float *tq = nullptr;                    // value of the pending entry of (16-byte access i, lane), [16][64]
     const bool pend = A.pending != nullptr;
     const int bits = TWO_BIT ? 2 : A.bits;
     const unsigned char *prec = nullptr, *pcodes = nullptr;
@@ -219,6 +221,8 @@ __global__ void SL_SELECT_BOUNDS k_select(SelectArgs A)
         pre = bm + BM_WORDS;
         ql = reinterpret_cast<float *>(pre + BM_WORDS);
         lutl = ql + k;
+        tm = reinterpret_cast<unsigned *>(lutl + 16);
+        tq = reinterpret_cast<float *>(tm + 128);
         prec = A.pending + d.rec_off;
         pcodes = prec + 3 * k / 2;
         const unsigned char *lutg =
@@ -235,6 +239,7 @@ __global__ void SL_SELECT_BOUNDS k_select(SelectArgs A)
     // the small record loads above and this LDS work hide behind them.
     auto pend_build = [&]() {
         reinterpret_cast<uint2 *>(bm)[lane] = make_uint2(0u, 0u);
+        reinterpret_cast<uint2 *>(tm)[lane] = make_uint2(0u, 0u);
         if (bits != 2 && bits != 32 && lane < (1 << bits)) lutl[lane] = p_lutv;
         sl_wave_sync();
         auto entry = [&](int m, unsigned w, unsigned vw) {
@@ -250,6 +255,12 @@ __global__ void SL_SELECT_BOUNDS k_select(SelectArgs A)
             }
             ql[m] = q;
             atomicOr(&bm[j >> 5], 1u << (j & 31u));
+            // lane-major copy: position j = 256*i + 4*l + cc is bit 4*i + cc of lane l's 64 bits,
+            // i.e. one nibble per 16-byte access of that lane
+            atomicOr(&tm[2u * ((j >> 2) & 63u) + (j >> 11)], 1u << (((j >> 6) & 28u) + (j & 3u)));
+            // ... and the value where that lane finds it with one conflict-free read.  Two entries
+            // in one 16-byte access overwrite each other here: such an access takes the ranked path.
+            tq[((j >> 8) << 6) + ((j >> 2) & 63u)] = q;
         };
         if (lane < k) entry(lane, p_w0, p_c0);
         for (int m = lane + 64; m < k; m += 64) {
@@ -335,19 +346,32 @@ __global__ void SL_SELECT_BOUNDS k_select(SelectArgs A)
         }
         if (!SUBK && !PARAMS && pend) {
             pend_build();
-            // e_true = e - (dequantised pending value) at this lane's positions:
-            // local index 256*i + 4*lane + cc is bit 4*(lane%8) + cc of word 8*i + lane/8
+            // e_true = e - (dequantised pending value) at this lane's positions.  Which of them
+            // are pending comes from the lane-major map (two registers); the value of a 16-byte
+            // access with one pending position comes from the lane-major value table: sixteen
+            // independent reads, no branches.  An access with two or more pending positions
+            // (rare) goes to the position-ordered map for the ranks of its entries:
+            // local index 256*i + 4*lane + cc is bit 4*(lane%8) + cc of word 8*i + lane/8.
+            const uint2 t2 = reinterpret_cast<const uint2 *>(tm)[lane];
+            const unsigned long long mine = ((unsigned long long)t2.y << 32) | t2.x;
             const unsigned sh = 4u * (lane & 7);
 #pragma unroll
             for (int i = 0; i < 16; ++i) {
-                const unsigned word = bm[8 * i + (lane >> 3)];
-                const unsigned nib = (word >> sh) & 0xFu;
-                if (nib) {
+                const unsigned nib = (unsigned)(mine >> (4 * i)) & 0xFu;
+                const float q = tq[64 * i + lane];          // meaningful only where nib != 0
+                if (nib & (nib - 1u)) {
+                    const unsigned word = bm[8 * i + (lane >> 3)];
                     int rk = (int)pre[8 * i + (lane >> 3)] + __popc(word & ((1u << sh) - 1u));
                     if (nib & 1u) ev[i].x = ev[i].x - ql[rk++];
                     if (nib & 2u) ev[i].y = ev[i].y - ql[rk++];
                     if (nib & 4u) ev[i].z = ev[i].z - ql[rk++];
                     if (nib & 8u) ev[i].w = ev[i].w - ql[rk++];
+                } else {
+                    // x - (+0.0f) leaves every x as it is, signed zeros included
+                    ev[i].x = ev[i].x - ((nib & 1u) ? q : 0.0f);
+                    ev[i].y = ev[i].y - ((nib & 2u) ? q : 0.0f);
+                    ev[i].z = ev[i].z - ((nib & 4u) ? q : 0.0f);
+                    ev[i].w = ev[i].w - ((nib & 8u) ? q : 0.0f);
                 }
             }
         }
@@ -615,7 +639,8 @@ static int launch_select(const sl_plan *p, float *e, const float *delta, const f
         b += 64 * sizeof(double);
         b = (b + 15) & ~(size_t)15;
         A.pend_off = (int)b;
-        if (pending) b += 2 * BM_WORDS * sizeof(unsigned) + 4 * (size_t)k + 16 * sizeof(float);
+        if (pending) b += 2 * BM_WORDS * sizeof(unsigned) + 4 * (size_t)k + 16 * sizeof(float) + 64 * sizeof(uint2) +
+                         16 * 64 * sizeof(float);
         A.lds_per_wave = (int)((b + 15) & ~(size_t)15);
     }
     A.vals = sub_only ? nullptr : reinterpret_cast<float *>(ws + p->ws_vals);
