@@ -146,30 +146,58 @@ __global__ void __launch_bounds__(256) k_apply(ApplyArgs A)
                 }
                 sl_wave_sync();
             }
-            for (int r = 0; r < nb; ++r) {
+            // One entry of a staged record: local index (0xFFFF for none) and value.
+            auto decode = [&](int r, int m, unsigned &j, float &q) {
                 const float *lutp = reinterpret_cast<const float *>(stage + r * rec_pad);
-                float4 lut = make_float4(0.f, 0.f, 0.f, 0.f);
-                if (TWO_BIT) lut = *reinterpret_cast<const float4 *>(lutp);
                 const unsigned char *rec = stage + r * rec_pad + hdr;
                 const unsigned char *codes = rec + 3 * k / 2;   // or the k fp32 values (4-byte aligned)
-                for (int m = lane; m < k; m += 64) {
-                    const int b = (3 * m) >> 1;
-                    const unsigned w = (unsigned)rec[b] | ((unsigned)rec[b + 1] << 8);
-                    const unsigned j = (m & 1) ? (w >> 4) : (w & 0xFFFu);
-                    if (NH == 1 || (int)(j >> 11) == h) {       // this half's entries
-                        float q;
-                        if (TWO_BIT) {
-                            const unsigned code = (codes[m >> 2] >> (2 * (m & 3))) & 3u;
-                            q = code == 0 ? lut.x : code == 1 ? lut.y : code == 2 ? lut.z : lut.w;
-                        } else if (bits == 32) {
-                            q = reinterpret_cast<const float *>(codes)[m];
-                        } else {
-                            q = lutp[sl_code_at(codes, m, bits)];
+                const int b = (3 * m) >> 1;
+                const unsigned w = (unsigned)rec[b] | ((unsigned)rec[b + 1] << 8);
+                j = (m & 1) ? (w >> 4) : (w & 0xFFFu);
+                if (TWO_BIT) q = lutp[(codes[m >> 2] >> (2 * (m & 3))) & 3u];
+                else if (bits == 32) q = reinterpret_cast<const float *>(codes)[m];
+                else q = lutp[sl_code_at(codes, m, bits)];
+            };
+            if (NH == 1 && k <= 128) {
+                // The entries of up to eight workers are decoded first (independent LDS reads,
+                // all in flight together), then added worker by worker: the additions form a
+                // chain of LDS round trips, the decoding no longer sits inside it.
+                for (int rb = 0; rb < nb; rb += 8) {
+                    unsigned jj[8][2];
+                    float qq[8][2];
+#pragma unroll
+                    for (int u = 0; u < 8; ++u)
+#pragma unroll
+                        for (int s2 = 0; s2 < 2; ++s2) {
+                            const int m = lane + 64 * s2;
+                            jj[u][s2] = 0xFFFFu;
+                            qq[u][s2] = 0.0f;
+                            if (rb + u < nb && m < k) decode(rb + u, m, jj[u][s2], qq[u][s2]);
                         }
-                        acc[j & (ACC_FLOATS - 1)] = acc[j & (ACC_FLOATS - 1)] + q;
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) {
+                        if (rb + u < nb) {
+#pragma unroll
+                            for (int s2 = 0; s2 < 2; ++s2) {
+                                const unsigned j = jj[u][s2];
+                                if (j != 0xFFFFu && (NH == 1 || (int)(j >> 11) == h))
+                                    acc[j & (ACC_FLOATS - 1)] = acc[j & (ACC_FLOATS - 1)] + qq[u][s2];
+                            }
+                            sl_wave_sync();   // worker r is complete before worker r+1 is added
+                        }
                     }
                 }
-                sl_wave_sync();           // worker r is complete before worker r+1 is added
+            } else {
+                for (int r = 0; r < nb; ++r) {
+                    for (int m = lane; m < k; m += 64) {
+                        unsigned j;
+                        float q;
+                        decode(r, m, j, q);
+                        if (NH == 1 || (int)(j >> 11) == h)         // this half's entries
+                            acc[j & (ACC_FLOATS - 1)] = acc[j & (ACC_FLOATS - 1)] + q;
+                    }
+                    sl_wave_sync();           // worker r is complete before worker r+1 is added
+                }
             }
         }
 
