@@ -118,6 +118,12 @@ def lib():
         L.slo_rice_encode.argtypes = [tp, i32, i32, i32, vp, vp, i64]
         L.slo_rice_decode.restype = i32
         L.slo_rice_decode.argtypes = [tp, i32, i32, i32, vp, vp]
+        L.slo_rice_max_bytes_b.restype = i64
+        L.slo_rice_max_bytes_b.argtypes = [tp, i32, i32, i32, i32]
+        L.slo_rice_encode_b.restype = i64
+        L.slo_rice_encode_b.argtypes = [tp, i32, i32, i32, i32, vp, vp, i64]
+        L.slo_rice_decode_b.restype = i32
+        L.slo_rice_decode_b.argtypes = [tp, i32, i32, i32, i32, vp, vp]
         L.slo_max_threads.restype = i32
         L.slo_max_threads.argtypes = []
         _lib = L
@@ -474,4 +480,30 @@ def rice_decode(descs, k, coded, tile=64):
     st = lib().slo_rice_decode(arr, n, tile, k, _ptr(coded), _ptr(out))
     if st:
         raise ValueError(f"slo_rice_decode: status {st}")
+    return out
+
+
+def rice_max_bytes_b(descs, k, bits, tile=64):
+    arr, n = make_tensors(descs)
+    return int(lib().slo_rice_max_bytes_b(arr, n, tile, k, bits))
+
+
+def rice_encode_b(descs, k, bits, payload, tile=64):
+    arr, n = make_tensors(descs)
+    _check(payload, np.uint8)
+    cap = rice_max_bytes_b(descs, k, bits, tile)
+    out = np.zeros(cap, dtype=np.uint8)
+    size = int(lib().slo_rice_encode_b(arr, n, tile, k, bits, _ptr(payload), _ptr(out), cap))
+    if size < 0:
+        raise ValueError(f"slo_rice_encode_b: status {size}")
+    return out[:size].copy()
+
+
+def rice_decode_b(descs, k, bits, coded, tile=64):
+    arr, n = make_tensors(descs)
+    _check(coded, np.uint8)
+    out = np.zeros(payload_bytes_b(descs, k, bits, tile), dtype=np.uint8)
+    st = lib().slo_rice_decode_b(arr, n, tile, k, bits, _ptr(coded), _ptr(out))
+    if st:
+        raise ValueError(f"slo_rice_decode_b: status {st}")
     return out

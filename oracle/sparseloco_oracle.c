@@ -1035,6 +1035,140 @@ static uint32_t get_bits(const uint8_t *p, int64_t *bit, int n)
     return v;
 }
 
+/* The coder with the value width as a parameter (bits in {1, 2, 3, 4}, or 32
+ * for unquantized values): the look-up table header of a tensor block has
+ * slo_header_bytes_b(bits) bytes (none at 32), and a chunk's k gap codes are
+ * followed by its k value fields of `bits` bits each, copied as they stand in
+ * the plain record (at 32: the fp32 bit patterns, LSB first).  bits = 2 is the
+ * format described above. */
+
+/* Upper bound of the coded size of payloads of this list. */
+int64_t slo_rice_max_bytes_b(const slo_tensor *t, int nt, int tile, int k, int bits)
+{
+    int b = slo_rice_param(k);
+    int64_t chunk_bits = (int64_t)k * (1 + b) + (4096 >> b) + (int64_t)bits * k;
+    int64_t hdr = slo_header_bytes_b(bits);
+    int64_t total = 16 + 8 * (int64_t)nt + 16;
+    for (int i = 0; i < nt; ++i) {
+        int64_t nc = slo_tensor_chunks(&t[i], tile);
+        int64_t ng = (nc + SLO_RICE_GROUP - 1) / SLO_RICE_GROUP;
+        total += hdr + 4 * ng + ng * ((SLO_RICE_GROUP * chunk_bits + 31) / 32 * 4) + 16;
+    }
+    return total;
+}
+
+/* payload (plain wire format) -> coded buffer; returns the coded size or <0. */
+int64_t slo_rice_encode_b(const slo_tensor *t, int nt, int tile, int k, int bits,
+                          const uint8_t *payload, uint8_t *out, int64_t cap)
+{
+    if (!bits_ok(k, bits, tile)) return SLO_ERR_ARG;
+    const int b = slo_rice_param(k);
+    const int64_t rec = slo_record_bytes_b(k, bits), hdr = slo_header_bytes_b(bits);
+    uint16_t *idx = (uint16_t *)malloc((size_t)k * sizeof(uint16_t));
+    uint8_t *code = (uint8_t *)calloc((size_t)k, 1);
+    float *val = (float *)calloc((size_t)k, sizeof(float));
+    memset(out, 0, (size_t)cap);
+    int64_t pos = (16 + 8 * (int64_t)nt + 15) / 16 * 16, pay_off = 0;
+    for (int ti = 0; ti < nt; ++ti) {
+        int64_t nc = slo_tensor_chunks(&t[ti], tile);
+        int64_t ng = (nc + SLO_RICE_GROUP - 1) / SLO_RICE_GROUP;
+        uint64_t toff = (uint64_t)pos;
+        memcpy(out + 16 + 8 * ti, &toff, 8);
+        uint8_t *blk = out + pos;
+        memcpy(blk, payload + pay_off, (size_t)hdr);             /* look-up table */
+        int64_t cur = hdr + 4 * ng;                               /* byte offset in the block */
+        for (int64_t g = 0; g < ng; ++g) {
+            uint32_t goff = (uint32_t)cur;
+            memcpy(blk + hdr + 4 * g, &goff, 4);
+            slo_bitw w = {blk + cur, 0};
+            for (int64_t c = g * SLO_RICE_GROUP; c < nc && c < (g + 1) * SLO_RICE_GROUP; ++c) {
+                slo_unpack_record_b(payload + pay_off + hdr + c * rec, k, bits, idx, code, val);
+                int prev = -1;
+                for (int m = 0; m < k; ++m) {
+                    uint32_t gap = (uint32_t)(idx[m] - prev - 1);
+                    prev = idx[m];
+                    for (uint32_t q = gap >> b; q > 0; --q) put_bits(&w, 1u, 1);
+                    put_bits(&w, 0u, 1);
+                    put_bits(&w, gap, b);
+                }
+                for (int m = 0; m < k; ++m) {
+                    if (bits == 32) {
+                        uint32_t u;
+                        memcpy(&u, &val[m], 4);
+                        put_bits(&w, u, 32);
+                    } else {
+                        put_bits(&w, code[m], bits);
+                    }
+                }
+            }
+            cur += (w.bit + 31) / 32 * 4;
+            if (pos + cur > cap) {
+                free(idx), free(code), free(val);
+                return SLO_ERR_ARG;
+            }
+        }
+        pos += (cur + 15) / 16 * 16;
+        pay_off += slo_tensor_block_bytes_b(&t[ti], tile, k, bits);
+    }
+    memcpy(out, SLO_RICE_MAGIC, 8);
+    uint64_t total = (uint64_t)pos;
+    memcpy(out + 8, &total, 8);
+    free(idx), free(code), free(val);
+    return pos;
+}
+
+/* coded buffer -> payload in the plain wire format (every byte written). */
+int slo_rice_decode_b(const slo_tensor *t, int nt, int tile, int k, int bits, const uint8_t *in,
+                      uint8_t *payload)
+{
+    if (!bits_ok(k, bits, tile) || memcmp(in, SLO_RICE_MAGIC, 8)) return SLO_ERR_PAYLOAD;
+    const int b = slo_rice_param(k);
+    const int64_t rec = slo_record_bytes_b(k, bits), hdr = slo_header_bytes_b(bits);
+    uint16_t *idx = (uint16_t *)malloc((size_t)k * sizeof(uint16_t));
+    uint8_t *code = (uint8_t *)calloc((size_t)k, 1);
+    float *val = (float *)calloc((size_t)k, sizeof(float));
+    int64_t pay_off = 0;
+    int status = SLO_OK;
+    for (int ti = 0; ti < nt && status == SLO_OK; ++ti) {
+        int64_t nc = slo_tensor_chunks(&t[ti], tile);
+        int64_t ng = (nc + SLO_RICE_GROUP - 1) / SLO_RICE_GROUP;
+        uint64_t toff;
+        memcpy(&toff, in + 16 + 8 * ti, 8);
+        const uint8_t *blk = in + toff;
+        memset(payload + pay_off, 0, (size_t)slo_tensor_block_bytes_b(&t[ti], tile, k, bits));
+        memcpy(payload + pay_off, blk, (size_t)hdr);
+        for (int64_t g = 0; g < ng && status == SLO_OK; ++g) {
+            uint32_t goff;
+            memcpy(&goff, blk + hdr + 4 * g, 4);
+            int64_t bit = 0;
+            for (int64_t c = g * SLO_RICE_GROUP; c < nc && c < (g + 1) * SLO_RICE_GROUP; ++c) {
+                int prev = -1;
+                for (int m = 0; m < k; ++m) {
+                    uint32_t q = 0;
+                    while (get_bits(blk + goff, &bit, 1)) ++q;
+                    uint32_t gap = q << b | get_bits(blk + goff, &bit, b);
+                    int v = prev + 1 + (int)gap;
+                    if (v > 4095) status = SLO_ERR_PAYLOAD, v = 4095;
+                    idx[m] = (uint16_t)v;
+                    prev = v;
+                }
+                for (int m = 0; m < k; ++m) {
+                    if (bits == 32) {
+                        uint32_t u = get_bits(blk + goff, &bit, 32);
+                        memcpy(&val[m], &u, 4);
+                    } else {
+                        code[m] = (uint8_t)get_bits(blk + goff, &bit, bits);
+                    }
+                }
+                slo_pack_record_b(idx, code, val, k, bits, payload + pay_off + hdr + c * rec);
+            }
+        }
+        pay_off += slo_tensor_block_bytes_b(&t[ti], tile, k, bits);
+    }
+    free(idx), free(code), free(val);
+    return status;
+}
+
 /* Upper bound of the coded size of payloads of this list. */
 int64_t slo_rice_max_bytes(const slo_tensor *t, int nt, int tile, int k)
 {

@@ -139,3 +139,84 @@ def bits_k32(oracle):
     descs = [(1, 4096 * nc, 0, FLAT)]
     enc = oracle.rice_encode(descs, 32, make_payload(oracle, descs, 32, rng))
     return enc.size * 8 / (nc * 32) - 2
+
+
+# --------------------------------------------------------------------------- other value widths
+def make_payload_b(oracle, descs, k, bits, rng):
+    pay = np.zeros(oracle.payload_bytes_b(descs, k, bits), dtype=np.uint8)
+    hdr, rec, off = oracle.header_bytes_b(bits), oracle.record_bytes_b(k, bits), 0
+    for d in descs:
+        if bits != 32:
+            pay[off:off + 4 * (1 << bits)] = rng.normal(0, 1e-3, 1 << bits).astype(np.float32).view(np.uint8)
+        for c in range(oracle.tensor_chunks(d)):
+            idx = np.sort(rng.choice(4096, k, replace=False))
+            sent = rng.normal(0, 1e-3, k).astype(np.float32) if bits == 32 else rng.integers(0, 1 << bits, k)
+            pay[off + hdr + c * rec: off + hdr + (c + 1) * rec] = oracle.pack_record_b(idx, sent, bits)
+        off += oracle.tensor_block_bytes_b(d, k, bits)
+    return pay
+
+
+def test_rice_two_bits_is_the_pinned_coder(oracle):
+    rng = np.random.default_rng(950)
+    descs = [(150, 210, 0, TILE), (1, 4096 * 9 + 1100, 150 * 210 + 20, FLAT)]
+    for k in (4, 32, 64, 100):
+        pay = make_payload(oracle, descs, k, rng)
+        enc = oracle.rice_encode(descs, k, pay)
+        assert np.array_equal(oracle.rice_encode_b(descs, k, 2, pay), enc)
+        assert np.array_equal(oracle.rice_decode_b(descs, k, 2, enc), pay)
+        assert oracle.rice_max_bytes_b(descs, k, 2) == oracle.rice_max_bytes(descs, k)
+
+
+@pytest.mark.parametrize("bits", [1, 3, 4, 32])
+def test_rice_other_widths_stream_model_and_round_trip(oracle, bits):
+    """One tensor of 11 chunks (two groups): the coded block is the table, the group offsets and,
+    per group, the chunks' gap codes (the pinned 2-bit coder's, unchanged) each followed by the k
+    value fields of `bits` bits - rebuilt here bit by bit from the records."""
+    k, nc = 16, 11
+    b = oracle.rice_param(k)
+    descs = [(1, 4096 * nc, 0, FLAT)]
+    rng = np.random.default_rng(960 + bits)
+    pay = make_payload_b(oracle, descs, k, bits, rng)
+    enc = oracle.rice_encode_b(descs, k, bits, pay)
+    assert enc.size <= oracle.rice_max_bytes_b(descs, k, bits)
+    assert np.array_equal(oracle.rice_decode_b(descs, k, bits, enc), pay)
+    hdr, rec = oracle.header_bytes_b(bits), oracle.record_bytes_b(k, bits)
+    assert enc[:8].tobytes() == b"SLRICE01" and int(enc[8:16].view(np.uint64)[0]) == enc.size
+    blk = enc[int(enc[16:24].view(np.uint64)[0]):]
+    assert np.array_equal(blk[:hdr], pay[:hdr])
+    goff = blk[hdr:hdr + 8].view(np.uint32)
+    assert goff[0] == hdr + 8
+    for g, (lo, hi) in enumerate(((0, 8), (8, 11))):
+        stream = []
+        for c in range(lo, hi):
+            idx, sent = oracle.unpack_record_b(pay[hdr + c * rec: hdr + (c + 1) * rec], k, bits)
+            prev = -1
+            for v in idx.astype(int):
+                gap = v - prev - 1
+                prev = v
+                stream += [1] * (gap >> b) + [0] + [(gap >> i) & 1 for i in range(b)]
+            fields = sent.view(np.uint32) if bits == 32 else sent
+            for f in fields.astype(np.uint64):
+                stream += [(int(f) >> i) & 1 for i in range(bits)]
+        want = bits_to_bytes(stream)
+        at = int(goff[g])
+        assert blk[at:at + len(want)].tobytes() == want, (bits, g)
+        end = int(goff[1]) if g == 0 else blk.size
+        if g == 0:
+            assert end - at == (len(want) + 3) // 4 * 4          # a group is padded to 4 bytes
+        assert not blk[at + len(want):end].any()
+
+
+@pytest.mark.parametrize("bits", [1, 3, 4, 32])
+@pytest.mark.parametrize("k", [8, 64, 104, 1024])
+def test_rice_other_widths_round_trip(oracle, bits, k):
+    rng = np.random.default_rng(970 + bits + k)
+    shapes = [(150, 210, TILE), (1, 4096 * 19 + 1100, FLAT), (1024, 16, TILE)] if k <= 256 else [(160, 224, TILE), (1, 4096 * 3, FLAT)]
+    descs, off = [], 0
+    for r, c, lay in shapes:
+        descs.append((r, c, off, lay))
+        off += (r * c + 63) // 64 * 64
+    pay = make_payload_b(oracle, descs, k, bits, rng)
+    enc = oracle.rice_encode_b(descs, k, bits, pay)
+    assert enc.size <= oracle.rice_max_bytes_b(descs, k, bits)
+    assert np.array_equal(oracle.rice_decode_b(descs, k, bits, enc), pay)
