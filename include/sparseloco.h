@@ -91,8 +91,7 @@ int sl_plan_destroy(sl_plan *plan);
  * c_j = 12 j / 2^bits - 6, end bins open-ended, per-bin centroid table - or 32:
  * the selected fp32 values travel unquantized and the error update leaves an
  * exact zero at every sent position.  Every other call works on such a plan
- * with the sizes and formats that follow from its width, except the index coder
- * (sl_rice_*: 2-bit plans only, INVALID_ARG otherwise).  Wire format: per
+ * with the sizes and formats that follow from its width.  Wire format: per
  * tensor a header of 2^bits floats padded with zeros to 16 bytes (no header at
  * 32), then per chunk the k 12-bit indices followed by the k codes as a
  * little-endian stream of bits-wide fields, or by the k fp32 values; a record
@@ -245,6 +244,8 @@ int sl_pack_indices_bits(const uint16_t *idx, const uint8_t *codes, const float 
  * the paper gives the rates it reaches - 8.9 / 6.6 / 5.6 bits per index for
  * k = 32 / 128 / 256 - but not the algorithm, so the coded format is this
  * library's own and is described in csrc/sl_rice.hip).  Lossless both ways.
+ * Works at every value width of sl_plan_create_bits: a chunk's gap codes are
+ * followed by its k value fields as they stand in the plain record.
  *
  * sl_rice_encode: payload (plain wire format, device) -> coded buffer `out`
  *   (device, 16-byte aligned, capacity >= sl_rice_max_bytes(), else

@@ -166,11 +166,11 @@ int sl_plan_create_bits(const sl_tensor *tensors, int n_tensors, int k, int valu
     {
         // upper bound of a coded payload (see sl_rice_encode) and the scratch its encoder needs
         const int b = sl_rice_param(k);
-        const size_t chunk_bits = (size_t)k * (1 + b) + (4096 >> b) + 2 * (size_t)k;
+        const size_t chunk_bits = (size_t)k * (1 + b) + (4096 >> b) + (size_t)bits * k;
         size_t total = 16 + 8 * (size_t)n_tensors + 16;
         for (int t = 0; t < n_tensors; ++t) {
             const size_t ng = (size_t)((tdev[(size_t)t].n_chunks + SL_RICE_GROUP - 1) / SL_RICE_GROUP);
-            total += 16 + 4 * ng + ng * ((SL_RICE_GROUP * chunk_bits + 31) / 32 * 4) + 16;
+            total += (size_t)hdr + 4 * ng + ng * ((SL_RICE_GROUP * chunk_bits + 31) / 32 * 4) + 16;
         }
         p->rice_max_bytes = total;
         const size_t rice_ws = align_up(8 * groups.size(), 256) + 8 * (size_t)n_tensors + 256;
@@ -292,12 +292,12 @@ int sl_compress_params(sl_plan *p, float *e, const float *theta_outer, const flo
     return compress_impl(p, e, theta_outer, theta_local, beta, flags, pending, payload, workspace, stream);
 }
 
-size_t sl_rice_max_bytes(const sl_plan *p) { return p && p->bits == 2 ? p->rice_max_bytes : 0; }
+size_t sl_rice_max_bytes(const sl_plan *p) { return p ? p->rice_max_bytes : 0; }
 
 int sl_rice_encode(sl_plan *p, const void *payload, void *out, size_t out_capacity, void *workspace,
                    void *stream)
 {
-    if (!p || !payload || !out || !workspace || p->bits != 2) return SL_ERR_INVALID_ARG;
+    if (!p || !payload || !out || !workspace) return SL_ERR_INVALID_ARG;
     if (out_capacity < p->rice_max_bytes || payload == out) return SL_ERR_INVALID_ARG;
     if (misaligned(payload, 16) || misaligned(out, 16) || misaligned(workspace, 256))
         return SL_ERR_INVALID_ARG;
@@ -309,7 +309,7 @@ int sl_rice_encode(sl_plan *p, const void *payload, void *out, size_t out_capaci
 
 int sl_rice_decode(sl_plan *p, const void *in, size_t in_bytes, void *payload, void *stream)
 {
-    if (!p || !in || !payload || in == payload || p->bits != 2) return SL_ERR_INVALID_ARG;
+    if (!p || !in || !payload || in == payload) return SL_ERR_INVALID_ARG;
     if (in_bytes < 16 + 8 * (size_t)p->n_tensors) return SL_ERR_INVALID_ARG;
     if (misaligned(in, 16) || misaligned(payload, 16)) return SL_ERR_INVALID_ARG;
     int rc = check_device(p);

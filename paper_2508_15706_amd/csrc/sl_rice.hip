@@ -13,7 +13,10 @@
 // a 4-byte boundary.  Tensor block (16-byte aligned): float LUT[4]; uint32
 // goff[n_groups] = byte offset of each group from the block start; the
 // streams; zero padding to 16.  Buffer: "SLRICE01", uint64 total bytes, uint64
-// tensor_off[n_tensors], zero padding to 16, the blocks.
+// tensor_off[n_tensors], zero padding to 16, the blocks.  At another value
+// width (1, 3, 4 bits, or 32 = unquantized) the table has 2^bits floats padded
+// to 16 bytes (none at 32) and a chunk's gap codes are followed by its k value
+// fields of that width, as they stand in the plain record.
 //
 // One lane codes or decodes one group sequentially (a group is the unit that
 // cannot be split); sizes are found first, then two small scans place the
@@ -117,6 +120,7 @@ struct RiceArgs {
     long long n_groups;
     int n_tensors;
     int k, b;
+    int bits, hdr_bytes, rec_bytes;   // value width of the payload and the sizes that follow from it
     unsigned *gsize;               // [n_groups] coded bytes of each group
     unsigned *goff;                // [n_groups] byte offset of each group in its block
     unsigned long long *tbytes;    // [n_tensors] bytes of each tensor block
@@ -131,12 +135,12 @@ SL_DEV unsigned code_group(const RiceArgs &A, long long G, const unsigned char *
     const SlGroup g = A.groups[G];
     const SlTensorDev td = A.tensors[g.tensor];
     const int k = A.k, b = A.b;
-    const long long rec = (long long)7 * k / 4;
+    const long long rec = A.rec_bytes;
     const long long c0 = (long long)g.local_group * SL_RICE_GROUP;
     const int nc = (int)min((long long)SL_RICE_GROUP, td.n_chunks - c0);
     BitWriter<COUNT, true> w(dst);
     for (int i = 0; i < nc; ++i) {
-        const unsigned char *r = payload + td.pay_off + 16 + (c0 + i) * rec;
+        const unsigned char *r = payload + td.pay_off + A.hdr_bytes + (c0 + i) * rec;
         BitReader<WORDS> rd(r, r + rec);
         int prev = -1;
         for (int m = 0; m < k; ++m) {
@@ -151,11 +155,11 @@ SL_DEV unsigned code_group(const RiceArgs &A, long long G, const unsigned char *
             if (q) w.put((1u << q) - 1u, (int)q);
             w.put((gap & ((1u << b) - 1u)) << 1, b + 1);      // the zero bit, then the remainder
         }
-        if (WORDS) {
-            for (int m = 0; m < k; m += 16) w.put(rd.get(32), 32);
-        } else {
-            for (int m = 0; m < k; m += 4) w.put(rd.get(8), 8);
-        }
+        // the k value fields as they stand in the record (k * bits is a multiple of 8)
+        int left = k * A.bits;
+        const int piece = WORDS ? 32 : 8;
+        for (; left >= piece; left -= piece) w.put(rd.get(piece), piece);
+        if (left) w.put(rd.get(left), left);
     }
     w.flush_word();
     return (unsigned)(w.total >> 3);
@@ -177,7 +181,7 @@ __global__ void __launch_bounds__(256) k_rice_scan(RiceArgs A)
     const SlTensorDev td = A.tensors[blockIdx.x];
     const long long ng = (td.n_chunks + SL_RICE_GROUP - 1) / SL_RICE_GROUP;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    if (tid == 0) carry = 16ull + 4ull * (unsigned long long)ng;
+    if (tid == 0) carry = (unsigned long long)A.hdr_bytes + 4ull * (unsigned long long)ng;
     __syncthreads();
     for (long long base = 0; base < ng; base += 256) {
         const long long i = base + tid;
@@ -225,10 +229,11 @@ __global__ void __launch_bounds__(64) k_rice_encode(RiceArgs A, const unsigned c
     const SlTensorDev td = A.tensors[g.tensor];
     unsigned char *blk = out + reinterpret_cast<const unsigned long long *>(out)[2 + g.tensor];
     const unsigned off = A.goff[G];
-    reinterpret_cast<unsigned *>(blk + 16)[g.local_group] = off;
+    reinterpret_cast<unsigned *>(blk + A.hdr_bytes)[g.local_group] = off;
     const unsigned bytes = code_group<false, WORDS>(A, G, payload, blk + off);
-    if (g.local_group == 0)
-        *reinterpret_cast<float4 *>(blk) = *reinterpret_cast<const float4 *>(payload + td.pay_off);
+    if (g.local_group == 0)                                    // the look-up table (a multiple of 16 bytes)
+        for (int q = 0; q < A.hdr_bytes; q += 16)
+            *reinterpret_cast<float4 *>(blk + q) = *reinterpret_cast<const float4 *>(payload + td.pay_off + q);
     const long long ng = (td.n_chunks + SL_RICE_GROUP - 1) / SL_RICE_GROUP;
     if (g.local_group == ng - 1)                               // zero padding of the block
         for (unsigned long long q = off + bytes; q < A.tbytes[g.tensor]; q += 4)
@@ -243,21 +248,21 @@ __global__ void __launch_bounds__(64) k_rice_decode(RiceArgs A, const unsigned c
     if (G >= A.n_groups) return;
     const SlGroup g = A.groups[G];
     const SlTensorDev td = A.tensors[g.tensor];
-    const int k = A.k, b = A.b;
-    const long long rec = (long long)7 * k / 4;
+    const int k = A.k, b = A.b, hdr = A.hdr_bytes;
+    const long long rec = A.rec_bytes;
     const unsigned char *end = in + in_bytes;
     unsigned long long toff = reinterpret_cast<const unsigned long long *>(in)[2 + g.tensor];
     if (toff > in_bytes) toff = in_bytes;
     const unsigned char *blk = in + toff;
     unsigned long long off = in_bytes;                         // beyond the end: reads as zeros
-    if (blk + 16 + 4ull * (g.local_group + 1) <= end)
-        off = toff + reinterpret_cast<const unsigned *>(blk + 16)[g.local_group];
+    if (blk + hdr + 4ull * (g.local_group + 1) <= end)
+        off = toff + reinterpret_cast<const unsigned *>(blk + hdr)[g.local_group];
     if (off > in_bytes) off = in_bytes;
     BitReader<true> rd(in + (off & ~3ull), end);
     const long long c0 = (long long)g.local_group * SL_RICE_GROUP;
     const int nc = (int)min((long long)SL_RICE_GROUP, td.n_chunks - c0);
     for (int i = 0; i < nc; ++i) {
-        unsigned char *r = payload + td.pay_off + 16 + (c0 + i) * rec;
+        unsigned char *r = payload + td.pay_off + hdr + (c0 + i) * rec;
         BitWriter<false, WORDS> w(r);
         int prev = -1;
         for (int m = 0; m < k; ++m) {
@@ -268,20 +273,21 @@ __global__ void __launch_bounds__(64) k_rice_decode(RiceArgs A, const unsigned c
             prev = idx;
             w.put((unsigned)idx, 12);
         }
-        if (WORDS) {
-            for (int m = 0; m < k; m += 16) w.put(rd.get(32), 32);
-        } else {
-            for (int m = 0; m < k; m += 4) w.put(rd.get(8), 8);
-        }
+        int left = k * A.bits;
+        const int piece = WORDS ? 32 : 8;
+        for (; left >= piece; left -= piece) w.put(rd.get(piece), piece);
+        if (left) w.put(rd.get(left), left);
     }
     if (g.local_group == 0) {
-        float4 lut = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (blk + 16 <= end) lut = *reinterpret_cast<const float4 *>(blk);
-        *reinterpret_cast<float4 *>(payload + td.pay_off) = lut;
+        for (int q = 0; q < hdr; q += 16) {
+            float4 lut = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (blk + q + 16 <= end) lut = *reinterpret_cast<const float4 *>(blk + q);
+            *reinterpret_cast<float4 *>(payload + td.pay_off + q) = lut;
+        }
     }
     const long long ng = (td.n_chunks + SL_RICE_GROUP - 1) / SL_RICE_GROUP;
     if (g.local_group == ng - 1)                               // padding of the plain tensor block
-        for (long long q = 16 + td.n_chunks * rec; q < td.block_bytes; ++q) payload[td.pay_off + q] = 0;
+        for (long long q = hdr + td.n_chunks * rec; q < td.block_bytes; ++q) payload[td.pay_off + q] = 0;
 }
 
 int launched()
@@ -304,6 +310,9 @@ RiceArgs make_args(const sl_plan *p, unsigned char *ws)
     A.n_tensors = p->n_tensors;
     A.k = p->k;
     A.b = sl_rice_param(p->k);
+    A.bits = p->bits;
+    A.hdr_bytes = p->hdr_bytes;
+    A.rec_bytes = p->rec_bytes;
     const size_t sec = ((size_t)p->n_groups * 4 + 255) & ~(size_t)255;
     A.gsize = ws ? reinterpret_cast<unsigned *>(ws) : nullptr;
     A.goff = ws ? reinterpret_cast<unsigned *>(ws + sec) : nullptr;
@@ -317,7 +326,7 @@ int slk_rice_encode(const sl_plan *p, const unsigned char *payload, unsigned cha
                     unsigned char *ws, hipStream_t st)
 {
     const RiceArgs A = make_args(p, ws);
-    const bool words = (p->k & 15) == 0;      // records and their code runs are 4-byte aligned
+    const bool words = (p->rec_bytes & 3) == 0 && ((3 * p->k / 2) & 3) == 0;   // records and their value runs are 4-byte aligned
     const unsigned nblk = (unsigned)((p->n_groups + 63) / 64);
     int rc;
     if (p->n_groups > 0) {
@@ -342,7 +351,7 @@ int slk_rice_decode(const sl_plan *p, const unsigned char *in, size_t in_bytes, 
 {
     if (p->n_groups == 0) return SL_OK;
     const RiceArgs A = make_args(p, nullptr);
-    const bool words = (p->k & 15) == 0;
+    const bool words = (p->rec_bytes & 3) == 0 && ((3 * p->k / 2) & 3) == 0;
     const unsigned nblk = (unsigned)((p->n_groups + 63) / 64);
     if (words)
         hipLaunchKernelGGL(k_rice_decode<true>, dim3(nblk), dim3(64), 0, st, A, in,

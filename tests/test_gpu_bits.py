@@ -54,9 +54,20 @@ def test_compress_matches_oracle(sl, oracle, bits, k):
         raise AssertionError(f"bits={bits} k={k}: payload differs at {diff.size} bytes, first at {diff[:8]}")
     assert_f32_close(e.cpu().numpy(), e_ref, f"bits={bits} k={k} e")
     assert sl.sl_payload_validate(plan, pay, ws)
-    if bits != 2:
-        with pytest.raises(sl.SparseLoCoError):
-            sl.sl_rice_encode(plan, pay, torch.zeros(1 << 20, dtype=torch.uint8, device="cuda"), ws)
+    # the index coder at this width: the oracle's coded bytes, and back
+    ref_enc = oracle.rice_encode_b(descs, k, bits, ref)
+    cap = sl.sl_rice_max_bytes(plan)
+    assert cap == oracle.rice_max_bytes_b(descs, k, bits) >= ref_enc.size
+    out = torch.full((cap,), 0xCD, dtype=torch.uint8, device="cuda")
+    sl.sl_rice_encode(plan, pay, out, ws)
+    torch.cuda.synchronize()
+    coded = out.cpu().numpy()
+    size = int(coded[8:16].view(np.uint64)[0])
+    assert size == ref_enc.size and np.array_equal(coded[:size], ref_enc)
+    back = torch.full((max(16, plan.payload_bytes),), 0xEE, dtype=torch.uint8, device="cuda")
+    sl.sl_rice_decode(plan, out, size, back)
+    torch.cuda.synchronize()
+    assert np.array_equal(back[:plan.payload_bytes].cpu().numpy(), ref)
     plan.close()
 
 
@@ -171,4 +182,4 @@ def test_argument_errors(sl):
     plan = sl.sl_plan_create_bits([(64, 64, 0, TILE)], 12, 2)      # a multiple of 4 is enough at 2 bits
     assert plan.value_bits == 2 and sl.sl_rice_max_bytes(plan) > 0
     plan = sl.sl_plan_create_bits([(64, 64, 0, TILE)], 16, 3)
-    assert sl.sl_rice_max_bytes(plan) == 0
+    assert plan.value_bits == 3 and sl.sl_rice_max_bytes(plan) > 0
