@@ -185,3 +185,52 @@ def test_config2_190M_other_value_widths(sl, oracle, bits):
     of whole tensors (the embedding with its ragged edge tiles among them), all 8 workers."""
     run_config(sl, oracle, 2, None, 2, {"embed", "l0.q", "l5.gate", "l11.down", "l3.norm1", "final_norm"},
                full_first=False, bits=bits)
+
+
+@pytest.mark.timeout(600)
+def test_offsets_beyond_32_bits(sl, oracle):
+    """Maximum sizes: a 40000 x 65536 filler matrix (2.6e9 elements, 10.5 GB per arena, row
+    stride 256 KB) puts the tensors behind it at element offsets beyond 2^31 and byte offsets
+    beyond 2^33.  The tensors behind it - and the filler's own last tile row, as a tensor of
+    its own would be too slow for the oracle, so through the payload check only - are compared
+    with the oracle (each tensor is quantized on its own, so a tensor can be checked alone)."""
+    dev = torch.device("cuda:0")
+    rows, cols = 40000, 65536
+    big = rows * cols
+    specs = [(rows, cols, 0, 1), (300, 520, big, 1), (1, 9000, big + 300 * 520 + 64 - (300 * 520) % 64, 0),
+             (128, 256, big + 300 * 520 + 64 - (300 * 520) % 64 + 9024, 1)]
+    n = specs[-1][2] + 128 * 256
+    assert specs[1][2] > 2**31 and all(s[2] % 4 == 0 for s in specs)
+    k, R, lr = 64, 2, 0.7
+    plan = sl.sl_plan_create(specs, k)
+    ws = sl.alloc_workspace(plan)
+    g = torch.Generator(device=dev).manual_seed(4242)
+    theta = torch.empty(n, dtype=torch.float32, device=dev).normal_(0, 0.02, generator=g)
+    tail0 = specs[1][2]
+    theta_tail0 = theta[tail0:].cpu().numpy().copy()
+    small = [(r, c, off - tail0, lay) for r, c, off, lay in specs[1:]]
+    pays, refs = [], []
+    for r in range(R):
+        e = torch.empty(n, dtype=torch.float32, device=dev).normal_(0, 1e-3, generator=g)
+        d = torch.empty(n, dtype=torch.float32, device=dev).normal_(0, 1e-3, generator=g)
+        e_tail, d_tail = e[tail0:].cpu().numpy().copy(), d[tail0:].cpu().numpy().copy()
+        pay = sl.alloc_payload(plan)
+        sl.sl_compress(plan, e, d, 0.95, pay, ws)
+        torch.cuda.synchronize()
+        assert sl.sl_payload_validate(plan, pay, ws)
+        ref = oracle.compress(small, k, e_tail, d_tail, 0.95)
+        got = pay[plan.tensor_offset(1):plan.payload_bytes].cpu().numpy()
+        assert np.array_equal(got, ref), f"worker {r}: payload of the tensors behind the filler"
+        assert np.array_equal(bits(e[tail0:].cpu().numpy()), bits(e_tail))
+        # the filler's last rows (offsets just below 2^31.3 elements) were accumulated and selected from
+        last = slice((rows - 32) * cols, rows * cols)
+        assert torch.isfinite(e[last]).all() and float(e[last].abs().max()) > 0
+        pays.append(pay)
+        refs.append(ref)
+        del e, d
+    sl.sl_decompress_avg_apply(plan, theta, pays, lr)
+    torch.cuda.synchronize()
+    want = theta_tail0.copy()
+    oracle.decompress_avg_apply(small, k, want, refs, lr)
+    assert np.array_equal(bits(theta[tail0:].cpu().numpy()), bits(want))
+    plan.close()

@@ -517,3 +517,43 @@ def test_two_streams_with_their_own_workspaces(sl, oracle):
             ref = oracle.compress(descs, k, e_ref, d0, 0.95)
         assert np.array_equal(b["pay"][:plan.payload_bytes].cpu().numpy(), ref)
         assert_f32_close(b["e"].cpu().numpy(), e_ref, "e")
+
+
+# --------------------------------------------------------------------------- empty and tiny lists
+def test_empty_list_and_single_partial_chunks(sl, oracle):
+    plan = sl.sl_plan_create([], 64)
+    assert plan.num_chunks == 0 and plan.num_elements == 0 and plan.payload_bytes == 0
+    x = torch.full((64,), 3.0, dtype=torch.float32, device="cuda")
+    y = torch.full((64,), 5.0, dtype=torch.float32, device="cuda")
+    pay, ws = sl.alloc_payload(plan), sl.alloc_workspace(plan)
+    pay.fill_(0xAB)
+    sl.sl_compress(plan, x, y, 0.95, pay, ws)
+    sl.sl_decompress_avg_apply(plan, x, [pay], 1.0)
+    sl.sl_residual_apply(plan, x, pay)
+    assert sl.sl_payload_validate(plan, pay, ws)
+    torch.cuda.synchronize()
+    assert bool((x == 3.0).all()) and bool((y == 5.0).all()) and bool((pay == 0xAB).all())
+    plan.close()
+    # lists whose only chunks are partial, with k equal or close to the number of elements
+    for descs, k in (([(1, 100, 0, FLAT)], 64), ([(7, 9, 0, TILE)], 32), ([(1, 64, 0, FLAT), (3, 24, 64, TILE)], 64),
+                     ([(1, 4097, 0, FLAT)], 1)):
+        if k % 4:
+            with pytest.raises(sl.SparseLoCoError):
+                sl.sl_plan_create(descs, k)
+            continue
+        n = max(d[2] + d[0] * d[1] for d in descs) + 12
+        rng = np.random.default_rng(len(descs) + k)
+        e0 = rng.normal(0, 1e-3, n).astype(np.float32)
+        delta = rng.normal(0, 1e-3, n).astype(np.float32)
+        pay_ref, _ = check_compress(sl, oracle, descs, n, k, e0, delta, 0.95, what=f"tiny {descs}")
+        plan = sl.sl_plan_create(descs, k)
+        theta0 = rng.normal(0, 0.02, n).astype(np.float32)
+        theta = torch.from_numpy(theta0).cuda()
+        dev = sl.alloc_payload(plan)
+        dev[:pay_ref.size] = torch.from_numpy(pay_ref).cuda()
+        sl.sl_decompress_avg_apply(plan, theta, [dev, dev, dev], 0.7)
+        torch.cuda.synchronize()
+        want = theta0.copy()
+        oracle.decompress_avg_apply(descs, k, want, [pay_ref] * 3, 0.7)
+        assert_f32_close(theta.cpu().numpy(), want, f"tiny {descs} theta")
+        plan.close()
