@@ -121,17 +121,19 @@ struct CodeArgs {
     int k;
 };
 
-struct BinStacks {       // one binary-counter stack of partial tree sums per bin
-    double a[13], b[13], c[13], d[13];
+template <int LV>
+struct BinStacksT {      // one binary-counter stack of partial tree sums per bin, LV levels (k <= 2^(LV-1))
+    double a[LV], b[LV], c[LV], d[LV];
 };
+using BinStacks = BinStacksT<13>;
 
 // Folds entry m (values v0..v3 for the four bins) into the stacks: while bit L
 // of m is set the partial sum of level L is the left sibling and is added; the
 // first clear bit is where the new partial sum is parked.
-template <int L>
-SL_DEV void stack_push(BinStacks &s, int m, double v0, double v1, double v2, double v3)
+template <int L, int LV>
+SL_DEV void stack_push(BinStacksT<LV> &s, int m, double v0, double v1, double v2, double v3)
 {
-    if constexpr (L < 13) {
+    if constexpr (L < LV) {
         if ((m >> L) & 1) {
             stack_push<L + 1>(s, m, s.a[L] + v0, s.b[L] + v1, s.c[L] + v2, s.d[L] + v3);
         } else {
@@ -151,9 +153,14 @@ constexpr int CODE_PITCH = 65;       // LDS row pitch in floats: conflict-free c
 // binary-counter stack (entry m is folded into the partial sums of the aligned
 // subtrees that end at m, which reproduces the adjacent-pair tree exactly).
 // The entry index is uniform over the wave, so the stack walk is scalar control flow.
-__global__ void __launch_bounds__(64 * CODE_WAVES, 2) k_codes(CodeArgs A)
+// LV: levels of the stacks (k <= 2^(LV-1)); TC: entries per chunk that are transposed at a
+// time.  Few levels and a small tile (the paper's densities: k <= 256) leave room for four
+// waves per SIMD, which this latency- and VALU-bound kernel needs.
+template <int LV, int TC, int WAVES_PER_EU>
+__global__ void __launch_bounds__(64 * CODE_WAVES, WAVES_PER_EU) k_codes(CodeArgs A)
 {
-    __shared__ float tile_all[CODE_WAVES][64 * CODE_PITCH];
+    constexpr int PITCH = TC + 1;            // conflict-free column reads
+    __shared__ float tile_all[CODE_WAVES][64 * PITCH];
     const int lane = threadIdx.x & 63, k = A.k;
     const int wave = sl_uniform((int)(threadIdx.x >> 6));
     const long long c0 = ((long long)blockIdx.x * CODE_WAVES + wave) * 64;
@@ -171,29 +178,30 @@ __global__ void __launch_bounds__(64 * CODE_WAVES, 2) k_codes(CodeArgs A)
         codes_out = A.payload + d.rec_off + 3 * k / 2;
     }
 
-    BinStacks st;
+    BinStacksT<LV> st;
 #pragma unroll
-    for (int l = 0; l < 13; ++l) st.a[l] = st.b[l] = st.c[l] = st.d[l] = 0.0;
+    for (int l = 0; l < LV; ++l) st.a[l] = st.b[l] = st.c[l] = st.d[l] = 0.0;
     unsigned n_b[4] = {0u, 0u, 0u, 0u};
     unsigned word = 0;
 
-    const int lr = lane >> 4, lc = (lane & 15) * 4;
-    for (int s0 = 0; s0 < k; s0 += 64) {
-        const int ncol = min(64, k - s0);          // multiple of 4
+    constexpr int LPR = TC / 4;              // lanes that load one row of the tile
+    const int lr = lane / LPR, lc = (lane % LPR) * 4;
+    for (int s0 = 0; s0 < k; s0 += TC) {
+        const int ncol = min(TC, k - s0);          // multiple of 4
         sl_wave_sync();
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {
-            const int row = 4 * i + lr;
+        for (int i = 0; i < LPR; ++i) {
+            const int row = (64 / LPR) * i + lr;
             if (c0 + row < A.n_chunks && lc < ncol) {
                 const float4 v = *reinterpret_cast<const float4 *>(A.vals + (c0 + row) * k + s0 + lc);
-                float *t = tile + row * CODE_PITCH + lc;
+                float *t = tile + row * PITCH + lc;
                 t[0] = v.x, t[1] = v.y, t[2] = v.z, t[3] = v.w;
             }
         }
         sl_wave_sync();
         for (int col = 0; col < ncol; ++col) {
             const int m = s0 + col;
-            const float xf = tile[lane * CODE_PITCH + col];
+            const float xf = tile[lane * PITCH + col];
             const double x = (double)xf;
             const double dlt = x - mu;
             const double dd = dlt * dlt;
@@ -219,7 +227,7 @@ __global__ void __launch_bounds__(64 * CODE_WAVES, 2) k_codes(CodeArgs A)
     if (live) {
         double r0 = st.a[0], r1 = st.b[0], r2 = st.c[0], r3 = st.d[0];
 #pragma unroll
-        for (int l = 1; l < 13; ++l)
+        for (int l = 1; l < LV; ++l)
             if (top == l) r0 = st.a[l], r1 = st.b[l], r2 = st.c[l], r3 = st.d[l];
         A.leafC[0 * A.n_chunks + c] = r0;
         A.leafC[1 * A.n_chunks + c] = r1;
@@ -497,7 +505,11 @@ int slk_quantize(const sl_plan *p, float *e, int skip_residual, unsigned char *p
         case 1: hipLaunchKernelGGL(k_codes_b<1>, dim3(nblk), dim3(64 * CODE_WAVES), 0, st, C); break;
         case 3: hipLaunchKernelGGL(k_codes_b<3>, dim3(nblk), dim3(64 * CODE_WAVES), 0, st, C); break;
         case 4: hipLaunchKernelGGL(k_codes_b<4>, dim3(nblk), dim3(64 * CODE_WAVES), 0, st, C); break;
-        default: hipLaunchKernelGGL(k_codes, dim3(nblk), dim3(64 * CODE_WAVES), 0, st, C); break;
+        default:
+            if (k <= 64) hipLaunchKernelGGL((k_codes<7, 32, 4>), dim3(nblk), dim3(64 * CODE_WAVES), 0, st, C);
+            else if (k <= 256) hipLaunchKernelGGL((k_codes<9, 32, 4>), dim3(nblk), dim3(64 * CODE_WAVES), 0, st, C);
+            else hipLaunchKernelGGL((k_codes<13, 64, 2>), dim3(nblk), dim3(64 * CODE_WAVES), 0, st, C);
+            break;
     }
     if ((rc = check_launch())) return rc;
     sl_prof_mark(p, SL_PROF_CODES, st);
