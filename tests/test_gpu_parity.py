@@ -557,3 +557,67 @@ def test_empty_list_and_single_partial_chunks(sl, oracle):
         oracle.decompress_avg_apply(descs, k, want, [pay_ref] * 3, 0.7)
         assert_f32_close(theta.cpu().numpy(), want, f"tiny {descs} theta")
         plan.close()
+
+
+# --------------------------------------------------------------------------- changing R, checkpoint / resume
+def test_worker_count_may_change_every_round_and_state_survives_a_checkpoint(sl, oracle):
+    """The number of contributing workers is a run-time argument (peers may come and go:
+    the average divides by the R actually passed).  The only state of the path is (theta, e_r):
+    five rounds in one go equal two rounds, a copy of the state out and back into fresh
+    buffers (after the pending error update has been flushed), and three more rounds."""
+    descs, n = layout_list([(150, 210, TILE), (1, 9000, FLAT), (128, 192, TILE)])
+    k, beta, lr = 64, 0.95, 0.7
+    Rs = [4, 2, 3, 1, 4]
+    rng = np.random.default_rng(99)
+    deltas = [[rng.normal(0, 1e-3, n).astype(np.float32) for _ in range(4)] for _ in Rs]
+    theta0 = rng.normal(0, 0.02, n).astype(np.float32)
+    plan = sl.sl_plan_create(descs, k)
+    ws = sl.alloc_workspace(plan)
+
+    def run(first, last, theta, e, pend):
+        """Rounds first..last-1, every worker in deferred mode; returns the pending payloads."""
+        for t in range(first, last):
+            cur = []
+            for r in range(Rs[t]):
+                out = sl.alloc_payload(plan)
+                sl.sl_compress(plan, e[r], torch.from_numpy(deltas[t][r]).cuda(), beta, out, ws,
+                               flags=sl.SL_COMPRESS_DEFER_RESIDUAL, pending=pend[r])
+                pend[r] = out
+                cur.append(out)
+            sl.sl_decompress_avg_apply(plan, theta, cur, lr)
+        return pend
+
+    def flush(e, pend):
+        for r in range(4):
+            if pend[r] is not None:
+                sl.sl_residual_apply(plan, e[r], pend[r])
+                pend[r] = None
+
+    # straight through
+    th_a = torch.from_numpy(theta0.copy()).cuda()
+    e_a = [torch.zeros(n, dtype=torch.float32, device="cuda") for _ in range(4)]
+    pend_a = run(0, 5, th_a, e_a, [None] * 4)
+    flush(e_a, pend_a)
+    # with a checkpoint after round 2
+    th_b = torch.from_numpy(theta0.copy()).cuda()
+    e_b = [torch.zeros(n, dtype=torch.float32, device="cuda") for _ in range(4)]
+    pend_b = run(0, 2, th_b, e_b, [None] * 4)
+    flush(e_b, pend_b)
+    torch.cuda.synchronize()
+    saved = (th_b.cpu().numpy().copy(), [x.cpu().numpy().copy() for x in e_b])
+    del th_b, e_b
+    th_c = torch.from_numpy(saved[0]).cuda()
+    e_c = [torch.from_numpy(x).cuda() for x in saved[1]]
+    pend_c = run(2, 5, th_c, e_c, [None] * 4)
+    flush(e_c, pend_c)
+    torch.cuda.synchronize()
+    assert torch.equal(th_a, th_c) and all(torch.equal(x, y) for x, y in zip(e_a, e_c))
+    # and both are the oracle's
+    th_ref = theta0.copy()
+    e_ref = [np.zeros(n, dtype=np.float32) for _ in range(4)]
+    for t, R in enumerate(Rs):
+        pays = [oracle.compress(descs, k, e_ref[r], deltas[t][r], beta) for r in range(R)]
+        oracle.decompress_avg_apply(descs, k, th_ref, pays, lr)
+    assert_f32_close(th_a.cpu().numpy(), th_ref, "theta after five rounds")
+    for r in range(4):
+        assert_f32_close(e_a[r].cpu().numpy(), e_ref[r], f"e[{r}] after five rounds")
