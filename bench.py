@@ -306,7 +306,7 @@ def main():
         for name, (fn, nbytes) in rows.items():
             if name == "sub_topk":
                 synth.fill_delta(w, mom, 3, 0)
-            ms = time_ms(fn)
+            ms = time_ms(fn, reps=10)
             out["outer_steps"][name] = {"ms": ms, "algorithmic_GBps": nbytes / (ms * 1e-3) / 1e9}
         del mom, dirs
     if not args.no_cpu_baseline:

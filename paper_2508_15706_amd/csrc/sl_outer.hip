@@ -9,11 +9,19 @@
 //                     [m <- mu*m + avg ; avg <- avg + mu*m] ; theta <- theta - lr*avg
 //
 // Every "c*y + z" is one fp32 fused multiply-add.  Both kernels are pure
-// streams: one wavefront owns one chunk and moves it in four quarters of four
+// streams: one wavefront owns one chunk and moves it in two halves of eight
 // 16-byte accesses per lane per stream, so that many workgroups stay resident.
 #include "sl_device.h"
 #include "sl_internal.h"
 
+// 16-byte accesses per lane and stream that are in flight together (half a chunk; a quarter
+// and a whole chunk measured the same within the run-to-run spread of these kernels)
+#ifndef SL_LOM_STEP
+#define SL_LOM_STEP 8
+#endif
+#ifndef SL_DENSE_STEP
+#define SL_DENSE_STEP 8
+#endif
 namespace {
 
 struct LomArgs {
@@ -39,22 +47,23 @@ __global__ void __launch_bounds__(256) k_lom_direction(LomArgs A)
     const unsigned stride = (unsigned)d.stride;
     if (d.flags & SLC_FULL) {
         const unsigned o0 = 4u * (lr * stride + lc), step = 16u * stride;
+        constexpr int S = SL_LOM_STEP;
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            sl_f4 mv[4], dv[4];
+        for (int q = 0; q < 16 / S; ++q) {
+            sl_f4 mv[S], dv[S];
 #pragma unroll
-            for (int u = 0; u < 4; ++u) mv[u] = sl_load_stream_at(mc, (4 * q + u) * step, o0);
+            for (int u = 0; u < S; ++u) mv[u] = sl_load_stream_at(mc, (S * q + u) * step, o0);
 #pragma unroll
-            for (int u = 0; u < 4; ++u) dv[u] = sl_load_stream_at(dc, (4 * q + u) * step, o0);
+            for (int u = 0; u < S; ++u) dv[u] = sl_load_stream_at(dc, (S * q + u) * step, o0);
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
+            for (int u = 0; u < S; ++u) {
                 sl_f4 m = mv[u], g = dv[u], o;
                 m.x = fmaf(A.mu, m.x, g.x), m.y = fmaf(A.mu, m.y, g.y);
                 m.z = fmaf(A.mu, m.z, g.z), m.w = fmaf(A.mu, m.w, g.w);
                 o.x = fmaf(A.mu, m.x, g.x), o.y = fmaf(A.mu, m.y, g.y);
                 o.z = fmaf(A.mu, m.z, g.z), o.w = fmaf(A.mu, m.w, g.w);
-                sl_store_stream_at(mc, (4 * q + u) * step, o0, m);
-                sl_store_stream_at(oc, (4 * q + u) * step, o0, o);
+                sl_store_stream_at(mc, (S * q + u) * step, o0, m);
+                sl_store_stream_at(oc, (S * q + u) * step, o0, o);
             }
         }
     } else {
@@ -101,40 +110,41 @@ __global__ void __launch_bounds__(256) k_dense_avg_apply(DenseArgs A)
     const int R = A.R;
     if (d.flags & SLC_FULL) {
         const unsigned o0 = 4u * (lr * stride + lc), step = 16u * stride;
+        constexpr int S = SL_DENSE_STEP;
 #pragma unroll 1
-        for (int q = 0; q < 4; ++q) {
-            sl_f4 th[4], mo[NESTEROV ? 4 : 1], acc[4];
+        for (int q = 0; q < 16 / S; ++q) {
+            sl_f4 th[S], mo[NESTEROV ? S : 1], acc[S];
 #pragma unroll
-            for (int u = 0; u < 4; ++u) th[u] = sl_load_stream_at(tc, (4 * q + u) * step, o0);
+            for (int u = 0; u < S; ++u) th[u] = sl_load_stream_at(tc, (S * q + u) * step, o0);
             if constexpr (NESTEROV) {
 #pragma unroll
-                for (int u = 0; u < 4; ++u) mo[u] = sl_load_stream_at(mc, (4 * q + u) * step, o0);
+                for (int u = 0; u < S; ++u) mo[u] = sl_load_stream_at(mc, (S * q + u) * step, o0);
             }
 #pragma unroll
-            for (int u = 0; u < 4; ++u) acc[u] = sl_f4{0.f, 0.f, 0.f, 0.f};
+            for (int u = 0; u < S; ++u) acc[u] = sl_f4{0.f, 0.f, 0.f, 0.f};
             for (int r = 0; r < R; ++r) {                   // r ascending: the order is part of the result
                 const float *gc = A.dirs[r] + d.base;
-                sl_f4 g[4];
+                sl_f4 g[S];
 #pragma unroll
-                for (int u = 0; u < 4; ++u) g[u] = sl_load_stream_at(gc, (4 * q + u) * step, o0);
+                for (int u = 0; u < S; ++u) g[u] = sl_load_stream_at(gc, (S * q + u) * step, o0);
 #pragma unroll
-                for (int u = 0; u < 4; ++u) acc[u] = acc[u] + g[u];
+                for (int u = 0; u < S; ++u) acc[u] = acc[u] + g[u];
             }
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
+            for (int u = 0; u < S; ++u) {
                 sl_f4 g = acc[u] * A.inv_R;
                 if constexpr (NESTEROV) {
                     sl_f4 m = mo[u];
                     m.x = fmaf(A.mu, m.x, g.x), m.y = fmaf(A.mu, m.y, g.y);
                     m.z = fmaf(A.mu, m.z, g.z), m.w = fmaf(A.mu, m.w, g.w);
-                    sl_store_stream_at(mc, (4 * q + u) * step, o0, m);
+                    sl_store_stream_at(mc, (S * q + u) * step, o0, m);
                     g.x = fmaf(A.mu, m.x, g.x), g.y = fmaf(A.mu, m.y, g.y);
                     g.z = fmaf(A.mu, m.z, g.z), g.w = fmaf(A.mu, m.w, g.w);
                 }
                 sl_f4 v = th[u];
                 v.x = fmaf(A.neg_lr, g.x, v.x), v.y = fmaf(A.neg_lr, g.y, v.y);
                 v.z = fmaf(A.neg_lr, g.z, v.z), v.w = fmaf(A.neg_lr, g.w, v.w);
-                sl_store_stream_at(tc, (4 * q + u) * step, o0, v);
+                sl_store_stream_at(tc, (S * q + u) * step, o0, v);
             }
         }
     } else {
