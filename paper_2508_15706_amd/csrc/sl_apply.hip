@@ -78,7 +78,7 @@ __global__ void __launch_bounds__(256) k_apply(ApplyArgs A)
     // R = 8 up to k = 128, R = 16 up to k = 64) are fetched into registers BEFORE the
     // theta loads: loads complete in order, so the decode below then waits for these
     // few words only and runs while the chunk's 16 KB of theta are still in flight.
-    constexpr int PF = 8;
+    constexpr int PF = TWO_BIT ? 8 : 12;   // wider records at other widths: 3 KB
     unsigned pf[PF];
     const int nb0 = min(A.batch, A.R);
     if (word_path) {
