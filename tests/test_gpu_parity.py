@@ -621,3 +621,49 @@ def test_worker_count_may_change_every_round_and_state_survives_a_checkpoint(sl,
     assert_f32_close(th_a.cpu().numpy(), th_ref, "theta after five rounds")
     for r in range(4):
         assert_f32_close(e_a[r].cpu().numpy(), e_ref[r], f"e[{r}] after five rounds")
+
+
+# --------------------------------------------------------------------------- fragments of the list
+def test_fragments_of_the_list_equal_the_whole(sl, oracle):
+    """The appendix "Streaming SparseLoCo" synchronises the model in three fragments at staggered
+    steps.  A fragment is a plan over a subset of the tensors in the same arenas: its payload is
+    the concatenation of those tensors' blocks of the whole list's payload, its error update
+    touches those tensors only, and aggregating fragment by fragment gives the whole update."""
+    shapes = [(150, 210, TILE), (1, 768, FLAT), (128, 192, TILE), (1, 9000, FLAT), (256, 64, TILE), (1, 4096, FLAT)]
+    descs, n = layout_list(shapes)
+    frags = [descs[0:2], descs[2:4], descs[4:6]]
+    k, R, lr = 32, 3, 0.7
+    rng = np.random.default_rng(123)
+    whole = sl.sl_plan_create(descs, k)
+    plans = [sl.sl_plan_create(f, k) for f in frags]
+    assert sum(p.payload_bytes for p in plans) == whole.payload_bytes
+    ws = sl.alloc_workspace(whole)
+    theta0 = rng.normal(0, 0.02, n).astype(np.float32)
+    th_w, th_f = torch.from_numpy(theta0.copy()).cuda(), torch.from_numpy(theta0.copy()).cuda()
+    pays_w, pays_f = [], [[] for _ in frags]
+    for r in range(R):
+        e0 = rng.normal(0, 1e-3, n).astype(np.float32)
+        d0 = rng.normal(0, 1e-3, n).astype(np.float32)
+        e_w, e_f, d = torch.from_numpy(e0.copy()).cuda(), torch.from_numpy(e0.copy()).cuda(), torch.from_numpy(d0).cuda()
+        pw = sl.alloc_payload(whole)
+        sl.sl_compress(whole, e_w, d, 0.95, pw, ws)
+        pays_w.append(pw)
+        parts = []
+        for i, p in enumerate(plans):
+            pf = sl.alloc_payload(p)
+            sl.sl_compress(p, e_f, d, 0.95, pf, ws)
+            torch.cuda.synchronize()
+            pays_f[i].append(pf)
+            parts.append(pf[:p.payload_bytes])
+        torch.cuda.synchronize()
+        assert torch.equal(torch.cat(parts), pw[:whole.payload_bytes]) and torch.equal(e_w, e_f)
+    sl.sl_decompress_avg_apply(whole, th_w, pays_w, lr)
+    for i, p in enumerate(plans):                      # one fragment at a time, as the streaming schedule would
+        before = th_f.clone()
+        sl.sl_decompress_avg_apply(p, th_f, pays_f[i], lr)
+        torch.cuda.synchronize()
+        changed = (before != th_f).cpu().numpy()
+        lo, hi = frags[i][0][2], frags[i][-1][2] + frags[i][-1][0] * frags[i][-1][1]
+        assert changed[lo:hi].any() and not changed[:lo].any() and not changed[hi:].any()
+    torch.cuda.synchronize()
+    assert torch.equal(th_w, th_f)
