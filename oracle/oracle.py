@@ -108,6 +108,12 @@ def lib():
                                                           C.c_float]
         L.slo_sub_topk.restype = i32
         L.slo_sub_topk.argtypes = [tp, i32, i32, i32, vp, vp]
+        L.slo_fmix32.restype = C.c_uint32
+        L.slo_fmix32.argtypes = [C.c_uint32]
+        L.slo_random_key.restype = C.c_uint32
+        L.slo_random_key.argtypes = [C.c_uint32, C.c_uint32, C.c_uint32]
+        L.slo_compress_random_b.restype = i32
+        L.slo_compress_random_b.argtypes = [tp, i32, i32, i32, i32, vp, vp, C.c_float, C.c_uint32, vp, vp]
         L.slo_validate_payload.restype = i32
         L.slo_validate_payload.argtypes = [tp, i32, i32, i32, vp]
         L.slo_rice_param.restype = i32
@@ -507,3 +513,24 @@ def rice_decode_b(descs, k, bits, coded, tile=64):
     if st:
         raise ValueError(f"slo_rice_decode_b: status {st}")
     return out
+
+
+# ---- Random-k ablation ----
+def fmix32(h):
+    return int(lib().slo_fmix32(int(h) & 0xFFFFFFFF))
+
+
+def random_key(seed, chunk, j):
+    return int(lib().slo_random_key(int(seed) & 0xFFFFFFFF, int(chunk) & 0xFFFFFFFF, int(j)))
+
+
+def compress_random_b(descs, k, bits, e, delta, beta, seed, tile=64, want_idx=False):
+    arr, n = make_tensors(descs)
+    _check(e, np.float32), _check(delta, np.float32)
+    payload = np.zeros(int(lib().slo_payload_bytes_b(arr, n, tile, k, bits)), dtype=np.uint8)
+    idx = np.zeros(int(lib().slo_num_chunks(arr, n, tile)) * k, dtype=np.uint16) if want_idx else None
+    st = lib().slo_compress_random_b(arr, n, tile, k, bits, _ptr(e), _ptr(delta), float(beta),
+                                     int(seed) & 0xFFFFFFFF, _ptr(payload), None if idx is None else _ptr(idx))
+    if st:
+        raise ValueError(f"slo_compress_random_b: status {st}")
+    return (payload, idx) if want_idx else payload

@@ -802,6 +802,116 @@ int slo_decompress_dense_b(const slo_tensor *t, int nt, int tile, int k, int bit
     return status;
 }
 
+/* ------------------------------------------------------------------------- */
+/* Random-k (ablation "SparseLoCo with Random-k vs. Top-k sparsification":    */
+/* the same pipeline with k randomly chosen positions per chunk instead of    */
+/* the k largest, "for the same number of indices selected").  Reading: every */
+/* valid position of a chunk gets a pseudo-random 31-bit key from a           */
+/* counter-based generator -                                                  */
+/*     key = fmix32(fmix32(fmix32(seed) ^ chunk) ^ j) >> 1                    */
+/* with the 32-bit finalizer of MurmurHash3 (Appleby, public domain), chunk = */
+/* the chunk's index in the whole list, j = local index (the seed is hashed   */
+/* on its own first, so that small seeds and small chunk numbers do not       */
+/* cancel each other) - and the k positions                                   */
+/* with the largest keys are taken, ties to the lower index: a uniformly      */
+/* random k-subset that both sides can reproduce from (seed, chunk, j).       */
+/* Everything after the selection (quantizer, residual, wire format) is as in */
+/* slo_compress_b.                                                            */
+/* ------------------------------------------------------------------------- */
+
+uint32_t slo_fmix32(uint32_t h)
+{
+    h ^= h >> 16;
+    h *= 0x85EBCA6Bu;
+    h ^= h >> 13;
+    h *= 0xC2B2AE35u;
+    h ^= h >> 16;
+    return h;
+}
+
+uint32_t slo_random_key(uint32_t seed, uint32_t chunk, uint32_t j)
+{
+    return slo_fmix32(slo_fmix32(slo_fmix32(seed) ^ chunk) ^ j) >> 1;
+}
+
+/* Random selection within chunk c of tensor t (chunk_list = its index in the
+ * whole list).  Same outputs as slo_topk_chunk. */
+int slo_randk_chunk(const slo_tensor *t, int tile, int64_t c, int64_t chunk_list, const float *a, int k,
+                    uint32_t seed, uint16_t *sel_idx, float *sel_val)
+{
+    int C = tile * tile, n = 0;
+    slo_cand *cand = (slo_cand *)malloc((size_t)C * sizeof(slo_cand));
+    for (int j = 0; j < C; ++j) {
+        if (slo_element_of(t, tile, c, j) < 0) continue;
+        cand[n].key = slo_random_key(seed, (uint32_t)chunk_list, (uint32_t)j);
+        cand[n].j = j;
+        ++n;
+    }
+    if (n < k) {
+        free(cand);
+        return -1;
+    }
+    qsort(cand, (size_t)n, sizeof(slo_cand), cmp_mag_desc_then_index);
+    qsort(cand, (size_t)k, sizeof(slo_cand), cmp_index_asc);
+    for (int m = 0; m < k; ++m) {
+        sel_idx[m] = (uint16_t)cand[m].j;
+        sel_val[m] = a[slo_element_of(t, tile, c, cand[m].j)];
+    }
+    free(cand);
+    return n;
+}
+
+/* slo_compress_b with Random-k in place of Top-k. */
+int slo_compress_random_b(const slo_tensor *t, int nt, int tile, int k, int bits, float *e,
+                          const float *delta, float beta, uint32_t seed, uint8_t *payload,
+                          uint16_t *sel_idx_out)
+{
+    if (nt < 0 || tile < 1 || tile > 64 || !bits_ok(k, bits, tile)) return SLO_ERR_ARG;
+    int nb = bits == 32 ? 0 : 1 << bits;
+    int64_t rec = slo_record_bytes_b(k, bits), hdr = slo_header_bytes_b(bits);
+    int64_t chunk0 = 0, pay_off = 0;
+    for (int ti = 0; ti < nt; ++ti) {
+        const slo_tensor *T = &t[ti];
+        int64_t n = T->rows * T->cols;
+        int64_t nc = slo_tensor_chunks(T, tile);
+        int64_t M = nc * k;
+        slo_tensor L = *T;
+        L.offset = 0;
+        slo_accumulate(e + T->offset, delta + T->offset, beta, n);
+        const float *a = e + T->offset;
+        uint16_t *idx = (uint16_t *)malloc((size_t)(M > 0 ? M : 1) * sizeof(uint16_t));
+        float *val = (float *)malloc((size_t)(M > 0 ? M : 1) * sizeof(float));
+        uint8_t *code = (uint8_t *)calloc((size_t)(M > 0 ? M : 1), 1);
+        int bad = 0;
+        for (int64_t c = 0; c < nc; ++c)
+            if (slo_randk_chunk(&L, tile, c, chunk0 + c, a, k, seed, idx + c * k, val + c * k) < 0) bad = 1;
+        if (bad) {
+            free(idx), free(val), free(code);
+            return SLO_ERR_ARG;
+        }
+        float lut[16] = {0};
+        if (bits != 32) slo_quantize_tensor_b(val, nc, k, bits, code, lut, NULL);
+        for (int64_t c = 0; c < nc; ++c)
+            for (int m = 0; m < k; ++m) {
+                int64_t i = slo_element_of(&L, tile, c, idx[c * k + m]);
+                float sent = bits == 32 ? val[c * k + m] : lut[code[c * k + m]];
+                e[T->offset + i] = a[i] - sent;
+            }
+        if (payload) {
+            uint8_t *blk = payload + pay_off;
+            memset(blk, 0, (size_t)slo_tensor_block_bytes_b(T, tile, k, bits));
+            memcpy(blk, lut, (size_t)4 * nb);
+            for (int64_t c = 0; c < nc; ++c)
+                slo_pack_record_b(idx + c * k, code + c * k, val + c * k, k, bits, blk + hdr + c * rec);
+        }
+        if (sel_idx_out) memcpy(sel_idx_out + chunk0 * k, idx, (size_t)M * sizeof(uint16_t));
+        free(idx), free(val), free(code);
+        chunk0 += nc;
+        pay_off += slo_tensor_block_bytes_b(T, tile, k, bits);
+    }
+    return SLO_OK;
+}
+
 /* Well-formedness of a received payload (a receiver-side check, not a step of
  * the method): every record lists k strictly ascending positions, each of them
  * inside the tensor.  Returns SLO_OK or SLO_ERR_PAYLOAD. */
