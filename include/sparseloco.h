@@ -149,6 +149,18 @@ int sl_compress_params(sl_plan *plan, float *e, const float *theta_outer, const 
                        float beta, int flags, const void *pending, void *payload, void *workspace,
                        void *stream);
 
+/* sl_compress with Random-k in place of Top-k (the ablation "SparseLoCo with
+ * Random-k vs. Top-k sparsification": k randomly chosen positions per chunk,
+ * "for the same number of indices selected").  The k-subset of a chunk is a
+ * function of (seed, index of the chunk in the list) alone - every position
+ * gets the key fmix32(fmix32(fmix32(seed) ^ chunk) ^ j) >> 1 (fmix32 = the
+ * 32-bit finalizer of MurmurHash3) and the k largest keys are taken, ties to
+ * the lower index - so a caller draws a fresh seed per round and worker.
+ * Everything else (flags, pending, quantizer, error update, payload) as
+ * sl_compress. */
+int sl_compress_random_k(sl_plan *plan, float *e, const float *delta, float beta, int flags,
+                         const void *pending, void *payload, void *workspace, uint32_t seed, void *stream);
+
 /* The error update on its own (Eq. (2) line 2, second half; Algorithm 1 error
  * update): e[i] <- e[i] - LUT[code] at the positions `payload` transmits.  Ends
  * a chain of SL_COMPRESS_DEFER_RESIDUAL calls (e.g. before a checkpoint).

@@ -31,6 +31,7 @@ EXPORTS = [
     "sl_rice_max_bytes", "sl_rice_encode", "sl_rice_decode", "sl_compress_params",
     "sl_payload_validate", "sl_plan_create_bits", "sl_plan_value_bits", "sl_pack_indices_bits",
     "sl_lom_direction", "sl_dense_avg_apply", "sl_decompress_avg_apply_nesterov", "sl_sub_topk",
+    "sl_compress_random_k",
 ]
 PROF_PHASES = ["select", "stats", "codes", "lut", "residual", "apply"]
 
@@ -91,6 +92,8 @@ def lib():
         L.sl_workspace_bytes.argtypes = [vp]
         L.sl_compress.restype = i32
         L.sl_compress.argtypes = [vp, vp, vp, C.c_float, i32, vp, vp, vp, vp]
+        L.sl_compress_random_k.restype = i32
+        L.sl_compress_random_k.argtypes = [vp, vp, vp, C.c_float, i32, vp, vp, vp, C.c_uint32, vp]
         L.sl_compress_params.restype = i32
         L.sl_compress_params.argtypes = [vp, vp, vp, vp, C.c_float, i32, vp, vp, vp, vp]
         L.sl_payload_validate.restype = i32
@@ -217,6 +220,18 @@ def sl_compress(plan: Plan, e: Optional[torch.Tensor], delta: torch.Tensor, beta
                            _stream_ptr(stream))
     if st:
         raise SparseLoCoError("sl_compress", st)
+
+
+def sl_compress_random_k(plan: Plan, e: Optional[torch.Tensor], delta: torch.Tensor, beta: float,
+                         payload: torch.Tensor, workspace: torch.Tensor, seed: int,
+                         flags: int = SL_COMPRESS_DEFAULT, pending: Optional[torch.Tensor] = None,
+                         stream=None) -> None:
+    st = lib().sl_compress_random_k(plan.handle, _dev_ptr(e, torch.float32), _dev_ptr(delta, torch.float32),
+                                    float(beta), int(flags), _dev_ptr(pending, torch.uint8),
+                                    _dev_ptr(payload, torch.uint8), _dev_ptr(workspace, torch.uint8),
+                                    int(seed) & 0xFFFFFFFF, _stream_ptr(stream))
+    if st:
+        raise SparseLoCoError("sl_compress_random_k", st)
 
 
 def sl_residual_apply(plan: Plan, e: torch.Tensor, payload: torch.Tensor, stream=None) -> None:

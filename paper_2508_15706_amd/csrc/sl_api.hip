@@ -252,7 +252,8 @@ static int check_device(const sl_plan *p)
 static bool misaligned(const void *ptr, size_t a) { return ((uintptr_t)ptr & (a - 1)) != 0; }
 
 static int compress_impl(sl_plan *p, float *e, const float *delta, const float *theta_local, float beta,
-                         int flags, const void *pending, void *payload, void *workspace, void *stream)
+                         int flags, const void *pending, void *payload, void *workspace, void *stream,
+                         bool random = false, unsigned seed = 0u)
 {
     if (!p || !delta || !payload || !workspace) return SL_ERR_INVALID_ARG;
     if (flags & ~(SL_COMPRESS_EF_FROZEN | SL_COMPRESS_DEFER_RESIDUAL)) return SL_ERR_INVALID_ARG;
@@ -271,9 +272,13 @@ static int compress_impl(sl_plan *p, float *e, const float *delta, const float *
     unsigned char *pay = static_cast<unsigned char *>(payload);
     unsigned char *ws = static_cast<unsigned char *>(workspace);
     sl_prof_mark(p, -1, st);
-    if ((rc = slk_select(p, e, delta, theta_local, beta, frozen,
-                         static_cast<const unsigned char *>(pending), pay, ws, st)))
-        return rc;
+    if (random)
+        rc = slk_select_random(p, e, delta, beta, frozen, static_cast<const unsigned char *>(pending), pay, ws,
+                               seed, st);
+    else
+        rc = slk_select(p, e, delta, theta_local, beta, frozen, static_cast<const unsigned char *>(pending),
+                        pay, ws, st);
+    if (rc) return rc;
     sl_prof_mark(p, SL_PROF_SELECT, st);
     return slk_quantize(p, e, frozen || defer, pay, ws, st);
 }
@@ -290,6 +295,12 @@ int sl_compress_params(sl_plan *p, float *e, const float *theta_outer, const flo
 {
     if (!theta_local) return SL_ERR_INVALID_ARG;
     return compress_impl(p, e, theta_outer, theta_local, beta, flags, pending, payload, workspace, stream);
+}
+
+int sl_compress_random_k(sl_plan *p, float *e, const float *delta, float beta, int flags, const void *pending,
+                         void *payload, void *workspace, uint32_t seed, void *stream)
+{
+    return compress_impl(p, e, delta, nullptr, beta, flags, pending, payload, workspace, stream, true, seed);
 }
 
 size_t sl_rice_max_bytes(const sl_plan *p) { return p ? p->rice_max_bytes : 0; }

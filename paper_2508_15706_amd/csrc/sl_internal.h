@@ -99,6 +99,10 @@ void sl_prof_mark(const sl_plan *p, int phase, hipStream_t st);
 int slk_select(const sl_plan *p, float *e, const float *delta, const float *theta_local, float beta,
                int frozen, const unsigned char *pending, unsigned char *payload, unsigned char *ws,
                hipStream_t st);
+// the same with Random-k in place of Top-k
+int slk_select_random(const sl_plan *p, float *e, const float *delta, float beta, int frozen,
+                      const unsigned char *pending, unsigned char *payload, unsigned char *ws, unsigned seed,
+                      hipStream_t st);
 // B, C, D and (unless skip_residual) E
 int slk_quantize(const sl_plan *p, float *e, int skip_residual, unsigned char *payload,
                  unsigned char *ws, hipStream_t st);

@@ -48,6 +48,7 @@ struct SelectArgs {
     int frozen;
     int k;
     int bits, hdr_bytes, rec_bytes; // value width of the payloads and the sizes that follow from it
+    unsigned seed_hash;     // Random-k: fmix32(seed), see random_key
     int lds_per_wave;
     int pend_off;           // offset of the pending-correction tables in a wave's LDS
     float *vals;            // [n_chunks * k] selected values, canonical order
@@ -57,6 +58,22 @@ struct SelectArgs {
 };
 
 SL_DEV int key_of(float x) { return (int)(__float_as_uint(x) & 0x7FFFFFFFu); }
+
+// Random-k (the paper's ablation "Random-k vs. Top-k"): every position gets a
+// pseudo-random 31-bit key from a counter-based generator built on the 32-bit
+// finalizer of MurmurHash3 (Appleby, public domain),
+//     key = fmix32(fmix32(fmix32(seed) ^ chunk) ^ j) >> 1,
+// chunk = index of the chunk in the list, j = local index; the k largest keys
+// are selected by the same machinery as the k largest magnitudes.
+SL_DEV unsigned fmix32(unsigned h)
+{
+    h ^= h >> 16;
+    h *= 0x85EBCA6Bu;
+    h ^= h >> 13;
+    h *= 0xC2B2AE35u;
+    h ^= h >> 16;
+    return h;
+}
 
 // Largest T in [lo, hi] with count_ge(T) >= k, given count_ge(lo) >= k and
 // 0 <= lo <= hi.  All values are wave-uniform.
@@ -77,7 +94,8 @@ SL_DEV int bisect_kth(int lo, int hi, int k, CountGE count_ge)
 // position outside the tensor; sg0/sg1 hold the sign of register r at bit
 // 31 - (r & 31) of sg[r / 32].  Writes the k selected (value, index) pairs in
 // ascending local index to sel_val / sel_idx.
-SL_DEV void select_general(int (&key)[64], unsigned sg0, unsigned sg1, int k, int lane,
+template <bool VALUES_FROM_A>
+SL_DEV void select_general(int (&key)[64], const float (&a)[64], unsigned sg0, unsigned sg1, int k, int lane,
                            float *sel_val, unsigned short *sel_idx)
 {
     auto count_regs = [&](int x) {
@@ -141,7 +159,8 @@ SL_DEV void select_general(int (&key)[64], unsigned sg0, unsigned sg1, int k, in
                 if (f[cc] && pos < k) {
                     const unsigned sg = r < 32 ? sg0 : sg1;
                     const unsigned sign = (sg << (r & 31)) & 0x80000000u;
-                    sel_val[pos] = __uint_as_float((unsigned)key[r] | sign);
+                    // a magnitude key and the sign give the value back; a random key does not
+                    sel_val[pos] = VALUES_FROM_A ? a[r] : __uint_as_float((unsigned)key[r] | sign);
                     sel_idx[pos] = (unsigned short)(256 * i + 4 * lane + cc);
                     ++pos;
                 }
@@ -164,10 +183,12 @@ SL_DEV void select_general(int (&key)[64], unsigned sg0, unsigned sg1, int k, in
 // zero, m <- m - Top-k(m) (Section 3.2, DiLoCo-LOM-Sub-k); nothing else is written.
 // TWO_BIT: payloads carry 2-bit codes (the paper's setting; the width is then a
 // compile-time constant); otherwise the width is A.bits.
-template <int GPL, int MODE, bool TWO_BIT>
+// RANDOM: Random-k instead of Top-k (only with GPL = 0: random keys cannot be pruned by magnitude).
+template <int GPL, int MODE, bool TWO_BIT, bool RANDOM = false>
 __global__ void SL_SELECT_BOUNDS k_select(SelectArgs A)
 {
     constexpr bool PARAMS = MODE == 1, SUBK = MODE == 2;
+    static_assert(!RANDOM || GPL == 0, "Random-k takes the general route");
     extern __shared__ __align__(16) unsigned char smem_all[];
     const int lane = threadIdx.x & 63;
     const int wave = sl_uniform((int)(threadIdx.x >> 6));
@@ -541,12 +562,17 @@ __global__ void SL_SELECT_BOUNDS k_select(SelectArgs A)
         for (int r = 0; r < 64; ++r) {
             const unsigned u = __float_as_uint(a[r]);
             const bool outside = !((inside >> r) & 1ull);
-            key[r] = outside ? -1 : (int)(u & 0x7FFFFFFFu);
+            if constexpr (RANDOM) {
+                const unsigned j = 256u * (r >> 2) + 4u * lane + (r & 3);
+                key[r] = outside ? -1 : (int)(fmix32(fmix32(A.seed_hash ^ (unsigned)c) ^ j) >> 1);
+            } else {
+                key[r] = outside ? -1 : (int)(u & 0x7FFFFFFFu);
+            }
             const unsigned sbit = outside ? 0u : (u >> 31);
             if (r < 32) sg0 = (sg0 << 1) | sbit;
             else sg1 = (sg1 << 1) | sbit;
         }
-        select_general(key, sg0, sg1, k, lane, sel_val, sel_idx);
+        select_general<RANDOM>(key, a, sg0, sg1, k, lane, sel_val, sel_idx);
     }
     sl_wave_sync();
 
@@ -614,9 +640,19 @@ __global__ void SL_SELECT_BOUNDS k_select(SelectArgs A)
 
 }  // namespace
 
+static unsigned host_fmix32(unsigned h)
+{
+    h ^= h >> 16;
+    h *= 0x85EBCA6Bu;
+    h ^= h >> 13;
+    h *= 0xC2B2AE35u;
+    h ^= h >> 16;
+    return h;
+}
+
 static int launch_select(const sl_plan *p, float *e, const float *delta, const float *theta_local, float beta,
                          int frozen, const unsigned char *pending, unsigned char *payload, unsigned char *ws,
-                         bool sub_only, hipStream_t st)
+                         bool sub_only, bool random, unsigned seed, hipStream_t st)
 {
     if (p->n_chunks == 0) return SL_OK;
     const int k = p->k;
@@ -633,6 +669,7 @@ static int launch_select(const sl_plan *p, float *e, const float *delta, const f
     A.bits = p->bits;
     A.hdr_bytes = p->hdr_bytes;
     A.rec_bytes = p->rec_bytes;
+    A.seed_hash = host_fmix32(seed);
     {
         size_t b = pruned ? sizeof(uint2) * CAND_CAP : 0;
         b += (6 * (size_t)k + 7) & ~(size_t)7;
@@ -662,6 +699,9 @@ static int launch_select(const sl_plan *p, float *e, const float *delta, const f
     const bool two = p->bits == 2;
     if (sub_only) {
         SL_LAUNCH_SELECT(2, false);
+    } else if (random) {
+        if (two) hipLaunchKernelGGL((k_select<0, 0, true, true>), grid, block, lds, st, A);
+        else hipLaunchKernelGGL((k_select<0, 0, false, true>), grid, block, lds, st, A);
     } else if (theta_local) {
         if (two) SL_LAUNCH_SELECT(1, true);
         else SL_LAUNCH_SELECT(1, false);
@@ -682,10 +722,17 @@ int slk_select(const sl_plan *p, float *e, const float *delta, const float *thet
                int frozen, const unsigned char *pending, unsigned char *payload, unsigned char *ws,
                hipStream_t st)
 {
-    return launch_select(p, e, delta, theta_local, beta, frozen, pending, payload, ws, false, st);
+    return launch_select(p, e, delta, theta_local, beta, frozen, pending, payload, ws, false, false, 0u, st);
+}
+
+int slk_select_random(const sl_plan *p, float *e, const float *delta, float beta, int frozen,
+                      const unsigned char *pending, unsigned char *payload, unsigned char *ws, unsigned seed,
+                      hipStream_t st)
+{
+    return launch_select(p, e, delta, nullptr, beta, frozen, pending, payload, ws, false, true, seed, st);
 }
 
 int slk_sub_topk(const sl_plan *p, float *m, hipStream_t st)
 {
-    return launch_select(p, m, nullptr, nullptr, 1.0f, 0, nullptr, nullptr, nullptr, true, st);
+    return launch_select(p, m, nullptr, nullptr, 1.0f, 0, nullptr, nullptr, nullptr, true, false, 0u, st);
 }

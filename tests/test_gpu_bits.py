@@ -183,3 +183,47 @@ def test_argument_errors(sl):
     assert plan.value_bits == 2 and sl.sl_rice_max_bytes(plan) > 0
     plan = sl.sl_plan_create_bits([(64, 64, 0, TILE)], 16, 3)
     assert plan.value_bits == 3 and sl.sl_rice_max_bytes(plan) > 0
+
+
+# --------------------------------------------------------------------------- Random-k ablation
+@pytest.mark.parametrize("bits", (2, 3, 32))
+@pytest.mark.parametrize("k", [8, 64, 512])
+def test_random_k_matches_oracle(sl, oracle, bits, k):
+    """sl_compress_random_k: the oracle's payload bytes and error buffer, over two rounds (the
+    second with the first round's update still pending), ragged tiles and tails included."""
+    if k <= 256:
+        shapes = [(150, 210, TILE), (1, 9000, FLAT), (1024, 16, TILE), (128, 192, TILE)]
+    else:
+        shapes = [(160, 224, TILE), (1, 8192 + 1000, FLAT)]
+    descs, n = layout_list(shapes)
+    rng = np.random.default_rng(1500 + k + bits)
+    plan = sl.sl_plan_create_bits(descs, k, bits)
+    ws = sl.alloc_workspace(plan)
+    e_ref = rng.normal(0, 1e-3, n).astype(np.float32)
+    e = torch.from_numpy(e_ref.copy()).cuda()
+    pays = [sl.alloc_payload(plan), sl.alloc_payload(plan)]
+    pending = None
+    for rnd, seed in enumerate((0, 0xC0FFEE11)):
+        delta = (1e-3 * rng.standard_t(3, n)).astype(np.float32)
+        out = pays[rnd]
+        out.fill_(0xAB)
+        sl.sl_compress_random_k(plan, e, torch.from_numpy(delta).cuda(), 0.95, out, ws, seed,
+                                flags=sl.SL_COMPRESS_DEFER_RESIDUAL, pending=pending)
+        torch.cuda.synchronize()
+        ref = oracle.compress_random_b(descs, k, bits, e_ref, delta, 0.95, seed)
+        got = out[:plan.payload_bytes].cpu().numpy()
+        assert np.array_equal(got, ref), f"round {rnd}: payload differs at {np.nonzero(got != ref)[0][:8]}"
+        assert sl.sl_payload_validate(plan, out, ws)
+        pending = out
+    sl.sl_residual_apply(plan, e, pending)
+    torch.cuda.synchronize()
+    assert_f32_close(e.cpu().numpy(), e_ref, "e")
+    # another seed gives another selection
+    e2 = torch.zeros(n, dtype=torch.float32, device="cuda")
+    d2 = torch.from_numpy(delta).cuda()
+    a, b = sl.alloc_payload(plan), sl.alloc_payload(plan)
+    sl.sl_compress_random_k(plan, e2, d2, 0.95, a, ws, 1)
+    e2.zero_()
+    sl.sl_compress_random_k(plan, e2, d2, 0.95, b, ws, 2)
+    torch.cuda.synchronize()
+    assert not torch.equal(a, b)
