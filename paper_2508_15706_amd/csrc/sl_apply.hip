@@ -374,7 +374,9 @@ int slk_apply(const sl_plan *p, float *theta, float *mom, float mu, const void *
     A.hdr_bytes = p->hdr_bytes;
     A.rec_bytes = p->rec_bytes;
     const int rec_pad = ((p->rec_bytes + 3) & ~3) + p->hdr_bytes;
-    int batch = 16384 / rec_pad;          // at most 16 KB of staged records
+    // at most 16 KB of staged records; 4 KB when a record alone is large (k >= 1024), so that the
+    // accumulators are not crowded out of the LDS
+    int batch = (rec_pad > 1024 ? 4096 : 16384) / rec_pad;
     if (batch < 1) batch = 1;
     if (batch > R) batch = R;
     A.batch = batch;

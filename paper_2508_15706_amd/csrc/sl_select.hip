@@ -228,7 +228,8 @@ __global__ void SL_SELECT_BOUNDS k_select(SelectArgs A)
     const unsigned char *prec = nullptr, *pcodes = nullptr;
     float4 plut = make_float4(0.f, 0.f, 0.f, 0.f);
     float p_lutv = 0.f;                     // other widths: table entry `lane`, parked in LDS later
-    unsigned p_w0 = 0, p_c0 = 0;            // this lane's first record entry, fetched early
+    constexpr int PFE = 2;                  // record entries per lane that are fetched early (k <= 128: all)
+    unsigned p_w[PFE], p_c[PFE];
     // The bytes of the value field of entry m: the code's byte window, or the fp32 value.
     auto value_window = [&](int m) -> unsigned {
         if (bits == 32) return reinterpret_cast<const unsigned *>(pcodes)[m];
@@ -250,10 +251,15 @@ __global__ void SL_SELECT_BOUNDS k_select(SelectArgs A)
             A.pending + (TWO_BIT ? sl_lut_off(d, 16, 7 * k / 4) : sl_lut_off(d, A.hdr_bytes, A.rec_bytes));
         if (bits == 2) plut = *reinterpret_cast<const float4 *>(lutg);
         else if (bits != 32 && lane < (1 << bits)) p_lutv = reinterpret_cast<const float *>(lutg)[lane];
-        if (lane < k) {
-            const int b0 = (3 * lane) >> 1;
-            p_w0 = (unsigned)prec[b0] | ((unsigned)prec[b0 + 1] << 8);
-            p_c0 = value_window(lane);
+#pragma unroll
+        for (int u = 0; u < PFE; ++u) {
+            const int m = lane + 64 * u;
+            p_w[u] = p_c[u] = 0;
+            if (m < k) {
+                const int b0 = (3 * m) >> 1;
+                p_w[u] = (unsigned)prec[b0] | ((unsigned)prec[b0 + 1] << 8);
+                p_c[u] = value_window(m);
+            }
         }
     }
     // Builds the tables; called once the chunk's bulk loads are in flight so that
@@ -283,8 +289,10 @@ __global__ void SL_SELECT_BOUNDS k_select(SelectArgs A)
             // in one 16-byte access overwrite each other here: such an access takes the ranked path.
             tq[((j >> 8) << 6) + ((j >> 2) & 63u)] = q;
         };
-        if (lane < k) entry(lane, p_w0, p_c0);
-        for (int m = lane + 64; m < k; m += 64) {
+#pragma unroll
+        for (int u = 0; u < PFE; ++u)
+            if (lane + 64 * u < k) entry(lane + 64 * u, p_w[u], p_c[u]);
+        for (int m = lane + 64 * PFE; m < k; m += 64) {
             const int b0 = (3 * m) >> 1;
             entry(m, (unsigned)prec[b0] | ((unsigned)prec[b0 + 1] << 8), value_window(m));
         }
