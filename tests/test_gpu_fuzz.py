@@ -1,0 +1,125 @@
+"""Seeded random configurations of the whole path against the oracle: random tensor lists
+(odd column counts, single-row and single-column matrices, tiny and multi-chunk tensors,
+gaps between tensors), random k, value width, worker count, EF decay and mode (eager,
+deferred chain, frozen, Random-k, pseudo-gradient from parameters).  Every case is valid
+input; payload bytes must be bit-exact, e and theta bit-identical or within 1e-6."""
+import numpy as np
+import pytest
+import torch
+
+from test_gpu_parity import FLAT, TILE, assert_f32_close, sl  # noqa: F401 (fixture)
+
+pytestmark = pytest.mark.gpu
+
+
+def random_list(rng, k):
+    """Tensors whose every chunk holds at least k elements."""
+    descs, off = [], int(rng.integers(0, 4)) * 4
+    for _ in range(int(rng.integers(1, 7))):
+        kind = rng.integers(0, 5)
+        if kind == 0:                                     # 1-D with a tail of at least k
+            n = int(rng.integers(1, 4)) * 4096 + int(rng.integers(k, 4097))
+            r, c, lay = 1, n, FLAT
+        elif kind == 1:                                   # matrix, arbitrary columns (also not multiples of 4)
+            side = int(np.ceil(np.sqrt(k)))
+            r = 64 * int(rng.integers(0, 3)) + int(rng.integers(side, 65))
+            c = 64 * int(rng.integers(0, 4)) + int(rng.integers(side, 65))
+            lay = TILE
+        elif kind == 2:                                   # narrow matrix: 16 or fewer columns
+            c = int(rng.integers(1, 17))
+            r = 64 * int(rng.integers(-(-k // (64 * c)) + 0, -(-k // (64 * c)) + 3)) if 64 * c >= k else 0
+            if r == 0:
+                r, c = 64 * (-(-k // c) // 64 + 1), c
+            lay = TILE
+            if min(64, r) * c < k or (r % 64 and (r % 64) * c < k):
+                r = 64 * (r // 64 + 1)
+                if 64 * c < k:
+                    continue
+        elif kind == 3:                                   # matrix cut into flat runs
+            r, c, lay = int(rng.integers(40, 90)), int(rng.integers(90, 200)), FLAT
+            if (r * c) % 4096 and (r * c) % 4096 < k:
+                c += 64
+            if (r * c) % 4096 and (r * c) % 4096 < k:
+                continue
+        else:                                             # exactly full tiles
+            r, c, lay = 64 * int(rng.integers(1, 3)), 64 * int(rng.integers(1, 4)), TILE
+        descs.append((r, c, off, lay))
+        off += r * c + int(rng.integers(0, 6)) * 4
+        off = (off + 3) // 4 * 4
+    return descs, off + 8
+
+
+@pytest.mark.parametrize("case", range(160))
+def test_random_configuration(sl, oracle, case):
+    rng = np.random.default_rng(7000 + case)
+    bits = int(rng.choice([1, 2, 2, 2, 3, 4, 32]))
+    k = int(rng.choice([4, 8, 12, 16, 32, 40, 64, 100, 128, 256, 320, 1024]))
+    if bits != 2:
+        k = max(8, k // 8 * 8)
+    descs, n = [], 0
+    while not descs:
+        descs, n = random_list(rng, k)
+    R = int(rng.choice([1, 2, 3, 4, 8, 13]))
+    beta = float(rng.choice([0.0, 0.9, 0.95, 1.0]))
+    lr = float(rng.choice([0.5, 0.7, 1.0]))
+    mode = str(rng.choice(["eager", "deferred", "frozen", "random", "params"]))
+    try:
+        plan = sl.sl_plan_create_bits(descs, k, bits)
+    except sl.SparseLoCoError:
+        pytest.skip("generator produced a chunk smaller than k")   # the oracle rejects it as well
+    assert plan.num_chunks == oracle.num_chunks(descs)
+    ws = sl.alloc_workspace(plan)
+    theta0 = rng.normal(0, 0.02, n).astype(np.float32)
+    theta = torch.from_numpy(theta0.copy()).cuda()
+    theta_ref = theta0.copy()
+    e = [torch.from_numpy(x).cuda() for x in (rng.normal(0, 1e-3, (R, n)).astype(np.float32))]
+    e_ref = [x.cpu().numpy().copy() for x in e]
+    pend = [None] * R
+    for rnd in range(2):
+        pays, refs = [], []
+        for r in range(R):
+            heavy = rng.random() < 0.5
+            delta = ((rng.standard_t(3, n) if heavy else rng.normal(0, 1, n)) * 1e-3).astype(np.float32)
+            if rng.random() < 0.2:
+                delta[rng.integers(0, n, n // 3)] = 0            # many exact zeros: ties
+            out = sl.alloc_payload(plan)
+            out.fill_(0xAB)
+            d = torch.from_numpy(delta).cuda()
+            if mode == "eager":
+                sl.sl_compress(plan, e[r], d, beta, out, ws)
+                ref = oracle.compress_b(descs, k, bits, e_ref[r], delta, beta)
+            elif mode == "deferred":
+                sl.sl_compress(plan, e[r], d, beta, out, ws, flags=sl.SL_COMPRESS_DEFER_RESIDUAL, pending=pend[r])
+                pend[r] = out
+                ref = oracle.compress_b(descs, k, bits, e_ref[r], delta, beta)
+            elif mode == "frozen":
+                sl.sl_compress(plan, e[r], d, beta, out, ws, flags=sl.SL_COMPRESS_EF_FROZEN)
+                ref = oracle.compress_b(descs, k, bits, e_ref[r], delta, beta, ef_frozen=True)
+            elif mode == "random":
+                seed = int(rng.integers(0, 2**32))
+                sl.sl_compress_random_k(plan, e[r], d, beta, out, ws, seed)
+                ref = oracle.compress_random_b(descs, k, bits, e_ref[r], delta, beta, seed)
+            else:
+                outer = rng.normal(0, 0.02, n).astype(np.float32)
+                local = (outer - delta).astype(np.float32)
+                sl.sl_compress_params(plan, e[r], torch.from_numpy(outer).cuda(), torch.from_numpy(local).cuda(),
+                                      beta, out, ws)
+                ref = oracle.compress_b(descs, k, bits, e_ref[r], outer - local, beta)
+            torch.cuda.synchronize()
+            got = out[:plan.payload_bytes].cpu().numpy()
+            assert np.array_equal(got, ref), (f"case {case} {mode} bits={bits} k={k} round {rnd} worker {r}: "
+                                              f"payload differs at {np.nonzero(got != ref)[0][:6]}; {descs}")
+            assert sl.sl_payload_validate(plan, out, ws)
+            pays.append(out)
+            refs.append(ref)
+        sl.sl_decompress_avg_apply(plan, theta, pays, lr)
+        oracle.decompress_avg_apply_b(descs, k, bits, theta_ref, refs, lr)
+        torch.cuda.synchronize()
+        assert_f32_close(theta.cpu().numpy(), theta_ref, f"case {case} theta round {rnd}")
+    for r in range(R):
+        if pend[r] is not None:
+            sl.sl_residual_apply(plan, e[r], pend[r])
+    torch.cuda.synchronize()
+    for r in range(R):
+        assert_f32_close(e[r].cpu().numpy(), e_ref[r], f"case {case} {mode} e[{r}]")
+    plan.close()
