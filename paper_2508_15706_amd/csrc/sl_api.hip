@@ -104,7 +104,7 @@ int sl_plan_create_bits(const sl_tensor *tensors, int n_tensors, int k, int valu
                         if (rv * cv < k) return SL_ERR_INVALID_ARG;
                         d.rows = (unsigned char)rv;
                         d.cols = d.last_cols = (unsigned char)cv;
-                        d.flags = (rv == 64 && cv == 64 && (T.cols & 3) == 0) ? SLC_FULL : 0;
+                        d.flags = (rv == 64 && cv == 64) ? SLC_FULL : 0;
                         d.tensor = t;
                         d.local_chunk = (int)(a * tc + b);
                         d.rec_off = (long long)pay + hdr + (long long)d.local_chunk * rec;

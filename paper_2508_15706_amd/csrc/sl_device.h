@@ -26,6 +26,11 @@ SL_DEV void sl_wave_sync()
 }
 
 typedef float sl_f4 __attribute__((ext_vector_type(4)));
+// The same vector in memory that is only 4-byte aligned (rows of a matrix whose column
+// count is not a multiple of 4): still one 16-byte access - global memory accesses need
+// no more than dword alignment on this target - so every streaming access below goes
+// through it and a full tile of any matrix takes the vector path.
+typedef float sl_f4u __attribute__((ext_vector_type(4), aligned(4)));
 
 // Streaming (non-temporal) 16-byte accesses for data that is touched once.
 // The *_at forms take a wave-uniform base and a 32-bit byte offset, which the
@@ -45,12 +50,22 @@ SL_DEV void sl_store_stream(float *p, sl_f4 v)
 SL_DEV sl_f4 sl_load_stream_at(const float *base, unsigned row_off, unsigned lane_off)
 {
     const char *row = reinterpret_cast<const char *>(base) + row_off;
-    return __builtin_nontemporal_load(reinterpret_cast<const sl_f4 *>(row + lane_off));
+    return __builtin_nontemporal_load(reinterpret_cast<const sl_f4u *>(row + lane_off));
 }
 SL_DEV void sl_store_stream_at(float *base, unsigned row_off, unsigned lane_off, sl_f4 v)
 {
     char *row = reinterpret_cast<char *>(base) + row_off;
-    __builtin_nontemporal_store(v, reinterpret_cast<sl_f4 *>(row + lane_off));
+    __builtin_nontemporal_store(v, reinterpret_cast<sl_f4u *>(row + lane_off));
+}
+
+// 16-byte streaming accesses at an address that is only 4-byte aligned.
+SL_DEV sl_f4 sl_load_stream_u(const float *p)
+{
+    return __builtin_nontemporal_load(reinterpret_cast<const sl_f4u *>(p));
+}
+SL_DEV void sl_store_stream_u(float *p, sl_f4 v)
+{
+    __builtin_nontemporal_store(v, reinterpret_cast<sl_f4u *>(p));
 }
 
 SL_DEV int sl_popc(unsigned long long m) { return __builtin_popcountll(m); }

@@ -19,7 +19,7 @@ struct SlChunkDesc {
     int local_chunk;        // index of the chunk inside its tensor
 };
 static_assert(sizeof(SlChunkDesc) == 32, "descriptor is one 32-byte load");
-enum { SLC_FULL = 1 };   // all 4096 positions valid and every row 16-byte aligned
+enum { SLC_FULL = 1 };   // all 4096 positions valid (rows need not be 16-byte aligned)
 
 struct SlTensorDev {
     long long chunk0;       // first chunk of the tensor in list order

@@ -527,38 +527,72 @@ __global__ void SL_SELECT_BOUNDS k_select(SelectArgs A)
             }
         }
     } else {
-        // ------------------------------------------------------------ partial chunk, scalar accesses
+        // ------------------------------------------------------------ partial chunk
+        // A lane whose four columns of a row all lie inside the tensor still moves them
+        // with one 16-byte access; a lane that straddles the edge goes element by element.
         const int rows = d.rows, cols = d.cols, last_cols = d.last_cols;
         if (!SUBK && pend) pend_build();
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
             const int row = 4 * i + lr;
             const int lim = row < rows - 1 ? cols : (row == rows - 1 ? last_cols : 0);
+            const bool all = lc + 3 < lim;
+            const unsigned o0 = row * stride + lc;
+            const bool need_e = SUBK || !A.frozen;
+            float ein[4] = {0.f, 0.f, 0.f, 0.f}, din[4] = {0.f, 0.f, 0.f, 0.f};
+            if (all) {
+                if (need_e) {
+                    const sl_f4 E = sl_load_stream_u(ec + o0);
+                    ein[0] = E.x, ein[1] = E.y, ein[2] = E.z, ein[3] = E.w;
+                }
+                if constexpr (!SUBK) {
+                    sl_f4 D = sl_load_stream_u(dc + o0);
+                    if constexpr (PARAMS) D = D - sl_load_stream_u(A.theta_local + d.base + o0);
+                    din[0] = D.x, din[1] = D.y, din[2] = D.z, din[3] = D.w;
+                }
+            } else {
+#pragma unroll
+                for (int cc = 0; cc < 4; ++cc) {
+                    if (lc + cc < lim) {
+                        if (need_e) ein[cc] = ec[o0 + cc];
+                        if constexpr (!SUBK)
+                            din[cc] = PARAMS ? dc[o0 + cc] - (A.theta_local + d.base)[o0 + cc] : dc[o0 + cc];
+                    }
+                }
+            }
+            float vout[4];
 #pragma unroll
             for (int cc = 0; cc < 4; ++cc) {
-                const int col = lc + cc;
                 float v = 0.0f;
-                if (col < lim) {
-                    const unsigned o = row * stride + col;
+                if (lc + cc < lim) {
                     if constexpr (SUBK) {
-                        v = ec[o];
+                        v = ein[cc];
                     } else if (!A.frozen) {
-                        float ee = ec[o];
+                        float ee = ein[cc];
                         if (pend) {
                             const unsigned w = 8 * i + (lane >> 3), bit = 4u * (lane & 7) + cc;
                             const unsigned word = bm[w];
                             if ((word >> bit) & 1u)
                                 ee = ee - ql[(int)pre[w] + __popc(word & ((1u << bit) - 1u))];
                         }
-                        v = fmaf(A.beta, ee, PARAMS ? dc[o] - (A.theta_local + d.base)[o] : dc[o]);
-                        ec[o] = v;
+                        v = fmaf(A.beta, ee, din[cc]);
                     } else {
-                        v = PARAMS ? dc[o] - (A.theta_local + d.base)[o] : dc[o];
+                        v = din[cc];
                     }
                 } else {
                     inside &= ~(1ull << (4 * i + cc));
                 }
+                vout[cc] = v;
                 a[4 * i + cc] = v;
+            }
+            if (!SUBK && !A.frozen) {
+                if (all) {
+                    sl_store_stream_u(ec + o0, sl_f4{vout[0], vout[1], vout[2], vout[3]});
+                } else {
+#pragma unroll
+                    for (int cc = 0; cc < 4; ++cc)
+                        if (lc + cc < lim) ec[o0 + cc] = vout[cc];
+                }
             }
         }
     }
