@@ -77,7 +77,9 @@ typedef struct sl_plan sl_plan; /* opaque: chunk work list and per-tensor tables
 
 /* Builds the work list for a tensor list and a per-chunk k (Section 3.3:
  * chunk-wise Top-k with a fixed k per chunk, density k/4096).  `tensors` is a
- * host array, copied.  k must be a multiple of 4 with 4 <= k <= 4096.  Allocates
+ * host array, copied.  k must be a multiple of 4 with 4 <= k <= 4096.  Limits:
+ * rows*cols <= 2^46 per tensor, cols <= 2^23 for a TILE64 tensor, at most 2^27
+ * chunks in the whole list (more than 288 GB of HBM can hold).  Allocates
  * small device tables on the current device (freed by sl_plan_destroy).
  * Errors: INVALID_ARG (shape, alignment, overlap, a chunk with fewer than k
  * elements), NOMEM, HIP. */

@@ -24,6 +24,10 @@ static int hip_fail(hipError_t e)
 
 static size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
+// limits of a plan (documented at sl_plan_create)
+static const int64_t SL_MAX_TENSOR_ELEMS = (int64_t)1 << 46;
+static const int64_t SL_MAX_CHUNKS = (int64_t)1 << 27;
+
 extern "C" int sl_profile_end(sl_plan *p, double *ms, int *calls);
 
 extern "C" {
@@ -71,16 +75,20 @@ int sl_plan_create_bits(const sl_tensor *tensors, int n_tensors, int k, int valu
     // tensors must not overlap: results would depend on processing order
     {
         std::vector<std::pair<int64_t, int64_t>> span;
+        int64_t total_chunks = 0;
         for (int t = 0; t < n_tensors; ++t) {
             const sl_tensor &T = tensors[t];
             if (T.rows < 1 || T.cols < 1 || T.offset < 0 || (T.offset & 3) || T.reserved != 0)
                 return SL_ERR_INVALID_ARG;
             if (T.layout != SL_LAYOUT_FLAT && T.layout != SL_LAYOUT_TILE64) return SL_ERR_INVALID_ARG;
-            if (T.rows > (int64_t)1 << 40 || T.cols > (int64_t)1 << 40 ||
-                T.rows * T.cols > (int64_t)1 << 46)
-                return SL_ERR_INVALID_ARG;
+            if (T.rows > SL_MAX_TENSOR_ELEMS / T.cols) return SL_ERR_INVALID_ARG;   // no overflow in the product
+            if (T.offset > ((int64_t)1 << 60)) return SL_ERR_INVALID_ARG;
             if (T.layout == SL_LAYOUT_TILE64 && T.cols > (int64_t)1 << 23) return SL_ERR_INVALID_ARG;
             span.emplace_back(T.offset, T.offset + T.rows * T.cols);
+            // the work list is built only once its length is known to be within the limit
+            total_chunks += T.layout == SL_LAYOUT_TILE64 ? ((T.rows + 63) / 64) * ((T.cols + 63) / 64)
+                                                         : (T.rows * T.cols + SL_CHUNK - 1) / SL_CHUNK;
+            if (total_chunks > SL_MAX_CHUNKS) return SL_ERR_INVALID_ARG;
         }
         std::sort(span.begin(), span.end());
         for (size_t i = 1; i < span.size(); ++i)
@@ -139,7 +147,6 @@ int sl_plan_create_bits(const sl_tensor *tensors, int n_tensors, int k, int valu
     } catch (const std::bad_alloc &) {
         return SL_ERR_NOMEM;
     }
-    if (desc.size() > 0x7FFFFFFFu) return SL_ERR_INVALID_ARG;
     for (const SlChunkDesc &d : desc) n_partial += !(d.flags & SLC_FULL);
 
     sl_plan *p = new (std::nothrow) sl_plan();

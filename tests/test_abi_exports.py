@@ -38,6 +38,15 @@ def test_host_side_argument_validation_needs_no_gpu():
     assert L.sl_plan_create(small, 1, 128, ctypes.byref(h)) == -1      # chunk smaller than k
     odd = (binding.SlTensor * 1)(binding.SlTensor(64, 64, 2, 1, 0))
     assert L.sl_plan_create(odd, 1, 32, ctypes.byref(h)) == -1         # misaligned offset
+    # limits: products that would overflow 64 bits, or work lists too long to build, are refused up front
+    for rows, cols, lay in ((1 << 40, 1 << 40, 0), (1 << 62, 4, 0), (1 << 23, 1 << 24, 1), (1 << 20, 1 << 25, 0),
+                            (1 << 22, 1 << 22, 1)):
+        huge = (binding.SlTensor * 1)(binding.SlTensor(rows, cols, 0, lay, 0))
+        assert L.sl_plan_create(huge, 1, 64, ctypes.byref(h)) == -1, (rows, cols, lay)
+    two = (binding.SlTensor * 2)(binding.SlTensor(64, 64, 0, 1, 0), binding.SlTensor(64, 64, 4092, 1, 0))
+    assert L.sl_plan_create(two, 2, 64, ctypes.byref(h)) == -1         # overlapping tensors
+    assert L.sl_plan_create_bits(bad, 1, 64, 5, ctypes.byref(h)) == -1   # no such value width
+    assert L.sl_plan_create_bits(bad, 1, 4, 3, ctypes.byref(h)) == -1    # records must end on a byte
     assert h.value is None
     assert L.sl_pack_indices(None, None, 1, 6, None, None) == -1
     assert L.sl_payload_bytes(None) == 0
