@@ -67,6 +67,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", type=int, default=4)
     ap.add_argument("--k", type=int, default=None)
+    ap.add_argument("--workers", type=int, default=None,
+                    help="number of workers R whose payloads are aggregated (default: the configuration's)")
     ap.add_argument("--flat", action="store_true", help="cut every tensor into runs of 4096")
     ap.add_argument("--bits", type=int, default=2, choices=[1, 2, 3, 4, 32],
                     help="payload value width (the paper's setting is 2; 32 = unquantized fp32)")
@@ -98,6 +100,10 @@ def main():
     dev = torch.device("cuda:0")
 
     w = synth.workload(args.config, k=args.k, flat=args.flat)
+    if args.workers is not None:
+        if not 1 <= args.workers <= 64:
+            raise SystemExit("--workers must be between 1 and 64")
+        w.R = args.workers
     descs = [s.desc() for s in w.specs]
     plan = sl.sl_plan_create(descs, w.k) if args.bits == 2 else sl.sl_plan_create_bits(descs, w.k, args.bits)
     N, n_chunks, arena = plan.num_elements, plan.num_chunks, w.arena
@@ -228,7 +234,7 @@ def main():
     # paper_2508_15706_amd/rocprof_summary.py from a profiled run of this same command)
     traffic = None
     tpath = os.path.join(ROOT, "profiles", f"traffic_config{w.config_id}_{PROFILE_TAGS.get(w.config_id, '')}.json")
-    if os.path.exists(tpath) and not args.flat and args.k is None and args.bits == 2:
+    if os.path.exists(tpath) and not args.flat and args.k is None and args.bits == 2 and args.workers is None:
         tk = json.load(open(tpath))["kernels"]
         name = next((n for n in tk if n.startswith("k_select")), None)
         if name and tk[name]["fetch_bytes"] is not None and tk[name]["write_bytes"] is not None:

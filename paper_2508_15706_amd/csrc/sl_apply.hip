@@ -16,10 +16,35 @@ namespace {
 
 // When there is much to decode per chunk (R*k entries), the chunk is aggregated
 // in NH = 2 halves of 32 rows (local indices below / from 2048): 8 KB of
-// accumulators per wave instead of 16, so that twice as many waves - and twice
-// as many bytes of theta in flight - fit a compute unit while the decode runs.
-// With little to decode one pass (NH = 1) is slightly faster.
-constexpr int APPLY_HALVES_FROM = 768;       // R*k from which two halves pay (measured)
+// accumulators per wave instead of 16, so that more waves - and more bytes of
+// theta in flight - fit a compute unit while the decode runs.  With little to
+// decode one pass (NH = 1) is faster; so it is when one record alone is large
+// (k > 512), where the halves would have to stage every record twice.
+#ifndef SL_APPLY_HALVES_FROM
+#define SL_APPLY_HALVES_FROM 1536   // R*k from which two halves pay (measured)
+#endif
+
+#ifndef SL_APPLY_OCTETS_FROM
+#define SL_APPLY_OCTETS_FROM 256   // k from which a lane decodes eight entries at a time
+#endif
+#ifndef SL_APPLY_HALVES_TO
+#define SL_APPLY_HALVES_TO 512     // largest k that is still aggregated in two halves (measured)
+#endif
+#ifndef SL_APPLY_STAGE_U
+#define SL_APPLY_STAGE_U 8    // words per lane loaded together while records are staged
+#endif
+#ifndef SL_APPLY_BIG_STAGE
+#define SL_APPLY_BIG_STAGE 4096   // staging bytes when one record is larger than 1 KB
+#endif
+
+// pointers into global memory, for addresses that are put together from integers
+typedef const unsigned char __attribute__((address_space(1))) *sl_gbytes;
+typedef const unsigned __attribute__((address_space(1))) *sl_gwords;
+
+// acc[j] += q in LDS, as a read, an fp32 add and a write.  (The LDS unit's own fp32 add gives the
+// same bits, subnormal sums included, but at a fraction of the rate: 2.35 -> 2.45 ms at k = 64 and
+// several times slower from k = 256.)
+SL_DEV void acc_add(float *acc, unsigned j, float q) { acc[j] = acc[j] + q; }
 
 struct ApplyArgs {
     const SlChunkDesc *desc;
@@ -30,6 +55,9 @@ struct ApplyArgs {
     int R, k;
     int bits, hdr_bytes, rec_bytes;   // value width and the sizes that follow from it
     int batch;               // records staged per round
+    // x / d for the staging loops without a division: __umulhi(x, floor(2^32 / d) + 1) is
+    // exact while x * d < 2^32 (x < 16384 here); d = words per (table + record), bytes per record
+    unsigned magic_src, magic_rec;
     int lds_per_wave;
     long long n_chunks;
     const unsigned char *payload[SL_MAX_WORKERS];
@@ -41,9 +69,18 @@ struct ApplyArgs {
 // NESTEROV: DiLoCo's global outer momentum on top of the aggregate (Eq. (1);
 // appendix algorithm "Outer step for DiLoCo+Top-k[+EF]"): m <- mu*m + avg,
 // d <- avg + mu*m, theta <- theta - lr*d at every element of the chunk.
-template <bool TWO_BIT, bool NESTEROV, int NH>
+// ROUTE: how a staged record's entries reach the accumulators.
+//   0 (k <= 128, one pass): the entries of several workers are decoded ahead of the additions;
+//   1: entry by entry, one worker at a time;
+//   2, 3 (k >= 256, a multiple of 8): a lane decodes eight consecutive entries from whole words;
+//      up to 4 KB (2) or 8 KB (3) of records are fetched ahead of the theta loads - the
+//      smaller kernel leaves registers for a third wave per SIMD.
+// The routes are separate instantiations, so that none pays for another's registers.
+template <bool TWO_BIT, bool NESTEROV, int NH, int ROUTE>
 __global__ void __launch_bounds__(256) k_apply(ApplyArgs A)
 {
+    constexpr bool SMALLK = ROUTE == 0, OCTETS = ROUTE >= 2;
+    static_assert(!SMALLK || NH == 1, "the small-k route makes one pass over the chunk");
     constexpr int ACC_FLOATS = SL_CHUNK / NH, ROWS4 = 16 / NH;   // accumulators, 16-byte accesses per lane
     extern __shared__ __align__(16) unsigned char smem_all[];
     const int lane = threadIdx.x & 63, k = A.k;
@@ -69,28 +106,42 @@ __global__ void __launch_bounds__(256) k_apply(ApplyArgs A)
     const bool word_path = (rec_bytes & 3) == 0;
     const int wpr_src = hdr_words + (rec_bytes >> 2);  // words per worker: LUT + record
     const int wpr_dst = rec_pad >> 2;
-    auto src_word = [&](int r, int q) -> unsigned {
-        const unsigned char *p = A.payload[r];
-        return q < hdr_words ? reinterpret_cast<const unsigned *>(p + lut_off)[q]
-                             : reinterpret_cast<const unsigned *>(p + rec_off)[q - hdr_words];
+    const int hdr_shift = 31 - __clz(hdr_words | 1);   // the table is 4, 8 or 16 words (or absent)
+    // Worker r's payload pointer where r differs from lane to lane: lane l keeps worker l's
+    // pointer (there are at most as many workers as lanes) and the others read it across
+    // lanes.  Indexing the kernel argument with a per-lane r instead costs a dependent vector
+    // load of the pointer in front of every access.  Called by all 64 lanes together.
+    static_assert(SL_MAX_WORKERS <= 64, "one payload pointer per lane");
+    const unsigned long long my_ptr = reinterpret_cast<unsigned long long>(A.payload[lane]);
+    // (the pointer comes back as an integer: it is cast to the global address space by hand, a
+    // generic pointer would turn every access into a flat load that LDS waits have to sit out)
+    auto payload_of = [&](int r) -> sl_gbytes {
+        const unsigned lo = (unsigned)__builtin_amdgcn_ds_bpermute(4 * r, (int)(unsigned)my_ptr);
+        const unsigned hi = (unsigned)__builtin_amdgcn_ds_bpermute(4 * r, (int)(unsigned)(my_ptr >> 32));
+        return reinterpret_cast<sl_gbytes>(((unsigned long long)hi << 32) | lo);
+    };
+    // Word w of workers r_first.. taken as one run of (LUT, record) blocks, or 0 beyond `nw`.
+    auto src_word = [&](int r_first, int w, int nw) -> unsigned {
+        const bool valid = w < nw;
+        const int r = valid ? (int)__umulhi((unsigned)w, A.magic_src) : 0, q = w - r * wpr_src;
+        const sl_gbytes p = payload_of(r_first + r);
+        unsigned v = 0;
+        if (valid)
+            v = q < hdr_words ? reinterpret_cast<sl_gwords>(p + lut_off)[q]
+                              : reinterpret_cast<sl_gwords>(p + rec_off)[q - hdr_words];
+        return v;
     };
     // The first 64*PF words of the first batch (all of it for R*(16 + 7k/4) <= 2 KB:
     // R = 8 up to k = 128, R = 16 up to k = 64) are fetched into registers BEFORE the
     // theta loads: loads complete in order, so the decode below then waits for these
     // few words only and runs while the chunk's 16 KB of theta are still in flight.
-    constexpr int PF = TWO_BIT ? 8 : 12;   // wider records at other widths: 3 KB
+    // (wider records at other widths: 3 KB; the eight-entry route exists for large records: 8 KB)
+    constexpr int PF = ROUTE == 3 ? 32 : ROUTE == 2 ? 16 : TWO_BIT ? 8 : 12;
     unsigned pf[PF];
     const int nb0 = min(A.batch, A.R);
     if (word_path) {
 #pragma unroll
-        for (int u = 0; u < PF; ++u) {
-            const int w = lane + 64 * u;
-            pf[u] = 0;
-            if (w < nb0 * wpr_src) {
-                const int r = w / wpr_src;
-                pf[u] = src_word(r, w - r * wpr_src);
-            }
-        }
+        for (int u = 0; u < PF; ++u) pf[u] = src_word(0, lane + 64 * u, nb0 * wpr_src);
     }
 
     sl_f4 th[16], mo[NESTEROV ? 16 : 1];
@@ -117,31 +168,46 @@ __global__ void __launch_bounds__(256) k_apply(ApplyArgs A)
             sl_wave_sync();
             if (h == 0 || !single) {
                 if (word_path) {
-                    int w0 = lane;
+                    const int nw = nb * wpr_src;
+                    int wb = 0;                       // wave-uniform: word wb + lane is this lane's next
                     if (r0 == 0 && h == 0) {
 #pragma unroll
                         for (int u = 0; u < PF; ++u) {
                             const int w = lane + 64 * u;
-                            if (w < nb * wpr_src) {
-                                const int r = w / wpr_src;
-                                reinterpret_cast<unsigned *>(stage)[r * wpr_dst + (w - r * wpr_src)] = pf[u];
-                            }
+                            // (whole-word records: the staging pitch is wpr_src words, word w lands at w)
+                            if (w < nw) reinterpret_cast<unsigned *>(stage)[w] = pf[u];
                         }
-                        w0 = lane + 64 * PF;
+                        wb = 64 * PF;
                     }
-                    for (int w = w0; w < nb * wpr_src; w += 64) {
-                        const int r = w / wpr_src, q = w - r * wpr_src;
-                        reinterpret_cast<unsigned *>(stage)[r * wpr_dst + q] = src_word(r0 + r, q);
+                    // the rest: SU words per lane are loaded before the first of them is parked in LDS
+                    constexpr int SU = OCTETS ? SL_APPLY_STAGE_U : 1;   // (small k: little or nothing is left)
+                    for (; wb < nw; wb += 64 * SU) {
+                        unsigned v[SU];
+#pragma unroll
+                        for (int u = 0; u < SU; ++u) v[u] = src_word(r0, wb + 64 * u + lane, nw);
+#pragma unroll
+                        for (int u = 0; u < SU; ++u) {
+                            const int w = wb + 64 * u + lane;
+                            if (w < nw) reinterpret_cast<unsigned *>(stage)[w] = v[u];
+                        }
                     }
                 } else {
-                    for (int w = lane; w < nb * hdr_words; w += 64) {    // the tensor's LUT of each worker
-                        const int r = w / hdr_words, q = w - r * hdr_words;
-                        reinterpret_cast<unsigned *>(stage)[r * wpr_dst + q] =
-                            reinterpret_cast<const unsigned *>(A.payload[r0 + r] + lut_off)[q];
+                    const int nlw = nb * hdr_words, nrb = nb * rec_bytes;
+                    for (int wb = 0; wb < nlw; wb += 64) {              // the tensor's LUT of each worker
+                        const int w = wb + lane;
+                        const bool valid = w < nlw;
+                        const int r = valid ? w >> hdr_shift : 0, q = w & (hdr_words - 1);
+                        const sl_gbytes p = payload_of(r0 + r);
+                        if (valid)
+                            reinterpret_cast<unsigned *>(stage)[r * wpr_dst + q] =
+                                reinterpret_cast<sl_gwords>(p + lut_off)[q];
                     }
-                    for (int b = lane; b < nb * rec_bytes; b += 64) {
-                        const int r = b / rec_bytes, q = b - r * rec_bytes;
-                        stage[r * rec_pad + hdr + q] = A.payload[r0 + r][rec_off + q];
+                    for (int bb = 0; bb < nrb; bb += 64) {
+                        const int b = bb + lane;
+                        const bool valid = b < nrb;
+                        const int r = valid ? (int)__umulhi((unsigned)b, A.magic_rec) : 0, q = b - r * rec_bytes;
+                        const sl_gbytes p = payload_of(r0 + r);
+                        if (valid) stage[r * rec_pad + hdr + q] = p[rec_off + q];
                     }
                 }
                 sl_wave_sync();
@@ -158,7 +224,7 @@ __global__ void __launch_bounds__(256) k_apply(ApplyArgs A)
                 else if (bits == 32) q = reinterpret_cast<const float *>(codes)[m];
                 else q = lutp[sl_code_at(codes, m, bits)];
             };
-            if (NH == 1 && k <= 128) {
+            if constexpr (SMALLK) {
                 // The entries of up to eight workers are decoded first (independent LDS reads,
                 // all in flight together), then added worker by worker: the additions form a
                 // chain of LDS round trips, the decoding no longer sits inside it.
@@ -181,11 +247,63 @@ __global__ void __launch_bounds__(256) k_apply(ApplyArgs A)
                             for (int s2 = 0; s2 < 2; ++s2) {
                                 const unsigned j = jj[u][s2];
                                 if (j != 0xFFFFu && (NH == 1 || (int)(j >> 11) == h))
-                                    acc[j & (ACC_FLOATS - 1)] = acc[j & (ACC_FLOATS - 1)] + qq[u][s2];
+                                    acc_add(acc, j & (ACC_FLOATS - 1), qq[u][s2]);
                             }
                             sl_wave_sync();   // worker r is complete before worker r+1 is added
                         }
                     }
+                }
+            } else if constexpr (OCTETS) {
+                // Eight consecutive entries per lane: their indices are three aligned words
+                // of the record and their codes `bits` bytes, so a lane decodes them with 4
+                // LDS reads instead of 24 and a fraction of the arithmetic.  The positions
+                // of one record are distinct: the eight accumulator reads, then the eight
+                // writes, are issued together.
+                for (int r = 0; r < nb; ++r) {
+                    const unsigned char *base = stage + r * rec_pad;
+                    const float *lutp = reinterpret_cast<const float *>(base);
+                    const unsigned *iw = reinterpret_cast<const unsigned *>(base + hdr);
+                    const unsigned char *codes = base + hdr + 3 * k / 2;
+                    float l0 = 0.f, l1 = 0.f, l2 = 0.f, l3 = 0.f;
+                    if (TWO_BIT) l0 = lutp[0], l1 = lutp[1], l2 = lutp[2], l3 = lutp[3];
+                    for (int o = lane; o < (k >> 3); o += 64) {
+                        const unsigned w0 = iw[3 * o], w1 = iw[3 * o + 1], w2 = iw[3 * o + 2];
+                        unsigned jj[8];
+                        jj[0] = w0 & 0xFFFu;
+                        jj[1] = (w0 >> 12) & 0xFFFu;
+                        jj[2] = (w0 >> 24) | ((w1 & 0xFu) << 8);
+                        jj[3] = (w1 >> 4) & 0xFFFu;
+                        jj[4] = (w1 >> 16) & 0xFFFu;
+                        jj[5] = (w1 >> 28) | ((w2 & 0xFFu) << 4);
+                        jj[6] = (w2 >> 8) & 0xFFFu;
+                        jj[7] = w2 >> 20;
+                        float qq[8];
+                        if (TWO_BIT) {
+                            const unsigned cw = reinterpret_cast<const unsigned short *>(codes)[o];
+#pragma unroll
+                            for (int e = 0; e < 8; ++e) {
+                                const unsigned cde = cw >> (2 * e);
+                                const float lo = (cde & 1u) ? l1 : l0, hi = (cde & 1u) ? l3 : l2;
+                                qq[e] = (cde & 2u) ? hi : lo;
+                            }
+                        } else if (bits == 32) {
+#pragma unroll
+                            for (int e = 0; e < 8; ++e) qq[e] = reinterpret_cast<const float *>(codes)[8 * o + e];
+                        } else {
+                            unsigned cw = 0;
+                            for (int b = 0; b < bits; ++b) cw |= (unsigned)codes[o * bits + b] << (8 * b);
+#pragma unroll
+                            for (int e = 0; e < 8; ++e) qq[e] = lutp[(cw >> (e * bits)) & ((1u << bits) - 1u)];
+                        }
+                        float t[8];
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) t[e] = acc[jj[e] & (ACC_FLOATS - 1)];
+#pragma unroll
+                        for (int e = 0; e < 8; ++e)
+                            if (NH == 1 || (int)(jj[e] >> 11) == h)
+                                acc[jj[e] & (ACC_FLOATS - 1)] = t[e] + qq[e];
+                    }
+                    sl_wave_sync();       // worker r is complete before worker r+1 is added
                 }
             } else {
                 for (int r = 0; r < nb; ++r) {
@@ -194,7 +312,7 @@ __global__ void __launch_bounds__(256) k_apply(ApplyArgs A)
                         float q;
                         decode(r, m, j, q);
                         if (NH == 1 || (int)(j >> 11) == h)         // this half's entries
-                            acc[j & (ACC_FLOATS - 1)] = acc[j & (ACC_FLOATS - 1)] + q;
+                            acc_add(acc, j & (ACC_FLOATS - 1), q);
                     }
                     sl_wave_sync();           // worker r is complete before worker r+1 is added
                 }
@@ -395,15 +513,18 @@ int slk_apply(const sl_plan *p, float *theta, float *mom, float mu, const void *
     const int rec_pad = ((p->rec_bytes + 3) & ~3) + p->hdr_bytes;
     // at most 16 KB of staged records; 4 KB when a record alone is large (k >= 1024), so that the
     // accumulators are not crowded out of the LDS
-    int batch = (rec_pad > 1024 ? 4096 : 16384) / rec_pad;
+    int batch = (rec_pad > 1024 ? SL_APPLY_BIG_STAGE : 16384) / rec_pad;
     if (batch < 1) batch = 1;
     if (batch > R) batch = R;
     A.batch = batch;
+    A.magic_src = (unsigned)(0x100000000ull / (unsigned)((p->hdr_bytes >> 2) + (p->rec_bytes >> 2)) + 1);
+    A.magic_rec = (unsigned)(0x100000000ull / (unsigned)p->rec_bytes + 1);
     for (int r = 0; r < SL_MAX_WORKERS; ++r)
         A.payload[r] = r < R ? static_cast<const unsigned char *>(payloads[r]) : nullptr;
     A.n_chunks = p->n_chunks;
     // (not when the staged records themselves are the larger part of the LDS: nothing would be gained)
-    const bool halves = (long long)R * p->k >= APPLY_HALVES_FROM && (size_t)batch * rec_pad <= 8192;
+    const bool halves = (long long)R * p->k >= SL_APPLY_HALVES_FROM && (size_t)batch * rec_pad <= 8192 &&
+                        p->k <= SL_APPLY_HALVES_TO;
     const size_t acc_bytes = SL_CHUNK * sizeof(float) / (halves ? 2 : 1);
     A.lds_per_wave = (int)((acc_bytes + (size_t)batch * rec_pad + 15) & ~(size_t)15);
     int wpb = 4;
@@ -411,10 +532,15 @@ int slk_apply(const sl_plan *p, float *theta, float *mom, float mu, const void *
     const size_t lds = (size_t)A.lds_per_wave * wpb;
     const bool two = p->bits == 2;
     typedef void (*kernel_t)(ApplyArgs);
-    static const kernel_t table[2][2][2] = {
-        {{k_apply<false, false, 1>, k_apply<false, false, 2>}, {k_apply<false, true, 1>, k_apply<false, true, 2>}},
-        {{k_apply<true, false, 1>, k_apply<true, false, 2>}, {k_apply<true, true, 1>, k_apply<true, true, 2>}}};
-    const kernel_t fn = table[two ? 1 : 0][mom ? 1 : 0][halves ? 1 : 0];
+    const bool octets = p->k >= SL_APPLY_OCTETS_FROM && (p->k & 7) == 0;
+    const int route = (!halves && p->k <= 128) ? 0 : !octets ? 1 : (size_t)batch * rec_pad <= 4096 ? 2 : 3;
+#define SL_APPLY_ROUTES(TWO, NEST)                                                                       \
+    {k_apply<TWO, NEST, 1, 0>, k_apply<TWO, NEST, 1, 1>, k_apply<TWO, NEST, 1, 2>, k_apply<TWO, NEST, 1, 3>, \
+     nullptr, k_apply<TWO, NEST, 2, 1>, k_apply<TWO, NEST, 2, 2>, k_apply<TWO, NEST, 2, 3>}
+    static const kernel_t table[2][2][8] = {{SL_APPLY_ROUTES(false, false), SL_APPLY_ROUTES(false, true)},
+                                            {SL_APPLY_ROUTES(true, false), SL_APPLY_ROUTES(true, true)}};
+#undef SL_APPLY_ROUTES
+    const kernel_t fn = table[two ? 1 : 0][mom ? 1 : 0][halves ? 4 + route : route];
     if (lds > 65536) {
         hipError_t aerr = hipFuncSetAttribute(reinterpret_cast<const void *>(fn),
                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);

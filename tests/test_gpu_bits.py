@@ -129,8 +129,54 @@ def test_deferred_residual_chain(sl, oracle, bits, k):
 @pytest.mark.parametrize("bits", (1, 3, 4, 32))
 @pytest.mark.parametrize("R,k,lr", [(1, 32, 1.0), (5, 24, 0.6), (8, 64, 1.0), (16, 128, 0.8), (3, 1024, 0.7)])
 def test_apply_matches_oracle(sl, oracle, bits, R, k, lr):
+    run_apply_case(sl, oracle, bits, R, k, lr)
+
+
+# From k = 256 a lane of the aggregate decodes eight entries at a time (word reads of the
+# record); k = 264 and 328 give records that are not a whole number of words, R = 24 at k = 2048
+# more records than are staged at once, R*k below and above the switch to two half-chunk passes.
+@pytest.mark.parametrize("bits", WIDTHS)
+@pytest.mark.parametrize("R,k,lr", [(2, 256, 1.0), (16, 256, 0.8), (2, 264, 0.9), (5, 328, 0.7), (8, 512, 1.0),
+                                    (4, 1024, 0.6), (24, 2048, 0.5), (2, 4096, 1.0)])
+def test_apply_high_density_matches_oracle(sl, oracle, bits, R, k, lr):
+    run_apply_case(sl, oracle, bits, R, k, lr)
+
+
+@pytest.mark.parametrize("bits", (2, 32))
+@pytest.mark.parametrize("R,k", [(8, 64), (16, 128), (4, 512)])
+def test_apply_keeps_subnormal_sums(sl, oracle, bits, R, k):
+    """Payload values in the subnormal range (multiples of 2^-149): every partial sum of the
+    aggregate, the average and the update of a zero theta are subnormal too, so a flush to zero
+    anywhere on the way shows as a difference from the oracle."""
+    shapes = [(128, 128, TILE), (1, 8192 + 1100, FLAT)]
+    descs, n = layout_list(shapes)
+    rng = np.random.default_rng(1700 + R + bits)
+    plan = sl.sl_plan_create_bits(descs, k, bits)
+    ws = sl.alloc_workspace(plan)
+    dev, host = [], []
+    for r in range(R):
+        delta = (rng.integers(-4000, 4000, n) * 2.0**-149).astype(np.float32)
+        e = torch.zeros(n, dtype=torch.float32, device="cuda")
+        pay = sl.alloc_payload(plan)
+        sl.sl_compress(plan, e, torch.from_numpy(delta).cuda(), 0.95, pay, ws)
+        torch.cuda.synchronize()
+        ref = oracle.compress_b(descs, k, bits, np.zeros(n, dtype=np.float32), delta, 0.95)
+        assert np.array_equal(pay[:plan.payload_bytes].cpu().numpy(), ref)
+        dev.append(pay)
+        host.append(ref)
+    theta = torch.zeros(n, dtype=torch.float32, device="cuda")
+    sl.sl_decompress_avg_apply(plan, theta, dev, 1.0)
+    torch.cuda.synchronize()
+    want = np.zeros(n, dtype=np.float32)
+    oracle.decompress_avg_apply_b(descs, k, bits, want, host, 1.0)
+    got = theta.cpu().numpy()
+    assert np.count_nonzero(want) > n // 100 and np.abs(want).max() < 2.0**-126   # the case is what it claims
+    assert np.array_equal(got.view(np.uint32), want.view(np.uint32))
+
+
+def run_apply_case(sl, oracle, bits, R, k, lr):
     shapes = [(150, 210, TILE), (1, 9000, FLAT), (128, 128, TILE), (1024, 16, TILE)] if k <= 256 \
-        else [(160, 224, TILE), (1, 8192 + 1100, FLAT)]
+        else [(160, 224, TILE), (1, 8192 + 1100, FLAT)] if k <= 1024 else [(128, 192, TILE), (1, 3 * 4096, FLAT)]
     descs, n = layout_list(shapes)
     rng = np.random.default_rng(1300 + 10 * R + bits)
     plan = sl.sl_plan_create_bits(descs, k, bits)
