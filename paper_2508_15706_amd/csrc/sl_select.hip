@@ -36,7 +36,9 @@ namespace {
 constexpr int CAND_CAP = 512;             // LDS candidate list, entries of 8 bytes
 constexpr int CAND_SLOTS = CAND_CAP / 64;
 
-constexpr int BM_WORDS = SL_CHUNK / 32;  // bitmap of the pending positions
+#ifndef SL_SELECT_PFE8
+#define SL_SELECT_PFE8 4
+#endif
 
 struct SelectArgs {
     const SlChunkDesc *desc;
@@ -51,6 +53,7 @@ struct SelectArgs {
     unsigned seed_hash;     // Random-k: fmix32(seed), see random_key
     int lds_per_wave;
     int pend_off;           // offset of the pending-correction tables in a wave's LDS
+    int pend_words;         // the pending record is staged in LDS as whole words (large k), see pend_half
     float *vals;            // [n_chunks * k] selected values, canonical order
     double *leafA;          // [2][n_chunks] per-chunk tree sums of x and x*x
     unsigned char *payload;
@@ -215,21 +218,25 @@ __global__ void SL_SELECT_BOUNDS k_select(SelectArgs A)
     unsigned long long inside = ~0ull;      // bit r: register r is a position of the tensor
     bool done = false;
 
-    // Pending error update of the previous round (deferred residual): the
-    // positions its record transmits become a 4096-bit map in LDS, with the
-    // number of set bits before each 32-bit word, and the dequantised values in
-    // record order (= ascending position, so rank in the map = record entry).
-    unsigned *bm = nullptr, *pre = nullptr;
-    float *ql = nullptr, *lutl = nullptr;
-    unsigned *tm = nullptr;                 // the same map once more, lane-major (see pend_build)
-    float *tq = nullptr;                    // value of the pending entry of (16-byte access i, lane), [16][64]
+    // Pending error update of the previous round (deferred residual): the values its
+    // record transmits are subtracted from e as e is read, see pend_half.
+    float *corr = nullptr;                  // pending values of one half of the chunk, by position
+    float *lutl = nullptr;                  // centroid table of the widths that keep it in LDS
     const bool pend = A.pending != nullptr;
     const int bits = TWO_BIT ? 2 : A.bits;
     const unsigned char *prec = nullptr, *pcodes = nullptr;
     float4 plut = make_float4(0.f, 0.f, 0.f, 0.f);
     float p_lutv = 0.f;                     // other widths: table entry `lane`, parked in LDS later
-    constexpr int PFE = 2;                  // record entries per lane that are fetched early (k <= 128: all)
+    // record entries per lane that are fetched early: all of them up to k = 256
+    constexpr int PFE = GPL == 8 ? SL_SELECT_PFE8 : 2;
     unsigned p_w[PFE], p_c[PFE];
+    // General route only (k > 256): a record of whole words that is a multiple of eight entries is
+    // staged in LDS and decoded eight entries per lane, instead of entry by entry from global memory.
+    constexpr int PW = GPL == 0 ? 8 : 1;
+    unsigned pw[PW];
+    const bool pwords = GPL == 0 && pend && A.pend_words;
+    const int rec_words = (TWO_BIT ? 7 * k / 4 : A.rec_bytes) >> 2;
+    unsigned *stg = nullptr;
     // The bytes of the value field of entry m: the code's byte window, or the fp32 value.
     auto value_window = [&](int m) -> unsigned {
         if (bits == 32) return reinterpret_cast<const unsigned *>(pcodes)[m];
@@ -239,75 +246,115 @@ __global__ void SL_SELECT_BOUNDS k_select(SelectArgs A)
         return w;
     };
     if (pend) {
-        bm = reinterpret_cast<unsigned *>(smem + A.pend_off);
-        pre = bm + BM_WORDS;
-        ql = reinterpret_cast<float *>(pre + BM_WORDS);
-        lutl = ql + k;
-        tm = reinterpret_cast<unsigned *>(lutl + 16);
-        tq = reinterpret_cast<float *>(tm + 128);
+        corr = reinterpret_cast<float *>(smem + A.pend_off);
+        lutl = corr + SL_CHUNK / 2;
         prec = A.pending + d.rec_off;
         pcodes = prec + 3 * k / 2;
         const unsigned char *lutg =
             A.pending + (TWO_BIT ? sl_lut_off(d, 16, 7 * k / 4) : sl_lut_off(d, A.hdr_bytes, A.rec_bytes));
         if (bits == 2) plut = *reinterpret_cast<const float4 *>(lutg);
         else if (bits != 32 && lane < (1 << bits)) p_lutv = reinterpret_cast<const float *>(lutg)[lane];
+        if (pwords) {
+            // large records (general route): the first 2 KB as whole words, coalesced
+            stg = reinterpret_cast<unsigned *>(lutl + 16);
 #pragma unroll
-        for (int u = 0; u < PFE; ++u) {
-            const int m = lane + 64 * u;
-            p_w[u] = p_c[u] = 0;
-            if (m < k) {
-                const int b0 = (3 * m) >> 1;
-                p_w[u] = (unsigned)prec[b0] | ((unsigned)prec[b0 + 1] << 8);
-                p_c[u] = value_window(m);
+            for (int u = 0; u < PW; ++u) {
+                const int w = lane + 64 * u;
+                pw[u] = w < rec_words ? reinterpret_cast<const unsigned *>(prec)[w] : 0u;
+            }
+        } else {
+#pragma unroll
+            for (int u = 0; u < PFE; ++u) {
+                const int m = lane + 64 * u;
+                p_w[u] = p_c[u] = 0;
+                if (m < k) {
+                    const int b0 = (3 * m) >> 1;
+                    p_w[u] = (unsigned)prec[b0] | ((unsigned)prec[b0 + 1] << 8);
+                    p_c[u] = value_window(m);
+                }
             }
         }
     }
-    // Builds the tables; called once the chunk's bulk loads are in flight so that
-    // the small record loads above and this LDS work hide behind them.
-    auto pend_build = [&]() {
-        reinterpret_cast<uint2 *>(bm)[lane] = make_uint2(0u, 0u);
-        reinterpret_cast<uint2 *>(tm)[lane] = make_uint2(0u, 0u);
-        if (bits != 2 && bits != 32 && lane < (1 << bits)) lutl[lane] = p_lutv;
-        sl_wave_sync();
-        auto entry = [&](int m, unsigned w, unsigned vw) {
-            const unsigned j = (m & 1) ? (w >> 4) : (w & 0xFFFu);
-            float q;
-            if (bits == 2) {
-                const unsigned code = (vw >> (2 * (m & 3))) & 3u;
-                q = code == 0 ? plut.x : code == 1 ? plut.y : code == 2 ? plut.z : plut.w;
-            } else if (bits == 32) {
-                q = __uint_as_float(vw);
-            } else {
-                q = lutl[(vw >> ((m * bits) & 7)) & ((1u << bits) - 1u)];
+    // The pending values of half h of the chunk (local indices h*2048 ..) as a dense array
+    // in LDS, +0.0f where nothing is pending: the error update is then e - corr, position by
+    // position (x - (+0.0f) leaves every x as it is, signed zeros included), with one 16-byte LDS
+    // read per 16-byte access of e and no look-ups.  A record's positions are distinct, so its
+    // entries are plain stores.  Called with the chunk's bulk loads in flight.
+    auto pend_half = [&](int h) __attribute__((always_inline)) {
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+            reinterpret_cast<float4 *>(corr)[64 * u + lane] = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (h == 0) {
+            if (bits != 2 && bits != 32 && lane < (1 << bits)) lutl[lane] = p_lutv;
+            if constexpr (GPL == 0) {
+                if (pwords) {
+#pragma unroll
+                    for (int u = 0; u < PW; ++u) {
+                        const int w = lane + 64 * u;
+                        if (w < rec_words) stg[w] = pw[u];
+                    }
+                    for (int w = lane + 64 * PW; w < rec_words; w += 64)       // k > 1024
+                        stg[w] = reinterpret_cast<const unsigned *>(prec)[w];
+                }
             }
-            ql[m] = q;
-            atomicOr(&bm[j >> 5], 1u << (j & 31u));
-            // lane-major copy: position j = 256*i + 4*l + cc is bit 4*i + cc of lane l's 64 bits,
-            // i.e. one nibble per 16-byte access of that lane
-            atomicOr(&tm[2u * ((j >> 2) & 63u) + (j >> 11)], 1u << (((j >> 6) & 28u) + (j & 3u)));
-            // ... and the value where that lane finds it with one conflict-free read.  Two entries
-            // in one 16-byte access overwrite each other here: such an access takes the ranked path.
-            tq[((j >> 8) << 6) + ((j >> 2) & 63u)] = q;
+        }
+        sl_wave_sync();
+        auto put = [&](unsigned j, float q) {
+            if ((int)(j >> 11) == h) corr[j & (SL_CHUNK / 2 - 1)] = q;
         };
+        const float pl0 = plut.x, pl1 = plut.y, pl2 = plut.z, pl3 = plut.w;
+        auto value_of = [&](unsigned field) -> float {       // field: the entry's code in the low bits
+            if (bits == 2) {      // two selects on the code's bits, on four scalars: selects between the
+                                  // elements of a vector become an indexed read of a copy in private memory
+                const float lo = (field & 1u) ? pl1 : pl0, hi = (field & 1u) ? pl3 : pl2;
+                return (field & 2u) ? hi : lo;
+            }
+            return lutl[field & ((1u << bits) - 1u)];
+        };
+        if (pwords) {
+            if constexpr (GPL == 0) {
+                const unsigned char *scodes = reinterpret_cast<const unsigned char *>(stg) + 3 * k / 2;
+                for (int o = lane; o < (k >> 3); o += 64) {
+                    // entries 8o .. 8o+7: three words of indices, `bits` bytes of codes
+                    const unsigned w0 = stg[3 * o], w1 = stg[3 * o + 1], w2 = stg[3 * o + 2];
+                    unsigned cw = 0;
+                    if (bits != 32)
+                        for (int b = 0; b < bits; ++b) cw |= (unsigned)scodes[o * bits + b] << (8 * b);
+                    // (written out entry by entry: an array of the eight indices ends up in private memory)
+                    auto put_e = [&](int e, unsigned j) __attribute__((always_inline)) {
+                        put(j, bits == 32 ? reinterpret_cast<const float *>(scodes)[8 * o + e]
+                                          : value_of(cw >> (e * bits)));
+                    };
+                    put_e(0, w0 & 0xFFFu);
+                    put_e(1, (w0 >> 12) & 0xFFFu);
+                    put_e(2, (w0 >> 24) | ((w1 & 0xFu) << 8));
+                    put_e(3, (w1 >> 4) & 0xFFFu);
+                    put_e(4, (w1 >> 16) & 0xFFFu);
+                    put_e(5, (w1 >> 28) | ((w2 & 0xFFu) << 4));
+                    put_e(6, (w2 >> 8) & 0xFFFu);
+                    put_e(7, w2 >> 20);
+                }
+            }
+        } else {
+            auto entry = [&](int m, unsigned w, unsigned vw) {
+                const unsigned j = (m & 1) ? (w >> 4) : (w & 0xFFFu);
+                put(j, bits == 32 ? __uint_as_float(vw) : value_of(vw >> ((m * bits) & 7)));
+            };
 #pragma unroll
-        for (int u = 0; u < PFE; ++u)
-            if (lane + 64 * u < k) entry(lane + 64 * u, p_w[u], p_c[u]);
-        for (int m = lane + 64 * PFE; m < k; m += 64) {
-            const int b0 = (3 * m) >> 1;
-            entry(m, (unsigned)prec[b0] | ((unsigned)prec[b0 + 1] << 8), value_window(m));
+            for (int u = 0; u < PFE; ++u)
+                if (lane + 64 * u < k) entry(lane + 64 * u, p_w[u], p_c[u]);
+            for (int m = lane + 64 * PFE; m < k; m += 64) {
+                const int b0 = (3 * m) >> 1;
+                entry(m, (unsigned)prec[b0] | ((unsigned)prec[b0 + 1] << 8), value_window(m));
+            }
         }
         sl_wave_sync();
-        const uint2 w2 = reinterpret_cast<const uint2 *>(bm)[lane];
-        const int c0 = __popc(w2.x), c1 = __popc(w2.y);
-        int incl = c0 + c1;
-#pragma unroll
-        for (int sft = 1; sft < 64; sft <<= 1) {
-            const int up = __shfl_up(incl, sft);
-            if (lane >= sft) incl += up;
-        }
-        const int excl = incl - (c0 + c1);
-        reinterpret_cast<uint2 *>(pre)[lane] = make_uint2((unsigned)excl, (unsigned)(excl + c0));
-        sl_wave_sync();
+    };
+    // e - corr for 16-byte access i of this lane (local indices 256*i + 4*lane ..)
+    auto pend_sub = [&](sl_f4 ee, int i) -> sl_f4 {
+        const float4 cq = reinterpret_cast<const float4 *>(corr)[64 * (i & 7) + lane];
+        ee.x = ee.x - cq.x, ee.y = ee.y - cq.y, ee.z = ee.z - cq.z, ee.w = ee.w - cq.w;
+        return ee;
     };
 
     if (full) {
@@ -324,7 +371,6 @@ __global__ void SL_SELECT_BOUNDS k_select(SelectArgs A)
             // accesses per lane and stream each), finished one after the other, so that
             // only a quarter of each stream sits in registers next to the result.
             const float *lc_ = A.theta_local + d.base;
-            const unsigned sh = 4u * (lane & 7);
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
                 sl_f4 dq[4], tq[4], eq[4];
@@ -336,7 +382,7 @@ __global__ void SL_SELECT_BOUNDS k_select(SelectArgs A)
 #pragma unroll
                     for (int u = 0; u < 4; ++u) eq[u] = sl_load_stream_at(ec, (4 * q + u) * step, o0);
                 }
-                if (q == 0 && pend) pend_build();
+                if (pend && (q & 1) == 0) pend_half(q >> 1);
 #pragma unroll
                 for (int u = 0; u < 4; ++u) {
                     const int i = 4 * q + u;
@@ -344,17 +390,7 @@ __global__ void SL_SELECT_BOUNDS k_select(SelectArgs A)
                     sl_f4 v = g;
                     if (!A.frozen) {
                         sl_f4 ee = eq[u];
-                        if (pend) {
-                            const unsigned word = bm[8 * i + (lane >> 3)];
-                            const unsigned nib = (word >> sh) & 0xFu;
-                            if (nib) {
-                                int rk = (int)pre[8 * i + (lane >> 3)] + __popc(word & ((1u << sh) - 1u));
-                                if (nib & 1u) ee.x = ee.x - ql[rk++];
-                                if (nib & 2u) ee.y = ee.y - ql[rk++];
-                                if (nib & 4u) ee.z = ee.z - ql[rk++];
-                                if (nib & 8u) ee.w = ee.w - ql[rk++];
-                            }
-                        }
+                        if (pend) ee = pend_sub(ee, i);
                         v.x = fmaf(A.beta, ee.x, g.x);
                         v.y = fmaf(A.beta, ee.y, g.y);
                         v.z = fmaf(A.beta, ee.z, g.z);
@@ -373,43 +409,17 @@ __global__ void SL_SELECT_BOUNDS k_select(SelectArgs A)
 #pragma unroll
             for (int i = 0; i < 16; ++i) dv[i] = sl_load_stream_at(dc, i * step, o0);
         }
-        if (!SUBK && !PARAMS && pend) {
-            pend_build();
-            // e_true = e - (dequantised pending value) at this lane's positions.  Which of them
-            // are pending comes from the lane-major map (two registers); the value of a 16-byte
-            // access with one pending position comes from the lane-major value table: sixteen
-            // independent reads, no branches.  An access with two or more pending positions
-            // (rare) goes to the position-ordered map for the ranks of its entries:
-            // local index 256*i + 4*lane + cc is bit 4*(lane%8) + cc of word 8*i + lane/8.
-            const uint2 t2 = reinterpret_cast<const uint2 *>(tm)[lane];
-            const unsigned long long mine = ((unsigned long long)t2.y << 32) | t2.x;
-            const unsigned sh = 4u * (lane & 7);
-#pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                const unsigned nib = (unsigned)(mine >> (4 * i)) & 0xFu;
-                const float q = tq[64 * i + lane];          // meaningful only where nib != 0
-                if (nib & (nib - 1u)) {
-                    const unsigned word = bm[8 * i + (lane >> 3)];
-                    int rk = (int)pre[8 * i + (lane >> 3)] + __popc(word & ((1u << sh) - 1u));
-                    if (nib & 1u) ev[i].x = ev[i].x - ql[rk++];
-                    if (nib & 2u) ev[i].y = ev[i].y - ql[rk++];
-                    if (nib & 4u) ev[i].z = ev[i].z - ql[rk++];
-                    if (nib & 8u) ev[i].w = ev[i].w - ql[rk++];
-                } else {
-                    // x - (+0.0f) leaves every x as it is, signed zeros included
-                    ev[i].x = ev[i].x - ((nib & 1u) ? q : 0.0f);
-                    ev[i].y = ev[i].y - ((nib & 2u) ? q : 0.0f);
-                    ev[i].z = ev[i].z - ((nib & 4u) ? q : 0.0f);
-                    ev[i].w = ev[i].w - ((nib & 8u) ? q : 0.0f);
-                }
-            }
-        }
+        if (!SUBK && !PARAMS && pend) pend_half(0);   // (half 1 follows inside the loop below, once half 0 is used up)
 #pragma unroll
         for (int i = 0; i < (PARAMS ? 0 : 16); ++i) {
             sl_f4 v;
             if constexpr (SUBK) {
                 v = ev[i];
             } else if (!A.frozen) {
+                if (pend) {
+                    if (i == 8) pend_half(1);
+                    ev[i] = pend_sub(ev[i], i);
+                }
                 v.x = fmaf(A.beta, ev[i].x, dv[i].x);
                 v.y = fmaf(A.beta, ev[i].y, dv[i].y);
                 v.z = fmaf(A.beta, ev[i].z, dv[i].z);
@@ -531,9 +541,11 @@ __global__ void SL_SELECT_BOUNDS k_select(SelectArgs A)
         // A lane whose four columns of a row all lie inside the tensor still moves them
         // with one 16-byte access; a lane that straddles the edge goes element by element.
         const int rows = d.rows, cols = d.cols, last_cols = d.last_cols;
-        if (!SUBK && pend) pend_build();
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
+            if constexpr (!SUBK) {
+                if (pend && (i & 7) == 0) pend_half(i >> 3);
+            }
             const int row = 4 * i + lr;
             const int lim = row < rows - 1 ? cols : (row == rows - 1 ? last_cols : 0);
             const bool all = lc + 3 < lim;
@@ -569,12 +581,7 @@ __global__ void SL_SELECT_BOUNDS k_select(SelectArgs A)
                         v = ein[cc];
                     } else if (!A.frozen) {
                         float ee = ein[cc];
-                        if (pend) {
-                            const unsigned w = 8 * i + (lane >> 3), bit = 4u * (lane & 7) + cc;
-                            const unsigned word = bm[w];
-                            if ((word >> bit) & 1u)
-                                ee = ee - ql[(int)pre[w] + __popc(word & ((1u << bit) - 1u))];
-                        }
+                        if (pend) ee = ee - corr[256 * (i & 7) + 4 * lane + cc];
                         v = fmaf(A.beta, ee, din[cc]);
                     } else {
                         v = din[cc];
@@ -717,9 +724,15 @@ static int launch_select(const sl_plan *p, float *e, const float *delta, const f
         b += (6 * (size_t)k + 7) & ~(size_t)7;
         b += 64 * sizeof(double);
         b = (b + 15) & ~(size_t)15;
-        A.pend_off = (int)b;
-        if (pending) b += 2 * BM_WORDS * sizeof(unsigned) + 4 * (size_t)k + 16 * sizeof(float) + 64 * sizeof(uint2) +
-                         16 * 64 * sizeof(float);
+        // general route: a pending record of whole words and whole groups of eight entries is staged in LDS
+        A.pend_words = pending && !pruned && (p->rec_bytes & 3) == 0 && (k & 7) == 0 && p->rec_bytes <= 8192;
+        // the pending tables are dead before the selection starts: they share its LDS
+        A.pend_off = 0;
+        if (pending) {
+            const size_t pb = (SL_CHUNK / 2) * sizeof(float) + 16 * sizeof(float) +
+                              (A.pend_words ? (size_t)p->rec_bytes : 0);
+            if (b < pb) b = pb;
+        }
         A.lds_per_wave = (int)((b + 15) & ~(size_t)15);
     }
     A.vals = sub_only ? nullptr : reinterpret_cast<float *>(ws + p->ws_vals);

@@ -91,10 +91,27 @@ def test_ef_frozen(sl, oracle, bits):
 @pytest.mark.parametrize("bits", (1, 3, 4, 32))
 @pytest.mark.parametrize("k", [8, 64, 128, 512])
 def test_deferred_residual_chain(sl, oracle, bits, k):
+    run_deferred_chain(sl, oracle, bits, k)
+
+
+# Large records reach the accumulate kernel through LDS as whole words (k a multiple of 8, record a
+# multiple of 4 bytes, at most 8 KB); 264, 520 and 1032 fall outside that at some widths, 2048 and
+# 4096 are more than the words fetched ahead, and fp32 values at k = 2048 are too large to stage.
+@pytest.mark.parametrize("bits", WIDTHS)
+@pytest.mark.parametrize("k", [256, 264, 520, 1024, 1032, 2048, 4096])
+def test_deferred_residual_chain_high_density(sl, oracle, bits, k):
+    run_deferred_chain(sl, oracle, bits, k)
+
+
+def run_deferred_chain(sl, oracle, bits, k):
     if k <= 256:
         shapes = [(150, 210, TILE), (1, 9000, FLAT), (1024, 16, TILE), (128, 192, TILE), (1, 4096 + 1030, FLAT)]
-    else:
+    elif k <= 1000:
         shapes = [(160, 224, TILE), (1024, 16, TILE), (1, 8192 + 1000, FLAT)]
+    elif k <= 2048:
+        shapes = [(128, 192, TILE), (1, 8192 + 2100, FLAT)]
+    else:
+        shapes = [(128, 128, TILE), (1, 8192, FLAT)]
     descs, n = layout_list(shapes)
     rng = np.random.default_rng(1200 + 10 * k + bits)
     plan = sl.sl_plan_create_bits(descs, k, bits)
