@@ -523,8 +523,11 @@ int slk_apply(const sl_plan *p, float *theta, float *mom, float mu, const void *
         A.payload[r] = r < R ? static_cast<const unsigned char *>(payloads[r]) : nullptr;
     A.n_chunks = p->n_chunks;
     // (not when the staged records themselves are the larger part of the LDS: nothing would be gained)
+    // (and not on the eight-entry route below k = 512, where half the lanes of a pass are idle and
+    // the number of passes, which two halves double, is what the time goes into)
+    const bool octets = p->k >= SL_APPLY_OCTETS_FROM && (p->k & 7) == 0;
     const bool halves = (long long)R * p->k >= SL_APPLY_HALVES_FROM && (size_t)batch * rec_pad <= 8192 &&
-                        p->k <= SL_APPLY_HALVES_TO;
+                        p->k <= SL_APPLY_HALVES_TO && !(octets && p->k < 512);
     const size_t acc_bytes = SL_CHUNK * sizeof(float) / (halves ? 2 : 1);
     A.lds_per_wave = (int)((acc_bytes + (size_t)batch * rec_pad + 15) & ~(size_t)15);
     int wpb = 4;
@@ -532,7 +535,6 @@ int slk_apply(const sl_plan *p, float *theta, float *mom, float mu, const void *
     const size_t lds = (size_t)A.lds_per_wave * wpb;
     const bool two = p->bits == 2;
     typedef void (*kernel_t)(ApplyArgs);
-    const bool octets = p->k >= SL_APPLY_OCTETS_FROM && (p->k & 7) == 0;
     const int route = (!halves && p->k <= 128) ? 0 : !octets ? 1 : (size_t)batch * rec_pad <= 4096 ? 2 : 3;
 #define SL_APPLY_ROUTES(TWO, NEST)                                                                       \
     {k_apply<TWO, NEST, 1, 0>, k_apply<TWO, NEST, 1, 1>, k_apply<TWO, NEST, 1, 2>, k_apply<TWO, NEST, 1, 3>, \

@@ -25,7 +25,7 @@
 //   3. T is bisected over that short list, and a second compaction over the
 //      list emits the selected entries, still in ascending local index; ties
 //      at T go to the lowest indices.
-// Partial chunks, a candidate list that overflows (massive ties) and k > 256
+// Partial chunks, a candidate list that overflows (massive ties) and k > 512
 // take the general route: T bisected over the registers directly and one
 // ordered compaction over the registers - slower, same result.
 #include "sl_device.h"
@@ -33,8 +33,8 @@
 
 namespace {
 
-constexpr int CAND_CAP = 512;             // LDS candidate list, entries of 8 bytes
-constexpr int CAND_SLOTS = CAND_CAP / 64;
+// LDS candidate list of the pruned route, entries of 8 bytes: 512, or 1024 with 16 groups per lane
+constexpr int cand_cap(int gpl) { return gpl == 16 ? 1024 : 512; }
 
 #ifndef SL_SELECT_PFE8
 #define SL_SELECT_PFE8 4
@@ -203,6 +203,7 @@ __global__ void SL_SELECT_BOUNDS k_select(SelectArgs A)
 
     // LDS of this wave: [candidates 8*CAND_CAP][sel_val 4k][sel_idx 2k][tree scratch 512]
     uint2 *cand = reinterpret_cast<uint2 *>(smem);
+    constexpr int CAND_CAP = cand_cap(GPL), CAND_SLOTS = CAND_CAP / 64;
     const size_t cand_bytes = GPL > 0 ? sizeof(uint2) * CAND_CAP : 0;
     float *sel_val = reinterpret_cast<float *>(smem + cand_bytes);
     unsigned short *sel_idx = reinterpret_cast<unsigned short *>(smem + cand_bytes + 4 * (size_t)k);
@@ -230,11 +231,12 @@ __global__ void SL_SELECT_BOUNDS k_select(SelectArgs A)
     // record entries per lane that are fetched early: all of them up to k = 256
     constexpr int PFE = GPL == 8 ? SL_SELECT_PFE8 : 2;
     unsigned p_w[PFE], p_c[PFE];
-    // General route only (k > 256): a record of whole words that is a multiple of eight entries is
+    // k > 256 only: a record of whole words that is a multiple of eight entries is
     // staged in LDS and decoded eight entries per lane, instead of entry by entry from global memory.
-    constexpr int PW = GPL == 0 ? 8 : 1;
+    constexpr bool BIG = GPL == 0 || GPL == 16;     // the instantiations that serve k > 256
+    constexpr int PW = BIG ? 8 : 1;
     unsigned pw[PW];
-    const bool pwords = GPL == 0 && pend && A.pend_words;
+    const bool pwords = BIG && pend && A.pend_words;
     const int rec_words = (TWO_BIT ? 7 * k / 4 : A.rec_bytes) >> 2;
     unsigned *stg = nullptr;
     // The bytes of the value field of entry m: the code's byte window, or the fp32 value.
@@ -286,7 +288,7 @@ __global__ void SL_SELECT_BOUNDS k_select(SelectArgs A)
             reinterpret_cast<float4 *>(corr)[64 * u + lane] = make_float4(0.f, 0.f, 0.f, 0.f);
         if (h == 0) {
             if (bits != 2 && bits != 32 && lane < (1 << bits)) lutl[lane] = p_lutv;
-            if constexpr (GPL == 0) {
+            if constexpr (BIG) {
                 if (pwords) {
 #pragma unroll
                     for (int u = 0; u < PW; ++u) {
@@ -312,7 +314,7 @@ __global__ void SL_SELECT_BOUNDS k_select(SelectArgs A)
             return lutl[field & ((1u << bits) - 1u)];
         };
         if (pwords) {
-            if constexpr (GPL == 0) {
+            if constexpr (BIG) {
                 const unsigned char *scodes = reinterpret_cast<const unsigned char *>(stg) + 3 * k / 2;
                 for (int o = lane; o < (k >> 3); o += 64) {
                     // entries 8o .. 8o+7: three words of indices, `bits` bytes of codes
@@ -705,7 +707,7 @@ static int launch_select(const sl_plan *p, float *e, const float *delta, const f
 {
     if (p->n_chunks == 0) return SL_OK;
     const int k = p->k;
-    const bool pruned = k <= 256;
+    const bool pruned = k <= 512;
     SelectArgs A;
     A.desc = p->d_desc;
     A.e = e;
@@ -720,12 +722,12 @@ static int launch_select(const sl_plan *p, float *e, const float *delta, const f
     A.rec_bytes = p->rec_bytes;
     A.seed_hash = host_fmix32(seed);
     {
-        size_t b = pruned ? sizeof(uint2) * CAND_CAP : 0;
+        size_t b = pruned ? sizeof(uint2) * cand_cap(k > 256 ? 16 : 8) : 0;
         b += (6 * (size_t)k + 7) & ~(size_t)7;
         b += 64 * sizeof(double);
         b = (b + 15) & ~(size_t)15;
-        // general route: a pending record of whole words and whole groups of eight entries is staged in LDS
-        A.pend_words = pending && !pruned && (p->rec_bytes & 3) == 0 && (k & 7) == 0 && p->rec_bytes <= 8192;
+        // k > 256: a pending record of whole words and whole groups of eight entries is staged in LDS
+        A.pend_words = pending && k > 256 && (p->rec_bytes & 3) == 0 && (k & 7) == 0 && p->rec_bytes <= 8192;
         // the pending tables are dead before the selection starts: they share its LDS
         A.pend_off = 0;
         if (pending) {
@@ -749,6 +751,7 @@ static int launch_select(const sl_plan *p, float *e, const float *delta, const f
         else if (k <= 64) hipLaunchKernelGGL((k_select<2, MODE, TWO>), grid, block, lds, st, A);    \
         else if (k <= 128) hipLaunchKernelGGL((k_select<4, MODE, TWO>), grid, block, lds, st, A);   \
         else if (k <= 256) hipLaunchKernelGGL((k_select<8, MODE, TWO>), grid, block, lds, st, A);   \
+        else if (k <= 512) hipLaunchKernelGGL((k_select<16, MODE, TWO>), grid, block, lds, st, A);  \
         else hipLaunchKernelGGL((k_select<0, MODE, TWO>), grid, block, lds, st, A);                 \
     } while (0)
     const bool two = p->bits == 2;

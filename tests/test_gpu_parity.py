@@ -93,7 +93,7 @@ def test_compress_dense_case_k_4096(sl, oracle):
     check_compress(sl, oracle, descs, n, 4096, e0, delta, 0.95, what="dense")
 
 
-@pytest.mark.parametrize("k", [32, 64, 128])
+@pytest.mark.parametrize("k", [32, 64, 128, 256, 320, 512, 640])
 def test_compress_ties_zeros_and_heavy_tails(sl, oracle, k):
     """Degenerate inputs: all-zero tensors (all ties), few distinct magnitudes, signed
     zeros, denormals, a heavy-tailed tensor, a tensor with one hot column."""
