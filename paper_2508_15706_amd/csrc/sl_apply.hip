@@ -475,6 +475,84 @@ k_pack_bits(const uint16_t *idx, const uint8_t *codes, const float *values, long
     }
 }
 
+// Record encoder, one thread per 32-bit word of the output: for records that are whole words
+// with the code stream starting on a word (k a multiple of 8, record a multiple of 4 bytes) and
+// 4-byte aligned `out` (and `codes` at 2 bits).  Same bytes as the byte-wise kernels above.
+SL_DEV void pack_word(const uint16_t *idx, const uint8_t *codes, const float *values, int k, int bits, int wpr,
+                      long long c0, int lw, unsigned magic, unsigned *out)
+{
+    const int cl = (int)__umulhi((unsigned)lw, magic);
+    const long long c = c0 + cl;
+    const int w = lw - cl * wpr, niw = 3 * k / 8;
+    const uint16_t *ic = idx + c * k;
+    unsigned v = 0;
+    if (w < niw) {
+        // the (up to four) 12-bit fields that overlap bits 32w .. 32w+31 of the index stream
+        const int bit0 = 32 * w;
+        int m = bit0 / 12;
+#pragma unroll
+        for (int q = 0; q < 4; ++q, ++m) {
+            const int sh = 12 * m - bit0;
+            if (m < k && sh < 32) {
+                const unsigned x = (unsigned)ic[m] & 0xFFFu;
+                v |= sh >= 0 ? x << sh : x >> (-sh);
+            }
+        }
+    } else if (bits == 32) {
+        v = __float_as_uint(values[c * k + (w - niw)]);
+    } else if (bits == 2) {
+        // sixteen codes, one per byte, from four aligned words
+        const unsigned *cw = reinterpret_cast<const unsigned *>(codes + c * k) + 4 * (w - niw);
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const unsigned x = cw[q];
+            v |= ((x & 3u) | ((x >> 6) & 0xCu) | ((x >> 12) & 0x30u) | ((x >> 18) & 0xC0u)) << (8 * q);
+        }
+    } else {
+        const int bit0 = 32 * (w - niw);
+        const unsigned mask = (1u << bits) - 1u;
+        const uint8_t *cc = codes + c * k;
+        for (int m = bit0 / bits; m < k && m * bits < bit0 + 32; ++m) {
+            const int sh = m * bits - bit0;
+            const unsigned cde = (unsigned)cc[m] & mask;
+            v |= sh >= 0 ? cde << sh : cde >> (-sh);
+        }
+    }
+    out[c0 * wpr + lw] = v;
+}
+
+__global__ void __launch_bounds__(256)
+k_pack_words(const uint16_t *idx, const uint8_t *codes, const float *values, long long n_chunks, int k, int bits,
+             int wpr, int cpb, unsigned magic, unsigned *out)
+{
+    // a block encodes `cpb` consecutive chunks: their records are one run of cpb*wpr words, and a
+    // word's chunk within the run is a multiplication away (magic = floor(2^32/wpr) + 1, exact
+    // while word * wpr < 2^32)
+    const long long c0 = (long long)blockIdx.x * cpb;
+    const int nloc = (int)min((long long)cpb, n_chunks - c0) * wpr;
+    for (int lw = threadIdx.x; lw < nloc; lw += blockDim.x)
+        pack_word(idx, codes, values, k, bits, wpr, c0, lw, magic, out);
+}
+
+
+// The word-wise encoder serves the call if the record layout and the pointers allow it.
+bool pack_words(const uint16_t *idx, const uint8_t *codes, const float *values, int64_t n_chunks, int k, int bits,
+                unsigned char *out, hipStream_t st)
+{
+    const long long rec = sl_rec_bytes(k, bits);
+    if ((k & 7) || (rec & 3) || ((uintptr_t)out & 3)) return false;
+    if (bits == 2 && (((uintptr_t)codes & 3) || (k & 15))) return false;
+    const int wpr = (int)(rec >> 2);
+    int cpb = 4096 / wpr;                                     // about 16 words per thread
+    cpb = cpb < 1 ? 1 : cpb > 64 ? 64 : cpb;
+    const long long blocks = (n_chunks + cpb - 1) / cpb;
+    if (blocks > 0x7FFFFFFFll) return false;                  // beyond one grid: the grid-stride kernel
+    hipLaunchKernelGGL(k_pack_words, dim3((unsigned)blocks), dim3(256), 0, st, idx, codes, values,
+                       (long long)n_chunks, k, bits, wpr, cpb, (unsigned)(0x100000000ull / (unsigned)wpr + 1),
+                       reinterpret_cast<unsigned *>(out));
+    return true;
+}
+
 }  // namespace
 
 int slk_pack_bits(const uint16_t *idx, const uint8_t *codes, const float *values, int64_t n_chunks, int k,
@@ -484,7 +562,8 @@ int slk_pack_bits(const uint16_t *idx, const uint8_t *codes, const float *values
     if (total == 0) return SL_OK;
     long long blocks = (total + 255) / 256;
     if (blocks > 65536) blocks = 65536;
-    hipLaunchKernelGGL(k_pack_bits, dim3((unsigned)blocks), dim3(256), 0, st, idx, codes, values,
+    if (!pack_words(idx, codes, values, n_chunks, k, bits, out, st))
+        hipLaunchKernelGGL(k_pack_bits, dim3((unsigned)blocks), dim3(256), 0, st, idx, codes, values,
                        (long long)n_chunks, k, bits, out);
     hipError_t err = hipGetLastError();
     if (err != hipSuccess) {
@@ -586,7 +665,8 @@ int slk_pack(const uint16_t *idx, const uint8_t *codes, int64_t n_chunks, int k,
     if (total == 0) return SL_OK;
     long long blocks = (total + 255) / 256;
     if (blocks > 65536) blocks = 65536;
-    hipLaunchKernelGGL(k_pack, dim3((unsigned)blocks), dim3(256), 0, st, idx, codes,
+    if (!pack_words(idx, codes, nullptr, n_chunks, k, 2, out, st))
+        hipLaunchKernelGGL(k_pack, dim3((unsigned)blocks), dim3(256), 0, st, idx, codes,
                        (long long)n_chunks, k, out);
     hipError_t err = hipGetLastError();
     if (err != hipSuccess) {

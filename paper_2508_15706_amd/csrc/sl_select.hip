@@ -234,7 +234,7 @@ __global__ void SL_SELECT_BOUNDS k_select(SelectArgs A)
     // k > 256 only: a record of whole words that is a multiple of eight entries is
     // staged in LDS and decoded eight entries per lane, instead of entry by entry from global memory.
     constexpr bool BIG = GPL == 0 || GPL == 16;     // the instantiations that serve k > 256
-    constexpr int PW = BIG ? 8 : 1;
+    constexpr int PW = GPL == 16 ? 4 : BIG ? 8 : 1;   // words per lane fetched early: 1 KB (k <= 512), 2 KB
     unsigned pw[PW];
     const bool pwords = BIG && pend && A.pend_words;
     const int rec_words = (TWO_BIT ? 7 * k / 4 : A.rec_bytes) >> 2;
@@ -295,7 +295,7 @@ __global__ void SL_SELECT_BOUNDS k_select(SelectArgs A)
                         const int w = lane + 64 * u;
                         if (w < rec_words) stg[w] = pw[u];
                     }
-                    for (int w = lane + 64 * PW; w < rec_words; w += 64)       // k > 1024
+                    for (int w = lane + 64 * PW; w < rec_words; w += 64)       // beyond the early words
                         stg[w] = reinterpret_cast<const unsigned *>(prec)[w];
                 }
             }

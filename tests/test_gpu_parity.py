@@ -305,17 +305,27 @@ def test_config1_three_rounds_four_workers(sl, oracle):
 
 
 # --------------------------------------------------------------------------- record encoder
-@pytest.mark.parametrize("k", [4, 32, 64, 100, 4096])
-def test_pack_indices(sl, oracle, k):
+@pytest.mark.parametrize("shift", [0, 1, 2])
+@pytest.mark.parametrize("k", [4, 16, 32, 48, 64, 100, 264, 1040, 4096])
+def test_pack_indices(sl, oracle, k, shift):
+    """Records of whole words take a word-wise encoder, the rest (and buffers that are not 4-byte
+    aligned: shift != 0) a byte-wise one; the bytes are the same."""
     rng = np.random.default_rng(400 + k)
     nc = 37
     idx = np.stack([np.sort(rng.choice(4096, k, replace=False)) for _ in range(nc)]).astype(np.uint16)
     code = rng.integers(0, 4, (nc, k)).astype(np.uint8)
-    out = torch.full((nc * 7 * k // 4,), 0xCD, dtype=torch.uint8, device="cuda")
+    rec = 7 * k // 4
+    buf = torch.full((nc * rec + 16,), 0xCD, dtype=torch.uint8, device="cuda")
+    out = buf[shift:shift + nc * rec]
+    code_buf = torch.zeros(nc * k + 16, dtype=torch.uint8, device="cuda")
+    code_dev = code_buf[shift:shift + nc * k]
+    code_dev.copy_(torch.from_numpy(code.ravel()).cuda())
     idx_dev = torch.from_numpy(idx.view(np.int16)).cuda().view(torch.uint16)
-    sl.sl_pack_indices(idx_dev, torch.from_numpy(code).cuda(), nc, k, out)
+    sl.sl_pack_indices(idx_dev, code_dev, nc, k, out)
     torch.cuda.synchronize()
     assert np.array_equal(out.cpu().numpy(), oracle.pack_indices(idx.ravel(), code.ravel(), nc, k))
+    host = buf.cpu().numpy()
+    assert (host[:shift] == 0xCD).all() and (host[shift + nc * rec:] == 0xCD).all()   # nothing written outside
 
 
 # --------------------------------------------------------------------------- argument errors
