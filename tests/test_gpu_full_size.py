@@ -154,6 +154,16 @@ def test_config3_510M_k_sweep_full_list(sl, oracle, k):
     run_config(sl, oracle, 3, k, 1, {"l0.q", "l3.gate", "l7.norm1", "l23.down", "final_norm"})
 
 
+@pytest.mark.timeout(600)
+@pytest.mark.parametrize("k", [256, 512, 1024])
+def test_config3_510M_high_densities(sl, oracle, k):
+    """Configuration 3 at densities of 6.25, 12.5 and 25 % (the upper part of the paper's density
+    sweep): two rounds on a sample of whole tensors, all 8 workers - the 16-group pruning, the
+    unpruned selection, the word-staged pending record and the eight-entry decode of the
+    aggregate at full size."""
+    run_config(sl, oracle, 3, k, 2, {"l0.q", "l3.gate", "l7.norm1", "l23.down", "final_norm"}, full_first=False)
+
+
 @pytest.mark.timeout(900)
 def test_config3_510M_five_rounds(sl, oracle):
     """Configuration 3, k = 64: five consecutive rounds carrying the error buffers."""
