@@ -30,6 +30,9 @@ namespace {
 #ifndef SL_APPLY_HALVES_TO
 #define SL_APPLY_HALVES_TO 512     // largest k that is still aggregated in two halves (measured)
 #endif
+#ifndef SL_APPLY_PF1
+#define SL_APPLY_PF1 16     // words per lane fetched ahead of the theta loads on the entry-by-entry route (2-bit codes)
+#endif
 #ifndef SL_APPLY_STAGE_U
 #define SL_APPLY_STAGE_U 8    // words per lane loaded together while records are staged
 #endif
@@ -135,8 +138,9 @@ __global__ void __launch_bounds__(256) k_apply(ApplyArgs A)
     // R = 8 up to k = 128, R = 16 up to k = 64) are fetched into registers BEFORE the
     // theta loads: loads complete in order, so the decode below then waits for these
     // few words only and runs while the chunk's 16 KB of theta are still in flight.
-    // (wider records at other widths: 3 KB; the eight-entry route exists for large records: 8 KB)
-    constexpr int PF = ROUTE == 3 ? 32 : ROUTE == 2 ? 16 : TWO_BIT ? 8 : 12;
+    // (wider records at other widths: 3 KB; many workers at small k, the entry-by-entry route: 4 KB;
+    // the eight-entry route exists for large records: 4 or 8 KB)
+    constexpr int PF = ROUTE == 3 ? 32 : ROUTE == 2 ? 16 : !TWO_BIT ? 12 : ROUTE == 1 ? SL_APPLY_PF1 : 8;
     unsigned pf[PF];
     const int nb0 = min(A.batch, A.R);
     if (word_path) {
@@ -180,7 +184,7 @@ __global__ void __launch_bounds__(256) k_apply(ApplyArgs A)
                         wb = 64 * PF;
                     }
                     // the rest: SU words per lane are loaded before the first of them is parked in LDS
-                    constexpr int SU = OCTETS ? SL_APPLY_STAGE_U : 1;   // (small k: little or nothing is left)
+                    constexpr int SU = SMALLK ? 1 : SL_APPLY_STAGE_U;   // (small k: little or nothing is left)
                     for (; wb < nw; wb += 64 * SU) {
                         unsigned v[SU];
 #pragma unroll
