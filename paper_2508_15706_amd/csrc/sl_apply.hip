@@ -14,21 +14,18 @@
 
 namespace {
 
-// When there is much to decode per chunk (R*k entries), the chunk is aggregated
-// in NH = 2 halves of 32 rows (local indices below / from 2048): 8 KB of
+// When there is much to decode per chunk (R*k entries) at small k, the chunk is
+// aggregated in NH = 2 halves of 32 rows (local indices below / from 2048): 8 KB of
 // accumulators per wave instead of 16, so that more waves - and more bytes of
 // theta in flight - fit a compute unit while the decode runs.  With little to
-// decode one pass (NH = 1) is faster; so it is when one record alone is large
-// (k > 512), where the halves would have to stage every record twice.
+// decode, and from k = 256 (cheaper decode, records staged 4 KB at a time), one
+// pass (NH = 1) is faster.
 #ifndef SL_APPLY_HALVES_FROM
 #define SL_APPLY_HALVES_FROM 1536   // R*k from which two halves pay (measured)
 #endif
 
 #ifndef SL_APPLY_OCTETS_FROM
 #define SL_APPLY_OCTETS_FROM 256   // k from which a lane decodes eight entries at a time
-#endif
-#ifndef SL_APPLY_HALVES_TO
-#define SL_APPLY_HALVES_TO 512     // largest k that is still aggregated in two halves (measured)
 #endif
 #ifndef SL_APPLY_PF1
 #define SL_APPLY_PF1 16     // words per lane fetched ahead of the theta loads on the entry-by-entry route (2-bit codes)
@@ -37,7 +34,7 @@ namespace {
 #define SL_APPLY_STAGE_U 8    // words per lane loaded together while records are staged
 #endif
 #ifndef SL_APPLY_BIG_STAGE
-#define SL_APPLY_BIG_STAGE 4096   // staging bytes when one record is larger than 1 KB
+#define SL_APPLY_BIG_STAGE 4096   // staging bytes on the eight-entry route, and when one record is larger than 1 KB
 #endif
 
 // pointers into global memory, for addresses that are put together from integers
@@ -75,15 +72,13 @@ struct ApplyArgs {
 // ROUTE: how a staged record's entries reach the accumulators.
 //   0 (k <= 128, one pass): the entries of several workers are decoded ahead of the additions;
 //   1: entry by entry, one worker at a time;
-//   2, 3 (k >= 256, a multiple of 8): a lane decodes eight consecutive entries from whole words;
-//      up to 4 KB (2) or 8 KB (3) of records are fetched ahead of the theta loads - the
-//      smaller kernel leaves registers for a third wave per SIMD.
+//   2 (k >= 256, a multiple of 8): a lane decodes eight consecutive entries from whole words.
 // The routes are separate instantiations, so that none pays for another's registers.
 template <bool TWO_BIT, bool NESTEROV, int NH, int ROUTE>
 __global__ void __launch_bounds__(256) k_apply(ApplyArgs A)
 {
-    constexpr bool SMALLK = ROUTE == 0, OCTETS = ROUTE >= 2;
-    static_assert(!SMALLK || NH == 1, "the small-k route makes one pass over the chunk");
+    constexpr bool SMALLK = ROUTE == 0, OCTETS = ROUTE == 2;
+    static_assert(ROUTE == 1 || NH == 1, "two halves go entry by entry");
     constexpr int ACC_FLOATS = SL_CHUNK / NH, ROWS4 = 16 / NH;   // accumulators, 16-byte accesses per lane
     extern __shared__ __align__(16) unsigned char smem_all[];
     const int lane = threadIdx.x & 63, k = A.k;
@@ -138,9 +133,9 @@ __global__ void __launch_bounds__(256) k_apply(ApplyArgs A)
     // R = 8 up to k = 128, R = 16 up to k = 64) are fetched into registers BEFORE the
     // theta loads: loads complete in order, so the decode below then waits for these
     // few words only and runs while the chunk's 16 KB of theta are still in flight.
-    // (wider records at other widths: 3 KB; many workers at small k, the entry-by-entry route: 4 KB;
-    // the eight-entry route exists for large records: 4 or 8 KB)
-    constexpr int PF = ROUTE == 3 ? 32 : ROUTE == 2 ? 16 : !TWO_BIT ? 12 : ROUTE == 1 ? SL_APPLY_PF1 : 8;
+    // (wider records at other widths: 3 KB; many workers at small k, the entry-by-entry route, and
+    // the eight-entry route: 4 KB, which is all that is staged at a time there)
+    constexpr int PF = ROUTE == 2 ? 16 : !TWO_BIT ? 12 : ROUTE == 1 ? SL_APPLY_PF1 : 8;
     unsigned pf[PF];
     const int nb0 = min(A.batch, A.R);
     if (word_path) {
@@ -594,9 +589,10 @@ int slk_apply(const sl_plan *p, float *theta, float *mom, float mu, const void *
     A.hdr_bytes = p->hdr_bytes;
     A.rec_bytes = p->rec_bytes;
     const int rec_pad = ((p->rec_bytes + 3) & ~3) + p->hdr_bytes;
-    // at most 16 KB of staged records; 4 KB when a record alone is large (k >= 1024), so that the
-    // accumulators are not crowded out of the LDS
-    int batch = (rec_pad > 1024 ? SL_APPLY_BIG_STAGE : 16384) / rec_pad;
+    // at most 16 KB of staged records; 4 KB on the eight-entry route (measured against 2, 8 and 16 KB:
+    // more waves per compute unit outweigh the extra staging rounds), and whenever a record alone is large
+    const bool octets = p->k >= SL_APPLY_OCTETS_FROM && (p->k & 7) == 0;
+    int batch = (rec_pad > 1024 || octets ? SL_APPLY_BIG_STAGE : 16384) / rec_pad;
     if (batch < 1) batch = 1;
     if (batch > R) batch = R;
     A.batch = batch;
@@ -606,11 +602,8 @@ int slk_apply(const sl_plan *p, float *theta, float *mom, float mu, const void *
         A.payload[r] = r < R ? static_cast<const unsigned char *>(payloads[r]) : nullptr;
     A.n_chunks = p->n_chunks;
     // (not when the staged records themselves are the larger part of the LDS: nothing would be gained)
-    // (and not on the eight-entry route below k = 512, where half the lanes of a pass are idle and
-    // the number of passes, which two halves double, is what the time goes into)
-    const bool octets = p->k >= SL_APPLY_OCTETS_FROM && (p->k & 7) == 0;
-    const bool halves = (long long)R * p->k >= SL_APPLY_HALVES_FROM && (size_t)batch * rec_pad <= 8192 &&
-                        p->k <= SL_APPLY_HALVES_TO && !(octets && p->k < 512);
+    // (not on the eight-entry route: with 4 KB staged at a time the halves would fetch every record twice)
+    const bool halves = (long long)R * p->k >= SL_APPLY_HALVES_FROM && (size_t)batch * rec_pad <= 8192 && !octets;
     const size_t acc_bytes = SL_CHUNK * sizeof(float) / (halves ? 2 : 1);
     A.lds_per_wave = (int)((acc_bytes + (size_t)batch * rec_pad + 15) & ~(size_t)15);
     int wpb = 4;
@@ -618,14 +611,13 @@ int slk_apply(const sl_plan *p, float *theta, float *mom, float mu, const void *
     const size_t lds = (size_t)A.lds_per_wave * wpb;
     const bool two = p->bits == 2;
     typedef void (*kernel_t)(ApplyArgs);
-    const int route = (!halves && p->k <= 128) ? 0 : !octets ? 1 : (size_t)batch * rec_pad <= 4096 ? 2 : 3;
-#define SL_APPLY_ROUTES(TWO, NEST)                                                                       \
-    {k_apply<TWO, NEST, 1, 0>, k_apply<TWO, NEST, 1, 1>, k_apply<TWO, NEST, 1, 2>, k_apply<TWO, NEST, 1, 3>, \
-     nullptr, k_apply<TWO, NEST, 2, 1>, k_apply<TWO, NEST, 2, 2>, k_apply<TWO, NEST, 2, 3>}
-    static const kernel_t table[2][2][8] = {{SL_APPLY_ROUTES(false, false), SL_APPLY_ROUTES(false, true)},
+    const int route = (!halves && p->k <= 128) ? 0 : !octets ? 1 : 2;
+#define SL_APPLY_ROUTES(TWO, NEST) \
+    {k_apply<TWO, NEST, 1, 0>, k_apply<TWO, NEST, 1, 1>, k_apply<TWO, NEST, 1, 2>, k_apply<TWO, NEST, 2, 1>}
+    static const kernel_t table[2][2][4] = {{SL_APPLY_ROUTES(false, false), SL_APPLY_ROUTES(false, true)},
                                             {SL_APPLY_ROUTES(true, false), SL_APPLY_ROUTES(true, true)}};
 #undef SL_APPLY_ROUTES
-    const kernel_t fn = table[two ? 1 : 0][mom ? 1 : 0][halves ? 4 + route : route];
+    const kernel_t fn = table[two ? 1 : 0][mom ? 1 : 0][halves ? 3 : route];   // (two halves: entry by entry only)
     if (lds > 65536) {
         hipError_t aerr = hipFuncSetAttribute(reinterpret_cast<const void *>(fn),
                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
