@@ -34,16 +34,55 @@ int sl_rice_param(int k)
 
 namespace {
 
-// Sequential reader of bit fields from a byte- or word-addressed stream.
-template <bool WORDS>
+// Sequential reader of bit fields from a byte- or word-addressed stream.  A lane reads its
+// stream alone, so every load is a round trip to memory that nothing else of the lane hides: with
+// AHEAD the word reader runs two 16-byte blocks ahead of the bits it hands out (never past `limit`;
+// what lies beyond reads as zeros).  This pays for the coded stream (decode at configuration 4:
+// 0.44 -> 0.33 ms), not for the plain records the encoder reads.
+typedef unsigned sl_u4u __attribute__((ext_vector_type(4), aligned(4)));
+template <bool WORDS, bool AHEAD = false>
 struct BitReader {
-    const unsigned char *p, *end;
+    const unsigned char *p, *end;            // p: the next byte (word, block) to load
     unsigned long long acc = 0;
     int n = 0;
-    SL_DEV BitReader(const unsigned char *start, const unsigned char *limit) : p(start), end(limit) {}
+    unsigned long long c0 = 0, c1 = 0, n0 = 0, n1 = 0;   // AHEAD: current and next block of four words
+    int left = 0;                                        // words of the current block not handed out yet
+    SL_DEV BitReader(const unsigned char *start, const unsigned char *limit) : p(start), end(limit)
+    {
+        if (AHEAD) {
+            load_block(c0, c1);
+            load_block(n0, n1);
+            left = 4;
+        }
+    }
+    SL_DEV void load_block(unsigned long long &a, unsigned long long &b)
+    {
+        unsigned w[4] = {0u, 0u, 0u, 0u};
+        if (p + 16 <= end) {
+            const sl_u4u v = *reinterpret_cast<const sl_u4u *>(p);
+            w[0] = v.x, w[1] = v.y, w[2] = v.z, w[3] = v.w;
+        } else {
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+                if (p + 4 * q + 4 <= end) w[q] = reinterpret_cast<const unsigned *>(p)[q];
+        }
+        a = (unsigned long long)w[0] | ((unsigned long long)w[1] << 32);
+        b = (unsigned long long)w[2] | ((unsigned long long)w[3] << 32);
+        p += 16;
+    }
     SL_DEV void refill()
     {
-        if (WORDS) {
+        if (AHEAD) {
+            const unsigned w = (unsigned)c0;
+            c0 = (c0 >> 32) | (c1 << 32);
+            c1 >>= 32;
+            if (--left == 0) {
+                c0 = n0, c1 = n1, left = 4;
+                load_block(n0, n1);
+            }
+            acc |= (unsigned long long)w << n;
+            n += 32;
+        } else if (WORDS) {
             const unsigned w = p + 4 <= end ? *reinterpret_cast<const unsigned *>(p) : 0u;
             acc |= (unsigned long long)w << n;
             p += 4, n += 32;
@@ -258,7 +297,7 @@ __global__ void __launch_bounds__(64) k_rice_decode(RiceArgs A, const unsigned c
     if (blk + hdr + 4ull * (g.local_group + 1) <= end)
         off = toff + reinterpret_cast<const unsigned *>(blk + hdr)[g.local_group];
     if (off > in_bytes) off = in_bytes;
-    BitReader<true> rd(in + (off & ~3ull), end);
+    BitReader<true, true> rd(in + (off & ~3ull), end);
     const long long c0 = (long long)g.local_group * SL_RICE_GROUP;
     const int nc = (int)min((long long)SL_RICE_GROUP, td.n_chunks - c0);
     for (int i = 0; i < nc; ++i) {
