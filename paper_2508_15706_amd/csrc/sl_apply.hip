@@ -4,11 +4,12 @@
 // sl_pack_indices (12-bit index fields + 2-bit codes).
 //
 // One wavefront owns one chunk.  The dense average never exists in HBM: the
-// chunk's fp32 accumulators live in LDS (one half of the chunk at a time, 8 KB),
-// the R records (7k/4 bytes each) are staged into LDS with coalesced loads, entries of one worker are
-// distinct positions so they are added without conflicts, workers are added in
-// the order r = 0..R-1, and theta streams through registers once
-// (8 bytes per element of HBM traffic plus R*7k/4 bytes per chunk).
+// chunk's fp32 accumulators live in LDS (16 KB, or one half of the chunk at a
+// time), the R records (7k/4 bytes each) are staged into LDS with coalesced
+// loads, entries of one worker are distinct positions so they are added without
+// conflicts, workers are added in the order r = 0..R-1, and theta streams
+// through registers once (8 bytes per element of HBM traffic plus R*7k/4 bytes
+// per chunk).
 #include "sl_device.h"
 #include "sl_internal.h"
 
@@ -64,8 +65,8 @@ struct ApplyArgs {
 };
 
 // One wave per chunk, several independent waves (adjacent chunks) per workgroup.
-// TWO_BIT: the 2-bit format with its four-entry table kept in registers;
-// otherwise any width (table of 2^bits entries read from LDS, or fp32 values).
+// TWO_BIT: the 2-bit format, its sizes compile-time constants; otherwise any
+// width (table of 2^bits entries, or fp32 values).
 // NESTEROV: DiLoCo's global outer momentum on top of the aggregate (Eq. (1);
 // appendix algorithm "Outer step for DiLoCo+Top-k[+EF]"): m <- mu*m + avg,
 // d <- avg + mu*m, theta <- theta - lr*d at every element of the chunk.
