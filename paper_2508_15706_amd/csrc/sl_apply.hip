@@ -154,6 +154,29 @@ __global__ void __launch_bounds__(256) k_apply(ApplyArgs A)
 #pragma unroll
             for (int i = 0; i < 16; ++i) mo[i] = sl_load_stream_at(mc, i * step, o0);
         }
+    } else {
+        // partial chunk: the same loads up front, 16 bytes where a lane's four columns lie inside
+        // the tensor (rows need no alignment), element by element at the edge, nothing outside
+        const int rows = d.rows, cols = d.cols, last_cols = d.last_cols;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            const int row = 4 * i + lr;
+            const int lim = row < rows - 1 ? cols : (row == rows - 1 ? last_cols : 0);
+            const unsigned o0 = row * stride + lc;
+            th[i] = sl_f4{0.f, 0.f, 0.f, 0.f};
+            if constexpr (NESTEROV) mo[i] = sl_f4{0.f, 0.f, 0.f, 0.f};
+            if (lc + 3 < lim) {
+                th[i] = sl_load_stream_u(tc + o0);
+                if constexpr (NESTEROV) mo[i] = sl_load_stream_u(mc + o0);
+            } else {
+#pragma unroll
+                for (int cc = 0; cc < 4; ++cc)
+                    if (lc + cc < lim) {
+                        th[i][cc] = tc[o0 + cc];
+                        if constexpr (NESTEROV) mo[i][cc] = mc[o0 + cc];
+                    }
+            }
+        }
     }
 
     const bool single = A.R <= A.batch;      // every record fits the staging area at once
@@ -344,40 +367,35 @@ __global__ void __launch_bounds__(256) k_apply(ApplyArgs A)
             }
         } else {
             const int rows = d.rows, cols = d.cols, last_cols = d.last_cols;
+#pragma unroll
             for (int i8 = 0; i8 < ROWS4; ++i8) {
-                const int row = 4 * (ROWS4 * h + i8) + lr;
+                const int i = ROWS4 * h + i8, row = 4 * i + lr;
                 const int lim = row < rows - 1 ? cols : (row == rows - 1 ? last_cols : 0);
                 const unsigned o0 = row * stride + lc;
+                const float4 a = reinterpret_cast<const float4 *>(acc)[i8 * 64 + lane];
+                sl_f4 g;
+                g.x = a.x * A.inv_R, g.y = a.y * A.inv_R, g.z = a.z * A.inv_R, g.w = a.w * A.inv_R;
+                sl_f4 m = sl_f4{0.f, 0.f, 0.f, 0.f};
+                if constexpr (NESTEROV) {
+                    m = mo[i];
+                    m.x = fmaf(A.mu, m.x, g.x), m.y = fmaf(A.mu, m.y, g.y);
+                    m.z = fmaf(A.mu, m.z, g.z), m.w = fmaf(A.mu, m.w, g.w);
+                    g.x = fmaf(A.mu, m.x, g.x), g.y = fmaf(A.mu, m.y, g.y);
+                    g.z = fmaf(A.mu, m.z, g.z), g.w = fmaf(A.mu, m.w, g.w);
+                }
+                sl_f4 v = th[i];
+                v.x = fmaf(A.neg_lr, g.x, v.x), v.y = fmaf(A.neg_lr, g.y, v.y);
+                v.z = fmaf(A.neg_lr, g.z, v.z), v.w = fmaf(A.neg_lr, g.w, v.w);
                 if (lc + 3 < lim) {
-                    // all four columns inside: one 16-byte access per stream (rows need no alignment)
-                    const float4 a = reinterpret_cast<const float4 *>(acc)[i8 * 64 + lane];
-                    sl_f4 g;
-                    g.x = a.x * A.inv_R, g.y = a.y * A.inv_R, g.z = a.z * A.inv_R, g.w = a.w * A.inv_R;
-                    if constexpr (NESTEROV) {
-                        sl_f4 m = sl_load_stream_u(mc + o0);
-                        m.x = fmaf(A.mu, m.x, g.x), m.y = fmaf(A.mu, m.y, g.y);
-                        m.z = fmaf(A.mu, m.z, g.z), m.w = fmaf(A.mu, m.w, g.w);
-                        sl_store_stream_u(mc + o0, m);
-                        g.x = fmaf(A.mu, m.x, g.x), g.y = fmaf(A.mu, m.y, g.y);
-                        g.z = fmaf(A.mu, m.z, g.z), g.w = fmaf(A.mu, m.w, g.w);
-                    }
-                    sl_f4 v = sl_load_stream_u(tc + o0);
-                    v.x = fmaf(A.neg_lr, g.x, v.x), v.y = fmaf(A.neg_lr, g.y, v.y);
-                    v.z = fmaf(A.neg_lr, g.z, v.z), v.w = fmaf(A.neg_lr, g.w, v.w);
+                    if constexpr (NESTEROV) sl_store_stream_u(mc + o0, m);
                     sl_store_stream_u(tc + o0, v);
                 } else {
-                    for (int cc = 0; cc < 4; ++cc) {
+#pragma unroll
+                    for (int cc = 0; cc < 4; ++cc)
                         if (lc + cc < lim) {
-                            const unsigned o = o0 + cc;
-                            float g = acc[256 * i8 + 4 * lane + cc] * A.inv_R;
-                            if constexpr (NESTEROV) {
-                                const float m = fmaf(A.mu, mc[o], g);
-                                mc[o] = m;
-                                g = fmaf(A.mu, m, g);
-                            }
-                            tc[o] = fmaf(A.neg_lr, g, tc[o]);
+                            if constexpr (NESTEROV) mc[o0 + cc] = m[cc];
+                            tc[o0 + cc] = v[cc];
                         }
-                    }
                 }
             }
         }

@@ -433,111 +433,6 @@ __global__ void SL_SELECT_BOUNDS k_select(SelectArgs A)
             a[4 * i + 0] = v.x, a[4 * i + 1] = v.y, a[4 * i + 2] = v.z, a[4 * i + 3] = v.w;
         }
 
-        if constexpr (GPL > 0) {
-            constexpr int G = GPL;
-            // group g of a lane = its registers r with r % G == g
-            int gm[G];
-#pragma unroll
-            for (int g = 0; g < G; ++g) {
-                int m = key_of(a[g]);
-#pragma unroll
-                for (int r = g + G; r < 64; r += G) m = max(m, key_of(a[r]));
-                gm[g] = m;
-            }
-            int lmin = gm[0], lmax = gm[0];
-#pragma unroll
-            for (int g = 1; g < G; ++g) lmin = min(lmin, gm[g]), lmax = max(lmax, gm[g]);
-            const int hi = sl_wave_max(lmax);               // largest key of the chunk
-            const int lo = sl_wave_min(lmin);
-            // L = k-th largest group maximum: a lower bound of T, because k
-            // distinct elements are >= L (64*G >= k groups, all non-empty here)
-            const int L = bisect_kth(lo, hi, k, [&](int x) {
-                int n = 0;
-#pragma unroll
-                for (int g = 0; g < G; ++g) n += sl_popc(sl_ballot(gm[g] >= x));
-                return n;
-            });
-            // ordered compaction of the entries with key >= L
-            int ncand = 0;
-#pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                bool f[4];
-                int pos = ncand, cnt = 0;
-                unsigned long long any = 0;
-#pragma unroll
-                for (int cc = 0; cc < 4; ++cc) {
-                    f[cc] = key_of(a[4 * i + cc]) >= L;
-                    const unsigned long long m = sl_ballot(f[cc]);
-                    pos += sl_mbcnt(m);
-                    cnt += sl_popc(m);
-                    any |= m;
-                }
-                if (any) {
-#pragma unroll
-                    for (int cc = 0; cc < 4; ++cc) {
-                        if (f[cc]) {
-                            if (pos < CAND_CAP)
-                                cand[pos] = make_uint2(__float_as_uint(a[4 * i + cc]),
-                                                       (unsigned)(256 * i + 4 * lane + cc));
-                            ++pos;
-                        }
-                    }
-                }
-                ncand += cnt;
-            }
-            sl_wave_sync();
-            if (ncand <= CAND_CAP) {
-                const int nslots = (ncand + 63) >> 6;
-                int ck[CAND_SLOTS];
-#pragma unroll
-                for (int s = 0; s < CAND_SLOTS; ++s) {
-                    const int p = s * 64 + lane;
-                    ck[s] = (s < nslots && p < ncand) ? (int)(cand[p].x & 0x7FFFFFFFu) : -1;
-                }
-                auto count_cand = [&](int x) {
-                    int n = 0;
-#pragma unroll
-                    for (int s = 0; s < CAND_SLOTS; ++s)
-                        if (s < nslots) n += sl_popc(sl_ballot(ck[s] >= x));
-                    return n;
-                };
-                const int T = bisect_kth(L, hi, k, count_cand);
-                const int n_ge = count_cand(T);
-                const bool ties = n_ge != k;
-                int need = 0;
-                if (ties) {
-                    int n_gt = 0;
-#pragma unroll
-                    for (int s = 0; s < CAND_SLOTS; ++s)
-                        if (s < nslots) n_gt += sl_popc(sl_ballot(ck[s] > T));
-                    need = k - n_gt;
-                }
-                int base = 0, tbase = 0;
-#pragma unroll
-                for (int s = 0; s < CAND_SLOTS; ++s) {
-                    if (s < nslots) {
-                        bool f;
-                        if (!ties) {
-                            f = ck[s] >= T;
-                        } else {
-                            const bool eq = ck[s] == T;
-                            const unsigned long long me = sl_ballot(eq);
-                            f = ck[s] > T || (eq && tbase + sl_mbcnt(me) < need);
-                            tbase += sl_popc(me);
-                        }
-                        const unsigned long long m = sl_ballot(f);
-                        const int pos = base + sl_mbcnt(m);
-                        if (f && pos < k) {
-                            const uint2 v = cand[s * 64 + lane];
-                            sel_val[pos] = __uint_as_float(v.x);
-                            sel_idx[pos] = (unsigned short)v.y;
-                        }
-                        base += sl_popc(m);
-                    }
-                }
-                done = true;
-            }
-        }
     } else {
         // ------------------------------------------------------------ partial chunk
         // A lane whose four columns of a row all lie inside the tensor still moves them
@@ -603,6 +498,116 @@ __global__ void SL_SELECT_BOUNDS k_select(SelectArgs A)
                         if (lc + cc < lim) ec[o0 + cc] = vout[cc];
                 }
             }
+        }
+    }
+
+    // Pruned selection.  A partial chunk takes it too: its positions outside the tensor hold 0.0f,
+    // i.e. key 0, and can only enter the candidate list if the bound L is 0 - then the list
+    // overflows (it would hold all 4096 positions) and the general route, which knows the
+    // outside positions, takes over.
+    if constexpr (GPL > 0) {
+        constexpr int G = GPL;
+        // group g of a lane = its registers r with r % G == g
+        int gm[G];
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+            int m = key_of(a[g]);
+#pragma unroll
+            for (int r = g + G; r < 64; r += G) m = max(m, key_of(a[r]));
+            gm[g] = m;
+        }
+        int lmin = gm[0], lmax = gm[0];
+#pragma unroll
+        for (int g = 1; g < G; ++g) lmin = min(lmin, gm[g]), lmax = max(lmax, gm[g]);
+        const int hi = sl_wave_max(lmax);               // largest key of the chunk
+        const int lo = sl_wave_min(lmin);
+        // L = k-th largest group maximum: a lower bound of T, because k
+        // distinct elements are >= L (64*G >= k groups, all non-empty here)
+        const int L = bisect_kth(lo, hi, k, [&](int x) {
+            int n = 0;
+#pragma unroll
+            for (int g = 0; g < G; ++g) n += sl_popc(sl_ballot(gm[g] >= x));
+            return n;
+        });
+        // ordered compaction of the entries with key >= L
+        int ncand = 0;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            bool f[4];
+            int pos = ncand, cnt = 0;
+            unsigned long long any = 0;
+#pragma unroll
+            for (int cc = 0; cc < 4; ++cc) {
+                f[cc] = key_of(a[4 * i + cc]) >= L;
+                const unsigned long long m = sl_ballot(f[cc]);
+                pos += sl_mbcnt(m);
+                cnt += sl_popc(m);
+                any |= m;
+            }
+            if (any) {
+#pragma unroll
+                for (int cc = 0; cc < 4; ++cc) {
+                    if (f[cc]) {
+                        if (pos < CAND_CAP)
+                            cand[pos] = make_uint2(__float_as_uint(a[4 * i + cc]),
+                                                   (unsigned)(256 * i + 4 * lane + cc));
+                        ++pos;
+                    }
+                }
+            }
+            ncand += cnt;
+        }
+        sl_wave_sync();
+        if (ncand <= CAND_CAP && (full || L > 0)) {
+            const int nslots = (ncand + 63) >> 6;
+            int ck[CAND_SLOTS];
+#pragma unroll
+            for (int s = 0; s < CAND_SLOTS; ++s) {
+                const int p = s * 64 + lane;
+                ck[s] = (s < nslots && p < ncand) ? (int)(cand[p].x & 0x7FFFFFFFu) : -1;
+            }
+            auto count_cand = [&](int x) {
+                int n = 0;
+#pragma unroll
+                for (int s = 0; s < CAND_SLOTS; ++s)
+                    if (s < nslots) n += sl_popc(sl_ballot(ck[s] >= x));
+                return n;
+            };
+            const int T = bisect_kth(L, hi, k, count_cand);
+            const int n_ge = count_cand(T);
+            const bool ties = n_ge != k;
+            int need = 0;
+            if (ties) {
+                int n_gt = 0;
+#pragma unroll
+                for (int s = 0; s < CAND_SLOTS; ++s)
+                    if (s < nslots) n_gt += sl_popc(sl_ballot(ck[s] > T));
+                need = k - n_gt;
+            }
+            int base = 0, tbase = 0;
+#pragma unroll
+            for (int s = 0; s < CAND_SLOTS; ++s) {
+                if (s < nslots) {
+                    bool f;
+                    if (!ties) {
+                        f = ck[s] >= T;
+                    } else {
+                        const bool eq = ck[s] == T;
+                        const unsigned long long me = sl_ballot(eq);
+                        f = ck[s] > T || (eq && tbase + sl_mbcnt(me) < need);
+                        tbase += sl_popc(me);
+                    }
+                    const unsigned long long m = sl_ballot(f);
+                    const int pos = base + sl_mbcnt(m);
+                    if (f && pos < k) {
+                        const uint2 v = cand[s * 64 + lane];
+                        sel_val[pos] = __uint_as_float(v.x);
+                        sel_idx[pos] = (unsigned short)v.y;
+                    }
+                    base += sl_popc(m);
+                }
+            }
+            done = true;
         }
     }
 
