@@ -437,65 +437,74 @@ __global__ void SL_SELECT_BOUNDS k_select(SelectArgs A)
         // ------------------------------------------------------------ partial chunk
         // A lane whose four columns of a row all lie inside the tensor still moves them
         // with one 16-byte access; a lane that straddles the edge goes element by element.
+        // As for a full chunk, every load is issued before the first result is needed.
         const int rows = d.rows, cols = d.cols, last_cols = d.last_cols;
-#pragma unroll
-        for (int i = 0; i < 16; ++i) {
-            if constexpr (!SUBK) {
-                if (pend && (i & 7) == 0) pend_half(i >> 3);
-            }
+        const bool need_e = SUBK || !A.frozen;
+        auto limit_of = [&](int i) -> int {            // columns of this lane's row 4*i + lr that exist
             const int row = 4 * i + lr;
-            const int lim = row < rows - 1 ? cols : (row == rows - 1 ? last_cols : 0);
-            const bool all = lc + 3 < lim;
-            const unsigned o0 = row * stride + lc;
-            const bool need_e = SUBK || !A.frozen;
-            float ein[4] = {0.f, 0.f, 0.f, 0.f}, din[4] = {0.f, 0.f, 0.f, 0.f};
-            if (all) {
-                if (need_e) {
-                    const sl_f4 E = sl_load_stream_u(ec + o0);
-                    ein[0] = E.x, ein[1] = E.y, ein[2] = E.z, ein[3] = E.w;
+            return row < rows - 1 ? cols : (row == rows - 1 ? last_cols : 0);
+        };
+        // (in two halves of 32 rows, as much as the registers hold next to the results)
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            sl_f4 pe[8], pd[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int i = 8 * h + u, lim = limit_of(i);
+                const unsigned o0 = (4 * i + lr) * stride + lc;
+                pe[u] = pd[u] = sl_f4{0.f, 0.f, 0.f, 0.f};
+                if (lc + 3 < lim) {
+                    if (need_e) pe[u] = sl_load_stream_u(ec + o0);
+                    if constexpr (!SUBK) {
+                        pd[u] = sl_load_stream_u(dc + o0);
+                        if constexpr (PARAMS) pd[u] = pd[u] - sl_load_stream_u(A.theta_local + d.base + o0);
+                    }
+                } else {
+#pragma unroll
+                    for (int cc = 0; cc < 4; ++cc) {
+                        if (lc + cc < lim) {
+                            if (need_e) pe[u][cc] = ec[o0 + cc];
+                            if constexpr (!SUBK)
+                                pd[u][cc] = PARAMS ? dc[o0 + cc] - (A.theta_local + d.base)[o0 + cc] : dc[o0 + cc];
+                        }
+                    }
                 }
-                if constexpr (!SUBK) {
-                    sl_f4 D = sl_load_stream_u(dc + o0);
-                    if constexpr (PARAMS) D = D - sl_load_stream_u(A.theta_local + d.base + o0);
-                    din[0] = D.x, din[1] = D.y, din[2] = D.z, din[3] = D.w;
-                }
-            } else {
+            }
+            if constexpr (!SUBK) {
+                if (pend) pend_half(h);
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int i = 8 * h + u, lim = limit_of(i);
+                const unsigned o0 = (4 * i + lr) * stride + lc;
+                sl_f4 vout;
 #pragma unroll
                 for (int cc = 0; cc < 4; ++cc) {
+                    float v = 0.0f;
                     if (lc + cc < lim) {
-                        if (need_e) ein[cc] = ec[o0 + cc];
-                        if constexpr (!SUBK)
-                            din[cc] = PARAMS ? dc[o0 + cc] - (A.theta_local + d.base)[o0 + cc] : dc[o0 + cc];
-                    }
-                }
-            }
-            float vout[4];
-#pragma unroll
-            for (int cc = 0; cc < 4; ++cc) {
-                float v = 0.0f;
-                if (lc + cc < lim) {
-                    if constexpr (SUBK) {
-                        v = ein[cc];
-                    } else if (!A.frozen) {
-                        float ee = ein[cc];
-                        if (pend) ee = ee - corr[256 * (i & 7) + 4 * lane + cc];
-                        v = fmaf(A.beta, ee, din[cc]);
+                        if constexpr (SUBK) {
+                            v = pe[u][cc];
+                        } else if (!A.frozen) {
+                            float ee = pe[u][cc];
+                            if (pend) ee = ee - corr[256 * u + 4 * lane + cc];
+                            v = fmaf(A.beta, ee, pd[u][cc]);
+                        } else {
+                            v = pd[u][cc];
+                        }
                     } else {
-                        v = din[cc];
+                        inside &= ~(1ull << (4 * i + cc));
                     }
-                } else {
-                    inside &= ~(1ull << (4 * i + cc));
+                    vout[cc] = v;
+                    a[4 * i + cc] = v;
                 }
-                vout[cc] = v;
-                a[4 * i + cc] = v;
-            }
-            if (!SUBK && !A.frozen) {
-                if (all) {
-                    sl_store_stream_u(ec + o0, sl_f4{vout[0], vout[1], vout[2], vout[3]});
-                } else {
+                if (!SUBK && !A.frozen) {
+                    if (lc + 3 < lim) {
+                        sl_store_stream_u(ec + o0, vout);
+                    } else {
 #pragma unroll
-                    for (int cc = 0; cc < 4; ++cc)
-                        if (lc + cc < lim) ec[o0 + cc] = vout[cc];
+                        for (int cc = 0; cc < 4; ++cc)
+                            if (lc + cc < lim) ec[o0 + cc] = vout[cc];
+                    }
                 }
             }
         }
