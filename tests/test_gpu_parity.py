@@ -252,6 +252,33 @@ def test_apply_matches_oracle(sl, oracle, R, k, lr):
     assert_f32_close(theta.cpu().numpy(), want, f"theta R={R}")
 
 
+@pytest.mark.parametrize("k", [16, 32, 64, 128, 256])
+def test_apply_every_worker_count_boundary(sl, oracle, k):
+    """The aggregate fetches the first words of the records ahead of theta, stages the rest in rounds,
+    and switches its decode route and the number of passes with R*k: worker counts on both sides of
+    those switches (and the largest, 64), each checked against the oracle on the same payloads."""
+    shapes = [(150, 210, TILE), (1, 9000, FLAT), (128, 128, TILE)]
+    descs, n = layout_list(shapes)
+    rng = np.random.default_rng(3300 + k)
+    plan = sl.sl_plan_create(descs, k)
+    dev, host = [], []
+    for r in range(64):
+        delta = (1e-3 * rng.standard_t(3, n)).astype(np.float32)
+        _, pay_host, pay_dev = gpu_compress(sl, plan, np.zeros(n, dtype=np.float32), delta, 0.95)
+        ref = oracle.compress(descs, k, np.zeros(n, dtype=np.float32), delta, 0.95)
+        assert np.array_equal(pay_host, ref)
+        dev.append(pay_dev)
+        host.append(ref)
+    theta0 = rng.normal(0, 0.02, n).astype(np.float32)
+    for R in (1, 2, 5, 8, 9, 11, 12, 13, 16, 17, 23, 24, 25, 31, 32, 33, 47, 48, 49, 63, 64):
+        theta = torch.from_numpy(theta0).cuda()
+        sl.sl_decompress_avg_apply(plan, theta, dev[:R], 0.9)
+        torch.cuda.synchronize()
+        want = theta0.copy()
+        oracle.decompress_avg_apply(descs, k, want, host[:R], 0.9)
+        assert_f32_close(theta.cpu().numpy(), want, f"theta k={k} R={R}")
+
+
 def test_apply_order_of_workers_is_r_ascending(sl, oracle):
     """Hand-made payloads: the fp32 sum at one coordinate depends on the order."""
     descs = [(1, 4096, 0, FLAT)]
