@@ -3,6 +3,8 @@
 gaps between tensors), random k, value width, worker count, EF decay and mode (eager,
 deferred chain, frozen, Random-k, pseudo-gradient from parameters).  Every case is valid
 input; payload bytes must be bit-exact, e and theta bit-identical or within 1e-6."""
+import os
+
 import numpy as np
 import pytest
 import torch
@@ -49,17 +51,22 @@ def random_list(rng, k):
     return descs, off + 8
 
 
-@pytest.mark.parametrize("case", range(160))
+# SL_FUZZ_CASES / SL_FUZZ_SEED: more cases, other seeds (the defaults are what the suite runs)
+N_CASES = int(os.environ.get("SL_FUZZ_CASES", "200"))
+SEED0 = int(os.environ.get("SL_FUZZ_SEED", "7000"))
+
+
+@pytest.mark.parametrize("case", range(N_CASES))
 def test_random_configuration(sl, oracle, case):
-    rng = np.random.default_rng(7000 + case)
+    rng = np.random.default_rng(SEED0 + case)
     bits = int(rng.choice([1, 2, 2, 2, 3, 4, 32]))
-    k = int(rng.choice([4, 8, 12, 16, 32, 40, 64, 100, 128, 256, 320, 1024]))
+    k = int(rng.choice([4, 8, 12, 16, 32, 40, 64, 100, 128, 256, 320, 512, 520, 1024, 2048]))
     if bits != 2:
         k = max(8, k // 8 * 8)
     descs, n = [], 0
     while not descs:
         descs, n = random_list(rng, k)
-    R = int(rng.choice([1, 2, 3, 4, 8, 13]))
+    R = int(rng.choice([1, 2, 3, 4, 8, 13, 16, 33]))
     beta = float(rng.choice([0.0, 0.9, 0.95, 1.0]))
     lr = float(rng.choice([0.5, 0.7, 1.0]))
     mode = str(rng.choice(["eager", "deferred", "frozen", "random", "params"]))
