@@ -117,11 +117,12 @@ def summarize(d, arena_bytes):
 def render(summary, bench_args, title):
     s = summary
     lines = [f"# {title}", "",
-             "Commands (each from /tmp with TMPDIR=/tmp, repository at $R):", "",
-             f"    rocprofv3 --kernel-trace --stats --output-format csv -d $R/gpurun_out/prof/trace -o t -- python3 $R/bench.py {bench_args}",
-             f"    rocprofv3 --pmc FETCH_SIZE --output-format csv -d $R/gpurun_out/prof/fetch -o f -- python3 $R/bench.py {bench_args}",
-             f"    rocprofv3 --pmc WRITE_SIZE --output-format csv -d $R/gpurun_out/prof/write -o w -- python3 $R/bench.py {bench_args}",
-             f"    python3 -m paper_2508_15706_amd.rocprof_summary $R/gpurun_out/prof <arena bytes> <this file>", "",
+             "Commands (each from /tmp with TMPDIR=/tmp; repository at $R, profiler output under $OUT):", "",
+             f"    rocprofv3 --kernel-trace --stats --output-format csv -d $OUT/trace -o t -- python3 $R/bench.py {bench_args}",
+             f"    rocprofv3 --pmc FETCH_SIZE --output-format csv -d $OUT/fetch -o f -- python3 $R/bench.py {bench_args}",
+             f"    rocprofv3 --pmc WRITE_SIZE --output-format csv -d $OUT/write -o w -- python3 $R/bench.py {bench_args}",
+             f"    python3 -m paper_2508_15706_amd.rocprof_summary $OUT <arena bytes> <this file>", "",
+             "(The two counter runs may take fewer steps, e.g. --steps 2 --warmup 1: the counters are read per dispatch.)", "",
              "Counter scaling: the whole-arena device copy bench.py performs (`__amd_rocclr_copyBuffer`, "
              f"{s['copy_known_KiB']:.0f} KiB read and written) reads FETCH_SIZE = {s['copy_fetch_KiB']:.1f} KiB "
              f"(scale {s['fetch_scale']:.4f}) and WRITE_SIZE = {s['copy_write_KiB']:.1f} KiB "
