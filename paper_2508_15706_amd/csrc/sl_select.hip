@@ -36,6 +36,9 @@ namespace {
 // LDS candidate list of the pruned route, entries of 8 bytes: 512, or 1024 with 16 groups per lane
 constexpr int cand_cap(int gpl) { return gpl == 16 ? 1024 : 512; }
 
+#ifndef SL_SELECT_BOUND_BITS
+#define SL_SELECT_BOUND_BITS 12   // bits of the pruning bound that are decided (0 = all)
+#endif
 #ifndef SL_SELECT_PFE8
 #define SL_SELECT_PFE8 4
 #endif
@@ -80,13 +83,17 @@ SL_DEV unsigned fmix32(unsigned h)
 
 // Largest T in [lo, hi] with count_ge(T) >= k, given count_ge(lo) >= k and
 // 0 <= lo <= hi.  All values are wave-uniform.
+// With `steps` > 0 only that many bits below the highest one in which lo and hi differ are
+// decided and the rest left zero: a value that is not above the exact answer and still has
+// count_ge >= k.
 template <class CountGE>
-SL_DEV int bisect_kth(int lo, int hi, int k, CountGE count_ge)
+SL_DEV int bisect_kth(int lo, int hi, int k, CountGE count_ge, int steps = 0)
 {
     if (lo >= hi) return lo;
     const int top = 31 - __clz(lo ^ hi);
+    const int last = steps > 0 ? max(0, top - steps + 1) : 0;
     int T = hi & ~(int)((2u << top) - 1u);
-    for (int b = top; b >= 0; --b) {
+    for (int b = top; b >= last; --b) {
         const int cand = T | (1 << b);
         if (count_ge(cand) >= k) T = cand;
     }
@@ -530,14 +537,16 @@ __global__ void SL_SELECT_BOUNDS k_select(SelectArgs A)
         for (int g = 1; g < G; ++g) lmin = min(lmin, gm[g]), lmax = max(lmax, gm[g]);
         const int hi = sl_wave_max(lmax);               // largest key of the chunk
         const int lo = sl_wave_min(lmin);
-        // L = k-th largest group maximum: a lower bound of T, because k
-        // distinct elements are >= L (64*G >= k groups, all non-empty here)
+        // L = k-th largest group maximum, or a little less: a lower bound of T, because k
+        // distinct elements are >= L (64*G >= k groups).  A bound is all that is needed, so
+        // only its leading bits are decided - a slightly longer candidate list for half the
+        // counting passes.
         const int L = bisect_kth(lo, hi, k, [&](int x) {
             int n = 0;
 #pragma unroll
             for (int g = 0; g < G; ++g) n += sl_popc(sl_ballot(gm[g] >= x));
             return n;
-        });
+        }, SL_SELECT_BOUND_BITS);
         // ordered compaction of the entries with key >= L
         int ncand = 0;
 #pragma unroll
