@@ -243,7 +243,11 @@ int sl_payload_validate(sl_plan *plan, const void *payload, void *workspace, voi
  * record; records are written back to back, without LUT headers.
  * idx    in, device, uint16[n_chunks*k]
  * codes  in, device, uint8[n_chunks*k]
- * out    out, device, n_chunks*7k/4 bytes */
+ * out    out, device, n_chunks*7k/4 bytes
+ * No alignment is required beyond that of the element types (4-byte aligned
+ * `codes` and `out` take a faster route when k is a multiple of 16; the bytes
+ * written are the same).  Only the low 12 bits of an index and the low bits of a
+ * code are used. */
 int sl_pack_indices(const uint16_t *idx, const uint8_t *codes, int64_t n_chunks, int k, void *out,
                     void *stream);
 /* The same for the other value widths of sl_plan_create_bits: codes (values
