@@ -143,6 +143,9 @@ SL_DEV void stack_push(BinStacksT<LV> &s, int m, double v0, double v1, double v2
 }
 
 constexpr int CODE_WAVES = 2;        // waves per workgroup
+#ifndef SL_CODES_WAVE_FROM
+#define SL_CODES_WAVE_FROM 512        // k from which a wave, not a lane, owns a chunk in kernel C
+#endif
 constexpr int CODE_PITCH = 65;       // LDS row pitch in floats: conflict-free column reads
 
 // One LANE per chunk, 64 consecutive chunks per wave.  The selected values of
@@ -235,6 +238,84 @@ __global__ void __launch_bounds__(64 * CODE_WAVES, WAVES_PER_EU) k_codes(CodeArg
         A.leafC[3 * A.n_chunks + c] = r3;
 #pragma unroll
         for (int b = 0; b < 4; ++b) A.cnt[b * A.n_chunks + c] = n_b[b];
+    }
+}
+
+// ------------------------------------------------------------------ kernel C at high densities
+// From k = 512 a lane per chunk has too long a walk (and too deep a stack).  Here one WAVE owns
+// a chunk: lane l takes the E = pow2ceil(k)/64 consecutive entries E*l .., folds them through
+// the same binary-counter stacks (log2(E) levels, resolved at compile time), and the upper
+// levels of the adjacent-pair tree are a butterfly over the lanes (a + b = b + a bit for bit,
+// so it does not matter which of a pair of lanes is the left one).  Entries from k on are the
+// +0.0 padding of the tree.  Same codes, counts and per-bin roots as k_codes.
+template <int E>
+__global__ void __launch_bounds__(256) k_codes_wave(CodeArgs A)
+{
+    constexpr int LV = (E == 8 ? 3 : E == 16 ? 4 : E == 32 ? 5 : 6) + 1;
+    const int lane = threadIdx.x & 63, k = A.k;
+    const int wave = sl_uniform((int)(threadIdx.x >> 6));
+    const long long c = (long long)blockIdx.x * (blockDim.x >> 6) + wave;
+    if (c >= A.n_chunks) return;
+    const SlChunkDesc d = A.desc[c];
+    const double mu = A.tstat[d.tensor].mu;
+    const double T = 9.0 * A.tstat[d.tensor].var;      // squared distance of the outer edges (3 sigma)
+    unsigned char *codes_out = A.payload + d.rec_off + 3 * k / 2;
+    const float *vin = A.vals + c * k;
+    const int m0 = E * lane;
+
+    BinStacksT<LV> st;
+#pragma unroll
+    for (int l = 0; l < LV; ++l) st.a[l] = st.b[l] = st.c[l] = st.d[l] = 0.0;
+    unsigned long long counts = 0;           // four 16-bit counters, bin b in bits 16b..
+    unsigned words[E / 16 > 0 ? E / 16 : 1];
+#pragma unroll
+    for (int w = 0; w < (E / 16 > 0 ? E / 16 : 1); ++w) words[w] = 0u;
+#pragma unroll
+    for (int j4 = 0; j4 < E; j4 += 4) {
+        float4 v4 = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (m0 + j4 < k) v4 = *reinterpret_cast<const float4 *>(vin + m0 + j4);    // k is a multiple of 4
+        const float xs[4] = {v4.x, v4.y, v4.z, v4.w};
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int j = j4 + q;
+            const bool valid = m0 + j < k;
+            const double x = (double)xs[q];
+            const double dlt = x - mu;
+            const double dd = dlt * dlt;
+            const int code = dlt < 0.0 ? (dd > T ? 0 : 1) : (dd >= T ? 3 : 2);
+            counts += valid ? 1ull << (16 * code) : 0ull;
+            stack_push<0>(st, j, valid && code == 0 ? x : 0.0, valid && code == 1 ? x : 0.0,
+                          valid && code == 2 ? x : 0.0, valid && code == 3 ? x : 0.0);
+            words[j / 16] |= (valid ? (unsigned)code : 0u) << (2 * (j & 15));
+        }
+    }
+    // the lane's subtree roots, then the levels above them across the lanes
+    double r0 = st.a[LV - 1], r1 = st.b[LV - 1], r2 = st.c[LV - 1], r3 = st.d[LV - 1];
+    r0 = sl_wave_tree(r0, 6), r1 = sl_wave_tree(r1, 6), r2 = sl_wave_tree(r2, 6), r3 = sl_wave_tree(r3, 6);
+#pragma unroll
+    for (int sft = 1; sft < 64; sft <<= 1) counts += __shfl_xor(counts, sft);
+
+    // codes: E/4 bytes per lane at byte E/4 * lane of the code stream (whole bytes: k % 4 == 0)
+    const int nbytes = min(E / 4, max(0, (k - m0) / 4));
+    if ((k & 15) == 0 && nbytes == E / 4) {          // records of whole words: aligned stores
+        if constexpr (E == 8) {
+            reinterpret_cast<unsigned short *>(codes_out)[lane] = (unsigned short)words[0];
+        } else {
+#pragma unroll
+            for (int w = 0; w < E / 16; ++w) reinterpret_cast<unsigned *>(codes_out)[(E / 16) * lane + w] = words[w];
+        }
+    } else {
+#pragma unroll
+        for (int b = 0; b < E / 4; ++b)
+            if (b < nbytes) codes_out[(E / 4) * lane + b] = (unsigned char)(words[b / 4] >> (8 * (b & 3)));
+    }
+    if (lane == 0) {
+        A.leafC[0 * A.n_chunks + c] = r0;
+        A.leafC[1 * A.n_chunks + c] = r1;
+        A.leafC[2 * A.n_chunks + c] = r2;
+        A.leafC[3 * A.n_chunks + c] = r3;
+#pragma unroll
+        for (int b = 0; b < 4; ++b) A.cnt[b * A.n_chunks + c] = (unsigned)(counts >> (16 * b)) & 0xFFFFu;
     }
 }
 
@@ -506,9 +587,20 @@ int slk_quantize(const sl_plan *p, float *e, int skip_residual, unsigned char *p
         case 3: hipLaunchKernelGGL(k_codes_b<3>, dim3(nblk), dim3(64 * CODE_WAVES), 0, st, C); break;
         case 4: hipLaunchKernelGGL(k_codes_b<4>, dim3(nblk), dim3(64 * CODE_WAVES), 0, st, C); break;
         default:
-            if (k <= 64) hipLaunchKernelGGL((k_codes<7, 32, 4>), dim3(nblk), dim3(64 * CODE_WAVES), 0, st, C);
-            else if (k <= 256) hipLaunchKernelGGL((k_codes<9, 32, 4>), dim3(nblk), dim3(64 * CODE_WAVES), 0, st, C);
-            else hipLaunchKernelGGL((k_codes<13, 64, 2>), dim3(nblk), dim3(64 * CODE_WAVES), 0, st, C);
+            if (k <= 64) {
+                hipLaunchKernelGGL((k_codes<7, 32, 4>), dim3(nblk), dim3(64 * CODE_WAVES), 0, st, C);
+            } else if (k <= 256) {
+                hipLaunchKernelGGL((k_codes<9, 32, 4>), dim3(nblk), dim3(64 * CODE_WAVES), 0, st, C);
+            } else if (k < SL_CODES_WAVE_FROM) {
+                hipLaunchKernelGGL((k_codes<13, 64, 2>), dim3(nblk), dim3(64 * CODE_WAVES), 0, st, C);
+            } else {
+                // a wave per chunk, E = pow2ceil(k) / 64 entries per lane
+                const dim3 wgrid((unsigned)((p->n_chunks + 3) / 4)), wblock(256);
+                if (k <= 512) hipLaunchKernelGGL(k_codes_wave<8>, wgrid, wblock, 0, st, C);
+                else if (k <= 1024) hipLaunchKernelGGL(k_codes_wave<16>, wgrid, wblock, 0, st, C);
+                else if (k <= 2048) hipLaunchKernelGGL(k_codes_wave<32>, wgrid, wblock, 0, st, C);
+                else hipLaunchKernelGGL(k_codes_wave<64>, wgrid, wblock, 0, st, C);
+            }
             break;
     }
     if ((rc = check_launch())) return rc;
