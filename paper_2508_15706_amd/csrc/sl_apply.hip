@@ -57,8 +57,9 @@ struct ApplyArgs {
     int bits, hdr_bytes, rec_bytes;   // value width and the sizes that follow from it
     int batch;               // records staged per round
     // x / d for the staging loops without a division: __umulhi(x, floor(2^32 / d) + 1) is
-    // exact while x * d < 2^32 (x < 16384 here); d = words per (table + record), bytes per record
-    unsigned magic_src, magic_rec;
+    // exact while x * d < 2^32 (x < 16384 here); d = words per (table + record), the record whole
+    // words or padded to them
+    unsigned magic_src, magic_pad;
     int lds_per_wave;
     long long n_chunks;
     const unsigned char *payload[SL_MAX_WORKERS];
@@ -105,7 +106,6 @@ __global__ void __launch_bounds__(256) k_apply(ApplyArgs A)
     const bool word_path = (rec_bytes & 3) == 0;
     const int wpr_src = hdr_words + (rec_bytes >> 2);  // words per worker: LUT + record
     const int wpr_dst = rec_pad >> 2;
-    const int hdr_shift = 31 - __clz(hdr_words | 1);   // the table is 4, 8 or 16 words (or absent)
     // Worker r's payload pointer where r differs from lane to lane: lane l keeps worker l's
     // pointer (there are at most as many workers as lanes) and the others read it across
     // lanes.  Indexing the kernel argument with a per-lane r instead costs a dependent vector
@@ -215,22 +215,41 @@ __global__ void __launch_bounds__(256) k_apply(ApplyArgs A)
                         }
                     }
                 } else {
-                    const int nlw = nb * hdr_words, nrb = nb * rec_bytes;
-                    for (int wb = 0; wb < nlw; wb += 64) {              // the tensor's LUT of each worker
-                        const int w = wb + lane;
-                        const bool valid = w < nlw;
-                        const int r = valid ? w >> hdr_shift : 0, q = w & (hdr_words - 1);
-                        const sl_gbytes p = payload_of(r0 + r);
-                        if (valid)
-                            reinterpret_cast<unsigned *>(stage)[r * wpr_dst + q] =
-                                reinterpret_cast<sl_gwords>(p + lut_off)[q];
-                    }
-                    for (int bb = 0; bb < nrb; bb += 64) {
-                        const int b = bb + lane;
-                        const bool valid = b < nrb;
-                        const int r = valid ? (int)__umulhi((unsigned)b, A.magic_rec) : 0, q = b - r * rec_bytes;
-                        const sl_gbytes p = payload_of(r0 + r);
-                        if (valid) stage[r * rec_pad + hdr + q] = p[rec_off + q];
+                    // Records that are not whole words lie at any byte of the payload.  They are
+                    // staged as whole words all the same: word i of a record is put together from
+                    // the two aligned words of the payload that hold its bytes (only words that
+                    // hold bytes of the record are read).
+                    const int wps = wpr_dst;                      // words per worker: LUT + padded record
+                    const int nwb = nb * wps;
+                    const unsigned sh = (unsigned)(rec_off & 3);
+                    const long long a0 = rec_off & ~3ll, a1 = (rec_off + rec_bytes + 3) & ~3ll;
+                    constexpr int SUB = SMALLK ? 2 : OCTETS ? SL_APPLY_STAGE_U : 4;
+                    for (int wb = 0; wb < nwb; wb += 64 * SUB) {
+                        unsigned v[SUB];
+#pragma unroll
+                        for (int u = 0; u < SUB; ++u) {
+                            const int w = wb + 64 * u + lane;
+                            const bool valid = w < nwb;
+                            const int r = valid ? (int)__umulhi((unsigned)w, A.magic_pad) : 0, q = w - r * wps;
+                            const sl_gbytes p = payload_of(r0 + r);
+                            v[u] = 0;
+                            if (valid) {
+                                if (q < hdr_words) {
+                                    v[u] = reinterpret_cast<sl_gwords>(p + lut_off)[q];
+                                } else {
+                                    const int i = q - hdr_words;
+                                    const sl_gwords src = reinterpret_cast<sl_gwords>(p + a0) + i;
+                                    const unsigned lo = src[0];
+                                    const unsigned hi = (sh != 0u && a0 + 4ll * i + 4 < a1) ? src[1] : 0u;
+                                    v[u] = __builtin_amdgcn_alignbyte(hi, lo, sh);
+                                }
+                            }
+                        }
+#pragma unroll
+                        for (int u = 0; u < SUB; ++u) {
+                            const int w = wb + 64 * u + lane;
+                            if (w < nwb) reinterpret_cast<unsigned *>(stage)[w] = v[u];
+                        }
                     }
                 }
                 sl_wave_sync();
@@ -616,7 +635,7 @@ int slk_apply(const sl_plan *p, float *theta, float *mom, float mu, const void *
     if (batch > R) batch = R;
     A.batch = batch;
     A.magic_src = (unsigned)(0x100000000ull / (unsigned)((p->hdr_bytes >> 2) + (p->rec_bytes >> 2)) + 1);
-    A.magic_rec = (unsigned)(0x100000000ull / (unsigned)p->rec_bytes + 1);
+    A.magic_pad = (unsigned)(0x100000000ull / (unsigned)(rec_pad >> 2) + 1);
     for (int r = 0; r < SL_MAX_WORKERS; ++r)
         A.payload[r] = r < R ? static_cast<const unsigned char *>(payloads[r]) : nullptr;
     A.n_chunks = p->n_chunks;
