@@ -57,9 +57,8 @@ struct ApplyArgs {
     int bits, hdr_bytes, rec_bytes;   // value width and the sizes that follow from it
     int batch;               // records staged per round
     // x / d for the staging loops without a division: __umulhi(x, floor(2^32 / d) + 1) is
-    // exact while x * d < 2^32 (x < 16384 here); d = words per (table + record), the record whole
-    // words or padded to them
-    unsigned magic_src, magic_pad;
+    // exact while x * d < 2^32 (x < 16384 here); d = words per (table + record padded to whole words)
+    unsigned magic_src;
     int lds_per_wave;
     long long n_chunks;
     const unsigned char *payload[SL_MAX_WORKERS];
@@ -102,10 +101,8 @@ __global__ void __launch_bounds__(256) k_apply(ApplyArgs A)
     const unsigned stride = (unsigned)d.stride;
     const bool full = d.flags & SLC_FULL;
 
-    // Word w of a batch's staging area: worker r = w / wpr_src, word q of (LUT, record)
-    const bool word_path = (rec_bytes & 3) == 0;
-    const int wpr_src = hdr_words + (rec_bytes >> 2);  // words per worker: LUT + record
-    const int wpr_dst = rec_pad >> 2;
+    // Word w of a batch's staging area: worker r = w / wpr, word q of (LUT, record padded to words)
+    const int wpr = rec_pad >> 2;
     // Worker r's payload pointer where r differs from lane to lane: lane l keeps worker l's
     // pointer (there are at most as many workers as lanes) and the others read it across
     // lanes.  Indexing the kernel argument with a per-lane r instead costs a dependent vector
@@ -119,15 +116,27 @@ __global__ void __launch_bounds__(256) k_apply(ApplyArgs A)
         const unsigned hi = (unsigned)__builtin_amdgcn_ds_bpermute(4 * r, (int)(unsigned)(my_ptr >> 32));
         return reinterpret_cast<sl_gbytes>(((unsigned long long)hi << 32) | lo);
     };
-    // Word w of workers r_first.. taken as one run of (LUT, record) blocks, or 0 beyond `nw`.
+    // Word w of workers r_first.. taken as one run of (LUT, record) blocks, or 0 beyond `nw`.  A
+    // record that is not a whole number of words lies at any byte of the payload: its word i is
+    // put together from the two aligned words that hold its bytes (only words that hold bytes
+    // of the record are read).
+    const unsigned sh = (unsigned)(rec_off & 3);
+    const long long a0 = rec_off & ~3ll, a1 = (rec_off + rec_bytes + 3) & ~3ll;
     auto src_word = [&](int r_first, int w, int nw) -> unsigned {
         const bool valid = w < nw;
-        const int r = valid ? (int)__umulhi((unsigned)w, A.magic_src) : 0, q = w - r * wpr_src;
+        const int r = valid ? (int)__umulhi((unsigned)w, A.magic_src) : 0, q = w - r * wpr;
         const sl_gbytes p = payload_of(r_first + r);
         unsigned v = 0;
-        if (valid)
-            v = q < hdr_words ? reinterpret_cast<sl_gwords>(p + lut_off)[q]
-                              : reinterpret_cast<sl_gwords>(p + rec_off)[q - hdr_words];
+        if (valid) {
+            if (q < hdr_words) {
+                v = reinterpret_cast<sl_gwords>(p + lut_off)[q];
+            } else {
+                const int i = q - hdr_words;
+                const sl_gwords src = reinterpret_cast<sl_gwords>(p + a0) + i;
+                v = src[0];
+                if (sh != 0u) v = __builtin_amdgcn_alignbyte(a0 + 4ll * i + 4 < a1 ? src[1] : 0u, v, sh);
+            }
+        }
         return v;
     };
     // The first 64*PF words of the first batch (all of it for R*(16 + 7k/4) <= 2 KB:
@@ -139,10 +148,8 @@ __global__ void __launch_bounds__(256) k_apply(ApplyArgs A)
     constexpr int PF = ROUTE == 2 ? 16 : !TWO_BIT ? 12 : ROUTE == 1 ? SL_APPLY_PF1 : 8;
     unsigned pf[PF];
     const int nb0 = min(A.batch, A.R);
-    if (word_path) {
 #pragma unroll
-        for (int u = 0; u < PF; ++u) pf[u] = src_word(0, lane + 64 * u, nb0 * wpr_src);
-    }
+    for (int u = 0; u < PF; ++u) pf[u] = src_word(0, lane + 64 * u, nb0 * wpr);
 
     sl_f4 th[16], mo[NESTEROV ? 16 : 1];
     float *mc = NESTEROV ? A.mom + d.base : nullptr;
@@ -190,66 +197,27 @@ __global__ void __launch_bounds__(256) k_apply(ApplyArgs A)
             const int nb = min(A.batch, A.R - r0);
             sl_wave_sync();
             if (h == 0 || !single) {
-                if (word_path) {
-                    const int nw = nb * wpr_src;
-                    int wb = 0;                       // wave-uniform: word wb + lane is this lane's next
-                    if (r0 == 0 && h == 0) {
+                const int nw = nb * wpr;
+                int wb = 0;                       // wave-uniform: word wb + lane is this lane's next
+                if (r0 == 0 && h == 0) {
 #pragma unroll
-                        for (int u = 0; u < PF; ++u) {
-                            const int w = lane + 64 * u;
-                            // (whole-word records: the staging pitch is wpr_src words, word w lands at w)
-                            if (w < nw) reinterpret_cast<unsigned *>(stage)[w] = pf[u];
-                        }
-                        wb = 64 * PF;
+                    for (int u = 0; u < PF; ++u) {
+                        const int w = lane + 64 * u;
+                        // (the staging pitch is wpr words: word w lands at w)
+                        if (w < nw) reinterpret_cast<unsigned *>(stage)[w] = pf[u];
                     }
-                    // the rest: SU words per lane are loaded before the first of them is parked in LDS
-                    constexpr int SU = SMALLK ? 1 : SL_APPLY_STAGE_U;   // (small k: little or nothing is left)
-                    for (; wb < nw; wb += 64 * SU) {
-                        unsigned v[SU];
+                    wb = 64 * PF;
+                }
+                // the rest: SU words per lane are loaded before the first of them is parked in LDS
+                constexpr int SU = SMALLK ? 1 : SL_APPLY_STAGE_U;   // (small k: little or nothing is left)
+                for (; wb < nw; wb += 64 * SU) {
+                    unsigned v[SU];
 #pragma unroll
-                        for (int u = 0; u < SU; ++u) v[u] = src_word(r0, wb + 64 * u + lane, nw);
+                    for (int u = 0; u < SU; ++u) v[u] = src_word(r0, wb + 64 * u + lane, nw);
 #pragma unroll
-                        for (int u = 0; u < SU; ++u) {
-                            const int w = wb + 64 * u + lane;
-                            if (w < nw) reinterpret_cast<unsigned *>(stage)[w] = v[u];
-                        }
-                    }
-                } else {
-                    // Records that are not whole words lie at any byte of the payload.  They are
-                    // staged as whole words all the same: word i of a record is put together from
-                    // the two aligned words of the payload that hold its bytes (only words that
-                    // hold bytes of the record are read).
-                    const int wps = wpr_dst;                      // words per worker: LUT + padded record
-                    const int nwb = nb * wps;
-                    const unsigned sh = (unsigned)(rec_off & 3);
-                    const long long a0 = rec_off & ~3ll, a1 = (rec_off + rec_bytes + 3) & ~3ll;
-                    constexpr int SUB = SMALLK ? 2 : OCTETS ? SL_APPLY_STAGE_U : 4;
-                    for (int wb = 0; wb < nwb; wb += 64 * SUB) {
-                        unsigned v[SUB];
-#pragma unroll
-                        for (int u = 0; u < SUB; ++u) {
-                            const int w = wb + 64 * u + lane;
-                            const bool valid = w < nwb;
-                            const int r = valid ? (int)__umulhi((unsigned)w, A.magic_pad) : 0, q = w - r * wps;
-                            const sl_gbytes p = payload_of(r0 + r);
-                            v[u] = 0;
-                            if (valid) {
-                                if (q < hdr_words) {
-                                    v[u] = reinterpret_cast<sl_gwords>(p + lut_off)[q];
-                                } else {
-                                    const int i = q - hdr_words;
-                                    const sl_gwords src = reinterpret_cast<sl_gwords>(p + a0) + i;
-                                    const unsigned lo = src[0];
-                                    const unsigned hi = (sh != 0u && a0 + 4ll * i + 4 < a1) ? src[1] : 0u;
-                                    v[u] = __builtin_amdgcn_alignbyte(hi, lo, sh);
-                                }
-                            }
-                        }
-#pragma unroll
-                        for (int u = 0; u < SUB; ++u) {
-                            const int w = wb + 64 * u + lane;
-                            if (w < nwb) reinterpret_cast<unsigned *>(stage)[w] = v[u];
-                        }
+                    for (int u = 0; u < SU; ++u) {
+                        const int w = wb + 64 * u + lane;
+                        if (w < nw) reinterpret_cast<unsigned *>(stage)[w] = v[u];
                     }
                 }
                 sl_wave_sync();
@@ -634,8 +602,7 @@ int slk_apply(const sl_plan *p, float *theta, float *mom, float mu, const void *
     if (batch < 1) batch = 1;
     if (batch > R) batch = R;
     A.batch = batch;
-    A.magic_src = (unsigned)(0x100000000ull / (unsigned)((p->hdr_bytes >> 2) + (p->rec_bytes >> 2)) + 1);
-    A.magic_pad = (unsigned)(0x100000000ull / (unsigned)(rec_pad >> 2) + 1);
+    A.magic_src = (unsigned)(0x100000000ull / (unsigned)(rec_pad >> 2) + 1);
     for (int r = 0; r < SL_MAX_WORKERS; ++r)
         A.payload[r] = r < R ? static_cast<const unsigned char *>(payloads[r]) : nullptr;
     A.n_chunks = p->n_chunks;
