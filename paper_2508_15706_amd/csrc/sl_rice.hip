@@ -243,19 +243,29 @@ __global__ void __launch_bounds__(256) k_rice_scan(RiceArgs A)
     if (tid == 0) A.tbytes[blockIdx.x] = (carry + 15ull) & ~15ull;
 }
 
-// Header: magic, total, tensor offsets (one workgroup; the scan over tensors is short).
+// Header: magic, total, tensor offsets (one wave scans the tensor blocks' sizes, 64 at a time).
 __global__ void __launch_bounds__(64) k_rice_header(RiceArgs A, unsigned char *out)
 {
-    if (threadIdx.x != 0) return;
+    const int lane = threadIdx.x;
     unsigned long long *h = reinterpret_cast<unsigned long long *>(out);
     unsigned long long pos = (16ull + 8ull * (unsigned long long)A.n_tensors + 15ull) & ~15ull;
-    if ((A.n_tensors & 1)) h[2 + A.n_tensors] = 0ull;          // padding of the header to 16 bytes
-    for (int t = 0; t < A.n_tensors; ++t) {
-        h[2 + t] = pos;
-        pos += A.tbytes[t];
+    for (int base = 0; base < A.n_tensors; base += 64) {
+        const int t = base + lane;
+        const unsigned long long v = t < A.n_tensors ? A.tbytes[t] : 0ull;
+        unsigned long long incl = v;
+#pragma unroll
+        for (int s = 1; s < 64; s <<= 1) {
+            const unsigned long long up = __shfl_up(incl, s);
+            if (lane >= s) incl += up;
+        }
+        if (t < A.n_tensors) h[2 + t] = pos + incl - v;
+        pos += __shfl(incl, 63);
     }
-    h[0] = 0x3130454349524C53ull;                              // "SLRICE01", little endian
-    h[1] = pos;
+    if (lane == 0) {
+        if ((A.n_tensors & 1)) h[2 + A.n_tensors] = 0ull;      // padding of the header to 16 bytes
+        h[0] = 0x3130454349524C53ull;                          // "SLRICE01", little endian
+        h[1] = pos;
+    }
 }
 
 template <bool WORDS>
