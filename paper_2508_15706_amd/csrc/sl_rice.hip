@@ -119,6 +119,78 @@ struct BitReader {
     }
 };
 
+// The decoder's reader.  The lanes of a wave decode different streams in lockstep (same k, same
+// loops) but sit at different bit positions, so with a reader that loads on demand some lane
+// loads on nearly every entry, and the wait that follows is for the whole wave.  Here every
+// lane keeps a window of W words of its stream in LDS (word-interleaved over the lanes) and all
+// lanes top their windows up together at fixed points of the loops; in between they read LDS
+// only.  W covers the most bits that can be consumed between two such points (see
+// rice_window_words); a malformed stream that consumes more reads stale words of the window -
+// garbage, as beyond the end of the input, but always inside the window.
+struct WinReader {
+    const unsigned char *src, *end;          // next word of the stream to load; end of the input
+    unsigned *win;                           // this wave's windows, word w of lane l at [w * 64 + l]
+    unsigned wmask;                          // W - 1, W a power of two
+    int lane;
+    unsigned fill = 0, rdw = 0;              // words loaded / handed out so far
+    unsigned long long acc = 0;
+    int n = 0;
+    SL_DEV WinReader(const unsigned char *start, const unsigned char *limit, unsigned *w, int W, int l)
+        : src(start), end(limit), win(w), wmask((unsigned)W - 1u), lane(l)
+    {
+        top_up();
+    }
+    SL_DEV void top_up()                     // called by the lanes of a wave together
+    {
+        const unsigned room = (wmask + 1u) - (fill - rdw);
+        for (unsigned j0 = 0; sl_ballot(j0 < room) != 0ull; j0 += 8) {
+            unsigned v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const unsigned char *p = src + 4ull * (j0 + u);
+                v[u] = (j0 + u < room && p + 4 <= end) ? *reinterpret_cast<const unsigned *>(p) : 0u;
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u)
+                if (j0 + u < room) win[((fill + j0 + u) & wmask) * 64u + lane] = v[u];
+        }
+        src += 4ull * room;
+        fill += room;
+    }
+    SL_DEV void refill()
+    {
+        const unsigned w = win[(rdw & wmask) * 64u + lane];
+        ++rdw;
+        acc |= (unsigned long long)w << n;
+        n += 32;
+    }
+    SL_DEV unsigned get(int bits)            // bits <= 32
+    {
+        while (n < bits) refill();
+        const unsigned v = bits == 32 ? (unsigned)acc : (unsigned)acc & ((1u << bits) - 1u);
+        acc >>= bits, n -= bits;
+        return v;
+    }
+    SL_DEV unsigned unary()                  // number of one-bits before the next zero bit
+    {
+        unsigned q = 0;
+        for (;;) {
+            if (n == 0) refill();
+            const unsigned long long inv = ~acc;
+            const int t = inv ? __ffsll((long long)inv) - 1 : 64;
+            if (t >= n) {                    // every buffered bit is a one
+                q += n;
+                acc = 0, n = 0;
+                if (q > 8192) return q;      // malformed input: stop
+            } else {
+                q += t;
+                acc >>= (t + 1), n -= (t + 1);
+                return q;
+            }
+        }
+    }
+};
+
 // Sequential writer; COUNT = only count the bits.
 template <bool COUNT, bool WORDS>
 struct BitWriter {
@@ -289,13 +361,29 @@ __global__ void __launch_bounds__(64) k_rice_encode(RiceArgs A, const unsigned c
             *reinterpret_cast<unsigned *>(blk + q) = 0u;
 }
 
+// Entries between two top-ups of the decoder's windows, and the window that covers them: the
+// gaps of `epr` entries of one chunk take at most epr * (1 + b) bits plus 4096 >> b one-bits
+// (the unary parts of a chunk add up to at most 4095 >> b), up to 64 consumed bits still sit in
+// the reader's register, and a word may be half used on either side.
+constexpr int RICE_EPR = 16;
+static int rice_window_words(int b)
+{
+    const int bits = RICE_EPR * (1 + b) + (4096 >> b);
+    int need = (bits + 31) / 32 + 4, W = 16;      // (at least 16: the value fields are copied 8 words at a time)
+    while (W < need) W <<= 1;
+    return W;
+}
+
 template <bool WORDS>
 __global__ void __launch_bounds__(64) k_rice_decode(RiceArgs A, const unsigned char *in,
-                                                    unsigned long long in_bytes, unsigned char *payload)
+                                                    unsigned long long in_bytes, unsigned char *payload, int W)
 {
-    const long long G = (long long)blockIdx.x * 64 + threadIdx.x;
-    if (G >= A.n_groups) return;
-    const SlGroup g = A.groups[G];
+    extern __shared__ unsigned rice_win[];
+    const int lane = threadIdx.x;
+    const long long G = (long long)blockIdx.x * 64 + lane;
+    // (a lane beyond the last group stays in the wave: the windows are topped up by all lanes together)
+    const bool live = G < A.n_groups;
+    const SlGroup g = live ? A.groups[G] : SlGroup{0, 0};
     const SlTensorDev td = A.tensors[g.tensor];
     const int k = A.k, b = A.b, hdr = A.hdr_bytes;
     const long long rec = A.rec_bytes;
@@ -304,17 +392,18 @@ __global__ void __launch_bounds__(64) k_rice_decode(RiceArgs A, const unsigned c
     if (toff > in_bytes) toff = in_bytes;
     const unsigned char *blk = in + toff;
     unsigned long long off = in_bytes;                         // beyond the end: reads as zeros
-    if (blk + hdr + 4ull * (g.local_group + 1) <= end)
+    if (live && blk + hdr + 4ull * (g.local_group + 1) <= end)
         off = toff + reinterpret_cast<const unsigned *>(blk + hdr)[g.local_group];
     if (off > in_bytes) off = in_bytes;
-    BitReader<true, true> rd(in + (off & ~3ull), end);
+    WinReader rd(in + (off & ~3ull), end, rice_win, W, lane);
     const long long c0 = (long long)g.local_group * SL_RICE_GROUP;
-    const int nc = (int)min((long long)SL_RICE_GROUP, td.n_chunks - c0);
+    const int nc = live ? (int)min((long long)SL_RICE_GROUP, td.n_chunks - c0) : 0;
     for (int i = 0; i < nc; ++i) {
         unsigned char *r = payload + td.pay_off + hdr + (c0 + i) * rec;
         BitWriter<false, WORDS> w(r);
         int prev = -1;
         for (int m = 0; m < k; ++m) {
+            if ((m & (RICE_EPR - 1)) == 0) rd.top_up();
             const unsigned q = rd.unary();
             const unsigned gap = (q << b) | rd.get(b);
             int idx = prev + 1 + (int)gap;
@@ -324,9 +413,13 @@ __global__ void __launch_bounds__(64) k_rice_decode(RiceArgs A, const unsigned c
         }
         int left = k * A.bits;
         const int piece = WORDS ? 32 : 8;
-        for (; left >= piece; left -= piece) w.put(rd.get(piece), piece);
+        for (int cnt = 0; left >= piece; left -= piece, ++cnt) {
+            if ((cnt & (WORDS ? 7 : 31)) == 0) rd.top_up();    // every 8 words of value fields
+            w.put(rd.get(piece), piece);
+        }
         if (left) w.put(rd.get(left), left);
     }
+    if (!live) return;
     if (g.local_group == 0) {
         for (int q = 0; q < hdr; q += 16) {
             float4 lut = make_float4(0.f, 0.f, 0.f, 0.f);
@@ -402,11 +495,13 @@ int slk_rice_decode(const sl_plan *p, const unsigned char *in, size_t in_bytes, 
     const RiceArgs A = make_args(p, nullptr);
     const bool words = (p->rec_bytes & 3) == 0 && ((3 * p->k / 2) & 3) == 0;
     const unsigned nblk = (unsigned)((p->n_groups + 63) / 64);
+    const int W = rice_window_words(A.b);                      // <= 256 words: 64 KB of LDS at most
+    const size_t lds = (size_t)W * 64 * sizeof(unsigned);
     if (words)
-        hipLaunchKernelGGL(k_rice_decode<true>, dim3(nblk), dim3(64), 0, st, A, in,
-                           (unsigned long long)in_bytes, payload);
+        hipLaunchKernelGGL(k_rice_decode<true>, dim3(nblk), dim3(64), lds, st, A, in,
+                           (unsigned long long)in_bytes, payload, W);
     else
-        hipLaunchKernelGGL(k_rice_decode<false>, dim3(nblk), dim3(64), 0, st, A, in,
-                           (unsigned long long)in_bytes, payload);
+        hipLaunchKernelGGL(k_rice_decode<false>, dim3(nblk), dim3(64), lds, st, A, in,
+                           (unsigned long long)in_bytes, payload, W);
     return launched();
 }
