@@ -34,55 +34,17 @@ int sl_rice_param(int k)
 
 namespace {
 
-// Sequential reader of bit fields from a byte- or word-addressed stream.  A lane reads its
-// stream alone, so every load is a round trip to memory that nothing else of the lane hides: with
-// AHEAD the word reader runs two 16-byte blocks ahead of the bits it hands out (never past `limit`;
-// what lies beyond reads as zeros).  This pays for the coded stream (decode at configuration 4:
-// 0.44 -> 0.33 ms), not for the plain records the encoder reads.
-typedef unsigned sl_u4u __attribute__((ext_vector_type(4), aligned(4)));
-template <bool WORDS, bool AHEAD = false>
+// Sequential reader of bit fields from a byte- or word-addressed stream (the encoder's reader of
+// plain records: all lanes consume the same number of bits per call, so they load together).
+template <bool WORDS>
 struct BitReader {
-    const unsigned char *p, *end;            // p: the next byte (word, block) to load
+    const unsigned char *p, *end;
     unsigned long long acc = 0;
     int n = 0;
-    unsigned long long c0 = 0, c1 = 0, n0 = 0, n1 = 0;   // AHEAD: current and next block of four words
-    int left = 0;                                        // words of the current block not handed out yet
-    SL_DEV BitReader(const unsigned char *start, const unsigned char *limit) : p(start), end(limit)
-    {
-        if (AHEAD) {
-            load_block(c0, c1);
-            load_block(n0, n1);
-            left = 4;
-        }
-    }
-    SL_DEV void load_block(unsigned long long &a, unsigned long long &b)
-    {
-        unsigned w[4] = {0u, 0u, 0u, 0u};
-        if (p + 16 <= end) {
-            const sl_u4u v = *reinterpret_cast<const sl_u4u *>(p);
-            w[0] = v.x, w[1] = v.y, w[2] = v.z, w[3] = v.w;
-        } else {
-#pragma unroll
-            for (int q = 0; q < 4; ++q)
-                if (p + 4 * q + 4 <= end) w[q] = reinterpret_cast<const unsigned *>(p)[q];
-        }
-        a = (unsigned long long)w[0] | ((unsigned long long)w[1] << 32);
-        b = (unsigned long long)w[2] | ((unsigned long long)w[3] << 32);
-        p += 16;
-    }
+    SL_DEV BitReader(const unsigned char *start, const unsigned char *limit) : p(start), end(limit) {}
     SL_DEV void refill()
     {
-        if (AHEAD) {
-            const unsigned w = (unsigned)c0;
-            c0 = (c0 >> 32) | (c1 << 32);
-            c1 >>= 32;
-            if (--left == 0) {
-                c0 = n0, c1 = n1, left = 4;
-                load_block(n0, n1);
-            }
-            acc |= (unsigned long long)w << n;
-            n += 32;
-        } else if (WORDS) {
+        if (WORDS) {
             const unsigned w = p + 4 <= end ? *reinterpret_cast<const unsigned *>(p) : 0u;
             acc |= (unsigned long long)w << n;
             p += 4, n += 32;
@@ -259,12 +221,18 @@ SL_DEV unsigned code_group(const RiceArgs &A, long long G, const unsigned char *
             unsigned gap = (unsigned)(idx - prev - 1);
             prev = idx;
             unsigned q = gap >> b;
-            while (q >= 32) {
-                w.put(0xFFFFFFFFu, 32);
-                q -= 32;
+            const unsigned rem = gap & ((1u << b) - 1u);
+            if (q + 1u + (unsigned)b <= 32u) {
+                // the usual case in one piece: q one-bits, the zero bit, the remainder
+                w.put(((1u << q) - 1u) | (rem << (q + 1u)), (int)q + 1 + b);
+            } else {
+                while (q >= 32) {
+                    w.put(0xFFFFFFFFu, 32);
+                    q -= 32;
+                }
+                if (q) w.put((1u << q) - 1u, (int)q);
+                w.put(rem << 1, b + 1);                           // the zero bit, then the remainder
             }
-            if (q) w.put((1u << q) - 1u, (int)q);
-            w.put((gap & ((1u << b) - 1u)) << 1, b + 1);      // the zero bit, then the remainder
         }
         // the k value fields as they stand in the record (k * bits is a multiple of 8)
         int left = k * A.bits;
@@ -404,8 +372,24 @@ __global__ void __launch_bounds__(64) k_rice_decode(RiceArgs A, const unsigned c
         int prev = -1;
         for (int m = 0; m < k; ++m) {
             if ((m & (RICE_EPR - 1)) == 0) rd.top_up();
-            const unsigned q = rd.unary();
-            const unsigned gap = (q << b) | rd.get(b);
+            // Common case in straight-line code: with 32 bits buffered, a unary part and a
+            // remainder that end inside them are taken with one count of trailing ones and one
+            // shift; a longer code goes through the general calls.  (The lanes of a wave run
+            // this loop as one instruction stream, and there is less than one wave per SIMD:
+            // the length of that stream is what the decoder's time is - 0.27 -> 0.16 ms at
+            // configuration 4.  Collecting the records in LDS and writing them out 64 words
+            // at a time instead of one word per lane gained 2 % and was left out.)
+            if (rd.n < 32) rd.refill();
+            const unsigned low = (unsigned)rd.acc;
+            const int t = __ffs((int)~low) - 1;                 // one-bits before the first zero (-1: 32 ones)
+            unsigned gap;
+            if (t >= 0 && t + 1 + b <= 32) {
+                gap = ((unsigned)t << b) | (unsigned)((rd.acc >> (t + 1)) & ((1ull << b) - 1ull));
+                rd.acc >>= (t + 1 + b), rd.n -= (t + 1 + b);
+            } else {
+                const unsigned q = rd.unary();
+                gap = (q << b) | rd.get(b);
+            }
             int idx = prev + 1 + (int)gap;
             if (idx > 4095 || idx < 0) idx = 4095;             // malformed input stays in range
             prev = idx;
