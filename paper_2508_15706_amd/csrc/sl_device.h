@@ -72,17 +72,49 @@ SL_DEV int sl_popc(unsigned long long m) { return __builtin_popcountll(m); }
 
 SL_DEV int sl_uniform(int v) { return __builtin_amdgcn_readfirstlane(v); }
 
+// Cross-lane moves inside a row of 16 lanes as data-parallel-primitive modifiers (no trip
+// through the LDS crossbar, unlike a shuffle).  With all 64 lanes active:
+//   SL_DPP_XOR1, SL_DPP_XOR2  lane i reads lane i ^ 1, i ^ 2 (quad permutations);
+//   SL_DPP_HALF_MIRROR        lane i reads lane 7 - i of its group of 8: a lane of the other quad;
+//   SL_DPP_MIRROR             lane i reads lane 15 - i of its row: a lane of the other group of 8.
+// In a butterfly whose earlier levels left the same value in every lane of a quad (a group of
+// 8), the mirrors therefore deliver exactly what lane i ^ 4 (i ^ 8) would.
+#define SL_DPP_XOR1 0xB1
+#define SL_DPP_XOR2 0x4E
+#define SL_DPP_HALF_MIRROR 0x141
+#define SL_DPP_MIRROR 0x140
+template <int CTRL>
+SL_DEV int sl_dpp(int v) { return __builtin_amdgcn_update_dpp(v, v, CTRL, 0xF, 0xF, false); }
+template <int CTRL>
+SL_DEV double sl_dpp(double v)
+{
+    return __hiloint2double(sl_dpp<CTRL>(__double2hiint(v)), sl_dpp<CTRL>(__double2loint(v)));
+}
+// Level l (0..5) of a butterfly over the wave: the value of the partner lane.
+template <class T>
+SL_DEV T sl_partner(T v, int l)
+{
+    switch (l) {
+    case 0: return sl_dpp<SL_DPP_XOR1>(v);
+    case 1: return sl_dpp<SL_DPP_XOR2>(v);
+    case 2: return sl_dpp<SL_DPP_HALF_MIRROR>(v);
+    case 3: return sl_dpp<SL_DPP_MIRROR>(v);
+    default: return __shfl_xor(v, 1 << l);
+    }
+}
+
+// (all 64 lanes active)
 SL_DEV int sl_wave_max(int v)
 {
 #pragma unroll
-    for (int s = 32; s >= 1; s >>= 1) v = max(v, __shfl_xor(v, s));
+    for (int l = 0; l < 6; ++l) v = max(v, sl_partner(v, l));
     return sl_uniform(v);
 }
 
 SL_DEV int sl_wave_min(int v)
 {
 #pragma unroll
-    for (int s = 32; s >= 1; s >>= 1) v = min(v, __shfl_xor(v, s));
+    for (int l = 0; l < 6; ++l) v = min(v, sl_partner(v, l));
     return sl_uniform(v);
 }
 
@@ -96,9 +128,13 @@ SL_DEV int sl_pow2ceil(int n)
 // Adjacent-pair tree over the 64 lanes' values, `levels` levels (1 <= 2^levels
 // <= 64): afterwards every lane whose index is a multiple of 2^levels holds the
 // sum of its aligned group in the fixed pairing (v[2i] + v[2i+1] at each level).
+// (All 64 lanes active.  a + b and b + a are the same double, so both lanes of a pair end
+// up with the same sum, and after level l all 2^(l+1) lanes of a group hold the group's.)
 SL_DEV double sl_wave_tree(double v, int levels)
 {
-    for (int l = 0; l < levels; ++l) v = v + __shfl_xor(v, 1 << l);
+#pragma unroll
+    for (int l = 0; l < 6; ++l)
+        if (l < levels) v = v + sl_partner(v, l);
     return v;
 }
 
@@ -109,33 +145,38 @@ SL_DEV double sl_lane0(double v)
     return __hiloint2double(hi, lo);
 }
 
-// Fixed summation tree of one chunk's k per-entry values (the leaf of the
-// two-level sum).  Entry p lives in lane p % 64, slot p / 64; y(slot) returns
-// this lane's value for that slot (+0.0 beyond k).  The sequence is padded with
-// +0.0 to P = pow2ceil(k) and reduced by adjacent pairs.  `scratch` is a
-// 64-double LDS array private to the wave.  The result is uniform.
+// Fixed summation trees of one chunk's k per-entry values x and of their squares (the leaves
+// of the two-level sums), both at once so that the two chains of cross-lane steps overlap.
+// Entry p lives in lane p % 64, slot p / 64; x_of(slot) returns this lane's value for that
+// slot (+0.0 beyond k).  Each sequence is padded with +0.0 to P = pow2ceil(k) and reduced by
+// adjacent pairs.  `scratch` is a 128-double LDS array private to the wave.  The results are uniform.
 template <class F>
-SL_DEV double sl_chunk_tree(int k, int lane, double *scratch, F y)
+SL_DEV void sl_chunk_trees(int k, int lane, double *scratch, F x_of, double &sum_x, double &sum_xx)
 {
     const int P = sl_pow2ceil(k);
     if (P <= 64) {
         int levels = 0;
         while ((1 << levels) < P) ++levels;
-        return sl_lane0(sl_wave_tree(y(0), levels));
+        const double x = x_of(0);
+        sum_x = sl_lane0(sl_wave_tree(x, levels));
+        sum_xx = sl_lane0(sl_wave_tree(x * x, levels));
+        return;
     }
     const int slots = P / 64;           // power of two, <= 64
     const int used = (k + 63) / 64;
+    double *sx = scratch, *sxx = scratch + 64;
     sl_wave_sync();
-    if (lane >= used && lane < slots) scratch[lane] = 0.0;
+    if (lane >= used && lane < slots) sx[lane] = 0.0, sxx[lane] = 0.0;
     for (int s = 0; s < used; ++s) {
-        double t = sl_wave_tree(y(s), 6);
-        if (lane == 0) scratch[s] = t;
+        const double x = x_of(s);
+        const double t = sl_wave_tree(x, 6), tt = sl_wave_tree(x * x, 6);
+        if (lane == 0) sx[s] = t, sxx[s] = tt;
     }
     sl_wave_sync();
-    double v = lane < slots ? scratch[lane] : 0.0;
+    const double v = lane < slots ? sx[lane] : 0.0, vv = lane < slots ? sxx[lane] : 0.0;
     int levels = 0;
     while ((1 << levels) < slots) ++levels;
-    double r = sl_lane0(sl_wave_tree(v, levels));
+    sum_x = sl_lane0(sl_wave_tree(v, levels));
+    sum_xx = sl_lane0(sl_wave_tree(vv, levels));
     sl_wave_sync();
-    return r;
 }

@@ -104,9 +104,21 @@ SL_DEV int bisect_kth(int lo, int hi, int k, CountGE count_ge, int steps = 0)
 // position outside the tensor; sg0/sg1 hold the sign of register r at bit
 // 31 - (r & 31) of sg[r / 32].  Writes the k selected (value, index) pairs in
 // ascending local index to sel_val / sel_idx.
+//
+// The threshold T (the k-th largest key) is found in two stages.  A pass over all 64 registers
+// of every lane is the expensive unit, so only the leading SL_SELECT_COARSE_BITS bits of T are
+// bisected that way; this leaves T inside a bucket [T1, T1 + width) that holds few keys (about
+// fifty at a quarter density on Gaussian data).  One more pass copies the bucket's keys to
+// `list` (LDS, SL_SELECT_LIST_CAP ints, any order) and counts the keys above the bucket; the
+// remaining bits are bisected over the list alone.  A bucket that does not fit the list (many
+// equal keys) is bisected over the registers as before.
+#ifndef SL_SELECT_COARSE_BITS
+#define SL_SELECT_COARSE_BITS 12
+#endif
+#define SL_SELECT_LIST_CAP 512
 template <bool VALUES_FROM_A>
 SL_DEV void select_general(int (&key)[64], const float (&a)[64], unsigned sg0, unsigned sg1, int k, int lane,
-                           float *sel_val, unsigned short *sel_idx)
+                           float *sel_val, unsigned short *sel_idx, int *list)
 {
     auto count_regs = [&](int x) {
         int n = 0;
@@ -118,14 +130,66 @@ SL_DEV void select_general(int (&key)[64], const float (&a)[64], unsigned sg0, u
 #pragma unroll
     for (int r = 1; r < 64; ++r) lmax = max(lmax, key[r]);
     const int hi = sl_wave_max(lmax);
-    const int T = bisect_kth(0, hi, k, count_regs);
-    const int n_ge = count_regs(T);
+    int T = 0, n_ge = 0, n_gt = -1;         // n_gt: keys above T, where the list already gave it
+    const int top = hi > 0 ? 31 - __clz(hi) : 0;
+    const int last = top - SL_SELECT_COARSE_BITS + 1;    // lowest bit the coarse stage decides
+    if (last >= 3) {
+        // T1: the leading bits of T.  count(T1) >= k, and count(T1 + width) < k: T1 + width is either
+        // beyond every key or a value the bisection tried and rejected.
+        const int T1 = bisect_kth(0, hi, k, count_regs, SL_SELECT_COARSE_BITS);
+        const int width = 1 << last, upper = T1 | (width - 1);
+        int n_above = 0, m = 0;
+#pragma unroll
+        for (int r = 0; r < 64; ++r) {
+            // (a position outside the tensor has key -1: never above, and far outside the bucket)
+            const bool in = (unsigned)(key[r] - T1) < (unsigned)width;
+            const unsigned long long mb = sl_ballot(in);
+            n_above += sl_popc(sl_ballot(key[r] > upper));
+            if (mb) {
+                const int pos = m + sl_mbcnt(mb);
+                if (in && pos < SL_SELECT_LIST_CAP) list[pos] = key[r];
+                m += sl_popc(mb);
+            }
+        }
+        sl_wave_sync();
+        if (m <= SL_SELECT_LIST_CAP) {
+            constexpr int SLOTS = SL_SELECT_LIST_CAP / 64;
+            const int nslots = (m + 63) >> 6;
+            int ck[SLOTS];
+#pragma unroll
+            for (int s = 0; s < SLOTS; ++s) {
+                const int p = s * 64 + lane;
+                ck[s] = (s < nslots && p < m) ? list[p] : -1;
+            }
+            auto count_list = [&](int x) {
+                int n = 0;
+#pragma unroll
+                for (int s = 0; s < SLOTS; ++s)
+                    if (s < nslots) n += sl_popc(sl_ballot(ck[s] >= x));
+                return n;
+            };
+            // the (k - n_above)-th largest key of the bucket
+            T = bisect_kth(T1, upper, k - n_above, count_list);
+            n_ge = n_above + count_list(T);
+            n_gt = n_above + (T == upper ? 0 : count_list(T + 1));    // keys above T: beyond the bucket, or in it
+        } else {
+            T = bisect_kth(T1, upper, k, count_regs);
+            n_ge = count_regs(T);
+        }
+        sl_wave_sync();                     // the list shares LDS with nothing live, but keep its reads
+                                            // ahead of whatever the caller stores next
+    } else {
+        T = bisect_kth(0, hi, k, count_regs);
+        n_ge = count_regs(T);
+    }
     const bool ties = n_ge != k;            // more keys equal to T than slots left
     int need = 0;                           // tie entries to take, lowest indices first
     if (ties) {
-        int n_gt = 0;
+        if (n_gt < 0) {
+            n_gt = 0;
 #pragma unroll
-        for (int r = 0; r < 64; ++r) n_gt += sl_popc(sl_ballot(key[r] > T));
+            for (int r = 0; r < 64; ++r) n_gt += sl_popc(sl_ballot(key[r] > T));
+        }
         need = k - n_gt;
     }
     int base = 0, tbase = 0;
@@ -208,10 +272,11 @@ __global__ void SL_SELECT_BOUNDS k_select(SelectArgs A)
     const SlChunkDesc d = A.desc[c];
     const int k = A.k;
 
-    // LDS of this wave: [candidates 8*CAND_CAP][sel_val 4k][sel_idx 2k][tree scratch 512]
+    // LDS of this wave: [candidates 8*CAND_CAP][sel_val 4k][sel_idx 2k][tree scratch 1024]
     uint2 *cand = reinterpret_cast<uint2 *>(smem);
     constexpr int CAND_CAP = cand_cap(GPL), CAND_SLOTS = CAND_CAP / 64;
-    const size_t cand_bytes = GPL > 0 ? sizeof(uint2) * CAND_CAP : 0;
+    // (the general route's key list takes the place of the candidates: 2 KB when GPL = 0)
+    const size_t cand_bytes = GPL > 0 ? sizeof(uint2) * CAND_CAP : sizeof(int) * SL_SELECT_LIST_CAP;
     float *sel_val = reinterpret_cast<float *>(smem + cand_bytes);
     unsigned short *sel_idx = reinterpret_cast<unsigned short *>(smem + cand_bytes + 4 * (size_t)k);
     double *scratch = reinterpret_cast<double *>(smem + cand_bytes + ((6 * (size_t)k + 7) & ~(size_t)7));
@@ -632,21 +697,30 @@ __global__ void SL_SELECT_BOUNDS k_select(SelectArgs A)
     if (!done) {
         int key[64];
         unsigned sg0 = 0, sg1 = 0;
+        if (!RANDOM && full) {
+#pragma unroll
+            for (int r = 0; r < 64; ++r) key[r] = key_of(a[r]);
+        } else {
+#pragma unroll
+            for (int r = 0; r < 64; ++r) {
+                const bool outside = !((inside >> r) & 1ull);
+                if constexpr (RANDOM) {
+                    const unsigned j = 256u * (r >> 2) + 4u * lane + (r & 3);
+                    key[r] = outside ? -1 : (int)(fmix32(fmix32(A.seed_hash ^ (unsigned)c) ^ j) >> 1);
+                } else {
+                    key[r] = outside ? -1 : key_of(a[r]);
+                }
+            }
+        }
+        // the signs, one bit per register (a position outside the tensor is never selected, so its
+        // bit is never read): sg = (sg << 1) | sign, as one funnel shift
 #pragma unroll
         for (int r = 0; r < 64; ++r) {
             const unsigned u = __float_as_uint(a[r]);
-            const bool outside = !((inside >> r) & 1ull);
-            if constexpr (RANDOM) {
-                const unsigned j = 256u * (r >> 2) + 4u * lane + (r & 3);
-                key[r] = outside ? -1 : (int)(fmix32(fmix32(A.seed_hash ^ (unsigned)c) ^ j) >> 1);
-            } else {
-                key[r] = outside ? -1 : (int)(u & 0x7FFFFFFFu);
-            }
-            const unsigned sbit = outside ? 0u : (u >> 31);
-            if (r < 32) sg0 = (sg0 << 1) | sbit;
-            else sg1 = (sg1 << 1) | sbit;
+            if (r < 32) sg0 = __builtin_amdgcn_alignbit(sg0, u, 31);
+            else sg1 = __builtin_amdgcn_alignbit(sg1, u, 31);
         }
-        select_general<RANDOM>(key, a, sg0, sg1, k, lane, sel_val, sel_idx);
+        select_general<RANDOM>(key, a, sg0, sg1, k, lane, sel_val, sel_idx, reinterpret_cast<int *>(smem));
     }
     sl_wave_sync();
 
@@ -697,15 +771,11 @@ __global__ void SL_SELECT_BOUNDS k_select(SelectArgs A)
     }
 
     // per-chunk leaves of the quantizer's mean / variance sums
-    const double s1 = sl_chunk_tree(k, lane, scratch, [&](int s) {
+    double s1, s2;
+    sl_chunk_trees(k, lane, scratch, [&](int s) {
         const int p = s * 64 + lane;
         return p < k ? (double)sel_val[p] : 0.0;
-    });
-    const double s2 = sl_chunk_tree(k, lane, scratch, [&](int s) {
-        const int p = s * 64 + lane;
-        const double x = p < k ? (double)sel_val[p] : 0.0;
-        return x * x;
-    });
+    }, s1, s2);
     if (lane == 0) {
         A.leafA[c] = s1;
         A.leafA[A.n_chunks + c] = s2;
@@ -745,9 +815,9 @@ static int launch_select(const sl_plan *p, float *e, const float *delta, const f
     A.rec_bytes = p->rec_bytes;
     A.seed_hash = host_fmix32(seed);
     {
-        size_t b = pruned ? sizeof(uint2) * cand_cap(k > 256 ? 16 : 8) : 0;
+        size_t b = pruned ? sizeof(uint2) * cand_cap(k > 256 ? 16 : 8) : sizeof(int) * SL_SELECT_LIST_CAP;
         b += (6 * (size_t)k + 7) & ~(size_t)7;
-        b += 64 * sizeof(double);
+        b += 128 * sizeof(double);
         b = (b + 15) & ~(size_t)15;
         // k > 256: a pending record of whole words and whole groups of eight entries is staged in LDS
         A.pend_words = pending && k > 256 && (p->rec_bytes & 3) == 0 && (k & 7) == 0 && p->rec_bytes <= 8192;

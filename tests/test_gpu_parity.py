@@ -125,6 +125,48 @@ def test_compress_ties_zeros_and_heavy_tails(sl, oracle, k):
     check_compress(sl, oracle, descs, n, k, e0, delta, 0.95, what="degenerate")
 
 
+@pytest.mark.parametrize("k", [64, 512, 520, 1024, 2048, 3000])
+def test_compress_ties_at_the_threshold(sl, oracle, k):
+    """Ties exactly at the k-th largest magnitude, a few per chunk and with both signs, so that
+    the lowest indices must win (the general route narrows the threshold to a short list of
+    keys first and resolves the ties from it); magnitudes cut to a coarse grid, so that many
+    keys coincide around the threshold; magnitudes from so narrow a band that they share all
+    leading bits, which overflows that list."""
+    shapes = [(128, 192, TILE), (1, 2 * 4096 + 4000, FLAT), (64, 64, TILE), (128, 128, TILE), (128, 64, TILE)]
+    descs, n = layout_list(shapes)
+    rng = np.random.default_rng(300 + k)
+    e0 = np.zeros(n, dtype=np.float32)
+    delta = rng.normal(0, 1e-3, n).astype(np.float32)
+    # tensors 0-2: copy each chunk's k-th largest magnitude to positions that hold smaller ones
+    for r, c, off, layout in descs[:3]:
+        x = delta[off:off + r * c]
+        if layout == TILE:
+            t = x.reshape(r // 64, 64, c // 64, 64).transpose(0, 2, 1, 3).reshape(-1, 4096).copy()
+        else:
+            t = None
+        chunks = t if t is not None else [x[i:i + 4096] for i in range(0, r * c, 4096)]
+        for ch in chunks:
+            if ch.size <= k:
+                continue
+            mag = np.abs(ch)
+            order = np.argsort(-mag, kind="stable")
+            thr = mag[order[k - 1]]
+            below = order[k:]
+            take = rng.choice(below, size=min(7, below.size), replace=False)
+            ch[take] = thr * rng.choice([-1.0, 1.0], take.size).astype(np.float32)
+        if t is not None:
+            x[:] = t.reshape(r // 64, c // 64, 64, 64).transpose(0, 2, 1, 3).reshape(-1)
+    # tensor 3: five mantissa bits only
+    r, c, off, _ = descs[3]
+    u = delta[off:off + r * c].view(np.uint32)
+    u &= np.uint32(0xFFFC0000)
+    # tensor 4: all magnitudes within 2^-12 of one another (relative)
+    r, c, off, _ = descs[4]
+    delta[off:off + r * c] = (1e-3 * (1.0 + rng.integers(0, 1500, r * c) * 2.0**-23)).astype(np.float32) * \
+        rng.choice([-1.0, 1.0], r * c).astype(np.float32)
+    check_compress(sl, oracle, descs, n, k, e0, delta, 0.0, what="threshold ties")
+
+
 @pytest.mark.parametrize("beta", [0.0, 0.9, 0.999, 1.0])
 def test_compress_other_ef_decays(sl, oracle, beta):
     """The EF decay values of the paper's ablation (0.9, 0.95, 0.999; 1 = plain error feedback;
