@@ -107,15 +107,17 @@ SL_DEV T sl_partner(T v, int l)
 SL_DEV int sl_wave_max(int v)
 {
 #pragma unroll
-    for (int l = 0; l < 6; ++l) v = max(v, sl_partner(v, l));
-    return sl_uniform(v);
+    for (int l = 0; l < 4; ++l) v = max(v, sl_partner(v, l));       // every lane: its row's maximum
+    return max(max(__builtin_amdgcn_readlane(v, 0), __builtin_amdgcn_readlane(v, 16)),
+               max(__builtin_amdgcn_readlane(v, 32), __builtin_amdgcn_readlane(v, 48)));
 }
 
 SL_DEV int sl_wave_min(int v)
 {
 #pragma unroll
-    for (int l = 0; l < 6; ++l) v = min(v, sl_partner(v, l));
-    return sl_uniform(v);
+    for (int l = 0; l < 4; ++l) v = min(v, sl_partner(v, l));
+    return min(min(__builtin_amdgcn_readlane(v, 0), __builtin_amdgcn_readlane(v, 16)),
+               min(__builtin_amdgcn_readlane(v, 32), __builtin_amdgcn_readlane(v, 48)));
 }
 
 SL_DEV int sl_pow2ceil(int n)
@@ -145,6 +147,25 @@ SL_DEV double sl_lane0(double v)
     return __hiloint2double(hi, lo);
 }
 
+SL_DEV double sl_lane(double v, int l)
+{
+    int lo = __builtin_amdgcn_readlane(__double2loint(v), l);
+    int hi = __builtin_amdgcn_readlane(__double2hiint(v), l);
+    return __hiloint2double(hi, lo);
+}
+
+// sl_wave_tree's result in lane 0, as a wave-uniform value.  The four levels inside a row of
+// 16 lanes leave each row's sum in every lane of the row; the two levels above them pair rows
+// (0, 1), (2, 3) and then the pairs, read lane by lane instead of being shuffled.
+SL_DEV double sl_wave_tree0(double v, int levels)
+{
+    v = sl_wave_tree(v, min(levels, 4));
+    if (levels <= 4) return sl_lane0(v);
+    const double r01 = sl_lane(v, 0) + sl_lane(v, 16);
+    if (levels == 5) return r01;
+    return r01 + (sl_lane(v, 32) + sl_lane(v, 48));
+}
+
 // Fixed summation trees of one chunk's k per-entry values x and of their squares (the leaves
 // of the two-level sums), both at once so that the two chains of cross-lane steps overlap.
 // Entry p lives in lane p % 64, slot p / 64; x_of(slot) returns this lane's value for that
@@ -158,8 +179,8 @@ SL_DEV void sl_chunk_trees(int k, int lane, double *scratch, F x_of, double &sum
         int levels = 0;
         while ((1 << levels) < P) ++levels;
         const double x = x_of(0);
-        sum_x = sl_lane0(sl_wave_tree(x, levels));
-        sum_xx = sl_lane0(sl_wave_tree(x * x, levels));
+        sum_x = sl_wave_tree0(x, levels);
+        sum_xx = sl_wave_tree0(x * x, levels);
         return;
     }
     const int slots = P / 64;           // power of two, <= 64
@@ -169,14 +190,14 @@ SL_DEV void sl_chunk_trees(int k, int lane, double *scratch, F x_of, double &sum
     if (lane >= used && lane < slots) sx[lane] = 0.0, sxx[lane] = 0.0;
     for (int s = 0; s < used; ++s) {
         const double x = x_of(s);
-        const double t = sl_wave_tree(x, 6), tt = sl_wave_tree(x * x, 6);
+        const double t = sl_wave_tree0(x, 6), tt = sl_wave_tree0(x * x, 6);
         if (lane == 0) sx[s] = t, sxx[s] = tt;
     }
     sl_wave_sync();
     const double v = lane < slots ? sx[lane] : 0.0, vv = lane < slots ? sxx[lane] : 0.0;
     int levels = 0;
     while ((1 << levels) < slots) ++levels;
-    sum_x = sl_lane0(sl_wave_tree(v, levels));
-    sum_xx = sl_lane0(sl_wave_tree(vv, levels));
+    sum_x = sl_wave_tree0(v, levels);
+    sum_xx = sl_wave_tree0(vv, levels);
     sl_wave_sync();
 }

@@ -736,9 +736,20 @@ __global__ void SL_SELECT_BOUNDS k_select(SelectArgs A)
     // ---------------------------------------------------------------- outputs
     unsigned char *rec = A.payload + d.rec_off;
 
-    for (int p = lane; p < k; p += 64) A.vals[c * k + p] = sel_val[p];
-    if (bits == 32)   // unquantized: the values themselves follow the indices (4-byte aligned)
-        for (int p = lane; p < k; p += 64) reinterpret_cast<float *>(rec + 3 * k / 2)[p] = sel_val[p];
+    // the selected values, four LDS reads in flight per round of stores
+    float *recv = bits == 32 ? reinterpret_cast<float *>(rec + 3 * k / 2) : nullptr;   // unquantized: the values
+                                                              // themselves follow the indices (4-byte aligned)
+    for (int p0 = lane; p0 < k; p0 += 256) {
+        float t[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) t[u] = p0 + 64 * u < k ? sel_val[p0 + 64 * u] : 0.f;
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+            if (p0 + 64 * u < k) {
+                A.vals[c * k + p0 + 64 * u] = t[u];
+                if (recv) recv[p0 + 64 * u] = t[u];
+            }
+    }
 
     if ((k & 15) == 0) {
         // 12-bit index stream, one 32-bit word per lane (records are 4-byte aligned)
