@@ -166,38 +166,60 @@ SL_DEV double sl_wave_tree0(double v, int levels)
     return r01 + (sl_lane(v, 32) + sl_lane(v, 48));
 }
 
-// Fixed summation trees of one chunk's k per-entry values x and of their squares (the leaves
-// of the two-level sums), both at once so that the two chains of cross-lane steps overlap.
-// Entry p lives in lane p % 64, slot p / 64; x_of(slot) returns this lane's value for that
-// slot (+0.0 beyond k).  Each sequence is padded with +0.0 to P = pow2ceil(k) and reduced by
-// adjacent pairs.  `scratch` is a 128-double LDS array private to the wave.  The results are uniform.
-template <class F>
-SL_DEV void sl_chunk_trees(int k, int lane, double *scratch, F x_of, double &sum_x, double &sum_xx)
+// Adjacent-pair trees of x and x*x over the E consecutive floats at v (E a power of two, v
+// aligned for the widest read used); entries from index n on count as +0.0 and are not read
+// (n a multiple of 4, or of 2 when E = 2: a read never straddles n).
+template <int E>
+SL_DEV void sl_lane_trees(const float *v, int n, double &sx, double &sxx)
+{
+    if constexpr (E == 2) {
+        float2 q = make_float2(0.f, 0.f);
+        if (n > 0) q = *reinterpret_cast<const float2 *>(v);
+        const double x0 = q.x, x1 = q.y;
+        sx = x0 + x1;
+        sxx = x0 * x0 + x1 * x1;
+    } else if constexpr (E == 4) {
+        float4 q = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (n > 0) q = *reinterpret_cast<const float4 *>(v);
+        const double x0 = q.x, x1 = q.y, x2 = q.z, x3 = q.w;
+        sx = (x0 + x1) + (x2 + x3);
+        sxx = (x0 * x0 + x1 * x1) + (x2 * x2 + x3 * x3);
+    } else {
+        double a, aa, b, bb;
+        sl_lane_trees<E / 2>(v, n, a, aa);
+        sl_lane_trees<E / 2>(v + E / 2, n - E / 2, b, bb);
+        sx = a + b;
+        sxx = aa + bb;
+    }
+}
+
+// Fixed summation trees of one chunk's k selected values x (canonical order, in LDS at
+// `val`, 16-byte aligned; k a multiple of 4) and of their squares: the leaves of the
+// two-level sums.  Each sequence is padded with +0.0 to P = pow2ceil(k) and reduced by adjacent
+// pairs.  Lane l owns the P/64 consecutive entries from l*P/64 on - a subtree, summed in
+// the lane - and one butterfly over the lanes finishes both trees.  MAXE bounds P/64 (the
+// instantiation's largest k / 64, rounded up to a power of two).  The results are uniform.
+template <int MAXE>
+SL_DEV void sl_chunk_trees(int k, int lane, const float *val, double &sum_x, double &sum_xx)
 {
     const int P = sl_pow2ceil(k);
+    double x = 0.0, xx = 0.0;
+    int levels = 6;
     if (P <= 64) {
-        int levels = 0;
+        levels = 0;
         while ((1 << levels) < P) ++levels;
-        const double x = x_of(0);
-        sum_x = sl_wave_tree0(x, levels);
-        sum_xx = sl_wave_tree0(x * x, levels);
-        return;
+        x = lane < k ? (double)val[lane] : 0.0;
+        xx = x * x;
+    } else {
+        const int E = P >> 6, n = k - lane * E;
+        const float *v = val + lane * E;
+        if (MAXE >= 2 && E == 2) sl_lane_trees<2>(v, n, x, xx);
+        else if (MAXE >= 4 && E == 4) sl_lane_trees<4>(v, n, x, xx);
+        else if (MAXE >= 8 && E == 8) sl_lane_trees<8>(v, n, x, xx);
+        else if (MAXE >= 16 && E == 16) sl_lane_trees<16>(v, n, x, xx);
+        else if (MAXE >= 32 && E == 32) sl_lane_trees<32>(v, n, x, xx);
+        else if (MAXE >= 64 && E == 64) sl_lane_trees<64>(v, n, x, xx);
     }
-    const int slots = P / 64;           // power of two, <= 64
-    const int used = (k + 63) / 64;
-    double *sx = scratch, *sxx = scratch + 64;
-    sl_wave_sync();
-    if (lane >= used && lane < slots) sx[lane] = 0.0, sxx[lane] = 0.0;
-    for (int s = 0; s < used; ++s) {
-        const double x = x_of(s);
-        const double t = sl_wave_tree0(x, 6), tt = sl_wave_tree0(x * x, 6);
-        if (lane == 0) sx[s] = t, sxx[s] = tt;
-    }
-    sl_wave_sync();
-    const double v = lane < slots ? sx[lane] : 0.0, vv = lane < slots ? sxx[lane] : 0.0;
-    int levels = 0;
-    while ((1 << levels) < slots) ++levels;
-    sum_x = sl_wave_tree0(v, levels);
-    sum_xx = sl_wave_tree0(vv, levels);
-    sl_wave_sync();
+    sum_x = sl_wave_tree0(x, levels);
+    sum_xx = sl_wave_tree0(xx, levels);
 }

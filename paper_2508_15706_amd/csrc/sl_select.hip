@@ -272,14 +272,13 @@ __global__ void SL_SELECT_BOUNDS k_select(SelectArgs A)
     const SlChunkDesc d = A.desc[c];
     const int k = A.k;
 
-    // LDS of this wave: [candidates 8*CAND_CAP][sel_val 4k][sel_idx 2k][tree scratch 1024]
+    // LDS of this wave: [candidates 8*CAND_CAP][sel_val 4k][sel_idx 2k]
     uint2 *cand = reinterpret_cast<uint2 *>(smem);
     constexpr int CAND_CAP = cand_cap(GPL), CAND_SLOTS = CAND_CAP / 64;
     // (the general route's key list takes the place of the candidates: 2 KB when GPL = 0)
     const size_t cand_bytes = GPL > 0 ? sizeof(uint2) * CAND_CAP : sizeof(int) * SL_SELECT_LIST_CAP;
     float *sel_val = reinterpret_cast<float *>(smem + cand_bytes);
     unsigned short *sel_idx = reinterpret_cast<unsigned short *>(smem + cand_bytes + 4 * (size_t)k);
-    double *scratch = reinterpret_cast<double *>(smem + cand_bytes + ((6 * (size_t)k + 7) & ~(size_t)7));
 
     float *ec = A.e + d.base;
     const float *dc = SUBK ? nullptr : A.delta + d.base;
@@ -783,10 +782,8 @@ __global__ void SL_SELECT_BOUNDS k_select(SelectArgs A)
 
     // per-chunk leaves of the quantizer's mean / variance sums
     double s1, s2;
-    sl_chunk_trees(k, lane, scratch, [&](int s) {
-        const int p = s * 64 + lane;
-        return p < k ? (double)sel_val[p] : 0.0;
-    }, s1, s2);
+    constexpr int MAXE = GPL == 0 ? 64 : GPL <= 2 ? 1 : GPL / 2;      // pow2ceil(largest k served) / 64
+    sl_chunk_trees<MAXE>(k, lane, sel_val, s1, s2);
     if (lane == 0) {
         A.leafA[c] = s1;
         A.leafA[A.n_chunks + c] = s2;
@@ -828,7 +825,6 @@ static int launch_select(const sl_plan *p, float *e, const float *delta, const f
     {
         size_t b = pruned ? sizeof(uint2) * cand_cap(k > 256 ? 16 : 8) : sizeof(int) * SL_SELECT_LIST_CAP;
         b += (6 * (size_t)k + 7) & ~(size_t)7;
-        b += 128 * sizeof(double);
         b = (b + 15) & ~(size_t)15;
         // k > 256: a pending record of whole words and whole groups of eight entries is staged in LDS
         A.pend_words = pending && k > 256 && (p->rec_bytes & 3) == 0 && (k & 7) == 0 && p->rec_bytes <= 8192;
