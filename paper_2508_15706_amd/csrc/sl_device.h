@@ -90,6 +90,12 @@ SL_DEV double sl_dpp(double v)
 {
     return __hiloint2double(sl_dpp<CTRL>(__double2hiint(v)), sl_dpp<CTRL>(__double2loint(v)));
 }
+template <int CTRL>
+SL_DEV unsigned long long sl_dpp(unsigned long long v)
+{
+    const unsigned lo = (unsigned)sl_dpp<CTRL>((int)(unsigned)v), hi = (unsigned)sl_dpp<CTRL>((int)(unsigned)(v >> 32));
+    return ((unsigned long long)hi << 32) | lo;
+}
 // Level l (0..5) of a butterfly over the wave: the value of the partner lane.
 template <class T>
 SL_DEV T sl_partner(T v, int l)

@@ -144,8 +144,10 @@ SL_DEV void stack_push(BinStacksT<LV> &s, int m, double v0, double v1, double v2
 
 constexpr int CODE_WAVES = 2;        // waves per workgroup
 #ifndef SL_CODES_WAVE_FROM
-#define SL_CODES_WAVE_FROM 512        // k from which a wave, not a lane, owns a chunk in kernel C
+#define SL_CODES_WAVE_FROM 129        // k from which a wave, not a lane, owns a chunk in kernel C (at least 129:
+                                      // a lane owns at least four entries there)
 #endif
+static_assert(SL_CODES_WAVE_FROM >= 129, "the wave kernel reads four entries per lane at least");
 constexpr int CODE_PITCH = 65;       // LDS row pitch in floats: conflict-free column reads
 
 // One LANE per chunk, 64 consecutive chunks per wave.  The selected values of
@@ -242,7 +244,7 @@ __global__ void __launch_bounds__(64 * CODE_WAVES, WAVES_PER_EU) k_codes(CodeArg
 }
 
 // ------------------------------------------------------------------ kernel C at high densities
-// From k = 512 a lane per chunk has too long a walk (and too deep a stack).  Here one WAVE owns
+// Above k = 128 a lane per chunk has too long a walk (and too deep a stack).  Here one WAVE owns
 // a chunk: lane l takes the E = pow2ceil(k)/64 consecutive entries E*l .., folds them through
 // the same binary-counter stacks (log2(E) levels, resolved at compile time), and the upper
 // levels of the adjacent-pair tree are a butterfly over the lanes (a + b = b + a bit for bit,
@@ -251,7 +253,7 @@ __global__ void __launch_bounds__(64 * CODE_WAVES, WAVES_PER_EU) k_codes(CodeArg
 template <int E>
 __global__ void __launch_bounds__(256) k_codes_wave(CodeArgs A)
 {
-    constexpr int LV = (E == 8 ? 3 : E == 16 ? 4 : E == 32 ? 5 : 6) + 1;
+    constexpr int LV = (E == 4 ? 2 : E == 8 ? 3 : E == 16 ? 4 : E == 32 ? 5 : 6) + 1;
     const int lane = threadIdx.x & 63, k = A.k;
     const int wave = sl_uniform((int)(threadIdx.x >> 6));
     const long long c = (long long)blockIdx.x * (blockDim.x >> 6) + wave;
@@ -293,12 +295,14 @@ __global__ void __launch_bounds__(256) k_codes_wave(CodeArgs A)
     double r0 = st.a[LV - 1], r1 = st.b[LV - 1], r2 = st.c[LV - 1], r3 = st.d[LV - 1];
     r0 = sl_wave_tree(r0, 6), r1 = sl_wave_tree(r1, 6), r2 = sl_wave_tree(r2, 6), r3 = sl_wave_tree(r3, 6);
 #pragma unroll
-    for (int sft = 1; sft < 64; sft <<= 1) counts += __shfl_xor(counts, sft);
+    for (int l = 0; l < 6; ++l) counts += sl_partner(counts, l);
 
     // codes: E/4 bytes per lane at byte E/4 * lane of the code stream (whole bytes: k % 4 == 0)
     const int nbytes = min(E / 4, max(0, (k - m0) / 4));
     if ((k & 15) == 0 && nbytes == E / 4) {          // records of whole words: aligned stores
-        if constexpr (E == 8) {
+        if constexpr (E == 4) {
+            codes_out[lane] = (unsigned char)words[0];
+        } else if constexpr (E == 8) {
             reinterpret_cast<unsigned short *>(codes_out)[lane] = (unsigned short)words[0];
         } else {
 #pragma unroll
@@ -589,14 +593,15 @@ int slk_quantize(const sl_plan *p, float *e, int skip_residual, unsigned char *p
         default:
             if (k <= 64) {
                 hipLaunchKernelGGL((k_codes<7, 32, 4>), dim3(nblk), dim3(64 * CODE_WAVES), 0, st, C);
-            } else if (k <= 256) {
+            } else if (k <= 256 && k < SL_CODES_WAVE_FROM) {
                 hipLaunchKernelGGL((k_codes<9, 32, 4>), dim3(nblk), dim3(64 * CODE_WAVES), 0, st, C);
             } else if (k < SL_CODES_WAVE_FROM) {
                 hipLaunchKernelGGL((k_codes<13, 64, 2>), dim3(nblk), dim3(64 * CODE_WAVES), 0, st, C);
             } else {
                 // a wave per chunk, E = pow2ceil(k) / 64 entries per lane
                 const dim3 wgrid((unsigned)((p->n_chunks + 3) / 4)), wblock(256);
-                if (k <= 512) hipLaunchKernelGGL(k_codes_wave<8>, wgrid, wblock, 0, st, C);
+                if (k <= 256) hipLaunchKernelGGL(k_codes_wave<4>, wgrid, wblock, 0, st, C);
+                else if (k <= 512) hipLaunchKernelGGL(k_codes_wave<8>, wgrid, wblock, 0, st, C);
                 else if (k <= 1024) hipLaunchKernelGGL(k_codes_wave<16>, wgrid, wblock, 0, st, C);
                 else if (k <= 2048) hipLaunchKernelGGL(k_codes_wave<32>, wgrid, wblock, 0, st, C);
                 else hipLaunchKernelGGL(k_codes_wave<64>, wgrid, wblock, 0, st, C);
