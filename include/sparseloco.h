@@ -26,6 +26,9 @@
  *     kernels are enqueued on it and the call returns without synchronising;
  *   - the caller owns every buffer it passes; the library owns only sl_plan.
  *   - results are deterministic: the same inputs give the same bytes.
+ *   - one environment variable is read, at every sl_compress*: SL_CODES_WAVE_BELOW, the list
+ *     length in chunks below which the code kernel gives a chunk to a wavefront instead of a
+ *     lane at any k (default 32768).  A tuning knob: the bytes written are the same either way.
  */
 #ifndef SPARSELOCO_H
 #define SPARSELOCO_H

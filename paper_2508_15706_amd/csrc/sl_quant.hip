@@ -14,6 +14,8 @@
 // leaves, produced by kernels A and C) and a tree over the chunk leaves in
 // chunk order.  Both trees pad with +0.0 to a power of two and add adjacent
 // pairs, so the result does not depend on scheduling.
+#include <cstdlib>
+
 #include "sl_device.h"
 #include "sl_internal.h"
 
@@ -144,10 +146,12 @@ SL_DEV void stack_push(BinStacksT<LV> &s, int m, double v0, double v1, double v2
 
 constexpr int CODE_WAVES = 2;        // waves per workgroup
 #ifndef SL_CODES_WAVE_FROM
-#define SL_CODES_WAVE_FROM 129        // k from which a wave, not a lane, owns a chunk in kernel C (at least 129:
-                                      // a lane owns at least four entries there)
+#define SL_CODES_WAVE_FROM 129        // k from which a wave, not a lane, owns a chunk in kernel C
 #endif
-static_assert(SL_CODES_WAVE_FROM >= 129, "the wave kernel reads four entries per lane at least");
+#ifndef SL_CODES_WAVE_BELOW
+#define SL_CODES_WAVE_BELOW 32768     // ... and at any k on a list of fewer chunks than this: with a lane per chunk
+                                      // such a list leaves most of the chip without a wave
+#endif
 constexpr int CODE_PITCH = 65;       // LDS row pitch in floats: conflict-free column reads
 
 // One LANE per chunk, 64 consecutive chunks per wave.  The selected values of
@@ -244,7 +248,8 @@ __global__ void __launch_bounds__(64 * CODE_WAVES, WAVES_PER_EU) k_codes(CodeArg
 }
 
 // ------------------------------------------------------------------ kernel C at high densities
-// Above k = 128 a lane per chunk has too long a walk (and too deep a stack).  Here one WAVE owns
+// Above k = 128 a lane per chunk has too long a walk (and too deep a stack), and on a short list
+// it leaves most of the chip idle.  Here one WAVE owns
 // a chunk: lane l takes the E = pow2ceil(k)/64 consecutive entries E*l .., folds them through
 // the same binary-counter stacks (log2(E) levels, resolved at compile time), and the upper
 // levels of the adjacent-pair tree are a butterfly over the lanes (a + b = b + a bit for bit,
@@ -253,7 +258,7 @@ __global__ void __launch_bounds__(64 * CODE_WAVES, WAVES_PER_EU) k_codes(CodeArg
 template <int E>
 __global__ void __launch_bounds__(256) k_codes_wave(CodeArgs A)
 {
-    constexpr int LV = (E == 4 ? 2 : E == 8 ? 3 : E == 16 ? 4 : E == 32 ? 5 : 6) + 1;
+    constexpr int LV = (E == 1 ? 0 : E == 2 ? 1 : E == 4 ? 2 : E == 8 ? 3 : E == 16 ? 4 : E == 32 ? 5 : 6) + 1;
     const int lane = threadIdx.x & 63, k = A.k;
     const int wave = sl_uniform((int)(threadIdx.x >> 6));
     const long long c = (long long)blockIdx.x * (blockDim.x >> 6) + wave;
@@ -272,34 +277,66 @@ __global__ void __launch_bounds__(256) k_codes_wave(CodeArgs A)
     unsigned words[E / 16 > 0 ? E / 16 : 1];
 #pragma unroll
     for (int w = 0; w < (E / 16 > 0 ? E / 16 : 1); ++w) words[w] = 0u;
+    auto entry = [&](int j, float xf) {      // entry j of this lane (j a compile-time constant after unrolling)
+        const bool valid = m0 + j < k;
+        const double x = (double)xf;
+        const double dlt = x - mu;
+        const double dd = dlt * dlt;
+        const int code = dlt < 0.0 ? (dd > T ? 0 : 1) : (dd >= T ? 3 : 2);
+        counts += valid ? 1ull << (16 * code) : 0ull;
+        stack_push<0>(st, j, valid && code == 0 ? x : 0.0, valid && code == 1 ? x : 0.0,
+                      valid && code == 2 ? x : 0.0, valid && code == 3 ? x : 0.0);
+        words[j / 16] |= (valid ? (unsigned)code : 0u) << (2 * (j & 15));
+    };
+    if constexpr (E == 1) {
+        entry(0, m0 < k ? vin[m0] : 0.f);
+    } else if constexpr (E == 2) {
+        float2 v2 = make_float2(0.f, 0.f);
+        if (m0 < k) v2 = *reinterpret_cast<const float2 *>(vin + m0);              // k is a multiple of 4
+        entry(0, v2.x);
+        entry(1, v2.y);
+    } else {
 #pragma unroll
-    for (int j4 = 0; j4 < E; j4 += 4) {
-        float4 v4 = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (m0 + j4 < k) v4 = *reinterpret_cast<const float4 *>(vin + m0 + j4);    // k is a multiple of 4
-        const float xs[4] = {v4.x, v4.y, v4.z, v4.w};
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            const int j = j4 + q;
-            const bool valid = m0 + j < k;
-            const double x = (double)xs[q];
-            const double dlt = x - mu;
-            const double dd = dlt * dlt;
-            const int code = dlt < 0.0 ? (dd > T ? 0 : 1) : (dd >= T ? 3 : 2);
-            counts += valid ? 1ull << (16 * code) : 0ull;
-            stack_push<0>(st, j, valid && code == 0 ? x : 0.0, valid && code == 1 ? x : 0.0,
-                          valid && code == 2 ? x : 0.0, valid && code == 3 ? x : 0.0);
-            words[j / 16] |= (valid ? (unsigned)code : 0u) << (2 * (j & 15));
+        for (int j4 = 0; j4 < E; j4 += 4) {
+            float4 v4 = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (m0 + j4 < k) v4 = *reinterpret_cast<const float4 *>(vin + m0 + j4);
+            entry(j4 + 0, v4.x);
+            entry(j4 + 1, v4.y);
+            entry(j4 + 2, v4.z);
+            entry(j4 + 3, v4.w);
         }
     }
-    // the lane's subtree roots, then the levels above them across the lanes
+    // the lane's subtree roots, then the levels above them across the lanes: log2(pow2ceil(k) / E)
+    // of them (six, except at E = 1, where the padded sequence may be shorter than the wave)
+    int levels = 6;
+    if constexpr (E == 1) {
+        levels = 0;
+        while ((1 << levels) < k) ++levels;
+    }
     double r0 = st.a[LV - 1], r1 = st.b[LV - 1], r2 = st.c[LV - 1], r3 = st.d[LV - 1];
-    r0 = sl_wave_tree(r0, 6), r1 = sl_wave_tree(r1, 6), r2 = sl_wave_tree(r2, 6), r3 = sl_wave_tree(r3, 6);
+    r0 = sl_wave_tree(r0, levels), r1 = sl_wave_tree(r1, levels), r2 = sl_wave_tree(r2, levels),
+    r3 = sl_wave_tree(r3, levels);
 #pragma unroll
     for (int l = 0; l < 6; ++l) counts += sl_partner(counts, l);
 
     // codes: E/4 bytes per lane at byte E/4 * lane of the code stream (whole bytes: k % 4 == 0)
     const int nbytes = min(E / 4, max(0, (k - m0) / 4));
-    if ((k & 15) == 0 && nbytes == E / 4) {          // records of whole words: aligned stores
+    if constexpr (E < 4) {
+        // 4 / E lanes share a byte, 16 / E lanes a word: OR the lanes' bits together inside the row
+        constexpr int LW = 16 / E;                           // lanes per word
+        unsigned w = words[0] << (2 * E * (lane & (LW - 1)));
+        w |= (unsigned)sl_dpp<SL_DPP_XOR1>((int)w);
+        w |= (unsigned)sl_dpp<SL_DPP_XOR2>((int)w);
+        w |= (unsigned)sl_dpp<SL_DPP_HALF_MIRROR>((int)w);
+        if constexpr (E == 1) w |= (unsigned)sl_dpp<SL_DPP_MIRROR>((int)w);
+        if ((k & 15) == 0) {
+            if ((lane & (LW - 1)) == 0 && m0 < k) reinterpret_cast<unsigned *>(codes_out)[lane / LW] = w;
+        } else {
+            constexpr int LB = 4 / E;                        // lanes per byte
+            if ((lane & (LB - 1)) == 0 && m0 < k)
+                codes_out[lane / LB] = (unsigned char)(w >> (8 * ((lane & (LW - 1)) / LB)));
+        }
+    } else if ((k & 15) == 0 && nbytes == E / 4) {   // records of whole words: aligned stores
         if constexpr (E == 4) {
             codes_out[lane] = (unsigned char)words[0];
         } else if constexpr (E == 8) {
@@ -586,21 +623,29 @@ int slk_quantize(const sl_plan *p, float *e, int skip_residual, unsigned char *p
     C.k = k;
     const long long per_block = 64ll * CODE_WAVES;
     const unsigned nblk = (unsigned)((p->n_chunks + per_block - 1) / per_block);
+    // (the environment variable SL_CODES_WAVE_BELOW overrides the list length, for tests and tuning:
+    // both kernels write the same bytes)
+    long long wave_below = SL_CODES_WAVE_BELOW;
+    if (const char *env = std::getenv("SL_CODES_WAVE_BELOW"))
+        if (*env) wave_below = std::atoll(env);
+    const bool by_wave = k >= SL_CODES_WAVE_FROM || p->n_chunks < wave_below;
     switch (p->bits) {
         case 1: hipLaunchKernelGGL(k_codes_b<1>, dim3(nblk), dim3(64 * CODE_WAVES), 0, st, C); break;
         case 3: hipLaunchKernelGGL(k_codes_b<3>, dim3(nblk), dim3(64 * CODE_WAVES), 0, st, C); break;
         case 4: hipLaunchKernelGGL(k_codes_b<4>, dim3(nblk), dim3(64 * CODE_WAVES), 0, st, C); break;
         default:
-            if (k <= 64) {
+            if (k <= 64 && !by_wave) {
                 hipLaunchKernelGGL((k_codes<7, 32, 4>), dim3(nblk), dim3(64 * CODE_WAVES), 0, st, C);
-            } else if (k <= 256 && k < SL_CODES_WAVE_FROM) {
+            } else if (k <= 256 && !by_wave) {
                 hipLaunchKernelGGL((k_codes<9, 32, 4>), dim3(nblk), dim3(64 * CODE_WAVES), 0, st, C);
-            } else if (k < SL_CODES_WAVE_FROM) {
+            } else if (!by_wave) {
                 hipLaunchKernelGGL((k_codes<13, 64, 2>), dim3(nblk), dim3(64 * CODE_WAVES), 0, st, C);
             } else {
                 // a wave per chunk, E = pow2ceil(k) / 64 entries per lane
                 const dim3 wgrid((unsigned)((p->n_chunks + 3) / 4)), wblock(256);
-                if (k <= 256) hipLaunchKernelGGL(k_codes_wave<4>, wgrid, wblock, 0, st, C);
+                if (k <= 64) hipLaunchKernelGGL(k_codes_wave<1>, wgrid, wblock, 0, st, C);
+                else if (k <= 128) hipLaunchKernelGGL(k_codes_wave<2>, wgrid, wblock, 0, st, C);
+                else if (k <= 256) hipLaunchKernelGGL(k_codes_wave<4>, wgrid, wblock, 0, st, C);
                 else if (k <= 512) hipLaunchKernelGGL(k_codes_wave<8>, wgrid, wblock, 0, st, C);
                 else if (k <= 1024) hipLaunchKernelGGL(k_codes_wave<16>, wgrid, wblock, 0, st, C);
                 else if (k <= 2048) hipLaunchKernelGGL(k_codes_wave<32>, wgrid, wblock, 0, st, C);
