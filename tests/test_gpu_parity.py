@@ -67,15 +67,13 @@ def check_compress(sl, oracle, descs, n, k, e0, delta, beta, flags=0, what=""):
 
 
 # --------------------------------------------------------------------------- compress
-@pytest.mark.parametrize("lane_codes", [False, True])
-@pytest.mark.parametrize("k", [4, 8, 20, 32, 64, 128, 256, 512, 1000])
+@pytest.mark.parametrize("k,lane_codes", [(k, False) for k in (4, 8, 20, 32, 64, 128, 256, 512, 1000)] +
+                         [(k, True) for k in (4, 8, 20, 32, 64, 128)])
 def test_compress_small_list_all_k_paths(sl, oracle, k, lane_codes, monkeypatch):
     """Several tiles, ragged edges in both directions, 16-column matrix, 1-D tails;
     k covers every pruning width, the byte-wise record writer and the unpruned path.
     Up to k = 128 the code kernel is chosen by the length of the list: both choices are run."""
     if lane_codes:
-        if k > 128:
-            pytest.skip("one code kernel above k = 128")
         monkeypatch.setenv("SL_CODES_WAVE_BELOW", "0")
     if k <= 256:      # smallest chunk: 22 x 18 = 396 elements
         shapes = [(150, 210, TILE), (1, 9000, FLAT), (1024, 16, TILE), (64, 64, TILE),
