@@ -28,6 +28,9 @@ namespace {
 #ifndef SL_APPLY_OCTETS_FROM
 #define SL_APPLY_OCTETS_FROM 256   // k from which a lane decodes eight entries at a time
 #endif
+#ifndef SL_APPLY_QUADS_FROM
+#define SL_APPLY_QUADS_FROM 136    // ... or four (2-bit records with many entries to decode per chunk)
+#endif
 #ifndef SL_APPLY_PF1
 #define SL_APPLY_PF1 16     // words per lane fetched ahead of the theta loads on the entry-by-entry route (2-bit codes)
 #endif
@@ -56,6 +59,8 @@ struct ApplyArgs {
     int R, k;
     int bits, hdr_bytes, rec_bytes;   // value width and the sizes that follow from it
     int batch;               // records staged per round
+    int quads;               // eight-entry route, 2-bit format: four entries per lane instead (up to k = 256: a
+                             // worker's record then spans up to 64 lanes instead of 32, in one round)
     // x / d for the staging loops without a division: __umulhi(x, floor(2^32 / d) + 1) is
     // exact while x * d < 2^32 (x < 16384 here); d = words per (table + record padded to whole words)
     unsigned magic_src;
@@ -276,6 +281,33 @@ __global__ void __launch_bounds__(256) k_apply(ApplyArgs A)
                     const unsigned char *codes = base + hdr + 3 * k / 2;
                     float l0 = 0.f, l1 = 0.f, l2 = 0.f, l3 = 0.f;
                     if (TWO_BIT) l0 = lutp[0], l1 = lutp[1], l2 = lutp[2], l3 = lutp[3];
+                    if (TWO_BIT && A.quads) {
+                        // four consecutive entries = 48 bits that start at bit 0 or 16 of a word
+                        for (int q = lane; q < (k >> 2); q += 64) {
+                            const int wi = (3 * q) >> 1;
+                            const unsigned wa = iw[wi], wb = iw[wi + 1], sh = 16u * (q & 1);
+                            const unsigned lo = __builtin_amdgcn_alignbit(wb, wa, sh), hi = wb >> sh;
+                            unsigned jq[4];
+                            jq[0] = lo & 0xFFFu;
+                            jq[1] = (lo >> 12) & 0xFFFu;
+                            jq[2] = (lo >> 24) | ((hi & 0xFu) << 8);
+                            jq[3] = (hi >> 4) & 0xFFFu;
+                            const unsigned cw = codes[q];
+                            float qv[4], tq[4];
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) {
+                                const unsigned cde = cw >> (2 * e);
+                                const float lo_v = (cde & 1u) ? l1 : l0, hi_v = (cde & 1u) ? l3 : l2;
+                                qv[e] = (cde & 2u) ? hi_v : lo_v;
+                            }
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) tq[e] = acc[jq[e] & (ACC_FLOATS - 1)];
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) acc[jq[e] & (ACC_FLOATS - 1)] = tq[e] + qv[e];
+                        }
+                        sl_wave_sync();       // worker r is complete before worker r+1 is added
+                        continue;
+                    }
                     for (int o = lane; o < (k >> 3); o += 64) {
                         const unsigned w0 = iw[3 * o], w1 = iw[3 * o + 1], w2 = iw[3 * o + 2];
                         unsigned jj[8];
@@ -597,12 +629,21 @@ int slk_apply(const sl_plan *p, float *theta, float *mom, float mu, const void *
     const int rec_pad = ((p->rec_bytes + 3) & ~3) + p->hdr_bytes;
     // at most 16 KB of staged records; 4 KB on the eight-entry route (measured against 2, 8 and 16 KB:
     // more waves per compute unit outweigh the extra staging rounds), and whenever a record alone is large
-    const bool octets = p->k >= SL_APPLY_OCTETS_FROM && (p->k & 7) == 0;
+    // ... and, four entries per lane, 2-bit records from k = 136 when there is much to decode (measured at
+    // 16 workers: k = 160 0.90 -> 0.83 ms, k = 192 1.31 -> 0.86 ms; below 2048 entries per chunk the two-halves
+    // route is as fast or faster)
+    const bool octets = (p->k & 7) == 0 &&
+                        (p->k >= SL_APPLY_OCTETS_FROM ||
+                         (p->bits == 2 && p->k >= SL_APPLY_QUADS_FROM && (long long)R * p->k >= 2048));
     int batch = (rec_pad > 1024 || octets ? SL_APPLY_BIG_STAGE : 16384) / rec_pad;
     if (batch < 1) batch = 1;
     if (batch > R) batch = R;
     A.batch = batch;
     A.magic_src = (unsigned)(0x100000000ull / (unsigned)(rec_pad >> 2) + 1);
+#ifndef SL_APPLY_QUADS_BELOW
+#define SL_APPLY_QUADS_BELOW 257
+#endif
+    A.quads = octets && p->bits == 2 && p->k < SL_APPLY_QUADS_BELOW;
     for (int r = 0; r < SL_MAX_WORKERS; ++r)
         A.payload[r] = r < R ? static_cast<const unsigned char *>(payloads[r]) : nullptr;
     A.n_chunks = p->n_chunks;

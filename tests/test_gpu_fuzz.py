@@ -62,7 +62,7 @@ def test_random_configuration(sl, oracle, case, monkeypatch):
     if case % 2:      # short lists take the wave-per-chunk code kernel: every other case forces the other one
         monkeypatch.setenv("SL_CODES_WAVE_BELOW", "0")
     bits = int(rng.choice([1, 2, 2, 2, 3, 4, 32]))
-    k = int(rng.choice([4, 8, 12, 16, 32, 40, 64, 100, 128, 256, 320, 512, 520, 1024, 2048]))
+    k = int(rng.choice([4, 8, 12, 16, 32, 40, 64, 100, 128, 136, 160, 200, 248, 256, 320, 512, 520, 1024, 2048]))
     if bits != 2:
         k = max(8, k // 8 * 8)
     descs, n = [], 0

@@ -298,7 +298,7 @@ def test_apply_matches_oracle(sl, oracle, R, k, lr):
     assert_f32_close(theta.cpu().numpy(), want, f"theta R={R}")
 
 
-@pytest.mark.parametrize("k", [16, 32, 64, 128, 256])
+@pytest.mark.parametrize("k", [16, 32, 64, 128, 136, 160, 200, 248, 256])
 def test_apply_every_worker_count_boundary(sl, oracle, k):
     """The aggregate fetches the first words of the records ahead of theta, stages the rest in rounds,
     and switches its decode route and the number of passes with R*k: worker counts on both sides of
