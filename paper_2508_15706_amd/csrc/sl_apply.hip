@@ -31,6 +31,9 @@ namespace {
 #ifndef SL_APPLY_QUADS_FROM
 #define SL_APPLY_QUADS_FROM 136    // ... or four (2-bit records with many entries to decode per chunk)
 #endif
+#ifndef SL_APPLY_QUADS_ENTRIES
+#define SL_APPLY_QUADS_ENTRIES 2048     // ... R * k from which that holds below k = 256
+#endif
 #ifndef SL_APPLY_PF1
 #define SL_APPLY_PF1 16     // words per lane fetched ahead of the theta loads on the entry-by-entry route (2-bit codes)
 #endif
@@ -634,7 +637,7 @@ int slk_apply(const sl_plan *p, float *theta, float *mom, float mu, const void *
     // route is as fast or faster)
     const bool octets = (p->k & 7) == 0 &&
                         (p->k >= SL_APPLY_OCTETS_FROM ||
-                         (p->bits == 2 && p->k >= SL_APPLY_QUADS_FROM && (long long)R * p->k >= 2048));
+                         (p->bits == 2 && p->k >= SL_APPLY_QUADS_FROM && (long long)R * p->k >= SL_APPLY_QUADS_ENTRIES));
     int batch = (rec_pad > 1024 || octets ? SL_APPLY_BIG_STAGE : 16384) / rec_pad;
     if (batch < 1) batch = 1;
     if (batch > R) batch = R;
