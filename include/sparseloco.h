@@ -46,7 +46,9 @@ typedef enum {
     SL_ERR_BAD_PAYLOAD = -2, /* sl_payload_validate found a malformed record        */
     SL_ERR_HIP = -3,         /* a HIP runtime call failed; see sl_last_hip_error()  */
     SL_ERR_NOMEM = -4,       /* host or device allocation failed (plan creation)    */
-    SL_ERR_DEVICE = -5       /* current device differs from the plan's device       */
+    SL_ERR_DEVICE = -5,      /* current device differs from the plan's device       */
+    SL_ERR_TOO_LARGE = -6    /* sl_compress_noalloc: the plan needs more scratch
+                                than SL_NOALLOC_SCRATCH_BYTES                      */
 } sl_status;
 
 enum { SL_LAYOUT_FLAT = 0,    /* chunks are runs of 4096 consecutive elements      */
@@ -143,6 +145,27 @@ size_t sl_workspace_bytes(const sl_plan *plan);
  * read nor written. */
 int sl_compress(sl_plan *plan, float *e, const float *delta, float beta, int flags,
                 const void *pending, void *payload, void *workspace, void *stream);
+
+/* sl_compress for callers that cannot allocate device memory or bring a
+ * workspace of their own: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  The scratch that sl_compress takes from its
+ * `workspace` argument lives in a device array inside the library,
+ * SL_NOALLOC_SCRATCH_BYTES per GPU, held from the moment the library is loaded
+ * until the process ends.  The call itself allocates and frees nothing, on the
+ * host or on the device, and launches the same kernels as sl_compress: payload
+ * and e are bit-identical to sl_compress's.
+ * Arguments and errors as sl_compress (no `workspace`), and in addition
+ *   SL_ERR_TOO_LARGE  sl_workspace_bytes(plan) > SL_NOALLOC_SCRATCH_BYTES
+ *                     (64 MiB: lists of up to about 200,000 chunks at k = 64);
+ *                     nothing is launched.
+ * Every call on a GPU uses that GPU's one array, which keeps the previous call's
+ * contents; nothing in it has to be cleared between calls (each section is
+ * written before it is read).  Two calls whose kernels may overlap on one GPU -
+ * two streams, two threads, two plans - race on it: keep such calls on one
+ * stream, or give the others a workspace of their own through sl_compress. */
+enum { SL_NOALLOC_SCRATCH_BYTES = 64 * 1024 * 1024 };
+int sl_compress_noalloc(sl_plan *plan, float *e, const float *delta, float beta, int flags,
+                        const void *pending, void *payload, void *stream);
 
 /* sl_compress with the pseudo-gradient formed on the fly (Section 3.1 and
  * Algorithm 1, "Pseudo-gradient": delta = theta_outer - theta_local, the

@@ -22,6 +22,8 @@ SL_COMPRESS_DEFAULT = 0
 SL_COMPRESS_EF_FROZEN = 1
 SL_COMPRESS_DEFER_RESIDUAL = 2
 SL_MAX_WORKERS = 64
+SL_NOALLOC_SCRATCH_BYTES = 64 * 1024 * 1024
+SL_ERR_TOO_LARGE = -6
 
 EXPORTS = [
     "sl_plan_create", "sl_plan_destroy", "sl_plan_num_chunks", "sl_plan_num_elements",
@@ -31,7 +33,7 @@ EXPORTS = [
     "sl_rice_max_bytes", "sl_rice_encode", "sl_rice_decode", "sl_compress_params",
     "sl_payload_validate", "sl_plan_create_bits", "sl_plan_value_bits", "sl_pack_indices_bits",
     "sl_lom_direction", "sl_dense_avg_apply", "sl_decompress_avg_apply_nesterov", "sl_sub_topk",
-    "sl_compress_random_k",
+    "sl_compress_random_k", "sl_compress_noalloc",
 ]
 PROF_PHASES = ["select", "stats", "codes", "lut", "residual", "apply"]
 
@@ -92,6 +94,8 @@ def lib():
         L.sl_workspace_bytes.argtypes = [vp]
         L.sl_compress.restype = i32
         L.sl_compress.argtypes = [vp, vp, vp, C.c_float, i32, vp, vp, vp, vp]
+        L.sl_compress_noalloc.restype = i32
+        L.sl_compress_noalloc.argtypes = [vp, vp, vp, C.c_float, i32, vp, vp, vp]
         L.sl_compress_random_k.restype = i32
         L.sl_compress_random_k.argtypes = [vp, vp, vp, C.c_float, i32, vp, vp, vp, C.c_uint32, vp]
         L.sl_compress_params.restype = i32
@@ -220,6 +224,17 @@ def sl_compress(plan: Plan, e: Optional[torch.Tensor], delta: torch.Tensor, beta
                            _stream_ptr(stream))
     if st:
         raise SparseLoCoError("sl_compress", st)
+
+
+def sl_compress_noalloc(plan: Plan, e: Optional[torch.Tensor], delta: torch.Tensor, beta: float,
+                        payload: torch.Tensor, flags: int = SL_COMPRESS_DEFAULT,
+                        pending: Optional[torch.Tensor] = None, stream=None) -> None:
+    """sl_compress with the library's own fixed scratch array in place of a workspace."""
+    st = lib().sl_compress_noalloc(plan.handle, _dev_ptr(e, torch.float32), _dev_ptr(delta, torch.float32),
+                                   float(beta), int(flags), _dev_ptr(pending, torch.uint8),
+                                   _dev_ptr(payload, torch.uint8), _stream_ptr(stream))
+    if st:
+        raise SparseLoCoError("sl_compress_noalloc", st)
 
 
 def sl_compress_random_k(plan: Plan, e: Optional[torch.Tensor], delta: torch.Tensor, beta: float,

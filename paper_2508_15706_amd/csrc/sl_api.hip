@@ -41,6 +41,7 @@ const char *sl_strerror(int status)
         case SL_ERR_HIP: return "HIP runtime error";
         case SL_ERR_NOMEM: return "out of memory";
         case SL_ERR_DEVICE: return "plan belongs to another device";
+        case SL_ERR_TOO_LARGE: return "plan needs more scratch memory than the entry point without allocations holds";
         default: return "unknown status";
     }
 }
@@ -189,6 +190,12 @@ int sl_plan_create_bits(const sl_tensor *tensors, int n_tensors, int k, int valu
         delete p;
         return hip_fail(err);
     }
+    {
+        // the scratch array of sl_compress_noalloc: looked up now, with the plan's device current, so that
+        // the entry point itself has nothing left to set up (a failure here is reported by that call)
+        void *unused = nullptr;
+        (void)sl_noalloc_scratch(p->device, &unused);
+    }
     p->max_lds = 65536;
     {
         int v = 0;
@@ -258,9 +265,11 @@ static int check_device(const sl_plan *p)
 
 static bool misaligned(const void *ptr, size_t a) { return ((uintptr_t)ptr & (a - 1)) != 0; }
 
-static int compress_impl(sl_plan *p, float *e, const float *delta, const float *theta_local, float beta,
-                         int flags, const void *pending, void *payload, void *workspace, void *stream,
-                         bool random = false, unsigned seed = 0u)
+}  // extern "C"
+
+int sl_compress_impl(sl_plan *p, float *e, const float *delta, const float *theta_local, float beta,
+                     int flags, const void *pending, void *payload, void *workspace, void *stream,
+                     bool random, unsigned seed)
 {
     if (!p || !delta || !payload || !workspace) return SL_ERR_INVALID_ARG;
     if (flags & ~(SL_COMPRESS_EF_FROZEN | SL_COMPRESS_DEFER_RESIDUAL)) return SL_ERR_INVALID_ARG;
@@ -290,10 +299,12 @@ static int compress_impl(sl_plan *p, float *e, const float *delta, const float *
     return slk_quantize(p, e, frozen || defer, pay, ws, st);
 }
 
+extern "C" {
+
 int sl_compress(sl_plan *p, float *e, const float *delta, float beta, int flags, const void *pending,
                 void *payload, void *workspace, void *stream)
 {
-    return compress_impl(p, e, delta, nullptr, beta, flags, pending, payload, workspace, stream);
+    return sl_compress_impl(p, e, delta, nullptr, beta, flags, pending, payload, workspace, stream);
 }
 
 int sl_compress_params(sl_plan *p, float *e, const float *theta_outer, const float *theta_local,
@@ -301,13 +312,13 @@ int sl_compress_params(sl_plan *p, float *e, const float *theta_outer, const flo
                        void *stream)
 {
     if (!theta_local) return SL_ERR_INVALID_ARG;
-    return compress_impl(p, e, theta_outer, theta_local, beta, flags, pending, payload, workspace, stream);
+    return sl_compress_impl(p, e, theta_outer, theta_local, beta, flags, pending, payload, workspace, stream);
 }
 
 int sl_compress_random_k(sl_plan *p, float *e, const float *delta, float beta, int flags, const void *pending,
                          void *payload, void *workspace, uint32_t seed, void *stream)
 {
-    return compress_impl(p, e, delta, nullptr, beta, flags, pending, payload, workspace, stream, true, seed);
+    return sl_compress_impl(p, e, delta, nullptr, beta, flags, pending, payload, workspace, stream, true, seed);
 }
 
 size_t sl_rice_max_bytes(const sl_plan *p) { return p ? p->rice_max_bytes : 0; }

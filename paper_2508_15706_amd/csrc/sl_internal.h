@@ -95,6 +95,14 @@ __host__ __device__ inline long long sl_lut_off(const SlChunkDesc &d, int hdr_by
 // Records an event after the kernel of `phase` (phase < 0: start of a call).
 void sl_prof_mark(const sl_plan *p, int phase, hipStream_t st);
 
+// sl_compress and its variants behind one argument check (sl_api.hip)
+int sl_compress_impl(sl_plan *p, float *e, const float *delta, const float *theta_local, float beta,
+                     int flags, const void *pending, void *payload, void *workspace, void *stream,
+                     bool random = false, unsigned seed = 0u);
+
+// device address of the library's own scratch array on `device` (the current device), sl_noalloc.hip
+int sl_noalloc_scratch(int device, void **out);
+
 // launchers (defined next to their kernels)
 int slk_select(const sl_plan *p, float *e, const float *delta, const float *theta_local, float beta,
                int frozen, const unsigned char *pending, unsigned char *payload, unsigned char *ws,
