@@ -123,13 +123,19 @@ def lib():
         L.slo_rice_encode.restype = i64
         L.slo_rice_encode.argtypes = [tp, i32, i32, i32, vp, vp, i64]
         L.slo_rice_decode.restype = i32
-        L.slo_rice_decode.argtypes = [tp, i32, i32, i32, vp, vp]
+        L.slo_rice_decode.argtypes = [tp, i32, i32, i32, vp, i64, vp]
+        L.slo_rice_qfield_bytes.restype = i32
+        L.slo_rice_qfield_bytes.argtypes = [i32]
+        L.slo_rice_dir_entry_bytes.restype = i64
+        L.slo_rice_dir_entry_bytes.argtypes = [i32]
+        L.slo_rice_fixed_bytes.restype = i64
+        L.slo_rice_fixed_bytes.argtypes = [i32, i32]
         L.slo_rice_max_bytes_b.restype = i64
         L.slo_rice_max_bytes_b.argtypes = [tp, i32, i32, i32, i32]
         L.slo_rice_encode_b.restype = i64
         L.slo_rice_encode_b.argtypes = [tp, i32, i32, i32, i32, vp, vp, i64]
         L.slo_rice_decode_b.restype = i32
-        L.slo_rice_decode_b.argtypes = [tp, i32, i32, i32, i32, vp, vp]
+        L.slo_rice_decode_b.argtypes = [tp, i32, i32, i32, i32, vp, i64, vp]
         L.slo_max_threads.restype = i32
         L.slo_max_threads.argtypes = []
         _lib = L
@@ -462,6 +468,21 @@ def rice_param(k):
     return int(lib().slo_rice_param(k))
 
 
+RICE_GROUP = 16      # chunks per directory entry of the coded format
+
+
+def rice_qfield_bytes(k):
+    return int(lib().slo_rice_qfield_bytes(k))
+
+
+def rice_dir_entry_bytes(k):
+    return int(lib().slo_rice_dir_entry_bytes(k))
+
+
+def rice_fixed_bytes(k, bits=2):
+    return int(lib().slo_rice_fixed_bytes(k, bits))
+
+
 def rice_max_bytes(descs, k, tile=64):
     arr, n = make_tensors(descs)
     return int(lib().slo_rice_max_bytes(arr, n, tile, k))
@@ -483,7 +504,7 @@ def rice_decode(descs, k, coded, tile=64):
     arr, n = make_tensors(descs)
     _check(coded, np.uint8)
     out = np.full(int(lib().slo_payload_bytes(arr, n, tile, k)), 0xEE, dtype=np.uint8)
-    st = lib().slo_rice_decode(arr, n, tile, k, _ptr(coded), _ptr(out))
+    st = lib().slo_rice_decode(arr, n, tile, k, _ptr(coded), coded.size, _ptr(out))
     if st:
         raise ValueError(f"slo_rice_decode: status {st}")
     return out
@@ -509,7 +530,7 @@ def rice_decode_b(descs, k, bits, coded, tile=64):
     arr, n = make_tensors(descs)
     _check(coded, np.uint8)
     out = np.zeros(payload_bytes_b(descs, k, bits, tile), dtype=np.uint8)
-    st = lib().slo_rice_decode_b(arr, n, tile, k, bits, _ptr(coded), _ptr(out))
+    st = lib().slo_rice_decode_b(arr, n, tile, k, bits, _ptr(coded), coded.size, _ptr(out))
     if st:
         raise ValueError(f"slo_rice_decode_b: status {st}")
     return out

@@ -1097,28 +1097,49 @@ int slo_max_threads(void)
 /* 6.6, 5.6 bits per index for k = 32, 128, 256 against the bounds 8.3, 6.3,  */
 /* 5.3) but does not describe it.  PARITY UNPINNED beyond: lossless round     */
 /* trip, size between the information bound and the paper's reached rates on  */
-/* uniformly random index sets, and the hand-computed bits of a tiny record.  */
-/* Reading (this build's own design):                                         */
+/* uniformly random index sets, and the hand-computed bytes of tiny records.  */
+/*                                                                           */
+/* Reading (this build's own format, "SLRICE02"; it is the wire format of a   */
+/* round: the compressor emits it and the aggregation consumes it):           */
 /*   - an ascending index list is coded as gaps g_0 = idx_0,                  */
 /*     g_i = idx_i - idx_(i-1) - 1, each as a Rice code with parameter b:     */
-/*     (g >> b) one-bits, a zero bit, then the b low bits of g, LSB first;    */
+/*     quotient q_i = g_i >> b in unary (q_i one-bits, then a zero bit) and   */
+/*     the b low bits of g_i as the remainder;                                */
 /*     b = floor(log2(floor(4096 ln 2) / k)) = floor(log2(2839 / k)), 0 when  */
 /*     2839 / k < 1 (the optimum for uniformly random positions);             */
+/*   - the two halves of the codes are stored apart, so that a decoder can    */
+/*     take a chunk's entries side by side instead of one after the other:    */
+/*     the remainders as k fields of b bits at fixed places, the quotients    */
+/*     as one bit vector per chunk (the unary codes back to back: k zero      */
+/*     bits, Q = sum of the q_i one-bits; entry i ends at the i-th zero,      */
+/*     which sits at bit i + q_0 + ... + q_i).  The bits are the Rice codes'  */
+/*     bits, regrouped: k (1 + b) + Q per chunk;                              */
 /*   - bits fill bytes LSB first (as the 12-bit fields of the plain format);  */
-/*   - a chunk = its k gap codes followed by its k 2-bit codes (entry m at    */
-/*     bits 2m, 2m+1 of that run); chunks of a group of 8 follow each other  */
-/*     without padding; a group starts on a 4-byte boundary (the sub-chunking:*/
-/*     a group is the unit that must be decoded sequentially);                */
-/*   - tensor block, 16-byte aligned: float LUT[4]; uint32 goff[n_groups] =   */
-/*     byte offset of each group's stream from the block start; the streams;  */
-/*     zero padding to 16 bytes;                                              */
-/*   - buffer: uint64 magic "SLRICE01", uint64 total bytes, uint64            */
-/*     tensor_off[nt] (byte offset of each tensor block), zero padding to 16, */
-/*     then the blocks.                                                       */
+/*   - fixed record of a chunk: the k remainders (b bits each, LSB first)     */
+/*     padded with zero bits to a byte, then the k value fields exactly as    */
+/*     they stand in the plain record (k * bits / 8 bytes), zero padding to a */
+/*     multiple of 4 bytes;                                                   */
+/*   - directory: one entry per group of 16 consecutive chunks of a tensor:   */
+/*     uint32 = offset of the group's run of quotient bit vectors, in 4-byte  */
+/*     words from the start of the quotient section, then 16 fields with the  */
+/*     Q of each chunk of the group - one byte each when the largest possible */
+/*     Q, (4096 - k) >> b, is below 256, else two (little endian); fields of  */
+/*     chunks beyond the tensor's last are zero.  A chunk's bit vector starts */
+/*     at bit  sum over the earlier chunks of its group of (k + Q)  of the    */
+/*     group's run;                                                           */
+/*   - tensor block, 16-byte aligned, at an offset that follows from the list */
+/*     alone: look-up table header as in the plain format; the directory; the */
+/*     fixed records in chunk order; zero padding to 16 bytes;                */
+/*   - quotient section, after the last block: the groups' runs in list       */
+/*     order, the chunks of a group back to back without padding, every run   */
+/*     zero-padded to a 4-byte boundary; zero padding to 16 bytes at the end; */
+/*   - buffer: "SLRICE02", uint64 total bytes, the blocks, the section.       */
+/* ("Group" is this format's own unit and no reading of the paper's           */
+/* "sub-chunking"; the format does not split a chunk.)                        */
 /* ------------------------------------------------------------------------- */
 
-#define SLO_RICE_GROUP 8
-static const char SLO_RICE_MAGIC[8] = {'S', 'L', 'R', 'I', 'C', 'E', '0', '1'};
+#define SLO_RICE_GROUP 16
+static const char SLO_RICE_MAGIC[8] = {'S', 'L', 'R', 'I', 'C', 'E', '0', '2'};
 
 int slo_rice_param(int k)
 {
@@ -1127,44 +1148,48 @@ int slo_rice_param(int k)
     return q < 1 ? 0 : b;
 }
 
-typedef struct {
-    uint8_t *p;
-    int64_t bit;
-} slo_bitw;
-
-static void put_bits(slo_bitw *w, uint32_t v, int n) /* n low bits of v, LSB first */
+/* bytes of a quotient-sum field, of a directory entry and of a fixed record */
+int slo_rice_qfield_bytes(int k) { return ((4096 - k) >> slo_rice_param(k)) < 256 ? 1 : 2; }
+int64_t slo_rice_dir_entry_bytes(int k) { return 4 + SLO_RICE_GROUP * (int64_t)slo_rice_qfield_bytes(k); }
+int64_t slo_rice_fixed_bytes(int k, int bits)
 {
-    for (int i = 0; i < n; ++i, ++w->bit)
-        if (v >> i & 1u) w->p[w->bit / 8] |= (uint8_t)(1u << (w->bit % 8));
+    int64_t rem = ((int64_t)k * slo_rice_param(k) + 7) / 8, val = (int64_t)k * bits / 8;
+    return (rem + val + 3) / 4 * 4;
 }
 
-static uint32_t get_bits(const uint8_t *p, int64_t *bit, int n)
+static void put_bit(uint8_t *p, int64_t bit, unsigned v)
 {
-    uint32_t v = 0;
-    for (int i = 0; i < n; ++i, ++*bit) v |= (uint32_t)(p[*bit / 8] >> (*bit % 8) & 1u) << i;
-    return v;
+    if (v & 1u) p[bit / 8] |= (uint8_t)(1u << (bit % 8));
 }
 
-/* The coder with the value width as a parameter (bits in {1, 2, 3, 4}, or 32
- * for unquantized values): the look-up table header of a tensor block has
- * slo_header_bytes_b(bits) bytes (none at 32), and a chunk's k gap codes are
- * followed by its k value fields of `bits` bits each, copied as they stand in
- * the plain record (at 32: the fp32 bit patterns, LSB first).  bits = 2 is the
- * format described above. */
+static unsigned get_bit(const uint8_t *p, int64_t bit) { return p[bit / 8] >> (bit % 8) & 1u; }
 
-/* Upper bound of the coded size of payloads of this list. */
+/* Bytes of the part whose layout follows from the list alone (header + blocks). */
+static int64_t rice_fixed_part(const slo_tensor *t, int nt, int tile, int k, int bits)
+{
+    int64_t pos = 16;
+    for (int i = 0; i < nt; ++i) {
+        int64_t nc = slo_tensor_chunks(&t[i], tile), ng = ceil_div(nc, SLO_RICE_GROUP);
+        pos += ceil_div(slo_header_bytes_b(bits) + ng * slo_rice_dir_entry_bytes(k) +
+                        nc * slo_rice_fixed_bytes(k, bits), 16) * 16;
+    }
+    return pos;
+}
+
+/* Upper bound of the coded size of payloads of this list (every Q at its maximum). */
 int64_t slo_rice_max_bytes_b(const slo_tensor *t, int nt, int tile, int k, int bits)
 {
-    int b = slo_rice_param(k);
-    int64_t chunk_bits = (int64_t)k * (1 + b) + (4096 >> b) + (int64_t)bits * k;
-    int64_t hdr = slo_header_bytes_b(bits);
-    int64_t total = 16 + 8 * (int64_t)nt + 16;
+    if (!bits_ok(k, bits, tile)) return SLO_ERR_ARG;
+    int64_t qmax = (4096 - k) >> slo_rice_param(k);
+    int64_t total = rice_fixed_part(t, nt, tile, k, bits);
     for (int i = 0; i < nt; ++i) {
         int64_t nc = slo_tensor_chunks(&t[i], tile);
-        int64_t ng = (nc + SLO_RICE_GROUP - 1) / SLO_RICE_GROUP;
-        total += hdr + 4 * ng + ng * ((SLO_RICE_GROUP * chunk_bits + 31) / 32 * 4) + 16;
+        for (int64_t c0 = 0; c0 < nc; c0 += SLO_RICE_GROUP) {
+            int64_t in_group = nc - c0 < SLO_RICE_GROUP ? nc - c0 : SLO_RICE_GROUP;
+            total += ceil_div(in_group * (k + qmax), 32) * 4;
+        }
     }
-    return total;
+    return ceil_div(total, 16) * 16;
 }
 
 /* payload (plain wire format) -> coded buffer; returns the coded size or <0. */
@@ -1172,217 +1197,148 @@ int64_t slo_rice_encode_b(const slo_tensor *t, int nt, int tile, int k, int bits
                           const uint8_t *payload, uint8_t *out, int64_t cap)
 {
     if (!bits_ok(k, bits, tile)) return SLO_ERR_ARG;
-    const int b = slo_rice_param(k);
+    const int b = slo_rice_param(k), qf = slo_rice_qfield_bytes(k);
     const int64_t rec = slo_record_bytes_b(k, bits), hdr = slo_header_bytes_b(bits);
+    const int64_t fix = slo_rice_fixed_bytes(k, bits), dent = slo_rice_dir_entry_bytes(k);
+    const int64_t section = rice_fixed_part(t, nt, tile, k, bits);   /* start of the quotient section */
+    if (section > cap) return SLO_ERR_ARG;
     uint16_t *idx = (uint16_t *)malloc((size_t)k * sizeof(uint16_t));
     uint8_t *code = (uint8_t *)calloc((size_t)k, 1);
     float *val = (float *)calloc((size_t)k, sizeof(float));
     memset(out, 0, (size_t)cap);
-    int64_t pos = (16 + 8 * (int64_t)nt + 15) / 16 * 16, pay_off = 0;
-    for (int ti = 0; ti < nt; ++ti) {
-        int64_t nc = slo_tensor_chunks(&t[ti], tile);
-        int64_t ng = (nc + SLO_RICE_GROUP - 1) / SLO_RICE_GROUP;
-        uint64_t toff = (uint64_t)pos;
-        memcpy(out + 16 + 8 * ti, &toff, 8);
-        uint8_t *blk = out + pos;
+    int64_t pos = 16, pay_off = 0, word = 0;      /* next block; tensor's plain block; next run, in words */
+    int status = SLO_OK;
+    for (int ti = 0; ti < nt && status == SLO_OK; ++ti) {
+        int64_t nc = slo_tensor_chunks(&t[ti], tile), ng = ceil_div(nc, SLO_RICE_GROUP);
+        uint8_t *blk = out + pos, *dir = blk + hdr, *fixed = dir + ng * dent;
         memcpy(blk, payload + pay_off, (size_t)hdr);             /* look-up table */
-        int64_t cur = hdr + 4 * ng;                               /* byte offset in the block */
-        for (int64_t g = 0; g < ng; ++g) {
-            uint32_t goff = (uint32_t)cur;
-            memcpy(blk + hdr + 4 * g, &goff, 4);
-            slo_bitw w = {blk + cur, 0};
+        for (int64_t g = 0; g < ng && status == SLO_OK; ++g) {
+            uint32_t w32 = (uint32_t)word;
+            memcpy(dir + g * dent, &w32, 4);
+            int64_t bit = 0;                                      /* bit inside the group's run */
             for (int64_t c = g * SLO_RICE_GROUP; c < nc && c < (g + 1) * SLO_RICE_GROUP; ++c) {
-                slo_unpack_record_b(payload + pay_off + hdr + c * rec, k, bits, idx, code, val);
+                const uint8_t *r = payload + pay_off + hdr + c * rec;
+                slo_unpack_record_b(r, k, bits, idx, code, val);
                 int prev = -1;
+                int64_t Q = 0;
+                /* worst case of this chunk's vector, checked before it is written */
+                if (section + 4 * word + (bit + k + ((4096 - k) >> b) + 7) / 8 > cap) {
+                    status = SLO_ERR_ARG;
+                    break;
+                }
                 for (int m = 0; m < k; ++m) {
                     uint32_t gap = (uint32_t)(idx[m] - prev - 1);
                     prev = idx[m];
-                    for (uint32_t q = gap >> b; q > 0; --q) put_bits(&w, 1u, 1);
-                    put_bits(&w, 0u, 1);
-                    put_bits(&w, gap, b);
+                    for (uint32_t q = gap >> b; q > 0; --q, ++bit, ++Q) put_bit(out + section + 4 * word, bit, 1u);
+                    ++bit;                                        /* the zero bit */
+                    for (int i = 0; i < b; ++i) put_bit(fixed + c * fix, (int64_t)m * b + i, gap >> i);
                 }
-                for (int m = 0; m < k; ++m) {
-                    if (bits == 32) {
-                        uint32_t u;
-                        memcpy(&u, &val[m], 4);
-                        put_bits(&w, u, 32);
-                    } else {
-                        put_bits(&w, code[m], bits);
-                    }
-                }
+                /* the value fields: the tail of the plain record, byte for byte */
+                memcpy(fixed + c * fix + ((int64_t)k * b + 7) / 8, r + 3 * k / 2, (size_t)((int64_t)k * bits / 8));
+                uint8_t *field = dir + g * dent + 4 + (c - g * SLO_RICE_GROUP) * qf;
+                field[0] = (uint8_t)(Q & 0xFF);
+                if (qf == 2) field[1] = (uint8_t)(Q >> 8);
             }
-            cur += (w.bit + 31) / 32 * 4;
-            if (pos + cur > cap) {
-                free(idx), free(code), free(val);
-                return SLO_ERR_ARG;
-            }
+            word += ceil_div(bit, 32);
         }
-        pos += (cur + 15) / 16 * 16;
+        pos += ceil_div(hdr + ng * dent + nc * fix, 16) * 16;
         pay_off += slo_tensor_block_bytes_b(&t[ti], tile, k, bits);
     }
+    free(idx), free(code), free(val);
+    if (status != SLO_OK) return status;
+    int64_t total = ceil_div(section + 4 * word, 16) * 16;
+    if (total > cap) return SLO_ERR_ARG;
     memcpy(out, SLO_RICE_MAGIC, 8);
-    uint64_t total = (uint64_t)pos;
-    memcpy(out + 8, &total, 8);
-    free(idx), free(code), free(val);
-    return pos;
-}
-
-/* coded buffer -> payload in the plain wire format (every byte written). */
-int slo_rice_decode_b(const slo_tensor *t, int nt, int tile, int k, int bits, const uint8_t *in,
-                      uint8_t *payload)
-{
-    if (!bits_ok(k, bits, tile) || memcmp(in, SLO_RICE_MAGIC, 8)) return SLO_ERR_PAYLOAD;
-    const int b = slo_rice_param(k);
-    const int64_t rec = slo_record_bytes_b(k, bits), hdr = slo_header_bytes_b(bits);
-    uint16_t *idx = (uint16_t *)malloc((size_t)k * sizeof(uint16_t));
-    uint8_t *code = (uint8_t *)calloc((size_t)k, 1);
-    float *val = (float *)calloc((size_t)k, sizeof(float));
-    int64_t pay_off = 0;
-    int status = SLO_OK;
-    for (int ti = 0; ti < nt && status == SLO_OK; ++ti) {
-        int64_t nc = slo_tensor_chunks(&t[ti], tile);
-        int64_t ng = (nc + SLO_RICE_GROUP - 1) / SLO_RICE_GROUP;
-        uint64_t toff;
-        memcpy(&toff, in + 16 + 8 * ti, 8);
-        const uint8_t *blk = in + toff;
-        memset(payload + pay_off, 0, (size_t)slo_tensor_block_bytes_b(&t[ti], tile, k, bits));
-        memcpy(payload + pay_off, blk, (size_t)hdr);
-        for (int64_t g = 0; g < ng && status == SLO_OK; ++g) {
-            uint32_t goff;
-            memcpy(&goff, blk + hdr + 4 * g, 4);
-            int64_t bit = 0;
-            for (int64_t c = g * SLO_RICE_GROUP; c < nc && c < (g + 1) * SLO_RICE_GROUP; ++c) {
-                int prev = -1;
-                for (int m = 0; m < k; ++m) {
-                    uint32_t q = 0;
-                    while (get_bits(blk + goff, &bit, 1)) ++q;
-                    uint32_t gap = q << b | get_bits(blk + goff, &bit, b);
-                    int v = prev + 1 + (int)gap;
-                    if (v > 4095) status = SLO_ERR_PAYLOAD, v = 4095;
-                    idx[m] = (uint16_t)v;
-                    prev = v;
-                }
-                for (int m = 0; m < k; ++m) {
-                    if (bits == 32) {
-                        uint32_t u = get_bits(blk + goff, &bit, 32);
-                        memcpy(&val[m], &u, 4);
-                    } else {
-                        code[m] = (uint8_t)get_bits(blk + goff, &bit, bits);
-                    }
-                }
-                slo_pack_record_b(idx, code, val, k, bits, payload + pay_off + hdr + c * rec);
-            }
-        }
-        pay_off += slo_tensor_block_bytes_b(&t[ti], tile, k, bits);
-    }
-    free(idx), free(code), free(val);
-    return status;
-}
-
-/* Upper bound of the coded size of payloads of this list. */
-int64_t slo_rice_max_bytes(const slo_tensor *t, int nt, int tile, int k)
-{
-    int b = slo_rice_param(k);
-    int64_t chunk_bits = (int64_t)k * (1 + b) + (4096 >> b) + 2 * (int64_t)k;
-    int64_t total = 16 + 8 * (int64_t)nt + 16;
-    for (int i = 0; i < nt; ++i) {
-        int64_t nc = slo_tensor_chunks(&t[i], tile);
-        int64_t ng = (nc + SLO_RICE_GROUP - 1) / SLO_RICE_GROUP;
-        total += 16 + 4 * ng + ng * ((SLO_RICE_GROUP * chunk_bits + 31) / 32 * 4) + 16;
-    }
+    uint64_t t64 = (uint64_t)total;
+    memcpy(out + 8, &t64, 8);
     return total;
 }
 
-/* payload (plain wire format) -> coded buffer; returns the coded size or <0. */
+/* coded buffer of in_bytes bytes -> payload in the plain wire format (every byte written).
+ * SLO_ERR_PAYLOAD: wrong magic or size, a run or a bit vector that leaves the buffer, a
+ * vector that does not hold k zero bits within its k + Q bits, an index beyond 4095. */
+int slo_rice_decode_b(const slo_tensor *t, int nt, int tile, int k, int bits, const uint8_t *in,
+                      int64_t in_bytes, uint8_t *payload)
+{
+    if (!bits_ok(k, bits, tile)) return SLO_ERR_ARG;
+    const int b = slo_rice_param(k), qf = slo_rice_qfield_bytes(k);
+    const int64_t rec = slo_record_bytes_b(k, bits), hdr = slo_header_bytes_b(bits);
+    const int64_t fix = slo_rice_fixed_bytes(k, bits), dent = slo_rice_dir_entry_bytes(k);
+    const int64_t section = rice_fixed_part(t, nt, tile, k, bits);
+    uint64_t total;
+    if (in_bytes < 16 || memcmp(in, SLO_RICE_MAGIC, 8)) return SLO_ERR_PAYLOAD;
+    memcpy(&total, in + 8, 8);
+    if ((int64_t)total != in_bytes || in_bytes < section) return SLO_ERR_PAYLOAD;
+    uint16_t *idx = (uint16_t *)malloc((size_t)k * sizeof(uint16_t));
+    uint8_t *code = (uint8_t *)calloc((size_t)k, 1);
+    float *val = (float *)calloc((size_t)k, sizeof(float));
+    int64_t pos = 16, pay_off = 0;
+    int status = SLO_OK;
+    for (int ti = 0; ti < nt && status == SLO_OK; ++ti) {
+        int64_t nc = slo_tensor_chunks(&t[ti], tile), ng = ceil_div(nc, SLO_RICE_GROUP);
+        const uint8_t *blk = in + pos, *dir = blk + hdr, *fixed = dir + ng * dent;
+        memset(payload + pay_off, 0, (size_t)slo_tensor_block_bytes_b(&t[ti], tile, k, bits));
+        memcpy(payload + pay_off, blk, (size_t)hdr);
+        for (int64_t c = 0; c < nc && status == SLO_OK; ++c) {
+            const int64_t g = c / SLO_RICE_GROUP;
+            uint32_t word;
+            memcpy(&word, dir + g * dent, 4);
+            int64_t bit = 0, Q = 0;                               /* start of the chunk's vector in the run */
+            for (int64_t c2 = g * SLO_RICE_GROUP; c2 <= c; ++c2) {
+                const uint8_t *field = dir + g * dent + 4 + (c2 - g * SLO_RICE_GROUP) * qf;
+                Q = field[0] | (qf == 2 ? field[1] << 8 : 0);
+                if (c2 < c) bit += k + Q;
+            }
+            const uint8_t *run = in + section + 4 * (int64_t)word;
+            if (section + 4 * (int64_t)word + (bit + k + Q + 7) / 8 > in_bytes) {
+                status = SLO_ERR_PAYLOAD;
+                break;
+            }
+            const int64_t end = bit + k + Q;
+            int prev = -1;
+            for (int m = 0; m < k; ++m) {
+                uint32_t q = 0, rem = 0;
+                while (bit < end && get_bit(run, bit)) ++q, ++bit;
+                if (bit >= end) {
+                    status = SLO_ERR_PAYLOAD;                     /* fewer than k zero bits */
+                    break;
+                }
+                ++bit;
+                for (int i = 0; i < b; ++i) rem |= get_bit(fixed + c * fix, (int64_t)m * b + i) << i;
+                int v = prev + 1 + (int)(q << b | rem);
+                if (v > 4095) status = SLO_ERR_PAYLOAD, v = 4095;
+                idx[m] = (uint16_t)v;
+                prev = v;
+            }
+            if (status != SLO_OK) break;
+            if (bit != end) status = SLO_ERR_PAYLOAD;             /* Q does not match the vector */
+            uint8_t *r = payload + pay_off + hdr + c * rec;
+            /* indices through the record encoder (with all-zero value fields), then the value
+             * fields byte for byte */
+            slo_pack_record_b(idx, code, val, k, bits, r);
+            memcpy(r + 3 * k / 2, fixed + c * fix + ((int64_t)k * b + 7) / 8, (size_t)((int64_t)k * bits / 8));
+        }
+        pos += ceil_div(hdr + ng * dent + nc * fix, 16) * 16;
+        pay_off += slo_tensor_block_bytes_b(&t[ti], tile, k, bits);
+    }
+    free(idx), free(code), free(val);
+    return status;
+}
+
+/* The paper's setting, 2-bit values. */
+int64_t slo_rice_max_bytes(const slo_tensor *t, int nt, int tile, int k)
+{
+    return slo_rice_max_bytes_b(t, nt, tile, k, 2);
+}
+
 int64_t slo_rice_encode(const slo_tensor *t, int nt, int tile, int k, const uint8_t *payload,
                         uint8_t *out, int64_t cap)
 {
-    if (k < 4 || k % 4) return SLO_ERR_ARG;
-    const int b = slo_rice_param(k);
-    const int64_t rec = slo_record_bytes(k);
-    uint16_t *idx = (uint16_t *)malloc((size_t)k * sizeof(uint16_t));
-    uint8_t *code = (uint8_t *)malloc((size_t)k);
-    memset(out, 0, (size_t)cap);
-    int64_t pos = (16 + 8 * (int64_t)nt + 15) / 16 * 16, pay_off = 0;
-    for (int ti = 0; ti < nt; ++ti) {
-        int64_t nc = slo_tensor_chunks(&t[ti], tile);
-        int64_t ng = (nc + SLO_RICE_GROUP - 1) / SLO_RICE_GROUP;
-        uint64_t toff = (uint64_t)pos;
-        memcpy(out + 16 + 8 * ti, &toff, 8);
-        uint8_t *blk = out + pos;
-        memcpy(blk, payload + pay_off, 16);                      /* LUT */
-        int64_t cur = 16 + 4 * ng;                                /* byte offset in the block */
-        for (int64_t g = 0; g < ng; ++g) {
-            uint32_t goff = (uint32_t)cur;
-            memcpy(blk + 16 + 4 * g, &goff, 4);
-            slo_bitw w = {blk + cur, 0};
-            for (int64_t c = g * SLO_RICE_GROUP; c < nc && c < (g + 1) * SLO_RICE_GROUP; ++c) {
-                slo_unpack_record(payload + pay_off + 16 + c * rec, k, idx, code);
-                int prev = -1;
-                for (int m = 0; m < k; ++m) {
-                    uint32_t gap = (uint32_t)(idx[m] - prev - 1);
-                    prev = idx[m];
-                    for (uint32_t q = gap >> b; q > 0; --q) put_bits(&w, 1u, 1);
-                    put_bits(&w, 0u, 1);
-                    put_bits(&w, gap, b);
-                }
-                for (int m = 0; m < k; ++m) put_bits(&w, code[m], 2);
-            }
-            cur += (w.bit + 31) / 32 * 4;
-            if (pos + cur > cap) {
-                free(idx), free(code);
-                return SLO_ERR_ARG;
-            }
-        }
-        pos += (cur + 15) / 16 * 16;
-        pay_off += slo_tensor_block_bytes(&t[ti], tile, k);
-    }
-    memcpy(out, SLO_RICE_MAGIC, 8);
-    uint64_t total = (uint64_t)pos;
-    memcpy(out + 8, &total, 8);
-    free(idx), free(code);
-    return pos;
+    return slo_rice_encode_b(t, nt, tile, k, 2, payload, out, cap);
 }
 
-/* coded buffer -> payload in the plain wire format (every byte written). */
-int slo_rice_decode(const slo_tensor *t, int nt, int tile, int k, const uint8_t *in, uint8_t *payload)
+int slo_rice_decode(const slo_tensor *t, int nt, int tile, int k, const uint8_t *in, int64_t in_bytes,
+                    uint8_t *payload)
 {
-    if (k < 4 || k % 4 || memcmp(in, SLO_RICE_MAGIC, 8)) return SLO_ERR_PAYLOAD;
-    const int b = slo_rice_param(k);
-    const int64_t rec = slo_record_bytes(k);
-    uint16_t *idx = (uint16_t *)malloc((size_t)k * sizeof(uint16_t));
-    uint8_t *code = (uint8_t *)malloc((size_t)k);
-    int64_t pay_off = 0;
-    int status = SLO_OK;
-    for (int ti = 0; ti < nt && status == SLO_OK; ++ti) {
-        int64_t nc = slo_tensor_chunks(&t[ti], tile);
-        int64_t ng = (nc + SLO_RICE_GROUP - 1) / SLO_RICE_GROUP;
-        uint64_t toff;
-        memcpy(&toff, in + 16 + 8 * ti, 8);
-        const uint8_t *blk = in + toff;
-        memset(payload + pay_off, 0, (size_t)slo_tensor_block_bytes(&t[ti], tile, k));
-        memcpy(payload + pay_off, blk, 16);
-        for (int64_t g = 0; g < ng && status == SLO_OK; ++g) {
-            uint32_t goff;
-            memcpy(&goff, blk + 16 + 4 * g, 4);
-            int64_t bit = 0;
-            for (int64_t c = g * SLO_RICE_GROUP; c < nc && c < (g + 1) * SLO_RICE_GROUP; ++c) {
-                int prev = -1;
-                for (int m = 0; m < k; ++m) {
-                    uint32_t q = 0;
-                    while (get_bits(blk + goff, &bit, 1)) ++q;
-                    uint32_t gap = q << b | get_bits(blk + goff, &bit, b);
-                    int v = prev + 1 + (int)gap;
-                    if (v > 4095) status = SLO_ERR_PAYLOAD, v = 4095;
-                    idx[m] = (uint16_t)v;
-                    prev = v;
-                }
-                for (int m = 0; m < k; ++m) code[m] = (uint8_t)get_bits(blk + goff, &bit, 2);
-                slo_pack_record(idx, code, k, payload + pay_off + 16 + c * rec);
-            }
-        }
-        pay_off += slo_tensor_block_bytes(&t[ti], tile, k);
-    }
-    free(idx), free(code);
-    return status;
+    return slo_rice_decode_b(t, nt, tile, k, 2, in, in_bytes, payload);
 }

@@ -1,7 +1,8 @@
 """Pins of the oracle's index coder (CPU only).  The paper names its coder and the
-rates it reaches but not the algorithm, so what can be pinned is: the round trip is
-lossless, the size lies between the information bound and the paper's reached rates
-on uniformly random index sets, and the bits of a small record worked out by hand."""
+rates it reaches but not the algorithm, so what can be pinned is: the bytes of small
+records worked out by hand, an independent bit-by-bit model of the format's description,
+a lossless round trip, and a size between the information bound and the paper's reached
+rates on uniformly random index sets."""
 import math
 import os
 
@@ -9,6 +10,7 @@ import numpy as np
 import pytest
 
 FLAT, TILE = 0, 1
+G = 16                      # chunks per directory entry
 GOLDEN = os.path.join(os.path.dirname(__file__), "golden", "paper_numbers.txt")
 
 
@@ -36,9 +38,32 @@ def make_payload(oracle, descs, k, rng, idx_fn=None):
     return pay
 
 
-def test_rice_parameter_rule(oracle):
-    assert [oracle.rice_param(k) for k in (4, 32, 64, 128, 256, 1024, 2048, 2840, 4096)] == \
-        [9, 6, 5, 4, 3, 1, 0, 0, 0]
+def make_payload_b(oracle, descs, k, bits, rng):
+    pay = np.zeros(oracle.payload_bytes_b(descs, k, bits), dtype=np.uint8)
+    hdr, rec, off = oracle.header_bytes_b(bits), oracle.record_bytes_b(k, bits), 0
+    for d in descs:
+        if bits != 32:
+            pay[off:off + 4 * (1 << bits)] = rng.normal(0, 1e-3, 1 << bits).astype(np.float32).view(np.uint8)
+        for c in range(oracle.tensor_chunks(d)):
+            idx = np.sort(rng.choice(4096, k, replace=False))
+            sent = rng.normal(0, 1e-3, k).astype(np.float32) if bits == 32 else rng.integers(0, 1 << bits, k)
+            pay[off + hdr + c * rec: off + hdr + (c + 1) * rec] = oracle.pack_record_b(idx, sent, bits)
+        off += oracle.tensor_block_bytes_b(d, k, bits)
+    return pay
+
+
+def layout(shapes):
+    descs, off = [], 0
+    for r, c, lay in shapes:
+        descs.append((r, c, off, lay))
+        off += (r * c + 63) // 64 * 64
+    return descs
+
+
+def rice_b(k):
+    """floor(log2(2839 / k)) written out: the largest b with 2^b <= 2839 // k (0 if there is none)."""
+    q = 2839 // k
+    return max(0, q.bit_length() - 1) if q >= 1 else 0
 
 
 def bits_to_bytes(bits):
@@ -48,69 +73,144 @@ def bits_to_bytes(bits):
     return bytes(out)
 
 
+def pad(buf, to):
+    return buf + bytes(-len(buf) % to)
+
+
+def model_encode(oracle, descs, k, bits, pay):
+    """The coded buffer built from the format's description alone, bit by bit: independent of
+    the oracle's encoder except for the record *unpacker* of the plain format (pinned elsewhere)."""
+    b = rice_b(k)
+    qf = 1 if ((4096 - k) >> b) < 256 else 2
+    hdr, rec = oracle.header_bytes_b(bits), oracle.record_bytes_b(k, bits)
+    blocks, runs, off, word = b"", b"", 0, 0
+    for d in descs:
+        nc = oracle.tensor_chunks(d)
+        directory, fixed = b"", b""
+        for g0 in range(0, nc, G):
+            qs, vec = [], []
+            for c in range(g0, min(nc, g0 + G)):
+                r = pay[off + hdr + c * rec: off + hdr + (c + 1) * rec]
+                idx, _ = oracle.unpack_record_b(r, k, bits)
+                gaps = np.diff(np.concatenate([[-1], idx.astype(np.int64)])) - 1
+                rem_bits = []
+                for gap in gaps.tolist():
+                    vec += [1] * (gap >> b) + [0]
+                    rem_bits += [(gap >> i) & 1 for i in range(b)]
+                qs.append(int((gaps >> b).sum()))
+                fixed += pad(bits_to_bytes(rem_bits) + r[3 * k // 2:].tobytes(), 4)
+            qs += [0] * (G - len(qs))
+            directory += word.to_bytes(4, "little") + b"".join(q.to_bytes(qf, "little") for q in qs)
+            run = pad(bits_to_bytes(vec), 4)
+            runs += run
+            word += len(run) // 4
+        blocks += pad(pay[off:off + hdr].tobytes() + directory + fixed, 16)
+        off += oracle.tensor_block_bytes_b(d, k, bits)
+    total = 16 + len(blocks) + len(pad(runs, 16))
+    return np.frombuffer(b"SLRICE02" + total.to_bytes(8, "little") + blocks + pad(runs, 16), dtype=np.uint8)
+
+
+def test_rice_parameter_rule(oracle):
+    ks = (4, 32, 64, 128, 256, 1024, 2048, 2840, 4096)
+    assert [oracle.rice_param(k) for k in ks] == [9, 6, 5, 4, 3, 1, 0, 0, 0] == [rice_b(k) for k in ks]
+    # quotient-sum fields: one byte while (4096 - k) >> b < 256
+    assert [oracle.rice_qfield_bytes(k) for k in (4, 32, 64, 128, 256, 512, 4096)] == [1, 1, 1, 1, 2, 2, 1]
+    assert oracle.rice_dir_entry_bytes(64) == 20 and oracle.rice_dir_entry_bytes(256) == 36
+    # fixed record: ceil(k b / 8) + k bits / 8, padded to 4:  k = 64: 40 + 16;  k = 4: 5 + 1 -> 8
+    assert oracle.rice_fixed_bytes(64) == 56 and oracle.rice_fixed_bytes(4) == 8 and oracle.rice_fixed_bytes(32) == 32
+    assert oracle.rice_fixed_bytes(128) == 96 and oracle.rice_fixed_bytes(256) == 160
+    assert oracle.rice_fixed_bytes(64, 4) == 40 + 32 and oracle.rice_fixed_bytes(64, 32) == 40 + 256
+
+
 def test_rice_hand_worked_record(oracle):
-    """k = 4 (b = 9), indices 3, 600, 601, 4095 -> gaps 3, 596, 0, 3493, written out by hand:
-    quotient in unary (ones, then a zero), remainder 9 bits LSB first; then the 2-bit codes."""
+    """k = 4 (b = 9), indices 3, 600, 601, 4095 -> gaps 3, 596, 0, 3493 = quotients 0, 1, 0, 6 and
+    remainders 3, 84, 0, 421, written out by hand."""
     descs = [(1, 4096, 0, FLAT)]
     pay = np.zeros(oracle.payload_bytes(descs, 4), dtype=np.uint8)
     pay[:16] = np.array([-2.0, -1.0, 1.0, 2.0], dtype=np.float32).view(np.uint8)
     pay[16:23] = oracle.pack_record([3, 600, 601, 4095], [0, 1, 2, 3])
     enc = oracle.rice_encode(descs, 4, pay)
-    s = ("0" "110000000"            # gap 3    = 0*512 + 3
-         "10" "001010100"           # gap 596  = 1*512 + 84,  84 = 0b001010100 -> LSB first
-         "0" "000000000"            # gap 0
-         "1111110" "101001011"      # gap 3493 = 6*512 + 421, 421 = 0b110100101 -> LSB first
-         "00" "10" "01" "11")       # codes 0, 1, 2, 3, LSB first
-    stream = bits_to_bytes([int(ch) for ch in s])
-    assert len(s) == 55 and len(stream) == 7
-    # header 16 + 8*1 -> 32; block: LUT 16, one group offset (= 20), stream padded to 4 bytes, block to 16
-    assert enc[:8].tobytes() == b"SLRICE01"
-    assert int(enc[8:16].view(np.uint64)[0]) == enc.size == 32 + 32
-    assert int(enc[16:24].view(np.uint64)[0]) == 32
-    blk = enc[32:]
+    rem = ("110000000"              # 3
+           "001010100"              # 84  = 0b001010100, LSB first
+           "000000000"              # 0
+           "101001011")             # 421 = 0b110100101, LSB first
+    fixed = bits_to_bytes([int(ch) for ch in rem]) + bytes([0xE4])        # 5 bytes of remainders, codes 0,1,2,3
+    vec = "0" "10" "0" "1111110"    # unary quotients 0, 1, 0, 6: k + Q = 4 + 7 bits
+    assert enc[:8].tobytes() == b"SLRICE02"
+    assert int(enc[8:16].view(np.uint64)[0]) == enc.size == 80
+    blk = enc[16:64]                # LUT 16, one directory entry 4 + 16, fixed record 8, padding to 48
     assert np.array_equal(blk[:16], pay[:16])
-    assert int(blk[16:20].view(np.uint32)[0]) == 20
-    assert blk[20:27].tobytes() == stream and not blk[27:].any()
+    assert blk[16:20].tobytes() == bytes(4)                               # first run: word 0 of the section
+    assert blk[20:36].tobytes() == bytes([7]) + bytes(15)                 # Q = 7, the other 15 fields unused
+    assert blk[36:42].tobytes() == fixed and not blk[42:].any()
+    assert enc[64:68].tobytes() == bits_to_bytes([int(ch) for ch in vec]) + bytes(2) and not enc[68:].any()
     assert np.array_equal(oracle.rice_decode(descs, 4, enc), pay)
+    assert np.array_equal(model_encode(oracle, descs, 4, 2, pay), enc)
+
+
+def test_rice_hand_worked_two_chunks_share_a_run(oracle):
+    """k = 8 (b = 8): two chunks of one group; the second chunk's vector starts at bit k + Q of the
+    first, inside the same byte."""
+    k = 8
+    assert rice_b(k) == 8
+    descs = [(1, 8192, 0, FLAT)]
+    pay = np.zeros(oracle.payload_bytes(descs, k), dtype=np.uint8)
+    i0 = [0, 1, 2, 3, 4, 5, 6, 1000]            # gaps 0 x7, 993 = 3*256 + 225
+    i1 = [255, 511, 767, 1023, 1279, 1535, 1791, 4095]   # gaps 255 x7, 2303 = 8*256 + 255
+    pay[16:30] = oracle.pack_record(i0, [3] * 8)
+    pay[30:44] = oracle.pack_record(i1, [1] * 8)
+    enc = oracle.rice_encode(descs, k, pay)
+    vec0 = [0] * 7 + [1, 1, 1, 0]               # 11 bits, Q = 3
+    vec1 = [0] * 7 + [1] * 8 + [0]              # 16 bits, Q = 8
+    run = pad(bits_to_bytes(vec0 + vec1), 4)
+    assert len(run) == 4
+    blk = enc[16:]
+    assert blk[16:20].tobytes() == bytes(4) and blk[20:36].tobytes() == bytes([3, 8]) + bytes(14)
+    fix = oracle.rice_fixed_bytes(k)
+    assert fix == 12                             # 8 remainders of 8 bits, 2 bytes of codes, padding
+    assert blk[36:36 + fix].tobytes() == bytes([0] * 7 + [225]) + bytes([0xFF, 0xFF]) + bytes(2)
+    assert blk[36 + fix:36 + 2 * fix].tobytes() == bytes([255] * 8) + bytes([0x55, 0x55]) + bytes(2)
+    section = 16 + (16 + 20 + 2 * fix + 15) // 16 * 16
+    assert enc[section:section + 4].tobytes() == run
+    assert int(enc[8:16].view(np.uint64)[0]) == enc.size == section + 16
+    assert np.array_equal(oracle.rice_decode(descs, k, enc), pay)
 
 
 @pytest.mark.parametrize("k", [4, 8, 32, 64, 100, 128, 256, 1000, 4096])
-def test_rice_round_trip(oracle, k):
+def test_rice_round_trip_and_model(oracle, k):
     rng = np.random.default_rng(900 + k)
     shapes = [(150, 210, TILE), (1, 4096 * 37 + 1100, FLAT), (64, 64, TILE), (1024, 16, TILE)] if k <= 256 \
         else [(160, 224, TILE), (1, 4096 * 3, FLAT)] if k <= 1024 else [(128, 128, TILE), (1, 4096, FLAT)]
-    descs, off = [], 0
-    for r, c, lay in shapes:
-        descs.append((r, c, off, lay))
-        off += (r * c + 63) // 64 * 64
+    descs = layout(shapes)
     pay = make_payload(oracle, descs, k, rng)
     enc = oracle.rice_encode(descs, k, pay)
-    assert enc.size <= oracle.rice_max_bytes(descs, k)
+    assert enc.size <= oracle.rice_max_bytes(descs, k) and enc.size % 16 == 0
     assert np.array_equal(oracle.rice_decode(descs, k, enc), pay)
-    nt = len(descs)
-    assert enc[:8].tobytes() == b"SLRICE01" and int(enc[8:16].view(np.uint64)[0]) == enc.size
-    toffs = enc[16:16 + 8 * nt].view(np.uint64)
-    assert all(int(t) % 16 == 0 for t in toffs) and list(toffs) == sorted(toffs)
-    for t, d in zip(toffs, descs):
-        ng = (oracle.tensor_chunks(d) + 7) // 8
-        goff = enc[int(t) + 16:int(t) + 16 + 4 * ng].view(np.uint32)
-        assert goff[0] == 16 + 4 * ng and all(int(g) % 4 == 0 for g in goff) and np.all(np.diff(goff.astype(np.int64)) > 0)
+    assert np.array_equal(model_encode(oracle, descs, k, 2, pay), enc)
 
 
 def test_rice_extreme_index_sets(oracle):
-    """First k, last k, one cluster, and the largest possible gaps: still lossless and within the bound."""
-    k = 32
-    descs = [(1, 4096 * 64, 0, FLAT)]
+    """First k, last k (the largest possible quotient sum), one cluster, and the largest possible gaps:
+    still lossless, within the bound, and equal to the model."""
     rng = np.random.default_rng(3)
-    sets = [np.arange(k), np.arange(4096 - k, 4096), np.arange(2000, 2000 + k),
-            np.concatenate([[0], np.arange(4096 - k + 1, 4096)]), np.arange(k) * 128, np.arange(k) * 128 + 127]
+    for k in (32, 256):
+        descs = [(1, 4096 * 64, 0, FLAT)]
+        step = 4096 // k
+        sets = [np.arange(k), np.arange(4096 - k, 4096), np.arange(2000, 2000 + k),
+                np.concatenate([[0], np.arange(4096 - k + 1, 4096)]), np.arange(k) * step, np.arange(k) * step + step - 1]
 
-    def idx_fn(c):
-        return sets[c % len(sets)]
-    pay = make_payload(oracle, descs, k, rng, idx_fn)
-    enc = oracle.rice_encode(descs, k, pay)
-    assert enc.size <= oracle.rice_max_bytes(descs, k)
-    assert np.array_equal(oracle.rice_decode(descs, k, enc), pay)
+        def idx_fn(c):
+            return sets[c % len(sets)]
+        pay = make_payload(oracle, descs, k, rng, idx_fn)
+        enc = oracle.rice_encode(descs, k, pay)
+        assert enc.size <= oracle.rice_max_bytes(descs, k)
+        assert np.array_equal(oracle.rice_decode(descs, k, enc), pay)
+        assert np.array_equal(model_encode(oracle, descs, k, 2, pay), enc)
+    # a list whose every chunk has the largest quotient sum reaches the stated upper bound exactly
+    k = 64
+    descs = [(1, 4096 * 40, 0, FLAT)]
+    pay = make_payload(oracle, descs, k, rng, lambda c: np.arange(4096 - k, 4096))
+    assert oracle.rice_encode(descs, k, pay).size == oracle.rice_max_bytes(descs, k)
 
 
 def test_rice_rate_between_bound_and_paper(oracle):
@@ -128,95 +228,54 @@ def test_rice_rate_between_bound_and_paper(oracle):
         assert abs(bound - p["entropy_bits_k%d" % k]) < 0.1
         assert bound < bits <= p["coder_bits_k%d" % k], (k, bits)
         assert bits < p["naive_index_bits"]
-    # Table 1 context: 512M-parameter model at k = 32 would need less than the paper's 5.45 MB
-    n_values = int(p["params_512M"]) * 32 / 4096
-    assert n_values * (bits_k32(oracle) + 2) / 8 / 1e6 < p["table1_size_MB_density_0p78"]
+        # the parts: k (1 + b) + Q bits of Rice codes per chunk, and the directory's share
+        b = rice_b(k)
+        rice_only = (k * (1 + b) + expected_q(k, b)) / k
+        assert abs(bits - rice_only - (8 * oracle.rice_qfield_bytes(k) + 3) / k) < 0.03, (k, bits, rice_only)
 
 
-def bits_k32(oracle):
-    rng = np.random.default_rng(5)
-    nc = 800
-    descs = [(1, 4096 * nc, 0, FLAT)]
-    enc = oracle.rice_encode(descs, 32, make_payload(oracle, descs, 32, rng))
-    return enc.size * 8 / (nc * 32) - 2
+def expected_q(k, b, n=4000, seed=11):
+    rng = np.random.default_rng(seed)
+    tot = 0
+    for _ in range(n):
+        idx = np.sort(rng.choice(4096, k, replace=False))
+        tot += int(((np.diff(np.concatenate([[-1], idx])) - 1) >> b).sum())
+    return tot / n
+
+
+def test_rice_rejects_malformed_buffers(oracle):
+    k = 32
+    descs = [(1, 4096 * 20, 0, FLAT)]
+    rng = np.random.default_rng(8)
+    pay = make_payload(oracle, descs, k, rng)
+    enc = oracle.rice_encode(descs, k, pay)
+    bad = enc.copy()
+    bad[7] = ord("1")
+    with pytest.raises(ValueError):
+        oracle.rice_decode(descs, k, bad)                         # another format's magic
+    with pytest.raises(ValueError):
+        oracle.rice_decode(descs, k, enc[:enc.size - 16].copy())  # truncated: size field disagrees
+    bad = enc.copy()
+    bad[16 + 16 + 4] ^= 0x01                                       # the first chunk's Q, off by one
+    with pytest.raises(ValueError):
+        oracle.rice_decode(descs, k, bad)
+    bad = enc.copy()
+    bad[16 + 16:16 + 20] = np.frombuffer((1 << 30).to_bytes(4, "little"), dtype=np.uint8)   # run beyond the buffer
+    with pytest.raises(ValueError):
+        oracle.rice_decode(descs, k, bad)
 
 
 # --------------------------------------------------------------------------- other value widths
-def make_payload_b(oracle, descs, k, bits, rng):
-    pay = np.zeros(oracle.payload_bytes_b(descs, k, bits), dtype=np.uint8)
-    hdr, rec, off = oracle.header_bytes_b(bits), oracle.record_bytes_b(k, bits), 0
-    for d in descs:
-        if bits != 32:
-            pay[off:off + 4 * (1 << bits)] = rng.normal(0, 1e-3, 1 << bits).astype(np.float32).view(np.uint8)
-        for c in range(oracle.tensor_chunks(d)):
-            idx = np.sort(rng.choice(4096, k, replace=False))
-            sent = rng.normal(0, 1e-3, k).astype(np.float32) if bits == 32 else rng.integers(0, 1 << bits, k)
-            pay[off + hdr + c * rec: off + hdr + (c + 1) * rec] = oracle.pack_record_b(idx, sent, bits)
-        off += oracle.tensor_block_bytes_b(d, k, bits)
-    return pay
-
-
-def test_rice_two_bits_is_the_pinned_coder(oracle):
-    rng = np.random.default_rng(950)
-    descs = [(150, 210, 0, TILE), (1, 4096 * 9 + 1100, 150 * 210 + 20, FLAT)]
-    for k in (4, 32, 64, 100):
-        pay = make_payload(oracle, descs, k, rng)
-        enc = oracle.rice_encode(descs, k, pay)
-        assert np.array_equal(oracle.rice_encode_b(descs, k, 2, pay), enc)
-        assert np.array_equal(oracle.rice_decode_b(descs, k, 2, enc), pay)
-        assert oracle.rice_max_bytes_b(descs, k, 2) == oracle.rice_max_bytes(descs, k)
-
-
-@pytest.mark.parametrize("bits", [1, 3, 4, 32])
-def test_rice_other_widths_stream_model_and_round_trip(oracle, bits):
-    """One tensor of 11 chunks (two groups): the coded block is the table, the group offsets and,
-    per group, the chunks' gap codes (the pinned 2-bit coder's, unchanged) each followed by the k
-    value fields of `bits` bits - rebuilt here bit by bit from the records."""
-    k, nc = 16, 11
-    b = oracle.rice_param(k)
-    descs = [(1, 4096 * nc, 0, FLAT)]
-    rng = np.random.default_rng(960 + bits)
-    pay = make_payload_b(oracle, descs, k, bits, rng)
-    enc = oracle.rice_encode_b(descs, k, bits, pay)
-    assert enc.size <= oracle.rice_max_bytes_b(descs, k, bits)
-    assert np.array_equal(oracle.rice_decode_b(descs, k, bits, enc), pay)
-    hdr, rec = oracle.header_bytes_b(bits), oracle.record_bytes_b(k, bits)
-    assert enc[:8].tobytes() == b"SLRICE01" and int(enc[8:16].view(np.uint64)[0]) == enc.size
-    blk = enc[int(enc[16:24].view(np.uint64)[0]):]
-    assert np.array_equal(blk[:hdr], pay[:hdr])
-    goff = blk[hdr:hdr + 8].view(np.uint32)
-    assert goff[0] == hdr + 8
-    for g, (lo, hi) in enumerate(((0, 8), (8, 11))):
-        stream = []
-        for c in range(lo, hi):
-            idx, sent = oracle.unpack_record_b(pay[hdr + c * rec: hdr + (c + 1) * rec], k, bits)
-            prev = -1
-            for v in idx.astype(int):
-                gap = v - prev - 1
-                prev = v
-                stream += [1] * (gap >> b) + [0] + [(gap >> i) & 1 for i in range(b)]
-            fields = sent.view(np.uint32) if bits == 32 else sent
-            for f in fields.astype(np.uint64):
-                stream += [(int(f) >> i) & 1 for i in range(bits)]
-        want = bits_to_bytes(stream)
-        at = int(goff[g])
-        assert blk[at:at + len(want)].tobytes() == want, (bits, g)
-        end = int(goff[1]) if g == 0 else blk.size
-        if g == 0:
-            assert end - at == (len(want) + 3) // 4 * 4          # a group is padded to 4 bytes
-        assert not blk[at + len(want):end].any()
-
-
 @pytest.mark.parametrize("bits", [1, 3, 4, 32])
 @pytest.mark.parametrize("k", [8, 64, 104, 1024])
-def test_rice_other_widths_round_trip(oracle, bits, k):
+def test_rice_other_widths_round_trip_and_model(oracle, bits, k):
+    """The value fields travel as they stand in the plain record, after the remainders; the table
+    header has the width's size.  Equal to the bit-by-bit model, and lossless."""
     rng = np.random.default_rng(970 + bits + k)
     shapes = [(150, 210, TILE), (1, 4096 * 19 + 1100, FLAT), (1024, 16, TILE)] if k <= 256 else [(160, 224, TILE), (1, 4096 * 3, FLAT)]
-    descs, off = [], 0
-    for r, c, lay in shapes:
-        descs.append((r, c, off, lay))
-        off += (r * c + 63) // 64 * 64
+    descs = layout(shapes)
     pay = make_payload_b(oracle, descs, k, bits, rng)
     enc = oracle.rice_encode_b(descs, k, bits, pay)
     assert enc.size <= oracle.rice_max_bytes_b(descs, k, bits)
     assert np.array_equal(oracle.rice_decode_b(descs, k, bits, enc), pay)
+    assert np.array_equal(model_encode(oracle, descs, k, bits, pay), enc)
