@@ -128,6 +128,8 @@ def lib():
         L.slo_rice_qfield_bytes.argtypes = [i32]
         L.slo_rice_dir_entry_bytes.restype = i64
         L.slo_rice_dir_entry_bytes.argtypes = [i32]
+        L.slo_rice_rem_bytes.restype = i64
+        L.slo_rice_rem_bytes.argtypes = [i32]
         L.slo_rice_fixed_bytes.restype = i64
         L.slo_rice_fixed_bytes.argtypes = [i32, i32]
         L.slo_rice_max_bytes_b.restype = i64
@@ -477,6 +479,10 @@ def rice_qfield_bytes(k):
 
 def rice_dir_entry_bytes(k):
     return int(lib().slo_rice_dir_entry_bytes(k))
+
+
+def rice_rem_bytes(k):
+    return int(lib().slo_rice_rem_bytes(k))
 
 
 def rice_fixed_bytes(k, bits=2):

@@ -1116,9 +1116,10 @@ int slo_max_threads(void)
 /*     bits, regrouped: k (1 + b) + Q per chunk;                              */
 /*   - bits fill bytes LSB first (as the 12-bit fields of the plain format);  */
 /*   - fixed record of a chunk: the k remainders (b bits each, LSB first)     */
-/*     padded with zero bits to a byte, then the k value fields exactly as    */
-/*     they stand in the plain record (k * bits / 8 bytes), zero padding to a */
-/*     multiple of 4 bytes;                                                   */
+/*     padded with zero bits to a multiple of 4 bytes, then the k value       */
+/*     fields exactly as they stand in the plain record (k * bits / 8 bytes), */
+/*     zero padding to a multiple of 4 bytes (both parts start on a 4-byte    */
+/*     boundary; neither padding is ever present when k is a multiple of 32); */
 /*   - directory: one entry per group of 16 consecutive chunks of a tensor:   */
 /*     uint32 = offset of the group's run of quotient bit vectors, in 4-byte  */
 /*     words from the start of the quotient section, then 16 fields with the  */
@@ -1151,10 +1152,10 @@ int slo_rice_param(int k)
 /* bytes of a quotient-sum field, of a directory entry and of a fixed record */
 int slo_rice_qfield_bytes(int k) { return ((4096 - k) >> slo_rice_param(k)) < 256 ? 1 : 2; }
 int64_t slo_rice_dir_entry_bytes(int k) { return 4 + SLO_RICE_GROUP * (int64_t)slo_rice_qfield_bytes(k); }
+int64_t slo_rice_rem_bytes(int k) { return ((int64_t)k * slo_rice_param(k) + 31) / 32 * 4; }
 int64_t slo_rice_fixed_bytes(int k, int bits)
 {
-    int64_t rem = ((int64_t)k * slo_rice_param(k) + 7) / 8, val = (int64_t)k * bits / 8;
-    return (rem + val + 3) / 4 * 4;
+    return (slo_rice_rem_bytes(k) + (int64_t)k * bits / 8 + 3) / 4 * 4;
 }
 
 static void put_bit(uint8_t *p, int64_t bit, unsigned v)
@@ -1234,7 +1235,7 @@ int64_t slo_rice_encode_b(const slo_tensor *t, int nt, int tile, int k, int bits
                     for (int i = 0; i < b; ++i) put_bit(fixed + c * fix, (int64_t)m * b + i, gap >> i);
                 }
                 /* the value fields: the tail of the plain record, byte for byte */
-                memcpy(fixed + c * fix + ((int64_t)k * b + 7) / 8, r + 3 * k / 2, (size_t)((int64_t)k * bits / 8));
+                memcpy(fixed + c * fix + slo_rice_rem_bytes(k), r + 3 * k / 2, (size_t)((int64_t)k * bits / 8));
                 uint8_t *field = dir + g * dent + 4 + (c - g * SLO_RICE_GROUP) * qf;
                 field[0] = (uint8_t)(Q & 0xFF);
                 if (qf == 2) field[1] = (uint8_t)(Q >> 8);
@@ -1316,7 +1317,7 @@ int slo_rice_decode_b(const slo_tensor *t, int nt, int tile, int k, int bits, co
             /* indices through the record encoder (with all-zero value fields), then the value
              * fields byte for byte */
             slo_pack_record_b(idx, code, val, k, bits, r);
-            memcpy(r + 3 * k / 2, fixed + c * fix + ((int64_t)k * b + 7) / 8, (size_t)((int64_t)k * bits / 8));
+            memcpy(r + 3 * k / 2, fixed + c * fix + slo_rice_rem_bytes(k), (size_t)((int64_t)k * bits / 8));
         }
         pos += ceil_div(hdr + ng * dent + nc * fix, 16) * 16;
         pay_off += slo_tensor_block_bytes_b(&t[ti], tile, k, bits);

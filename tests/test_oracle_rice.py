@@ -98,7 +98,7 @@ def model_encode(oracle, descs, k, bits, pay):
                     vec += [1] * (gap >> b) + [0]
                     rem_bits += [(gap >> i) & 1 for i in range(b)]
                 qs.append(int((gaps >> b).sum()))
-                fixed += pad(bits_to_bytes(rem_bits) + r[3 * k // 2:].tobytes(), 4)
+                fixed += pad(pad(bits_to_bytes(rem_bits), 4) + r[3 * k // 2:].tobytes(), 4)
             qs += [0] * (G - len(qs))
             directory += word.to_bytes(4, "little") + b"".join(q.to_bytes(qf, "little") for q in qs)
             run = pad(bits_to_bytes(vec), 4)
@@ -116,8 +116,9 @@ def test_rice_parameter_rule(oracle):
     # quotient-sum fields: one byte while (4096 - k) >> b < 256
     assert [oracle.rice_qfield_bytes(k) for k in (4, 32, 64, 128, 256, 512, 4096)] == [1, 1, 1, 1, 2, 2, 1]
     assert oracle.rice_dir_entry_bytes(64) == 20 and oracle.rice_dir_entry_bytes(256) == 36
-    # fixed record: ceil(k b / 8) + k bits / 8, padded to 4:  k = 64: 40 + 16;  k = 4: 5 + 1 -> 8
-    assert oracle.rice_fixed_bytes(64) == 56 and oracle.rice_fixed_bytes(4) == 8 and oracle.rice_fixed_bytes(32) == 32
+    # fixed record: k b / 8 bytes padded to 4, then k bits / 8 padded to 4:  k = 64: 40 + 16;  k = 4: 5 -> 8, 1 -> 4
+    assert oracle.rice_fixed_bytes(64) == 56 and oracle.rice_fixed_bytes(4) == 12 and oracle.rice_fixed_bytes(32) == 32
+    assert oracle.rice_fixed_bytes(48) == 32 + 12           # b = 5: 30 -> 32 bytes of remainders
     assert oracle.rice_fixed_bytes(128) == 96 and oracle.rice_fixed_bytes(256) == 160
     assert oracle.rice_fixed_bytes(64, 4) == 40 + 32 and oracle.rice_fixed_bytes(64, 32) == 40 + 256
 
@@ -134,15 +135,15 @@ def test_rice_hand_worked_record(oracle):
            "001010100"              # 84  = 0b001010100, LSB first
            "000000000"              # 0
            "101001011")             # 421 = 0b110100101, LSB first
-    fixed = bits_to_bytes([int(ch) for ch in rem]) + bytes([0xE4])        # 5 bytes of remainders, codes 0,1,2,3
+    fixed = bits_to_bytes([int(ch) for ch in rem]) + bytes(3) + bytes([0xE4])   # 5 bytes of remainders padded to 8, codes 0,1,2,3
     vec = "0" "10" "0" "1111110"    # unary quotients 0, 1, 0, 6: k + Q = 4 + 7 bits
     assert enc[:8].tobytes() == b"SLRICE02"
     assert int(enc[8:16].view(np.uint64)[0]) == enc.size == 80
-    blk = enc[16:64]                # LUT 16, one directory entry 4 + 16, fixed record 8, padding to 48
+    blk = enc[16:64]                # LUT 16, one directory entry 4 + 16, fixed record 12: 48 bytes
     assert np.array_equal(blk[:16], pay[:16])
     assert blk[16:20].tobytes() == bytes(4)                               # first run: word 0 of the section
     assert blk[20:36].tobytes() == bytes([7]) + bytes(15)                 # Q = 7, the other 15 fields unused
-    assert blk[36:42].tobytes() == fixed and not blk[42:].any()
+    assert blk[36:45].tobytes() == fixed and not blk[45:].any()
     assert enc[64:68].tobytes() == bits_to_bytes([int(ch) for ch in vec]) + bytes(2) and not enc[68:].any()
     assert np.array_equal(oracle.rice_decode(descs, 4, enc), pay)
     assert np.array_equal(model_encode(oracle, descs, 4, 2, pay), enc)
