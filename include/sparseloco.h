@@ -14,7 +14,8 @@
  * tensor, runs of 4096 elements of a 1-D tensor, k largest |a| per chunk.  Q is
  * the 2-bit statistical quantizer of Section 4 (per tensor: centre by the mean,
  * four uniform bins over [-6 sigma, 6 sigma], per-bin centroid look-up table).
- * Indices travel as 12-bit fields (appendix "Compression of indices in Top-k").
+ * Indices travel as 12-bit fields, or Rice-coded (appendix "Compression of indices in
+ * Top-k"): sl_compress_coded / sl_decompress_avg_apply_coded.
  *
  * Conventions for every function
  *   - returns SL_OK (0) or a negative sl_status; never throws, never aborts;
@@ -25,10 +26,9 @@
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream);
  *     kernels are enqueued on it and the call returns without synchronising;
  *   - the caller owns every buffer it passes; the library owns only sl_plan.
- *   - results are deterministic: the same inputs give the same bytes.
- *   - one environment variable is read, at every sl_compress*: SL_CODES_WAVE_BELOW, the list
- *     length in chunks below which the code kernel gives a chunk to a wavefront instead of a
- *     lane at any k (default 32768).  A tuning knob: the bytes written are the same either way.
+ *   - results are deterministic: the same inputs give the same bytes;
+ *   - no environment variable is read; the one tuning knob is a field of the plan
+ *     (sl_plan_set_codes_wave_below).
  */
 #ifndef SPARSELOCO_H
 #define SPARSELOCO_H
@@ -90,6 +90,11 @@ typedef struct sl_plan sl_plan; /* opaque: chunk work list and per-tensor tables
  * elements), NOMEM, HIP. */
 int sl_plan_create(const sl_tensor *tensors, int n_tensors, int k, sl_plan **out);
 int sl_plan_destroy(sl_plan *plan);
+/* Tuning knob of the code kernel of sl_compress* (Section 4 set-up: the 2-bit codes): lists of
+ * fewer than `n_chunks` chunks give a chunk to a wavefront instead of a lane at any k (a lane
+ * per chunk leaves most of the chip idle on a short list).  Default 32768.  The bytes written are
+ * the same either way; takes effect at the next call on the plan. */
+int sl_plan_set_codes_wave_below(sl_plan *plan, int64_t n_chunks);
 
 /* sl_plan_create for another value width (the ablation "Effect of quantization
  * on loss": 1-, 2-, 3- and 4-bit values and full precision).  value_bits is
@@ -283,24 +288,66 @@ int sl_pack_indices(const uint16_t *idx, const uint8_t *codes, int64_t n_chunks,
 int sl_pack_indices_bits(const uint16_t *idx, const uint8_t *codes, const float *values,
                          int64_t n_chunks, int k, int value_bits, void *out, void *stream);
 
-/* Index coder (appendix "Compression of indices in Top-k": the indices of a
- * payload are compressed for transmission with sub-chunking and Rice coding;
- * the paper gives the rates it reaches - 8.9 / 6.6 / 5.6 bits per index for
- * k = 32 / 128 / 256 - but not the algorithm, so the coded format is this
- * library's own and is described in csrc/sl_rice.hip).  Lossless both ways.
- * Works at every value width of sl_plan_create_bits: a chunk's gap codes are
- * followed by its k value fields as they stand in the plain record.
+/* ---- The coded wire format (appendix "Compression of indices in Top-k": the indices of a
+ * payload travel compressed - the paper names its coder, "sub-chunking and Rice coding", and
+ * the rates it reaches, 8.9 / 6.6 / 5.6 bits per index at k = 32 / 128 / 256, but not the
+ * algorithm, so the format is this library's own; it reaches 8.8 / 6.6 / 5.5).
  *
- * sl_rice_encode: payload (plain wire format, device) -> coded buffer `out`
- *   (device, 16-byte aligned, capacity >= sl_rice_max_bytes(), else
- *   INVALID_ARG).  When the stream work has completed, bytes 8..15 of `out`
- *   hold the coded size as a little-endian uint64; only that many bytes need to
- *   travel.  `workspace`: device, sl_workspace_bytes() bytes, 256-byte aligned.
- * sl_rice_decode: coded buffer `in` of `in_bytes` bytes (device, 16-byte
- *   aligned) -> payload in the plain wire format, every byte written.  Reads
- *   never leave [in, in + in_bytes); malformed input gives indices clamped to
- *   4095, never a fault. */
+ * Format "SLRICE02".  A chunk's ascending indices are coded as gaps g_0 = idx_0,
+ * g_i = idx_i - idx_(i-1) - 1, each a Rice code with parameter b = floor(log2(2839 / k))
+ * (0 when 2839 / k < 1), whose two halves are stored apart: the remainders (b low bits of g_i)
+ * as k fields at fixed places, the quotients g_i >> b in unary - q_i one-bits, a zero bit -
+ * back to back as one bit vector of k + Q bits per chunk (Q = sum of the quotients).  Bits fill
+ * bytes LSB first.  Buffer:
+ *   "SLRICE02", uint64 total bytes (little endian);
+ *   per tensor, at a 16-byte aligned offset that follows from the list alone:
+ *     the table header of the plain format (sl_plan_create_bits);
+ *     directory, one entry per 16 consecutive chunks: uint32 offset of the group's run of bit
+ *       vectors in 4-byte words from the start of the quotient section, then the 16 chunks' Q,
+ *       one byte each when (4096 - k) >> b < 256, else two (unused fields 0);
+ *     fixed records, one per chunk: the k remainders padded to 4 bytes, the k value fields as
+ *       they stand in the plain record, padded to 4 bytes;
+ *     zero padding to 16 bytes;
+ *   quotient section: per group one run - its chunks' bit vectors back to back, zero-padded to
+ *     4 bytes - in list order; zero padding to 16 bytes.
+ * Everything but the section lies at offsets that sl_coded_fixed_bytes() bounds; the total
+ * size varies with the data, at most sl_rice_max_bytes(), which is 0 for a list so long that
+ * run offsets could pass 2^32 words (every coded call then returns INVALID_ARG).
+ *
+ * sl_compress_coded: sl_compress that ALSO emits the payload in the coded format, in the same
+ *   kernels - no pass reads the plain payload back.
+ *   record    out, device, sl_payload_bytes(): the payload in the plain format.  It stays with
+ *             the worker: it is what `pending` of the next call takes (deferred error update)
+ *             and what sl_residual_apply takes; it need not travel.
+ *   coded     out, device, 16-byte aligned, capacity >= sl_rice_max_bytes() (else INVALID_ARG).
+ *             When the stream work has completed, bytes 8..15 hold the coded size as a little
+ *             endian uint64; only that many bytes travel.
+ *   e, delta, beta, flags, pending, workspace: as sl_compress.
+ * sl_decompress_avg_apply_coded (and _nesterov_coded): the aggregate and outer step of
+ *   sl_decompress_avg_apply (sl_decompress_avg_apply_nesterov) over R coded payloads, decoded
+ *   inside the kernel: theta is bit-identical to the plain call on the decoded payloads.
+ *   coded        HOST array of R DEVICE pointers, 16-byte aligned
+ *   coded_bytes  HOST array of the R buffers' sizes (>= sl_coded_fixed_bytes(), else
+ *                INVALID_ARG).  No read leaves [coded[r], coded[r] + coded_bytes[r]); a
+ *                malformed payload gives indices clamped into the chunk, never a fault.
+ * sl_rice_encode: payload (plain format, device) -> coded buffer `out` (device, 16-byte
+ *   aligned, capacity >= sl_rice_max_bytes(), else INVALID_ARG): the same bytes as
+ *   sl_compress_coded writes.  Indices of a record that are not strictly ascending are coded as
+ *   if each repeated or descending one followed its predecessor directly (gap 0); nothing is
+ *   written outside `out`.  `workspace`: device, sl_workspace_bytes() bytes, 256-byte aligned.
+ * sl_rice_decode: coded buffer `in` of `in_bytes` bytes (device, 16-byte aligned) -> payload in
+ *   the plain format, every byte written; reads bounded as above.  Lossless both ways, at every
+ *   value width of sl_plan_create_bits. */
 size_t sl_rice_max_bytes(const sl_plan *plan);
+size_t sl_coded_fixed_bytes(const sl_plan *plan);
+int sl_compress_coded(sl_plan *plan, float *e, const float *delta, float beta, int flags,
+                      const void *pending, void *record, void *coded, size_t coded_capacity,
+                      void *workspace, void *stream);
+int sl_decompress_avg_apply_coded(sl_plan *plan, float *theta, const void *const *coded,
+                                  const size_t *coded_bytes, int R, float lr, void *stream);
+int sl_decompress_avg_apply_nesterov_coded(sl_plan *plan, float *theta, float *momentum,
+                                           const void *const *coded, const size_t *coded_bytes, int R,
+                                           float lr, float mu, void *stream);
 int sl_rice_encode(sl_plan *plan, const void *payload, void *out, size_t out_capacity,
                    void *workspace, void *stream);
 int sl_rice_decode(sl_plan *plan, const void *in, size_t in_bytes, void *payload, void *stream);
@@ -319,8 +366,10 @@ enum { SL_PROF_SELECT = 0,  /* accumulate + chunk Top-k          (sl_compress)  
        SL_PROF_CODES = 2,   /* 2-bit codes + record codes                        */
        SL_PROF_LUT = 3,     /* per-tensor centroids                              */
        SL_PROF_RESIDUAL = 4,/* e <- a - LUT[code] at the selected positions      */
-       SL_PROF_APPLY = 5,   /* sl_decompress_avg_apply                           */
-       SL_PROF_PHASES = 6 };
+       SL_PROF_APPLY = 5,   /* sl_decompress_avg_apply[_coded]                   */
+       SL_PROF_INDEX = 6,   /* coded format: placement of the quotient bit vectors
+                               (sl_compress_coded)                               */
+       SL_PROF_PHASES = 7 };
 int sl_profile_begin(sl_plan *plan, int max_calls);
 int sl_profile_end(sl_plan *plan, double *ms, int *calls);
 

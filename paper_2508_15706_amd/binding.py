@@ -33,9 +33,10 @@ EXPORTS = [
     "sl_rice_max_bytes", "sl_rice_encode", "sl_rice_decode", "sl_compress_params",
     "sl_payload_validate", "sl_plan_create_bits", "sl_plan_value_bits", "sl_pack_indices_bits",
     "sl_lom_direction", "sl_dense_avg_apply", "sl_decompress_avg_apply_nesterov", "sl_sub_topk",
-    "sl_compress_random_k", "sl_compress_noalloc",
+    "sl_compress_random_k", "sl_compress_noalloc", "sl_plan_set_codes_wave_below", "sl_coded_fixed_bytes",
+    "sl_compress_coded", "sl_decompress_avg_apply_coded", "sl_decompress_avg_apply_nesterov_coded",
 ]
-PROF_PHASES = ["select", "stats", "codes", "lut", "residual", "apply"]
+PROF_PHASES = ["select", "stats", "codes", "lut", "residual", "apply", "index"]
 
 
 class SlTensor(C.Structure):
@@ -108,6 +109,17 @@ def lib():
         L.sl_decompress_avg_apply.argtypes = [vp, vp, C.POINTER(vp), i32, C.c_float, vp]
         L.sl_pack_indices.restype = i32
         L.sl_pack_indices.argtypes = [vp, vp, i64, i32, vp, vp]
+        L.sl_plan_set_codes_wave_below.restype = i32
+        L.sl_plan_set_codes_wave_below.argtypes = [vp, i64]
+        L.sl_coded_fixed_bytes.restype = sz
+        L.sl_coded_fixed_bytes.argtypes = [vp]
+        L.sl_compress_coded.restype = i32
+        L.sl_compress_coded.argtypes = [vp, vp, vp, C.c_float, i32, vp, vp, vp, sz, vp, vp]
+        L.sl_decompress_avg_apply_coded.restype = i32
+        L.sl_decompress_avg_apply_coded.argtypes = [vp, vp, C.POINTER(vp), C.POINTER(sz), i32, C.c_float, vp]
+        L.sl_decompress_avg_apply_nesterov_coded.restype = i32
+        L.sl_decompress_avg_apply_nesterov_coded.argtypes = [vp, vp, vp, C.POINTER(vp), C.POINTER(sz), i32,
+                                                             C.c_float, C.c_float, vp]
         L.sl_rice_max_bytes.restype = sz
         L.sl_rice_max_bytes.argtypes = [vp]
         L.sl_rice_encode.restype = i32
@@ -341,6 +353,61 @@ def sl_profile_end(plan: Plan) -> dict:
     if st:
         raise SparseLoCoError("sl_profile_end", st)
     return {name: (ms[i], calls[i]) for i, name in enumerate(PROF_PHASES)}
+
+
+def sl_plan_set_codes_wave_below(plan: Plan, n_chunks: int) -> None:
+    st = lib().sl_plan_set_codes_wave_below(plan.handle, int(n_chunks))
+    if st:
+        raise SparseLoCoError("sl_plan_set_codes_wave_below", st)
+
+
+def sl_coded_fixed_bytes(plan: Plan) -> int:
+    return int(lib().sl_coded_fixed_bytes(plan.handle))
+
+
+def alloc_coded(plan: Plan, device="cuda") -> torch.Tensor:
+    return torch.zeros(max(16, sl_rice_max_bytes(plan)), dtype=torch.uint8, device=device)
+
+
+def coded_size(coded: torch.Tensor) -> int:
+    """Bytes of a coded buffer that travel (its header's size field; waits for the device)."""
+    return int(coded[8:16].cpu().numpy().view("<u8")[0])
+
+
+def sl_compress_coded(plan: Plan, e: Optional[torch.Tensor], delta: torch.Tensor, beta: float,
+                      record: torch.Tensor, coded: torch.Tensor, workspace: torch.Tensor,
+                      flags: int = SL_COMPRESS_DEFAULT, pending: Optional[torch.Tensor] = None,
+                      stream=None) -> None:
+    st = lib().sl_compress_coded(plan.handle, _dev_ptr(e, torch.float32), _dev_ptr(delta, torch.float32),
+                                 float(beta), int(flags), _dev_ptr(pending, torch.uint8),
+                                 _dev_ptr(record, torch.uint8), _dev_ptr(coded, torch.uint8), coded.numel(),
+                                 _dev_ptr(workspace, torch.uint8), _stream_ptr(stream))
+    if st:
+        raise SparseLoCoError("sl_compress_coded", st)
+
+
+def sl_decompress_avg_apply_coded(plan: Plan, theta: torch.Tensor, coded: Sequence[torch.Tensor],
+                                  coded_bytes: Sequence[int], lr: float, stream=None) -> None:
+    R = len(coded)
+    ptrs = (C.c_void_p * max(1, R))(*[_dev_ptr(p, torch.uint8) for p in coded])
+    sizes = (C.c_size_t * max(1, R))(*[int(b) for b in coded_bytes])
+    st = lib().sl_decompress_avg_apply_coded(plan.handle, _dev_ptr(theta, torch.float32), ptrs, sizes, R,
+                                             float(lr), _stream_ptr(stream))
+    if st:
+        raise SparseLoCoError("sl_decompress_avg_apply_coded", st)
+
+
+def sl_decompress_avg_apply_nesterov_coded(plan: Plan, theta: torch.Tensor, momentum: torch.Tensor,
+                                           coded: Sequence[torch.Tensor], coded_bytes: Sequence[int], lr: float,
+                                           mu: float, stream=None) -> None:
+    R = len(coded)
+    ptrs = (C.c_void_p * max(1, R))(*[_dev_ptr(p, torch.uint8) for p in coded])
+    sizes = (C.c_size_t * max(1, R))(*[int(b) for b in coded_bytes])
+    st = lib().sl_decompress_avg_apply_nesterov_coded(plan.handle, _dev_ptr(theta, torch.float32),
+                                                      _dev_ptr(momentum, torch.float32), ptrs, sizes, R,
+                                                      float(lr), float(mu), _stream_ptr(stream))
+    if st:
+        raise SparseLoCoError("sl_decompress_avg_apply_nesterov_coded", st)
 
 
 def sl_rice_max_bytes(plan: Plan) -> int:

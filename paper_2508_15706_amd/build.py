@@ -9,7 +9,8 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libsparseloco.so")
-SOURCES = ["sl_api.hip", "sl_select.hip", "sl_quant.hip", "sl_apply.hip", "sl_rice.hip", "sl_outer.hip", "sl_noalloc.hip"]
+SOURCES = ["sl_api.hip", "sl_select.hip", "sl_quant.hip", "sl_apply.hip", "sl_coded.hip", "sl_apply_coded.hip", "sl_outer.hip",
+           "sl_noalloc.hip"]
 OBJ_DIR = os.path.join(PKG, "_build")
 
 HIPCC_FLAGS = [

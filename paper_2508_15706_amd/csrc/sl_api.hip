@@ -68,14 +68,16 @@ int sl_plan_create_bits(const sl_tensor *tensors, int n_tensors, int k, int valu
     const int64_t rec = sl_rec_bytes(k, bits), hdr = sl_hdr_bytes(bits);
     const int nbins = bits == 32 ? 0 : 1 << bits;
     std::vector<SlChunkDesc> desc;
-    std::vector<SlTensorDev> tdev((size_t)n_tensors);
+    std::vector<SlTensorDev> tdev;
     std::vector<SlGroup> groups;
     int64_t n_elements = 0, n_partial = 0;
     size_t pay = 0;
 
     // tensors must not overlap: results would depend on processing order
-    {
+    try {
+        tdev.resize((size_t)n_tensors);
         std::vector<std::pair<int64_t, int64_t>> span;
+        span.reserve((size_t)n_tensors);
         int64_t total_chunks = 0;
         for (int t = 0; t < n_tensors; ++t) {
             const sl_tensor &T = tensors[t];
@@ -94,6 +96,8 @@ int sl_plan_create_bits(const sl_tensor *tensors, int n_tensors, int k, int valu
         std::sort(span.begin(), span.end());
         for (size_t i = 1; i < span.size(); ++i)
             if (span[i].first < span[i - 1].second) return SL_ERR_INVALID_ARG;
+    } catch (const std::bad_alloc &) {
+        return SL_ERR_NOMEM;
     }
 
     try {
@@ -171,18 +175,41 @@ int sl_plan_create_bits(const sl_tensor *tensors, int n_tensors, int k, int valu
     p->ws_tstat = off;  off = align_up(off + (size_t)n_tensors * sizeof(SlTensorStat), 256);
     p->ws_bytes = off ? off : 256;
     p->n_groups = (int64_t)groups.size();
+    p->codes_wave_below = 32768;
     {
-        // upper bound of a coded payload (see sl_rice_encode) and the scratch its encoder needs
-        const int b = sl_rice_param(k);
-        const size_t chunk_bits = (size_t)k * (1 + b) + (4096 >> b) + (size_t)bits * k;
-        size_t total = 16 + 8 * (size_t)n_tensors + 16;
+        // the coded format's sizes, its upper bound and the scratch its writers need
+        SlCodedGeom &g = p->cg;
+        g.k = k, g.bits = bits;
+        g.b = sl_rice_param(k);
+        g.qmax = (SL_CHUNK - k) >> g.b;
+        g.qf = g.qmax < 256 ? 1 : 2;
+        g.dent = 4 + SL_RICE_GROUP * g.qf;
+        g.rem_bytes = (k * g.b + 31) / 32 * 4;
+        g.val_bytes = k * bits / 8;
+        g.cfix = (g.rem_bytes + g.val_bytes + 3) / 4 * 4;
+        g.hdr = (int)hdr;
+        g.ua = (k + g.qmax + 31) / 32;
+        size_t pos = 16, words = 0;
         for (int t = 0; t < n_tensors; ++t) {
-            const size_t ng = (size_t)((tdev[(size_t)t].n_chunks + SL_RICE_GROUP - 1) / SL_RICE_GROUP);
-            total += (size_t)hdr + 4 * ng + ng * ((SL_RICE_GROUP * chunk_bits + 31) / 32 * 4) + 16;
+            SlTensorDev &D = tdev[(size_t)t];
+            const size_t ng = (size_t)((D.n_chunks + SL_RICE_GROUP - 1) / SL_RICE_GROUP);
+            D.cblk_off = (long long)pos;
+            D.cdir_off = D.cblk_off + hdr;
+            D.cfix_off = D.cdir_off + (long long)(ng * (size_t)g.dent);
+            D.cblk_bytes = (long long)align_up((size_t)hdr + ng * (size_t)g.dent + (size_t)D.n_chunks * (size_t)g.cfix, 16);
+            pos += (size_t)D.cblk_bytes;
+            for (long long c0 = 0; c0 < D.n_chunks; c0 += SL_RICE_GROUP)
+                words += ((size_t)std::min<long long>(SL_RICE_GROUP, D.n_chunks - c0) * (size_t)(k + g.qmax) + 31) / 32;
         }
-        p->rice_max_bytes = total;
-        const size_t rice_ws = align_up(8 * groups.size(), 256) + 8 * (size_t)n_tensors + 256;
-        if (p->ws_bytes < rice_ws) p->ws_bytes = rice_ws;
+        g.section = (long long)pos;
+        // run offsets travel as 32-bit word counts
+        p->rice_max_bytes = words < ((size_t)1 << 32) ? align_up(pos + 4 * words, 16) : 0;
+        p->ws_uvec = off;    off = align_up(off + (size_t)p->n_chunks * (size_t)g.ua * 4, 256);
+        p->ws_qsum = off;    off = align_up(off + (size_t)p->n_chunks * 2, 256);
+        p->ws_gwords = off;  off = align_up(off + groups.size() * 4, 256);
+        p->ws_goff = off;    off = align_up(off + groups.size() * 4, 256);
+        p->ws_twords = off;  off = align_up(off + ((size_t)n_tensors + 1) * 8, 256);
+        p->ws_bytes = off;
     }
 
     hipError_t err = hipGetDevice(&p->device);
@@ -269,9 +296,12 @@ static bool misaligned(const void *ptr, size_t a) { return ((uintptr_t)ptr & (a 
 
 int sl_compress_impl(sl_plan *p, float *e, const float *delta, const float *theta_local, float beta,
                      int flags, const void *pending, void *payload, void *workspace, void *stream,
-                     bool random, unsigned seed)
+                     bool random, unsigned seed, void *coded, size_t coded_capacity)
 {
     if (!p || !delta || !payload || !workspace) return SL_ERR_INVALID_ARG;
+    if (coded && (p->rice_max_bytes == 0 || coded_capacity < p->rice_max_bytes || misaligned(coded, 16) ||
+                  coded == payload || coded == pending || random))
+        return SL_ERR_INVALID_ARG;
     if (flags & ~(SL_COMPRESS_EF_FROZEN | SL_COMPRESS_DEFER_RESIDUAL)) return SL_ERR_INVALID_ARG;
     const int frozen = (flags & SL_COMPRESS_EF_FROZEN) ? 1 : 0;
     const int defer = (flags & SL_COMPRESS_DEFER_RESIDUAL) ? 1 : 0;
@@ -293,10 +323,14 @@ int sl_compress_impl(sl_plan *p, float *e, const float *delta, const float *thet
                                seed, st);
     else
         rc = slk_select(p, e, delta, theta_local, beta, frozen, static_cast<const unsigned char *>(pending),
-                        pay, ws, st);
+                        pay, static_cast<unsigned char *>(coded), ws, st);
     if (rc) return rc;
     sl_prof_mark(p, SL_PROF_SELECT, st);
-    return slk_quantize(p, e, frozen || defer, pay, ws, st);
+    rc = slk_quantize(p, e, frozen || defer, pay, static_cast<unsigned char *>(coded), ws, st);
+    if (rc || !coded) return rc;
+    rc = slk_coded_finish(p, static_cast<unsigned char *>(coded), ws, st);
+    sl_prof_mark(p, SL_PROF_INDEX, st);
+    return rc;
 }
 
 extern "C" {
@@ -321,13 +355,29 @@ int sl_compress_random_k(sl_plan *p, float *e, const float *delta, float beta, i
     return sl_compress_impl(p, e, delta, nullptr, beta, flags, pending, payload, workspace, stream, true, seed);
 }
 
+int sl_compress_coded(sl_plan *p, float *e, const float *delta, float beta, int flags, const void *pending,
+                      void *record, void *coded, size_t coded_capacity, void *workspace, void *stream)
+{
+    if (!coded) return SL_ERR_INVALID_ARG;
+    return sl_compress_impl(p, e, delta, nullptr, beta, flags, pending, record, workspace, stream, false, 0u,
+                            coded, coded_capacity);
+}
+
+int sl_plan_set_codes_wave_below(sl_plan *p, int64_t n_chunks)
+{
+    if (!p || n_chunks < 0) return SL_ERR_INVALID_ARG;
+    p->codes_wave_below = n_chunks;
+    return SL_OK;
+}
+
 size_t sl_rice_max_bytes(const sl_plan *p) { return p ? p->rice_max_bytes : 0; }
+size_t sl_coded_fixed_bytes(const sl_plan *p) { return p ? (size_t)p->cg.section : 0; }
 
 int sl_rice_encode(sl_plan *p, const void *payload, void *out, size_t out_capacity, void *workspace,
                    void *stream)
 {
     if (!p || !payload || !out || !workspace) return SL_ERR_INVALID_ARG;
-    if (out_capacity < p->rice_max_bytes || payload == out) return SL_ERR_INVALID_ARG;
+    if (p->rice_max_bytes == 0 || out_capacity < p->rice_max_bytes || payload == out) return SL_ERR_INVALID_ARG;
     if (misaligned(payload, 16) || misaligned(out, 16) || misaligned(workspace, 256))
         return SL_ERR_INVALID_ARG;
     int rc = check_device(p);
@@ -339,12 +389,42 @@ int sl_rice_encode(sl_plan *p, const void *payload, void *out, size_t out_capaci
 int sl_rice_decode(sl_plan *p, const void *in, size_t in_bytes, void *payload, void *stream)
 {
     if (!p || !in || !payload || in == payload) return SL_ERR_INVALID_ARG;
-    if (in_bytes < 16 + 8 * (size_t)p->n_tensors) return SL_ERR_INVALID_ARG;
+    if (p->rice_max_bytes == 0 || in_bytes < (size_t)p->cg.section) return SL_ERR_INVALID_ARG;
     if (misaligned(in, 16) || misaligned(payload, 16)) return SL_ERR_INVALID_ARG;
     int rc = check_device(p);
     if (rc) return rc;
-    return slk_rice_decode(p, static_cast<const unsigned char *>(in), in_bytes,
-                           static_cast<unsigned char *>(payload), static_cast<hipStream_t>(stream));
+    const void *one[1] = {in};
+    return slk_apply_coded(p, 2, nullptr, nullptr, 0.0f, static_cast<unsigned char *>(payload), one, &in_bytes, 1,
+                           0.0f, static_cast<hipStream_t>(stream));
+}
+
+static int apply_coded(sl_plan *p, float *theta, float *momentum, float mu, const void *const *coded,
+                       const size_t *coded_bytes, int R, float lr, void *stream)
+{
+    if (!p || !theta || !coded || !coded_bytes || R < 1 || R > SL_MAX_WORKERS) return SL_ERR_INVALID_ARG;
+    if (p->rice_max_bytes == 0 || misaligned(theta, 16) || misaligned(momentum, 16)) return SL_ERR_INVALID_ARG;
+    for (int r = 0; r < R; ++r)
+        if (!coded[r] || misaligned(coded[r], 16) || coded_bytes[r] < (size_t)p->cg.section) return SL_ERR_INVALID_ARG;
+    int rc = check_device(p);
+    if (rc) return rc;
+    sl_prof_mark(p, -2, static_cast<hipStream_t>(stream));
+    rc = slk_apply_coded(p, momentum ? 1 : 0, theta, momentum, mu, nullptr, coded, coded_bytes, R, lr,
+                         static_cast<hipStream_t>(stream));
+    sl_prof_mark(p, SL_PROF_APPLY, static_cast<hipStream_t>(stream));
+    return rc;
+}
+
+int sl_decompress_avg_apply_coded(sl_plan *p, float *theta, const void *const *coded, const size_t *coded_bytes,
+                                  int R, float lr, void *stream)
+{
+    return apply_coded(p, theta, nullptr, 0.0f, coded, coded_bytes, R, lr, stream);
+}
+
+int sl_decompress_avg_apply_nesterov_coded(sl_plan *p, float *theta, float *momentum, const void *const *coded,
+                                           const size_t *coded_bytes, int R, float lr, float mu, void *stream)
+{
+    if (!momentum || momentum == theta) return SL_ERR_INVALID_ARG;
+    return apply_coded(p, theta, momentum, mu, coded, coded_bytes, R, lr, stream);
 }
 
 int sl_payload_validate(sl_plan *p, const void *payload, void *workspace, void *stream)
@@ -451,15 +531,21 @@ int sl_pack_indices(const uint16_t *idx, const uint8_t *codes, int64_t n_chunks,
 }  // extern "C"
 
 // ---------------------------------------------------------------------------
-// Optional per-kernel timing.  A compress call records 6 events (start + one
-// after each of its 5 kernels), an apply call 2.
+// Optional per-kernel timing.  A compress call records up to 7 events (start + one after each
+// of its phases), an apply call 2.
+enum { PROF_CEV = 7 };
+// event slot of a compress phase: 1 + phase, the coded format's placement passes last
+static int prof_cslot(int phase) { return phase == SL_PROF_INDEX ? 6 : 1 + phase; }
+static const int PROF_CPHASES[6] = {SL_PROF_SELECT, SL_PROF_STATS, SL_PROF_CODES, SL_PROF_LUT, SL_PROF_RESIDUAL,
+                                    SL_PROF_INDEX};
+
 struct SlProfile {
     int max_calls;
     int n_compress, n_apply;
     bool in_compress;
-    std::vector<hipEvent_t> ev_compress;   // [max_calls][6]
+    std::vector<hipEvent_t> ev_compress;   // [max_calls][PROF_CEV]
     std::vector<hipEvent_t> ev_apply;      // [max_calls][2]
-    std::vector<unsigned char> have;       // [max_calls][6] which compress events were recorded
+    std::vector<unsigned char> have;       // [max_calls][PROF_CEV] which compress events were recorded
     int cur;                               // slot of the call being recorded, or -1
 };
 
@@ -476,9 +562,9 @@ void sl_prof_mark(const sl_plan *p, int phase, hipStream_t st)
         }
         P->cur = n++;
         if (P->in_compress) {
-            for (int i = 0; i < 6; ++i) P->have[(size_t)P->cur * 6 + i] = 0;
-            P->have[(size_t)P->cur * 6] = 1;
-            (void)hipEventRecord(P->ev_compress[(size_t)P->cur * 6], st);
+            for (int i = 0; i < PROF_CEV; ++i) P->have[(size_t)P->cur * PROF_CEV + i] = 0;
+            P->have[(size_t)P->cur * PROF_CEV] = 1;
+            (void)hipEventRecord(P->ev_compress[(size_t)P->cur * PROF_CEV], st);
         } else {
             (void)hipEventRecord(P->ev_apply[(size_t)P->cur * 2], st);
         }
@@ -488,8 +574,8 @@ void sl_prof_mark(const sl_plan *p, int phase, hipStream_t st)
     if (phase == SL_PROF_APPLY) {
         (void)hipEventRecord(P->ev_apply[(size_t)P->cur * 2 + 1], st);
     } else {
-        P->have[(size_t)P->cur * 6 + 1 + phase] = 1;
-        (void)hipEventRecord(P->ev_compress[(size_t)P->cur * 6 + 1 + phase], st);
+        P->have[(size_t)P->cur * PROF_CEV + prof_cslot(phase)] = 1;
+        (void)hipEventRecord(P->ev_compress[(size_t)P->cur * PROF_CEV + prof_cslot(phase)], st);
     }
 }
 
@@ -514,8 +600,15 @@ extern "C" int sl_profile_begin(sl_plan *p, int max_calls)
     P->n_compress = P->n_apply = 0;
     P->cur = -1;
     P->in_compress = false;
-    P->have.assign((size_t)max_calls * 6, 0);
-    for (int i = 0; i < max_calls * 6; ++i) {
+    try {
+        P->have.assign((size_t)max_calls * PROF_CEV, 0);
+        P->ev_compress.reserve((size_t)max_calls * PROF_CEV);
+        P->ev_apply.reserve((size_t)max_calls * 2);
+    } catch (const std::bad_alloc &) {
+        delete P;
+        return SL_ERR_NOMEM;
+    }
+    for (int i = 0; i < max_calls * PROF_CEV; ++i) {
         hipEvent_t e;
         hipError_t err = hipEventCreate(&e);
         if (err != hipSuccess) {
@@ -541,14 +634,15 @@ extern "C" int sl_profile_end(sl_plan *p, double *ms, int *calls)
 {
     if (!p || !p->prof) return SL_ERR_INVALID_ARG;
     SlProfile *P = p->prof;
-    double sum[SL_PROF_PHASES] = {0, 0, 0, 0, 0, 0};
-    int cnt[SL_PROF_PHASES] = {0, 0, 0, 0, 0, 0};
+    double sum[SL_PROF_PHASES] = {0, 0, 0, 0, 0, 0, 0};
+    int cnt[SL_PROF_PHASES] = {0, 0, 0, 0, 0, 0, 0};
     int rc = SL_OK;
     for (int c = 0; c < P->n_compress && rc == SL_OK; ++c) {
         int prev = 0;
-        for (int ph = 0; ph < 5; ++ph) {
-            if (!P->have[(size_t)c * 6 + 1 + ph]) continue;
-            hipEvent_t a = P->ev_compress[(size_t)c * 6 + prev], b = P->ev_compress[(size_t)c * 6 + 1 + ph];
+        for (int i = 0; i < 6; ++i) {
+            const int ph = PROF_CPHASES[i], slot = prof_cslot(ph);
+            if (!P->have[(size_t)c * PROF_CEV + slot]) continue;
+            hipEvent_t a = P->ev_compress[(size_t)c * PROF_CEV + prev], b = P->ev_compress[(size_t)c * PROF_CEV + slot];
             hipError_t err = hipEventSynchronize(b);
             float t = 0.f;
             if (err == hipSuccess) err = hipEventElapsedTime(&t, a, b);
@@ -558,7 +652,7 @@ extern "C" int sl_profile_end(sl_plan *p, double *ms, int *calls)
             }
             sum[ph] += t;
             cnt[ph]++;
-            prev = 1 + ph;
+            prev = slot;
         }
     }
     for (int c = 0; c < P->n_apply && rc == SL_OK; ++c) {

@@ -1,0 +1,144 @@
+// The coded wire format ("SLRICE02") on the device: what a wavefront needs to write and to
+// read one chunk of it.  (The paper's appendix "Compression of indices in Top-k" names its index
+// coder - Rice coding - and the rates it reaches, not the format; this one is the library's.)
+//
+// A chunk's ascending index list idx_0 < ... < idx_(k-1) is coded as gaps g_0 = idx_0,
+// g_i = idx_i - idx_(i-1) - 1, each split by the Rice parameter b = floor(log2(2839 / k)) into a
+// quotient q_i = g_i >> b and a remainder of b bits.  The two halves are stored apart:
+//   * remainders: k fields of b bits (LSB first) at the start of the chunk's FIXED RECORD, padded
+//     to 4 bytes, followed there by the k value fields as they stand in a plain record;
+//   * quotients: one BIT VECTOR per chunk, the unary codes back to back - q_i one-bits, then a
+//     zero bit - so entry i ends at the vector's i-th zero bit, at position
+//     z_i = i + q_0 + ... + q_i, and the vector has k + Q bits, Q = sum of the q_i.
+// So idx_i = i + ((z_i - i) << b) + r_0 + ... + r_i: every entry follows from the position of its
+// own zero bit and a prefix sum of remainders, and a wave decodes a chunk's entries side by side.
+//
+// Buffer: "SLRICE02", uint64 total bytes; per tensor a 16-byte aligned block [table header]
+// [directory][fixed records] at offsets that follow from the tensor list alone; then the
+// quotient section: per group of 16 consecutive chunks of a tensor one run of their bit vectors,
+// back to back, zero-padded to a 4-byte word.  A directory entry = uint32 offset of the group's
+// run (in words from the start of the section) + the 16 chunks' Q (1 byte each while the
+// largest possible Q is below 256, else 2).
+#pragma once
+#include "sl_device.h"
+#include "sl_internal.h"
+
+typedef unsigned __attribute__((address_space(3))) *sl_lds_words;
+
+// LDS word |= v, &= v (the lanes of a wave may hit one word together)
+SL_DEV void sl_lds_or(unsigned *p, unsigned v)
+{
+    __hip_atomic_fetch_or((sl_lds_words)p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
+}
+SL_DEV void sl_lds_and(unsigned *p, unsigned v)
+{
+    __hip_atomic_fetch_and((sl_lds_words)p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
+}
+
+// Lane i reads lane i - S of its row of 16 lanes, 0 where there is none (S = 1, 2, 4, 8).
+template <int S>
+SL_DEV int sl_row_shr(int v) { return __builtin_amdgcn_update_dpp(0, v, 0x110 + S, 0xF, 0xF, true); }
+
+// Inclusive prefix sum over the 64 lanes (all active): four steps inside each row of 16 lanes,
+// then the totals of the rows below are added (read from the rows' last lanes).
+SL_DEV int sl_wave_iscan(int v)
+{
+    v += sl_row_shr<1>(v);
+    v += sl_row_shr<2>(v);
+    v += sl_row_shr<4>(v);
+    v += sl_row_shr<8>(v);
+    const int t0 = __builtin_amdgcn_readlane(v, 15), t1 = __builtin_amdgcn_readlane(v, 31),
+              t2 = __builtin_amdgcn_readlane(v, 47);
+    const int row = (int)(threadIdx.x & 63) >> 4;
+    return v + (row >= 1 ? t0 : 0) + (row >= 2 ? t1 : 0) + (row >= 3 ? t2 : 0);
+}
+
+// Value of lane `src` (any lane; all lanes call this together).
+SL_DEV int sl_lane_read(int v, int src) { return __builtin_amdgcn_ds_bpermute(4 * src, v); }
+
+// ---------------------------------------------------------------------------------- writer
+// Codes the k ascending indices idx[0..k) (LDS) of one chunk.  uv (LDS, G.ua words) receives
+// the bit vector, bits beyond its k + Q left as ones; rw (LDS, G.rem_bytes / 4 words) the
+// remainder fields, padding zero.  Returns Q (uniform).  Called by all 64 lanes; the caller
+// orders its own earlier LDS accesses before the call and reads uv / rw after it.
+// Indices that are not strictly ascending (a malformed plain record - a compressor never
+// produces one) are coded as gap 0, and a vector that would outgrow k + qmax bits is cut there.
+SL_DEV int sl_coded_emit(const SlCodedGeom &G, int lane, const unsigned short *idx, unsigned *uv, unsigned *rw)
+{
+    const int k = G.k, b = G.b, nrw = G.rem_bytes >> 2;
+    for (int w = lane; w < G.ua; w += 64) uv[w] = 0xFFFFFFFFu;
+    for (int w = lane; w < nrw; w += 64) rw[w] = 0u;
+    sl_wave_sync();
+    const int limit = k + G.qmax;            // bits of the longest vector
+    int carry = 0;
+    for (int m0 = 0; m0 < k; m0 += 64) {
+        const int m = m0 + lane;
+        const bool valid = m < k;
+        const int cur = valid ? (int)idx[m] : 0, prev = (valid && m > 0) ? (int)idx[m - 1] : -1;
+        int gap = valid ? cur - prev - 1 : 0;
+        if (gap < 0) gap = 0;
+        const int q = gap >> b;
+        const unsigned r = (unsigned)gap & ((1u << b) - 1u);
+        const int incl = sl_wave_iscan(q);
+        const int z = carry + incl + m;      // position of entry m's zero bit
+        if (valid) {
+            if (z < limit) sl_lds_and(&uv[z >> 5], ~(1u << (z & 31)));
+            if (b) {
+                const int bit = m * b, sh = bit & 31;
+                sl_lds_or(&rw[bit >> 5], r << sh);
+                if (sh + b > 32) sl_lds_or(&rw[(bit >> 5) + 1], r >> (32 - sh));
+            }
+        }
+        carry += __builtin_amdgcn_readlane(incl, 63);
+    }
+    sl_wave_sync();
+    return min(carry, G.qmax);
+}
+
+// ---------------------------------------------------------------------------------- reader
+// One directory entry (16-byte loads need only 4-byte alignment): for the chunk at position
+// `pos` of its group, the word offset of the group's run, the bit at which the chunk's vector
+// starts inside the run and the vector's length.  Quotient sums are clamped to qmax, so that
+// a malformed entry still describes a vector of at most k + qmax bits that starts below
+// 15 (k + qmax).
+struct SlVecPlace {
+    unsigned run_word;      // the group's run, in words from the start of the quotient section
+    int start_bit;          // first bit of the chunk's vector inside the run
+    int nbits;              // k + Q
+};
+
+// pointers into global memory, for addresses that are put together from integers (a generic
+// pointer would turn every access into a flat load that LDS waits have to sit out)
+typedef const unsigned char __attribute__((address_space(1))) *sl_gbytes;
+typedef const unsigned __attribute__((address_space(1))) *sl_gwords;
+typedef unsigned sl_u4u __attribute__((ext_vector_type(4), aligned(4)));
+typedef const sl_u4u __attribute__((address_space(1))) *sl_gu4;
+
+SL_DEV SlVecPlace sl_coded_dir_entry(const SlCodedGeom &G, sl_gbytes entry, int pos)
+{
+    SlVecPlace P;
+    const sl_gwords e = reinterpret_cast<sl_gwords>(entry);
+    P.run_word = e[0];
+    unsigned f[8];
+    const sl_u4u a = *reinterpret_cast<sl_gu4>(e + 1);
+    f[0] = a.x, f[1] = a.y, f[2] = a.z, f[3] = a.w;
+    if (G.qf == 2) {
+        const sl_u4u c = *reinterpret_cast<sl_gu4>(e + 5);
+        f[4] = c.x, f[5] = c.y, f[6] = c.z, f[7] = c.w;
+    } else {
+        f[4] = f[5] = f[6] = f[7] = 0u;
+    }
+    int before = 0, own = 0;
+#pragma unroll
+    for (int j = 0; j < SL_RICE_GROUP; ++j) {
+        unsigned q;
+        if (G.qf == 2) q = (f[j >> 1] >> (16 * (j & 1))) & 0xFFFFu;
+        else q = (f[j >> 2] >> (8 * (j & 3))) & 0xFFu;
+        const int qc = min((int)q, G.qmax);
+        before += j < pos ? qc : 0;
+        own = j == pos ? qc : own;
+    }
+    P.start_bit = pos * G.k + before;
+    P.nbits = G.k + own;
+    return P;
+}

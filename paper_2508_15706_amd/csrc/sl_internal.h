@@ -26,10 +26,28 @@ struct SlTensorDev {
     long long n_chunks;
     long long pay_off;      // byte offset of the tensor's block in a payload
     long long block_bytes;  // align16(16 + n_chunks * record_bytes)
-    long long group0;       // first coding group (8 chunks) of the tensor, list order
+    long long group0;       // first directory group (16 chunks) of the tensor, list order
+    // coded format: byte offsets inside a coded buffer of the tensor's block (table header first),
+    // of its directory and of its first fixed record; size of the block
+    long long cblk_off, cdir_off, cfix_off, cblk_bytes;
 };
 
-enum { SL_RICE_GROUP = 8 };   // chunks that are coded back to back (decoded sequentially)
+enum { SL_RICE_GROUP = 16 };  // chunks per directory entry of the coded format
+
+// Sizes of the coded format that follow from k and the value width (see sl_coded.h).
+struct SlCodedGeom {
+    int k, bits;
+    int b;                  // Rice parameter
+    int qmax;               // largest possible sum of a chunk's quotients, (4096 - k) >> b
+    int qf;                 // bytes of a quotient-sum field in the directory: 1 or 2
+    int dent;               // bytes of a directory entry: 4 + 16 * qf
+    int rem_bytes;          // the k remainders, padded to 4 bytes
+    int val_bytes;          // the k value fields: k * bits / 8
+    int cfix;               // fixed record: rem_bytes + val_bytes padded to 4
+    int hdr;                // table header of a tensor block
+    int ua;                 // words of a chunk's longest bit vector: ceil((k + qmax) / 32)
+    long long section;      // byte offset of the quotient section (end of the last block)
+};
 
 struct SlGroup {            // one coding group of the index coder
     int tensor;
@@ -79,7 +97,12 @@ struct sl_plan {
     SlTensorDev *d_tensors;
     SlGroup *d_groups;
     int64_t n_groups;
-    size_t rice_max_bytes;
+    size_t rice_max_bytes;      // upper bound of a coded buffer, 0 when the list is beyond the coded format
+    SlCodedGeom cg;
+    // workspace sections of the coded path: per-chunk bit vectors (cg.ua words each) and quotient
+    // sums, per-group run lengths and offsets (words), per-tensor section offsets (words)
+    size_t ws_uvec, ws_qsum, ws_gwords, ws_goff, ws_twords;
+    long long codes_wave_below; // list length below which the code kernel gives a chunk to a wave at any k
     // host copies
     SlTensorDev *h_tensors;
     // optional per-kernel timing (sl_profile_begin / sl_profile_end)
@@ -96,23 +119,24 @@ __host__ __device__ inline long long sl_lut_off(const SlChunkDesc &d, int hdr_by
 void sl_prof_mark(const sl_plan *p, int phase, hipStream_t st);
 
 // sl_compress and its variants behind one argument check (sl_api.hip)
+// (coded != null: the coded wire format is written as well, `coded_capacity` bytes available)
 int sl_compress_impl(sl_plan *p, float *e, const float *delta, const float *theta_local, float beta,
                      int flags, const void *pending, void *payload, void *workspace, void *stream,
-                     bool random = false, unsigned seed = 0u);
+                     bool random = false, unsigned seed = 0u, void *coded = nullptr, size_t coded_capacity = 0);
 
 // device address of the library's own scratch array on `device` (the current device), sl_noalloc.hip
 int sl_noalloc_scratch(int device, void **out);
 
 // launchers (defined next to their kernels)
 int slk_select(const sl_plan *p, float *e, const float *delta, const float *theta_local, float beta,
-               int frozen, const unsigned char *pending, unsigned char *payload, unsigned char *ws,
-               hipStream_t st);
+               int frozen, const unsigned char *pending, unsigned char *payload, unsigned char *coded,
+               unsigned char *ws, hipStream_t st);
 // the same with Random-k in place of Top-k
 int slk_select_random(const sl_plan *p, float *e, const float *delta, float beta, int frozen,
                       const unsigned char *pending, unsigned char *payload, unsigned char *ws, unsigned seed,
                       hipStream_t st);
 // B, C, D and (unless skip_residual) E
-int slk_quantize(const sl_plan *p, float *e, int skip_residual, unsigned char *payload,
+int slk_quantize(const sl_plan *p, float *e, int skip_residual, unsigned char *payload, unsigned char *coded,
                  unsigned char *ws, hipStream_t st);
 // E on its own: e[idx] -= LUT[code] for the entries of `payload`
 int slk_residual(const sl_plan *p, float *e, const unsigned char *payload, hipStream_t st);
@@ -131,7 +155,10 @@ int slk_pack_bits(const uint16_t *idx, const uint8_t *codes, const float *values
                   int bits, unsigned char *out, hipStream_t st);
 int slk_rice_encode(const sl_plan *p, const unsigned char *payload, unsigned char *out,
                     unsigned char *ws, hipStream_t st);
-int slk_rice_decode(const sl_plan *p, const unsigned char *in, size_t in_bytes, unsigned char *payload,
-                    hipStream_t st);
+// coded wire format: the passes that place the quotient bit vectors once a buffer's writers have run
+int slk_coded_finish(const sl_plan *p, unsigned char *out, unsigned char *ws, hipStream_t st);
+// mode 0: theta update from R coded payloads; 1: with the global momentum `mom`; 2: payloads[0] decoded into `plain`
+int slk_apply_coded(const sl_plan *p, int mode, float *theta, float *mom, float mu, unsigned char *plain,
+                    const void *const *payloads, const size_t *bytes, int R, float lr, hipStream_t st);
 int sl_rice_param(int k);
 void sl_note_hip_error(hipError_t e);

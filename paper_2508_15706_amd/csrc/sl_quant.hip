@@ -14,8 +14,6 @@
 // leaves, produced by kernels A and C) and a tree over the chunk leaves in
 // chunk order.  Both trees pad with +0.0 to a power of two and add adjacent
 // pairs, so the result does not depend on scheduling.
-#include <cstdlib>
-
 #include "sl_device.h"
 #include "sl_internal.h"
 
@@ -121,7 +119,19 @@ struct CodeArgs {
     unsigned char *payload;
     long long n_chunks;
     int k;
+    // coded wire format next to the plain record (null: not wanted): the value fields of a chunk are
+    // the same bytes in both, in the coded buffer they follow the chunk's remainder fields
+    unsigned char *coded;
+    const SlTensorDev *tensors;
+    int cfix, rem_bytes;
 };
+
+// Where a chunk's value fields go in the coded buffer (null when none is written).
+SL_DEV unsigned char *coded_values(const CodeArgs &A, const SlChunkDesc &d)
+{
+    if (!A.coded) return nullptr;
+    return A.coded + A.tensors[d.tensor].cfix_off + (long long)d.local_chunk * A.cfix + A.rem_bytes;
+}
 
 template <int LV>
 struct BinStacksT {      // one binary-counter stack of partial tree sums per bin, LV levels (k <= 2^(LV-1))
@@ -148,10 +158,8 @@ constexpr int CODE_WAVES = 2;        // waves per workgroup
 #ifndef SL_CODES_WAVE_FROM
 #define SL_CODES_WAVE_FROM 129        // k from which a wave, not a lane, owns a chunk in kernel C
 #endif
-#ifndef SL_CODES_WAVE_BELOW
-#define SL_CODES_WAVE_BELOW 32768     // ... and at any k on a list of fewer chunks than this: with a lane per chunk
-                                      // such a list leaves most of the chip without a wave
-#endif
+// (... and at any k on a list of fewer chunks than the plan's codes_wave_below, 32768 unless set: with a lane per
+// chunk such a list leaves most of the chip without a wave)
 constexpr int CODE_PITCH = 65;       // LDS row pitch in floats: conflict-free column reads
 
 // One LANE per chunk, 64 consecutive chunks per wave.  The selected values of
@@ -179,12 +187,13 @@ __global__ void __launch_bounds__(64 * CODE_WAVES, WAVES_PER_EU) k_codes(CodeArg
     const bool live = c < A.n_chunks;
 
     double mu = 0.0, T = 0.0;
-    unsigned char *codes_out = nullptr;
+    unsigned char *codes_out = nullptr, *codes_out2 = nullptr;
     if (live) {
         const SlChunkDesc d = A.desc[c];
         mu = A.tstat[d.tensor].mu;
         T = 9.0 * A.tstat[d.tensor].var;      // squared distance of the outer edges (3 sigma)
         codes_out = A.payload + d.rec_off + 3 * k / 2;
+        codes_out2 = coded_values(A, d);
     }
 
     BinStacksT<LV> st;
@@ -221,10 +230,12 @@ __global__ void __launch_bounds__(64 * CODE_WAVES, WAVES_PER_EU) k_codes(CodeArg
             if ((k & 15) == 0) {
                 if ((m & 15) == 15) {
                     if (live) reinterpret_cast<unsigned *>(codes_out)[m >> 4] = word;
+                    if (codes_out2) reinterpret_cast<unsigned *>(codes_out2)[m >> 4] = word;
                     word = 0;
                 }
             } else if ((m & 3) == 3) {
                 if (live) codes_out[m >> 2] = (unsigned char)(word >> (2 * (m & 12)));
+                if (codes_out2) codes_out2[m >> 2] = (unsigned char)(word >> (2 * (m & 12)));
                 if ((m & 15) == 15) word = 0;
             }
         }
@@ -266,7 +277,7 @@ __global__ void __launch_bounds__(256) k_codes_wave(CodeArgs A)
     const SlChunkDesc d = A.desc[c];
     const double mu = A.tstat[d.tensor].mu;
     const double T = 9.0 * A.tstat[d.tensor].var;      // squared distance of the outer edges (3 sigma)
-    unsigned char *codes_out = A.payload + d.rec_off + 3 * k / 2;
+    unsigned char *const record_codes = A.payload + d.rec_off + 3 * k / 2;
     const float *vin = A.vals + c * k;
     const int m0 = E * lane;
 
@@ -321,6 +332,7 @@ __global__ void __launch_bounds__(256) k_codes_wave(CodeArgs A)
 
     // codes: E/4 bytes per lane at byte E/4 * lane of the code stream (whole bytes: k % 4 == 0)
     const int nbytes = min(E / 4, max(0, (k - m0) / 4));
+    auto store_codes = [&](unsigned char *codes_out) __attribute__((always_inline)) {
     if constexpr (E < 4) {
         // 4 / E lanes share a byte, 16 / E lanes a word: OR the lanes' bits together inside the row
         constexpr int LW = 16 / E;                           // lanes per word
@@ -350,6 +362,9 @@ __global__ void __launch_bounds__(256) k_codes_wave(CodeArgs A)
         for (int b = 0; b < E / 4; ++b)
             if (b < nbytes) codes_out[(E / 4) * lane + b] = (unsigned char)(words[b / 4] >> (8 * (b & 3)));
     }
+    };
+    store_codes(record_codes);
+    if (unsigned char *second = coded_values(A, d)) store_codes(second);
     if (lane == 0) {
         A.leafC[0 * A.n_chunks + c] = r0;
         A.leafC[1 * A.n_chunks + c] = r1;
@@ -402,12 +417,13 @@ __global__ void __launch_bounds__(64 * CODE_WAVES, 2) k_codes_b(CodeArgs A)
     const bool live = c < A.n_chunks;
 
     double mu = 0.0, var = 0.0;
-    unsigned char *codes_out = nullptr;
+    unsigned char *codes_out = nullptr, *codes_out2 = nullptr;
     if (live) {
         const SlChunkDesc d = A.desc[c];
         mu = A.tstat[d.tensor].mu;
         var = A.tstat[d.tensor].var;
         codes_out = A.payload + d.rec_off + 3 * k / 2;
+        codes_out2 = coded_values(A, d);
     }
     int P = 1, top = 0;
     while (P < k) P <<= 1, ++top;
@@ -449,6 +465,11 @@ __global__ void __launch_bounds__(64 * CODE_WAVES, 2) k_codes_b(CodeArgs A)
                             for (int q = 0; q < BITS; ++q)
                                 codes_out[(m >> 3) * BITS + q] = (unsigned char)(bitbuf >> (8 * q));
                         }
+                        if (codes_out2) {
+#pragma unroll
+                            for (int q = 0; q < BITS; ++q)
+                                codes_out2[(m >> 3) * BITS + q] = (unsigned char)(bitbuf >> (8 * q));
+                        }
                         bitbuf = 0;
                     }
                 }
@@ -475,7 +496,8 @@ __global__ void __launch_bounds__(64 * CODE_WAVES, 2) k_codes_b(CodeArgs A)
 // count, centroid -> LUT[b] in the tensor block's header.
 __global__ void __launch_bounds__(RED_THREADS)
 k_tensor_lut(const SlTensorDev *tensors, const double *leafC, const unsigned *cnt,
-             long long n_chunks_total, int hdr_bytes, int rec_bytes, int nbins, unsigned char *payload)
+             long long n_chunks_total, int hdr_bytes, int rec_bytes, int nbins, unsigned char *payload,
+             unsigned char *coded, int cfix)
 {
     __shared__ RedShared sh;
     const SlTensorDev td = tensors[blockIdx.x];
@@ -496,20 +518,29 @@ k_tensor_lut(const SlTensorDev *tensors, const double *leafC, const unsigned *cn
         float cen = nb ? (float)(Sb / (double)nb) : 0.0f;
         if (cen == 0.0f) cen = 0.0f;        // never -0.0f on the wire
         reinterpret_cast<float *>(payload + td.pay_off)[b] = cen;
+        if (coded) reinterpret_cast<float *>(coded + td.cblk_off)[b] = cen;
     }
     // zero the padding that rounds the header (two floats at 1 bit) and the tensor block up to 16 bytes
-    if (b == 0 && tid >= nbins && 4 * tid < hdr_bytes) reinterpret_cast<float *>(payload + td.pay_off)[tid] = 0.0f;
+    if (b == 0 && tid >= nbins && 4 * tid < hdr_bytes) {
+        reinterpret_cast<float *>(payload + td.pay_off)[tid] = 0.0f;
+        if (coded) reinterpret_cast<float *>(coded + td.cblk_off)[tid] = 0.0f;
+    }
     const long long used = hdr_bytes + td.n_chunks * (long long)rec_bytes;
     if (b == 0 && tid < td.block_bytes - used) payload[td.pay_off + used + tid] = 0;
+    // the same table and padding in the coded buffer's block
+    const long long cused = (td.cfix_off - td.cblk_off) + td.n_chunks * (long long)cfix;
+    if (coded && b == 0 && tid < td.cblk_bytes - cused) coded[td.cblk_off + cused + tid] = 0;
 }
 
 // Unquantized values: there is no table, only the block padding is left to write.
 __global__ void __launch_bounds__(64)
-k_pad_blocks(const SlTensorDev *tensors, int rec_bytes, unsigned char *payload)
+k_pad_blocks(const SlTensorDev *tensors, int rec_bytes, unsigned char *payload, unsigned char *coded, int cfix)
 {
     const SlTensorDev td = tensors[blockIdx.x];
     const long long used = td.n_chunks * (long long)rec_bytes;
     if ((long long)threadIdx.x < td.block_bytes - used) payload[td.pay_off + used + threadIdx.x] = 0;
+    const long long cused = (td.cfix_off - td.cblk_off) + td.n_chunks * (long long)cfix;
+    if (coded && (long long)threadIdx.x < td.cblk_bytes - cused) coded[td.cblk_off + cused + threadIdx.x] = 0;
 }
 
 // ------------------------------------------------------------------ kernel E
@@ -582,7 +613,7 @@ int slk_residual(const sl_plan *p, float *e, const unsigned char *payload, hipSt
     return launch_residual(p, e, nullptr, payload, st);
 }
 
-int slk_quantize(const sl_plan *p, float *e, int skip_residual, unsigned char *payload,
+int slk_quantize(const sl_plan *p, float *e, int skip_residual, unsigned char *payload, unsigned char *coded,
                  unsigned char *ws, hipStream_t st)
 {
     if (p->n_chunks == 0) return SL_OK;
@@ -597,7 +628,7 @@ int slk_quantize(const sl_plan *p, float *e, int skip_residual, unsigned char *p
     if (p->bits == 32) {
         // nothing to quantize: kernel A wrote the values into the records
         hipLaunchKernelGGL(k_pad_blocks, dim3(p->n_tensors), dim3(64), 0, st, p->d_tensors, p->rec_bytes,
-                           payload);
+                           payload, coded, p->cg.cfix);
         if ((rc = check_launch())) return rc;
         sl_prof_mark(p, SL_PROF_LUT, st);
         if (!skip_residual) {
@@ -621,14 +652,14 @@ int slk_quantize(const sl_plan *p, float *e, int skip_residual, unsigned char *p
     C.payload = payload;
     C.n_chunks = p->n_chunks;
     C.k = k;
+    C.coded = coded;
+    C.tensors = p->d_tensors;
+    C.cfix = p->cg.cfix;
+    C.rem_bytes = p->cg.rem_bytes;
     const long long per_block = 64ll * CODE_WAVES;
     const unsigned nblk = (unsigned)((p->n_chunks + per_block - 1) / per_block);
-    // (the environment variable SL_CODES_WAVE_BELOW overrides the list length, for tests and tuning:
-    // both kernels write the same bytes)
-    long long wave_below = SL_CODES_WAVE_BELOW;
-    if (const char *env = std::getenv("SL_CODES_WAVE_BELOW"))
-        if (*env) wave_below = std::atoll(env);
-    const bool by_wave = k >= SL_CODES_WAVE_FROM || p->n_chunks < wave_below;
+    // (the list length is a field of the plan, sl_plan_set_codes_wave_below: both kernels write the same bytes)
+    const bool by_wave = k >= SL_CODES_WAVE_FROM || p->n_chunks < p->codes_wave_below;
     switch (p->bits) {
         case 1: hipLaunchKernelGGL(k_codes_b<1>, dim3(nblk), dim3(64 * CODE_WAVES), 0, st, C); break;
         case 3: hipLaunchKernelGGL(k_codes_b<3>, dim3(nblk), dim3(64 * CODE_WAVES), 0, st, C); break;
@@ -658,7 +689,7 @@ int slk_quantize(const sl_plan *p, float *e, int skip_residual, unsigned char *p
 
     hipLaunchKernelGGL(k_tensor_lut, dim3(p->n_tensors, 1 << p->bits), dim3(RED_THREADS), 0, st,
                        p->d_tensors, leafC, cnt, (long long)p->n_chunks, p->hdr_bytes, p->rec_bytes,
-                       1 << p->bits, payload);
+                       1 << p->bits, payload, coded, p->cg.cfix);
     if ((rc = check_launch())) return rc;
     sl_prof_mark(p, SL_PROF_LUT, st);
 

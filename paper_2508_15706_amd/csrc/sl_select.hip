@@ -28,8 +28,7 @@
 // Partial chunks, a candidate list that overflows (massive ties) and k > 512
 // take the general route: T bisected over the registers directly and one
 // ordered compaction over the registers - slower, same result.
-#include "sl_device.h"
-#include "sl_internal.h"
+#include "sl_coded.h"
 
 namespace {
 
@@ -61,6 +60,13 @@ struct SelectArgs {
     double *leafA;          // [2][n_chunks] per-chunk tree sums of x and x*x
     unsigned char *payload;
     long long n_chunks;
+    // coded wire format written next to the plain record (null: not wanted): the remainder fields go
+    // to their place in the buffer, the chunk's quotient bit vector and quotient sum to the workspace
+    unsigned char *coded;
+    const SlTensorDev *tensors;
+    SlCodedGeom G;
+    unsigned *uvec;
+    unsigned short *qsum;
 };
 
 SL_DEV int key_of(float x) { return (int)(__float_as_uint(x) & 0x7FFFFFFFu); }
@@ -780,6 +786,28 @@ __global__ void SL_SELECT_BOUNDS k_select(SelectArgs A)
         }
     }
 
+    // the coded form of the index list (the candidate list's LDS is free by now)
+    if (A.coded) {
+        const SlCodedGeom &G = A.G;
+        const SlTensorDev td = A.tensors[d.tensor];
+        unsigned *uv = reinterpret_cast<unsigned *>(smem), *rw = uv + G.ua;
+        const int nrw = G.rem_bytes >> 2;
+        const int Q = sl_coded_emit(G, lane, sel_idx, uv, rw);
+        unsigned char *fix = A.coded + td.cfix_off + (long long)d.local_chunk * G.cfix;
+        for (int w = lane; w < nrw; w += 64) reinterpret_cast<unsigned *>(fix)[w] = rw[w];
+        if (bits == 32) {
+            // unquantized: the values follow the remainders as they follow the indices of a plain record
+            for (int m = lane; m < k; m += 64) reinterpret_cast<float *>(fix + G.rem_bytes)[m] = sel_val[m];
+        } else if ((G.val_bytes & 3) && lane == 0) {
+            // the record's last word holds value fields and padding: cleared here, the codes come later
+            *reinterpret_cast<unsigned *>(fix + G.cfix - 4) = 0u;
+        }
+        unsigned *uvo = A.uvec + (size_t)c * G.ua;
+        const int words = (k + Q + 31) >> 5;
+        for (int w = lane; w < words; w += 64) uvo[w] = uv[w];
+        if (lane == 0) A.qsum[c] = (unsigned short)Q;
+    }
+
     // per-chunk leaves of the quantizer's mean / variance sums
     double s1, s2;
     constexpr int MAXE = GPL == 0 ? 64 : GPL <= 2 ? 1 : GPL / 2;      // pow2ceil(largest k served) / 64
@@ -803,8 +831,8 @@ static unsigned host_fmix32(unsigned h)
 }
 
 static int launch_select(const sl_plan *p, float *e, const float *delta, const float *theta_local, float beta,
-                         int frozen, const unsigned char *pending, unsigned char *payload, unsigned char *ws,
-                         bool sub_only, bool random, unsigned seed, hipStream_t st)
+                         int frozen, const unsigned char *pending, unsigned char *payload, unsigned char *coded,
+                         unsigned char *ws, bool sub_only, bool random, unsigned seed, hipStream_t st)
 {
     if (p->n_chunks == 0) return SL_OK;
     const int k = p->k;
@@ -824,6 +852,7 @@ static int launch_select(const sl_plan *p, float *e, const float *delta, const f
     A.seed_hash = host_fmix32(seed);
     {
         size_t b = pruned ? sizeof(uint2) * cand_cap(k > 256 ? 16 : 8) : sizeof(int) * SL_SELECT_LIST_CAP;
+        // (the coded form's bit vector and remainder words reuse this first part: at most 128 + 64 words)
         b += (6 * (size_t)k + 7) & ~(size_t)7;
         b = (b + 15) & ~(size_t)15;
         // k > 256: a pending record of whole words and whole groups of eight entries is staged in LDS
@@ -841,6 +870,11 @@ static int launch_select(const sl_plan *p, float *e, const float *delta, const f
     A.leafA = sub_only ? nullptr : reinterpret_cast<double *>(ws + p->ws_leafA);
     A.payload = payload;
     A.n_chunks = p->n_chunks;
+    A.coded = sub_only ? nullptr : coded;
+    A.tensors = p->d_tensors;
+    A.G = p->cg;
+    A.uvec = (sub_only || !coded) ? nullptr : reinterpret_cast<unsigned *>(ws + p->ws_uvec);
+    A.qsum = (sub_only || !coded) ? nullptr : reinterpret_cast<unsigned short *>(ws + p->ws_qsum);
     // waves (= chunks) per workgroup: 4 adjacent chunks when their LDS fits
     const int wpb = 4 * (size_t)A.lds_per_wave <= 65536 ? 4 : 1;
     const dim3 grid((unsigned)((p->n_chunks + wpb - 1) / wpb)), block(64 * wpb);
@@ -877,20 +911,20 @@ static int launch_select(const sl_plan *p, float *e, const float *delta, const f
 }
 
 int slk_select(const sl_plan *p, float *e, const float *delta, const float *theta_local, float beta,
-               int frozen, const unsigned char *pending, unsigned char *payload, unsigned char *ws,
-               hipStream_t st)
+               int frozen, const unsigned char *pending, unsigned char *payload, unsigned char *coded,
+               unsigned char *ws, hipStream_t st)
 {
-    return launch_select(p, e, delta, theta_local, beta, frozen, pending, payload, ws, false, false, 0u, st);
+    return launch_select(p, e, delta, theta_local, beta, frozen, pending, payload, coded, ws, false, false, 0u, st);
 }
 
 int slk_select_random(const sl_plan *p, float *e, const float *delta, float beta, int frozen,
                       const unsigned char *pending, unsigned char *payload, unsigned char *ws, unsigned seed,
                       hipStream_t st)
 {
-    return launch_select(p, e, delta, nullptr, beta, frozen, pending, payload, ws, false, true, seed, st);
+    return launch_select(p, e, delta, nullptr, beta, frozen, pending, payload, nullptr, ws, false, true, seed, st);
 }
 
 int slk_sub_topk(const sl_plan *p, float *m, hipStream_t st)
 {
-    return launch_select(p, m, nullptr, nullptr, 1.0f, 0, nullptr, nullptr, nullptr, true, false, 0u, st);
+    return launch_select(p, m, nullptr, nullptr, 1.0f, 0, nullptr, nullptr, nullptr, nullptr, true, false, 0u, st);
 }

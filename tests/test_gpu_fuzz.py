@@ -57,10 +57,9 @@ SEED0 = int(os.environ.get("SL_FUZZ_SEED", "7000"))
 
 
 @pytest.mark.parametrize("case", range(N_CASES))
-def test_random_configuration(sl, oracle, case, monkeypatch):
+def test_random_configuration(sl, oracle, case):
     rng = np.random.default_rng(SEED0 + case)
-    if case % 2:      # short lists take the wave-per-chunk code kernel: every other case forces the other one
-        monkeypatch.setenv("SL_CODES_WAVE_BELOW", "0")
+    coded = (case // 2) % 2 == 1      # every other pair of cases travels in the coded wire format
     bits = int(rng.choice([1, 2, 2, 2, 3, 4, 32]))
     k = int(rng.choice([4, 8, 12, 16, 32, 40, 64, 100, 128, 136, 160, 200, 248, 256, 320, 512, 520, 1024, 2048]))
     if bits != 2:
@@ -77,6 +76,8 @@ def test_random_configuration(sl, oracle, case, monkeypatch):
     except sl.SparseLoCoError:
         pytest.skip("generator produced a chunk smaller than k")   # the oracle rejects it as well
     assert plan.num_chunks == oracle.num_chunks(descs)
+    if case % 2:      # short lists take the wave-per-chunk code kernel: every other case forces the other one
+        sl.sl_plan_set_codes_wave_below(plan, 0)
     ws = sl.alloc_workspace(plan)
     theta0 = rng.normal(0, 0.02, n).astype(np.float32)
     theta = torch.from_numpy(theta0.copy()).cuda()
@@ -85,7 +86,7 @@ def test_random_configuration(sl, oracle, case, monkeypatch):
     e_ref = [x.cpu().numpy().copy() for x in e]
     pend = [None] * R
     for rnd in range(2):
-        pays, refs = [], []
+        pays, refs, wires, sizes = [], [], [], []
         for r in range(R):
             heavy = rng.random() < 0.5
             delta = ((rng.standard_t(3, n) if heavy else rng.normal(0, 1, n)) * 1e-3).astype(np.float32)
@@ -94,15 +95,23 @@ def test_random_configuration(sl, oracle, case, monkeypatch):
             out = sl.alloc_payload(plan)
             out.fill_(0xAB)
             d = torch.from_numpy(delta).cuda()
+            wire = torch.full((sl.sl_rice_max_bytes(plan) + 32,), 0xCD, dtype=torch.uint8, device="cuda") if coded else None
+
+            def compress(flags=0, pending=None):
+                if coded:      # the same call, emitting the coded format next to the plain record
+                    sl.sl_compress_coded(plan, e[r], d, beta, out, wire, ws, flags=flags, pending=pending)
+                else:
+                    sl.sl_compress(plan, e[r], d, beta, out, ws, flags=flags, pending=pending)
+            emitted = coded and mode in ("eager", "deferred", "frozen")
             if mode == "eager":
-                sl.sl_compress(plan, e[r], d, beta, out, ws)
+                compress()
                 ref = oracle.compress_b(descs, k, bits, e_ref[r], delta, beta)
             elif mode == "deferred":
-                sl.sl_compress(plan, e[r], d, beta, out, ws, flags=sl.SL_COMPRESS_DEFER_RESIDUAL, pending=pend[r])
+                compress(flags=sl.SL_COMPRESS_DEFER_RESIDUAL, pending=pend[r])
                 pend[r] = out
                 ref = oracle.compress_b(descs, k, bits, e_ref[r], delta, beta)
             elif mode == "frozen":
-                sl.sl_compress(plan, e[r], d, beta, out, ws, flags=sl.SL_COMPRESS_EF_FROZEN)
+                compress(flags=sl.SL_COMPRESS_EF_FROZEN)
                 ref = oracle.compress_b(descs, k, bits, e_ref[r], delta, beta, ef_frozen=True)
             elif mode == "random":
                 seed = int(rng.integers(0, 2**32))
@@ -119,9 +128,25 @@ def test_random_configuration(sl, oracle, case, monkeypatch):
             assert np.array_equal(got, ref), (f"case {case} {mode} bits={bits} k={k} round {rnd} worker {r}: "
                                               f"payload differs at {np.nonzero(got != ref)[0][:6]}; {descs}")
             assert sl.sl_payload_validate(plan, out, ws)
+            if coded:
+                if not emitted:   # these modes have no coded variant: the payload is transcoded
+                    sl.sl_rice_encode(plan, out, wire, ws)
+                    torch.cuda.synchronize()
+                want = oracle.rice_encode_b(descs, k, bits, ref)
+                have = wire.cpu().numpy()
+                assert int(have[8:16].view(np.uint64)[0]) == want.size, f"case {case} {mode}: coded size"
+                assert np.array_equal(have[:want.size], want), (
+                    f"case {case} {mode} bits={bits} k={k} round {rnd} worker {r}: coded bytes differ at "
+                    f"{np.nonzero(have[:want.size] != want)[0][:6]}; {descs}")
+                assert bool((have[want.size:] == 0xCD).all()), "bytes beyond the coded size were written"
+                wires.append(wire)
+                sizes.append(want.size)
             pays.append(out)
             refs.append(ref)
-        sl.sl_decompress_avg_apply(plan, theta, pays, lr)
+        if coded:
+            sl.sl_decompress_avg_apply_coded(plan, theta, wires, sizes, lr)
+        else:
+            sl.sl_decompress_avg_apply(plan, theta, pays, lr)
         oracle.decompress_avg_apply_b(descs, k, bits, theta_ref, refs, lr)
         torch.cuda.synchronize()
         assert_f32_close(theta.cpu().numpy(), theta_ref, f"case {case} theta round {rnd}")

@@ -51,8 +51,10 @@ def gpu_compress(sl, plan, e_host, d_host, beta, flags=0):
     return e.cpu().numpy(), pay[:plan.payload_bytes].cpu().numpy(), pay
 
 
-def check_compress(sl, oracle, descs, n, k, e0, delta, beta, flags=0, what=""):
+def check_compress(sl, oracle, descs, n, k, e0, delta, beta, flags=0, what="", wave_below=None):
     plan = sl.sl_plan_create(descs, k)
+    if wave_below is not None:
+        sl.sl_plan_set_codes_wave_below(plan, wave_below)
     assert plan.num_chunks == oracle.num_chunks(descs)
     assert plan.payload_bytes == oracle.payload_bytes(descs, k)
     e_gpu, pay_gpu, _ = gpu_compress(sl, plan, e0, delta, beta, flags)
@@ -69,12 +71,10 @@ def check_compress(sl, oracle, descs, n, k, e0, delta, beta, flags=0, what=""):
 # --------------------------------------------------------------------------- compress
 @pytest.mark.parametrize("k,lane_codes", [(k, False) for k in (4, 8, 20, 32, 64, 128, 256, 512, 1000)] +
                          [(k, True) for k in (4, 8, 20, 32, 64, 128)])
-def test_compress_small_list_all_k_paths(sl, oracle, k, lane_codes, monkeypatch):
+def test_compress_small_list_all_k_paths(sl, oracle, k, lane_codes):
     """Several tiles, ragged edges in both directions, 16-column matrix, 1-D tails;
     k covers every pruning width, the byte-wise record writer and the unpruned path.
     Up to k = 128 the code kernel is chosen by the length of the list: both choices are run."""
-    if lane_codes:
-        monkeypatch.setenv("SL_CODES_WAVE_BELOW", "0")
     if k <= 256:      # smallest chunk: 22 x 18 = 396 elements
         shapes = [(150, 210, TILE), (1, 9000, FLAT), (1024, 16, TILE), (64, 64, TILE),
                   (1, 4096 + 1030, FLAT), (128, 192, TILE)]
@@ -86,7 +86,7 @@ def test_compress_small_list_all_k_paths(sl, oracle, k, lane_codes, monkeypatch)
     rng = np.random.default_rng(100 + k)
     e0 = rng.normal(0, 1e-3, n).astype(np.float32)
     delta = rng.normal(0, 1e-3, n).astype(np.float32)
-    check_compress(sl, oracle, descs, n, k, e0, delta, 0.95, what="small list")
+    check_compress(sl, oracle, descs, n, k, e0, delta, 0.95, what="small list", wave_below=0 if lane_codes else None)
 
 
 def test_compress_dense_case_k_4096(sl, oracle):
@@ -429,51 +429,6 @@ def test_argument_errors_are_reported_not_launched(sl):
 
 
 # --------------------------------------------------------------------------- index coder
-@pytest.mark.parametrize("k", [4, 20, 32, 64, 128, 256, 1000])
-def test_rice_transcode_matches_oracle(sl, oracle, k):
-    """sl_rice_encode produces the oracle's coded bytes, sl_rice_decode restores the payload
-    (from the GPU's and from the oracle's coded buffer); a truncated buffer is decoded without
-    leaving the buffer."""
-    if k <= 256:
-        shapes = [(150, 210, TILE), (1, 4096 * 37 + 1100, FLAT), (1024, 16, TILE), (64, 64, TILE), (256, 320, TILE)]
-    else:
-        shapes = [(160, 224, TILE), (1, 4096 * 20 + 1000, FLAT)]
-    descs, n = layout_list(shapes)
-    rng = np.random.default_rng(700 + k)
-    e0 = rng.normal(0, 1e-3, n).astype(np.float32)
-    delta = (1e-3 * rng.standard_t(3, n)).astype(np.float32)
-    plan = sl.sl_plan_create(descs, k)
-    ws = sl.alloc_workspace(plan)
-    _, pay_host, pay_dev = gpu_compress(sl, plan, e0, delta, 0.95)
-    ref_pay = oracle.compress(descs, k, e0.copy(), delta, 0.95)
-    assert np.array_equal(pay_host, ref_pay)
-    ref_enc = oracle.rice_encode(descs, k, ref_pay)
-
-    cap = sl.sl_rice_max_bytes(plan)
-    assert cap >= ref_enc.size
-    out = torch.full((cap,), 0xCD, dtype=torch.uint8, device="cuda")
-    sl.sl_rice_encode(plan, pay_dev, out, ws)
-    torch.cuda.synchronize()
-    got = out.cpu().numpy()
-    size = int(got[8:16].view(np.uint64)[0])
-    assert size == ref_enc.size
-    assert np.array_equal(got[:size], ref_enc)
-    assert size < plan.payload_bytes or k <= 8            # the coded form is smaller
-
-    for src in (out, torch.from_numpy(np.concatenate([ref_enc, np.zeros(16, np.uint8)])).cuda()):
-        back = torch.full((max(16, plan.payload_bytes),), 0xEE, dtype=torch.uint8, device="cuda")
-        sl.sl_rice_decode(plan, src, size, back)
-        torch.cuda.synchronize()
-        assert np.array_equal(back[:plan.payload_bytes].cpu().numpy(), ref_pay)
-
-    back = torch.zeros(max(16, plan.payload_bytes), dtype=torch.uint8, device="cuda")
-    sl.sl_rice_decode(plan, out, size // 2 // 16 * 16, back)   # truncated input: defined, in bounds
-    torch.cuda.synchronize()
-    with pytest.raises(sl.SparseLoCoError):
-        sl.sl_rice_encode(plan, pay_dev, out[:cap - 16], ws)   # capacity too small
-    plan.close()
-
-
 # --------------------------------------------------------------------------- pseudo-gradient formed on the fly
 @pytest.mark.parametrize("k,flags", [(32, 0), (64, 0), (64, 1), (512, 0)])
 def test_compress_params_equals_compress_of_the_difference(sl, oracle, k, flags):
