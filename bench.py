@@ -1,15 +1,21 @@
 #!/usr/bin/env python3
 """Benchmark of the SparseLoCo compress + aggregate path on one MI355X.
 
-One "step" is one worker-round: sl_compress of one worker's pseudo-gradient
+One "step" is one worker-round: the compression of one worker's pseudo-gradient
 (error-feedback accumulate, chunk Top-k, 2-bit quantizer, residual, payload) and
-sl_decompress_avg_apply of R workers' payloads fused with the outer SGD step,
-over the whole tensor list.  Inputs are synthetic and resident in HBM before
-the timed region.  Prints ONE JSON line.
+the aggregate of R workers' payloads fused with the outer SGD step, over the
+whole tensor list.  Inputs are synthetic and resident in HBM before the timed
+region.  Two wire formats are timed in the same run: the plain one (12-bit
+indices: sl_compress + sl_decompress_avg_apply) and the coded one (Rice-coded
+indices emitted by the compressor and decoded inside the aggregate:
+sl_compress_coded + sl_decompress_avg_apply_coded); --wire chooses which of them
+is the line's `value`, the other is reported under `other_wire`.
+Prints ONE JSON line.
 
-  python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 4] [--no-cpu-baseline]
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 4 | --list paper512M] [--wire plain|coded]
 """
 import argparse
+import hashlib
 import json
 import os
 import sys
@@ -20,43 +26,49 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E peak
 PROFILE_TAGS = {4: "1p8B"}
+# Table 1 of the paper (512M model, R = 8, H = 15): pseudo-gradient size per worker and sync in MB at
+# density 0.78 % (k = 32) and 3.12 % (k = 128), and the bits per index its coder reaches
+# (appendix "Compression of indices in Top-k")
+PAPER_TABLE1_MB = {32: 5.45, 128: 17.21}
+PAPER_INDEX_BITS = {32: 8.9, 128: 6.6, 256: 5.6}
 
 
-def cpu_baseline(w, sample_layers):
-    """The CPU oracle, as it stands, on a bounded sample of the same workload: the
-    tensors of the first `sample_layers` transformer layers, R workers compressed
-    (each timed) and one aggregation (timed)."""
+def sources_sha():
+    """Hash of the kernel sources: a counter profile is only quoted while it matches them."""
+    h = hashlib.sha256()
+    d = os.path.join(ROOT, "paper_2508_15706_amd", "csrc")
+    for name in sorted(os.listdir(d)):
+        if name.endswith((".hip", ".h")):
+            h.update(name.encode())
+            h.update(open(os.path.join(d, name), "rb").read())
+    return h.hexdigest()[:16]
+
+
+def cpu_baseline(w, descs, host, sample_desc):
+    """The CPU oracle, as it stands, on the benchmarked list itself: one compress of worker 0 from host
+    copies of the bench's own e and delta, one aggregate of host copies of the R payloads the GPU
+    produced.  Its outputs are compared with the GPU's for the same round (a whole-list parity check
+    that costs nothing extra)."""
     import numpy as np
-    import torch
     from oracle import oracle
-    from paper_2508_15706_amd import synth
 
-    names = tuple(f"l{l}." for l in range(sample_layers))
-    specs = [s for s in w.specs if s.name.startswith(names)] or list(w.specs)
-    base = min(s.offset for s in specs)
-    descs = [(s.rows, s.cols, s.offset - base, s.layout) for s in specs]
-    n = max(d[2] + d[0] * d[1] for d in descs)
-    n_el = sum(d[0] * d[1] for d in descs)
-    g = torch.Generator().manual_seed(synth.seed_for(w.config_id, 50, 0))
-    t_comp, pays = [], []
-    for r in range(w.R):
-        e = (torch.randn(n, generator=g) * w.scale).numpy()
-        d = (torch.randn(n, generator=g) * w.scale).numpy()
-        t0 = time.perf_counter()
-        pays.append(oracle.compress(descs, w.k, e, d, w.beta))
-        t_comp.append(time.perf_counter() - t0)
-    theta = (torch.randn(n, generator=g) * 0.02).numpy()
     t0 = time.perf_counter()
-    oracle.decompress_avg_apply(descs, w.k, theta, pays, w.lr)
+    pay = oracle.compress(descs, w.k, host["e"], host["delta"], w.beta)
+    t_comp = time.perf_counter() - t0
+    same_payload = bool(np.array_equal(pay, host["payloads"][0]))
+    same_e = bool(np.array_equal(host["e"].view(np.uint32), host["e_gpu"].view(np.uint32)))
+    t0 = time.perf_counter()
+    oracle.decompress_avg_apply(descs, w.k, host["theta"], host["payloads"], w.lr)
     t_apply = time.perf_counter() - t0
-    t_round = sum(t_comp) / len(t_comp) + t_apply
+    same_theta = bool(np.array_equal(host["theta"].view(np.uint32), host["theta_gpu"].view(np.uint32)))
+    n_el = sum(d[0] * d[1] for d in descs)
     return {
-        "value": n_el / t_round / 1e9, "unit": "Gelem/s", "cores": oracle.max_threads(),
+        "value": n_el / (t_comp + t_apply) / 1e9, "unit": "Gelem/s", "cores": oracle.max_threads(),
         "kind": "oracle",
-        "sample": f"tensors of the first {sample_layers} layers of the list ({len(specs)} tensors, "
-                  f"{n_el} elements): mean of R={w.R} compress calls + one aggregation; "
-                  f"cpu work {sum(t_comp) + t_apply:.1f} s",
-        "ms_compress": 1e3 * sum(t_comp) / len(t_comp), "ms_apply": 1e3 * t_apply,
+        "sample": f"{sample_desc}: one compress of worker 0 (host copies of the bench's e and delta) + one "
+                  f"aggregate of the R={w.R} payloads; cpu work {t_comp + t_apply:.1f} s",
+        "ms_compress": 1e3 * t_comp, "ms_apply": 1e3 * t_apply,
+        "gpu_equals_oracle": {"payload": same_payload, "e": same_e, "theta": same_theta},
     }
 
 
@@ -66,6 +78,12 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", type=int, default=4)
+    ap.add_argument("--list", choices=["config", "paper178M", "paper512M", "paper2B"], default="config",
+                    help="the tensor list: the configuration's (default) or one of the paper's own three "
+                         "architectures (vocabulary 32000, every dimension a multiple of 64)")
+    ap.add_argument("--wire", choices=["plain", "coded"], default="plain",
+                    help="wire format of the timed steps: 12-bit indices, or Rice-coded indices emitted by "
+                         "the compressor and decoded inside the aggregate")
     ap.add_argument("--k", type=int, default=None)
     ap.add_argument("--workers", type=int, default=None,
                     help="number of workers R whose payloads are aggregated (default: the configuration's)")
@@ -78,18 +96,21 @@ def main():
     ap.add_argument("--outer-steps", action="store_true",
                     help="also time the dense outer steps of the DiLoCo family (extra arenas: R + 1)")
     ap.add_argument("--delta-buffers", type=int, default=3)
-    ap.add_argument("--cpu-layers", type=int, default=4)
+    ap.add_argument("--cpu-sample-layers", type=int, default=None,
+                    help="time the CPU oracle on the tensors of the first layers only (default: the whole list "
+                         "while it has at most 2.5e9 elements)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--mode", choices=["deferred", "eager"], default="deferred",
                     help="deferred: the error update of a round is folded into the next round's "
                          "read of e (SL_COMPRESS_DEFER_RESIDUAL + pending); eager: scattered update "
-                         "inside every sl_compress")
+                         "inside every compress call")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (the R workers are R payload buffers on "
               "it, no collectives); --gpus must be 1", file=sys.stderr)
         sys.exit(2)
 
+    import numpy as np
     import torch
     from paper_2508_15706_amd import binding as sl
     from paper_2508_15706_amd import synth
@@ -99,7 +120,12 @@ def main():
     torch.cuda.set_device(0)
     dev = torch.device("cuda:0")
 
-    w = synth.workload(args.config, k=args.k, flat=args.flat)
+    if args.list == "config":
+        w = synth.workload(args.config, k=args.k, flat=args.flat)
+        list_name = f"config {w.config_id}: {w.name}"
+    else:
+        w = synth.paper_workload(args.list, k=args.k, flat=args.flat)
+        list_name = f"the paper's own {w.name[6:]} architecture"
     if args.workers is not None:
         if not 1 <= args.workers <= 64:
             raise SystemExit("--workers must be between 1 and 64")
@@ -108,12 +134,16 @@ def main():
     plan = sl.sl_plan_create(descs, w.k) if args.bits == 2 else sl.sl_plan_create_bits(descs, w.k, args.bits)
     N, n_chunks, arena = plan.num_elements, plan.num_chunks, w.arena
     ws = sl.alloc_workspace(plan)
+    cap = sl.sl_rice_max_bytes(plan)
+    if cap == 0:
+        raise SystemExit("list too long for the coded format")
 
-    # state: theta, worker 0's error buffer (persistent), R payload buffers
+    # state: theta, worker 0's error buffer (persistent), R payloads in both wire formats
     theta = torch.empty(arena, dtype=torch.float32, device=dev)
     synth.fill_theta(w, theta)
     e0 = torch.zeros(arena, dtype=torch.float32, device=dev)
     pays = [sl.alloc_payload(plan) for _ in range(w.R)]
+    wires = [torch.zeros(cap, dtype=torch.uint8, device=dev) for _ in range(w.R)]
     deltas = [torch.empty(arena, dtype=torch.float32, device=dev) for _ in range(args.delta_buffers)]
 
     # set-up (untimed): the other workers' payloads of this round, each from its own delta
@@ -121,52 +151,59 @@ def main():
     for r in range(1, w.R):
         synth.fill_delta(w, deltas[0], 1, r)
         scratch_e.zero_()
-        sl.sl_compress(plan, scratch_e, deltas[0], w.beta, pays[r], ws)
+        sl.sl_compress_coded(plan, scratch_e, deltas[0], w.beta, pays[r], wires[r], ws)
     del scratch_e
     for i, d in enumerate(deltas):             # worker 0's pseudo-gradients of successive rounds
         synth.fill_delta(w, d, 1 + i, 0)
     torch.cuda.synchronize()
+    wire_bytes = [cap] + [sl.coded_size(wires[r]) for r in range(1, w.R)]   # worker 0's: the buffer's capacity
 
     # worker 0's payload alternates between two buffers so that the previous round's
-    # payload can be handed back as `pending`
+    # record can be handed back as `pending`
     own = [pays[0], sl.alloc_payload(plan)]
     state = {"pending": None, "i": 0}
 
-    def step(mode):
+    def step(mode, wire):
         i = state["i"]
         out = own[i % 2]
-        if mode == "deferred":
-            sl.sl_compress(plan, e0, deltas[i % len(deltas)], w.beta, out, ws,
-                           flags=sl.SL_COMPRESS_DEFER_RESIDUAL, pending=state["pending"])
-            state["pending"] = out
+        flags = sl.SL_COMPRESS_DEFER_RESIDUAL if mode == "deferred" else sl.SL_COMPRESS_DEFAULT
+        if wire == "coded":
+            sl.sl_compress_coded(plan, e0, deltas[i % len(deltas)], w.beta, out, wires[0], ws, flags=flags,
+                                 pending=state["pending"])
+            sl.sl_decompress_avg_apply_coded(plan, theta, wires, wire_bytes, w.lr)
         else:
-            sl.sl_compress(plan, e0, deltas[i % len(deltas)], w.beta, out, ws, pending=state["pending"])
-            state["pending"] = None
-        sl.sl_decompress_avg_apply(plan, theta, [out] + pays[1:], w.lr)
+            sl.sl_compress(plan, e0, deltas[i % len(deltas)], w.beta, out, ws, flags=flags, pending=state["pending"])
+            sl.sl_decompress_avg_apply(plan, theta, [out] + pays[1:], w.lr)
+        state["pending"] = out if mode == "deferred" else None
         state["i"] = i + 1
 
-    def timed(mode, steps):
+    def flush():
+        if state["pending"] is not None:
+            sl.sl_residual_apply(plan, e0, state["pending"])
+            state["pending"] = None
+
+    def timed(mode, wire, steps):
         for _ in range(args.warmup):
-            step(mode)
+            step(mode, wire)
         torch.cuda.synchronize()
         sl.sl_profile_begin(plan, steps)
         t0 = time.perf_counter()
         for _ in range(steps):
-            step(mode)
-        if state["pending"] is not None:
-            # the last round's error update is applied inside the timed region, so that no
-            # work of the K rounds is left outstanding when the clock stops
-            sl.sl_residual_apply(plan, e0, state["pending"])
-            state["pending"] = None
+            step(mode, wire)
+        # the last round's error update is applied inside the timed region, so that no
+        # work of the K rounds is left outstanding when the clock stops
+        flush()
         torch.cuda.synchronize()
         dt = time.perf_counter() - t0
-        return dt, sl.sl_profile_end(plan)
+        return 1e3 * dt / steps, sl.sl_profile_end(plan)
 
-    other = "eager" if args.mode == "deferred" else "deferred"
-    dt_other, prof_other = timed(other, max(2, args.steps // 4))
-    ms_other = 1e3 * dt_other / max(2, args.steps // 4)
-    dt, prof = timed(args.mode, args.steps)
-    ms_step = 1e3 * dt / args.steps
+    few = max(2, args.steps // 4)
+    other_mode = "eager" if args.mode == "deferred" else "deferred"
+    other_wire = "coded" if args.wire == "plain" else "plain"
+    ms_other_mode, prof_other_mode = timed(other_mode, args.wire, few)
+    ms_other_wire, prof_other_wire = timed(args.mode, other_wire, max(few, args.steps // 2))
+    ms_step, prof = timed(args.mode, args.wire, args.steps)
+    own_coded_bytes = sl.coded_size(wires[0])      # (one of the two loops wrote worker 0's coded payload)
 
     graph_info = None
     if args.graph:
@@ -176,10 +213,10 @@ def main():
         cycle = 2 * len(deltas) // math.gcd(2, len(deltas))
         if state["i"] % cycle:
             for _ in range(cycle - state["i"] % cycle):
-                step(args.mode)
+                step(args.mode, args.wire)
         if state["pending"] is None and args.mode == "deferred":
             for _ in range(cycle):
-                step(args.mode)                  # the captured first step expects a pending payload
+                step(args.mode, args.wire)       # the captured first step expects a pending payload
         torch.cuda.synchronize()
         side = torch.cuda.Stream()
         side.wait_stream(torch.cuda.current_stream())
@@ -187,7 +224,7 @@ def main():
         with torch.cuda.stream(side):
             with torch.cuda.graph(graph, stream=side):
                 for _ in range(cycle):
-                    step(args.mode)
+                    step(args.mode, args.wire)
         torch.cuda.synchronize()
         replays = max(1, -(-args.steps // cycle))
         for _ in range(max(1, args.warmup // cycle)):
@@ -196,26 +233,36 @@ def main():
         t0 = time.perf_counter()
         for _ in range(replays):
             graph.replay()
-        if state["pending"] is not None:
-            sl.sl_residual_apply(plan, e0, state["pending"])
-            state["pending"] = None
+        flush()
         torch.cuda.synchronize()
         ms_eager = ms_step
         ms_step = 1e3 * (time.perf_counter() - t0) / (replays * cycle)
         graph_info = {"steps_per_graph": cycle, "replays": replays, "eager_ms_per_step": ms_eager}
         args.steps = replays * cycle
 
+    # ---- algorithmic bytes.  Plain wire: 20 B per element + (R + 1) payloads of 7k/4 B per chunk and a
+    # table per tensor.  Coded wire: the payloads at their coded sizes (worker 0's written, R read).
     rec = 3 * w.k // 2 + w.k * args.bits // 8
     hdr = 0 if args.bits == 32 else max(16, 4 << args.bits)
-    bytes_round = 20 * N + (w.R + 1) * rec * n_chunks + hdr * len(descs) * (w.R + 1)
-    # dominant kernel: accumulate + select.  Algorithmic bytes per launch: read e and
-    # delta, write e (12 B/element) + the packed indices it writes (3k/2 B per chunk)
+    plain_payload = rec * n_chunks + hdr * len(descs)
+    coded_read = own_coded_bytes + sum(wire_bytes[1:])
+
+    def path_bytes(wire):
+        return 20 * N + ((w.R + 1) * plain_payload if wire == "plain" else own_coded_bytes + coded_read)
+
+    def index_bytes(wire):      # what kernel A writes per launch besides e: the index part of the payload
+        if wire == "plain":
+            return (3 * w.k // 2 + (4 * w.k if args.bits == 32 else 0)) * n_chunks
+        return own_coded_bytes - (w.k * args.bits // 8) * n_chunks - hdr * len(descs)
+
+    # dominant kernel: accumulate + select.  Algorithmic bytes per launch: read e and delta, write e
+    # (12 B per element) + the index part of the payload
     sel_ms = prof["select"][0]
-    sel_bytes = 12 * N + (3 * w.k // 2 + (4 * w.k if args.bits == 32 else 0)) * n_chunks
+    sel_bytes = 12 * N + index_bytes(args.wire)
     sel_gbs = sel_bytes / (sel_ms * 1e-3) / 1e9 if sel_ms > 0 else 0.0
     apply_ms = prof["apply"][0]
-    apply_bytes = 8 * N + w.R * (rec * n_chunks + hdr * len(descs))
-    compress_ms = sum(prof[p][0] for p in ("select", "stats", "codes", "lut", "residual"))
+    apply_bytes = 8 * N + (w.R * plain_payload if args.wire == "plain" else coded_read)
+    compress_ms = sum(prof[p][0] for p in ("select", "stats", "codes", "lut", "residual", "index"))
 
     # a plain device copy of the same footprint as a practical ceiling (context only)
     src, dst = deltas[0], deltas[1 % len(deltas)]
@@ -228,17 +275,30 @@ def main():
     ev1.record()
     torch.cuda.synchronize()
     copy_gbs = 5 * 8 * arena / (ev0.elapsed_time(ev1) * 1e-3) / 1e9
+    synth.fill_delta(w, dst, 1 + (1 % len(deltas)), 0)      # the copy overwrote a pseudo-gradient: restore it
 
-    # HBM bytes per launch of the dominant kernel as measured with rocprofv3 counters
-    # (FETCH_SIZE + WRITE_SIZE, scaled by a plain copy; written by
-    # paper_2508_15706_amd/rocprof_summary.py from a profiled run of this same command)
-    traffic = None
-    tpath = os.path.join(ROOT, "profiles", f"traffic_config{w.config_id}_{PROFILE_TAGS.get(w.config_id, '')}.json")
-    if os.path.exists(tpath) and not args.flat and args.k is None and args.bits == 2 and args.workers is None:
-        tk = json.load(open(tpath))["kernels"]
-        name = next((n for n in tk if n.startswith("k_select")), None)
-        if name and tk[name]["fetch_bytes"] is not None and tk[name]["write_bytes"] is not None:
-            traffic = tk[name]["fetch_bytes"] + tk[name]["write_bytes"]
+    # HBM bytes per launch of the dominant kernel as measured with rocprofv3 counters (FETCH_SIZE +
+    # WRITE_SIZE, scaled by a plain copy; written by paper_2508_15706_amd/rocprof_summary.py from profiled
+    # runs of this same command).  Quoted only while the profile was taken with the kernel sources of this
+    # tree and for this command's workload; otherwise null, with the reason.
+    traffic, traffic_source = None, "no counter profile for this workload"
+    tag = PROFILE_TAGS.get(w.config_id, "")
+    tpath = os.path.join(ROOT, "profiles", f"traffic_config{w.config_id}_{tag}_{args.wire}.json")
+    default_workload = (args.list == "config" and not args.flat and args.k is None and args.bits == 2 and
+                        args.workers is None and args.mode == "deferred")
+    if os.path.exists(tpath) and default_workload:
+        tj = json.load(open(tpath))
+        name = next((n for n in tj["kernels"] if n.startswith("k_select")), None)
+        if tj.get("sources_sha") != sources_sha():
+            traffic_source = f"profiles/{os.path.basename(tpath)} is older than the kernel sources: not quoted"
+        elif name and tj["kernels"][name]["fetch_bytes"] is not None and tj["kernels"][name]["write_bytes"] is not None:
+            traffic = tj["kernels"][name]["fetch_bytes"] + tj["kernels"][name]["write_bytes"]
+            traffic_source = (f"profiles/{os.path.basename(tpath)}: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of "
+                              f"`bench.py {tj.get('bench_args', '')}` at kernel sources {tj['sources_sha']} "
+                              "(a separate run, not this one)")
+
+    def frac(nbytes, ms):
+        return nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS
 
     out = {
         "metric": "pseudo-gradient elements compressed+aggregated/sec",
@@ -247,27 +307,41 @@ def main():
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
-        "config": {"workload": f"config {w.config_id}: {w.name}, {len(descs)} fp32 tensors, "
+        "config": {"workload": f"{list_name}, {len(descs)} fp32 tensors, "
                                f"N={N}, chunk 4096 ({'flat runs' if args.flat else '64x64 tiles / 1-D runs'}), "
                                f"k={w.k}, R={w.R}, beta={w.beta}, lr={w.lr}, "
-                               f"{'fp32' if args.bits == 32 else str(args.bits) + '-bit'} values, {args.mode} residual",
-                   "n_elements": N, "n_chunks": n_chunks, "k": w.k, "R": w.R, "value_bits": args.bits},
+                               f"{'fp32' if args.bits == 32 else str(args.bits) + '-bit'} values, {args.mode} residual, "
+                               f"{args.wire} wire format",
+                   "n_elements": N, "n_chunks": n_chunks, "k": w.k, "R": w.R, "value_bits": args.bits,
+                   "wire": args.wire},
+        "argv": " ".join(sys.argv[1:]),
         "roofline": {"bound": "hbm", "kernel": "k_select (EF accumulate + chunk Top-k)",
                      "achieved": sel_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": sel_gbs / HBM_PEAK_GBS, "traffic": traffic,
+                     "frac": sel_gbs / HBM_PEAK_GBS, "traffic": traffic, "traffic_source": traffic_source,
                      "ms": sel_ms, "algorithmic_bytes": sel_bytes},
-        "path_hbm": {"algorithmic_bytes_per_step": bytes_round,
-                     "achieved_GBps": bytes_round / (ms_step * 1e-3) / 1e9,
-                     "frac_of_peak": bytes_round / (ms_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
+        "path_hbm": {"algorithmic_bytes_per_step": path_bytes(args.wire),
+                     "achieved_GBps": path_bytes(args.wire) / (ms_step * 1e-3) / 1e9,
+                     "frac_of_peak": frac(path_bytes(args.wire), ms_step),
                      "device_copy_GBps": copy_gbs},
         "mode": args.mode, "hip_graph": graph_info,
-        "other_mode": {"mode": other, "ms_per_step": ms_other, "value": N / (ms_other * 1e-3) / 1e9,
-                       "kernels_ms": {p: prof_other[p][0] for p in prof_other}},
+        "other_mode": {"mode": other_mode, "ms_per_step": ms_other_mode, "value": N / (ms_other_mode * 1e-3) / 1e9,
+                       "kernels_ms": {p: prof_other_mode[p][0] for p in prof_other_mode}},
+        "other_wire": {"wire": other_wire, "ms_per_step": ms_other_wire, "value": N / (ms_other_wire * 1e-3) / 1e9,
+                       "algorithmic_bytes_per_step": path_bytes(other_wire),
+                       "frac_of_peak": frac(path_bytes(other_wire), ms_other_wire),
+                       "kernels_ms": {p: prof_other_wire[p][0] for p in prof_other_wire}},
         "kernels_ms": {p: prof[p][0] for p in prof},
         "compress_ms": compress_ms, "apply_ms": apply_ms,
         "apply_GBps": apply_bytes / (apply_ms * 1e-3) / 1e9 if apply_ms > 0 else 0.0,
+        "payload": {"plain_bytes": plain_payload, "coded_bytes": own_coded_bytes,
+                    "bits_per_index": (own_coded_bytes - hdr * len(descs)) * 8 / (n_chunks * w.k) - args.bits,
+                    "paper_bits_per_index": PAPER_INDEX_BITS.get(w.k)},
     }
-    # index coder (not part of the timed step): coded size and transcoding time of one payload
+    if args.list == "paper512M" and args.bits == 2 and w.k in PAPER_TABLE1_MB:
+        # Table 1 of the paper quotes the message size per worker on this very model
+        out["payload"]["table1"] = {"coded_MB": own_coded_bytes / 1e6, "paper_MB": PAPER_TABLE1_MB[w.k],
+                                    "density_percent": 100.0 * w.k / 4096}
+
     def time_ms(fn, reps=3):
         fn()
         torch.cuda.synchronize()
@@ -279,18 +353,17 @@ def main():
         torch.cuda.synchronize()
         return a.elapsed_time(b) / reps
 
-    if args.bits == 2:
-        coded = torch.empty(sl.sl_rice_max_bytes(plan), dtype=torch.uint8, device=dev)
-        back = sl.alloc_payload(plan)
-        enc_ms = time_ms(lambda: sl.sl_rice_encode(plan, own[0], coded, ws))
-        coded_bytes = int(coded[8:16].cpu().numpy().view("uint64")[0])
-        dec_ms = time_ms(lambda: sl.sl_rice_decode(plan, coded, coded_bytes, back))
-        out["index_coder"] = {
-            "plain_bytes": plan.payload_bytes, "coded_bytes": coded_bytes,
-            "bits_per_index": coded_bytes * 8 / (n_chunks * w.k) - 2.0,
-            "lossless": bool(torch.equal(back[:plan.payload_bytes], own[0][:plan.payload_bytes])),
-            "encode_ms": enc_ms, "decode_ms": dec_ms,
-        }
+    # the stand-alone transcoders (not part of the timed step)
+    back = sl.alloc_payload(plan)
+    coded2 = torch.zeros(cap, dtype=torch.uint8, device=dev)
+    enc_ms = time_ms(lambda: sl.sl_rice_encode(plan, pays[w.R - 1], coded2, ws))
+    dec_ms = time_ms(lambda: sl.sl_rice_decode(plan, coded2, sl.coded_size(coded2), back))
+    out["payload"]["transcoders"] = {
+        "encode_ms": enc_ms, "decode_ms": dec_ms,
+        "lossless": bool(torch.equal(back[:plan.payload_bytes], pays[w.R - 1][:plan.payload_bytes])),
+        "equals_compressor_output": bool(w.R < 2 or torch.equal(coded2[:wire_bytes[-1]], wires[-1][:wire_bytes[-1]]))}
+    del back, coded2
+
     if args.outer_steps:
         # the DiLoCo-family entry points, each timed alone on the same list (context rows, not
         # part of the step): algorithmic bytes = 4 B per element per stream touched
@@ -298,6 +371,7 @@ def main():
         dirs = [torch.empty(arena, dtype=torch.float32, device=dev) for _ in range(w.R)]
         for r, dbuf in enumerate(dirs):
             synth.fill_delta(w, dbuf, 2, r)
+        pl_apply = 8 * N + w.R * plain_payload
         rows = {
             "lom_direction": (lambda: sl.sl_lom_direction(plan, mom, deltas[0], 0.9, dirs[0]), 16 * N),
             "dense_avg_apply": (lambda: sl.sl_dense_avg_apply(plan, theta, None, dirs, w.lr), (w.R + 2) * 4 * N),
@@ -305,7 +379,10 @@ def main():
                                          (w.R + 4) * 4 * N),
             "decompress_avg_apply_nesterov": (
                 lambda: sl.sl_decompress_avg_apply_nesterov(plan, theta, mom, [own[0]] + pays[1:], w.lr, 0.9),
-                apply_bytes + 8 * N),
+                pl_apply + 8 * N),
+            "decompress_avg_apply_nesterov_coded": (
+                lambda: sl.sl_decompress_avg_apply_nesterov_coded(plan, theta, mom, wires, wire_bytes, w.lr, 0.9),
+                8 * N + coded_read + 8 * N),
             "sub_topk": (lambda: sl.sl_sub_topk(plan, mom), 4 * N + 4 * w.k * n_chunks),
         }
         out["outer_steps"] = {}
@@ -315,9 +392,51 @@ def main():
             ms = time_ms(fn, reps=10)
             out["outer_steps"][name] = {"ms": ms, "algorithmic_GBps": nbytes / (ms * 1e-3) / 1e9}
         del mom, dirs
+
     if not args.no_cpu_baseline:
-        del deltas, theta, e0
-        out["cpu_baseline"] = cpu_baseline(w, args.cpu_layers)
+        # One more round on the GPU (eager, plain wire, state as the timed rounds left it) with host copies
+        # of its inputs taken first; the oracle then does the same round on the host's cores.
+        layers = args.cpu_sample_layers
+        if layers is None and N > 2_500_000_000:
+            layers = 4
+        if layers is None:
+            sub_specs, sample_desc = list(w.specs), "the whole benchmarked list"
+        else:
+            names = tuple(f"l{l}." for l in range(layers))
+            sub_specs = [s for s in w.specs if s.name.startswith(names)] or list(w.specs)
+            sample_desc = (f"the tensors of the first {layers} layers of the list ({len(sub_specs)} tensors, "
+                           f"{sum(s.numel for s in sub_specs)} elements)")
+        lo = min(s.offset for s in sub_specs)
+        hi = max(s.offset + s.numel for s in sub_specs)
+        sub_descs = [(s.rows, s.cols, s.offset - lo, s.layout) for s in sub_specs]
+        sub_plan = plan if layers is None else (sl.sl_plan_create(sub_descs, w.k) if args.bits == 2 else None)
+        if sub_plan is None or args.bits != 2:
+            out["cpu_baseline"] = None
+        else:
+            d_dev = deltas[state["i"] % len(deltas)]
+            host = {"e": e0[lo:hi].cpu().numpy(), "delta": d_dev[lo:hi].cpu().numpy(),
+                    "theta": theta[lo:hi].cpu().numpy()}
+            sub_pays = [sl.alloc_payload(sub_plan) for _ in range(w.R)]
+            sub_ws = sl.alloc_workspace(sub_plan)
+            e_sub, th_sub = e0[lo:hi], theta[lo:hi]
+            if layers is not None:       # the other workers' payloads on the sub-list
+                tmp_e = torch.zeros(hi - lo, dtype=torch.float32, device=dev)
+                tmp_d = torch.empty(arena, dtype=torch.float32, device=dev)
+                for r in range(1, w.R):
+                    synth.fill_delta(w, tmp_d, 1, r)
+                    tmp_e.zero_()
+                    sl.sl_compress(sub_plan, tmp_e, tmp_d[lo:hi], w.beta, sub_pays[r], sub_ws)
+                del tmp_e, tmp_d
+            else:
+                sub_pays[1:] = pays[1:]
+            sl.sl_compress(sub_plan, e_sub, d_dev[lo:hi], w.beta, sub_pays[0], sub_ws)
+            sl.sl_decompress_avg_apply(sub_plan, th_sub, sub_pays, w.lr)
+            torch.cuda.synchronize()
+            host["payloads"] = [p[:sub_plan.payload_bytes].cpu().numpy() for p in sub_pays]
+            host["e_gpu"] = e_sub.cpu().numpy()
+            host["theta_gpu"] = th_sub.cpu().numpy()
+            del deltas, theta, e0, e_sub, th_sub
+            out["cpu_baseline"] = cpu_baseline(w, sub_descs, host, sample_desc)
     print(json.dumps(out), flush=True)
 
 

@@ -240,7 +240,25 @@ int sl_plan_create_bits(const sl_tensor *tensors, int n_tensors, int k, int valu
     if (p->n_chunks > 0) {
         const size_t b_desc = desc.size() * sizeof(SlChunkDesc),
                      b_t = (size_t)n_tensors * sizeof(SlTensorDev);
+        std::vector<SlCodedDesc> cdesc;
+        try {
+            cdesc.resize(desc.size());
+        } catch (const std::bad_alloc &) {
+            sl_plan_destroy(p);
+            return SL_ERR_NOMEM;
+        }
+        for (size_t i = 0; i < desc.size(); ++i) {
+            const SlTensorDev &D = tdev[(size_t)desc[i].tensor];
+            cdesc[i].lut_off = D.cblk_off;
+            cdesc[i].dir_off = D.cdir_off + (long long)(desc[i].local_chunk / SL_RICE_GROUP) * p->cg.dent;
+            cdesc[i].fix_off = D.cfix_off + (long long)desc[i].local_chunk * p->cg.cfix;
+            cdesc[i].pos = desc[i].local_chunk % SL_RICE_GROUP;
+            cdesc[i].reserved = 0;
+        }
         if ((err = hipMalloc((void **)&p->d_desc, b_desc)) != hipSuccess ||
+            (err = hipMalloc((void **)&p->d_cdesc, cdesc.size() * sizeof(SlCodedDesc))) != hipSuccess ||
+            (err = hipMemcpy(p->d_cdesc, cdesc.data(), cdesc.size() * sizeof(SlCodedDesc),
+                             hipMemcpyHostToDevice)) != hipSuccess ||
             (err = hipMalloc((void **)&p->d_tensors, b_t)) != hipSuccess ||
             (err = hipMalloc((void **)&p->d_groups, groups.size() * sizeof(SlGroup))) != hipSuccess ||
             (err = hipMemcpy(p->d_groups, groups.data(), groups.size() * sizeof(SlGroup),
@@ -260,6 +278,7 @@ int sl_plan_destroy(sl_plan *p)
 {
     if (!p) return SL_OK;
     if (p->d_desc) (void)hipFree(p->d_desc);
+    if (p->d_cdesc) (void)hipFree(p->d_cdesc);
     if (p->d_tensors) (void)hipFree(p->d_tensors);
     if (p->d_groups) (void)hipFree(p->d_groups);
     std::free(p->h_tensors);

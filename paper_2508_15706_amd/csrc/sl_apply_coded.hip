@@ -25,13 +25,17 @@ namespace {
 #ifndef SL_CAPPLY_STAGE
 #define SL_CAPPLY_STAGE 4096      // LDS bytes for one batch of staged workers
 #endif
-#ifndef SL_CAPPLY_PF
-#define SL_CAPPLY_PF 6            // words per lane fetched ahead of the theta loads
+#ifndef SL_CAPPLY_PFF
+#define SL_CAPPLY_PFF 4           // words per lane fetched ahead of the theta loads: tables and fixed records,
+#endif
+#ifndef SL_CAPPLY_PFU
+#define SL_CAPPLY_PFU 2           // ... bit vectors
 #endif
 
 struct CodedApplyArgs {
     SlCodedGeom G;
     const SlChunkDesc *desc;
+    const SlCodedDesc *cdesc;
     const SlTensorDev *tensors;
     float *theta;
     float *mom;              // global outer momentum buffer (Nesterov variant), else null
@@ -69,15 +73,12 @@ __global__ void __launch_bounds__(256) k_apply_coded(CodedApplyArgs A)
     float *acc = reinterpret_cast<float *>(smem);
     unsigned char *stage = smem + (DECODE ? 0 : SL_CHUNK * sizeof(float));
     const SlChunkDesc d = A.desc[c];
-    const SlTensorDev td = A.tensors[d.tensor];
+    const SlCodedDesc cd = A.cdesc[c];
     const int bits = TWO_BIT ? 2 : G.bits;
     const int hdr = TWO_BIT ? 16 : G.hdr, hdrw = hdr >> 2;
     const int fwp = A.fwp, uraw = G.ua + 1, nrw = G.rem_bytes >> 2;
     // one staged worker: [table header][fixed record][uraw words of the bit vector][k 16-bit values]
     const int off_u = 4 * fwp, off_h = (off_u + 4 * uraw + 15) & ~15;
-    const long long dir_off = td.cdir_off + (long long)(d.local_chunk >> 4) * G.dent;
-    const long long fix_off = td.cfix_off + (long long)d.local_chunk * G.cfix;
-    const int pos = d.local_chunk & (SL_RICE_GROUP - 1);
 
     float *tc = DECODE ? nullptr : A.theta + d.base;
     const int lr = lane >> 4, lc = (lane & 15) * 4;
@@ -93,58 +94,60 @@ __global__ void __launch_bounds__(256) k_apply_coded(CodedApplyArgs A)
         const unsigned hi = (unsigned)sl_lane_read((int)(unsigned)(my_ptr >> 32), r);
         return reinterpret_cast<sl_gbytes>(((unsigned long long)hi << 32) | lo);
     };
-    // Step 1 for the batch that starts at worker r0: lane r < nb learns where worker r0 + r keeps
-    // the chunk's bit vector: first word (clamped into the section), shift and length.
+    // Step 1, once for all workers: lane r < R learns where worker r keeps the chunk's bit vector:
+    // first word (bounded by the section's size when it is used), shift and length.  This is the one
+    // load that the loads of the vectors depend on.
     unsigned v_word = 0;         // first word of the vector, from the start of the section
-    int v_meta = 0;              // (first bit inside that word) | (bits << 5)
-    auto read_directory = [&](int r0, int nb) {
-        const sl_gbytes p = payload_of(min(r0 + lane, SL_MAX_WORKERS - 1));
-        SlVecPlace P;
-        P.run_word = 0, P.start_bit = 0, P.nbits = k;
-        if (lane < nb) P = sl_coded_dir_entry(G, p + dir_off, pos);
+    int v_meta = k << 5;         // (first bit inside that word) | (bits << 5)
+    if (lane < A.R) {
+        const SlVecPlace P = sl_coded_dir_entry(G, reinterpret_cast<sl_gbytes>(my_ptr) + cd.dir_off, cd.pos);
         v_word = P.run_word + (unsigned)(P.start_bit >> 5);
         v_meta = (P.start_bit & 31) | (P.nbits << 5);
-    };
-    // Word w of a batch's staging area, from global memory: first nb blocks of (table, fixed
-    // record), then nb vectors of uraw words (all ones beyond a payload's end: no entries).
-    auto src_word = [&](int r0, int nb, int w) -> unsigned {
-        const int nf = nb * fwp, nu = nb * uraw;
-        const bool in_f = w < nf, in_u = !in_f && w < nf + nu;
-        const int wu = w - nf;
-        const int r = in_f ? (int)__umulhi((unsigned)w, A.magic_f) : in_u ? (int)__umulhi((unsigned)wu, A.magic_u) : 0;
-        const int q = in_f ? w - r * fwp : wu - r * uraw;
+    }
+    // A batch's staging area has two parts, fetched by separate loops so that each is straight-line
+    // code: nb blocks of (table header, fixed record), fwp words each, and nb bit vectors of uraw words
+    // (all ones beyond a payload's end: no entries).  Word w of either part, from global memory:
+    auto src_fixed = [&](int r0, int nb, int w) -> unsigned {
+        const bool valid = w < nb * fwp;
+        const int r = valid ? (int)__umulhi((unsigned)w, A.magic_f) : 0, q = w - r * fwp;
         const sl_gbytes p = payload_of(r0 + r);
-        const unsigned word0 = (unsigned)sl_lane_read((int)v_word, r);
-        const unsigned limit = (unsigned)sl_lane_read((int)my_words, r0 + r);
-        unsigned v = 0xFFFFFFFFu;
-        if (in_f) {
-            v = q < hdrw ? reinterpret_cast<sl_gwords>(p + td.cblk_off)[q]
-                         : reinterpret_cast<sl_gwords>(p + fix_off)[q - hdrw];
-        } else if (in_u) {
-            const unsigned long long at = (unsigned long long)word0 + (unsigned)q;
-            if (at < limit) v = reinterpret_cast<sl_gwords>(p + G.section)[at];
-        }
-        return v;
+        const long long at = q < hdrw ? cd.lut_off + 4 * q : cd.fix_off + 4 * (q - hdrw);
+        return valid ? *reinterpret_cast<sl_gwords>(p + at) : 0u;
     };
-    // where word w of a batch's staging area lives in LDS
-    auto stage_word = [&](int nb, int w) -> unsigned * {
-        const int nf = nb * fwp;
-        const bool in_f = w < nf;
-        const int wu = w - nf;
-        const int r = in_f ? (int)__umulhi((unsigned)w, A.magic_f) : (int)__umulhi((unsigned)wu, A.magic_u);
-        const int q = in_f ? w - r * fwp : wu - r * uraw;
-        return reinterpret_cast<unsigned *>(stage + r * A.slot_bytes + (in_f ? 0 : off_u)) + q;
+    auto src_vector = [&](int r0, int nb, int w) -> unsigned {
+        const bool in = w < nb * uraw;
+        const int r = in ? (int)__umulhi((unsigned)w, A.magic_u) : 0, q = w - r * uraw;
+        const sl_gbytes p = payload_of(r0 + r);
+        const unsigned word0 = (unsigned)sl_lane_read((int)v_word, r0 + r);
+        const unsigned limit = (unsigned)sl_lane_read((int)my_words, r0 + r);
+        const unsigned long long at = (unsigned long long)word0 + (unsigned)q;
+        return (in && at < limit) ? reinterpret_cast<sl_gwords>(p + G.section)[at] : 0xFFFFFFFFu;
+    };
+    // ... and where it lives in LDS
+    auto stage_fixed = [&](int w) -> unsigned * {
+        const int r = (int)__umulhi((unsigned)w, A.magic_f), q = w - r * fwp;
+        return reinterpret_cast<unsigned *>(stage + r * A.slot_bytes) + q;
+    };
+    auto stage_vector = [&](int w) -> unsigned * {
+        const int r = (int)__umulhi((unsigned)w, A.magic_u), q = w - r * uraw;
+        return reinterpret_cast<unsigned *>(stage + r * A.slot_bytes + off_u) + q;
     };
 
-    constexpr int PF = SL_CAPPLY_PF;
-    unsigned pf[PF];
+    constexpr int PFF = SL_CAPPLY_PFF, PFU = SL_CAPPLY_PFU;
+    unsigned pf_f[PFF], pf_u[PFU], pn_f[PFF], pn_u[PFU];
     const int nb0 = min(A.batch, A.R);
-    read_directory(0, nb0);
-#pragma unroll
-    for (int u = 0; u < PF; ++u) pf[u] = src_word(0, nb0, lane + 64 * u);
 
     sl_f4 th[DECODE ? 1 : 16], mo[NESTEROV ? 16 : 1];
     float *mc = NESTEROV ? A.mom + d.base : nullptr;
+    // The first 64 * PF words of the first batch are fetched BEFORE the theta loads: loads complete in
+    // order, so the decode then waits for these few words only and runs while the chunk's 16 KB of
+    // theta are in flight.  (Tried: the directory entry one chunk ahead, a wave taking several chunks
+    // in turn - the loop costs more registers than a wave has next to a second one; and half of the
+    // theta loads ahead of these words, which leaves too little of the stream behind the decode.)
+#pragma unroll
+    for (int u = 0; u < PFF; ++u) pf_f[u] = src_fixed(0, nb0, lane + 64 * u);
+#pragma unroll
+    for (int u = 0; u < PFU; ++u) pf_u[u] = src_vector(0, nb0, lane + 64 * u);
     if constexpr (!DECODE) {
         if (full) {
             const unsigned o0 = 4u * (lr * stride + lc), step = 16u * stride;
@@ -186,30 +189,43 @@ __global__ void __launch_bounds__(256) k_apply_coded(CodedApplyArgs A)
     for (int r0 = 0; r0 < A.R; r0 += A.batch) {
         const int nb = min(A.batch, A.R - r0);
         sl_wave_sync();
-        // ---- step 2: stage the batch
+        // ---- step 2: stage the batch.  The first words of both parts are in registers: fetched ahead of
+        // the theta loads for the first batch (pf_*), while the previous batch was decoded for the others
+        // (pn_*: registers of their own, so that the wait in front of the first batch's words stays
+        // "everything but the theta loads" - one array written on both paths would make it "everything").
         {
-            const int nw = nb * (fwp + uraw);
-            int wb = 0;
+            const int nf = nb * fwp, nu = nb * uraw;
             if (r0 == 0) {
 #pragma unroll
-                for (int u = 0; u < PF; ++u) {
-                    const int w = lane + 64 * u;
-                    if (w < nw) *stage_word(nb, w) = pf[u];
-                }
-                wb = 64 * PF;
+                for (int u = 0; u < PFF; ++u)
+                    if (lane + 64 * u < nf) *stage_fixed(lane + 64 * u) = pf_f[u];
+#pragma unroll
+                for (int u = 0; u < PFU; ++u)
+                    if (lane + 64 * u < nu) *stage_vector(lane + 64 * u) = pf_u[u];
             } else {
-                read_directory(r0, nb);
+#pragma unroll
+                for (int u = 0; u < PFF; ++u)
+                    if (lane + 64 * u < nf) *stage_fixed(lane + 64 * u) = pn_f[u];
+#pragma unroll
+                for (int u = 0; u < PFU; ++u)
+                    if (lane + 64 * u < nu) *stage_vector(lane + 64 * u) = pn_u[u];
             }
-            constexpr int SU = 4;
-            for (; wb < nw; wb += 64 * SU) {
-                unsigned v[SU];
+            for (int wb = 64 * PFF; wb < nf; wb += 128) {      // what the registers did not hold
+                const unsigned v0 = src_fixed(r0, nb, wb + lane), v1 = src_fixed(r0, nb, wb + 64 + lane);
+                if (wb + lane < nf) *stage_fixed(wb + lane) = v0;
+                if (wb + 64 + lane < nf) *stage_fixed(wb + 64 + lane) = v1;
+            }
+            for (int wb = 64 * PFU; wb < nu; wb += 128) {
+                const unsigned v0 = src_vector(r0, nb, wb + lane), v1 = src_vector(r0, nb, wb + 64 + lane);
+                if (wb + lane < nu) *stage_vector(wb + lane) = v0;
+                if (wb + 64 + lane < nu) *stage_vector(wb + 64 + lane) = v1;
+            }
+            if (r0 + A.batch < A.R) {
+                const int nbn = min(A.batch, A.R - r0 - A.batch);
 #pragma unroll
-                for (int u = 0; u < SU; ++u) v[u] = src_word(r0, nb, wb + 64 * u + lane);
+                for (int u = 0; u < PFF; ++u) pn_f[u] = src_fixed(r0 + A.batch, nbn, lane + 64 * u);
 #pragma unroll
-                for (int u = 0; u < SU; ++u) {
-                    const int w = wb + 64 * u + lane;
-                    if (w < nw) *stage_word(nb, w) = v[u];
-                }
+                for (int u = 0; u < PFU; ++u) pn_u[u] = src_vector(r0 + A.batch, nbn, lane + 64 * u);
             }
             sl_wave_sync();
         }
@@ -221,7 +237,7 @@ __global__ void __launch_bounds__(256) k_apply_coded(CodedApplyArgs A)
                 const int slot = s0 + lane;
                 const int r = slot >> A.uwp_log2, j = slot & (uwp - 1);
                 const bool live = slot < slots && j < G.ua;
-                const int meta = sl_lane_read(v_meta, live ? r : 0);
+                const int meta = sl_lane_read(v_meta, live ? r0 + r : 0);
                 const int sh = meta & 31, n = meta >> 5;
                 unsigned zeros = 0;
                 unsigned short *hs = reinterpret_cast<unsigned short *>(stage + (live ? r : 0) * A.slot_bytes + off_h);
@@ -340,12 +356,15 @@ __global__ void __launch_bounds__(256) k_apply_coded(CodedApplyArgs A)
             }
             const unsigned char *vals = stage + 4 * hdrw + G.rem_bytes;
             for (int q = lane; q < G.val_bytes; q += 64) rec[nbytes + q] = vals[q];
-            if (d.local_chunk == 0)
-                for (int q = lane; q < hdrw; q += 64)
-                    reinterpret_cast<unsigned *>(A.plain + td.pay_off)[q] = reinterpret_cast<const unsigned *>(stage)[q];
-            if (d.local_chunk == td.n_chunks - 1)
-                for (long long q = hdr + td.n_chunks * (long long)A.rec_bytes + lane; q < td.block_bytes; q += 64)
-                    A.plain[td.pay_off + q] = 0;
+            if (d.local_chunk == 0 || d.local_chunk == A.tensors[d.tensor].n_chunks - 1) {
+                const SlTensorDev td = A.tensors[d.tensor];
+                if (d.local_chunk == 0)
+                    for (int q = lane; q < hdrw; q += 64)
+                        reinterpret_cast<unsigned *>(A.plain + td.pay_off)[q] = reinterpret_cast<const unsigned *>(stage)[q];
+                if (d.local_chunk == td.n_chunks - 1)
+                    for (long long q = hdr + td.n_chunks * (long long)A.rec_bytes + lane; q < td.block_bytes; q += 64)
+                        A.plain[td.pay_off + q] = 0;
+            }
         } else {
             // ---- step 5: the additions, worker by worker
             auto value_at = [&](const unsigned char *slot, int m) -> float {
@@ -481,6 +500,7 @@ int slk_apply_coded(const sl_plan *p, int mode, float *theta, float *mom, float 
     CodedApplyArgs A;
     A.G = p->cg;
     A.desc = p->d_desc;
+    A.cdesc = p->d_cdesc;
     A.tensors = p->d_tensors;
     A.theta = theta;
     A.mom = mom;
@@ -494,7 +514,11 @@ int slk_apply_coded(const sl_plan *p, int mode, float *theta, float *mom, float 
     A.E = (G.k & 7) ? 4 : 8;
     A.rec_bytes = p->rec_bytes;
     A.slot_bytes = (int)(((((size_t)4 * A.fwp + 4 * ((size_t)G.ua + 1) + 15) & ~(size_t)15) + 2 * (size_t)G.k + 15) & ~(size_t)15);
+    A.uwp_log2 = pow2_log2_at_least(G.ua);
     int batch = SL_CAPPLY_STAGE / A.slot_bytes;
+    // (a whole number of passes of step 3, where a pass holds several workers' vectors)
+    const int per_pass = A.uwp_log2 < 6 ? 64 >> A.uwp_log2 : 1;
+    if (batch > per_pass) batch -= batch % per_pass;
     if (batch < 1) batch = 1;
     if (batch > R) batch = R;
     A.batch = batch;
@@ -502,7 +526,6 @@ int slk_apply_coded(const sl_plan *p, int mode, float *theta, float *mom, float 
     A.magic_u = (unsigned)(0x100000000ull / (unsigned)(G.ua + 1) + 1);
     const int L = G.k / A.E;
     A.magic_l = L > 1 ? (unsigned)(0x100000000ull / (unsigned)L + 1) : 0u;
-    A.uwp_log2 = pow2_log2_at_least(G.ua);
     A.n_chunks = p->n_chunks;
     for (int r = 0; r < SL_MAX_WORKERS; ++r) {
         A.payload[r] = r < R ? static_cast<const unsigned char *>(payloads[r]) : nullptr;

@@ -114,31 +114,61 @@ typedef const unsigned __attribute__((address_space(1))) *sl_gwords;
 typedef unsigned sl_u4u __attribute__((ext_vector_type(4), aligned(4)));
 typedef const sl_u4u __attribute__((address_space(1))) *sl_gu4;
 
-SL_DEV SlVecPlace sl_coded_dir_entry(const SlCodedGeom &G, sl_gbytes entry, int pos)
+// The words of a directory entry as loaded (the loads are issued here; nothing waits for them
+// until sl_coded_dir_parse reads the words).
+struct SlDirWords {
+    unsigned run_word;
+    sl_u4u lo, hi;          // the 16 quotient sums: 16 bytes, or 32 when they are two bytes each
+};
+
+SL_DEV SlDirWords sl_coded_dir_load(const SlCodedGeom &G, sl_gbytes entry)
+{
+    SlDirWords W;
+    const sl_gwords e = reinterpret_cast<sl_gwords>(entry);
+    W.run_word = e[0];
+    W.lo = *reinterpret_cast<sl_gu4>(e + 1);
+    W.hi = sl_u4u{0u, 0u, 0u, 0u};
+    if (G.qf == 2) W.hi = *reinterpret_cast<sl_gu4>(e + 5);
+    return W;
+}
+
+// Field j (0..15) of a directory entry's quotient sums, j a compile-time constant.
+template <int J>
+SL_DEV unsigned sl_dir_field(int qf, sl_u4u lo, sl_u4u hi)
+{
+    if (qf == 2) {
+        const sl_u4u v = J < 8 ? lo : hi;
+        const unsigned w = ((J >> 1) & 3) == 0 ? v.x : ((J >> 1) & 3) == 1 ? v.y : ((J >> 1) & 3) == 2 ? v.z : v.w;
+        return (w >> (16 * (J & 1))) & 0xFFFFu;
+    }
+    const unsigned w = (J >> 2) == 0 ? lo.x : (J >> 2) == 1 ? lo.y : (J >> 2) == 2 ? lo.z : lo.w;
+    return (w >> (8 * (J & 3))) & 0xFFu;
+}
+
+template <int J>
+SL_DEV void sl_dir_sum(int qf, int qmax, sl_u4u lo, sl_u4u hi, int pos, int &before, int &own)
+{
+    if constexpr (J < SL_RICE_GROUP) {
+        const int qc = min((int)sl_dir_field<J>(qf, lo, hi), qmax);
+        before += J < pos ? qc : 0;
+        own = J == pos ? qc : own;
+        sl_dir_sum<J + 1>(qf, qmax, lo, hi, pos, before, own);
+    }
+}
+
+SL_DEV SlVecPlace sl_coded_dir_parse(const SlCodedGeom &G, unsigned run_word, sl_u4u lo, sl_u4u hi, int pos)
 {
     SlVecPlace P;
-    const sl_gwords e = reinterpret_cast<sl_gwords>(entry);
-    P.run_word = e[0];
-    unsigned f[8];
-    const sl_u4u a = *reinterpret_cast<sl_gu4>(e + 1);
-    f[0] = a.x, f[1] = a.y, f[2] = a.z, f[3] = a.w;
-    if (G.qf == 2) {
-        const sl_u4u c = *reinterpret_cast<sl_gu4>(e + 5);
-        f[4] = c.x, f[5] = c.y, f[6] = c.z, f[7] = c.w;
-    } else {
-        f[4] = f[5] = f[6] = f[7] = 0u;
-    }
+    P.run_word = run_word;
     int before = 0, own = 0;
-#pragma unroll
-    for (int j = 0; j < SL_RICE_GROUP; ++j) {
-        unsigned q;
-        if (G.qf == 2) q = (f[j >> 1] >> (16 * (j & 1))) & 0xFFFFu;
-        else q = (f[j >> 2] >> (8 * (j & 3))) & 0xFFu;
-        const int qc = min((int)q, G.qmax);
-        before += j < pos ? qc : 0;
-        own = j == pos ? qc : own;
-    }
+    sl_dir_sum<0>(G.qf, G.qmax, lo, hi, pos, before, own);
     P.start_bit = pos * G.k + before;
     P.nbits = G.k + own;
     return P;
+}
+
+SL_DEV SlVecPlace sl_coded_dir_entry(const SlCodedGeom &G, sl_gbytes entry, int pos)
+{
+    const SlDirWords W = sl_coded_dir_load(G, entry);
+    return sl_coded_dir_parse(G, W.run_word, W.lo, W.hi, pos);
 }

@@ -34,6 +34,17 @@ struct SlTensorDev {
 
 enum { SL_RICE_GROUP = 16 };  // chunks per directory entry of the coded format
 
+// Where a chunk's parts lie in a coded buffer (byte offsets that follow from the tensor list):
+// what the coded aggregate needs about a chunk besides its SlChunkDesc, in one 32-byte load.
+struct SlCodedDesc {
+    long long lut_off;      // table header of the chunk's tensor block
+    long long dir_off;      // directory entry of the chunk's group
+    long long fix_off;      // the chunk's fixed record
+    int pos;                // position of the chunk in its group, 0..15
+    int reserved;
+};
+static_assert(sizeof(SlCodedDesc) == 32, "descriptor is one 32-byte load");
+
 // Sizes of the coded format that follow from k and the value width (see sl_coded.h).
 struct SlCodedGeom {
     int k, bits;
@@ -94,6 +105,7 @@ struct sl_plan {
     size_t ws_vals, ws_leafA, ws_leafC, ws_cnt, ws_tstat;
     // device tables
     SlChunkDesc *d_desc;
+    SlCodedDesc *d_cdesc;
     SlTensorDev *d_tensors;
     SlGroup *d_groups;
     int64_t n_groups;

@@ -10,6 +10,10 @@ FETCH_SIZE / WRITE_SIZE are read in KiB per dispatch and scaled by what the same
 counter reads for the plain device-to-device copy of known size that bench.py
 performs (hipMemcpy D2D of one arena, kernel __amd_rocclr_copyBuffer).
 
+The bench line each run printed is expected next to its output (<dir>/bench_trace.json, the
+JSON line of the trace run): the command's own arguments are taken from its "argv" field, so a
+summary cannot name another command than the one that was profiled.
+
   python -m paper_2508_15706_amd.rocprof_summary <dir> <arena_bytes> <out.md> [<traffic.json>]
 """
 from __future__ import annotations
@@ -146,7 +150,15 @@ def main(argv):
         return 2
     d, arena_bytes, out_md = argv[1], float(argv[2]), argv[3]
     summary = summarize(d, arena_bytes)
-    bench_args = os.environ.get("SL_BENCH_ARGS", "--config 4 --no-cpu-baseline")
+    bench_args = None
+    line_path = os.path.join(d, "bench_trace.json")
+    if os.path.exists(line_path):
+        for line in open(line_path):
+            if line.startswith("{"):
+                bench_args = json.loads(line).get("argv")
+    if bench_args is None:
+        print(f"{line_path} holds no bench line with an argv field: the profiled command is unknown", file=sys.stderr)
+        return 2
     title = os.environ.get("SL_PROFILE_TITLE", "rocprofv3 summary")
     with open(out_md, "w") as f:
         f.write(render(summary, bench_args, title))
@@ -154,8 +166,16 @@ def main(argv):
         traffic = {k: {"fetch_bytes": v["fetch_bytes"], "write_bytes": v["write_bytes"], "avg_us": v["avg_us"],
                        "timed_us": v.get("timed_us")}
                    for k, v in summary["kernels"].items()}
+        import hashlib
+        h = hashlib.sha256()
+        csrc = os.path.join(os.path.dirname(os.path.abspath(__file__)), "csrc")
+        for name in sorted(os.listdir(csrc)):       # the same hash bench.py checks before it quotes the file
+            if name.endswith((".hip", ".h")):
+                h.update(name.encode())
+                h.update(open(os.path.join(csrc, name), "rb").read())
         with open(argv[4], "w") as f:
-            json.dump({"bench_args": bench_args, "fetch_scale": summary["fetch_scale"],
+            json.dump({"bench_args": bench_args, "sources_sha": h.hexdigest()[:16],
+                       "fetch_scale": summary["fetch_scale"],
                        "write_scale": summary["write_scale"], "kernels": traffic}, f, indent=1)
     return 0
 

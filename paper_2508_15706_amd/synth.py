@@ -151,6 +151,20 @@ def paper_shape_list(which: str) -> List[TensorSpec]:
     raise ValueError(which)
 
 
+PAPER_LISTS = {"paper178M": ("178M", 6, 8, 1.0), "paper512M": ("512M", 7, 8, 1.0), "paper2B": ("2B", 8, 16, 0.8)}
+
+
+def paper_workload(name: str, k: Optional[int] = None, flat: bool = False) -> Workload:
+    """One of the paper's own three architectures as a workload: Gaussian pseudo-gradients, the
+    worker counts and outer learning rates of the paper's runs on that model (R = 8 and 1.0 for
+    178M and 512M, R = 16 and 0.8 for 2B), k = 64 unless given."""
+    which, cid, R, lr = PAPER_LISTS[name]
+    sp = paper_shape_list(which)
+    if flat:
+        sp = _finish(sp, True)
+    return Workload(f"paper-{which}", cid, sp, k or 64, R, 0.95, lr, 1, "gauss", 1e-3)
+
+
 def seed_for(config_id: int, rnd: int, worker: int) -> int:
     return 1000 * config_id + 100 * rnd + worker
 
