@@ -1,7 +1,9 @@
-"""GPU parity at the benchmark configurations' full sizes (configurations 2-5), in the
-launch configuration bench.py times.
+"""GPU parity at the benchmark configurations' full sizes (configurations 2-5) and on the paper's
+own 512M architecture, in the launch configuration bench.py times.
 
-The GPU always processes the whole tensor list.  The oracle checks
+The GPU always processes the whole tensor list.  Configuration 4, the benchmark workload, is
+compared on the whole list for every worker and round (its own test below).  In the other tests
+the oracle checks
   - worker 0, round 1: the WHOLE list (every payload byte, every element of e);
   - every other worker and every later round: a sample of whole tensors (a tensor's
     LUT depends on all its chunks, so the unit that can be checked on its own is a
@@ -70,9 +72,9 @@ class SubList:
             assert rel.max() <= 1e-6, f"{what}: {bad} values differ, max rel err {rel.max():.3e}"
 
 
-def run_config(sl, oracle, config_id, k, rounds, sample_names, full_first=True, bits=2):
+def run_config(sl, oracle, config_id, k, rounds, sample_names, full_first=True, bits=2, workload=None):
     from paper_2508_15706_amd import synth
-    w = synth.workload(config_id, k=k)
+    w = workload if workload is not None else synth.workload(config_id, k=k)
     dev = torch.device("cuda:0")
     descs = [s.desc() for s in w.specs]
     plan = sl.sl_plan_create(descs, w.k) if bits == 2 else sl.sl_plan_create_bits(descs, w.k, bits)
@@ -146,13 +148,6 @@ def test_config2_190M_full_list_all_workers(sl, oracle):
     run_config(sl, oracle, 2, None, 1, None, full_first=False)
 
 
-@pytest.mark.timeout(600)
-@pytest.mark.parametrize("k", [32, 128])
-def test_config3_510M_k_sweep_full_list(sl, oracle, k):
-    """Configuration 3 (heavy-tailed mixture), k = 32 and 128: whole list for worker 0,
-    sample for the others."""
-    run_config(sl, oracle, 3, k, 1, {"l0.q", "l3.gate", "l7.norm1", "l23.down", "final_norm"})
-
 
 @pytest.mark.timeout(600)
 @pytest.mark.parametrize("k", [256, 512, 1024])
@@ -165,9 +160,14 @@ def test_config3_510M_high_densities(sl, oracle, k):
 
 
 @pytest.mark.timeout(900)
-def test_config3_510M_five_rounds(sl, oracle):
-    """Configuration 3, k = 64: five consecutive rounds carrying the error buffers."""
-    run_config(sl, oracle, 3, 64, 5, {"l0.q", "l3.gate", "l7.norm1", "l23.down", "final_norm"})
+@pytest.mark.parametrize("k", [32, 64, 128])
+def test_config3_510M_k_sweep_five_rounds(sl, oracle, k):
+    """Configuration 3 (heavy-tailed mixture) as configured: k swept over 32, 64 and 128, five consecutive
+    rounds carrying the error buffers at each.  Compared: worker 0's round-1 payload and error buffer on
+    the WHOLE list; in every round and for all 8 workers the payload bytes and (workers 1-7: every round,
+    worker 0: after its deferred chain) the error buffers of five whole tensors; theta of those tensors
+    after every round's aggregate."""
+    run_config(sl, oracle, 3, k, 5, {"l0.q", "l3.gate", "l7.norm1", "l23.down", "final_norm"})
 
 
 @pytest.mark.timeout(900)
@@ -175,6 +175,99 @@ def test_config4_1p8B_three_rounds(sl, oracle):
     """Configuration 4 (the benchmark workload): whole list for worker 0 in round 1,
     then three rounds on a sample that includes the ragged-edge head."""
     run_config(sl, oracle, 4, None, 3, {"l0.q", "l0.norm1", "l11.down", "l23.up", "final_norm", "head"})
+
+
+@pytest.mark.timeout(1150)
+def test_config4_1p8B_whole_list_all_workers_three_rounds(sl, oracle):
+    """Configuration 4 on the WHOLE list: all 8 workers x 3 rounds, every worker on the deferred-residual
+    chain bench.py times, the compressor emitting the coded wire format as well.  Compared bit for bit
+    against the oracle, over all 1.8e9 elements and all 443,569 chunks: every worker's payload bytes in
+    every round; every worker's error buffer after every round (the pending update applied to a copy);
+    theta after every round's aggregate - rounds 1 and 3 through the plain aggregate, round 2 through
+    the coded one; worker 0's coded bytes in every round (against the oracle's encoder)."""
+    from paper_2508_15706_amd import synth
+    w = synth.workload(4)
+    dev = torch.device("cuda:0")
+    descs = [s.desc() for s in w.specs]
+    plan = sl.sl_plan_create(descs, w.k)
+    ws = sl.alloc_workspace(plan)
+    cap = sl.sl_rice_max_bytes(plan)
+    nb = plan.payload_bytes
+    delta = torch.empty(w.arena, dtype=torch.float32, device=dev)
+    theta = torch.empty(w.arena, dtype=torch.float32, device=dev)
+    tmp = torch.empty(w.arena, dtype=torch.float32, device=dev)
+    synth.fill_theta(w, theta)
+    theta_ref = theta.cpu().numpy()
+    e_dev = [torch.zeros(w.arena, dtype=torch.float32, device=dev) for _ in range(w.R)]
+    e_ref = [np.zeros(w.arena, dtype=np.float32) for _ in range(w.R)]
+    recs = [[sl.alloc_payload(plan), sl.alloc_payload(plan)] for _ in range(w.R)]
+    wires = [torch.zeros(cap, dtype=torch.uint8, device=dev) for _ in range(w.R)]
+    for rnd in range(1, w.rounds + 1):
+        refs, sizes = [], []
+        for r in range(w.R):
+            synth.fill_delta(w, delta, rnd, r)
+            d_host = delta.cpu().numpy()
+            out = recs[r][rnd % 2]
+            sl.sl_compress_coded(plan, e_dev[r], delta, w.beta, out, wires[r], ws, flags=sl.SL_COMPRESS_DEFER_RESIDUAL,
+                                 pending=recs[r][(rnd + 1) % 2] if rnd > 1 else None)
+            tmp.copy_(e_dev[r])
+            sl.sl_residual_apply(plan, tmp, out)
+            ref = oracle.compress(descs, w.k, e_ref[r], d_host, w.beta)
+            torch.cuda.synchronize()
+            got = out[:nb].cpu().numpy()
+            assert np.array_equal(got, ref), (f"round {rnd} worker {r}: payload differs at "
+                                              f"{np.nonzero(got != ref)[0][:6]}")
+            assert torch.equal(tmp.view(torch.int32), torch.from_numpy(e_ref[r]).to(dev).view(torch.int32)), \
+                f"round {rnd} worker {r}: error buffer differs"
+            sizes.append(sl.coded_size(wires[r]))
+            if r == 0:
+                enc = oracle.rice_encode(descs, w.k, ref)
+                assert sizes[0] == enc.size and np.array_equal(wires[0][:enc.size].cpu().numpy(), enc), \
+                    f"round {rnd}: coded bytes of worker 0 differ"
+            refs.append(ref)
+            print(f"round {rnd} worker {r}: payload, error buffer ok", flush=True)
+        if rnd == 2:
+            sl.sl_decompress_avg_apply_coded(plan, theta, wires, sizes, w.lr)
+        else:
+            sl.sl_decompress_avg_apply(plan, theta, [recs[r][rnd % 2] for r in range(w.R)], w.lr)
+        oracle.decompress_avg_apply(descs, w.k, theta_ref, refs, w.lr)
+        torch.cuda.synchronize()
+        assert torch.equal(theta.view(torch.int32), torch.from_numpy(theta_ref).to(dev).view(torch.int32)), \
+            f"round {rnd}: theta differs"
+        print(f"round {rnd}: theta ok", flush=True)
+    plan.close()
+
+
+@pytest.mark.timeout(900)
+@pytest.mark.parametrize("k", [32, 128, 2048])
+def test_paper_512M_list(sl, oracle, k):
+    """The paper's own 512M architecture (vocabulary 32000, every dimension a multiple of 64: no ragged
+    tiles), at the two densities of its Table 1 (k = 32, 128) and at 50 % (k = 2048, the top of its density
+    sweep, which the configurations' ragged head tiles rule out; there the list is the model's matrices -
+    its norm vectors have 1536 elements, fewer than k).  Two rounds, all 8 workers, on a sample
+    of whole tensors (payload bytes, error buffers, theta); at the Table 1 densities the coded size of a
+    worker's whole payload, as the compressor emits it, must not exceed the size the paper prints."""
+    from paper_2508_15706_amd import synth
+    w = synth.paper_workload("paper512M", k=k)
+    if k > 1536:
+        w.specs = [s for s in w.specs if s.rows > 1]
+    run_config(sl, oracle, None, k, 2, {"embed", "l0.q", "l5.gate", "l11.down", "l3.norm1", "final_norm"},
+               full_first=False, workload=w)
+    table1_mb = {32: 5.45, 128: 17.21}
+    if k in table1_mb:
+        dev = torch.device("cuda:0")
+        plan = sl.sl_plan_create([s.desc() for s in w.specs], k)
+        e = torch.zeros(w.arena, dtype=torch.float32, device=dev)
+        d = torch.empty(w.arena, dtype=torch.float32, device=dev)
+        synth.fill_delta(w, d, 1, 0)
+        wire = sl.alloc_coded(plan)
+        sl.sl_compress_coded(plan, e, d, w.beta, sl.alloc_payload(plan), wire, sl.alloc_workspace(plan))
+        torch.cuda.synchronize()
+        mb = sl.coded_size(wire) / 1e6
+        assert plan.num_elements == 512398848
+        assert mb <= table1_mb[k], f"k={k}: coded payload {mb:.3f} MB, the paper's Table 1 prints {table1_mb[k]}"
+        assert mb > 0.9 * table1_mb[k]
+        plan.close()
 
 
 @pytest.mark.timeout(900)

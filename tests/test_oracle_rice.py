@@ -280,3 +280,27 @@ def test_rice_other_widths_round_trip_and_model(oracle, bits, k):
     assert enc.size <= oracle.rice_max_bytes_b(descs, k, bits)
     assert np.array_equal(oracle.rice_decode_b(descs, k, bits, enc), pay)
     assert np.array_equal(model_encode(oracle, descs, k, bits, pay), enc)
+
+
+def test_coded_size_on_the_papers_512M_model_is_within_table_1(oracle):
+    """Table 1 prints the size of one worker's pseudo-gradient message on the 512M model (512,398,848
+    parameters, 2-bit values, Rice-coded indices): 5.45 MB at density 0.78 % (k = 32) and 17.21 MB at
+    3.12 % (k = 128).  The oracle's whole pipeline - compress a Gaussian pseudo-gradient on the paper's own
+    tensor list, then code the payload - must not need more (and, the coder being of the same family,
+    not much less)."""
+    import torch
+    from paper_2508_15706_amd import synth
+    p = paper_numbers()
+    w = synth.paper_workload("paper512M", k=32)
+    descs = [s.desc() for s in w.specs]
+    assert sum(d[0] * d[1] for d in descs) == int(p["params_512M"])
+    delta = torch.empty(w.arena, dtype=torch.float32)
+    synth.fill_delta(w, delta, 1, 0)
+    delta = delta.numpy()
+    for k, key in ((32, "table1_size_MB_density_0p78"), (128, "table1_size_MB_density_3p12")):
+        e = np.zeros(w.arena, dtype=np.float32)
+        pay = oracle.compress(descs, k, e, delta, 0.95)
+        enc = oracle.rice_encode(descs, k, pay)
+        mb = enc.size / 1e6
+        assert 0.95 * p[key] < mb <= p[key], (k, mb, p[key])
+        assert np.array_equal(oracle.rice_decode(descs, k, enc), pay)
