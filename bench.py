@@ -100,6 +100,9 @@ def main():
                     help="time the CPU oracle on the tensors of the first layers only (default: the whole list "
                          "while it has at most 2.5e9 elements)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-kernel-times", action="store_true",
+                    help="skip the extra steps that are run with per-kernel events after the timed ones; the "
+                         "per-kernel fields are then 0")
     ap.add_argument("--mode", choices=["deferred", "eager"], default="deferred",
                     help="deferred: the error update of a round is folded into the next round's "
                          "read of e (SL_COMPRESS_DEFER_RESIDUAL + pending); eager: scattered update "
@@ -182,11 +185,18 @@ def main():
             sl.sl_residual_apply(plan, e0, state["pending"])
             state["pending"] = None
 
+    # The library's per-kernel events cost a few microseconds per kernel.  On the benchmark lists that is
+    # nothing and they are recorded over the timed steps themselves; on a list of a few hundred chunks it
+    # would be a large part of the step, so there the K timed steps run bare and the events are recorded
+    # over extra steps afterwards.
+    events_inline = n_chunks >= 16384 and not args.no_kernel_times
+
     def timed(mode, wire, steps):
         for _ in range(args.warmup):
             step(mode, wire)
         torch.cuda.synchronize()
-        sl.sl_profile_begin(plan, steps)
+        if events_inline:
+            sl.sl_profile_begin(plan, steps)
         t0 = time.perf_counter()
         for _ in range(steps):
             step(mode, wire)
@@ -195,7 +205,19 @@ def main():
         flush()
         torch.cuda.synchronize()
         dt = time.perf_counter() - t0
-        return 1e3 * dt / steps, sl.sl_profile_end(plan)
+        prof = {p: (0.0, 0) for p in sl.PROF_PHASES}
+        if events_inline:
+            prof = sl.sl_profile_end(plan)
+        elif not args.no_kernel_times:
+            n_ev = max(4, steps // 2)
+            step(mode, wire)
+            sl.sl_profile_begin(plan, n_ev)
+            for _ in range(n_ev):
+                step(mode, wire)
+            flush()
+            torch.cuda.synchronize()
+            prof = sl.sl_profile_end(plan)
+        return 1e3 * dt / steps, prof
 
     few = max(2, args.steps // 4)
     other_mode = "eager" if args.mode == "deferred" else "deferred"
@@ -313,7 +335,7 @@ def main():
                                f"{'fp32' if args.bits == 32 else str(args.bits) + '-bit'} values, {args.mode} residual, "
                                f"{args.wire} wire format",
                    "n_elements": N, "n_chunks": n_chunks, "k": w.k, "R": w.R, "value_bits": args.bits,
-                   "wire": args.wire},
+                   "wire": args.wire, "arena_bytes": 4 * arena},
         "argv": " ".join(sys.argv[1:]),
         "roofline": {"bound": "hbm", "kernel": "k_select (EF accumulate + chunk Top-k)",
                      "achieved": sel_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
@@ -324,6 +346,7 @@ def main():
                      "frac_of_peak": frac(path_bytes(args.wire), ms_step),
                      "device_copy_GBps": copy_gbs},
         "mode": args.mode, "hip_graph": graph_info,
+        "kernel_events": "over the timed steps" if events_inline else "over extra steps after the timed ones",
         "other_mode": {"mode": other_mode, "ms_per_step": ms_other_mode, "value": N / (ms_other_mode * 1e-3) / 1e9,
                        "kernels_ms": {p: prof_other_mode[p][0] for p in prof_other_mode}},
         "other_wire": {"wire": other_wire, "ms_per_step": ms_other_wire, "value": N / (ms_other_wire * 1e-3) / 1e9,

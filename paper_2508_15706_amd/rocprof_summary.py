@@ -14,7 +14,8 @@ The bench line each run printed is expected next to its output (<dir>/bench_trac
 JSON line of the trace run): the command's own arguments are taken from its "argv" field, so a
 summary cannot name another command than the one that was profiled.
 
-  python -m paper_2508_15706_amd.rocprof_summary <dir> <arena_bytes> <out.md> [<traffic.json>]
+  python -m paper_2508_15706_amd.rocprof_summary <dir> <arena_bytes | auto> <out.md> [<traffic.json>]
+  (auto: the arena size the bench line reports)
 """
 from __future__ import annotations
 
@@ -125,7 +126,7 @@ def render(summary, bench_args, title):
              f"    rocprofv3 --kernel-trace --stats --output-format csv -d $OUT/trace -o t -- python3 $R/bench.py {bench_args}",
              f"    rocprofv3 --pmc FETCH_SIZE --output-format csv -d $OUT/fetch -o f -- python3 $R/bench.py {bench_args}",
              f"    rocprofv3 --pmc WRITE_SIZE --output-format csv -d $OUT/write -o w -- python3 $R/bench.py {bench_args}",
-             f"    python3 -m paper_2508_15706_amd.rocprof_summary $OUT <arena bytes> <this file>", "",
+             f"    python3 -m paper_2508_15706_amd.rocprof_summary $OUT auto <this file>     (with the trace run's bench line in $OUT/bench_trace.json)", "",
              "(The two counter runs may take fewer steps, e.g. --steps 2 --warmup 1: the counters are read per dispatch.)", "",
              "Counter scaling: the whole-arena device copy bench.py performs (`__amd_rocclr_copyBuffer`, "
              f"{s['copy_known_KiB']:.0f} KiB read and written) reads FETCH_SIZE = {s['copy_fetch_KiB']:.1f} KiB "
@@ -148,17 +149,21 @@ def main(argv):
     if len(argv) < 4:
         print(__doc__)
         return 2
-    d, arena_bytes, out_md = argv[1], float(argv[2]), argv[3]
-    summary = summarize(d, arena_bytes)
-    bench_args = None
+    d, out_md = argv[1], argv[3]
+    bench_args, arena_bytes = None, None
     line_path = os.path.join(d, "bench_trace.json")
     if os.path.exists(line_path):
         for line in open(line_path):
             if line.startswith("{"):
-                bench_args = json.loads(line).get("argv")
+                rec = json.loads(line)
+                bench_args = rec.get("argv")
+                arena_bytes = rec.get("config", {}).get("arena_bytes")
     if bench_args is None:
         print(f"{line_path} holds no bench line with an argv field: the profiled command is unknown", file=sys.stderr)
         return 2
+    if argv[2] != "auto":
+        arena_bytes = float(argv[2])
+    summary = summarize(d, float(arena_bytes))
     title = os.environ.get("SL_PROFILE_TITLE", "rocprofv3 summary")
     with open(out_md, "w") as f:
         f.write(render(summary, bench_args, title))
