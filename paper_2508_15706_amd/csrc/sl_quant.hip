@@ -124,6 +124,7 @@ struct CodeArgs {
     unsigned char *coded;
     const SlTensorDev *tensors;
     int cfix, rem_bytes;
+    int park;               // k_codes_b: the codes of the first pass are kept in LDS for the later ones
 };
 
 // Where a chunk's value fields go in the coded buffer (null when none is written).
@@ -383,36 +384,50 @@ __global__ void __launch_bounds__(256) k_codes_wave(CodeArgs A)
 // reached, each edge decided on squares against (c_j * c_j) * var.  The bins
 // are handled four at a time (one pass over the chunk's values per group of
 // four), so that the per-bin tree stacks stay in registers.
+// Is the value at distance dlt from the mean at or beyond inner edge j (1 <= j < 2^BITS)?  The edge
+// sits at c_j sigma, c_j = 12 j / 2^BITS - 6 (exact in fp64); decided on squares against (c_j c_j) var.
+template <int BITS>
+SL_DEV bool edge_reached(int j, double dlt, double dd, double var)
+{
+    const double cj = (double)j * (12.0 / (double)(1 << BITS)) - 6.0;    // exact: small integer times a power-of-two multiple of 3
+    const double Tj = (cj * cj) * var;
+    const bool nonneg = dlt >= 0.0;
+    return cj < 0.0 ? (nonneg || dd <= Tj) : cj == 0.0 ? nonneg : (nonneg && dd >= Tj);
+}
+
+// The code of a value = the number of inner edges it has reached.  The edges ascend, so "reached"
+// holds for a prefix of them and the count is found by bisection (BITS decisions instead of 2^BITS - 1).
 template <int BITS>
 SL_DEV int code_of(double dlt, double var)
 {
-    constexpr int NB = 1 << BITS;
     const double dd = dlt * dlt;
     int code = 0;
 #pragma unroll
-    for (int j = 1; j < NB; ++j) {
-        const double cj = 12.0 * (double)j / (double)NB - 6.0;   // exact in fp64
-        const double Tj = (cj * cj) * var;
-        bool reached;
-        if (cj < 0.0) reached = dlt >= 0.0 || dd <= Tj;
-        else if (cj == 0.0) reached = dlt >= 0.0;
-        else reached = dlt >= 0.0 && dd >= Tj;
-        code += reached ? 1 : 0;
+    for (int s = BITS - 1; s >= 0; --s) {
+        const int mid = code + (1 << s);
+        code = edge_reached<BITS>(mid, dlt, dd, var) ? mid : code;
     }
     return code;
 }
 
-template <int BITS>
-__global__ void __launch_bounds__(64 * CODE_WAVES, 2) k_codes_b(CodeArgs A)
+// One lane per chunk as in k_codes.  The codes are found in the first pass and parked in LDS (a
+// word per eight entries); every pass sums NBP bins.
+template <int BITS, int LV, int NBP, int WAVES_PER_EU>
+__global__ void __launch_bounds__(64 * CODE_WAVES, WAVES_PER_EU) k_codes_b(CodeArgs A)
 {
     constexpr int NB = 1 << BITS;
-    constexpr int PASSES = (NB + 3) / 4;
-    __shared__ float tile_all[CODE_WAVES][64 * CODE_PITCH];
+    constexpr int PASSES = (NB + NBP - 1) / NBP;
+    constexpr int TC = 32, PITCH = TC + 1;
+    extern __shared__ __align__(16) unsigned char codes_lds[];
     const int lane = threadIdx.x & 63, k = A.k;
     const int wave = sl_uniform((int)(threadIdx.x >> 6));
     const long long c0 = ((long long)blockIdx.x * CODE_WAVES + wave) * 64;
     if (c0 >= A.n_chunks) return;
-    float *tile = tile_all[wave];
+    // per wave: the value tile, then the parked codes (k / 8 words per lane, word w of lane l at [w * 64 + l])
+    const bool park = PASSES > 1 && A.park;
+    const size_t per_wave = sizeof(float) * 64 * PITCH + (park ? sizeof(unsigned) * 64 * (size_t)(k >> 3) : 0);
+    float *tile = reinterpret_cast<float *>(codes_lds + (size_t)wave * per_wave);
+    unsigned *parked = reinterpret_cast<unsigned *>(tile + 64 * PITCH);
     const long long c = c0 + lane;
     const bool live = c < A.n_chunks;
 
@@ -427,38 +442,44 @@ __global__ void __launch_bounds__(64 * CODE_WAVES, 2) k_codes_b(CodeArgs A)
     }
     int P = 1, top = 0;
     while (P < k) P <<= 1, ++top;
-    const int lr = lane >> 4, lc = (lane & 15) * 4;
+    constexpr int LPR = TC / 4;              // lanes that load one row of the tile
+    const int lr = lane / LPR, lc = (lane % LPR) * 4;
 
     for (int pass = 0; pass < PASSES; ++pass) {
-        const int q0 = 4 * pass;
-        BinStacks st;
+        const int q0 = NBP * pass;
+        // (four bins to a set of stacks, as in k_codes; NBP = 8: two sets)
+        BinStacksT<LV> st, st2;
 #pragma unroll
-        for (int l = 0; l < 13; ++l) st.a[l] = st.b[l] = st.c[l] = st.d[l] = 0.0;
-        unsigned n_b[4] = {0u, 0u, 0u, 0u};
-        unsigned long long bitbuf = 0;          // codes of 8 entries = BITS bytes
-        for (int s0 = 0; s0 < k; s0 += 64) {
-            const int ncol = min(64, k - s0);
+        for (int l = 0; l < LV; ++l) {
+            st.a[l] = st.b[l] = st.c[l] = st.d[l] = 0.0;
+            st2.a[l] = st2.b[l] = st2.c[l] = st2.d[l] = 0.0;
+        }
+        unsigned n_b[NBP];
+#pragma unroll
+        for (int q = 0; q < NBP; ++q) n_b[q] = 0u;
+        unsigned bitbuf = 0;                    // codes of 8 entries = BITS bytes
+        for (int s0 = 0; s0 < k; s0 += TC) {
+            const int ncol = min(TC, k - s0);   // a multiple of 8
             sl_wave_sync();
 #pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                const int row = 4 * i + lr;
+            for (int i = 0; i < LPR; ++i) {
+                const int row = (64 / LPR) * i + lr;
                 if (c0 + row < A.n_chunks && lc < ncol) {
                     const float4 v = *reinterpret_cast<const float4 *>(A.vals + (c0 + row) * k + s0 + lc);
-                    float *t = tile + row * CODE_PITCH + lc;
+                    float *t = tile + row * PITCH + lc;
                     t[0] = v.x, t[1] = v.y, t[2] = v.z, t[3] = v.w;
                 }
             }
             sl_wave_sync();
             for (int col = 0; col < ncol; ++col) {
                 const int m = s0 + col;
-                const double x = (double)tile[lane * CODE_PITCH + col];
-                const int code = code_of<BITS>(x - mu, var);
-                const int rel = code - q0;
-                n_b[0] += rel == 0, n_b[1] += rel == 1, n_b[2] += rel == 2, n_b[3] += rel == 3;
-                stack_push<0>(st, m, rel == 0 ? x : 0.0, rel == 1 ? x : 0.0, rel == 2 ? x : 0.0,
-                              rel == 3 ? x : 0.0);
+                const double x = (double)tile[lane * PITCH + col];
+                int code;
+                if (pass == 0 || !park) {
+                    code = code_of<BITS>(x - mu, var);
+                }
                 if (pass == 0) {
-                    bitbuf |= (unsigned long long)code << (BITS * (m & 7));
+                    bitbuf |= (unsigned)code << (BITS * (m & 7));
                     if ((m & 7) == 7) {         // k is a multiple of 8
                         if (live) {
 #pragma unroll
@@ -470,19 +491,35 @@ __global__ void __launch_bounds__(64 * CODE_WAVES, 2) k_codes_b(CodeArgs A)
                             for (int q = 0; q < BITS; ++q)
                                 codes_out2[(m >> 3) * BITS + q] = (unsigned char)(bitbuf >> (8 * q));
                         }
+                        if (park) parked[(m >> 3) * 64 + lane] = bitbuf;
                         bitbuf = 0;
                     }
+                } else if (park) {
+                    if ((m & 7) == 0) bitbuf = parked[(m >> 3) * 64 + lane];
+                    code = (int)((bitbuf >> (BITS * (m & 7))) & (unsigned)(NB - 1));
                 }
+                const int rel = code - q0;
+#pragma unroll
+                for (int q = 0; q < NBP; ++q) n_b[q] += rel == q;
+                stack_push<0>(st, m, rel == 0 ? x : 0.0, rel == 1 ? x : 0.0, rel == 2 ? x : 0.0, rel == 3 ? x : 0.0);
+                if constexpr (NBP > 4)
+                    stack_push<0>(st2, m, rel == 4 ? x : 0.0, rel == 5 ? x : 0.0, rel == 6 ? x : 0.0, rel == 7 ? x : 0.0);
             }
         }
-        for (int m = k; m < P; ++m) stack_push<0>(st, m, 0.0, 0.0, 0.0, 0.0);
+        for (int m = k; m < P; ++m) {
+            stack_push<0>(st, m, 0.0, 0.0, 0.0, 0.0);
+            if constexpr (NBP > 4) stack_push<0>(st2, m, 0.0, 0.0, 0.0, 0.0);
+        }
         if (live) {
-            double r[4] = {st.a[0], st.b[0], st.c[0], st.d[0]};
+            double r[8] = {st.a[0], st.b[0], st.c[0], st.d[0], st2.a[0], st2.b[0], st2.c[0], st2.d[0]};
 #pragma unroll
-            for (int l = 1; l < 13; ++l)
-                if (top == l) r[0] = st.a[l], r[1] = st.b[l], r[2] = st.c[l], r[3] = st.d[l];
+            for (int l = 1; l < LV; ++l)
+                if (top == l) {
+                    r[0] = st.a[l], r[1] = st.b[l], r[2] = st.c[l], r[3] = st.d[l];
+                    r[4] = st2.a[l], r[5] = st2.b[l], r[6] = st2.c[l], r[7] = st2.d[l];
+                }
 #pragma unroll
-            for (int q = 0; q < 4; ++q)
+            for (int q = 0; q < NBP; ++q)
                 if (q0 + q < NB) {
                     A.leafC[(long long)(q0 + q) * A.n_chunks + c] = r[q];
                     A.cnt[(long long)(q0 + q) * A.n_chunks + c] = n_b[q];
@@ -656,14 +693,39 @@ int slk_quantize(const sl_plan *p, float *e, int skip_residual, unsigned char *p
     C.tensors = p->d_tensors;
     C.cfix = p->cg.cfix;
     C.rem_bytes = p->cg.rem_bytes;
+    C.park = 0;
     const long long per_block = 64ll * CODE_WAVES;
     const unsigned nblk = (unsigned)((p->n_chunks + per_block - 1) / per_block);
     // (the list length is a field of the plan, sl_plan_set_codes_wave_below: both kernels write the same bytes)
     const bool by_wave = k >= SL_CODES_WAVE_FROM || p->n_chunks < p->codes_wave_below;
     switch (p->bits) {
-        case 1: hipLaunchKernelGGL(k_codes_b<1>, dim3(nblk), dim3(64 * CODE_WAVES), 0, st, C); break;
-        case 3: hipLaunchKernelGGL(k_codes_b<3>, dim3(nblk), dim3(64 * CODE_WAVES), 0, st, C); break;
-        case 4: hipLaunchKernelGGL(k_codes_b<4>, dim3(nblk), dim3(64 * CODE_WAVES), 0, st, C); break;
+        case 1:
+        case 3:
+        case 4: {
+            // stack depth by k as in k_codes; bins per pass: as many as the registers hold next to it
+            const int depth = k <= 64 ? 7 : k <= 256 ? 9 : 13;
+            const int nbp = p->bits == 1 ? 2 : 4;     // (eight at a time is no faster: the pushes per bin are the cost)
+            const int passes = ((1 << p->bits) + nbp - 1) / nbp;
+            C.park = passes > 1 && k <= 512;          // 32 KB of LDS per workgroup at most
+            const size_t lds = CODE_WAVES * (sizeof(float) * 64 * 33 + (C.park ? sizeof(unsigned) * 64 * (size_t)(k >> 3) : 0));
+            const dim3 g(nblk), b(64 * CODE_WAVES);
+#define SL_CODES_B(BITS, LV, NBP, WPE) hipLaunchKernelGGL((k_codes_b<BITS, LV, NBP, WPE>), g, b, lds, st, C)
+            if (p->bits == 1) {
+                if (depth == 7) SL_CODES_B(1, 7, 2, 4);
+                else if (depth == 9) SL_CODES_B(1, 9, 2, 4);
+                else SL_CODES_B(1, 13, 2, 2);
+            } else if (p->bits == 3) {
+                if (depth == 7) SL_CODES_B(3, 7, 4, 4);
+                else if (depth == 9) SL_CODES_B(3, 9, 4, 3);
+                else SL_CODES_B(3, 13, 4, 2);
+            } else {
+                if (depth == 7) SL_CODES_B(4, 7, 4, 4);
+                else if (depth == 9) SL_CODES_B(4, 9, 4, 3);
+                else SL_CODES_B(4, 13, 4, 2);
+            }
+#undef SL_CODES_B
+            break;
+        }
         default:
             if (k <= 64 && !by_wave) {
                 hipLaunchKernelGGL((k_codes<7, 32, 4>), dim3(nblk), dim3(64 * CODE_WAVES), 0, st, C);
