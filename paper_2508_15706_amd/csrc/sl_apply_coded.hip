@@ -89,6 +89,7 @@ __global__ void __launch_bounds__(256) k_apply_coded(CodedApplyArgs A)
     static_assert(SL_MAX_WORKERS <= 64, "one payload per lane");
     const unsigned long long my_ptr = reinterpret_cast<unsigned long long>(A.payload[lane]);
     const unsigned my_words = A.sec_words[lane];
+    asm volatile("" ::"v"(my_words));   // arrives with the pointer: no later wait may count it among the prefetches
     auto payload_of = [&](int r) -> sl_gbytes {
         const unsigned lo = (unsigned)sl_lane_read((int)(unsigned)my_ptr, r);
         const unsigned hi = (unsigned)sl_lane_read((int)(unsigned)(my_ptr >> 32), r);
@@ -149,33 +150,40 @@ __global__ void __launch_bounds__(256) k_apply_coded(CodedApplyArgs A)
 #pragma unroll
     for (int u = 0; u < PFU; ++u) pf_u[u] = src_vector(0, nb0, lane + 64 * u);
     if constexpr (!DECODE) {
-        if (full) {
-            const unsigned o0 = 4u * (lr * stride + lc), step = 16u * stride;
+        // Sixteen loads are issued for EVERY chunk, so that the wait in front of the words fetched above
+        // is "all but the last sixteen" whatever the chunk: a ragged chunk (a tensor's edge) reads its own
+        // descriptor sixteen times instead, and then loads its elements one by one, without branches (an
+        // element outside the chunk reads the chunk's first one and is replaced by zero).  Were the
+        // sixteen under a condition, the number of loads behind those words would be unknown and the
+        // wait would be for all of them on the full chunks too.
+        {
+            const float *none = reinterpret_cast<const float *>(A.desc + c);
+            const float *ts = full ? tc : none, *ms = (NESTEROV && full) ? mc : none;
+            const unsigned o0 = full ? 4u * (lr * stride + lc) : 0u, step = full ? 16u * stride : 0u;
 #pragma unroll
-            for (int i = 0; i < 16; ++i) th[i] = sl_load_stream_at(tc, i * step, o0);
+            for (int i = 0; i < 16; ++i) th[i] = sl_load_stream_at(ts, i * step, o0);
             if constexpr (NESTEROV) {
 #pragma unroll
-                for (int i = 0; i < 16; ++i) mo[i] = sl_load_stream_at(mc, i * step, o0);
+                for (int i = 0; i < 16; ++i) mo[i] = sl_load_stream_at(ms, i * step, o0);
             }
-        } else {
+        }
+        if (!full) {
             const int rows = d.rows, cols = d.cols, last_cols = d.last_cols;
 #pragma unroll
             for (int i = 0; i < 16; ++i) {
                 const int row = 4 * i + lr;
                 const int lim = row < rows - 1 ? cols : (row == rows - 1 ? last_cols : 0);
                 const unsigned o0 = row * stride + lc;
-                th[i] = sl_f4{0.f, 0.f, 0.f, 0.f};
-                if constexpr (NESTEROV) mo[i] = sl_f4{0.f, 0.f, 0.f, 0.f};
-                if (lc + 3 < lim) {
-                    th[i] = sl_load_stream_u(tc + o0);
-                    if constexpr (NESTEROV) mo[i] = sl_load_stream_u(mc + o0);
-                } else {
 #pragma unroll
-                    for (int cc = 0; cc < 4; ++cc)
-                        if (lc + cc < lim) {
-                            th[i][cc] = tc[o0 + cc];
-                            if constexpr (NESTEROV) mo[i][cc] = mc[o0 + cc];
-                        }
+                for (int cc = 0; cc < 4; ++cc) {
+                    const bool in = lc + cc < lim;
+                    const unsigned at = in ? o0 + cc : 0u;
+                    const float tv = __builtin_nontemporal_load(tc + at);
+                    th[i][cc] = in ? tv : 0.f;
+                    if constexpr (NESTEROV) {
+                        const float mv = __builtin_nontemporal_load(mc + at);
+                        mo[i][cc] = in ? mv : 0.f;
+                    }
                 }
             }
         }
@@ -186,7 +194,11 @@ __global__ void __launch_bounds__(256) k_apply_coded(CodedApplyArgs A)
 
     const int E = A.E, L = k / E;                 // step 4: entries per lane, lanes per worker
     const int uwp = 1 << A.uwp_log2;
-    for (int r0 = 0; r0 < A.R; r0 += A.batch) {
+    // One batch of workers: staged, decoded, added.  The first batch is processed by straight-line code
+    // of its own ahead of the loop over the others: inside a loop the wait in front of the staged words
+    // is for every outstanding load, the theta loads included, and the decode would start only once the
+    // whole chunk has arrived; ahead of the loop it is for the words alone.
+    auto do_batch = [&](const int r0, const bool first) __attribute__((always_inline)) {
         const int nb = min(A.batch, A.R - r0);
         sl_wave_sync();
         // ---- step 2: stage the batch.  The first words of both parts are in registers: fetched ahead of
@@ -195,7 +207,7 @@ __global__ void __launch_bounds__(256) k_apply_coded(CodedApplyArgs A)
         // "everything but the theta loads" - one array written on both paths would make it "everything").
         {
             const int nf = nb * fwp, nu = nb * uraw;
-            if (r0 == 0) {
+            if (first) {
 #pragma unroll
                 for (int u = 0; u < PFF; ++u)
                     if (lane + 64 * u < nf) *stage_fixed(lane + 64 * u) = pf_f[u];
@@ -260,11 +272,16 @@ __global__ void __launch_bounds__(256) k_apply_coded(CodedApplyArgs A)
                     rank = carry + incl - nz;
                     carry += __builtin_amdgcn_readlane(incl, 63);
                 }
+                // the word's zero bits from both ends at once: two independent chains per turn of the loop
+                // (the length of this loop - the word with the most zeros - is on the chunk's critical path)
+                int rank_hi = rank + nz - 1;
                 while (zeros) {
-                    const int p = __builtin_ctz(zeros);
+                    const int pl = __builtin_ctz(zeros), ph = 31 - __builtin_clz(zeros);
+                    if (rank < k) hs[rank] = (unsigned short)(32 * j + pl - rank);
+                    if (ph != pl && rank_hi < k) hs[rank_hi] = (unsigned short)(32 * j + ph - rank_hi);
                     zeros &= zeros - 1u;
-                    if (rank < k) hs[rank] = (unsigned short)(32 * j + p - rank);
-                    ++rank;
+                    zeros &= ~(1u << ph);
+                    ++rank, --rank_hi;
                 }
             }
             sl_wave_sync();
@@ -421,7 +438,9 @@ __global__ void __launch_bounds__(256) k_apply_coded(CodedApplyArgs A)
                 }
             }
         }
-    }
+    };
+    do_batch(0, true);
+    for (int r0 = A.batch; r0 < A.R; r0 += A.batch) do_batch(r0, false);
 
     if constexpr (!DECODE) {
         if (full) {
