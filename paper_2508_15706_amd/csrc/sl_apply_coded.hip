@@ -45,7 +45,8 @@ struct CodedApplyArgs {
     int batch;               // workers staged at a time
     int slot_bytes;          // LDS bytes of one staged worker
     int fwp;                 // words of (table header + fixed record)
-    unsigned magic_f, magic_u, magic_l;   // floor(2^32 / d) + 1 for d = fwp, G.ua + 1, lanes per worker in step 4
+    unsigned magic_l;        // floor(2^32 / d) + 1 for d = lanes per worker in step 4
+    int lpw_log2;            // staging: log2 of the lanes that fetch one worker's words (64 / lanes >= batch)
     int uwp_log2;            // log2 of the slots per worker in step 3 (a power of two >= G.ua)
     int E;                   // entries per lane in step 4: 8, or 4 when k is not a multiple of 8
     int rec_bytes;           // MODE 2: bytes of a plain record
@@ -105,33 +106,45 @@ __global__ void __launch_bounds__(256) k_apply_coded(CodedApplyArgs A)
         v_word = P.run_word + (unsigned)(P.start_bit >> 5);
         v_meta = (P.start_bit & 31) | (P.nbits << 5);
     }
-    // A batch's staging area has two parts, fetched by separate loops so that each is straight-line
-    // code: nb blocks of (table header, fixed record), fwp words each, and nb bit vectors of uraw words
-    // (all ones beyond a payload's end: no entries).  Word w of either part, from global memory:
-    auto src_fixed = [&](int r0, int nb, int w) -> unsigned {
-        const bool valid = w < nb * fwp;
-        const int r = valid ? (int)__umulhi((unsigned)w, A.magic_f) : 0, q = w - r * fwp;
-        const sl_gbytes p = payload_of(r0 + r);
+    // Staging.  A batch's workers share the wave's lanes: lanes [rs * LPW, (rs + 1) * LPW) fetch the words
+    // of the batch's worker rs, LPW words at a time, so a lane needs its worker's pointer, vector place and
+    // section size once per batch (four lane reads) and its addresses step by a constant.  Two parts per
+    // worker, each fetched by straight-line code: fwp words of (table header, fixed record) and uraw words
+    // of the bit vector (all ones beyond a payload's end: no entries).
+    const int LPW = 1 << A.lpw_log2, rs = lane >> A.lpw_log2, qs = lane & (LPW - 1);
+    unsigned char *const my_stage = stage + rs * A.slot_bytes;
+    struct StageSrc {
+        sl_gbytes p;
+        unsigned word0, limit;
+        bool live;
+    };
+    auto stage_src = [&](int r0, int nb) -> StageSrc {
+        StageSrc S;
+        S.live = rs < nb;
+        const int r = S.live ? r0 + rs : r0;
+        S.p = payload_of(r);
+        S.word0 = (unsigned)sl_lane_read((int)v_word, r);
+        S.limit = (unsigned)sl_lane_read((int)my_words, r);
+        return S;
+    };
+    auto src_fixed = [&](const StageSrc &S, int u) -> unsigned {
+        const int q = qs + (u << A.lpw_log2);
+        const bool valid = S.live && q < fwp;
         const long long at = q < hdrw ? cd.lut_off + 4 * q : cd.fix_off + 4 * (q - hdrw);
-        return valid ? *reinterpret_cast<sl_gwords>(p + at) : 0u;
+        return valid ? *reinterpret_cast<sl_gwords>(S.p + at) : 0u;
     };
-    auto src_vector = [&](int r0, int nb, int w) -> unsigned {
-        const bool in = w < nb * uraw;
-        const int r = in ? (int)__umulhi((unsigned)w, A.magic_u) : 0, q = w - r * uraw;
-        const sl_gbytes p = payload_of(r0 + r);
-        const unsigned word0 = (unsigned)sl_lane_read((int)v_word, r0 + r);
-        const unsigned limit = (unsigned)sl_lane_read((int)my_words, r0 + r);
-        const unsigned long long at = (unsigned long long)word0 + (unsigned)q;
-        return (in && at < limit) ? reinterpret_cast<sl_gwords>(p + G.section)[at] : 0xFFFFFFFFu;
+    auto src_vector = [&](const StageSrc &S, int u) -> unsigned {
+        const int q = qs + (u << A.lpw_log2);
+        const unsigned long long at = (unsigned long long)S.word0 + (unsigned)q;
+        return (S.live && q < uraw && at < S.limit) ? reinterpret_cast<sl_gwords>(S.p + G.section)[at] : 0xFFFFFFFFu;
     };
-    // ... and where it lives in LDS
-    auto stage_fixed = [&](int w) -> unsigned * {
-        const int r = (int)__umulhi((unsigned)w, A.magic_f), q = w - r * fwp;
-        return reinterpret_cast<unsigned *>(stage + r * A.slot_bytes) + q;
+    auto park_fixed = [&](int nb, int u, unsigned v) {
+        const int q = qs + (u << A.lpw_log2);
+        if (rs < nb && q < fwp) reinterpret_cast<unsigned *>(my_stage)[q] = v;
     };
-    auto stage_vector = [&](int w) -> unsigned * {
-        const int r = (int)__umulhi((unsigned)w, A.magic_u), q = w - r * uraw;
-        return reinterpret_cast<unsigned *>(stage + r * A.slot_bytes + off_u) + q;
+    auto park_vector = [&](int nb, int u, unsigned v) {
+        const int q = qs + (u << A.lpw_log2);
+        if (rs < nb && q < uraw) reinterpret_cast<unsigned *>(my_stage + off_u)[q] = v;
     };
 
     constexpr int PFF = SL_CAPPLY_PFF, PFU = SL_CAPPLY_PFU;
@@ -145,10 +158,13 @@ __global__ void __launch_bounds__(256) k_apply_coded(CodedApplyArgs A)
     // theta are in flight.  (Tried: the directory entry one chunk ahead, a wave taking several chunks
     // in turn - the loop costs more registers than a wave has next to a second one; and half of the
     // theta loads ahead of these words, which leaves too little of the stream behind the decode.)
+    {
+        const StageSrc S = stage_src(0, nb0);
 #pragma unroll
-    for (int u = 0; u < PFF; ++u) pf_f[u] = src_fixed(0, nb0, lane + 64 * u);
+        for (int u = 0; u < PFF; ++u) pf_f[u] = src_fixed(S, u);
 #pragma unroll
-    for (int u = 0; u < PFU; ++u) pf_u[u] = src_vector(0, nb0, lane + 64 * u);
+        for (int u = 0; u < PFU; ++u) pf_u[u] = src_vector(S, u);
+    }
     if constexpr (!DECODE) {
         // Sixteen loads are issued for EVERY chunk, so that the wait in front of the words fetched above
         // is "all but the last sixteen" whatever the chunk: a ragged chunk (a tensor's edge) reads its own
@@ -206,38 +222,36 @@ __global__ void __launch_bounds__(256) k_apply_coded(CodedApplyArgs A)
         // (pn_*: registers of their own, so that the wait in front of the first batch's words stays
         // "everything but the theta loads" - one array written on both paths would make it "everything").
         {
-            const int nf = nb * fwp, nu = nb * uraw;
             if (first) {
 #pragma unroll
-                for (int u = 0; u < PFF; ++u)
-                    if (lane + 64 * u < nf) *stage_fixed(lane + 64 * u) = pf_f[u];
+                for (int u = 0; u < PFF; ++u) park_fixed(nb, u, pf_f[u]);
 #pragma unroll
-                for (int u = 0; u < PFU; ++u)
-                    if (lane + 64 * u < nu) *stage_vector(lane + 64 * u) = pf_u[u];
+                for (int u = 0; u < PFU; ++u) park_vector(nb, u, pf_u[u]);
             } else {
 #pragma unroll
-                for (int u = 0; u < PFF; ++u)
-                    if (lane + 64 * u < nf) *stage_fixed(lane + 64 * u) = pn_f[u];
+                for (int u = 0; u < PFF; ++u) park_fixed(nb, u, pn_f[u]);
 #pragma unroll
-                for (int u = 0; u < PFU; ++u)
-                    if (lane + 64 * u < nu) *stage_vector(lane + 64 * u) = pn_u[u];
+                for (int u = 0; u < PFU; ++u) park_vector(nb, u, pn_u[u]);
             }
-            for (int wb = 64 * PFF; wb < nf; wb += 128) {      // what the registers did not hold
-                const unsigned v0 = src_fixed(r0, nb, wb + lane), v1 = src_fixed(r0, nb, wb + 64 + lane);
-                if (wb + lane < nf) *stage_fixed(wb + lane) = v0;
-                if (wb + 64 + lane < nf) *stage_fixed(wb + 64 + lane) = v1;
-            }
-            for (int wb = 64 * PFU; wb < nu; wb += 128) {
-                const unsigned v0 = src_vector(r0, nb, wb + lane), v1 = src_vector(r0, nb, wb + 64 + lane);
-                if (wb + lane < nu) *stage_vector(wb + lane) = v0;
-                if (wb + 64 + lane < nu) *stage_vector(wb + 64 + lane) = v1;
+            if ((PFF << A.lpw_log2) < fwp || (PFU << A.lpw_log2) < uraw) {      // what the registers did not hold
+                const StageSrc S = stage_src(r0, nb);
+                for (int u = PFF; (u << A.lpw_log2) < fwp; u += 2) {
+                    const unsigned v0 = src_fixed(S, u), v1 = src_fixed(S, u + 1);
+                    park_fixed(nb, u, v0);
+                    park_fixed(nb, u + 1, v1);
+                }
+                for (int u = PFU; (u << A.lpw_log2) < uraw; u += 2) {
+                    const unsigned v0 = src_vector(S, u), v1 = src_vector(S, u + 1);
+                    park_vector(nb, u, v0);
+                    park_vector(nb, u + 1, v1);
+                }
             }
             if (r0 + A.batch < A.R) {
-                const int nbn = min(A.batch, A.R - r0 - A.batch);
+                const StageSrc S = stage_src(r0 + A.batch, min(A.batch, A.R - r0 - A.batch));
 #pragma unroll
-                for (int u = 0; u < PFF; ++u) pn_f[u] = src_fixed(r0 + A.batch, nbn, lane + 64 * u);
+                for (int u = 0; u < PFF; ++u) pn_f[u] = src_fixed(S, u);
 #pragma unroll
-                for (int u = 0; u < PFU; ++u) pn_u[u] = src_vector(r0 + A.batch, nbn, lane + 64 * u);
+                for (int u = 0; u < PFU; ++u) pn_u[u] = src_vector(S, u);
             }
             sl_wave_sync();
         }
@@ -272,16 +286,41 @@ __global__ void __launch_bounds__(256) k_apply_coded(CodedApplyArgs A)
                     rank = carry + incl - nz;
                     carry += __builtin_amdgcn_readlane(incl, 63);
                 }
-                // the word's zero bits from both ends at once: two independent chains per turn of the loop
-                // (the length of this loop - the word with the most zeros - is on the chunk's critical path)
-                int rank_hi = rank + nz - 1;
-                while (zeros) {
-                    const int pl = __builtin_ctz(zeros), ph = 31 - __builtin_clz(zeros);
-                    if (rank < k) hs[rank] = (unsigned short)(32 * j + pl - rank);
-                    if (ph != pl && rank_hi < k) hs[rank_hi] = (unsigned short)(32 * j + ph - rank_hi);
-                    zeros &= zeros - 1u;
-                    zeros &= ~(1u << ph);
-                    ++rank, --rank_hi;
+                // The word's zero bits, two from each end per turn of the loop (four independent chains; the
+                // length of this loop - the word with the most zeros - is on the chunk's critical path).  Entry
+                // `rank` is the word's lowest zero, entry `rank + nz - 1` its highest; when one zero is left both
+                // ends write the same value to the same place.  A vector with more than k zeros (malformed)
+                // takes the loop that checks every store.
+                if (__builtin_amdgcn_ballot_w64(rank + nz > k) == 0) {
+                    // (byte addresses and values as plain integers the compiler may not take apart again:
+                    // it would rebuild each of them from j and rank in every turn)
+                    unsigned lo = (unsigned)(size_t)(hs + rank), hi = (unsigned)(size_t)(hs + rank + nz - 1);
+                    int vlo = 32 * j - rank, vhi = 32 * j + 31 - (rank + nz - 1);
+                    asm volatile("" : "+v"(lo), "+v"(hi), "+v"(vlo), "+v"(vhi));
+                    auto put = [](unsigned at, int v) {
+                        *reinterpret_cast<unsigned short __attribute__((address_space(3))) *>(at) = (unsigned short)v;
+                    };
+                    while (zeros) {
+                        const int pl = __builtin_ctz(zeros), ch = __builtin_clz(zeros);
+                        put(lo, vlo + pl);
+                        put(hi, vhi - ch);
+                        zeros &= (zeros - 1u) & ~(0x80000000u >> ch);
+                        if (zeros) {
+                            const int pl2 = __builtin_ctz(zeros), ch2 = __builtin_clz(zeros);
+                            put(lo + 2, vlo - 1 + pl2);
+                            put(hi - 2, vhi + 1 - ch2);
+                            zeros &= (zeros - 1u) & ~(0x80000000u >> ch2);
+                        }
+                        lo += 4, hi -= 4, vlo -= 2, vhi += 2;
+                    }
+                } else {
+                    int rk = rank;
+                    while (zeros) {
+                        const int pl = __builtin_ctz(zeros);
+                        if (rk < k) hs[rk] = (unsigned short)(32 * j + pl - rk);
+                        zeros &= zeros - 1u;
+                        ++rk;
+                    }
                 }
             }
             sl_wave_sync();
@@ -541,8 +580,7 @@ int slk_apply_coded(const sl_plan *p, int mode, float *theta, float *mom, float 
     if (batch < 1) batch = 1;
     if (batch > R) batch = R;
     A.batch = batch;
-    A.magic_f = (unsigned)(0x100000000ull / (unsigned)A.fwp + 1);
-    A.magic_u = (unsigned)(0x100000000ull / (unsigned)(G.ua + 1) + 1);
+    A.lpw_log2 = 6 - pow2_log2_at_least(batch);
     const int L = G.k / A.E;
     A.magic_l = L > 1 ? (unsigned)(0x100000000ull / (unsigned)L + 1) : 0u;
     A.n_chunks = p->n_chunks;
