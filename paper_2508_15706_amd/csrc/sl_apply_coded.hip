@@ -342,18 +342,28 @@ __global__ void __launch_bounds__(256) k_apply_coded(CodedApplyArgs A)
                     int pre[8];
                     int total = 0;
                     if (live) {
+                        // (the two words behind the one that holds the first field are read whether or not
+                        // the fields reach them: they lie inside the worker's slot)
                         const unsigned *rem = reinterpret_cast<const unsigned *>(slot + 4 * hdrw);
                         const int bit = o * E * b, wi = bit >> 5;
-                        const unsigned w0 = b ? rem[wi] : 0u, w1 = (b && wi + 1 < nrw) ? rem[wi + 1] : 0u,
-                                       w2 = (b && wi + 2 < nrw) ? rem[wi + 2] : 0u;
+                        const unsigned w0 = rem[wi], w1 = rem[wi + 1], w2 = rem[wi + 2];
                         const unsigned lo = __builtin_amdgcn_alignbit(w1, w0, (unsigned)(bit & 31));
                         const unsigned hi = __builtin_amdgcn_alignbit(w2, w1, (unsigned)(bit & 31));
                         const unsigned long long win = ((unsigned long long)hi << 32) | lo;
+                        int t = 0;
+                        if (b <= 8) {
+                            // four fields fit a word: entries 0..3 from the window's low word, 4..7 from
+                            // the word that starts at field 4
+                            const unsigned lo4 = (unsigned)(win >> (4 * b));
 #pragma unroll
-                        for (int e = 0; e < 8; ++e) {
-                            if (e < E) total += (int)((unsigned)(win >> (e * b)) & fmask);
-                            pre[e] = total;
+                            for (int e = 0; e < 4; ++e) pre[e] = (t += (int)__builtin_amdgcn_ubfe(lo, (unsigned)(e * b), (unsigned)b));
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) pre[4 + e] = (t += (int)__builtin_amdgcn_ubfe(lo4, (unsigned)(e * b), (unsigned)b));
+                        } else {
+#pragma unroll
+                            for (int e = 0; e < 8; ++e) pre[e] = (t += (int)((unsigned)(win >> (e * b)) & fmask));
                         }
+                        total = E == 8 ? pre[7] : pre[3];
                     } else {
 #pragma unroll
                         for (int e = 0; e < 8; ++e) pre[e] = 0;
@@ -383,17 +393,20 @@ __global__ void __launch_bounds__(256) k_apply_coded(CodedApplyArgs A)
                             hv[2] = (unsigned short)q2.y, hv[3] = (unsigned short)(q2.y >> 16);
                             hv[4] = hv[5] = hv[6] = hv[7] = 0;
                         }
-                        unsigned iv[8];
+                        // two indices per word, cut to 12 bits each after packing: a malformed payload stays
+                        // inside the chunk (a valid one never reaches bit 12)
+                        unsigned pw[4];
+                        const unsigned base = (unsigned)(o * E) + (unsigned)excl;
 #pragma unroll
-                        for (int e = 0; e < 8; ++e) {
-                            const unsigned idx = (unsigned)(o * E + e) + ((unsigned)hv[e] << b) + (unsigned)(excl + pre[e]);
-                            iv[e] = min(idx, 4095u);            // a malformed payload stays inside the chunk
+                        for (int e = 0; e < 8; e += 2) {
+                            const unsigned i0 = base + (unsigned)e + ((unsigned)hv[e] << b) + (unsigned)pre[e];
+                            const unsigned i1 = base + (unsigned)(e + 1) + ((unsigned)hv[e + 1] << b) + (unsigned)pre[e + 1];
+                            pw[e >> 1] = (i0 | (i1 << 16)) & 0x0FFF0FFFu;
                         }
                         if (E == 8)
-                            *reinterpret_cast<uint4 *>(hs) = make_uint4(iv[0] | (iv[1] << 16), iv[2] | (iv[3] << 16),
-                                                                        iv[4] | (iv[5] << 16), iv[6] | (iv[7] << 16));
+                            *reinterpret_cast<uint4 *>(hs) = make_uint4(pw[0], pw[1], pw[2], pw[3]);
                         else
-                            *reinterpret_cast<uint2 *>(hs) = make_uint2(iv[0] | (iv[1] << 16), iv[2] | (iv[3] << 16));
+                            *reinterpret_cast<uint2 *>(hs) = make_uint2(pw[0], pw[1]);
                     }
                 }
             }
