@@ -70,27 +70,36 @@ SL_DEV int sl_coded_emit(const SlCodedGeom &G, int lane, const unsigned short *i
     for (int w = lane; w < nrw; w += 64) rw[w] = 0u;
     sl_wave_sync();
     const int limit = k + G.qmax;            // bits of the longest vector
-    int carry = 0;
-    for (int m0 = 0; m0 < k; m0 += 64) {
-        const int m = m0 + lane;
-        const bool valid = m < k;
-        const int cur = valid ? (int)idx[m] : 0, prev = (valid && m > 0) ? (int)idx[m - 1] : -1;
-        int gap = valid ? cur - prev - 1 : 0;
-        if (gap < 0) gap = 0;
-        const int q = gap >> b;
-        const unsigned r = (unsigned)gap & ((1u << b) - 1u);
-        const int incl = sl_wave_iscan(q);
-        const int z = carry + incl + m;      // position of entry m's zero bit
-        if (valid) {
-            if (z < limit) sl_lds_and(&uv[z >> 5], ~(1u << (z & 31)));
-            if (b) {
-                const int bit = m * b, sh = bit & 31;
-                sl_lds_or(&rw[bit >> 5], r << sh);
-                if (sh + b > 32) sl_lds_or(&rw[(bit >> 5) + 1], r >> (32 - sh));
-            }
-        }
-        carry += __builtin_amdgcn_readlane(incl, 63);
+    // A lane owns ceil(k / 64) CONSECUTIVE entries: one wave scan for the whole chunk, and the lanes of one
+    // store instruction are that many entries apart, so that at high densities they land in different
+    // words of the vector (64 neighbouring entries would share two or three words, and the LDS atomics on
+    // one word take turns).
+    const int E = (k + 63) >> 6, m0 = lane * E, m1 = min(k, m0 + E);
+    const int first_prev = (m0 > 0 && m0 < k) ? (int)idx[m0 - 1] : -1;
+    int prev = first_prev, qsum = 0;
+    for (int m = m0; m < m1; ++m) {
+        const int cur = (int)idx[m];
+        qsum += max(cur - prev - 1, 0) >> b;
+        prev = cur;
     }
+    const int incl = sl_wave_iscan(qsum);
+    int qrun = incl - qsum;                  // quotients of all entries before the lane's first
+    prev = first_prev;
+    for (int m = m0; m < m1; ++m) {
+        const int cur = (int)idx[m];
+        const int gap = max(cur - prev - 1, 0);
+        prev = cur;
+        qrun += gap >> b;
+        const unsigned r = (unsigned)gap & ((1u << b) - 1u);
+        const int z = qrun + m;              // position of entry m's zero bit
+        if (z < limit) sl_lds_and(&uv[z >> 5], ~(1u << (z & 31)));
+        if (b) {
+            const int bit = m * b, sh = bit & 31;
+            sl_lds_or(&rw[bit >> 5], r << sh);
+            if (sh + b > 32) sl_lds_or(&rw[(bit >> 5) + 1], r >> (32 - sh));
+        }
+    }
+    const int carry = __builtin_amdgcn_readlane(incl, 63);
     sl_wave_sync();
     return min(carry, G.qmax);
 }
