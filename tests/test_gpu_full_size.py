@@ -27,6 +27,28 @@ def sl():
     return binding
 
 
+# These tests run for minutes with the oracle at work on the host; a line per worker goes to the real
+# standard output (past pytest's capture), so that a watcher sees the run alive.
+def SAY(msg):
+    pass
+
+
+@pytest.fixture(autouse=True)
+def _progress_lines(request):
+    global SAY
+    capman = request.config.pluginmanager.getplugin("capturemanager")
+
+    def say(msg):
+        if capman is None:
+            print(msg, flush=True)
+            return
+        with capman.global_and_fixture_disabled():
+            print(msg, flush=True)
+    SAY = say
+    yield
+    SAY = lambda msg: None
+
+
 def bits(x):
     return np.asarray(x).view(np.uint32)
 
@@ -132,6 +154,8 @@ def run_config(sl, oracle, config_id, k, rounds, sample_names, full_first=True, 
             if r > 0:
                 sample.compare_values(e_dev[r], e_ref[r], f"cfg{config_id} round {rnd} worker {r} e")
             ref_pays.append(ref)
+            if r % 4 == 3 or r == w.R - 1:
+                SAY(f"  [{w.name} k={w.k}] round {rnd}: workers 0..{r} ok")
         sl.sl_decompress_avg_apply(plan, theta, cur, w.lr)
         torch.cuda.synchronize()
         o_apply(sample.descs, w.k, theta_ref, ref_pays, w.lr)
@@ -225,7 +249,7 @@ def test_config4_1p8B_whole_list_all_workers_three_rounds(sl, oracle):
                 assert sizes[0] == enc.size and np.array_equal(wires[0][:enc.size].cpu().numpy(), enc), \
                     f"round {rnd}: coded bytes of worker 0 differ"
             refs.append(ref)
-            print(f"round {rnd} worker {r}: payload, error buffer ok", flush=True)
+            SAY(f"  [config 4 whole list] round {rnd} worker {r}: payload, error buffer ok")
         if rnd == 2:
             sl.sl_decompress_avg_apply_coded(plan, theta, wires, sizes, w.lr)
         else:
@@ -234,7 +258,7 @@ def test_config4_1p8B_whole_list_all_workers_three_rounds(sl, oracle):
         torch.cuda.synchronize()
         assert torch.equal(theta.view(torch.int32), torch.from_numpy(theta_ref).to(dev).view(torch.int32)), \
             f"round {rnd}: theta differs"
-        print(f"round {rnd}: theta ok", flush=True)
+        SAY(f"  [config 4 whole list] round {rnd}: theta ok")
     plan.close()
 
 
