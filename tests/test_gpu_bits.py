@@ -54,6 +54,17 @@ def test_compress_matches_oracle(sl, oracle, bits, k):
         raise AssertionError(f"bits={bits} k={k}: payload differs at {diff.size} bytes, first at {diff[:8]}")
     assert_f32_close(e.cpu().numpy(), e_ref, f"bits={bits} k={k} e")
     assert sl.sl_payload_validate(plan, pay, ws)
+    # the same list again with the list-length knob of the code kernel at zero (at 2 bits: a lane per chunk
+    # instead of a wave per chunk)
+    sl.sl_plan_set_codes_wave_below(plan, 0)
+    e2 = torch.from_numpy(e0.copy()).cuda()
+    pay2 = sl.alloc_payload(plan)
+    pay2.fill_(0x5A)
+    sl.sl_compress(plan, e2, torch.from_numpy(delta).cuda(), 0.95, pay2, ws)
+    torch.cuda.synchronize()
+    assert np.array_equal(pay2[:plan.payload_bytes].cpu().numpy(), ref), f"bits={bits} k={k}: the other route differs"
+    assert torch.equal(e2.view(torch.int32), e.view(torch.int32))
+    sl.sl_plan_set_codes_wave_below(plan, 32768)
     # the index coder at this width: the oracle's coded bytes, and back
     ref_enc = oracle.rice_encode_b(descs, k, bits, ref)
     cap = sl.sl_rice_max_bytes(plan)
