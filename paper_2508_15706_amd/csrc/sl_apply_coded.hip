@@ -77,7 +77,7 @@ __global__ void __launch_bounds__(256) k_apply_coded(CodedApplyArgs A)
     const SlCodedDesc cd = A.cdesc[c];
     const int bits = TWO_BIT ? 2 : G.bits;
     const int hdr = TWO_BIT ? 16 : G.hdr, hdrw = hdr >> 2;
-    const int fwp = A.fwp, uraw = G.ua + 1, nrw = G.rem_bytes >> 2;
+    const int fwp = A.fwp, uraw = G.ua + 1;
     // one staged worker: [table header][fixed record][uraw words of the bit vector][k 16-bit values]
     const int off_u = 4 * fwp, off_h = (off_u + 4 * uraw + 15) & ~15;
 

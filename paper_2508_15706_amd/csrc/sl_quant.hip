@@ -161,7 +161,6 @@ constexpr int CODE_WAVES = 2;        // waves per workgroup
 #endif
 // (... and at any k on a list of fewer chunks than the plan's codes_wave_below, 32768 unless set: with a lane per
 // chunk such a list leaves most of the chip without a wave)
-constexpr int CODE_PITCH = 65;       // LDS row pitch in floats: conflict-free column reads
 
 // One LANE per chunk, 64 consecutive chunks per wave.  The selected values of
 // the 64 chunks are read with coalesced 16-byte loads, 64 entries per chunk at a
