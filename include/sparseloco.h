@@ -330,6 +330,8 @@ int sl_pack_indices_bits(const uint16_t *idx, const uint8_t *codes, const float 
  *   coded_bytes  HOST array of the R buffers' sizes (>= sl_coded_fixed_bytes(), else
  *                INVALID_ARG).  No read leaves [coded[r], coded[r] + coded_bytes[r]); a
  *                malformed payload gives indices clamped into the chunk, never a fault.
+ *                Any bound from the coded size up to the buffer's capacity will do: a caller
+ *                that cannot read the size word back (stream capture) passes the capacity.
  * sl_rice_encode: payload (plain format, device) -> coded buffer `out` (device, 16-byte
  *   aligned, capacity >= sl_rice_max_bytes(), else INVALID_ARG): the same bytes as
  *   sl_compress_coded writes.  Indices of a record that are not strictly ascending are coded as
