@@ -190,7 +190,8 @@ def test_compress_coded_deferred_chain_and_determinism(sl, oracle):
 # --------------------------------------------------------------------------- the coded aggregate
 @pytest.mark.parametrize("R,k,lr", [(1, 32, 1.0), (3, 64, 0.7), (4, 64, 0.7), (8, 64, 1.0), (16, 32, 0.8), (8, 128, 1.0),
                                     (16, 256, 0.8), (33, 64, 0.6), (64, 32, 0.5), (5, 100, 1.0), (8, 12, 1.0),
-                                    (3, 512, 1.0), (2, 1000, 1.0), (3, 2048, 1.0), (2, 4096, 1.0), (20, 200, 0.9)])
+                                    (3, 512, 1.0), (2, 1000, 1.0), (3, 2048, 1.0), (2, 4096, 1.0), (20, 200, 0.9),
+                                    (64, 4, 1.0), (64, 64, 0.9), (64, 256, 0.7), (17, 8, 1.0), (9, 520, 0.8)])
 def test_apply_coded_matches_oracle(sl, oracle, R, k, lr):
     """theta after sl_decompress_avg_apply_coded over the GPU's own coded payloads against the oracle's
     aggregate of the oracle's payloads: every decode layout (lanes per worker, words per vector, one-
