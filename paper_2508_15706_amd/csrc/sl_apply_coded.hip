@@ -255,6 +255,78 @@ __global__ void __launch_bounds__(256) k_apply_coded(CodedApplyArgs A)
             }
             sl_wave_sync();
         }
+        // the dequantised value of a staged worker's entry m
+        auto value_at = [&](const unsigned char *slot, int m) -> float {
+            const float *lutp = reinterpret_cast<const float *>(slot);
+            const unsigned char *vals = slot + 4 * hdrw + G.rem_bytes;
+            if (TWO_BIT) return lutp[(vals[m >> 2] >> (2 * (m & 3))) & 3u];
+            if (bits == 32) return reinterpret_cast<const float *>(vals)[m];
+            return lutp[sl_code_at(vals, m, bits)];
+        };
+        // ---- no remainders (b = 0, k above 1419): a gap is its quotient, the vector is the chunk's bit map -
+        // bit p is zero exactly where index p is selected - and the entries are added straight from it, the
+        // i-th zero with the i-th value, worker after worker.  (Steps 3 to 5 would give the same sums.)
+        if (!DECODE && b == 0) {
+            const int passes = (G.ua + 63) >> 6;
+            for (int r = 0; r < nb; ++r) {
+                const unsigned char *slot = stage + r * A.slot_bytes;
+                const unsigned *raw = reinterpret_cast<const unsigned *>(slot + off_u);
+                const int meta = sl_lane_read(v_meta, r0 + r);
+                const int sh = meta & 31, n = meta >> 5;
+                int carry = 0;
+                for (int t = 0; t < passes; ++t) {
+                    const int j = 64 * t + lane;
+                    unsigned zeros = 0;
+                    if (j < G.ua) {
+                        const unsigned w = __builtin_amdgcn_alignbit(raw[j + 1], raw[j], (unsigned)sh);
+                        const int left = n - 32 * j;
+                        const unsigned mask = left >= 32 ? 0xFFFFFFFFu : left > 0 ? (1u << left) - 1u : 0u;
+                        zeros = ~w & mask;
+                    }
+                    const int nz = __builtin_popcount(zeros);
+                    const int incl = sl_wave_iscan(nz);
+                    int lo = carry + incl - nz, hi = lo + nz - 1;    // entries of the word's lowest and highest zero
+                    carry += __builtin_amdgcn_readlane(incl, 63);
+                    // Two zeros per turn, one from each end of the word: two independent chains, their LDS
+                    // reads issued together.  (An entry beyond k - 1 can only come from a malformed vector
+                    // and takes the last entry's value.)
+                    if constexpr (TWO_BIT) {
+                        // the word's nz two-bit codes, entry `lo` at bit 0 of a 64-bit window
+                        const unsigned *cw = reinterpret_cast<const unsigned *>(slot + 4 * hdrw + G.rem_bytes);
+                        const int e0 = min(lo, k - 1), wi = (2 * e0) >> 5, csh = (2 * e0) & 31;
+                        const unsigned c0 = cw[wi], c1 = cw[wi + 1], c2 = cw[wi + 2];
+                        unsigned long long wl = ((unsigned long long)__builtin_amdgcn_alignbit(c2, c1, (unsigned)csh) << 32) |
+                                                __builtin_amdgcn_alignbit(c1, c0, (unsigned)csh);
+                        unsigned long long wh = nz ? wl << (64 - 2 * nz) : 0ull;      // entry `hi` in the two top bits
+                        const float *lutp = reinterpret_cast<const float *>(slot);
+                        while (zeros) {
+                            const int pl = __builtin_ctz(zeros), ph = 31 - __builtin_clz(zeros);
+                            const float q_lo = lutp[(unsigned)wl & 3u], q_hi = lutp[(unsigned)(wh >> 62)];
+                            const unsigned j_lo = (unsigned)(32 * j + pl), j_hi = (unsigned)(32 * j + ph);
+                            const float a_lo = acc[j_lo], a_hi = acc[j_hi];
+                            acc[j_lo] = a_lo + q_lo;
+                            if (ph != pl) acc[j_hi] = a_hi + q_hi;
+                            zeros &= zeros - 1u;
+                            zeros &= ~(1u << ph);
+                            wl >>= 2, wh <<= 2;
+                        }
+                    } else {
+                        while (zeros) {
+                            const int pl = __builtin_ctz(zeros), ph = 31 - __builtin_clz(zeros);
+                            const float q_lo = value_at(slot, min(lo, k - 1));
+                            const float q_hi = value_at(slot, min(hi, k - 1));
+                            acc_add(acc, (unsigned)(32 * j + pl), q_lo);
+                            if (ph != pl) acc_add(acc, (unsigned)(32 * j + ph), q_hi);
+                            zeros &= zeros - 1u;
+                            zeros &= ~(1u << ph);
+                            ++lo, --hi;
+                        }
+                    }
+                }
+                sl_wave_sync();               // worker r is complete before worker r+1 is added
+            }
+            return;
+        }
         // ---- step 3: the zero bits of the vectors -> running quotient sums, by entry
         {
             const int slots = nb << A.uwp_log2;
@@ -436,13 +508,6 @@ __global__ void __launch_bounds__(256) k_apply_coded(CodedApplyArgs A)
             }
         } else {
             // ---- step 5: the additions, worker by worker
-            auto value_at = [&](const unsigned char *slot, int m) -> float {
-                const float *lutp = reinterpret_cast<const float *>(slot);
-                const unsigned char *vals = slot + 4 * hdrw + G.rem_bytes;
-                if (TWO_BIT) return lutp[(vals[m >> 2] >> (2 * (m & 3))) & 3u];
-                if (bits == 32) return reinterpret_cast<const float *>(vals)[m];
-                return lutp[sl_code_at(vals, m, bits)];
-            };
             if (k <= 128) {
                 // the entries of up to eight workers are fetched first (independent LDS reads),
                 // then added worker by worker: the additions form a chain of LDS round trips
