@@ -245,6 +245,11 @@ __global__ void __launch_bounds__(256) k_apply_coded(CodedApplyArgs A)
                     park_vector(nb, u, v0);
                     park_vector(nb, u + 1, v1);
                 }
+                // (every load of this block has been waited for by a lane that parked its word; said once
+                // more for all of them, so that the registers they used are not taken to be in flight by
+                // code that follows - which would put a wait for the theta loads in front of steps 4 and 5
+                // on the lists that never come here)
+                __builtin_amdgcn_s_waitcnt(0x0F70);          // vmcnt(0)
             }
             if (r0 + A.batch < A.R) {
                 const StageSrc S = stage_src(r0 + A.batch, min(A.batch, A.R - r0 - A.batch));
