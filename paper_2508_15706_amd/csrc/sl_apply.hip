@@ -149,8 +149,11 @@ __global__ void __launch_bounds__(256) k_apply(ApplyArgs A)
     };
     // The first 64*PF words of the first batch (all of it for R*(16 + 7k/4) <= 2 KB:
     // R = 8 up to k = 128, R = 16 up to k = 64) are fetched into registers BEFORE the
-    // theta loads: loads complete in order, so the decode below then waits for these
-    // few words only and runs while the chunk's 16 KB of theta are still in flight.
+    // theta loads, so that they arrive with the chunk instead of costing a second round
+    // trip to memory behind it.  (As compiled, the wait in front of the words' parking
+    // below is for every outstanding load, theta included: the parking sits in a loop.
+    // With that wait made exact the decode overlaps the theta loads, and nothing is
+    // gained - this kernel's decode is short - so the simpler form stays.)
     // (wider records at other widths: 3 KB; many workers at small k, the entry-by-entry route, and
     // the eight-entry route: 4 KB, which is all that is staged at a time there)
     constexpr int PF = ROUTE == 2 ? 16 : !TWO_BIT ? 12 : ROUTE == 1 ? SL_APPLY_PF1 : 8;
